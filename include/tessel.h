@@ -1,0 +1,188 @@
+/*
+ * tessel.h -- C ABI of the MI355X (gfx950) repetend-candidate evaluator.
+ *
+ * The library scores candidate repetends of the Tessel schedule search (arXiv 2311.15269):
+ * every candidate is one per-device ordering of the blocks of N_R consecutive micro-batches
+ * plus a micro-batch index assignment; scoring means its steady-state period and its
+ * per-device peak memory against a cap; the best (period, index) is kept.  All arithmetic
+ * is integer (Sec. III-A).  Everything below runs on ONE GPU; the "devices" of a problem
+ * are simulated entities of the schedule, not GPUs.
+ *
+ * Pointer conventions: `*_dev` arguments are DEVICE pointers, every other pointer is a HOST
+ * pointer.  Host arrays handed to tessel_problem_create() are read during the call only.
+ * The library allocates no device memory: the caller owns the workspace and the stream.
+ * Every function returns TESSEL_OK (0) or a negative TESSEL_E_* code; nothing aborts or
+ * throws across this boundary.  One problem handle must not be used from two host threads
+ * at once; there is no global state.
+ */
+#ifndef TESSEL_H
+#define TESSEL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- limits of this implementation -------------------------------------------------- */
+#define TESSEL_MAX_DEVICES        8    /* simulated devices D                               */
+#define TESSEL_MAX_TYPES_PER_DEV  4    /* block types that occupy one device                */
+#define TESSEL_MAX_NR             8    /* micro-batches per repetend window, N_R            */
+#define TESSEL_MAX_TYPES          32   /* K                                                 */
+#define TESSEL_NUM_STATUS         6
+
+/* ---- error codes --------------------------------------------------------------------- */
+enum {
+    TESSEL_OK                 = 0,
+    TESSEL_E_INVALID_ARG      = -1,
+    TESSEL_E_BAD_DEP          = -2,   /* the micro-batch dependency graph has a cycle            */
+    TESSEL_E_UNBALANCED_MEMORY= -3,   /* sum of m over the blocks of a device != 0: no steady state */
+    TESSEL_E_TOOBIG           = -4,   /* a count or a time bound exceeds what the kernels hold   */
+    TESSEL_E_WORKSPACE        = -5,   /* workspace missing, misaligned or too small              */
+    TESSEL_E_HIP              = -6,   /* a HIP runtime call failed (see tessel_last_hip_error)   */
+    TESSEL_E_NO_FEASIBLE      = -7,   /* nothing scored so far is feasible                       */
+    TESSEL_E_RANGE            = -8,   /* candidate range outside the space / too few micro-batches */
+    TESSEL_E_UNSUPPORTED      = -9,   /* valid problem outside the limits above                  */
+    TESSEL_E_NO_SCHEDULE      = -10   /* completion cannot order warm-up/cool-down under the cap */
+};
+
+/* ---- candidate spaces (how a 64-bit candidate index is turned into a candidate) --------
+ * A candidate = a lead vector (the micro-batch index n_i of Eq. 3 for every block type,
+ * 0 <= n_i < N_R) + for every device the order of its n_d = (#types on d) * N_R blocks.
+ * By Property 1 (Sec. IV-B) blocks of one type run in increasing micro-batch order, so an
+ * order is a sequence of type ids; the q-th occurrence of type i in window k handles
+ * micro-batch n_i + q + N_R*k.
+ *
+ * FACTORIAL       factorial number system per device over labelled blocks
+ *                 (type ascending, label 0..N_R-1): index = sum_d r_d * prod_{d'<d} n_d'!,
+ *                 r_d = lexicographic permutation rank.  The first label of a type is its
+ *                 lead; labels that do not continue cyclically name a Property-1 duplicate.
+ * CANONICAL       index = r_0 + C_0*(r_1 + ... + C_{D-1}*lead_rank): r_d = lexicographic rank
+ *                 of the device's type sequence, lead_rank = rank among the lead vectors that
+ *                 satisfy Property 2 and have minimum 0, in lexicographic order.
+ * SAMPLED_STRICT  index = ordinal of a counter-based pseudo-random stream keyed by `seed`
+ *                 that draws leads and uniformly random type sequences; an order that can
+ *                 never execute is rejected (DEADLOCK).
+ * SAMPLED_REPAIR  the same draws, then a deterministic head-of-line repair that turns the
+ *                 drawn priority lists into the nearest executable orders.                 */
+enum {
+    TESSEL_SPACE_FACTORIAL      = 0,
+    TESSEL_SPACE_CANONICAL      = 1,
+    TESSEL_SPACE_SAMPLED_STRICT = 2,
+    TESSEL_SPACE_SAMPLED_REPAIR = 3
+};
+
+/* ---- per-candidate status; every candidate gets exactly one --------------------------- */
+enum {
+    TESSEL_STATUS_OK          = 0,   /* executable and within the cap: has a period             */
+    TESSEL_STATUS_DUP         = 1,   /* FACTORIAL only: Property-1 duplicate of another index   */
+    TESSEL_STATUS_TP_MISMATCH = 2,   /* FACTORIAL only: a multi-device block has two leads      */
+    TESSEL_STATUS_PROP2       = 3,   /* a producer's lead is below its consumer's (Property 2)  */
+    TESSEL_STATUS_DEADLOCK    = 4,   /* the per-device orders can never execute                 */
+    TESSEL_STATUS_MEM         = 5    /* a device's peak memory exceeds the cap (Eq. 1 [2])      */
+};
+
+/* ---- problem statement (Table I, Sec. III-A) ----------------------------------------- */
+typedef struct {
+    int32_t  num_devices;       /* D                                                            */
+    int32_t  num_block_types;   /* K blocks per micro-batch                                     */
+    int32_t  nr;                /* N_R, micro-batches per repetend window (Eq. 3)               */
+    int32_t  mem_cap;           /* M, the same on every device                                  */
+    const int32_t  *time;       /* [K] t_B >= 1                                                 */
+    const int32_t  *mem;        /* [K] m_B, negative = releases memory                          */
+    const uint32_t *dev_mask;   /* [K] bit d set <=> the block occupies device d (d_B)          */
+    int32_t  num_deps;          /* dependencies inside one micro-batch, B_src -> B_dst          */
+    const int32_t  *dep_src;    /* [num_deps]                                                   */
+    const int32_t  *dep_dst;    /* [num_deps]                                                   */
+    int32_t  space;             /* TESSEL_SPACE_*                                               */
+    const int32_t  *fixed_leads;/* [K] or NULL; not allowed with TESSEL_SPACE_FACTORIAL         */
+    uint64_t seed;              /* sampled spaces                                               */
+    uint32_t lead_step_q16;     /* sampled spaces: P(lead grows by one across a dependency
+                                   between different device sets) * 65536                       */
+} tessel_problem_desc;
+
+typedef struct tessel_problem tessel_problem;   /* opaque, host memory only */
+
+/* ---- results -------------------------------------------------------------------------- */
+typedef struct {
+    int32_t  period;                          /* best T* (repetend time t_R, Eq. 4)            */
+    uint64_t index;                           /* lowest candidate index attaining it (Alg. 1
+                                                 replaces the incumbent on strict < only)      */
+    int32_t  peak_mem[TESSEL_MAX_DEVICES];    /* per-device peak of the best candidate         */
+    int32_t  peak_max;
+    int32_t  lower_bound;                     /* N_R * max_d sum of t on d (Alg. 1 GetLowerBound) */
+    uint64_t n_evaluated;
+    uint64_t n_feasible;
+    uint64_t n_reject[TESSEL_NUM_STATUS];     /* indexed by TESSEL_STATUS_*; [0] unused        */
+} tessel_result;
+
+/* A complete schedule of N micro-batches: warm-up, R copies of the best window, cool-down
+ * (Sec. IV-C, Eq. 5-6).  All arrays are caller-allocated host memory. */
+typedef struct {
+    int32_t  num_microbatches;   /* in:  N                                                     */
+    int32_t  capacity;           /* in:  elements available in start[] and in each row of
+                                         dev_order[]; needs K*N                                 */
+    int32_t *start;              /* out: [K*N] start time of block (type, mu) at type*N + mu    */
+    int32_t *dev_order;          /* out: [D][capacity] blocks (type*N+mu) in execution order    */
+    int32_t *dev_len;            /* out: [D]                                                    */
+    int32_t  makespan;           /* out: max end time (objective of Eq. 1)                      */
+    int32_t  period;             /* out: T* of the window that was repeated                     */
+    int32_t  num_windows;        /* out: R                                                      */
+} tessel_schedule;
+
+/* Validates the problem statement (Sec. III-A) and builds the host-side tables.
+ * Errors: INVALID_ARG, BAD_DEP, UNBALANCED_MEMORY, UNSUPPORTED, TOOBIG. */
+int  tessel_problem_create(const tessel_problem_desc *desc, tessel_problem **out);
+void tessel_problem_destroy(tessel_problem *p);
+
+/* Number of candidates of the problem's space; UINT64_MAX for the sampled spaces (any
+ * ordinal is a candidate). */
+int  tessel_candidate_count(const tessel_problem *p, uint64_t *count);
+
+/* Bytes of device workspace tessel_eval_candidates / tessel_score_candidates need. */
+int  tessel_workspace_bytes(const tessel_problem *p, size_t *bytes);
+
+/* Scores candidates first .. first+count-1 (Alg. 1, the loop over repetends: decode,
+ * validity, period, memory) and merges into the running best of `p` under the total order
+ * (period, index).  Asynchronous on `hip_stream` (a hipStream_t, NULL = default stream).
+ * May be called again with any other range, in any order; the running best and the
+ * counters live in `workspace_dev`, which must be the same 256-byte aligned buffer for all
+ * calls of one search.  tessel_reset() starts a new search. */
+int  tessel_eval_candidates(tessel_problem *p, uint64_t first, uint64_t count,
+                            void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/* Per-candidate records for tests and analysis: code_dev[k] = T* of candidate first+k when
+ * it is feasible, else -(TESSEL_STATUS_*); peak_dev[k] (may be NULL) = its largest
+ * per-device peak when the status is OK or MEM, else 0.  Does not touch the running best. */
+int  tessel_score_candidates(tessel_problem *p, uint64_t first, uint64_t count,
+                             int32_t *code_dev, int32_t *peak_dev,
+                             void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/* Waits for the stream of the last call, then returns the running best.  NO_FEASIBLE when
+ * nothing feasible has been scored (counters in *out are still valid). */
+int  tessel_best(tessel_problem *p, tessel_result *out);
+
+/* Decoded form of the best candidate as the GPU decoded it: leads[K], order_len[D] and
+ * orders[D][32] (block type ids in device order, after repair in the REPAIR space), and
+ * its least start times at T*: starts[K*N_R] at type*N_R + occurrence. Any pointer may be NULL. */
+int  tessel_best_candidate(tessel_problem *p, int32_t *leads, int32_t *order_len, int32_t *orders,
+                           int32_t *starts);
+
+/* Forgets the running best and the counters. */
+int  tessel_reset(tessel_problem *p);
+
+/* Extends the best window to N micro-batches (Sec. IV-C): warm-up and cool-down block sets
+ * of Eq. 5-6, ordered by a deterministic greedy list schedule (instead of the paper's
+ * time-optimal solver), R = floor((N - max lead)/N_R) windows in between; start times are
+ * the earliest ones for that per-device order.  Errors: NO_FEASIBLE, RANGE (R < 1 or
+ * capacity too small), NO_SCHEDULE. */
+int  tessel_complete_schedule(tessel_problem *p, tessel_schedule *out);
+
+const char *tessel_strerror(int code);
+int  tessel_last_hip_error(const tessel_problem *p);   /* hipError_t of the last failure, 0 if none */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TESSEL_H */

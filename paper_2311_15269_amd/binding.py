@@ -1,0 +1,197 @@
+"""Thin ctypes binding of the C ABI in include/tessel.h -- argument marshalling only.
+
+PyTorch is used for device memory (workspace, output buffers) and for the current HIP
+stream; every step of the evaluation runs in the library's kernels.  There is no CPU
+fallback: if the HIP library is missing or no GPU is present, calls raise.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+MAX_DEVICES = 8
+MAX_POS = 32
+NUM_STATUS = 6
+STATUS_NAMES = ("OK", "DUP", "TP_MISMATCH", "PROP2", "DEADLOCK", "MEM")
+SPACE = {"factorial": 0, "canonical": 1, "sampled_strict": 2, "sampled_repair": 3}
+
+E_NO_FEASIBLE = -7
+
+EXPORTS = (
+    "tessel_problem_create", "tessel_problem_destroy", "tessel_candidate_count", "tessel_workspace_bytes",
+    "tessel_eval_candidates", "tessel_score_candidates", "tessel_best", "tessel_best_candidate", "tessel_reset",
+    "tessel_complete_schedule", "tessel_strerror", "tessel_last_hip_error",
+)
+
+
+class ProblemDesc(C.Structure):
+    _fields_ = [("num_devices", C.c_int32), ("num_block_types", C.c_int32), ("nr", C.c_int32), ("mem_cap", C.c_int32),
+                ("time", C.c_void_p), ("mem", C.c_void_p), ("dev_mask", C.c_void_p),
+                ("num_deps", C.c_int32), ("dep_src", C.c_void_p), ("dep_dst", C.c_void_p),
+                ("space", C.c_int32), ("fixed_leads", C.c_void_p), ("seed", C.c_uint64), ("lead_step_q16", C.c_uint32)]
+
+
+class Result(C.Structure):
+    _fields_ = [("period", C.c_int32), ("index", C.c_uint64), ("peak_mem", C.c_int32 * MAX_DEVICES),
+                ("peak_max", C.c_int32), ("lower_bound", C.c_int32), ("n_evaluated", C.c_uint64),
+                ("n_feasible", C.c_uint64), ("n_reject", C.c_uint64 * NUM_STATUS)]
+
+
+class Schedule(C.Structure):
+    _fields_ = [("num_microbatches", C.c_int32), ("capacity", C.c_int32), ("start", C.c_void_p),
+                ("dev_order", C.c_void_p), ("dev_len", C.c_void_p), ("makespan", C.c_int32), ("period", C.c_int32),
+                ("num_windows", C.c_int32)]
+
+
+class TesselError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("tessel error %d: %s" % (code, text))
+        self.code = code
+
+
+_lib = None
+
+
+def library_path():
+    return _build.LIB
+
+
+def load_library():
+    """Loads the in-tree HIP library; builds it first only if it has never been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build_library()
+        lib = C.CDLL(_build.LIB)
+        lib.tessel_problem_create.argtypes = [C.POINTER(ProblemDesc), C.POINTER(C.c_void_p)]
+        lib.tessel_problem_destroy.argtypes = [C.c_void_p]
+        lib.tessel_problem_destroy.restype = None
+        lib.tessel_candidate_count.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
+        lib.tessel_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
+        lib.tessel_eval_candidates.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.tessel_score_candidates.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p,
+                                                C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.tessel_best.argtypes = [C.c_void_p, C.POINTER(Result)]
+        lib.tessel_best_candidate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.tessel_reset.argtypes = [C.c_void_p]
+        lib.tessel_complete_schedule.argtypes = [C.c_void_p, C.POINTER(Schedule)]
+        lib.tessel_strerror.argtypes = [C.c_int]
+        lib.tessel_strerror.restype = C.c_char_p
+        lib.tessel_last_hip_error.argtypes = [C.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def _check(rc, allow=()):
+    if rc != 0 and rc not in allow:
+        raise TesselError(rc, load_library().tessel_strerror(rc).decode())
+    return rc
+
+
+def _i32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+class Problem:
+    """tessel_problem_create / _destroy and the calls on the handle, same names as the C ABI."""
+
+    def __init__(self, problem):
+        lib = load_library()
+        self.problem = problem
+        self.D, self.K, self.NR = problem["D"], problem["K"], problem["NR"]
+        self._t, self._m = _i32(problem["t"]), _i32(problem["m"])
+        self._mask = np.ascontiguousarray(np.asarray(problem["dev_mask"], dtype=np.uint32))
+        deps = problem["deps"]
+        self._src, self._dst = _i32([a for a, _ in deps]), _i32([b for _, b in deps])
+        fixed = problem.get("fixed_leads")
+        self._fixed = _i32(fixed) if fixed is not None else None
+        desc = ProblemDesc(self.D, self.K, self.NR, problem["M"], self._t.ctypes.data, self._m.ctypes.data,
+                           self._mask.ctypes.data, len(deps), self._src.ctypes.data if len(deps) else None,
+                           self._dst.ctypes.data if len(deps) else None, SPACE[problem["space"]],
+                           self._fixed.ctypes.data if self._fixed is not None else None,
+                           problem.get("seed", 0), problem.get("lead_step_q16", 0))
+        h = C.c_void_p()
+        _check(lib.tessel_problem_create(C.byref(desc), C.byref(h)))
+        self._h = h
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load_library().tessel_problem_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    # ---- plumbing: device memory and stream come from torch
+    def _workspace(self):
+        import torch
+        if self._ws is None:
+            n = C.c_size_t()
+            _check(load_library().tessel_workspace_bytes(self._h, C.byref(n)))
+            self._ws = torch.empty(n.value + 256, dtype=torch.uint8, device="cuda")
+        ptr = (self._ws.data_ptr() + 255) & ~255
+        return ptr, self._ws.numel() - (ptr - self._ws.data_ptr())
+
+    @staticmethod
+    def _stream():
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+
+    # ---- the C ABI
+    def candidate_count(self):
+        n = C.c_uint64()
+        _check(load_library().tessel_candidate_count(self._h, C.byref(n)))
+        return n.value
+
+    def workspace_bytes(self):
+        n = C.c_size_t()
+        _check(load_library().tessel_workspace_bytes(self._h, C.byref(n)))
+        return n.value
+
+    def eval_candidates(self, first, count, stream=None):
+        ptr, size = self._workspace()
+        _check(load_library().tessel_eval_candidates(self._h, first, count, ptr, size,
+                                                      self._stream() if stream is None else stream))
+
+    def score_candidates(self, first, count):
+        """returns (code, peak) int32 CUDA tensors"""
+        import torch
+        ptr, size = self._workspace()
+        code = torch.empty(count, dtype=torch.int32, device="cuda")
+        peak = torch.empty(count, dtype=torch.int32, device="cuda")
+        _check(load_library().tessel_score_candidates(self._h, first, count, code.data_ptr(), peak.data_ptr(), ptr,
+                                                       size, self._stream()))
+        return code, peak
+
+    def best(self):
+        r = Result()
+        rc = _check(load_library().tessel_best(self._h, C.byref(r)), allow=(E_NO_FEASIBLE,))
+        return {"period": r.period, "index": int(r.index), "peak": list(r.peak_mem[:self.D]), "peak_max": r.peak_max,
+                "lower_bound": r.lower_bound, "n_evaluated": int(r.n_evaluated), "n_feasible": int(r.n_feasible),
+                "n_reject": [int(x) for x in r.n_reject], "feasible": rc == 0}
+
+    def best_candidate(self):
+        leads = np.zeros(self.K, dtype=np.int32)
+        olen = np.zeros(self.D, dtype=np.int32)
+        orders = np.zeros((self.D, MAX_POS), dtype=np.int32)
+        starts = np.zeros(self.K * self.NR, dtype=np.int32)
+        _check(load_library().tessel_best_candidate(self._h, leads.ctypes.data, olen.ctypes.data, orders.ctypes.data,
+                                                     starts.ctypes.data))
+        return {"leads": leads.tolist(), "orders": [orders[d, :olen[d]].tolist() for d in range(self.D)],
+                "starts": starts.reshape(self.K, self.NR)}
+
+    def reset(self):
+        _check(load_library().tessel_reset(self._h))
+
+    def complete_schedule(self, num_microbatches):
+        N = num_microbatches
+        cap = self.K * N
+        start = np.full(cap, -1, dtype=np.int32)
+        dev_order = np.full((self.D, cap), -1, dtype=np.int32)
+        dev_len = np.zeros(self.D, dtype=np.int32)
+        s = Schedule(N, cap, start.ctypes.data, dev_order.ctypes.data, dev_len.ctypes.data, 0, 0, 0)
+        _check(load_library().tessel_complete_schedule(self._h, C.byref(s)))
+        return {"makespan": s.makespan, "period": s.period, "num_windows": s.num_windows,
+                "start": start.reshape(self.K, N), "dev_order": [dev_order[d, :dev_len[d]].tolist() for d in range(self.D)]}

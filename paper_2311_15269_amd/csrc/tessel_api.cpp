@@ -1,0 +1,574 @@
+// Host side of the C ABI declared in include/tessel.h: validation of the problem statement
+// (Sec. III-A of the Tessel paper), static tables for the kernels, launches, result read-back,
+// and schedule completion (Sec. IV-C) for the best repetend.  All candidate scoring is done
+// by the kernels in tessel_kernels.hip; nothing here falls back to the CPU for it.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <climits>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/tessel.h"
+#include "tessel_device.h"
+
+using namespace tessel;
+
+namespace tessel { size_t block_rec_bytes(int blocks); }
+
+struct tessel_problem {
+    KParams kp;
+    std::vector<int32_t> t, m;
+    std::vector<uint32_t> mask;
+    std::vector<int32_t> dep_src, dep_dst;
+    std::vector<int8_t> leadtab;        // CANONICAL
+    std::vector<uint64_t> wtab;         // CANONICAL
+    uint64_t nlead = 0;
+    uint64_t count = 0;
+    int num_cus = 0;
+    void *ws = nullptr;                 // workspace the running best lives in
+    bool ws_ready = false;
+    hipStream_t stream = nullptr;
+    int last_hip = 0;
+    bool have_detail = false;
+    uint64_t detail_index = 0;
+    DevDetail detail;
+    DevResult result;
+};
+
+static int hip_fail(tessel_problem *p, int e) { p->last_hip = e; return TESSEL_E_HIP; }
+
+extern "C" const char *tessel_strerror(int code)
+{
+    switch (code) {
+    case TESSEL_OK: return "ok";
+    case TESSEL_E_INVALID_ARG: return "invalid argument";
+    case TESSEL_E_BAD_DEP: return "dependency graph of a micro-batch has a cycle";
+    case TESSEL_E_UNBALANCED_MEMORY: return "memory deltas on a device do not sum to zero";
+    case TESSEL_E_TOOBIG: return "count or time bound too large";
+    case TESSEL_E_WORKSPACE: return "workspace missing, misaligned or too small";
+    case TESSEL_E_HIP: return "HIP runtime error";
+    case TESSEL_E_NO_FEASIBLE: return "no feasible candidate scored";
+    case TESSEL_E_RANGE: return "range outside the candidate space or too few micro-batches";
+    case TESSEL_E_UNSUPPORTED: return "problem outside the limits of this implementation";
+    case TESSEL_E_NO_SCHEDULE: return "no warm-up/cool-down order fits the memory cap";
+    default: return "unknown error";
+    }
+}
+
+// number of distinct sequences of a multiset; 0 on 64-bit overflow
+static uint64_t multiset_sequences(const int *cnt, int ntypes)
+{
+    unsigned __int128 r = 1;
+    unsigned placed = 0;
+    for (int y = 0; y < ntypes; y++)
+        for (int k = 1; k <= cnt[y]; k++) {
+            placed++;
+            r = r * placed / (unsigned)k;
+            if (r >> 64) return 0;
+        }
+    return (uint64_t)r;
+}
+
+// lead vectors of the CANONICAL space: Property 2 on every dependency, minimum 0,
+// lexicographic with type 0 most significant
+static bool gen_leads(const tessel_problem &p, int K, int NR, std::vector<int8_t> &tab, size_t limit)
+{
+    std::vector<int> cur(K, 0);
+    int i = 0;
+    cur[0] = -1;
+    while (i >= 0) {
+        cur[i]++;
+        if (cur[i] >= NR) { i--; continue; }
+        bool ok = true;
+        for (size_t e = 0; e < p.dep_src.size() && ok; e++) {
+            int a = p.dep_src[e], b = p.dep_dst[e];
+            if (std::max(a, b) == i && cur[a] < cur[b]) ok = false;
+        }
+        if (!ok) continue;
+        if (i == K - 1) {
+            if (*std::min_element(cur.begin(), cur.end()) == 0) {
+                if (tab.size() / K >= limit) return false;
+                for (int k = 0; k < K; k++) tab.push_back((int8_t)cur[k]);
+            }
+        } else {
+            i++;
+            cur[i] = -1;
+        }
+    }
+    return true;
+}
+
+extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_problem **out)
+{
+    if (!desc || !out) return TESSEL_E_INVALID_ARG;
+    *out = nullptr;
+    const int D = desc->num_devices, K = desc->num_block_types, NR = desc->nr;
+    if (D < 1 || K < 1 || NR < 1 || desc->num_deps < 0 || !desc->time || !desc->mem || !desc->dev_mask ||
+        (desc->num_deps > 0 && (!desc->dep_src || !desc->dep_dst)) || desc->space < 0 || desc->space > 3 ||
+        desc->lead_step_q16 > 65536u)
+        return TESSEL_E_INVALID_ARG;
+    if (D > 31) return TESSEL_E_UNSUPPORTED;
+    for (int i = 0; i < K; i++)
+        if (desc->time[i] < 1 || desc->dev_mask[i] == 0 || (desc->dev_mask[i] >> D)) return TESSEL_E_INVALID_ARG;
+    for (int e = 0; e < desc->num_deps; e++)
+        if (desc->dep_src[e] < 0 || desc->dep_src[e] >= K || desc->dep_dst[e] < 0 || desc->dep_dst[e] >= K ||
+            desc->dep_src[e] == desc->dep_dst[e])
+            return TESSEL_E_INVALID_ARG;
+    if (desc->fixed_leads) {
+        if (desc->space == TESSEL_SPACE_FACTORIAL) return TESSEL_E_INVALID_ARG;
+        for (int i = 0; i < K; i++) if (desc->fixed_leads[i] < 0 || desc->fixed_leads[i] >= NR) return TESSEL_E_INVALID_ARG;
+        for (int e = 0; e < desc->num_deps; e++)
+            if (desc->fixed_leads[desc->dep_src[e]] < desc->fixed_leads[desc->dep_dst[e]]) return TESSEL_E_INVALID_ARG;
+    }
+    // acyclic?
+    {
+        std::vector<int> indeg(K, 0), done(K, 0);
+        for (int e = 0; e < desc->num_deps; e++) indeg[desc->dep_dst[e]]++;
+        int n = 0;
+        for (bool again = true; again;) {
+            again = false;
+            for (int i = 0; i < K; i++) if (!done[i] && indeg[i] == 0) {
+                done[i] = 1; n++; again = true;
+                for (int e = 0; e < desc->num_deps; e++) if (desc->dep_src[e] == i) indeg[desc->dep_dst[e]]--;
+            }
+        }
+        if (n != K) return TESSEL_E_BAD_DEP;
+    }
+    for (int d = 0; d < D; d++) {
+        int net = 0;
+        for (int i = 0; i < K; i++) if (desc->dev_mask[i] >> d & 1u) net += desc->mem[i];
+        if (net != 0) return TESSEL_E_UNBALANCED_MEMORY;
+    }
+    // limits of the kernels
+    if (D > kMaxD || K > kMaxK || NR > kMaxNR) return TESSEL_E_UNSUPPORTED;
+    std::vector<int> indeg(K, 0), outdeg(K, 0);
+    for (int e = 0; e < desc->num_deps; e++) { outdeg[desc->dep_src[e]]++; indeg[desc->dep_dst[e]]++; }
+    for (int i = 0; i < K; i++) if (indeg[i] > 1 || outdeg[i] > 1) return TESSEL_E_UNSUPPORTED;   // chains only
+
+    tessel_problem *p = new (std::nothrow) tessel_problem();
+    if (!p) return TESSEL_E_INVALID_ARG;
+    p->t.assign(desc->time, desc->time + K);
+    p->m.assign(desc->mem, desc->mem + K);
+    p->mask.assign(desc->dev_mask, desc->dev_mask + K);
+    p->dep_src.assign(desc->dep_src, desc->dep_src + desc->num_deps);
+    p->dep_dst.assign(desc->dep_dst, desc->dep_dst + desc->num_deps);
+    KParams &kp = p->kp;
+    memset(&kp, 0, sizeof kp);
+    kp.D = D; kp.K = K; kp.NR = NR; kp.M = desc->mem_cap; kp.total = K * NR; kp.space = desc->space;
+    kp.seed = desc->seed; kp.step_q16 = desc->lead_step_q16;
+    kp.has_fixed = desc->fixed_leads != nullptr;
+    for (int i = 0; i < K; i++) { kp.pred[i] = -1; kp.succ[i] = -1; kp.fixed[i] = desc->fixed_leads ? (uint8_t)desc->fixed_leads[i] : 0; }
+    for (int e = 0; e < desc->num_deps; e++) {
+        int a = desc->dep_src[e], b = desc->dep_dst[e];
+        kp.succ[a] = (int8_t)b; kp.pred[b] = (int8_t)a;
+        kp.edge_out[a] = (uint8_t)e;
+        kp.cross_out[a] = desc->dev_mask[a] != desc->dev_mask[b];
+    }
+    // chains and their token slots; reverse topological order = walk every chain from its end
+    std::vector<int> path_of(K, -1);
+    int npaths = 0, nrt = 0;
+    for (int i = 0; i < K; i++) if (kp.pred[i] < 0) {
+        int len = 0;
+        for (int g = i; g >= 0; g = kp.succ[g]) { path_of[g] = npaths; len++; }
+        npaths++;
+        (void)len;
+    }
+    for (int i = 0; i < K; i++) if (kp.succ[i] < 0)
+        for (int g = i; g >= 0; g = kp.pred[g]) kp.rtopo[nrt++] = (uint8_t)g;
+    kp.npaths = npaths;
+    kp.nslots = D + npaths * 2 * NR;
+    kp.nsweeps = D + npaths * NR + 1;
+    if (kp.nslots > 63 || kp.nsweeps - 1 > 24) { delete p; return TESSEL_E_UNSUPPORTED; }
+    int sumt = 0;
+    for (int i = 0; i < K; i++) {
+        if (desc->time[i] > (1 << 20)) { delete p; return TESSEL_E_TOOBIG; }
+        sumt += desc->time[i];
+    }
+    kp.UB = NR * sumt;
+    // the period kernel multiplies (sweeps * UB) by a sweep count
+    if ((int64_t)kp.UB * kp.nsweeps * kp.nsweeps >= (int64_t)1 << 31) { delete p; return TESSEL_E_TOOBIG; }
+    kp.LB = 0;
+    for (int d = 0; d < kMaxD; d++) { kp.type_of[d] = kp.pred_of[d] = 0xFFFFFFFFu; kp.mask_of[d] = kp.tok_of[d] = kp.home_of[d] = 0; }
+    std::vector<int> home(K, -1);
+    for (int d = 0; d < D; d++) {
+        int n = 0, busy = 0;
+        for (int i = 0; i < K; i++) if (desc->dev_mask[i] >> d & 1u) {
+            if (n >= kMaxLT) { delete p; return TESSEL_E_UNSUPPORTED; }
+            if (home[i] < 0) home[i] = d * 4 + n;
+            kp.type_of[d] = (kp.type_of[d] & ~(0xFFu << (8 * n))) | ((uint32_t)i << (8 * n));
+            uint32_t pr = kp.pred[i] < 0 ? 0xFFu : (uint32_t)kp.pred[i];
+            kp.pred_of[d] = (kp.pred_of[d] & ~(0xFFu << (8 * n))) | (pr << (8 * n));
+            kp.mask_of[d] |= (desc->dev_mask[i] & 0xFFu) << (8 * n);
+            kp.tok_of[d] |= (uint32_t)(D + path_of[i] * 2 * NR) << (8 * n);
+            kp.home_of[d] |= (uint32_t)home[i] << (8 * n);
+            kp.t_of[d][n] = desc->time[i];
+            kp.m_of[d][n] = desc->mem[i];
+            busy += desc->time[i];
+            n++;
+        }
+        kp.ntd[d] = n;
+        kp.LB = std::max(kp.LB, NR * busy);
+    }
+    for (int i = 0; i < K; i++) {
+        kp.t_loc[home[i]] = desc->time[i];
+        kp.mask_loc[home[i]] = desc->dev_mask[i];
+        if (desc->dev_mask[i] & (desc->dev_mask[i] - 1)) kp.tp = 1;
+    }
+    // candidate count and the tables of the exhaustive spaces
+    if (desc->space == TESSEL_SPACE_FACTORIAL) {
+        kp.fact[0] = 1;
+        for (int n = 1; n <= 12; n++) kp.fact[n] = kp.fact[n - 1] * (uint32_t)n;
+        unsigned __int128 c = 1;
+        for (int d = 0; d < D; d++) {
+            int n = kp.ntd[d] * NR;
+            if (n > 12) { delete p; return n > 20 ? TESSEL_E_TOOBIG : TESSEL_E_UNSUPPORTED; }
+            kp.cdev[d] = kp.fact[n];
+            uint64_t list = 0;
+            int k = 0;
+            for (int y = 0; y < kp.ntd[d]; y++)
+                for (int l = 0; l < NR; l++, k++) list |= (uint64_t)((y << 3) | l) << (5 * k);
+            kp.init_list[d] = list;
+            c *= kp.cdev[d];
+            if (c >> 64) { delete p; return TESSEL_E_TOOBIG; }
+        }
+        p->count = (uint64_t)c;
+    } else if (desc->space == TESSEL_SPACE_CANONICAL) {
+        if (kp.has_fixed) {
+            for (int i = 0; i < K; i++) p->leadtab.push_back((int8_t)desc->fixed_leads[i]);
+        } else if (!gen_leads(*p, K, NR, p->leadtab, (kWsTablesMax / 2) / K)) {
+            delete p; return TESSEL_E_TOOBIG;
+        }
+        p->nlead = p->leadtab.size() / K;
+        unsigned __int128 c = p->nlead;
+        for (int d = 0; d < D; d++) {
+            int cnt[kMaxLT];
+            for (int y = 0; y < kMaxLT; y++) cnt[y] = y < kp.ntd[d] ? NR : 0;
+            kp.cdev[d] = multiset_sequences(cnt, kMaxLT);
+            if (!kp.cdev[d]) { delete p; return TESSEL_E_TOOBIG; }
+            c *= kp.cdev[d];
+            if (c >> 64) { delete p; return TESSEL_E_TOOBIG; }
+        }
+        p->count = (uint64_t)c;
+        const int B = NR + 1;
+        p->wtab.resize((size_t)B * B * B * B);
+        for (int c0 = 0; c0 < B; c0++) for (int c1 = 0; c1 < B; c1++) for (int c2 = 0; c2 < B; c2++) for (int c3 = 0; c3 < B; c3++) {
+            int cnt[4] = {c0, c1, c2, c3};
+            p->wtab[(((size_t)c0 * B + c1) * B + c2) * B + c3] = multiset_sequences(cnt, 4);   // 0 only where never needed
+        }
+    } else {
+        if (desc->num_deps > 128) { delete p; return TESSEL_E_UNSUPPORTED; }
+        p->count = UINT64_MAX;
+    }
+    p->result.period = INT_MAX;
+    *out = p;
+    return TESSEL_OK;
+}
+
+extern "C" void tessel_problem_destroy(tessel_problem *p) { delete p; }
+
+extern "C" int tessel_candidate_count(const tessel_problem *p, uint64_t *count)
+{
+    if (!p || !count) return TESSEL_E_INVALID_ARG;
+    *count = p->count;
+    return TESSEL_OK;
+}
+
+static int ensure_device(tessel_problem *p)
+{
+    if (p->num_cus) return TESSEL_OK;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(p, (int)e);
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) return hip_fail(p, (int)e);
+    p->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    return TESSEL_OK;
+}
+
+static size_t workspace_need(const tessel_problem *p, int num_cus)
+{
+    LaunchShape s = eval_launch_shape(p->kp, num_cus);
+    return kWsBlockRecOff + block_rec_bytes(s.blocks) + 256;
+}
+
+extern "C" int tessel_workspace_bytes(const tessel_problem *p, size_t *bytes)
+{
+    if (!p || !bytes) return TESSEL_E_INVALID_ARG;
+    // sized for the largest grid the launcher uses (8 blocks on each of 256 compute units at most,
+    // more if the device reports more)
+    int cus = p->num_cus ? p->num_cus : 512;
+    *bytes = workspace_need(p, std::max(cus, 512));
+    return TESSEL_OK;
+}
+
+static int range_ok(const tessel_problem *p, uint64_t first, uint64_t count)
+{
+    if (p->count == UINT64_MAX) return first + count >= first ? TESSEL_OK : TESSEL_E_RANGE;
+    if (first > p->count || count > p->count - first) return TESSEL_E_RANGE;
+    return TESSEL_OK;
+}
+
+// binds the workspace: uploads the tables of the exhaustive spaces and clears the running best
+static int bind_workspace(tessel_problem *p, void *ws, size_t bytes, hipStream_t st)
+{
+    if (!ws || ((uintptr_t)ws & 255u)) return TESSEL_E_WORKSPACE;
+    int rc = ensure_device(p);
+    if (rc) return rc;
+    if (bytes < workspace_need(p, p->num_cus)) return TESSEL_E_WORKSPACE;
+    if (p->ws == ws && p->ws_ready) return TESSEL_OK;
+    char *base = (char *)ws + kWsTablesOff;
+    size_t lead_bytes = (p->leadtab.size() + 255) & ~(size_t)255, w_bytes = p->wtab.size() * sizeof(uint64_t);
+    if (lead_bytes + w_bytes > kWsTablesMax) return TESSEL_E_TOOBIG;
+    if (!p->leadtab.empty()) {
+        hipError_t e = hipMemcpyAsync(base, p->leadtab.data(), p->leadtab.size(), hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) return hip_fail(p, (int)e);
+        e = hipMemcpyAsync(base + lead_bytes, p->wtab.data(), w_bytes, hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) return hip_fail(p, (int)e);
+        p->kp.leadtab = (const int8_t *)base;
+        p->kp.wtab = (const uint64_t *)(base + lead_bytes);
+    }
+    int e = launch_reset(ws, st);
+    if (e) return hip_fail(p, e);
+    p->ws = ws; p->ws_ready = true; p->have_detail = false;
+    return TESSEL_OK;
+}
+
+extern "C" int tessel_eval_candidates(tessel_problem *p, uint64_t first, uint64_t count, void *workspace_dev,
+                                      size_t workspace_bytes, void *hip_stream)
+{
+    if (!p) return TESSEL_E_INVALID_ARG;
+    int rc = range_ok(p, first, count);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    rc = bind_workspace(p, workspace_dev, workspace_bytes, st);
+    if (rc) return rc;
+    p->stream = st;
+    p->have_detail = false;
+    if (count == 0) return TESSEL_OK;
+    int e = launch_eval(p->kp, first, count, workspace_dev, p->num_cus, st);
+    return e ? hip_fail(p, e) : TESSEL_OK;
+}
+
+extern "C" int tessel_score_candidates(tessel_problem *p, uint64_t first, uint64_t count, int32_t *code_dev,
+                                       int32_t *peak_dev, void *workspace_dev, size_t workspace_bytes, void *hip_stream)
+{
+    if (!p || !code_dev) return TESSEL_E_INVALID_ARG;
+    int rc = range_ok(p, first, count);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // the workspace carries the tables of the exhaustive spaces; binding a new one clears the running best
+    rc = bind_workspace(p, workspace_dev, workspace_bytes, st);
+    if (rc) return rc;
+    p->stream = st;
+    if (count == 0) return TESSEL_OK;
+    int e = launch_score(p->kp, first, count, code_dev, peak_dev, st);
+    return e ? hip_fail(p, e) : TESSEL_OK;
+}
+
+extern "C" int tessel_reset(tessel_problem *p)
+{
+    if (!p) return TESSEL_E_INVALID_ARG;
+    p->have_detail = false;
+    p->result.period = INT_MAX;
+    if (!p->ws || !p->ws_ready) return TESSEL_OK;
+    int e = launch_reset(p->ws, p->stream);
+    return e ? hip_fail(p, e) : TESSEL_OK;
+}
+
+static int fetch_best(tessel_problem *p)
+{
+    if (!p->ws || !p->ws_ready) { memset(&p->result, 0, sizeof p->result); p->result.period = INT_MAX; return TESSEL_OK; }
+    hipError_t e = hipStreamSynchronize(p->stream);
+    if (e != hipSuccess) return hip_fail(p, (int)e);
+    e = hipMemcpy(&p->result, (char *)p->ws + kWsResultOff, sizeof(DevResult), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(p, (int)e);
+    if (p->result.period == INT_MAX) { p->have_detail = false; return TESSEL_OK; }
+    if (p->have_detail && p->detail_index == p->result.index) return TESSEL_OK;
+    // decode and re-score the best candidate on the GPU for its peaks and orders
+    int le = launch_detail(p->kp, p->result.index, p->ws, p->stream);
+    if (le) return hip_fail(p, le);
+    e = hipStreamSynchronize(p->stream);
+    if (e != hipSuccess) return hip_fail(p, (int)e);
+    e = hipMemcpy(&p->detail, (char *)p->ws + kWsDetailOff, sizeof(DevDetail), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(p, (int)e);
+    p->have_detail = true; p->detail_index = p->result.index;
+    return TESSEL_OK;
+}
+
+extern "C" int tessel_best(tessel_problem *p, tessel_result *out)
+{
+    if (!p || !out) return TESSEL_E_INVALID_ARG;
+    int rc = fetch_best(p);
+    if (rc) return rc;
+    memset(out, 0, sizeof *out);
+    out->lower_bound = p->kp.LB;
+    out->n_evaluated = p->result.n_evaluated;
+    out->n_feasible = p->result.n_status[kOk];
+    for (int s = 1; s < kNumStatus; s++) out->n_reject[s] = p->result.n_status[s];
+    if (p->result.period == INT_MAX) { out->period = -1; return TESSEL_E_NO_FEASIBLE; }
+    out->period = p->result.period;
+    out->index = p->result.index;
+    out->peak_max = INT_MIN;
+    for (int d = 0; d < p->kp.D; d++) { out->peak_mem[d] = p->detail.peak[d]; out->peak_max = std::max(out->peak_max, p->detail.peak[d]); }
+    if (p->detail.status != kOk || p->detail.period != p->result.period) return TESSEL_E_HIP;   // kernels disagree: never expected
+    return TESSEL_OK;
+}
+
+// ---- host post-processing of the single best candidate ---------------------------------
+namespace {
+
+struct Edge { int u, v, w, lag; };
+
+// Difference constraints of the repeated window for the decoded candidate (Eq. 1 [1] and [3]
+// with the window-to-window lags), then the least non-negative start times at period T.
+std::vector<int> least_starts(const tessel_problem *p, const DevDetail &c, int T)
+{
+    const int NR = p->kp.NR, K = p->kp.K, D = p->kp.D;
+    std::vector<Edge> edges;
+    for (size_t e = 0; e < p->dep_src.size(); e++) {
+        int i = p->dep_src[e], j = p->dep_dst[e], delta = c.leads[i] - c.leads[j];
+        for (int q = 0; q < NR; q++) {
+            int qp = q - delta;
+            edges.push_back(qp >= 0 ? Edge{i * NR + qp, j * NR + q, p->t[i], 0} : Edge{i * NR + qp + NR, j * NR + q, p->t[i], 1});
+        }
+    }
+    for (int d = 0; d < D; d++) {
+        std::vector<int> occ(K, 0), nodes;
+        for (int k = 0; k < c.order_len[d]; k++) { int g = c.orders[d][k]; nodes.push_back(g * NR + occ[g]++); }
+        for (size_t k = 0; k + 1 < nodes.size(); k++) edges.push_back(Edge{nodes[k], nodes[k + 1], p->t[nodes[k] / NR], 0});
+        if (!nodes.empty()) edges.push_back(Edge{nodes.back(), nodes.front(), p->t[nodes.back() / NR], 1});
+    }
+    std::vector<int> s(K * NR, 0);
+    for (int pass = 0; pass <= K * NR; pass++) {
+        bool changed = false;
+        for (const Edge &e : edges) {
+            int v = s[e.u] + e.w - e.lag * T;
+            if (v > s[e.v]) { s[e.v] = v; changed = true; }
+        }
+        if (!changed) break;
+    }
+    return s;
+}
+
+}  // namespace
+
+extern "C" int tessel_best_candidate(tessel_problem *p, int32_t *leads, int32_t *order_len, int32_t *orders, int32_t *starts)
+{
+    if (!p) return TESSEL_E_INVALID_ARG;
+    int rc = fetch_best(p);
+    if (rc) return rc;
+    if (p->result.period == INT_MAX) return TESSEL_E_NO_FEASIBLE;
+    const DevDetail &c = p->detail;
+    if (leads) for (int i = 0; i < p->kp.K; i++) leads[i] = c.leads[i];
+    if (order_len) for (int d = 0; d < p->kp.D; d++) order_len[d] = c.order_len[d];
+    if (orders) for (int d = 0; d < p->kp.D; d++) for (int k = 0; k < kMaxPos; k++) orders[d * kMaxPos + k] = k < c.order_len[d] ? c.orders[d][k] : -1;
+    if (starts) {
+        std::vector<int> s = least_starts(p, c, c.period);
+        for (size_t k = 0; k < s.size(); k++) starts[k] = s[k];
+    }
+    return TESSEL_OK;
+}
+
+// Sec. IV-C.  Warm-up = blocks (i, mu) with mu < lead_i, steady = R windows, cool-down = the rest
+// (Eq. 5-6 for every micro-batch the windows do not cover).  Warm-up and cool-down are ordered by a
+// serial greedy list schedule: of the blocks of the phase that are ready (producers scheduled) and
+// fit the cap on each device they occupy, append the one with the smallest (earliest start,
+// micro-batch, type).  A block starts at the maximum of its devices' free times and its producers'
+// ends, which is also the earliest start for the final per-device orders.
+extern "C" int tessel_complete_schedule(tessel_problem *p, tessel_schedule *out)
+{
+    if (!p || !out || !out->start || !out->dev_order || !out->dev_len) return TESSEL_E_INVALID_ARG;
+    int rc = fetch_best(p);
+    if (rc) return rc;
+    if (p->result.period == INT_MAX) return TESSEL_E_NO_FEASIBLE;
+    const DevDetail &c = p->detail;
+    const int N = out->num_microbatches, K = p->kp.K, D = p->kp.D, NR = p->kp.NR, M = p->kp.M;
+    int maxlead = 0;
+    for (int i = 0; i < K; i++) maxlead = std::max(maxlead, c.leads[i]);
+    const int R = N >= 1 ? (N - maxlead) / NR : 0;
+    if (R < 1 || out->capacity < K * N) return TESSEL_E_RANGE;
+    std::vector<int> finish(K * N, -1);
+    std::vector<int> dev_free(D, 0), dev_mem(D, 0);
+    for (int d = 0; d < D; d++) out->dev_len[d] = 0;
+    std::vector<std::vector<int>> producers(K);
+    for (size_t e = 0; e < p->dep_src.size(); e++) producers[p->dep_dst[e]].push_back(p->dep_src[e]);
+
+    auto earliest = [&](int i, int mu, int &est) -> bool {      // false if a producer is not scheduled yet
+        est = 0;
+        for (int a : producers[i]) {
+            if (finish[a * N + mu] < 0) return false;
+            est = std::max(est, finish[a * N + mu]);
+        }
+        for (int d = 0; d < D; d++) if (p->mask[i] >> d & 1u) est = std::max(est, dev_free[d]);
+        return true;
+    };
+    auto commit = [&](int i, int mu, int est) {
+        out->start[i * N + mu] = est;
+        finish[i * N + mu] = est + p->t[i];
+        for (int d = 0; d < D; d++) if (p->mask[i] >> d & 1u) {
+            dev_free[d] = est + p->t[i];
+            dev_mem[d] += p->m[i];
+            out->dev_order[(size_t)d * out->capacity + out->dev_len[d]++] = i * N + mu;
+        }
+    };
+    auto greedy_phase = [&](bool warmup) -> int {
+        std::vector<std::pair<int, int>> todo;
+        for (int i = 0; i < K; i++) {
+            int lo = warmup ? 0 : c.leads[i] + NR * R, hi = warmup ? c.leads[i] : N;
+            for (int mu = lo; mu < hi; mu++) todo.push_back({i, mu});
+        }
+        while (!todo.empty()) {
+            int pick = -1, pick_est = 0;
+            for (size_t k = 0; k < todo.size(); k++) {
+                int i = todo[k].first, mu = todo[k].second, est;
+                if (!earliest(i, mu, est)) continue;
+                bool fits = true;
+                if (p->m[i] > 0)
+                    for (int d = 0; d < D; d++) if ((p->mask[i] >> d & 1u) && dev_mem[d] + p->m[i] > M) fits = false;
+                if (!fits) continue;
+                if (pick < 0) { pick = (int)k; pick_est = est; continue; }
+                int bi = todo[pick].first, bmu = todo[pick].second;
+                if (est < pick_est || (est == pick_est && (mu < bmu || (mu == bmu && i < bi)))) { pick = (int)k; pick_est = est; }
+            }
+            if (pick < 0) return TESSEL_E_NO_SCHEDULE;
+            commit(todo[pick].first, todo[pick].second, pick_est);
+            todo.erase(todo.begin() + pick);
+        }
+        return TESSEL_OK;
+    };
+
+    rc = greedy_phase(true);
+    if (rc) return rc;
+    for (int k = 0; k < R; k++) {
+        // replay the window in any executable sequence of the decoded per-device orders
+        std::vector<int> pos(D, 0), occ(K, 0);
+        int left = K * NR;
+        while (left > 0) {
+            bool moved = false;
+            for (int d = 0; d < D; d++) {
+                if (pos[d] >= c.order_len[d]) continue;
+                int i = c.orders[d][pos[d]], mu = c.leads[i] + occ[i] + NR * k, est;
+                bool heads = true;
+                for (int dd = 0; dd < D; dd++)
+                    if ((p->mask[i] >> dd & 1u) && (pos[dd] >= c.order_len[dd] || c.orders[dd][pos[dd]] != i)) heads = false;
+                if (!heads || !earliest(i, mu, est)) continue;
+                commit(i, mu, est);
+                for (int dd = 0; dd < D; dd++) if (p->mask[i] >> dd & 1u) pos[dd]++;
+                occ[i]++; left--; moved = true;
+            }
+            if (!moved) return TESSEL_E_NO_SCHEDULE;
+        }
+    }
+    rc = greedy_phase(false);
+    if (rc) return rc;
+    out->makespan = *std::max_element(finish.begin(), finish.end());
+    out->period = c.period;
+    out->num_windows = R;
+    return TESSEL_OK;
+}
+
+extern "C" int tessel_last_hip_error(const tessel_problem *p) { return p ? p->last_hip : 0; }

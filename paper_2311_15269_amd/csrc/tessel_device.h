@@ -1,0 +1,92 @@
+// Shared between the host side of the library and its HIP kernels: the kernel-argument
+// block that carries one problem's static tables, and the records the kernels write.
+// (Not part of the public ABI; the oracle does not see this file.)
+#pragma once
+#include <stdint.h>
+
+namespace tessel {
+
+constexpr int kMaxD = 8;         // simulated devices
+constexpr int kMaxLT = 4;        // block types per device
+constexpr int kMaxNR = 8;        // micro-batches per window
+constexpr int kMaxK = 32;        // block types
+constexpr int kMaxPos = kMaxLT * kMaxNR;   // blocks per device and window (32)
+constexpr int kNumStatus = 6;
+constexpr int kWave = 64;
+
+enum Space { kFactorial = 0, kCanonical = 1, kSampledStrict = 2, kSampledRepair = 3 };
+enum Status { kOk = 0, kDup = 1, kTpMismatch = 2, kProp2 = 3, kDeadlock = 4, kMem = 5 };
+
+// Everything a kernel needs to know about the problem (Table I of the paper: D, K, M,
+// t_B, m_B, d_B, dependencies) plus derived tables.  "local symbol" y = position of a block
+// type among the types of one device (ascending type id); a device order is a sequence of
+// 2-bit local symbols.
+struct KParams {
+    int32_t D, K, NR, M;
+    int32_t total;               // K * NR blocks per window
+    int32_t space;               // Space
+    int32_t tp;                  // some block occupies more than one device
+    int32_t npaths;              // dependency chains
+    int32_t nslots;              // D device slots + npaths * 2*NR token slots
+    int32_t nsweeps;             // D + npaths*NR + 1 window sweeps determine the period
+    int32_t LB, UB;
+    int32_t has_fixed;
+    uint32_t step_q16;
+    uint64_t seed;
+    int32_t  ntd[kMaxD];         // block types on device d
+    uint32_t type_of[kMaxD];     // 4 x 8 bit: type id of local symbol y (0xFF = none)
+    uint32_t pred_of[kMaxD];     // 4 x 8 bit: type id of its producer (0xFF = none)
+    uint32_t mask_of[kMaxD];     // 4 x 8 bit: device mask of that type
+    uint32_t tok_of[kMaxD];      // 4 x 8 bit: first token slot of the type's chain
+    uint32_t home_of[kMaxD];     // 4 x 8 bit: (lowest device)*4 + local symbol there
+    int32_t  t_of[kMaxD][kMaxLT];
+    int32_t  m_of[kMaxD][kMaxLT];
+    int8_t   succ[kMaxK];        // consumer type of type g or -1
+    uint8_t  edge_out[kMaxK];    // position of the dependency g -> succ[g] in the caller's list
+    uint8_t  cross_out[kMaxK];   // that dependency joins different device sets
+    uint8_t  rtopo[kMaxK];       // types, consumers before producers
+    uint8_t  fixed[kMaxK];       // fixed leads
+    int8_t   pred[kMaxK];        // producer type of type g or -1
+    int32_t  t_loc[kMaxK];       // t by home code (device*4 + symbol)
+    uint32_t mask_loc[kMaxK];    // device mask by home code
+    uint32_t fact[13];           // FACTORIAL: n! for n <= 12
+    uint64_t init_list[kMaxD];   // FACTORIAL: labelled blocks of a device, 5 bits each (y<<3 | label)
+    uint64_t cdev[kMaxD];        // FACTORIAL: n_d!;  CANONICAL: arrangements of device d
+    const int8_t   *leadtab;     // CANONICAL: [nlead][K] in device memory
+    const uint64_t *wtab;        // CANONICAL: arrangements by remaining counts, base NR+1 digits
+};
+
+// Running best + counters of one search; lives at the start of the caller's workspace.
+struct DevResult {
+    int32_t  period;             // INT32_MAX = nothing feasible yet
+    int32_t  pad;
+    uint64_t index;
+    uint64_t n_evaluated;
+    uint64_t n_status[kNumStatus];   // [kOk] = feasible
+};
+
+// Decoded best candidate, written by the detail kernel.
+struct DevDetail {
+    int32_t status, period;
+    int32_t peak[kMaxD];
+    int32_t leads[kMaxK];
+    int32_t order_len[kMaxD];
+    int32_t orders[kMaxD][kMaxPos];
+};
+
+constexpr size_t kWsResultOff = 0;
+constexpr size_t kWsDetailOff = 256;
+constexpr size_t kWsTablesOff = 4096;          // lead table, arrangement table
+constexpr size_t kWsTablesMax = 1 << 20;
+constexpr size_t kWsBlockRecOff = kWsTablesOff + kWsTablesMax;
+
+struct LaunchShape { int blocks, threads; size_t lds_bytes; };
+
+// kernels.hip
+LaunchShape eval_launch_shape(const KParams &kp, int num_cus);
+int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream);
+int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *stream);
+int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream);
+int launch_reset(void *ws, void *stream);
+
+}  // namespace tessel

@@ -1,0 +1,636 @@
+// HIP kernels (gfx950) that score repetend candidates: one candidate per lane.
+//
+// Per candidate (Tessel, arXiv 2311.15269; Alg. 1, body of the loop over repetends):
+//   decode   index -> lead vector (n_i of Eq. 3) + per-device block orders
+//   build    walk the orders in an executable (topological) sequence, detect orders that
+//            can never run, repair them in the REPAIR space, track the per-device memory
+//            prefix (Eq. 1 [2]) and leave a compact "program" of the window in LDS
+//   period   the repetend time t_R of Eq. 4 (with compaction of neighbouring repetends):
+//            the least period of the rigidly repeated window.  The window is a max-plus
+//            linear map on (device free times, end times of the micro-batches that are in
+//            flight at the window boundary); its growth rate is the maximum cycle ratio,
+//            obtained exactly from Karp's formula after V+1 sweeps of the window
+//   argmin   (period, index) lexicographic, lane -> wave -> block record -> grid merge
+//
+// State that is indexed per lane at run time (device free times, micro-batch tokens, the
+// program) lives in LDS laid out [slot][lane], which is bank-conflict free for any
+// per-lane slot; everything else is in VGPRs.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <limits.h>
+
+#include "tessel_device.h"
+
+namespace tessel {
+
+struct BlockRec {
+    int32_t  period;
+    int32_t  pad;
+    uint64_t index;
+    uint32_t n_status[kNumStatus];
+    uint32_t n_evaluated;
+    uint32_t pad2;
+};
+
+// ------------------------------------------------------------------ counter-based sampler
+// SplitMix64 finaliser keys the candidate; MurmurHash3's 32-bit finaliser, with the second
+// key folded in between its multiplications, gives the w-th word; two 16-bit draws a word.
+__device__ __forceinline__ uint64_t mix64(uint64_t z)
+{
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27; z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31;
+    return z;
+}
+__device__ __forceinline__ uint32_t stream_word(uint32_t a, uint32_t b, uint32_t w)
+{
+    uint32_t x = a + w * 0x9E3779B9u;
+    x ^= x >> 16; x *= 0x85EBCA6Bu;
+    x ^= b;
+    x ^= x >> 13; x *= 0xC2B2AE35u;
+    x ^= x >> 16;
+    return x;
+}
+constexpr uint32_t kDrawLeadBase = 0u;
+constexpr uint32_t kDrawOrdBase = 128u;
+
+// ------------------------------------------------------------------ 4-bit counters per type
+// next micro-batch index of every block type: lead + occurrences placed, 4 bits each
+struct Mu {
+    uint64_t lo, hi;
+    __device__ __forceinline__ uint32_t get(uint32_t g) const
+    {
+        uint64_t w = g < 16 ? lo : hi;
+        return (uint32_t)(w >> ((g & 15u) * 4u)) & 15u;
+    }
+    __device__ __forceinline__ void set(uint32_t g, uint32_t v)
+    {
+        uint64_t m = 15ull << ((g & 15u) * 4u), x = (uint64_t)v << ((g & 15u) * 4u);
+        if (g < 16) lo = (lo & ~m) | x; else hi = (hi & ~m) | x;
+    }
+    __device__ __forceinline__ void inc(uint32_t g)
+    {
+        uint64_t x = 1ull << ((g & 15u) * 4u);
+        if (g < 16) lo += x; else hi += x;
+    }
+};
+
+__device__ __forceinline__ uint32_t byte_of(uint32_t packed, uint32_t y) { return (packed >> (8u * y)) & 0xFFu; }
+
+__device__ __forceinline__ int sel4(const int32_t (&v)[kMaxLT], uint32_t y)
+{
+    int a = y & 1u ? v[1] : v[0];
+    int b = y & 1u ? v[3] : v[2];
+    return y & 2u ? b : a;
+}
+
+// remove the 2-bit entry at position pos (entries above move down)
+__device__ __forceinline__ uint64_t remove_at(uint64_t x, uint32_t pos)
+{
+    uint64_t low = x & ((1ull << (2u * pos)) - 1ull);
+    uint64_t high = ((x >> (2u * pos)) >> 2) << (2u * pos);
+    return low | high;
+}
+
+// position of the first entry equal to y among the first len entries, or 64 if none
+__device__ __forceinline__ uint32_t find_first(uint64_t x, uint32_t len, uint32_t y)
+{
+    uint64_t z = x ^ (0x5555555555555555ull * y);
+    uint64_t hit = ~(z | (z >> 1)) & 0x5555555555555555ull;
+    if (len < 32) hit &= (1ull << (2u * len)) - 1ull;
+    return hit ? (uint32_t)__builtin_ctzll(hit) >> 1 : 64u;
+}
+
+// ------------------------------------------------------------------ one window sweep
+// Program entry: bits 0-4 home code of the block type (device*4 + symbol), bits 5-10 token
+// slot.  s = max(free time of its device(s), end of the micro-batch's previous block);
+// both become s + t.  A chain's first block reads a token slot nobody has written: 0.
+template <bool TP>
+__device__ __forceinline__ void sweep_window(const KParams &P, const uint16_t *prog, uint32_t *state,
+                                             const int32_t *t_tab, const uint32_t *mask_tab)
+{
+    const int total = P.total;
+    for (int k = 0; k < total; k++) {
+        uint32_t e = prog[k * kWave];
+        uint32_t loc = e & 31u, ts = e >> 5;
+        uint32_t tok = state[ts * kWave];
+        uint32_t t = (uint32_t)t_tab[loc];
+        if (!TP) {
+            uint32_t ds = loc >> 2;
+            uint32_t en = max(state[ds * kWave], tok) + t;
+            state[ds * kWave] = en;
+            state[ts * kWave] = en;
+        } else {
+            uint32_t mask = mask_tab[loc], s = tok;
+            for (int d = 0; d < P.D; d++)
+                if (mask >> d & 1u) s = max(s, state[d * kWave]);
+            uint32_t en = s + t;
+            for (int d = 0; d < P.D; d++)
+                if (mask >> d & 1u) state[d * kWave] = en;
+            state[ts * kWave] = en;
+        }
+    }
+    // window boundary: micro-batches mu >= N_R are mu - N_R of the next window
+    for (int p = 0; p < P.npaths; p++)
+        for (int mu = 0; mu < P.NR; mu++) {
+            int base = P.D + p * 2 * P.NR + mu;
+            state[base * kWave] = state[(base + P.NR) * kWave];
+            state[(base + P.NR) * kWave] = 0;
+        }
+}
+
+__device__ __forceinline__ int reduced_slot(const KParams &P, int v)
+{
+    if (v < P.D) return v;
+    int p = (v - P.D) / P.NR, mu = (v - P.D) % P.NR;
+    return P.D + p * 2 * P.NR + mu;
+}
+
+// Least period of the repeated window = ceil(maximum cycle ratio) of the max-plus map x -> F(x)
+// that one sweep applies to the V = D + npaths*N_R boundary values (plus the constant 0 that
+// keeps start times non-negative).  Karp: with x(j) the vector after j+1 sweeps from 0 and
+// n = V+1 sweeps in total, lambda = max_v min_{j<n-1} (x_v(n-1) - x_v(j)) / (n-1-j).
+// Two passes over the same sweeps so that no history has to be stored.
+template <int VM, bool TP>
+__device__ int least_period(const KParams &P, const uint16_t *prog, uint32_t *state, const int32_t *t_tab,
+                            const uint32_t *mask_tab)
+{
+    const int V = P.nsweeps - 1, n = P.nsweeps;
+    uint32_t xn[VM], bn[VM], bd[VM];
+    for (int s = 0; s < P.nslots; s++) state[s * kWave] = 0;
+    for (int j = 0; j < n; j++) sweep_window<TP>(P, prog, state, t_tab, mask_tab);
+#pragma unroll
+    for (int v = 0; v < VM; v++) {
+        xn[v] = v < V ? state[reduced_slot(P, v) * kWave] : 0u;
+        bn[v] = 0xFFFFFFFFu; bd[v] = 1u;
+    }
+    for (int s = 0; s < P.nslots; s++) state[s * kWave] = 0;
+    for (int j = 0; j < n - 1; j++) {
+        sweep_window<TP>(P, prog, state, t_tab, mask_tab);
+        uint32_t den = (uint32_t)(n - 1 - j);
+#pragma unroll
+        for (int v = 0; v < VM; v++) {
+            if (v < V) {
+                uint32_t a = xn[v] - state[reduced_slot(P, v) * kWave];
+                // a/den < bn/bd  <=>  a*bd < bn*den   (all below 2^31, checked at problem creation)
+                bool better = bn[v] == 0xFFFFFFFFu || (uint64_t)a * bd[v] < (uint64_t)bn[v] * den;
+                if (better) { bn[v] = a; bd[v] = den; }
+            }
+        }
+    }
+    uint32_t T = 0;
+#pragma unroll
+    for (int v = 0; v < VM; v++) {
+        if (v < V) {
+            uint32_t c = (bn[v] + bd[v] - 1u) / bd[v];
+            T = max(T, c);
+        }
+    }
+    return (int)T;
+}
+
+// ------------------------------------------------------------------ one candidate
+template <int DM, int VM>
+__device__ int evaluate(const KParams &P, uint64_t idx, uint16_t *prog, uint32_t *state, const int32_t *t_tab,
+                        const uint32_t *mask_tab, int &period, int (&peak)[DM], DevDetail *detail)
+{
+    const uint32_t NR = (uint32_t)P.NR;
+    uint64_t rem[DM];
+    int remlen[DM];
+    Mu mu;
+    mu.lo = 0; mu.hi = 0;
+    period = 0;
+#pragma unroll
+    for (int d = 0; d < DM; d++) { rem[d] = 0; remlen[d] = 0; peak[d] = 0; }
+
+    // ---------------- decode
+    if (P.space == kFactorial) {
+        uint64_t rest = idx;
+        bool dup = false, tpm = false;
+        uint32_t seen_types = 0;
+#pragma unroll
+        for (int d = 0; d < DM; d++) {
+            if (d >= P.D) continue;
+            const uint32_t n = (uint32_t)P.ntd[d] * NR;
+            uint32_t r = (uint32_t)(rest % P.cdev[d]);
+            rest /= P.cdev[d];
+            uint64_t list = P.init_list[d], o = 0;
+            uint32_t firstlab = 0xFFFFFFFFu, seencnt = 0;
+            for (uint32_t pos = 0; pos < n; pos++) {
+                uint32_t f = P.fact[n - 1 - pos];
+                uint32_t digit = r / f;
+                r -= digit * f;
+                uint32_t code = (uint32_t)(list >> (5u * digit)) & 31u;
+                uint64_t low = list & ((1ull << (5u * digit)) - 1ull);
+                list = low | (((list >> (5u * digit)) >> 5) << (5u * digit));
+                uint32_t y = code >> 3, lab = code & 7u;
+                o |= (uint64_t)y << (2u * pos);
+                uint32_t fl = byte_of(firstlab, y), sc = byte_of(seencnt, y);
+                if (fl == 0xFFu) firstlab = (firstlab & ~(0xFFu << (8u * y))) | (lab << (8u * y));
+                else {
+                    uint32_t want = fl + sc;                 // labels continue cyclically (Property 1)
+                    if (want >= NR) want -= NR;
+                    if (lab != want) dup = true;
+                }
+                seencnt += 1u << (8u * y);
+            }
+            rem[d] = o; remlen[d] = (int)n;
+            for (int y = 0; y < P.ntd[d]; y++) {
+                uint32_t g = byte_of(P.type_of[d], (uint32_t)y), fl = byte_of(firstlab, (uint32_t)y);
+                if (seen_types >> g & 1u) { if (mu.get(g) != fl) tpm = true; }
+                else { mu.set(g, fl); seen_types |= 1u << g; }
+            }
+        }
+        if (dup) return kDup;
+        if (tpm) return kTpMismatch;
+        for (int g = 0; g < P.K; g++) {
+            int p = P.pred[g];
+            if (p >= 0 && mu.get((uint32_t)p) < mu.get((uint32_t)g)) return kProp2;
+        }
+    } else if (P.space == kCanonical) {
+        uint64_t rest = idx;
+        const uint32_t B = NR + 1;
+#pragma unroll
+        for (int d = 0; d < DM; d++) {
+            if (d >= P.D) continue;
+            const uint32_t n = (uint32_t)P.ntd[d] * NR;
+            uint64_t r = rest % P.cdev[d];
+            rest /= P.cdev[d];
+            uint32_t c[kMaxLT];
+#pragma unroll
+            for (int y = 0; y < kMaxLT; y++) c[y] = y < P.ntd[d] ? NR : 0u;
+            uint64_t o = 0;
+            for (uint32_t pos = 0; pos < n; pos++) {
+                bool chosen = false;
+#pragma unroll
+                for (int y = 0; y < kMaxLT; y++) {
+                    if (!chosen && c[y] > 0) {
+                        c[y]--;
+                        uint64_t w = P.wtab[((c[0] * B + c[1]) * B + c[2]) * B + c[3]];
+                        if (r < w) { o |= (uint64_t)y << (2u * pos); chosen = true; }
+                        else { r -= w; c[y]++; }
+                    }
+                }
+            }
+            rem[d] = o; remlen[d] = (int)n;
+        }
+        const int8_t *row = P.leadtab + rest * (uint64_t)P.K;
+        for (int g = 0; g < P.K; g++) mu.set((uint32_t)g, (uint32_t)row[g]);
+    } else {
+        uint64_t z = mix64(P.seed + 0x9E3779B97F4A7C15ULL * (idx + 1));
+        const uint32_t a = (uint32_t)z, b = (uint32_t)(z >> 32);
+        if (P.has_fixed) {
+            for (int g = 0; g < P.K; g++) mu.set((uint32_t)g, P.fixed[g]);
+        } else {
+            for (int k = 0; k < P.K; k++) {
+                uint32_t i = P.rtopo[k];
+                int j = P.succ[i];
+                uint32_t lead = 0;
+                if (j >= 0) {
+                    uint32_t e = kDrawLeadBase + P.edge_out[i];
+                    uint32_t u = (stream_word(a, b, e >> 1) >> (16u * (e & 1u))) & 0xFFFFu;
+                    uint32_t step = (P.cross_out[i] && u < P.step_q16) ? 1u : 0u;
+                    lead = min(NR - 1u, mu.get((uint32_t)j) + step);
+                }
+                mu.set(i, lead);
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < DM; d++) {
+            if (d >= P.D) continue;
+            const uint32_t n = (uint32_t)P.ntd[d] * NR;
+            uint32_t c0 = P.ntd[d] > 0 ? NR : 0u, c1 = P.ntd[d] > 1 ? NR : 0u, c2 = P.ntd[d] > 2 ? NR : 0u;
+            uint64_t o = 0;
+            uint32_t word = 0;
+            for (uint32_t pos = 0; pos < n; pos++) {
+                uint32_t j = kDrawOrdBase + 32u * (uint32_t)d + pos;
+                if ((pos & 1u) == 0) word = stream_word(a, b, j >> 1);
+                uint32_t u = (word >> (16u * (pos & 1u))) & 0xFFFFu;
+                uint32_t digit = (u * (n - pos)) >> 16;
+                uint32_t y = (digit >= c0) + (digit >= c0 + c1) + (digit >= c0 + c1 + c2);
+                c0 -= y == 0; c1 -= y == 1; c2 -= y == 2;
+                o |= (uint64_t)y << (2u * pos);
+            }
+            rem[d] = o; remlen[d] = (int)n;
+        }
+    }
+
+    if (detail) {
+        for (int g = 0; g < P.K; g++) detail->leads[g] = (int)mu.get((uint32_t)g);
+        for (int d = 0; d < kMaxD; d++) detail->order_len[d] = 0;
+    }
+
+    // ---------------- memory at the window entry: blocks that ran before it (type i has
+    // handled micro-batches 0 .. lead_i - 1)
+    int memcur[DM];
+#pragma unroll
+    for (int d = 0; d < DM; d++) {
+        memcur[d] = 0;
+        if (d < P.D)
+            for (int y = 0; y < P.ntd[d]; y++)
+                memcur[d] += P.m_of[d][y] * (int)mu.get(byte_of(P.type_of[d], (uint32_t)y));
+        peak[d] = INT_MIN;
+    }
+
+    // ---------------- build: place blocks in an executable sequence
+    const bool repair = P.space == kSampledRepair;
+    int placed = 0;
+    const int total = P.total;
+    bool deadlock = false;
+
+    // places block type g (its next occurrence) taking entry pos[dd] of every device dd it occupies
+    auto place = [&](uint32_t g, uint32_t mask, uint32_t home, uint32_t tokbase, int m, uint32_t pos_d, int d_static) {
+        uint32_t mug = mu.get(g);
+        prog[placed * kWave] = (uint16_t)(home | ((tokbase + mug) << 5));
+        mu.inc(g);
+        placed++;
+#pragma unroll
+        for (int dd = 0; dd < DM; dd++) {
+            if (dd >= P.D) continue;
+            bool here = (mask >> dd) & 1u;
+            if (!here) continue;
+            uint32_t pos = 0;
+            if (dd == d_static) pos = pos_d;
+            else if (pos_d != 0xFFFFFFFFu && repair) {
+                // multi-device block placed out of line: its earliest entry on the other devices
+                uint32_t ysym = 0;
+                for (int y = 0; y < P.ntd[dd]; y++) if (byte_of(P.type_of[dd], (uint32_t)y) == g) ysym = (uint32_t)y;
+                pos = find_first(rem[dd], (uint32_t)remlen[dd], ysym);
+            }
+            rem[dd] = remove_at(rem[dd], pos);
+            remlen[dd]--;
+            memcur[dd] += m;
+            peak[dd] = max(peak[dd], memcur[dd]);
+            if (detail) detail->orders[dd][detail->order_len[dd]++] = (int)g;
+        }
+    };
+
+    while (placed < total && !deadlock) {
+        bool progress = false;
+#pragma unroll
+        for (int d = 0; d < DM; d++) {
+            if (d >= P.D || remlen[d] == 0) continue;
+            uint32_t y = (uint32_t)rem[d] & 3u;
+            uint32_t g = byte_of(P.type_of[d], y), pr = byte_of(P.pred_of[d], y);
+            uint32_t mask = byte_of(P.mask_of[d], y);
+            bool ok = pr == 0xFFu || mu.get(pr) > mu.get(g);
+            if (P.tp && mask != (1u << d)) {
+                // a multi-device block runs when it heads the list of all its devices; it is
+                // placed from its lowest device
+                if ((mask & ((1u << d) - 1u)) != 0) ok = false;
+#pragma unroll
+                for (int dd = 0; dd < DM; dd++) {
+                    if (dd >= P.D || dd == d || !((mask >> dd) & 1u)) continue;
+                    bool head = remlen[dd] > 0 && byte_of(P.type_of[dd], (uint32_t)rem[dd] & 3u) == g;
+                    if (!head) ok = false;
+                }
+            }
+            if (ok) {
+                place(g, mask, byte_of(P.home_of[d], y), byte_of(P.tok_of[d], y), sel4(P.m_of[d], y), 0u, d);
+                progress = true;
+            }
+        }
+        if (progress) continue;
+        if (!repair) { deadlock = true; break; }
+        // Nothing at the head of any list can run.  Ascending over devices, then over the
+        // device's remaining entries in list order: the first block whose producers are
+        // placed goes next (only the first entry of each type can be that block).
+        bool done = false;
+#pragma unroll
+        for (int d = 0; d < DM; d++) {
+            if (done || d >= P.D || remlen[d] == 0) continue;
+            uint32_t best_pos = 64u, best_y = 0;
+#pragma unroll
+            for (int y = 0; y < kMaxLT; y++) {
+                if (y >= P.ntd[d]) continue;
+                uint32_t g = byte_of(P.type_of[d], (uint32_t)y), pr = byte_of(P.pred_of[d], (uint32_t)y);
+                bool ready = pr == 0xFFu || mu.get(pr) > mu.get(g);
+                uint32_t pos = ready ? find_first(rem[d], (uint32_t)remlen[d], (uint32_t)y) : 64u;
+                if (pos < best_pos) { best_pos = pos; best_y = (uint32_t)y; }
+            }
+            if (best_pos < 64u) {
+                uint32_t y = best_y;
+                place(byte_of(P.type_of[d], y), byte_of(P.mask_of[d], y), byte_of(P.home_of[d], y),
+                      byte_of(P.tok_of[d], y), sel4(P.m_of[d], y), best_pos, d);
+                done = true;
+            }
+        }
+        if (!done) { deadlock = true; }     // cannot happen: unplaced blocks form a DAG
+    }
+    if (deadlock) {
+#pragma unroll
+        for (int d = 0; d < DM; d++) peak[d] = 0;
+        return kDeadlock;
+    }
+    int peak_max = INT_MIN;
+#pragma unroll
+    for (int d = 0; d < DM; d++) {
+        if (d >= P.D || peak[d] == INT_MIN) peak[d] = 0;      // a device without blocks
+        if (d < P.D) peak_max = max(peak_max, peak[d]);
+    }
+    if (peak_max > P.M) return kMem;
+
+    // ---------------- period
+    period = P.tp ? least_period<VM, true>(P, prog, state, t_tab, mask_tab)
+                  : least_period<VM, false>(P, prog, state, t_tab, mask_tab);
+    return kOk;
+}
+
+// ------------------------------------------------------------------ kernels
+__device__ __forceinline__ bool key_less(int pa, uint64_t ia, int pb, uint64_t ib)
+{
+    return pa < pb || (pa == pb && ia < ib);
+}
+
+template <int DM, int VM>
+__global__ __launch_bounds__(kWave) void eval_kernel(KParams P, uint64_t first, uint64_t count, BlockRec *recs,
+                                                     int32_t *code_out, int32_t *peak_out, DevDetail *detail)
+{
+    extern __shared__ uint32_t lds[];
+    int32_t *t_tab = (int32_t *)lds;
+    uint32_t *mask_tab = lds + kMaxK;
+    uint32_t *state_all = lds + 2 * kMaxK;
+    uint16_t *prog_all = (uint16_t *)(state_all + P.nslots * kWave);
+    const int lane = threadIdx.x;
+    if (lane < kMaxK) { t_tab[lane] = P.t_loc[lane]; mask_tab[lane] = P.mask_loc[lane]; }
+    __syncthreads();
+    uint32_t *state = state_all + lane;
+    uint16_t *prog = prog_all + lane;
+
+    int best = INT_MAX;
+    uint64_t best_idx = 0;
+    uint32_t cnt[kNumStatus];
+#pragma unroll
+    for (int s = 0; s < kNumStatus; s++) cnt[s] = 0;
+    uint32_t nev = 0;
+
+    const uint64_t stride = (uint64_t)gridDim.x * kWave;
+    for (uint64_t k = (uint64_t)blockIdx.x * kWave + lane; k < count; k += stride) {
+        int period, peak[DM];
+        int status = evaluate<DM, VM>(P, first + k, prog, state, t_tab, mask_tab, period, peak, detail);
+        nev++;
+#pragma unroll
+        for (int s = 0; s < kNumStatus; s++) cnt[s] += status == s;
+        if (status == kOk && period < best) { best = period; best_idx = first + k; }   // ascending k: first wins
+        int pk = 0;
+        if (status == kOk || status == kMem) {
+            pk = INT_MIN;
+#pragma unroll
+            for (int d = 0; d < DM; d++) if (d < P.D) pk = max(pk, peak[d]);
+        }
+        if (code_out) code_out[k] = status == kOk ? period : -status;
+        if (peak_out) peak_out[k] = pk;
+        if (detail) {
+            detail->status = status; detail->period = period;
+            for (int d = 0; d < kMaxD; d++) detail->peak[d] = 0;
+#pragma unroll
+            for (int d = 0; d < DM; d++) if (d < P.D) detail->peak[d] = peak[d];
+        }
+    }
+    if (!recs) return;
+    // wave argmin over the total order (period, index); sums of the counters
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        int op = __shfl_xor(best, off);
+        uint32_t ilo = __shfl_xor((uint32_t)best_idx, off), ihi = __shfl_xor((uint32_t)(best_idx >> 32), off);
+        uint64_t oi = ((uint64_t)ihi << 32) | ilo;
+        if (key_less(op, oi, best, best_idx)) { best = op; best_idx = oi; }
+#pragma unroll
+        for (int s = 0; s < kNumStatus; s++) cnt[s] += __shfl_xor(cnt[s], off);
+        nev += __shfl_xor(nev, off);
+    }
+    if (lane == 0) {
+        BlockRec r;
+        r.period = best; r.pad = 0; r.index = best_idx; r.n_evaluated = nev; r.pad2 = 0;
+#pragma unroll
+        for (int s = 0; s < kNumStatus; s++) r.n_status[s] = cnt[s];
+        recs[blockIdx.x] = r;
+    }
+}
+
+// merges the block records of one launch into the running best (one wave)
+__global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int nrecs, DevResult *res)
+{
+    const int lane = threadIdx.x;
+    int best = INT_MAX;
+    uint64_t best_idx = 0, nev = 0, cnt[kNumStatus];
+#pragma unroll
+    for (int s = 0; s < kNumStatus; s++) cnt[s] = 0;
+    for (int k = lane; k < nrecs; k += kWave) {
+        BlockRec r = recs[k];
+        if (key_less(r.period, r.index, best, best_idx)) { best = r.period; best_idx = r.index; }
+        nev += r.n_evaluated;
+#pragma unroll
+        for (int s = 0; s < kNumStatus; s++) cnt[s] += r.n_status[s];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        int op = __shfl_xor(best, off);
+        uint32_t ilo = __shfl_xor((uint32_t)best_idx, off), ihi = __shfl_xor((uint32_t)(best_idx >> 32), off);
+        uint64_t oi = ((uint64_t)ihi << 32) | ilo;
+        if (key_less(op, oi, best, best_idx)) { best = op; best_idx = oi; }
+        uint32_t lo = __shfl_xor((uint32_t)nev, off), hi = __shfl_xor((uint32_t)(nev >> 32), off);
+        nev += ((uint64_t)hi << 32) | lo;
+#pragma unroll
+        for (int s = 0; s < kNumStatus; s++) {
+            uint32_t l2 = __shfl_xor((uint32_t)cnt[s], off), h2 = __shfl_xor((uint32_t)(cnt[s] >> 32), off);
+            cnt[s] += ((uint64_t)h2 << 32) | l2;
+        }
+    }
+    if (lane == 0) {
+        if (key_less(best, best_idx, res->period, res->index)) { res->period = best; res->index = best_idx; }
+        res->n_evaluated += nev;
+#pragma unroll
+        for (int s = 0; s < kNumStatus; s++) res->n_status[s] += cnt[s];
+    }
+}
+
+__global__ void reset_kernel(DevResult *res)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        res->period = INT_MAX; res->pad = 0; res->index = ~0ull; res->n_evaluated = 0;
+        for (int s = 0; s < kNumStatus; s++) res->n_status[s] = 0;
+    }
+}
+
+// ------------------------------------------------------------------ launchers
+static size_t lds_bytes_for(const KParams &kp)
+{
+    return (size_t)2 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)kp.total * kWave * 2;
+}
+
+LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
+{
+    LaunchShape s;
+    s.threads = kWave;
+    s.lds_bytes = lds_bytes_for(kp);
+    int per_cu = (int)((160 * 1024) / s.lds_bytes);
+    if (per_cu > 8) per_cu = 8;
+    if (per_cu < 1) per_cu = 1;
+    s.blocks = num_cus * per_cu;
+    return s;
+}
+
+typedef void (*eval_fn)(KParams, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, DevDetail *);
+
+static eval_fn pick_kernel(const KParams &kp)
+{
+    const int V = kp.nsweeps - 1;
+    if (kp.D <= 2 && V <= 4) return eval_kernel<2, 4>;
+    if (kp.D <= 4 && V <= 8) return eval_kernel<4, 8>;
+    if (kp.D <= 8 && V <= 16) return eval_kernel<8, 16>;
+    return eval_kernel<8, 24>;
+}
+
+static int launch_common(const KParams &kp, uint64_t first, uint64_t count, int blocks, BlockRec *recs, int32_t *code,
+                         int32_t *peak, DevDetail *detail, hipStream_t st)
+{
+    eval_fn fn = pick_kernel(kp);
+    size_t lds = lds_bytes_for(kp);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return (int)e;
+    }
+    hipLaunchKernelGGL(fn, dim3(blocks), dim3(kWave), lds, st, kp, first, count, recs, code, peak, detail);
+    return (int)hipGetLastError();
+}
+
+int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    LaunchShape s = eval_launch_shape(kp, num_cus);
+    uint64_t need = (count + kWave - 1) / kWave;
+    int blocks = need < (uint64_t)s.blocks ? (int)need : s.blocks;
+    if (blocks < 1) return 0;
+    BlockRec *recs = (BlockRec *)((char *)ws + kWsBlockRecOff);
+    int rc = launch_common(kp, first, count, blocks, recs, nullptr, nullptr, nullptr, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(merge_kernel, dim3(1), dim3(kWave), 0, st, recs, blocks, (DevResult *)((char *)ws + kWsResultOff));
+    return (int)hipGetLastError();
+}
+
+int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    LaunchShape s = eval_launch_shape(kp, 256);
+    uint64_t need = (count + kWave - 1) / kWave;
+    int blocks = need < (uint64_t)s.blocks ? (int)need : s.blocks;
+    if (blocks < 1) return 0;
+    return launch_common(kp, first, count, blocks, nullptr, code, peak, nullptr, st);
+}
+
+int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream)
+{
+    return launch_common(kp, index, 1, 1, nullptr, nullptr, nullptr, (DevDetail *)((char *)ws + kWsDetailOff),
+                         (hipStream_t)stream);
+}
+
+int launch_reset(void *ws, void *stream)
+{
+    hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream, (DevResult *)((char *)ws + kWsResultOff));
+    return (int)hipGetLastError();
+}
+
+size_t block_rec_bytes(int blocks) { return (size_t)blocks * sizeof(BlockRec); }
+
+}  // namespace tessel

@@ -1,0 +1,52 @@
+"""The C-ABI library loads and exports every symbol include/tessel.h declares; host-only
+error paths.  No GPU, no compute calls."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2311_15269_amd import binding, workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "tessel.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tessel_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load_library()
+    names = declared_functions()
+    assert len(names) >= 10
+    assert sorted(names) == sorted(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_problem_create_validates_on_the_host():
+    p = binding.Problem(W.config1())
+    assert p.candidate_count() == 576
+    assert binding.Problem(W.config2()).candidate_count() == 120 * 70 ** 4
+    assert binding.Problem(W.config5()).candidate_count() == 2 ** 64 - 1
+    assert p.workspace_bytes() > 0
+    for bad, code in (
+        (dict(W.config1(), m=[1, 1, -1, 0]), -3),
+        (dict(W.config1(), deps=[(0, 1), (1, 0)]), -2),
+        (dict(W.config1(), t=[0, 1, 2, 2]), -1),
+        (dict(W.config1(), NR=9), -9),
+        (dict(W.config1(), deps=[(0, 1), (0, 2), (2, 3)]), -9),
+        (dict(W.config1(), fixed_leads=[0, 0, 0, 0]), -1),
+        (W.pipeline_problem(W.folded_placement(8), [1] * 16, [1] * 16, 8, 8, 10, "canonical"), -4),
+    ):
+        with pytest.raises(binding.TesselError) as e:
+            binding.Problem(bad)
+        assert e.value.code == code, bad
+
+
+def test_strerror_covers_all_codes():
+    lib = binding.load_library()
+    texts = {lib.tessel_strerror(c).decode() for c in range(0, -11, -1)}
+    assert len(texts) == 11 and "unknown error" not in texts

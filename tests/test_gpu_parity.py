@@ -1,0 +1,256 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI, element by element.
+Integer work: everything must match bit-exactly."""
+import numpy as np
+import pytest
+
+from paper_2311_15269_amd import workloads as W
+from tests import schedule_checks as SC
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: the HIP path has no CPU fallback")
+    from paper_2311_15269_amd import binding
+    binding.load_library()
+    return binding
+
+
+def compare_scores(gpu, prob, first, count):
+    from oracle import Oracle
+    g = gpu.Problem(prob)
+    code, peak = g.score_candidates(first, count)
+    want_code, want_peak = Oracle(prob).score_range(first, count)
+    code, peak = code.cpu().numpy(), peak.cpu().numpy()
+    bad = np.nonzero(code != want_code)[0]
+    assert bad.size == 0, (prob["name"], "first mismatch at", first + int(bad[0]), int(code[bad[0]]), int(want_code[bad[0]]))
+    bad = np.nonzero(peak != want_peak)[0]
+    assert bad.size == 0, (prob["name"], "peak mismatch at", first + int(bad[0]), int(peak[bad[0]]), int(want_peak[bad[0]]))
+    return want_code
+
+
+def compare_best(gpu, prob, first, count, pieces=None):
+    from oracle import Oracle
+    g = gpu.Problem(prob)
+    if pieces is None:
+        g.eval_candidates(first, count)
+    else:
+        for a, n in pieces:
+            g.eval_candidates(a, n)
+    got = g.best()
+    want = Oracle(prob).sweep(first, count)
+    assert got["n_evaluated"] == want["n_evaluated"] == count
+    assert got["n_feasible"] == want["n_feasible"]
+    assert got["n_reject"][1:] == want["n_reject"][1:]
+    assert got["lower_bound"] == Oracle(prob).lower_bound
+    if want["n_feasible"] == 0:
+        assert not got["feasible"]
+        return g, got, want
+    assert got["feasible"]
+    assert (got["period"], got["index"]) == (want["period"], want["index"])
+    assert got["peak"] == want["peak"] and got["peak_max"] == want["peak_max"]
+    return g, got, want
+
+
+# ---------------------------------------------------------------- config 1: exhaustive
+def test_config1_every_candidate(gpu):
+    prob = W.config1()
+    code = compare_scores(gpu, prob, 0, 576)
+    assert (code > 0).sum() == 27
+    g, got, want = compare_best(gpu, prob, 0, 576)
+    assert got["period"] == 6 == got["lower_bound"]
+    from oracle import Oracle
+    orc = Oracle(prob)
+    cand = g.best_candidate()
+    st, leads, orders = orc.decode(got["index"])
+    assert cand["leads"] == leads and cand["orders"] == orders
+    assert cand["starts"].tolist() == orc.eval_index(got["index"], want_starts=True)["starts"].tolist()
+
+
+def test_config1_split_ranges_in_any_order_give_the_same_best(gpu):
+    prob = W.config1()
+    compare_best(gpu, prob, 0, 576, pieces=[(300, 276), (0, 57), (57, 243)])
+    compare_best(gpu, prob, 0, 576, pieces=[(k, 1) for k in range(575, -1, -1)])
+
+
+def test_empty_and_tiny_ranges(gpu):
+    prob = W.config1()
+    g = gpu.Problem(prob)
+    g.eval_candidates(5, 0)
+    got = g.best()
+    assert got["n_evaluated"] == 0 and not got["feasible"]
+    compare_best(gpu, prob, 56, 1)
+    compare_best(gpu, prob, 0, 3)              # all rejected
+    with pytest.raises(gpu.TesselError):
+        g.eval_candidates(570, 7)              # past the end of the space
+
+
+def test_reset_starts_a_new_search(gpu):
+    prob = W.config1()
+    g = gpu.Problem(prob)
+    g.eval_candidates(0, 576)
+    assert g.best()["period"] == 6
+    g.reset()
+    g.eval_candidates(100, 20)
+    from oracle import Oracle
+    want = Oracle(prob).sweep(100, 20)
+    got = g.best()
+    assert got["n_evaluated"] == 20 and got["n_feasible"] == want["n_feasible"]
+
+
+# ---------------------------------------------------------------- config 2: canonical, exhaustive space
+def multiset_rank(seq, symbols, nr):
+    """lexicographic rank of a sequence among the arrangements of its multiset"""
+    from math import factorial
+    cnt = {s: nr for s in symbols}
+
+    def ways(c):
+        n = sum(c.values())
+        w = factorial(n)
+        for v in c.values():
+            w //= factorial(v)
+        return w
+
+    rank = 0
+    for x in seq:
+        for s in symbols:
+            if s == x:
+                break
+            if cnt[s]:
+                cnt[s] -= 1
+                rank += ways(cnt)
+                cnt[s] += 1
+        cnt[x] -= 1
+    return rank
+
+
+def test_config2_slices_and_the_1f1b_candidate(gpu):
+    from oracle import Oracle
+    prob = W.config2()
+    orc = Oracle(prob)
+    total = orc.count
+    assert gpu.Problem(prob).candidate_count() == total
+    for first, count in ((0, 70000), (total - 33333, 33333), (70 ** 4 * 57 + 12345, 65537)):
+        compare_scores(gpu, prob, first, count)
+    # index of the 1F1B candidate: leads (3,2,1,0,0,0,0,0), every device alternates F, B
+    leads = [3, 2, 1, 0, 0, 0, 0, 0]
+    lead_rank = None
+    # lead vectors in lexicographic order
+    import itertools
+    vecs = [v for v in itertools.product(range(4), repeat=8)
+            if all(v[i] >= v[i + 1] for i in range(7)) and min(v) == 0]
+    lead_rank = vecs.index(tuple(leads))
+    idx, mult = 0, 1
+    for d in range(4):
+        f, b = d, 7 - d
+        idx += mult * multiset_rank([f, b] * 4, [f, b], 4)
+        mult *= 70
+    idx += mult * lead_rank
+    g = gpu.Problem(prob)
+    code, peak = g.score_candidates(idx, 1)
+    assert int(code[0]) == 12 and int(peak[0]) == 4        # zero bubble: N_R (tf + tb)
+    g.eval_candidates(idx - 1000, 2000)
+    got = g.best()
+    assert got["period"] == 12 and got["peak"] == [4, 3, 2, 1]
+    compare_best(gpu, prob, idx - 1000, 2000)
+
+
+# ---------------------------------------------------------------- configs 3-5: sampled spaces
+@pytest.mark.parametrize("cfg,space,count", [
+    (3, "sampled_repair", 40000), (3, "sampled_strict", 20000),
+    (4, "sampled_repair", 40000), (4, "sampled_strict", 20000),
+    (5, "sampled_repair", 12289), (5, "sampled_strict", 8000),
+])
+def test_sampled_configs_elementwise(gpu, cfg, space, count):
+    prob = W.CONFIGS[cfg](space)
+    first = (1 << 40) + 12345 if cfg == 5 else 777
+    code = compare_scores(gpu, prob, first, count)
+    if space == "sampled_repair":
+        assert (code > 0).sum() > 0
+    compare_best(gpu, prob, first, count, pieces=[(first, count // 3), (first + count // 3, count - count // 3)])
+
+
+def test_config5_completion_matches_oracle_and_is_valid(gpu):
+    from oracle import Oracle
+    prob = W.config5()
+    N = prob["num_microbatches"]
+    g, got, want = compare_best(gpu, prob, 0, 20000)
+    orc = Oracle(prob)
+    cand = g.best_candidate()
+    st, leads, orders = orc.decode(got["index"])
+    assert cand["leads"] == leads and cand["orders"] == orders
+    assert cand["starts"].tolist() == orc.eval_index(got["index"], want_starts=True)["starts"].tolist()
+    assert SC.check_periodic(prob, leads, orders, cand["starts"].tolist(), got["period"])
+    sched = g.complete_schedule(N)
+    ref = orc.complete(leads, orders, N)
+    assert sched["makespan"] == ref["makespan"] and sched["period"] == got["period"]
+    assert sched["start"].tolist() == ref["start"].tolist()
+    assert sched["dev_order"] == ref["dev_order"]
+    ok, makespan, peaks = SC.check_flat_schedule(prob, N, sched["start"].tolist(), sched["dev_order"])
+    assert ok and makespan == sched["makespan"] and max(peaks) <= prob["M"]
+
+
+# ---------------------------------------------------------------- other shapes and degenerate cases
+def _shape_cases():
+    cases = []
+    # odd sizes, one device, N_R = 1, largest N_R
+    cases.append(W.pipeline_problem(W.linear_placement(3), [1, 2, 1], [2, 3, 1], 3, 3, 3, "canonical", name="lin3-nr3"))
+    cases.append(W.pipeline_problem(W.linear_placement(1), [2], [3], 1, 5, 5, "canonical", name="one-device"))
+    cases.append(W.pipeline_problem(W.linear_placement(3), [1, 1, 1], [2, 2, 2], 3, 1, 1, "factorial", name="nr1"))
+    cases.append(W.pipeline_problem(W.linear_placement(2), [1, 1], [2, 1], 2, 3, 3, "factorial", name="fact-nr3"))
+    cases.append(W.pipeline_problem(W.folded_placement(3), [1, 2, 3, 1, 2, 3], [2, 2, 4, 3, 1, 5], 3, 5, 7,
+                                    "sampled_repair", seed=99, lead_step_q16=30000, name="fold3-nr5"))
+    cases.append(W.pipeline_problem(W.folded_placement(5), [1, 2, 3, 1, 2, 3, 2, 1, 1, 3], [2, 2, 4, 3, 1, 5, 2, 2, 1, 3],
+                                    5, 8, 12, "sampled_repair", seed=5, lead_step_q16=9000, name="fold5-nr8"))
+    cases.append(W.pipeline_problem(W.folded_placement(8), [1] * 16, [2] * 16, 8, 2, 4, "sampled_repair", seed=3,
+                                    lead_step_q16=20000, name="fold8-nr2"))
+    # fixed leads (the paper's split: leads outside, orders inside)
+    cases.append(W.pipeline_problem(W.linear_placement(4), [1] * 4, [2] * 4, 4, 4, 4, "canonical",
+                                    fixed_leads=[3, 2, 1, 0, 0, 0, 0, 0], name="fixed-1f1b-leads"))
+    cases.append(W.pipeline_problem(W.linear_placement(4), [1] * 4, [2] * 4, 4, 4, 4, "sampled_repair", seed=8,
+                                    fixed_leads=[3, 2, 1, 0, 0, 0, 0, 0], name="fixed-leads-sampled"))
+    # a tensor-parallel block in the factorial space (label mismatch across its devices)
+    cases.append({"name": "tp-factorial", "D": 2, "K": 3, "NR": 2, "M": 4, "t": [1, 2, 1], "m": [1, 0, -1],
+                  "dev_mask": [0b11, 0b01, 0b11], "deps": [(0, 1), (1, 2)], "space": "factorial", "seed": 0,
+                  "lead_step_q16": 0, "fixed_leads": None})
+    # two independent chains (bidirectional pipelines sharing the devices), forward-only blocks with m = 0
+    cases.append({"name": "two-chains", "D": 3, "K": 6, "NR": 3, "M": 1, "t": [1, 2, 1, 2, 1, 3], "m": [0] * 6,
+                  "dev_mask": [1, 2, 4, 4, 2, 1], "deps": [(0, 1), (1, 2), (3, 4), (4, 5)], "space": "sampled_repair",
+                  "seed": 17, "lead_step_q16": 30000, "fixed_leads": None})
+    cases.append({"name": "two-chains-canonical", "D": 2, "K": 4, "NR": 2, "M": 1, "t": [1, 2, 2, 1], "m": [0] * 4,
+                  "dev_mask": [1, 2, 2, 1], "deps": [(0, 1), (2, 3)], "space": "canonical",
+                  "seed": 0, "lead_step_q16": 0, "fixed_leads": None})
+    # no dependencies at all, a device without blocks
+    cases.append({"name": "no-deps", "D": 3, "K": 2, "NR": 4, "M": 2, "t": [3, 1], "m": [1, -1],
+                  "dev_mask": [1, 1], "deps": [], "space": "canonical", "seed": 0, "lead_step_q16": 0, "fixed_leads": None})
+    return cases
+
+
+@pytest.mark.parametrize("prob", _shape_cases(), ids=lambda p: p["name"])
+def test_other_shapes_elementwise(gpu, prob):
+    from oracle import Oracle
+    total = Oracle(prob).count
+    count = min(total, 20011)
+    code = compare_scores(gpu, prob, 0, count)
+    compare_best(gpu, prob, 0, count)
+    if prob["name"] == "fixed-1f1b-leads":
+        assert code[code > 0].min() == 12
+    if prob["name"] == "tp-factorial":
+        assert (code == -2).sum() > 0
+    if prob["name"] == "fact-nr3":
+        assert (code == -1).sum() > 0
+
+
+def test_statuses_all_occur_somewhere(gpu):
+    """DUP, TP_MISMATCH, PROP2, DEADLOCK, MEM and OK are all exercised by the cases above."""
+    seen = set()
+    from oracle import Oracle
+    for prob in _shape_cases()[:4] + [_shape_cases()[9], W.config1()]:
+        total = min(Oracle(prob).count, 20011)
+        code, _ = gpu.Problem(prob).score_candidates(0, total)
+        code = code.cpu().numpy()
+        seen |= {0 if c > 0 else -int(c) for c in np.unique(code)}
+    assert seen == {0, 1, 2, 3, 4, 5}
