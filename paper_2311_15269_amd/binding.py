@@ -118,11 +118,15 @@ class Problem:
         self._ws = None
 
     def close(self):
-        if getattr(self, "_h", None):
-            load_library().tessel_problem_destroy(self._h)
-            self._h = None
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.tessel_problem_destroy(self._h)
+        self._h = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:       # interpreter shutdown
+            pass
 
     # ---- plumbing: device memory and stream come from torch
     def _workspace(self):

