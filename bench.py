@@ -1,0 +1,132 @@
+#!/usr/bin/env python3
+"""Benchmark of the repetend-candidate evaluator on one MI355X.
+
+One step = the whole hot path over one batch: score every candidate of the workload
+(decode, build, memory, period), reduce to the best (period, index), read it back and
+complete the schedule from it.  Workload: the 8-simulated-device folded ("V") placement
+with 16 stages, N_R = 8, 2^28 seeded candidates, completion to 64 micro-batches.
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT32_OPS = 256 * 64 * 2.4e9 / 1e12      # T int32 lane-ops/s: 256 CUs x 64 lanes x 2.4 GHz, full-rate VALU ops
+
+
+def algorithmic_ops(prob, n_candidates, n_feasible):
+    """Integer operations the method needs (not what the kernel happens to issue):
+    decode 2 per block (digit, pick); build 3 per block and device it occupies (readiness
+    compare, memory add, running max); period: one max + one add per block and window sweep,
+    V + 1 sweeps with V = D + chains * N_R boundary values, plus 3 V^2 for the cycle-ratio
+    formula -- only for candidates that are executable and within the cap."""
+    n = prob["K"] * prob["NR"]
+    occ = sum(bin(m).count("1") for m in prob["dev_mask"]) * prob["NR"]
+    chains = prob["K"] - len(prob["deps"])
+    V = prob["D"] + chains * prob["NR"]
+    per_cand = 2 * occ + 3 * occ
+    per_feasible = 2 * n * (V + 1) + 3 * V * V
+    return n_candidates * per_cand + n_feasible * per_feasible
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--log2-candidates", type=int, default=28, help="candidates per step = 2^this (28 = the workload)")
+    ap.add_argument("--log2-chunk", type=int, default=24, help="candidates per kernel launch")
+    ap.add_argument("--cpu-sample-log2", type=int, default=17, help="oracle baseline sample size")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; the problem's 8 'devices' are simulated "
+              "entities of the schedule, not GPUs. Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2311_15269_amd import workloads
+    from paper_2311_15269_amd.binding import Problem
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    prob = workloads.config5()
+    n_cand = 1 << args.log2_candidates
+    chunk = min(1 << args.log2_chunk, n_cand)
+    N = prob["num_microbatches"]
+    gpu = Problem(prob)
+
+    def step(events=None):
+        gpu.reset()
+        for first in range(0, n_cand, chunk):
+            if events is not None:
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+            gpu.eval_candidates(first, chunk)
+            if events is not None:
+                b.record()
+                events.append((a, b))
+        best = gpu.best()
+        sched = gpu.complete_schedule(N)
+        return best, sched
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        best, sched = step(events)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    launch_ms = [a.elapsed_time(b) for a, b in events]
+    avg_launch_s = sum(launch_ms) / len(launch_ms) / 1e3
+    feas_frac = best["n_feasible"] / best["n_evaluated"]
+    ops_per_launch = algorithmic_ops(prob, chunk, feas_frac * chunk)
+    achieved = ops_per_launch / avg_launch_s / 1e12
+
+    out = {
+        "metric": "repetend candidates evaluated/sec + % peak VALU int ops, 8-dev V-shape",
+        "value": n_cand * args.steps / dt,
+        "unit": "candidates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": "cfg5: 8 simulated devices, 16 folded stages, N_R=8, 256 blocks/window, "
+                               "2^%d seeded candidates (sampled_repair), completion to %d micro-batches" % (args.log2_candidates, N),
+                   "candidates_per_step": n_cand, "candidates_per_launch": chunk, "mem_cap": prob["M"]},
+        "result": {"best_period": best["period"], "best_index": best["index"], "lower_bound": best["lower_bound"],
+                   "peak_mem": best["peak"], "n_feasible": best["n_feasible"], "n_reject": best["n_reject"],
+                   "makespan_%d_microbatches" % N: sched["makespan"], "windows": sched["num_windows"]},
+        "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_INT32_OPS, "unit": "Tint32op/s",
+                     "frac": achieved / PEAK_INT32_OPS, "traffic": None,
+                     "kernel": "eval_kernel", "avg_launch_ms": avg_launch_s * 1e3,
+                     "algorithmic_ops_per_candidate": ops_per_launch / chunk},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import Oracle
+        cores = min(os.cpu_count() or 1, 16)
+        sample = 1 << args.cpu_sample_log2
+        orc = Oracle(prob)
+        t1 = time.perf_counter()
+        ref = orc.sweep(0, sample, threads=cores)
+        cdt = time.perf_counter() - t1
+        out["cpu_baseline"] = {"value": sample / cdt, "unit": "candidates/s", "cores": cores, "kind": "oracle",
+                               "sample": "first 2^%d ordinals of the same workload, %d threads, %.1f s" % (args.cpu_sample_log2, cores, cdt),
+                               "oracle_ops_per_candidate": ref["ops"] / sample}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

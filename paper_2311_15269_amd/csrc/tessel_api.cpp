@@ -331,6 +331,8 @@ static int bind_workspace(tessel_problem *p, void *ws, size_t bytes, hipStream_t
         p->kp.leadtab = (const int8_t *)base;
         p->kp.wtab = (const uint64_t *)(base + lead_bytes);
     }
+    hipError_t pe = hipMemcpyAsync((char *)ws + kWsParamsOff, &p->kp, sizeof(KParams), hipMemcpyHostToDevice, st);
+    if (pe != hipSuccess) return hip_fail(p, (int)pe);
     int e = launch_reset(ws, st);
     if (e) return hip_fail(p, e);
     p->ws = ws; p->ws_ready = true; p->have_detail = false;
@@ -365,7 +367,7 @@ extern "C" int tessel_score_candidates(tessel_problem *p, uint64_t first, uint64
     if (rc) return rc;
     p->stream = st;
     if (count == 0) return TESSEL_OK;
-    int e = launch_score(p->kp, first, count, code_dev, peak_dev, st);
+    int e = launch_score(p->kp, first, count, code_dev, peak_dev, workspace_dev, st);
     return e ? hip_fail(p, e) : TESSEL_OK;
 }
 

@@ -76,16 +76,20 @@ struct DevDetail {
 
 constexpr size_t kWsResultOff = 0;
 constexpr size_t kWsDetailOff = 256;
-constexpr size_t kWsTablesOff = 4096;          // lead table, arrangement table
+constexpr size_t kWsParamsOff = 2048;          // KParams of the bound problem
+constexpr size_t kWsTablesOff = 8192;          // lead table, arrangement table
 constexpr size_t kWsTablesMax = 1 << 20;
 constexpr size_t kWsBlockRecOff = kWsTablesOff + kWsTablesMax;
+
+static_assert(sizeof(KParams) <= kWsTablesOff - kWsParamsOff, "parameter block must fit its workspace slot");
+static_assert(sizeof(DevDetail) <= kWsParamsOff - kWsDetailOff, "detail record must fit its workspace slot");
 
 struct LaunchShape { int blocks, threads; size_t lds_bytes; };
 
 // kernels.hip
 LaunchShape eval_launch_shape(const KParams &kp, int num_cus);
 int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream);
-int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *stream);
+int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *ws, void *stream);
 int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream);
 int launch_reset(void *ws, void *stream);
 

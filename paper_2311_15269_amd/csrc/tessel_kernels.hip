@@ -152,7 +152,7 @@ __device__ __forceinline__ int reduced_slot(const KParams &P, int v)
 // n = V+1 sweeps in total, lambda = max_v min_{j<n-1} (x_v(n-1) - x_v(j)) / (n-1-j).
 // Two passes over the same sweeps so that no history has to be stored.
 template <int VM, bool TP>
-__device__ int least_period(const KParams &P, const uint16_t *prog, uint32_t *state, const int32_t *t_tab,
+__device__ __forceinline__ int least_period(const KParams &P, const uint16_t *prog, uint32_t *state, const int32_t *t_tab,
                             const uint32_t *mask_tab)
 {
     const int V = P.nsweeps - 1, n = P.nsweeps;
@@ -191,7 +191,7 @@ __device__ int least_period(const KParams &P, const uint16_t *prog, uint32_t *st
 
 // ------------------------------------------------------------------ one candidate
 template <int DM, int VM>
-__device__ int evaluate(const KParams &P, uint64_t idx, uint16_t *prog, uint32_t *state, const int32_t *t_tab,
+__device__ __forceinline__ int evaluate(const KParams &P, uint64_t idx, uint16_t *prog, uint32_t *state, const int32_t *t_tab,
                         const uint32_t *mask_tab, int &period, int (&peak)[DM], DevDetail *detail)
 {
     const uint32_t NR = (uint32_t)P.NR;
@@ -443,9 +443,11 @@ __device__ __forceinline__ bool key_less(int pa, uint64_t ia, int pb, uint64_t i
 }
 
 template <int DM, int VM>
-__global__ __launch_bounds__(kWave) void eval_kernel(KParams P, uint64_t first, uint64_t count, BlockRec *recs,
-                                                     int32_t *code_out, int32_t *peak_out, DevDetail *detail)
+__global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
+                                                     BlockRec *__restrict__ recs, int32_t *__restrict__ code_out,
+                                                     int32_t *__restrict__ peak_out, DevDetail *__restrict__ detail)
 {
+    const KParams &P = *Pp;
     extern __shared__ uint32_t lds[];
     int32_t *t_tab = (int32_t *)lds;
     uint32_t *mask_tab = lds + kMaxK;
@@ -571,7 +573,7 @@ LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
     return s;
 }
 
-typedef void (*eval_fn)(KParams, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, DevDetail *);
+typedef void (*eval_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, DevDetail *);
 
 static eval_fn pick_kernel(const KParams &kp)
 {
@@ -582,8 +584,8 @@ static eval_fn pick_kernel(const KParams &kp)
     return eval_kernel<8, 24>;
 }
 
-static int launch_common(const KParams &kp, uint64_t first, uint64_t count, int blocks, BlockRec *recs, int32_t *code,
-                         int32_t *peak, DevDetail *detail, hipStream_t st)
+static int launch_common(const KParams &kp, const KParams *kp_dev, uint64_t first, uint64_t count, int blocks, BlockRec *recs,
+                         int32_t *code, int32_t *peak, DevDetail *detail, hipStream_t st)
 {
     eval_fn fn = pick_kernel(kp);
     size_t lds = lds_bytes_for(kp);
@@ -591,7 +593,7 @@ static int launch_common(const KParams &kp, uint64_t first, uint64_t count, int 
         hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return (int)e;
     }
-    hipLaunchKernelGGL(fn, dim3(blocks), dim3(kWave), lds, st, kp, first, count, recs, code, peak, detail);
+    hipLaunchKernelGGL(fn, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, detail);
     return (int)hipGetLastError();
 }
 
@@ -603,26 +605,26 @@ int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int
     int blocks = need < (uint64_t)s.blocks ? (int)need : s.blocks;
     if (blocks < 1) return 0;
     BlockRec *recs = (BlockRec *)((char *)ws + kWsBlockRecOff);
-    int rc = launch_common(kp, first, count, blocks, recs, nullptr, nullptr, nullptr, st);
+    int rc = launch_common(kp, (const KParams *)((char *)ws + kWsParamsOff), first, count, blocks, recs, nullptr, nullptr, nullptr, st);
     if (rc) return rc;
     hipLaunchKernelGGL(merge_kernel, dim3(1), dim3(kWave), 0, st, recs, blocks, (DevResult *)((char *)ws + kWsResultOff));
     return (int)hipGetLastError();
 }
 
-int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *stream)
+int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *ws, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
     LaunchShape s = eval_launch_shape(kp, 256);
     uint64_t need = (count + kWave - 1) / kWave;
     int blocks = need < (uint64_t)s.blocks ? (int)need : s.blocks;
     if (blocks < 1) return 0;
-    return launch_common(kp, first, count, blocks, nullptr, code, peak, nullptr, st);
+    return launch_common(kp, (const KParams *)((char *)ws + kWsParamsOff), first, count, blocks, nullptr, code, peak, nullptr, st);
 }
 
 int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream)
 {
-    return launch_common(kp, index, 1, 1, nullptr, nullptr, nullptr, (DevDetail *)((char *)ws + kWsDetailOff),
-                         (hipStream_t)stream);
+    return launch_common(kp, (const KParams *)((char *)ws + kWsParamsOff), index, 1, 1, nullptr, nullptr, nullptr,
+                         (DevDetail *)((char *)ws + kWsDetailOff), (hipStream_t)stream);
 }
 
 int launch_reset(void *ws, void *stream)
