@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <climits>
+#include <cstdlib>
 #include <cstdint>
 #include <cstring>
 #include <new>
@@ -33,6 +34,7 @@ struct tessel_problem {
     hipStream_t stream = nullptr;
     int last_hip = 0;
     bool have_detail = false;
+    bool force_general = false;         // TESSEL_FORCE_GENERAL=1: score with the general kernel only
     uint64_t detail_index = 0;
     DevDetail detail;
     DevResult result;
@@ -217,6 +219,27 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         kp.mask_loc[home[i]] = desc->dev_mask[i];
         if (desc->dev_mask[i] & (desc->dev_mask[i] - 1)) kp.tp = 1;
     }
+    // tables of the fast kernel: single-device blocks, small memory deltas, few slots
+    {
+        bool ok = !kp.tp && kp.nslots <= 32 && kp.nsweeps - 1 <= 24;
+        long mem_span = 0;
+        for (int i = 0; i < K; i++) {
+            if (desc->mem[i] < -127 || desc->mem[i] > 127) ok = false;
+            mem_span += (long)std::abs(desc->mem[i]) * 2 * NR;
+        }
+        if (mem_span > 30000) ok = false;
+        for (int i = 0; i < kMaxK; i++) kp.info_loc[i] = 63u | (63u << 6);
+        for (int i = 0; i < K && ok; i++) {
+            uint32_t su = kp.succ[i] < 0 ? 63u : (uint32_t)home[kp.succ[i]];
+            uint32_t pr = kp.pred[i] < 0 ? 63u : (uint32_t)home[kp.pred[i]];
+            uint32_t tokbase = (uint32_t)(D + path_of[i] * 2 * NR);
+            kp.info_loc[home[i]] = su | (pr << 6) | (tokbase << 12) | (((uint32_t)desc->mem[i] & 0xFFu) << 18);
+        }
+        int v = D;
+        for (int i = 0; i < K; i++) if (kp.pred[i] < 0)
+            for (int j = 0; j < NR; j++, v++) if (v < 24) { kp.v_src[v] = (uint8_t)i; kp.v_j[v] = (uint8_t)j; }
+        kp.fast_ok = ok;
+    }
     // candidate count and the tables of the exhaustive spaces
     if (desc->space == TESSEL_SPACE_FACTORIAL) {
         kp.fact[0] = 1;
@@ -263,6 +286,8 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         p->count = UINT64_MAX;
     }
     p->result.period = INT_MAX;
+    { const char *fg = getenv("TESSEL_FORCE_GENERAL"); p->force_general = fg && fg[0] == '1'; }
+    if (p->force_general) kp.fast_ok = 0;
     *out = p;
     return TESSEL_OK;
 }
@@ -367,7 +392,7 @@ extern "C" int tessel_score_candidates(tessel_problem *p, uint64_t first, uint64
     if (rc) return rc;
     p->stream = st;
     if (count == 0) return TESSEL_OK;
-    int e = launch_score(p->kp, first, count, code_dev, peak_dev, workspace_dev, st);
+    int e = launch_score(p->kp, first, count, code_dev, peak_dev, workspace_dev, p->num_cus, p->force_general, st);
     return e ? hip_fail(p, e) : TESSEL_OK;
 }
 

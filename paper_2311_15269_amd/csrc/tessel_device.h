@@ -52,6 +52,12 @@ struct KParams {
     uint32_t fact[13];           // FACTORIAL: n! for n <= 12
     uint64_t init_list[kMaxD];   // FACTORIAL: labelled blocks of a device, 5 bits each (y<<3 | label)
     uint64_t cdev[kMaxD];        // FACTORIAL: n_d!;  CANONICAL: arrangements of device d
+    // fast path (single-device blocks only), block types addressed by code = device*4 + symbol
+    int32_t  fast_ok;            // the problem fits the fast kernel
+    uint32_t info_loc[kMaxK];    // bits 0-5 consumer code (63 none), 6-11 producer code (63 none),
+                                 // 12-17 first token slot of the chain, 18-25 memory delta (signed)
+    uint8_t  v_src[24];          // boundary value v >= D: type id of the first block of its chain
+    uint8_t  v_j[24];            //                        and its micro-batch offset j (slot N_R + j)
     const int8_t   *leadtab;     // CANONICAL: [nlead][K] in device memory
     const uint64_t *wtab;        // CANONICAL: arrangements by remaining counts, base NR+1 digits
 };
@@ -89,7 +95,8 @@ struct LaunchShape { int blocks, threads; size_t lds_bytes; };
 // kernels.hip
 LaunchShape eval_launch_shape(const KParams &kp, int num_cus);
 int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream);
-int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *ws, void *stream);
+int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *ws, int num_cus,
+                 bool general, void *stream);
 int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream);
 int launch_reset(void *ws, void *stream);
 

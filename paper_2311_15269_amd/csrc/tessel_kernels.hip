@@ -189,21 +189,17 @@ __device__ __forceinline__ int least_period(const KParams &P, const uint16_t *pr
     return (int)T;
 }
 
-// ------------------------------------------------------------------ one candidate
-template <int DM, int VM>
-__device__ __forceinline__ int evaluate(const KParams &P, uint64_t idx, uint16_t *prog, uint32_t *state, const int32_t *t_tab,
-                        const uint32_t *mask_tab, int &period, int (&peak)[DM], DevDetail *detail)
+// ------------------------------------------------------------------ candidate decoding
+// index -> leads (4-bit counters by block type id) and, per device, the order of its blocks as
+// 2-bit local symbols (first block in the lowest bits).  Returns kOk or the structural reject
+// reason of the FACTORIAL space.
+template <int DM>
+__device__ __forceinline__ int decode_candidate(const KParams &P, uint64_t idx, uint64_t (&rem)[DM], int (&remlen)[DM], Mu &mu)
 {
     const uint32_t NR = (uint32_t)P.NR;
-    uint64_t rem[DM];
-    int remlen[DM];
-    Mu mu;
     mu.lo = 0; mu.hi = 0;
-    period = 0;
 #pragma unroll
-    for (int d = 0; d < DM; d++) { rem[d] = 0; remlen[d] = 0; peak[d] = 0; }
-
-    // ---------------- decode
+    for (int d = 0; d < DM; d++) { rem[d] = 0; remlen[d] = 0; }
     if (P.space == kFactorial) {
         uint64_t rest = idx;
         bool dup = false, tpm = false;
@@ -313,6 +309,25 @@ __device__ __forceinline__ int evaluate(const KParams &P, uint64_t idx, uint16_t
             }
             rem[d] = o; remlen[d] = (int)n;
         }
+    }
+
+    return kOk;
+}
+
+// ------------------------------------------------------------------ one candidate (general path)
+template <int DM, int VM>
+__device__ __forceinline__ int evaluate(const KParams &P, uint64_t idx, uint16_t *prog, uint32_t *state, const int32_t *t_tab,
+                        const uint32_t *mask_tab, int &period, int (&peak)[DM], DevDetail *detail)
+{
+    uint64_t rem[DM];
+    int remlen[DM];
+    Mu mu;
+    period = 0;
+#pragma unroll
+    for (int d = 0; d < DM; d++) peak[d] = 0;
+    {
+        int st = decode_candidate<DM>(P, idx, rem, remlen, mu);
+        if (st != kOk) return st;
     }
 
     if (detail) {
@@ -436,12 +451,317 @@ __device__ __forceinline__ int evaluate(const KParams &P, uint64_t idx, uint16_t
     return kOk;
 }
 
-// ------------------------------------------------------------------ kernels
 __device__ __forceinline__ bool key_less(int pa, uint64_t ia, int pb, uint64_t ib)
 {
     return pa < pb || (pa == pb && ia < ib);
 }
 
+// ==================================================================== fast path
+// Single-device blocks only.  Block types are addressed by their code c = device*4 + symbol, so
+// that bit c of a 32-bit mask means "type c": R = types whose next occurrence may be placed now
+// (producer ahead and occurrences left), HM = the type at the head of every device's list.
+// One block is placed per step and lane:
+//   heads first   : lowest set bit of R & HM            (any order of runnable heads gives the
+//                                                         same per-device orders)
+//   else repair   : lowest device with a runnable type = lowest set bit of R; inside the device
+//                   the earliest remaining entry whose type is runnable
+// The per-device data that is picked by a run-time device number lives in LDS [device][lane];
+// masks and the 4-bit micro-batch counters stay in VGPRs.
+
+struct FastLds {
+    uint32_t *t_tab;      // [32]  t by code
+    uint32_t *info_tab;   // [32]  packed consumer/producer/token base/memory delta by code
+    uint4 *recA;          // [DM][64] order (64 bit) | not-yet-placed mask (bit 2*pos)
+    uint2 *recB;          // [DM][64] x: lead+N_R of the 4 types (4 bits each); y: memory now (lo16) | peak (hi16)
+    uint32_t *prog;       // [ceil(total/3)][64] three 10-bit entries a word: code | slot<<5
+    uint32_t *state;      // [nslots][64]
+};
+
+__device__ __forceinline__ uint32_t ctz64_parts(uint32_t lo, uint32_t hi)
+{
+    return lo ? (uint32_t)__builtin_ctz(lo) : 32u + (uint32_t)__builtin_ctz(hi | 0x80000000u);
+}
+__device__ __forceinline__ uint32_t bfi(uint32_t sel, uint32_t a, uint32_t b) { return (sel & a) | (~sel & b); }
+
+// one sweep of the window over the 10-bit program
+__device__ __forceinline__ void sweep_fast(const KParams &P, const FastLds &L, int lane)
+{
+    const int total = P.total;
+    const int nwords = (total + 2) / 3;
+    for (int i = 0; i < nwords; i++) {
+        uint32_t w = L.prog[i * kWave + lane];
+#pragma unroll
+        for (int j = 0; j < 3; j++) {
+            if (3 * i + j < total) {
+                uint32_t e = (w >> (10 * j)) & 1023u;
+                uint32_t code = e & 31u, ts = e >> 5, ds = code >> 2;
+                uint32_t en = max(L.state[ds * kWave + lane], L.state[ts * kWave + lane]) + L.t_tab[code];
+                L.state[ds * kWave + lane] = en;
+                L.state[ts * kWave + lane] = en;
+            }
+        }
+    }
+    for (int p = 0; p < P.npaths; p++)
+        for (int mu = 0; mu < P.NR; mu++) {
+            int base = P.D + p * 2 * P.NR + mu;
+            L.state[base * kWave + lane] = L.state[(base + P.NR) * kWave + lane];
+            L.state[(base + P.NR) * kWave + lane] = 0;
+        }
+}
+
+// Period of the repeated window.  The sweep is a max-plus linear map F on the boundary vector x
+// (device free times, in-flight micro-batch end times).  If after some sweep every live component
+// has grown by the same delta, x is an eigenvector of F and delta is its eigenvalue = the maximum
+// cycle ratio, exactly.  Almost every candidate gets there within two or three sweeps; the rest
+// take Karp's formula over V+1 sweeps (two passes, no history).
+template <int VM>
+__device__ __forceinline__ int period_fast(const KParams &P, const FastLds &L, int lane, const Mu &leads, bool want)
+{
+    const int V = P.nsweeps - 1, n = P.nsweeps;
+    uint32_t live = 0;                                    // per lane: which boundary values mean anything
+#pragma unroll
+    for (int v = 0; v < VM; v++) {
+        if (v < P.D) live |= (P.ntd[v] > 0 ? 1u : 0u) << v;
+        else if (v < V) live |= (leads.get(P.v_src[v]) > (uint32_t)P.v_j[v] ? 1u : 0u) << v;
+    }
+    for (int s = 0; s < P.nslots; s++) L.state[s * kWave + lane] = 0;
+    uint32_t prev[VM];
+#pragma unroll
+    for (int v = 0; v < VM; v++) prev[v] = 0;
+    int T = 0;
+    bool done = !want;
+    constexpr int kTry = 6;
+    for (int j = 0; j < kTry; j++) {
+        if (__ballot(!done) == 0) break;
+        sweep_fast(P, L, lane);
+        bool same = true, have = false;
+        uint32_t delta = 0;
+#pragma unroll
+        for (int v = 0; v < VM; v++) {
+            if (v < V) {
+                uint32_t x = L.state[reduced_slot(P, v) * kWave + lane];
+                uint32_t dv = x - prev[v];
+                prev[v] = x;
+                if (live >> v & 1u) {
+                    if (!have) { delta = dv; have = true; }
+                    else if (dv != delta) same = false;
+                }
+            }
+        }
+        if (!done && same && have) { T = (int)delta; done = true; }
+    }
+    if (__ballot(!done) == 0) return T;
+    // rare: no eigenvector yet.  Karp over n = V+1 sweeps, twice.
+    uint32_t xn[VM], bn[VM], bd[VM];
+    for (int s = 0; s < P.nslots; s++) L.state[s * kWave + lane] = 0;
+    for (int j = 0; j < n; j++) sweep_fast(P, L, lane);
+#pragma unroll
+    for (int v = 0; v < VM; v++) {
+        xn[v] = v < V ? L.state[reduced_slot(P, v) * kWave + lane] : 0u;
+        bn[v] = 0xFFFFFFFFu; bd[v] = 1u;
+    }
+    for (int s = 0; s < P.nslots; s++) L.state[s * kWave + lane] = 0;
+    for (int j = 0; j < n - 1; j++) {
+        sweep_fast(P, L, lane);
+        uint32_t den = (uint32_t)(n - 1 - j);
+#pragma unroll
+        for (int v = 0; v < VM; v++) {
+            if (v < V) {
+                uint32_t a = xn[v] - L.state[reduced_slot(P, v) * kWave + lane];
+                bool better = bn[v] == 0xFFFFFFFFu || (uint64_t)a * bd[v] < (uint64_t)bn[v] * den;
+                if (better) { bn[v] = a; bd[v] = den; }
+            }
+        }
+    }
+    uint32_t Tk = 0;
+#pragma unroll
+    for (int v = 0; v < VM; v++)
+        if (v < V) Tk = max(Tk, (bn[v] + bd[v] - 1u) / bd[v]);
+    return done ? T : (int)Tk;
+}
+
+template <int DM, int VM>
+__device__ __forceinline__ int evaluate_fast(const KParams &P, uint64_t idx, const FastLds &L, int lane, int &period, int &peak_max,
+                                             bool valid)
+{
+    uint64_t ord[DM];
+    int nlen[DM];
+    Mu leads;
+    period = 0; peak_max = 0;
+    int status = decode_candidate<DM>(P, idx, ord, nlen, leads);
+    const uint32_t NR = (uint32_t)P.NR;
+
+    // counters by code, ready / exhausted / head masks, per-device records
+    Mu mu;
+    mu.lo = 0; mu.hi = 0;
+    uint32_t R = 0, HM = 0, X = 0;
+#pragma unroll
+    for (int d = 0; d < DM; d++) {
+        if (d >= P.D) continue;
+        uint32_t lim = 0;
+        int mem0 = 0;
+#pragma unroll
+        for (int y = 0; y < kMaxLT; y++) {
+            if (y >= P.ntd[d]) continue;
+            uint32_t g = byte_of(P.type_of[d], (uint32_t)y), lead = leads.get(g);
+            mu.set((uint32_t)(4 * d + y), lead);
+            lim |= (lead + NR) << (4 * y);
+            mem0 += P.m_of[d][y] * (int)lead;                 // blocks that ran before the window
+        }
+        uint64_t alive = nlen[d] >= 32 ? 0x5555555555555555ull : ((1ull << (2 * nlen[d])) - 1ull) & 0x5555555555555555ull;
+        L.recA[d * kWave + lane] = make_uint4((uint32_t)ord[d], (uint32_t)(ord[d] >> 32), (uint32_t)alive, (uint32_t)(alive >> 32));
+        L.recB[d * kWave + lane] = make_uint2(lim, ((uint32_t)mem0 & 0xFFFFu) | (0x8000u << 16));
+        if (nlen[d] > 0) HM |= 1u << (4 * d + ((uint32_t)ord[d] & 3u));
+    }
+#pragma unroll
+    for (int d = 0; d < DM; d++) {
+        if (d >= P.D) continue;
+#pragma unroll
+        for (int y = 0; y < kMaxLT; y++) {
+            if (y >= P.ntd[d]) continue;
+            uint32_t c = (uint32_t)(4 * d + y), pr = (P.info_loc[c] >> 6) & 63u;
+            bool ready = pr == 63u || mu.get(pr) > mu.get(c);
+            R |= (ready ? 1u : 0u) << c;
+        }
+    }
+
+    const bool repair = P.space == kSampledRepair;
+    const int total = P.total;
+    bool building = valid && status == kOk;
+    uint32_t acc = 0;
+    for (int k = 0; k < total; k++) {
+        if (__ballot(building) == 0) break;
+        uint32_t hm = R & HM;
+        uint32_t sel = hm ? hm : (repair ? R : 0u);
+        if (building && sel == 0) { status = kDeadlock; building = false; }
+        const uint32_t b = (uint32_t)__builtin_ctz(sel | 0x80000000u) & 31u;
+        const uint32_t d = building ? b >> 2 : 0u;
+        const uint4 a = L.recA[d * kWave + lane];
+        uint2 bb = L.recB[d * kWave + lane];
+        const uint4 inf4 = *(const uint4 *)(L.info_tab + 4 * d);
+        // earliest remaining entry of device d whose type is allowed (all types when its head runs)
+        const uint32_t r4 = hm ? 15u : (R >> (4 * d)) & 15u;
+        const uint32_t r0 = 0u - (r4 & 1u), r1 = 0u - ((r4 >> 1) & 1u), r2 = 0u - ((r4 >> 2) & 1u), r3 = 0u - (r4 >> 3);
+        const uint32_t h_lo = (a.x >> 1) | (a.y << 31), h_hi = a.y >> 1;
+        const uint32_t g_lo = bfi(h_lo, bfi(a.x, r3, r2), bfi(a.x, r1, r0));
+        const uint32_t g_hi = bfi(h_hi, bfi(a.y, r3, r2), bfi(a.y, r1, r0));
+        const uint32_t u_lo = a.z & g_lo, u_hi = a.w & g_hi;
+        const uint32_t p = ctz64_parts(u_lo, u_hi) & 63u;
+        const uint64_t ordw = ((uint64_t)a.y << 32) | a.x;
+        const uint32_t y = (uint32_t)(ordw >> p) & 3u;
+        const uint32_t c = 4u * d + y;
+        const uint32_t info = y & 2u ? (y & 1u ? inf4.w : inf4.z) : (y & 1u ? inf4.y : inf4.x);
+        // take the entry out, new head of the device
+        uint64_t alive = (((uint64_t)a.w << 32) | a.z) & ~(1ull << p);
+        const uint32_t al_lo = (uint32_t)alive, al_hi = (uint32_t)(alive >> 32);
+        const uint32_t p2 = ctz64_parts(al_lo, al_hi) & 63u;
+        const uint32_t y2 = (uint32_t)(ordw >> p2) & 3u;
+        uint32_t hm_new = HM & ~(15u << (4 * d));
+        if (alive) hm_new |= 1u << (4 * d + y2);
+        // counters and readiness of this type and of its consumer
+        const uint32_t mg = mu.get(c);
+        const uint32_t lim = (bb.x >> (4 * y)) & 15u;
+        const uint32_t pr = (info >> 6) & 63u, su = info & 63u;
+        const bool exhausted = mg + 1u == lim;
+        const bool ready_c = !exhausted && (pr == 63u || mu.get(pr) > mg + 1u);
+        uint32_t r_new = (R & ~(1u << c)) | ((ready_c ? 1u : 0u) << c);
+        const uint32_t x_new = X | ((exhausted ? 1u : 0u) << c);
+        if (su != 63u) r_new |= (1u << su) & ~x_new;
+        // memory prefix of the device (Eq. 1 [2])
+        const int m = (int)(info << 6) >> 24;
+        const int memcur = (int)(int16_t)(bb.y & 0xFFFFu) + m;
+        const int pk = max((int)(int16_t)(bb.y >> 16), memcur);
+        const uint32_t entry = c | ((((info >> 12) & 63u) + mg) << 5);
+        const int sh = 10 * (k % 3);
+        if (building) {
+            R = r_new; X = x_new; HM = hm_new;
+            mu.inc(c);
+            L.recA[d * kWave + lane].z = al_lo;
+            L.recA[d * kWave + lane].w = al_hi;
+            L.recB[d * kWave + lane].y = ((uint32_t)memcur & 0xFFFFu) | ((uint32_t)pk << 16);
+            acc |= entry << sh;
+        }
+        if (k % 3 == 2 || k == total - 1) {
+            L.prog[(k / 3) * kWave + lane] = acc;
+            acc = 0;
+        }
+    }
+    if (status != kOk) return status;
+    int worst = INT_MIN;
+#pragma unroll
+    for (int d = 0; d < DM; d++) {
+        if (d >= P.D) continue;
+        int pk = (int)(int16_t)(L.recB[d * kWave + lane].y >> 16);
+        if (P.ntd[d] == 0) pk = 0;
+        worst = max(worst, pk);
+    }
+    peak_max = worst;
+    if (valid && worst > P.M) status = kMem;
+    int T = period_fast<VM>(P, L, lane, leads, valid && status == kOk);
+    if (status == kOk) period = T;
+    return status;
+}
+
+template <int DM, int VM>
+__global__ __launch_bounds__(kWave) void eval_fast_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
+                                                          BlockRec *__restrict__ recs, int32_t *__restrict__ code_out,
+                                                          int32_t *__restrict__ peak_out)
+{
+    extern __shared__ uint32_t lds[];
+    const KParams &P = *Pp;
+    const int lane = threadIdx.x;
+    FastLds L;
+    L.t_tab = lds;
+    L.info_tab = lds + kMaxK;
+    L.recA = (uint4 *)(lds + 2 * kMaxK);
+    L.recB = (uint2 *)(lds + 2 * kMaxK + DM * kWave * 4);
+    L.state = lds + 2 * kMaxK + DM * kWave * 6;
+    L.prog = L.state + P.nslots * kWave;
+    if (lane < kMaxK) { L.t_tab[lane] = (uint32_t)P.t_loc[lane]; L.info_tab[lane] = P.info_loc[lane]; }
+    __syncthreads();
+
+    int best = INT_MAX;
+    uint64_t best_idx = 0;
+    uint32_t cnt[kNumStatus];
+#pragma unroll
+    for (int s = 0; s < kNumStatus; s++) cnt[s] = 0;
+    uint32_t nev = 0;
+    const uint64_t stride = (uint64_t)gridDim.x * kWave;
+    const uint64_t rounds = (count + stride - 1) / stride;          // the same trip count for every lane of the grid
+    for (uint64_t r = 0; r < rounds; r++) {
+        const uint64_t k = r * stride + (uint64_t)blockIdx.x * kWave + lane;
+        const bool valid = k < count;
+        int period, pk;
+        int status = evaluate_fast<DM, VM>(P, first + (valid ? k : 0), L, lane, period, pk, valid);
+        if (!valid) continue;
+        nev++;
+#pragma unroll
+        for (int s = 0; s < kNumStatus; s++) cnt[s] += status == s;
+        if (status == kOk && period < best) { best = period; best_idx = first + k; }
+        if (code_out) code_out[k] = status == kOk ? period : -status;
+        if (peak_out) peak_out[k] = (status == kOk || status == kMem) ? pk : 0;
+    }
+    if (!recs) return;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        int op = __shfl_xor(best, off);
+        uint32_t ilo = __shfl_xor((uint32_t)best_idx, off), ihi = __shfl_xor((uint32_t)(best_idx >> 32), off);
+        uint64_t oi = ((uint64_t)ihi << 32) | ilo;
+        if (key_less(op, oi, best, best_idx)) { best = op; best_idx = oi; }
+#pragma unroll
+        for (int s = 0; s < kNumStatus; s++) cnt[s] += __shfl_xor(cnt[s], off);
+        nev += __shfl_xor(nev, off);
+    }
+    if (lane == 0) {
+        BlockRec rr;
+        rr.period = best; rr.pad = 0; rr.index = best_idx; rr.n_evaluated = nev; rr.pad2 = 0;
+#pragma unroll
+        for (int s = 0; s < kNumStatus; s++) rr.n_status[s] = cnt[s];
+        recs[blockIdx.x] = rr;
+    }
+}
+
+// ------------------------------------------------------------------ kernels
 template <int DM, int VM>
 __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
                                                      BlockRec *__restrict__ recs, int32_t *__restrict__ code_out,
@@ -556,24 +876,8 @@ __global__ void reset_kernel(DevResult *res)
 }
 
 // ------------------------------------------------------------------ launchers
-static size_t lds_bytes_for(const KParams &kp)
-{
-    return (size_t)2 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)kp.total * kWave * 2;
-}
-
-LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
-{
-    LaunchShape s;
-    s.threads = kWave;
-    s.lds_bytes = lds_bytes_for(kp);
-    int per_cu = (int)((160 * 1024) / s.lds_bytes);
-    if (per_cu > 8) per_cu = 8;
-    if (per_cu < 1) per_cu = 1;
-    s.blocks = num_cus * per_cu;
-    return s;
-}
-
 typedef void (*eval_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, DevDetail *);
+typedef void (*fast_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *);
 
 static eval_fn pick_kernel(const KParams &kp)
 {
@@ -584,47 +888,89 @@ static eval_fn pick_kernel(const KParams &kp)
     return eval_kernel<8, 24>;
 }
 
-static int launch_common(const KParams &kp, const KParams *kp_dev, uint64_t first, uint64_t count, int blocks, BlockRec *recs,
-                         int32_t *code, int32_t *peak, DevDetail *detail, hipStream_t st)
+static int fast_dm(const KParams &kp) { return kp.D <= 2 ? 2 : kp.D <= 4 ? 4 : 8; }
+
+static fast_fn pick_fast(const KParams &kp)
 {
-    eval_fn fn = pick_kernel(kp);
-    size_t lds = lds_bytes_for(kp);
+    const int V = kp.nsweeps - 1;
+    if (!kp.fast_ok) return nullptr;
+    if (kp.D <= 2) return V <= 4 ? eval_fast_kernel<2, 4> : eval_fast_kernel<2, 24>;
+    if (kp.D <= 4) return V <= 8 ? eval_fast_kernel<4, 8> : eval_fast_kernel<4, 24>;
+    return V <= 16 ? eval_fast_kernel<8, 16> : eval_fast_kernel<8, 24>;
+}
+
+static size_t general_lds_bytes(const KParams &kp)
+{
+    return (size_t)2 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)kp.total * kWave * 2;
+}
+
+static size_t fast_lds_bytes(const KParams &kp)
+{
+    return (size_t)2 * kMaxK * 4 + (size_t)fast_dm(kp) * kWave * 24 + (size_t)kp.nslots * kWave * 4 +
+           (size_t)((kp.total + 2) / 3) * kWave * 4;
+}
+
+LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
+{
+    LaunchShape s;
+    s.threads = kWave;
+    s.lds_bytes = pick_fast(kp) ? fast_lds_bytes(kp) : general_lds_bytes(kp);
+    int per_cu = (int)((160 * 1024) / (s.lds_bytes + 512));
+    if (per_cu > 8) per_cu = 8;
+    if (per_cu < 1) per_cu = 1;
+    s.blocks = num_cus * per_cu;
+    return s;
+}
+
+// general == true forces the general kernel (the only one that writes the decoded candidate)
+static int launch_common(const KParams &kp, const KParams *kp_dev, uint64_t first, uint64_t count, int blocks, BlockRec *recs,
+                         int32_t *code, int32_t *peak, DevDetail *detail, bool general, hipStream_t st)
+{
+    fast_fn ff = general ? nullptr : pick_fast(kp);
+    const size_t lds = ff ? fast_lds_bytes(kp) : general_lds_bytes(kp);
+    const void *fn = ff ? (const void *)ff : (const void *)pick_kernel(kp);
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return (int)e;
     }
-    hipLaunchKernelGGL(fn, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, detail);
+    if (ff) hipLaunchKernelGGL(ff, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak);
+    else hipLaunchKernelGGL(pick_kernel(kp), dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, detail);
     return (int)hipGetLastError();
+}
+
+static int grid_for(const KParams &kp, uint64_t count, int num_cus)
+{
+    LaunchShape s = eval_launch_shape(kp, num_cus);
+    uint64_t need = (count + kWave - 1) / kWave;
+    return need < (uint64_t)s.blocks ? (int)need : s.blocks;
 }
 
 int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    LaunchShape s = eval_launch_shape(kp, num_cus);
-    uint64_t need = (count + kWave - 1) / kWave;
-    int blocks = need < (uint64_t)s.blocks ? (int)need : s.blocks;
+    int blocks = grid_for(kp, count, num_cus);
     if (blocks < 1) return 0;
     BlockRec *recs = (BlockRec *)((char *)ws + kWsBlockRecOff);
-    int rc = launch_common(kp, (const KParams *)((char *)ws + kWsParamsOff), first, count, blocks, recs, nullptr, nullptr, nullptr, st);
+    int rc = launch_common(kp, (const KParams *)((char *)ws + kWsParamsOff), first, count, blocks, recs, nullptr, nullptr,
+                           nullptr, false, st);
     if (rc) return rc;
     hipLaunchKernelGGL(merge_kernel, dim3(1), dim3(kWave), 0, st, recs, blocks, (DevResult *)((char *)ws + kWsResultOff));
     return (int)hipGetLastError();
 }
 
-int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *ws, void *stream)
+int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *ws, int num_cus,
+                 bool general, void *stream)
 {
-    hipStream_t st = (hipStream_t)stream;
-    LaunchShape s = eval_launch_shape(kp, 256);
-    uint64_t need = (count + kWave - 1) / kWave;
-    int blocks = need < (uint64_t)s.blocks ? (int)need : s.blocks;
+    int blocks = grid_for(kp, count, num_cus);
     if (blocks < 1) return 0;
-    return launch_common(kp, (const KParams *)((char *)ws + kWsParamsOff), first, count, blocks, nullptr, code, peak, nullptr, st);
+    return launch_common(kp, (const KParams *)((char *)ws + kWsParamsOff), first, count, blocks, nullptr, code, peak, nullptr,
+                         general, (hipStream_t)stream);
 }
 
 int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream)
 {
     return launch_common(kp, (const KParams *)((char *)ws + kWsParamsOff), index, 1, 1, nullptr, nullptr, nullptr,
-                         (DevDetail *)((char *)ws + kWsDetailOff), (hipStream_t)stream);
+                         (DevDetail *)((char *)ws + kWsDetailOff), true, (hipStream_t)stream);
 }
 
 int launch_reset(void *ws, void *stream)
