@@ -715,8 +715,10 @@ __global__ __launch_bounds__(kWave) void eval_fast_kernel(const KParams *__restr
     L.info_tab = lds + kMaxK;
     L.recA = (uint4 *)(lds + 2 * kMaxK);
     L.recB = (uint2 *)(lds + 2 * kMaxK + DM * kWave * 4);
-    L.state = lds + 2 * kMaxK + DM * kWave * 6;
-    L.prog = L.state + P.nslots * kWave;
+    // the sweep state is only used once the build is over: it shares the build records' space when it fits
+    const bool share = P.nslots <= DM * 6;
+    L.state = share ? lds + 2 * kMaxK : lds + 2 * kMaxK + DM * kWave * 6;
+    L.prog = share ? lds + 2 * kMaxK + DM * kWave * 6 : L.state + P.nslots * kWave;
     if (lane < kMaxK) { L.t_tab[lane] = (uint32_t)P.t_loc[lane]; L.info_tab[lane] = P.info_loc[lane]; }
     __syncthreads();
 
@@ -906,7 +908,8 @@ static size_t general_lds_bytes(const KParams &kp)
 
 static size_t fast_lds_bytes(const KParams &kp)
 {
-    return (size_t)2 * kMaxK * 4 + (size_t)fast_dm(kp) * kWave * 24 + (size_t)kp.nslots * kWave * 4 +
+    const bool share = kp.nslots <= fast_dm(kp) * 6;
+    return (size_t)2 * kMaxK * 4 + (size_t)fast_dm(kp) * kWave * 24 + (share ? 0 : (size_t)kp.nslots * kWave * 4) +
            (size_t)((kp.total + 2) / 3) * kWave * 4;
 }
 
