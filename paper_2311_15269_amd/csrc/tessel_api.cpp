@@ -222,12 +222,13 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
     // tables of the fast kernel: single-device blocks, small memory deltas, few slots
     {
         bool ok = !kp.tp && kp.nslots <= 32 && kp.nsweeps - 1 <= 24;
-        long mem_span = 0;
-        for (int i = 0; i < K; i++) {
-            if (desc->mem[i] < -127 || desc->mem[i] > 127) ok = false;
-            mem_span += (long)std::abs(desc->mem[i]) * 2 * NR;
+        // the memory prefix of a device is kept in 8 bits: entry (lead <= N_R-1 each) plus N_R occurrences
+        for (int d = 0; d < D; d++) {
+            long span = 0;
+            for (int i = 0; i < K; i++) if (desc->dev_mask[i] >> d & 1u) span += (long)std::abs(desc->mem[i]) * (2 * NR - 1);
+            if (span > 120) ok = false;
         }
-        if (mem_span > 30000) ok = false;
+        for (int i = 0; i < K; i++) if (desc->mem[i] < -127 || desc->mem[i] > 127) ok = false;
         for (int i = 0; i < kMaxK; i++) kp.info_loc[i] = 63u | (63u << 6);
         for (int i = 0; i < K && ok; i++) {
             uint32_t su = kp.succ[i] < 0 ? 63u : (uint32_t)home[kp.succ[i]];
@@ -235,9 +236,24 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
             uint32_t tokbase = (uint32_t)(D + path_of[i] * 2 * NR);
             kp.info_loc[home[i]] = su | (pr << 6) | (tokbase << 12) | (((uint32_t)desc->mem[i] & 0xFFu) << 18);
         }
-        int v = D;
-        for (int i = 0; i < K; i++) if (kp.pred[i] < 0)
-            for (int j = 0; j < NR; j++, v++) if (v < 24) { kp.v_src[v] = (uint8_t)i; kp.v_j[v] = (uint8_t)j; }
+        for (int k = 0; k < K && ok; k++) {
+            int i = kp.rtopo[k];
+            uint32_t su = kp.succ[i] < 0 ? 63u : (uint32_t)home[kp.succ[i]];
+            kp.chain_tab[k] = (uint32_t)home[i] | (su << 6) | ((uint32_t)(kp.succ[i] < 0 ? 0 : kp.edge_out[i]) << 12) |
+                              ((uint32_t)(kp.succ[i] >= 0 && kp.cross_out[i]) << 19) | ((uint32_t)(kp.pred[i] < 0) << 20) |
+                              ((uint32_t)i << 21);
+            kp.valid_codes |= 1u << home[i];
+        }
+        for (int d = 0; d < D; d++) {
+            kp.vtab[d] = (uint32_t)d | (1u << 6) | ((uint32_t)(kp.ntd[d] > 0) << 17);
+            for (int y = 0; y < kp.ntd[d]; y++) kp.mpack[d] |= ((uint32_t)kp.m_of[d][y] & 0xFFu) << (8 * y);
+        }
+        int v = D, path = 0;
+        for (int i = 0; i < K && ok; i++) if (kp.pred[i] < 0) {
+            for (int j = 0; j < NR; j++, v++)
+                if (v < 24) kp.vtab[v] = (uint32_t)(D + path * 2 * NR + j) | ((uint32_t)home[i] << 7) | ((uint32_t)j << 13);
+            path++;
+        }
         kp.fast_ok = ok;
     }
     // candidate count and the tables of the exhaustive spaces

@@ -56,8 +56,13 @@ struct KParams {
     int32_t  fast_ok;            // the problem fits the fast kernel
     uint32_t info_loc[kMaxK];    // bits 0-5 consumer code (63 none), 6-11 producer code (63 none),
                                  // 12-17 first token slot of the chain, 18-25 memory delta (signed)
-    uint8_t  v_src[24];          // boundary value v >= D: type id of the first block of its chain
-    uint8_t  v_j[24];            //                        and its micro-batch offset j (slot N_R + j)
+    uint32_t chain_tab[kMaxK];   // k-th block type, consumers before producers: bits 0-5 code, 6-11 consumer code
+                                 // (63 none), 12-18 dependency number, 19 different device sets, 20 first of its
+                                 // chain, 21-26 type id
+    uint32_t vtab[24];           // boundary value v: bits 0-5 state slot; 6 device value; 7-12 code of the first block
+                                 // of the chain (token values); 13-16 micro-batch offset j; 17 device has blocks
+    uint32_t mpack[kMaxD];       // memory deltas of the device's 4 types, 8 bits each (signed)
+    uint32_t valid_codes;        // bit c set <=> code c names a block type
     const int8_t   *leadtab;     // CANONICAL: [nlead][K] in device memory
     const uint64_t *wtab;        // CANONICAL: arrangements by remaining counts, base NR+1 digits
 };
@@ -69,6 +74,7 @@ struct DevResult {
     uint64_t index;
     uint64_t n_evaluated;
     uint64_t n_status[kNumStatus];   // [kOk] = feasible
+    uint64_t n_sweeps;               // window sweeps spent on period computations (fast kernel)
 };
 
 // Decoded best candidate, written by the detail kernel.

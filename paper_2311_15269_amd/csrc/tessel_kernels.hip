@@ -18,6 +18,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <limits.h>
+#include <stdlib.h>
 
 #include "tessel_device.h"
 
@@ -29,7 +30,7 @@ struct BlockRec {
     uint64_t index;
     uint32_t n_status[kNumStatus];
     uint32_t n_evaluated;
-    uint32_t pad2;
+    uint32_t n_sweeps;           // window sweeps spent on period computations
 };
 
 // ------------------------------------------------------------------ counter-based sampler
@@ -465,48 +466,94 @@ __device__ __forceinline__ bool key_less(int pa, uint64_t ia, int pb, uint64_t i
 //                                                         same per-device orders)
 //   else repair   : lowest device with a runnable type = lowest set bit of R; inside the device
 //                   the earliest remaining entry whose type is runnable
-// The per-device data that is picked by a run-time device number lives in LDS [device][lane];
-// masks and the 4-bit micro-batch counters stay in VGPRs.
+// A device's order is kept as two bit planes (bit p of lo/hi = low/high bit of the symbol at
+// position p) and a mask of the entries not yet placed.  The per-device record is picked by a
+// run-time device number and therefore lives in LDS [device][lane]; masks and the 4-bit
+// micro-batch counters stay in VGPRs.
 
 struct FastLds {
-    uint32_t *t_tab;      // [32]  t by code
-    uint32_t *info_tab;   // [32]  packed consumer/producer/token base/memory delta by code
-    uint4 *recA;          // [DM][64] order (64 bit) | not-yet-placed mask (bit 2*pos)
-    uint2 *recB;          // [DM][64] x: lead+N_R of the 4 types (4 bits each); y: memory now (lo16) | peak (hi16)
-    uint32_t *prog;       // [ceil(total/3)][64] three 10-bit entries a word: code | slot<<5
-    uint32_t *state;      // [nslots][64]
+    uint2 *tt_tab;        // [32]  x: t by code, y: byte offset of the first token slot of the code's chain
+    uint32_t *info_tab;   // [32]  packed consumer/producer/memory delta by code
+    uint32_t *chain_tab;  // [32]  KParams::chain_tab
+    uint32_t *vtab;       // [32]  KParams::vtab
+    uint4 *rec;           // build: [DM][64] x: low plane, y: high plane, z: not-yet-placed mask,
+                          //        w: micro-batches waiting at the input of the 4 types (4 bits each)
+                          //           | memory now (8 bit) << 16 | peak << 24
+    uint2 *drec;          // sweeps: [D][64] x: device free time, y: next micro-batch of the 4 types (4 bits each)
+    uint32_t *tok;        // sweeps: [token slots][64] end time of the micro-batch's latest block
+    uint32_t *prog;       // [ceil(total/6)][64] six 5-bit type codes a word, in executable order
 };
 
-__device__ __forceinline__ uint32_t ctz64_parts(uint32_t lo, uint32_t hi)
-{
-    return lo ? (uint32_t)__builtin_ctz(lo) : 32u + (uint32_t)__builtin_ctz(hi | 0x80000000u);
-}
+// problem scalars, read once per workgroup
+template <int DM>
+struct FastConst {
+    int D, K, NR, M, total, nslots, npaths, nsweeps, space, has_fixed, nwords;
+    uint32_t step_q16;
+    uint64_t seed;
+    int ntd[DM];
+    uint32_t mpack[DM];
+};
+
 __device__ __forceinline__ uint32_t bfi(uint32_t sel, uint32_t a, uint32_t b) { return (sel & a) | (~sel & b); }
 
-// one sweep of the window over the 10-bit program
-__device__ __forceinline__ void sweep_fast(const KParams &P, const FastLds &L, int lane)
+// keeps a value in a VGPR at this point, so that the loads above it are issued together instead of
+// being sunk into later branches
+#define TESSEL_PIN(x) asm volatile("" : "+v"(x))
+
+// one block of the window: s = max(device free, previous block of the micro-batch); both become s + t.
+// The micro-batch it handles is the device record's counter of its type.
+__device__ __forceinline__ void sweep_node(const FastLds &L, uint32_t code, uint32_t lane8, uint32_t lane4)
 {
-    const int total = P.total;
-    const int nwords = (total + 2) / 3;
-    for (int i = 0; i < nwords; i++) {
-        uint32_t w = L.prog[i * kWave + lane];
+    const uint32_t y4 = (code & 3u) << 2;
+    uint2 *dr = (uint2 *)((char *)L.drec + (((code & 28u) << 7) | lane8));       // (code >> 2) * 512
+    const uint2 dv = *dr;
+    const uint2 tt = L.tt_tab[code];
+    const uint32_t mu = (dv.y >> y4) & 15u;
+    uint32_t *tk = (uint32_t *)((char *)L.tok + (tt.y + (mu << 8) + lane4));
+    const uint32_t en = max(dv.x, *tk) + tt.x;
+    *dr = make_uint2(en, dv.y + (1u << y4));
+    *tk = en;
+}
+
+// One sweep of the window over the program, then the window boundary.
+template <int DM>
+__device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds &L, int lane, const Mu &lead_code, bool active)
+{
+    // a lane without a complete program (rejected candidate, lane past the end of the range) must not run one:
+    // its counters would leave the token ring
+    if (!active) return;
+    const uint32_t lane4 = (uint32_t)lane * 4u, lane8 = (uint32_t)lane * 8u;
+    const int full = C.total / 6, tail = C.total - 6 * full;
+    uint32_t w = L.prog[lane];
+    for (int i = 0; i < full; i++) {
+        const uint32_t wn = L.prog[(i + 1 < C.nwords ? i + 1 : i) * kWave + lane];     // next word, early
 #pragma unroll
-        for (int j = 0; j < 3; j++) {
-            if (3 * i + j < total) {
-                uint32_t e = (w >> (10 * j)) & 1023u;
-                uint32_t code = e & 31u, ts = e >> 5, ds = code >> 2;
-                uint32_t en = max(L.state[ds * kWave + lane], L.state[ts * kWave + lane]) + L.t_tab[code];
-                L.state[ds * kWave + lane] = en;
-                L.state[ts * kWave + lane] = en;
-            }
-        }
+        for (int j = 0; j < 6; j++) sweep_node(L, (w >> (5 * j)) & 31u, lane8, lane4);
+        w = wn;
     }
-    for (int p = 0; p < P.npaths; p++)
-        for (int mu = 0; mu < P.NR; mu++) {
-            int base = P.D + p * 2 * P.NR + mu;
-            L.state[base * kWave + lane] = L.state[(base + P.NR) * kWave + lane];
-            L.state[(base + P.NR) * kWave + lane] = 0;
+#pragma unroll
+    for (int j = 0; j < 5; j++)
+        if (j < tail) sweep_node(L, (w >> (5 * j)) & 31u, lane8, lane4);
+    // window boundary: micro-batches mu >= N_R are mu - N_R of the next window; counters restart at the leads
+    for (int p = 0; p < C.npaths; p++)
+        for (int mu = 0; mu < C.NR; mu++) {
+            int base = p * 2 * C.NR + mu;
+            L.tok[base * kWave + lane] = L.tok[(base + C.NR) * kWave + lane];
+            L.tok[(base + C.NR) * kWave + lane] = 0;
         }
+#pragma unroll
+    for (int d = 0; d < DM; d++)
+        if (d < C.D) L.drec[d * kWave + lane].y = (uint32_t)((d < 4 ? lead_code.lo : lead_code.hi) >> (16 * (d & 3))) & 0xFFFFu;
+}
+
+template <int DM>
+__device__ __forceinline__ void reset_sweep_state(const FastConst<DM> &C, const FastLds &L, int lane, const Mu &lead_code)
+{
+    for (int s = 0; s < C.nslots - C.D; s++) L.tok[s * kWave + lane] = 0;
+#pragma unroll
+    for (int d = 0; d < DM; d++)
+        if (d < C.D)
+            L.drec[d * kWave + lane] = make_uint2(0u, (uint32_t)((d < 4 ? lead_code.lo : lead_code.hi) >> (16 * (d & 3))) & 0xFFFFu);
 }
 
 // Period of the repeated window.  The sweep is a max-plus linear map F on the boundary vector x
@@ -514,17 +561,27 @@ __device__ __forceinline__ void sweep_fast(const KParams &P, const FastLds &L, i
 // has grown by the same delta, x is an eigenvector of F and delta is its eigenvalue = the maximum
 // cycle ratio, exactly.  Almost every candidate gets there within two or three sweeps; the rest
 // take Karp's formula over V+1 sweeps (two passes, no history).
-template <int VM>
-__device__ __forceinline__ int period_fast(const KParams &P, const FastLds &L, int lane, const Mu &leads, bool want)
+template <int DM, int VM>
+__device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds &L, int lane, const Mu &lead_code, bool want,
+                                           uint32_t &nsweeps_used)
 {
-    const int V = P.nsweeps - 1, n = P.nsweeps;
+    const int V = C.nsweeps - 1, n = C.nsweeps;
+    const uint32_t lane4 = (uint32_t)lane * 4u;
     uint32_t live = 0;                                    // per lane: which boundary values mean anything
+    uint32_t vaddr[VM];
 #pragma unroll
     for (int v = 0; v < VM; v++) {
-        if (v < P.D) live |= (P.ntd[v] > 0 ? 1u : 0u) << v;
-        else if (v < V) live |= (leads.get(P.v_src[v]) > (uint32_t)P.v_j[v] ? 1u : 0u) << v;
+        vaddr[v] = lane4;
+        if (v < V) {
+            const uint32_t e = L.vtab[v];
+            const bool on = (e >> 6 & 1u) ? (e >> 17 & 1u) != 0 : lead_code.get((e >> 7) & 31u) > ((e >> 13) & 15u);
+            live |= (on ? 1u : 0u) << v;
+            const uint32_t slot = e & 63u;                // device value: in its record; token value: in the token array
+            vaddr[v] = (e >> 6 & 1u) ? (uint32_t)((char *)&L.drec[slot * kWave + lane].x - (char *)L.drec)
+                                     : (uint32_t)((char *)&L.tok[(slot - (uint32_t)C.D) * kWave + lane] - (char *)L.drec);
+        }
     }
-    for (int s = 0; s < P.nslots; s++) L.state[s * kWave + lane] = 0;
+    reset_sweep_state<DM>(C, L, lane, lead_code);
     uint32_t prev[VM];
 #pragma unroll
     for (int v = 0; v < VM; v++) prev[v] = 0;
@@ -533,14 +590,15 @@ __device__ __forceinline__ int period_fast(const KParams &P, const FastLds &L, i
     constexpr int kTry = 6;
     for (int j = 0; j < kTry; j++) {
         if (__ballot(!done) == 0) break;
-        sweep_fast(P, L, lane);
+        sweep_fast<DM>(C, L, lane, lead_code, !done);
+        nsweeps_used += done ? 0u : 1u;
         bool same = true, have = false;
         uint32_t delta = 0;
 #pragma unroll
         for (int v = 0; v < VM; v++) {
             if (v < V) {
-                uint32_t x = L.state[reduced_slot(P, v) * kWave + lane];
-                uint32_t dv = x - prev[v];
+                const uint32_t x = *(const uint32_t *)((const char *)L.drec + vaddr[v]);
+                const uint32_t dv = x - prev[v];
                 prev[v] = x;
                 if (live >> v & 1u) {
                     if (!have) { delta = dv; have = true; }
@@ -553,26 +611,27 @@ __device__ __forceinline__ int period_fast(const KParams &P, const FastLds &L, i
     if (__ballot(!done) == 0) return T;
     // rare: no eigenvector yet.  Karp over n = V+1 sweeps, twice.
     uint32_t xn[VM], bn[VM], bd[VM];
-    for (int s = 0; s < P.nslots; s++) L.state[s * kWave + lane] = 0;
-    for (int j = 0; j < n; j++) sweep_fast(P, L, lane);
+    reset_sweep_state<DM>(C, L, lane, lead_code);
+    for (int j = 0; j < n; j++) sweep_fast<DM>(C, L, lane, lead_code, !done);
 #pragma unroll
     for (int v = 0; v < VM; v++) {
-        xn[v] = v < V ? L.state[reduced_slot(P, v) * kWave + lane] : 0u;
+        xn[v] = v < V ? *(const uint32_t *)((const char *)L.drec + vaddr[v]) : 0u;
         bn[v] = 0xFFFFFFFFu; bd[v] = 1u;
     }
-    for (int s = 0; s < P.nslots; s++) L.state[s * kWave + lane] = 0;
+    reset_sweep_state<DM>(C, L, lane, lead_code);
     for (int j = 0; j < n - 1; j++) {
-        sweep_fast(P, L, lane);
-        uint32_t den = (uint32_t)(n - 1 - j);
+        sweep_fast<DM>(C, L, lane, lead_code, !done);
+        const uint32_t den = (uint32_t)(n - 1 - j);
 #pragma unroll
         for (int v = 0; v < VM; v++) {
             if (v < V) {
-                uint32_t a = xn[v] - L.state[reduced_slot(P, v) * kWave + lane];
-                bool better = bn[v] == 0xFFFFFFFFu || (uint64_t)a * bd[v] < (uint64_t)bn[v] * den;
+                const uint32_t a = xn[v] - *(const uint32_t *)((const char *)L.drec + vaddr[v]);
+                const bool better = bn[v] == 0xFFFFFFFFu || (uint64_t)a * bd[v] < (uint64_t)bn[v] * den;
                 if (better) { bn[v] = a; bd[v] = den; }
             }
         }
     }
+    nsweeps_used += done ? 0u : (uint32_t)(2 * n - 1);
     uint32_t Tk = 0;
 #pragma unroll
     for (int v = 0; v < VM; v++)
@@ -580,124 +639,184 @@ __device__ __forceinline__ int period_fast(const KParams &P, const FastLds &L, i
     return done ? T : (int)Tk;
 }
 
-template <int DM, int VM>
-__device__ __forceinline__ int evaluate_fast(const KParams &P, uint64_t idx, const FastLds &L, int lane, int &period, int &peak_max,
-                                             bool valid)
+// even bits of a 64-bit word, compacted (bit 2p -> bit p)
+__device__ __forceinline__ uint32_t even_bits(uint64_t x)
 {
-    uint64_t ord[DM];
-    int nlen[DM];
-    Mu leads;
-    period = 0; peak_max = 0;
-    int status = decode_candidate<DM>(P, idx, ord, nlen, leads);
-    const uint32_t NR = (uint32_t)P.NR;
+    x &= 0x5555555555555555ull;
+    x = (x | (x >> 1)) & 0x3333333333333333ull;
+    x = (x | (x >> 2)) & 0x0F0F0F0F0F0F0F0Full;
+    x = (x | (x >> 4)) & 0x00FF00FF00FF00FFull;
+    x = (x | (x >> 8)) & 0x0000FFFF0000FFFFull;
+    x = (x | (x >> 16)) & 0x00000000FFFFFFFFull;
+    return (uint32_t)x;
+}
 
-    // counters by code, ready / exhausted / head masks, per-device records
-    Mu mu;
+template <int DM, int VM>
+__device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<DM> &C, uint64_t idx, const FastLds &L, int lane,
+                                             int &period, int &peak_max, bool valid, uint32_t &nsweeps_used)
+{
+    uint32_t plo[DM], phi[DM];       // order planes per device
+    int nlen[DM];
+    period = 0; peak_max = 0;
+    const uint32_t NR = (uint32_t)C.NR;
+    int status = kOk;
+    const bool sampled = C.space == kSampledStrict || C.space == kSampledRepair;
+    Mu leads_type;                   // by type id (exhaustive spaces, fixed leads)
+    leads_type.lo = 0; leads_type.hi = 0;
+    uint32_t ka = 0, kb = 0;
+    if (sampled) {
+        const uint64_t z = mix64(C.seed + 0x9E3779B97F4A7C15ULL * (idx + 1));
+        ka = (uint32_t)z; kb = (uint32_t)(z >> 32);
+#pragma unroll
+        for (int d = 0; d < DM; d++) {
+            plo[d] = phi[d] = 0; nlen[d] = 0;
+            if (d >= C.D) continue;
+            const uint32_t n = (uint32_t)C.ntd[d] * NR;
+            uint32_t c0 = C.ntd[d] > 0 ? NR : 0u, c1 = C.ntd[d] > 1 ? NR : 0u, c2 = C.ntd[d] > 2 ? NR : 0u;
+            uint32_t lo = 0, hi = 0, word = 0;
+            for (uint32_t pos = 0; pos < n; pos++) {
+                if ((pos & 1u) == 0) word = stream_word(ka, kb, (kDrawOrdBase + 32u * (uint32_t)d + pos) >> 1);
+                const uint32_t u = (pos & 1u) ? word >> 16 : word & 0xFFFFu;
+                const uint32_t digit = (u * (n - pos)) >> 16;
+                const uint32_t ge0 = digit >= c0, ge1 = digit >= c0 + c1, ge2 = digit >= c0 + c1 + c2;
+                const uint32_t y = ge0 + ge1 + ge2;
+                c0 -= 1u - ge0; c1 -= ge0 - ge1; c2 -= ge1 - ge2;
+                lo |= (y & 1u) << pos; hi |= (y >> 1) << pos;
+            }
+            plo[d] = lo; phi[d] = hi; nlen[d] = (int)n;
+        }
+        if (C.has_fixed)
+            for (int g = 0; g < C.K; g++) leads_type.set((uint32_t)g, P.fixed[g]);
+    } else {
+        uint64_t ord[DM];
+        status = decode_candidate<DM>(P, idx, ord, nlen, leads_type);
+#pragma unroll
+        for (int d = 0; d < DM; d++) { plo[d] = even_bits(ord[d]); phi[d] = even_bits(ord[d] >> 1); }
+    }
+
+    // leads by code, walking every chain from its last block to its first; R gets a type as soon
+    // as its producer's lead is ahead (the previous window already handled that micro-batch)
+    Mu mu, Q;                        // leads by code; micro-batches waiting at the input of every type
     mu.lo = 0; mu.hi = 0;
+    Q.lo = Q.hi = 0xFFFFFFFFFFFFFFFFull;          // 15: a chain's first block never waits
     uint32_t R = 0, HM = 0, X = 0;
+    const bool draw_leads = sampled && !C.has_fixed;
+    for (int k = 0; k < C.K; k++) {
+        const uint32_t ct = L.chain_tab[k];
+        const uint32_t c = ct & 63u, sc = (ct >> 6) & 63u;
+        const bool has_succ = sc != 63u;
+        const uint32_t lead_succ = mu.get(sc & 31u);
+        uint32_t lead;
+        if (draw_leads) {
+            const uint32_t e = (ct >> 12) & 127u;
+            const uint32_t wv = stream_word(ka, kb, (kDrawLeadBase + e) >> 1);
+            const uint32_t u = (e & 1u) ? wv >> 16 : wv & 0xFFFFu;
+            const uint32_t step = ((ct >> 19) & 1u) && u < C.step_q16 ? 1u : 0u;
+            lead = has_succ ? min(NR - 1u, lead_succ + step) : 0u;
+        } else {
+            lead = leads_type.get(ct >> 21);
+        }
+        mu.set(c, lead);
+        if (has_succ) Q.set(sc & 31u, lead - lead_succ);          // handled by the previous window already
+        if (has_succ && lead > lead_succ) R |= 1u << (sc & 31u);
+        if ((ct >> 20) & 1u) R |= 1u << c;
+    }
+
+    // per-device records
 #pragma unroll
     for (int d = 0; d < DM; d++) {
-        if (d >= P.D) continue;
-        uint32_t lim = 0;
+        if (d >= C.D) continue;
+        const uint32_t mud = (uint32_t)((d < 4 ? mu.lo : mu.hi) >> (16 * (d & 3))) & 0xFFFFu;
+        const uint32_t qd = (uint32_t)((d < 4 ? Q.lo : Q.hi) >> (16 * (d & 3))) & 0xFFFFu;
         int mem0 = 0;
 #pragma unroll
         for (int y = 0; y < kMaxLT; y++) {
-            if (y >= P.ntd[d]) continue;
-            uint32_t g = byte_of(P.type_of[d], (uint32_t)y), lead = leads.get(g);
-            mu.set((uint32_t)(4 * d + y), lead);
-            lim |= (lead + NR) << (4 * y);
-            mem0 += P.m_of[d][y] * (int)lead;                 // blocks that ran before the window
+            if (y >= C.ntd[d]) continue;
+            const uint32_t lead = (mud >> (4 * y)) & 15u;
+            mem0 += ((int)(C.mpack[d] << (24 - 8 * y)) >> 24) * (int)lead;     // blocks that ran before the window
         }
-        uint64_t alive = nlen[d] >= 32 ? 0x5555555555555555ull : ((1ull << (2 * nlen[d])) - 1ull) & 0x5555555555555555ull;
-        L.recA[d * kWave + lane] = make_uint4((uint32_t)ord[d], (uint32_t)(ord[d] >> 32), (uint32_t)alive, (uint32_t)(alive >> 32));
-        L.recB[d * kWave + lane] = make_uint2(lim, ((uint32_t)mem0 & 0xFFFFu) | (0x8000u << 16));
-        if (nlen[d] > 0) HM |= 1u << (4 * d + ((uint32_t)ord[d] & 3u));
-    }
-#pragma unroll
-    for (int d = 0; d < DM; d++) {
-        if (d >= P.D) continue;
-#pragma unroll
-        for (int y = 0; y < kMaxLT; y++) {
-            if (y >= P.ntd[d]) continue;
-            uint32_t c = (uint32_t)(4 * d + y), pr = (P.info_loc[c] >> 6) & 63u;
-            bool ready = pr == 63u || mu.get(pr) > mu.get(c);
-            R |= (ready ? 1u : 0u) << c;
-        }
+        const uint32_t alive = nlen[d] >= 32 ? 0xFFFFFFFFu : (1u << nlen[d]) - 1u;
+        L.rec[d * kWave + lane] = make_uint4(plo[d], phi[d], alive, qd | (((uint32_t)mem0 & 0xFFu) << 16) | (0x80u << 24));
+        if (nlen[d] > 0) HM |= 1u << (4 * d + ((plo[d] & 1u) | ((phi[d] & 1u) << 1)));
     }
 
-    const bool repair = P.space == kSampledRepair;
-    const int total = P.total;
+    const Mu lead_code = mu;
+    const bool repair = C.space == kSampledRepair;
+    const int total = C.total;
     bool building = valid && status == kOk;
     uint32_t acc = 0;
+    int sh = 0, wi = 0;
     for (int k = 0; k < total; k++) {
         if (__ballot(building) == 0) break;
-        uint32_t hm = R & HM;
-        uint32_t sel = hm ? hm : (repair ? R : 0u);
+        const uint32_t hm = R & HM;
+        const uint32_t sel = hm ? hm : (repair ? R : 0u);
         if (building && sel == 0) { status = kDeadlock; building = false; }
-        const uint32_t b = (uint32_t)__builtin_ctz(sel | 0x80000000u) & 31u;
-        const uint32_t d = building ? b >> 2 : 0u;
-        const uint4 a = L.recA[d * kWave + lane];
-        uint2 bb = L.recB[d * kWave + lane];
-        const uint4 inf4 = *(const uint4 *)(L.info_tab + 4 * d);
-        // earliest remaining entry of device d whose type is allowed (all types when its head runs)
-        const uint32_t r4 = hm ? 15u : (R >> (4 * d)) & 15u;
+        const uint32_t b = (uint32_t)__builtin_ctz(sel | 0x80000000u);
+        const uint32_t d4 = building ? b & 28u : 0u;             // 4 * device
+        uint4 a = L.rec[(d4 >> 2) * kWave + lane];
+        uint4 inf4 = *(const uint4 *)(L.info_tab + d4);
+        TESSEL_PIN(a.x); TESSEL_PIN(a.y); TESSEL_PIN(a.z); TESSEL_PIN(a.w);
+        TESSEL_PIN(inf4.x); TESSEL_PIN(inf4.y); TESSEL_PIN(inf4.z); TESSEL_PIN(inf4.w);
+        // earliest remaining entry of the device whose type is allowed (all types when its head runs):
+        // a 4-way multiplexer keyed by the two planes
+        const uint32_t r4 = hm ? 15u : (R >> d4) & 15u;
         const uint32_t r0 = 0u - (r4 & 1u), r1 = 0u - ((r4 >> 1) & 1u), r2 = 0u - ((r4 >> 2) & 1u), r3 = 0u - (r4 >> 3);
-        const uint32_t h_lo = (a.x >> 1) | (a.y << 31), h_hi = a.y >> 1;
-        const uint32_t g_lo = bfi(h_lo, bfi(a.x, r3, r2), bfi(a.x, r1, r0));
-        const uint32_t g_hi = bfi(h_hi, bfi(a.y, r3, r2), bfi(a.y, r1, r0));
-        const uint32_t u_lo = a.z & g_lo, u_hi = a.w & g_hi;
-        const uint32_t p = ctz64_parts(u_lo, u_hi) & 63u;
-        const uint64_t ordw = ((uint64_t)a.y << 32) | a.x;
-        const uint32_t y = (uint32_t)(ordw >> p) & 3u;
-        const uint32_t c = 4u * d + y;
+        const uint32_t gate = bfi(a.y, bfi(a.x, r3, r2), bfi(a.x, r1, r0));
+        const uint32_t p = (uint32_t)__builtin_ctz((a.z & gate) | 0x80000000u);
+        const uint32_t y = ((a.x >> p) & 1u) | (((a.y >> p) & 1u) << 1);
+        const uint32_t c = d4 + y;
         const uint32_t info = y & 2u ? (y & 1u ? inf4.w : inf4.z) : (y & 1u ? inf4.y : inf4.x);
-        // take the entry out, new head of the device
-        uint64_t alive = (((uint64_t)a.w << 32) | a.z) & ~(1ull << p);
-        const uint32_t al_lo = (uint32_t)alive, al_hi = (uint32_t)(alive >> 32);
-        const uint32_t p2 = ctz64_parts(al_lo, al_hi) & 63u;
-        const uint32_t y2 = (uint32_t)(ordw >> p2) & 3u;
-        uint32_t hm_new = HM & ~(15u << (4 * d));
-        if (alive) hm_new |= 1u << (4 * d + y2);
-        // counters and readiness of this type and of its consumer
-        const uint32_t mg = mu.get(c);
-        const uint32_t lim = (bb.x >> (4 * y)) & 15u;
-        const uint32_t pr = (info >> 6) & 63u, su = info & 63u;
-        const bool exhausted = mg + 1u == lim;
-        const bool ready_c = !exhausted && (pr == 63u || mu.get(pr) > mg + 1u);
+        // take the entry out; new head of the device
+        const uint32_t alive = a.z & ~(1u << p);
+        const uint32_t p2 = (uint32_t)__builtin_ctz(alive | 0x80000000u);
+        const uint32_t y2 = ((a.x >> p2) & 1u) | (((a.y >> p2) & 1u) << 1);
+        uint32_t hm_new = HM & ~(15u << d4);
+        if (alive) hm_new |= 1u << (d4 + y2);
+        // one waiting micro-batch is consumed; the type stays runnable while another one waits and
+        // entries of it remain; its consumer gets one more and becomes runnable
+        const uint32_t y4 = 4u * y;
+        const uint32_t ml = 0u - (1u - (y & 1u)), mh = 0u - (1u - (y >> 1));
+        const bool exhausted = (alive & (a.x ^ ml) & (a.y ^ mh)) == 0;
+        const uint32_t qc = (a.w >> y4) & 15u;
+        const bool ready_c = !exhausted && qc >= 2u;
+        const uint32_t su = info & 63u;
         uint32_t r_new = (R & ~(1u << c)) | ((ready_c ? 1u : 0u) << c);
         const uint32_t x_new = X | ((exhausted ? 1u : 0u) << c);
-        if (su != 63u) r_new |= (1u << su) & ~x_new;
+        const bool has_su = su != 63u;
+        if (has_su) r_new |= (1u << (su & 31u)) & ~x_new;
+        const uint32_t su_inc = has_su ? 1u << (4u * (su & 3u)) : 0u;
+        const bool su_here = (su & 28u) == d4;
         // memory prefix of the device (Eq. 1 [2])
         const int m = (int)(info << 6) >> 24;
-        const int memcur = (int)(int16_t)(bb.y & 0xFFFFu) + m;
-        const int pk = max((int)(int16_t)(bb.y >> 16), memcur);
-        const uint32_t entry = c | ((((info >> 12) & 63u) + mg) << 5);
-        const int sh = 10 * (k % 3);
+        const int memcur = ((int)(a.w << 8) >> 24) + m;
+        const int pk = max((int)a.w >> 24, memcur);
+        const uint32_t w_new = (((a.w & 0xFFFFu) - (1u << y4) + (su_here ? su_inc : 0u)) & 0xFFFFu) |
+                               (((uint32_t)memcur & 0xFFu) << 16) | ((uint32_t)pk << 24);
         if (building) {
             R = r_new; X = x_new; HM = hm_new;
-            mu.inc(c);
-            L.recA[d * kWave + lane].z = al_lo;
-            L.recA[d * kWave + lane].w = al_hi;
-            L.recB[d * kWave + lane].y = ((uint32_t)memcur & 0xFFFFu) | ((uint32_t)pk << 16);
-            acc |= entry << sh;
+            L.rec[(d4 >> 2) * kWave + lane].z = alive;
+            L.rec[(d4 >> 2) * kWave + lane].w = w_new;
+            if (has_su && !su_here) atomicAdd(&L.rec[((su & 28u) >> 2) * kWave + lane].w, su_inc);
+            acc |= c << sh;
         }
-        if (k % 3 == 2 || k == total - 1) {
-            L.prog[(k / 3) * kWave + lane] = acc;
-            acc = 0;
+        sh += 5;
+        if (sh == 30 || k == total - 1) {
+            L.prog[wi * kWave + lane] = acc;
+            acc = 0; sh = 0; wi++;
         }
     }
     if (status != kOk) return status;
     int worst = INT_MIN;
 #pragma unroll
     for (int d = 0; d < DM; d++) {
-        if (d >= P.D) continue;
-        int pk = (int)(int16_t)(L.recB[d * kWave + lane].y >> 16);
-        if (P.ntd[d] == 0) pk = 0;
+        if (d >= C.D) continue;
+        int pk = (int)L.rec[d * kWave + lane].w >> 24;
+        if (C.ntd[d] == 0) pk = 0;
         worst = max(worst, pk);
     }
     peak_max = worst;
-    if (valid && worst > P.M) status = kMem;
-    int T = period_fast<VM>(P, L, lane, leads, valid && status == kOk);
+    if (valid && worst > C.M) status = kMem;
+    int T = period_fast<DM, VM>(C, L, lane, lead_code, valid && status == kOk, nsweeps_used);
     if (status == kOk) period = T;
     return status;
 }
@@ -711,30 +830,46 @@ __global__ __launch_bounds__(kWave) void eval_fast_kernel(const KParams *__restr
     const KParams &P = *Pp;
     const int lane = threadIdx.x;
     FastLds L;
-    L.t_tab = lds;
-    L.info_tab = lds + kMaxK;
-    L.recA = (uint4 *)(lds + 2 * kMaxK);
-    L.recB = (uint2 *)(lds + 2 * kMaxK + DM * kWave * 4);
-    // the sweep state is only used once the build is over: it shares the build records' space when it fits
-    const bool share = P.nslots <= DM * 6;
-    L.state = share ? lds + 2 * kMaxK : lds + 2 * kMaxK + DM * kWave * 6;
-    L.prog = share ? lds + 2 * kMaxK + DM * kWave * 6 : L.state + P.nslots * kWave;
-    if (lane < kMaxK) { L.t_tab[lane] = (uint32_t)P.t_loc[lane]; L.info_tab[lane] = P.info_loc[lane]; }
+    L.tt_tab = (uint2 *)lds;                                  // 64 words
+    L.info_tab = lds + 2 * kMaxK;
+    L.chain_tab = lds + 3 * kMaxK;
+    L.vtab = lds + 4 * kMaxK;
+    uint32_t *base = lds + 5 * kMaxK;
+    L.rec = (uint4 *)base;
+    // the sweep state is only used once the build is over: it shares the records' space when it fits
+    const int ntok = P.nslots - P.D;
+    const bool share = P.D * 2 + ntok <= DM * 4;
+    uint32_t *sweep_base = share ? base : base + DM * kWave * 4;
+    L.drec = (uint2 *)sweep_base;
+    L.tok = sweep_base + P.D * kWave * 2;
+    L.prog = share ? base + DM * kWave * 4 : L.tok + ntok * kWave;
+    if (lane < kMaxK) {
+        const uint32_t inf = P.info_loc[lane];
+        L.tt_tab[lane] = make_uint2((uint32_t)P.t_loc[lane], ((((inf >> 12) & 63u) - (uint32_t)P.D) << 8));
+        L.info_tab[lane] = inf;
+        L.chain_tab[lane] = P.chain_tab[lane]; L.vtab[lane] = lane < 24 ? P.vtab[lane] : 0u;
+    }
     __syncthreads();
+    FastConst<DM> C;
+    C.D = P.D; C.K = P.K; C.NR = P.NR; C.M = P.M; C.total = P.total; C.nslots = P.nslots; C.npaths = P.npaths;
+    C.nsweeps = P.nsweeps; C.space = P.space; C.has_fixed = P.has_fixed; C.nwords = (P.total + 5) / 6;
+    C.step_q16 = P.step_q16; C.seed = P.seed;
+#pragma unroll
+    for (int d = 0; d < DM; d++) { C.ntd[d] = P.ntd[d]; C.mpack[d] = P.mpack[d]; }
 
     int best = INT_MAX;
     uint64_t best_idx = 0;
     uint32_t cnt[kNumStatus];
 #pragma unroll
     for (int s = 0; s < kNumStatus; s++) cnt[s] = 0;
-    uint32_t nev = 0;
+    uint32_t nev = 0, nsw = 0;
     const uint64_t stride = (uint64_t)gridDim.x * kWave;
     const uint64_t rounds = (count + stride - 1) / stride;          // the same trip count for every lane of the grid
     for (uint64_t r = 0; r < rounds; r++) {
         const uint64_t k = r * stride + (uint64_t)blockIdx.x * kWave + lane;
         const bool valid = k < count;
         int period, pk;
-        int status = evaluate_fast<DM, VM>(P, first + (valid ? k : 0), L, lane, period, pk, valid);
+        int status = evaluate_fast<DM, VM>(P, C, first + (valid ? k : 0), L, lane, period, pk, valid, nsw);
         if (!valid) continue;
         nev++;
 #pragma unroll
@@ -753,10 +888,11 @@ __global__ __launch_bounds__(kWave) void eval_fast_kernel(const KParams *__restr
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) cnt[s] += __shfl_xor(cnt[s], off);
         nev += __shfl_xor(nev, off);
+        nsw += __shfl_xor(nsw, off);
     }
     if (lane == 0) {
         BlockRec rr;
-        rr.period = best; rr.pad = 0; rr.index = best_idx; rr.n_evaluated = nev; rr.pad2 = 0;
+        rr.period = best; rr.pad = 0; rr.index = best_idx; rr.n_evaluated = nev; rr.n_sweeps = nsw;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) rr.n_status[s] = cnt[s];
         recs[blockIdx.x] = rr;
@@ -825,7 +961,7 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
     }
     if (lane == 0) {
         BlockRec r;
-        r.period = best; r.pad = 0; r.index = best_idx; r.n_evaluated = nev; r.pad2 = 0;
+        r.period = best; r.pad = 0; r.index = best_idx; r.n_evaluated = nev; r.n_sweeps = 0;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) r.n_status[s] = cnt[s];
         recs[blockIdx.x] = r;
@@ -837,13 +973,14 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
 {
     const int lane = threadIdx.x;
     int best = INT_MAX;
-    uint64_t best_idx = 0, nev = 0, cnt[kNumStatus];
+    uint64_t best_idx = 0, nev = 0, nsw = 0, cnt[kNumStatus];
 #pragma unroll
     for (int s = 0; s < kNumStatus; s++) cnt[s] = 0;
     for (int k = lane; k < nrecs; k += kWave) {
         BlockRec r = recs[k];
         if (key_less(r.period, r.index, best, best_idx)) { best = r.period; best_idx = r.index; }
         nev += r.n_evaluated;
+        nsw += r.n_sweeps;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) cnt[s] += r.n_status[s];
     }
@@ -855,6 +992,8 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
         if (key_less(op, oi, best, best_idx)) { best = op; best_idx = oi; }
         uint32_t lo = __shfl_xor((uint32_t)nev, off), hi = __shfl_xor((uint32_t)(nev >> 32), off);
         nev += ((uint64_t)hi << 32) | lo;
+        uint32_t slo = __shfl_xor((uint32_t)nsw, off), shi = __shfl_xor((uint32_t)(nsw >> 32), off);
+        nsw += ((uint64_t)shi << 32) | slo;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) {
             uint32_t l2 = __shfl_xor((uint32_t)cnt[s], off), h2 = __shfl_xor((uint32_t)(cnt[s] >> 32), off);
@@ -864,6 +1003,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
     if (lane == 0) {
         if (key_less(best, best_idx, res->period, res->index)) { res->period = best; res->index = best_idx; }
         res->n_evaluated += nev;
+        res->n_sweeps += nsw;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) res->n_status[s] += cnt[s];
     }
@@ -872,7 +1012,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
 __global__ void reset_kernel(DevResult *res)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
-        res->period = INT_MAX; res->pad = 0; res->index = ~0ull; res->n_evaluated = 0;
+        res->period = INT_MAX; res->pad = 0; res->index = ~0ull; res->n_evaluated = 0; res->n_sweeps = 0;
         for (int s = 0; s < kNumStatus; s++) res->n_status[s] = 0;
     }
 }
@@ -908,9 +1048,10 @@ static size_t general_lds_bytes(const KParams &kp)
 
 static size_t fast_lds_bytes(const KParams &kp)
 {
-    const bool share = kp.nslots <= fast_dm(kp) * 6;
-    return (size_t)2 * kMaxK * 4 + (size_t)fast_dm(kp) * kWave * 24 + (share ? 0 : (size_t)kp.nslots * kWave * 4) +
-           (size_t)((kp.total + 2) / 3) * kWave * 4;
+    const int ntok = kp.nslots - kp.D;
+    const bool share = kp.D * 2 + ntok <= fast_dm(kp) * 4;
+    return (size_t)5 * kMaxK * 4 + (size_t)fast_dm(kp) * kWave * 16 + (share ? 0 : (size_t)(kp.D * 2 + ntok) * kWave * 4) +
+           (size_t)((kp.total + 5) / 6) * kWave * 4;
 }
 
 LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
@@ -918,8 +1059,12 @@ LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
     LaunchShape s;
     s.threads = kWave;
     s.lds_bytes = pick_fast(kp) ? fast_lds_bytes(kp) : general_lds_bytes(kp);
-    int per_cu = (int)((160 * 1024) / (s.lds_bytes + 512));
+    int per_cu = (int)((160 * 1024) / ((s.lds_bytes + 511) / 512 * 512));
     if (per_cu > 8) per_cu = 8;
+    if (const char *env = getenv("TESSEL_BLOCKS_PER_CU")) {        // tuning knob: fewer resident workgroups per CU
+        int want = atoi(env);
+        if (want >= 1 && want < per_cu) per_cu = want;
+    }
     if (per_cu < 1) per_cu = 1;
     s.blocks = num_cus * per_cu;
     return s;

@@ -152,6 +152,9 @@ def test_config2_slices_and_the_1f1b_candidate(gpu):
     g = gpu.Problem(prob)
     code, peak = g.score_candidates(idx, 1)
     assert int(code[0]) == 12 and int(peak[0]) == 4        # zero bubble: N_R (tf + tb)
+    # ragged launches: waves with lanes past the end of the range next to feasible candidates
+    for first, count in ((idx - 3, 8), (idx - 70, 75), (idx - 1, 65)):
+        compare_scores(gpu, prob, first, count)
     g.eval_candidates(idx - 1000, 2000)
     got = g.best()
     assert got["period"] == 12 and got["peak"] == [4, 3, 2, 1]
