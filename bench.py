@@ -18,32 +18,31 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_INT32_OPS = 256 * 64 * 2.4e9 / 1e12      # T int32 lane-ops/s: 256 CUs x 64 lanes x 2.4 GHz, full-rate VALU ops
+# HBM bytes of one launch of 2^24 candidates, from the FETCH_SIZE / WRITE_SIZE passes in
+# profiles/eval_fast_kernel_cfg5_counters.md (253.25 KiB x 2.0 + 2176 KiB x 1.0, copy-calibrated)
+TRAFFIC_BYTES_PER_2P24_LAUNCH = int((253.25 * 2.0 + 2176 * 1.0) * 1024)
 
 
-def algorithmic_ops(prob, n_candidates, n_feasible):
-    """Integer operations the method needs (not what the kernel happens to issue):
-    decode 2 per block (digit, pick); build 3 per block and device it occupies (readiness
-    compare, memory add, running max); period: one max + one add per block and window sweep,
-    V + 1 sweeps with V = D + chains * N_R boundary values, plus 3 V^2 for the cycle-ratio
-    formula -- only for candidates that are executable and within the cap."""
+def algorithmic_ops(prob, n_candidates, n_sweeps):
+    """Integer operations of a straight-line statement of the method (not what the kernel
+    happens to issue), per block of the window: decode 17 (half a hash word, digit, pick),
+    build 34 (select, union of runnable entries, remove, new head, counters, masks, memory
+    add + max, emit), and 2 (one max, one add) per block and executed window sweep."""
     n = prob["K"] * prob["NR"]
-    occ = sum(bin(m).count("1") for m in prob["dev_mask"]) * prob["NR"]
-    chains = prob["K"] - len(prob["deps"])
-    V = prob["D"] + chains * prob["NR"]
-    per_cand = 2 * occ + 3 * occ
-    per_feasible = 2 * n * (V + 1) + 3 * V * V
-    return n_candidates * per_cand + n_feasible * per_feasible
+    return n_candidates * n * (17 + 34) + n_sweeps * n * 2
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--log2-candidates", type=int, default=28, help="candidates per step = 2^this (28 = the workload)")
     ap.add_argument("--log2-chunk", type=int, default=24, help="candidates per kernel launch")
-    ap.add_argument("--cpu-sample-log2", type=int, default=17, help="oracle baseline sample size")
+    ap.add_argument("--cpu-sample-log2", type=int, default=20, help="oracle baseline sample size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run one plain device copy of 1 GiB instead (reference for the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; the problem's 8 'devices' are simulated "
@@ -51,6 +50,14 @@ def main():
         sys.exit(2)
 
     import torch
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": 1 << 30}))
+        return
     from paper_2311_15269_amd import workloads
     from paper_2311_15269_amd.binding import Problem
 
@@ -90,8 +97,8 @@ def main():
 
     launch_ms = [a.elapsed_time(b) for a, b in events]
     avg_launch_s = sum(launch_ms) / len(launch_ms) / 1e3
-    feas_frac = best["n_feasible"] / best["n_evaluated"]
-    ops_per_launch = algorithmic_ops(prob, chunk, feas_frac * chunk)
+    sweeps_per_cand = best["n_window_sweeps"] / best["n_evaluated"]
+    ops_per_launch = algorithmic_ops(prob, chunk, sweeps_per_cand * chunk)
     achieved = ops_per_launch / avg_launch_s / 1e12
 
     out = {
@@ -109,9 +116,11 @@ def main():
                    "peak_mem": best["peak"], "n_feasible": best["n_feasible"], "n_reject": best["n_reject"],
                    "makespan_%d_microbatches" % N: sched["makespan"], "windows": sched["num_windows"]},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_INT32_OPS, "unit": "Tint32op/s",
-                     "frac": achieved / PEAK_INT32_OPS, "traffic": None,
-                     "kernel": "eval_kernel", "avg_launch_ms": avg_launch_s * 1e3,
-                     "algorithmic_ops_per_candidate": ops_per_launch / chunk},
+                     "frac": achieved / PEAK_INT32_OPS,
+                     "traffic": TRAFFIC_BYTES_PER_2P24_LAUNCH if chunk == 1 << 24 else None,
+                     "kernel": "eval_fast_kernel<8, 16>", "avg_launch_ms": avg_launch_s * 1e3,
+                     "algorithmic_ops_per_candidate": ops_per_launch / chunk,
+                     "window_sweeps_per_candidate": sweeps_per_cand},
     }
 
     if not args.no_cpu_baseline:

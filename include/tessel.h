@@ -115,6 +115,8 @@ typedef struct {
     uint64_t n_evaluated;
     uint64_t n_feasible;
     uint64_t n_reject[TESSEL_NUM_STATUS];     /* indexed by TESSEL_STATUS_*; [0] unused        */
+    uint64_t n_window_sweeps;                 /* sweeps of the window spent on period computations
+                                                 (0 when the general kernel did the scoring)    */
 } tessel_result;
 
 /* A complete schedule of N micro-batches: warm-up, R copies of the best window, cool-down
