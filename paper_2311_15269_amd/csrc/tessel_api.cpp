@@ -244,6 +244,19 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
                               ((uint32_t)i << 21);
             kp.valid_codes |= 1u << home[i];
         }
+        {
+            // chain_tab lists every chain from its last block to its first, one chain after the other
+            std::vector<int> pos(K, 0);
+            for (int k = 0; k < K; k++) pos[kp.rtopo[k]] = k;
+            for (int i = 0; i < K && ok; i++) {
+                uint32_t cum = 0;
+                for (int g = i; kp.succ[g] >= 0; g = kp.succ[g]) cum |= 1u << pos[g];
+                kp.cum_code[home[i]] = cum;
+                kp.pred_bit[home[i]] = kp.pred[i] < 0 ? 0u : 1u << pos[kp.pred[i]];
+                if (kp.succ[i] >= 0 && kp.edge_out[i] < kMaxK) kp.dep_bit[kp.edge_out[i]] = kp.cross_out[i] ? 1u << pos[i] : 0u;
+            }
+            if (desc->num_deps > kMaxK) ok = false;
+        }
         for (int d = 0; d < D; d++) {
             kp.vtab[d] = (uint32_t)d | (1u << 6) | ((uint32_t)(kp.ntd[d] > 0) << 17);
             for (int y = 0; y < kp.ntd[d]; y++) kp.mpack[d] |= ((uint32_t)kp.m_of[d][y] & 0xFFu) << (8 * y);

@@ -61,6 +61,11 @@ struct KParams {
                                  // chain, 21-26 type id
     uint32_t vtab[24];           // boundary value v: bits 0-5 state slot; 6 device value; 7-12 code of the first block
                                  // of the chain (token values); 13-16 micro-batch offset j; 17 device has blocks
+    // sampled leads as sums of per-dependency steps (bit k of the step mask = dependency out of the k-th
+    // entry of chain_tab)
+    uint32_t cum_code[kMaxK];    // by code: step bits whose sum (capped at N_R-1) is the type's lead
+    uint32_t pred_bit[kMaxK];    // by code: step bit of the dependency from its producer (0 = first of its chain)
+    uint32_t dep_bit[kMaxK];     // by dependency number: its step bit, 0 if both ends sit on the same device set
     uint32_t mpack[kMaxD];       // memory deltas of the device's 4 types, 8 bits each (signed)
     uint32_t valid_codes;        // bit c set <=> code c names a block type
     const int8_t   *leadtab;     // CANONICAL: [nlead][K] in device memory

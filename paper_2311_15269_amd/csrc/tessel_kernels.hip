@@ -476,6 +476,7 @@ struct FastLds {
     uint32_t *info_tab;   // [32]  packed consumer/producer/memory delta by code
     uint32_t *chain_tab;  // [32]  KParams::chain_tab
     uint32_t *vtab;       // [32]  KParams::vtab
+    uint32_t *cum_tab, *predbit_tab, *depbit_tab;   // [32] each: KParams::cum_code, pred_bit, dep_bit
     uint4 *rec;           // build: [DM][64] x: low plane, y: high plane, z: not-yet-placed mask,
                           //        w: micro-batches waiting at the input of the 4 types (4 bits each)
                           //           | memory now (8 bit) << 16 | peak << 24
@@ -487,7 +488,7 @@ struct FastLds {
 // problem scalars, read once per workgroup
 template <int DM>
 struct FastConst {
-    int D, K, NR, M, total, nslots, npaths, nsweeps, space, has_fixed, nwords;
+    int D, K, NR, M, total, nslots, npaths, nsweeps, space, has_fixed, nwords, ndeps;
     uint32_t step_q16;
     uint64_t seed;
     int ntd[DM];
@@ -672,16 +673,25 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
             plo[d] = phi[d] = 0; nlen[d] = 0;
             if (d >= C.D) continue;
             const uint32_t n = (uint32_t)C.ntd[d] * NR;
-            uint32_t c0 = C.ntd[d] > 0 ? NR : 0u, c1 = C.ntd[d] > 1 ? NR : 0u, c2 = C.ntd[d] > 2 ? NR : 0u;
-            uint32_t lo = 0, hi = 0, word = 0;
-            for (uint32_t pos = 0; pos < n; pos++) {
-                if ((pos & 1u) == 0) word = stream_word(ka, kb, (kDrawOrdBase + 32u * (uint32_t)d + pos) >> 1);
-                const uint32_t u = (pos & 1u) ? word >> 16 : word & 0xFFFFu;
-                const uint32_t digit = (u * (n - pos)) >> 16;
-                const uint32_t ge0 = digit >= c0, ge1 = digit >= c0 + c1, ge2 = digit >= c0 + c1 + c2;
-                const uint32_t y = ge0 + ge1 + ge2;
-                c0 -= 1u - ge0; c1 -= ge0 - ge1; c2 -= ge1 - ge2;
-                lo |= (y & 1u) << pos; hi |= (y >> 1) << pos;
+            // cumulative counts of the remaining blocks by type: a digit below t1 picks symbol 0, below t2 symbol 1, ...
+            uint32_t t1 = C.ntd[d] > 0 ? NR : 0u, t2 = t1 + (C.ntd[d] > 1 ? NR : 0u), t3 = t2 + (C.ntd[d] > 2 ? NR : 0u);
+            uint32_t lo = 0, hi = 0;
+            for (uint32_t pos = 0; pos < n; pos += 2) {
+                const uint32_t word = stream_word(ka, kb, (kDrawOrdBase + 32u * (uint32_t)d + pos) >> 1);
+                {
+                    const uint32_t digit = __umul24(word & 0xFFFFu, n - pos) >> 16;
+                    const uint32_t g1 = digit >= t1, g2 = digit >= t2, g3 = digit >= t3;
+                    const uint32_t y = g1 + g2 + g3;
+                    t1 += g1 - 1u; t2 += g2 - 1u; t3 += g3 - 1u;
+                    lo |= (y & 1u) << pos; hi |= (y >> 1) << pos;
+                }
+                if (pos + 1 < n) {
+                    const uint32_t digit = __umul24(word >> 16, n - pos - 1u) >> 16;
+                    const uint32_t g1 = digit >= t1, g2 = digit >= t2, g3 = digit >= t3;
+                    const uint32_t y = g1 + g2 + g3;
+                    t1 += g1 - 1u; t2 += g2 - 1u; t3 += g3 - 1u;
+                    lo |= (y & 1u) << (pos + 1u); hi |= (y >> 1) << (pos + 1u);
+                }
             }
             plo[d] = lo; phi[d] = hi; nlen[d] = (int)n;
         }
@@ -701,25 +711,47 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
     Q.lo = Q.hi = 0xFFFFFFFFFFFFFFFFull;          // 15: a chain's first block never waits
     uint32_t R = 0, HM = 0, X = 0;
     const bool draw_leads = sampled && !C.has_fixed;
-    for (int k = 0; k < C.K; k++) {
-        const uint32_t ct = L.chain_tab[k];
-        const uint32_t c = ct & 63u, sc = (ct >> 6) & 63u;
-        const bool has_succ = sc != 63u;
-        const uint32_t lead_succ = mu.get(sc & 31u);
-        uint32_t lead;
-        if (draw_leads) {
-            const uint32_t e = (ct >> 12) & 127u;
-            const uint32_t wv = stream_word(ka, kb, (kDrawLeadBase + e) >> 1);
-            const uint32_t u = (e & 1u) ? wv >> 16 : wv & 0xFFFFu;
-            const uint32_t step = ((ct >> 19) & 1u) && u < C.step_q16 ? 1u : 0u;
-            lead = has_succ ? min(NR - 1u, lead_succ + step) : 0u;
-        } else {
-            lead = leads_type.get(ct >> 21);
+    if (draw_leads) {
+        // every dependency between different device sets steps the lead with probability step_q16 / 65536;
+        // a lead is the number of steps from its type to the end of the chain, capped at N_R - 1
+        uint32_t S = 0;
+        for (int e = 0; e < C.ndeps; e += 2) {
+            const uint32_t wv = stream_word(ka, kb, (kDrawLeadBase + (uint32_t)e) >> 1);
+            S |= (wv & 0xFFFFu) < C.step_q16 ? L.depbit_tab[e] : 0u;
+            S |= (wv >> 16) < C.step_q16 && e + 1 < C.ndeps ? L.depbit_tab[e + 1] : 0u;
         }
-        mu.set(c, lead);
-        if (has_succ) Q.set(sc & 31u, lead - lead_succ);          // handled by the previous window already
-        if (has_succ && lead > lead_succ) R |= 1u << (sc & 31u);
-        if ((ct >> 20) & 1u) R |= 1u << c;
+#pragma unroll
+        for (int d = 0; d < DM; d++) {
+            if (d >= C.D) continue;
+            uint32_t mud = 0, qd = 0;
+#pragma unroll
+            for (int y = 0; y < kMaxLT; y++) {
+                if (y >= C.ntd[d]) continue;
+                const int c = 4 * d + y;
+                const uint32_t pb = L.predbit_tab[c];
+                const uint32_t cnt = (uint32_t)__builtin_popcount(S & L.cum_tab[c]);
+                const uint32_t lead = min(NR - 1u, cnt);
+                // micro-batches its producer handled in the previous window already; 15: no producer, never waits
+                const uint32_t wait = pb ? min(NR - 1u, cnt + ((S & pb) ? 1u : 0u)) - lead : 15u;
+                mud |= lead << (4 * y);
+                qd |= wait << (4 * y);
+                R |= (wait ? 1u : 0u) << c;
+            }
+            if (d < 4) { mu.lo |= (uint64_t)mud << (16 * d); Q.lo = (Q.lo & ~(0xFFFFull << (16 * d))) | ((uint64_t)qd << (16 * d)); }
+            else { mu.hi |= (uint64_t)mud << (16 * (d - 4)); Q.hi = (Q.hi & ~(0xFFFFull << (16 * (d - 4)))) | ((uint64_t)qd << (16 * (d - 4))); }
+        }
+    } else {
+        for (int k = 0; k < C.K; k++) {
+            const uint32_t ct = L.chain_tab[k];
+            const uint32_t c = ct & 63u, sc = (ct >> 6) & 63u;
+            const bool has_succ = sc != 63u;
+            const uint32_t lead_succ = mu.get(sc & 31u);
+            const uint32_t lead = leads_type.get(ct >> 21);
+            mu.set(c, lead);
+            if (has_succ) Q.set(sc & 31u, lead - lead_succ);          // handled by the previous window already
+            if (has_succ && lead > lead_succ) R |= 1u << (sc & 31u);
+            if ((ct >> 20) & 1u) R |= 1u << c;
+        }
     }
 
     // per-device records
@@ -834,7 +866,10 @@ __global__ __launch_bounds__(kWave) void eval_fast_kernel(const KParams *__restr
     L.info_tab = lds + 2 * kMaxK;
     L.chain_tab = lds + 3 * kMaxK;
     L.vtab = lds + 4 * kMaxK;
-    uint32_t *base = lds + 5 * kMaxK;
+    L.cum_tab = lds + 5 * kMaxK;
+    L.predbit_tab = lds + 6 * kMaxK;
+    L.depbit_tab = lds + 7 * kMaxK;
+    uint32_t *base = lds + 8 * kMaxK;
     L.rec = (uint4 *)base;
     // the sweep state is only used once the build is over: it shares the records' space when it fits
     const int ntok = P.nslots - P.D;
@@ -848,11 +883,12 @@ __global__ __launch_bounds__(kWave) void eval_fast_kernel(const KParams *__restr
         L.tt_tab[lane] = make_uint2((uint32_t)P.t_loc[lane], ((((inf >> 12) & 63u) - (uint32_t)P.D) << 8));
         L.info_tab[lane] = inf;
         L.chain_tab[lane] = P.chain_tab[lane]; L.vtab[lane] = lane < 24 ? P.vtab[lane] : 0u;
+        L.cum_tab[lane] = P.cum_code[lane]; L.predbit_tab[lane] = P.pred_bit[lane]; L.depbit_tab[lane] = P.dep_bit[lane];
     }
     __syncthreads();
     FastConst<DM> C;
     C.D = P.D; C.K = P.K; C.NR = P.NR; C.M = P.M; C.total = P.total; C.nslots = P.nslots; C.npaths = P.npaths;
-    C.nsweeps = P.nsweeps; C.space = P.space; C.has_fixed = P.has_fixed; C.nwords = (P.total + 5) / 6;
+    C.nsweeps = P.nsweeps; C.space = P.space; C.has_fixed = P.has_fixed; C.nwords = (P.total + 5) / 6; C.ndeps = P.K - P.npaths;
     C.step_q16 = P.step_q16; C.seed = P.seed;
 #pragma unroll
     for (int d = 0; d < DM; d++) { C.ntd[d] = P.ntd[d]; C.mpack[d] = P.mpack[d]; }
@@ -1050,7 +1086,7 @@ static size_t fast_lds_bytes(const KParams &kp)
 {
     const int ntok = kp.nslots - kp.D;
     const bool share = kp.D * 2 + ntok <= fast_dm(kp) * 4;
-    return (size_t)5 * kMaxK * 4 + (size_t)fast_dm(kp) * kWave * 16 + (share ? 0 : (size_t)(kp.D * 2 + ntok) * kWave * 4) +
+    return (size_t)8 * kMaxK * 4 + (size_t)fast_dm(kp) * kWave * 16 + (share ? 0 : (size_t)(kp.D * 2 + ntok) * kWave * 4) +
            (size_t)((kp.total + 5) / 6) * kWave * 4;
 }
 
