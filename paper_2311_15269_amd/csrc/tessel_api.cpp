@@ -346,7 +346,7 @@ static int ensure_device(tessel_problem *p)
 static size_t workspace_need(const tessel_problem *p, int num_cus)
 {
     LaunchShape s = eval_launch_shape(p->kp, num_cus);
-    return kWsBlockRecOff + block_rec_bytes(s.blocks) + 256;
+    return kWsBlockRecOff + block_rec_bytes(s.blocks + kDeferBlocks) + 256;
 }
 
 extern "C" int tessel_workspace_bytes(const tessel_problem *p, size_t *bytes)
@@ -355,7 +355,7 @@ extern "C" int tessel_workspace_bytes(const tessel_problem *p, size_t *bytes)
     // sized for the largest grid the launcher uses (8 blocks on each of 256 compute units at most,
     // more if the device reports more)
     int cus = p->num_cus ? p->num_cus : 512;
-    *bytes = workspace_need(p, std::max(cus, 512));
+    *bytes = workspace_need(p, std::max(cus, 512));      // 16 workgroups per CU at most
     return TESSEL_OK;
 }
 
@@ -466,6 +466,7 @@ extern "C" int tessel_best(tessel_problem *p, tessel_result *out)
     out->n_feasible = p->result.n_status[kOk];
     for (int s = 1; s < kNumStatus; s++) out->n_reject[s] = p->result.n_status[s];
     out->n_window_sweeps = p->result.n_sweeps;
+    if (p->result.overflow) return TESSEL_E_WORKSPACE;       // more candidates deferred than the list holds
     if (p->result.period == INT_MAX) { out->period = -1; return TESSEL_E_NO_FEASIBLE; }
     out->period = p->result.period;
     out->index = p->result.index;

@@ -80,6 +80,10 @@ struct DevResult {
     uint64_t n_evaluated;
     uint64_t n_status[kNumStatus];   // [kOk] = feasible
     uint64_t n_sweeps;               // window sweeps spent on period computations (fast kernel)
+    uint32_t n_deferred;             // candidates the fast kernel handed to the general kernel so far
+    uint32_t overflow;               // the deferred list was too small at some point: results are incomplete
+    uint32_t defer_count;            // entries of the deferred list of the launch in flight
+    uint32_t pad2;
 };
 
 // Decoded best candidate, written by the detail kernel.
@@ -96,7 +100,10 @@ constexpr size_t kWsDetailOff = 256;
 constexpr size_t kWsParamsOff = 2048;          // KParams of the bound problem
 constexpr size_t kWsTablesOff = 8192;          // lead table, arrangement table
 constexpr size_t kWsTablesMax = 1 << 20;
-constexpr size_t kWsBlockRecOff = kWsTablesOff + kWsTablesMax;
+constexpr size_t kWsListOff = kWsTablesOff + kWsTablesMax;     // candidates deferred to the general kernel
+constexpr uint32_t kWsListCap = 1u << 16;
+constexpr size_t kWsBlockRecOff = kWsListOff + (size_t)kWsListCap * 8;
+constexpr int kDeferBlocks = 64;                                // grid of the deferred pass
 
 static_assert(sizeof(KParams) <= kWsTablesOff - kWsParamsOff, "parameter block must fit its workspace slot");
 static_assert(sizeof(DevDetail) <= kWsParamsOff - kWsDetailOff, "detail record must fit its workspace slot");

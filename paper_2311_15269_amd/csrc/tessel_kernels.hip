@@ -24,6 +24,8 @@
 
 namespace tessel {
 
+constexpr int kDeferred = -1;    // fast kernel only: the general kernel has to score this candidate
+
 struct BlockRec {
     int32_t  period;
     int32_t  pad;
@@ -471,6 +473,17 @@ __device__ __forceinline__ bool key_less(int pa, uint64_t ia, int pb, uint64_t i
 // run-time device number and therefore lives in LDS [device][lane]; masks and the 4-bit
 // micro-batch counters stay in VGPRs.
 
+// the window's program: six 5-bit type codes a word, in executable order.  It is written and read with a
+// wave-uniform word index, so it can live in VGPRs (indirect register addressing) and costs no LDS.
+typedef uint32_t u32x32 __attribute__((ext_vector_type(32)));
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+struct FastProgram {
+    u32x32 a;
+    u32x16 b;
+    __device__ __forceinline__ uint32_t get(int i) const { return i < 32 ? a[i] : b[i - 32]; }
+    __device__ __forceinline__ void set(int i, uint32_t v) { if (i < 32) a[i] = v; else b[i - 32] = v; }
+};
+
 struct FastLds {
     uint2 *tt_tab;        // [32]  x: t by code, y: byte offset of the first token slot of the code's chain
     uint32_t *info_tab;   // [32]  packed consumer/producer/memory delta by code
@@ -482,7 +495,6 @@ struct FastLds {
                           //           | memory now (8 bit) << 16 | peak << 24
     uint2 *drec;          // sweeps: [D][64] x: device free time, y: next micro-batch of the 4 types (4 bits each)
     uint32_t *tok;        // sweeps: [token slots][64] end time of the micro-batch's latest block
-    uint32_t *prog;       // [ceil(total/6)][64] six 5-bit type codes a word, in executable order
 };
 
 // problem scalars, read once per workgroup
@@ -518,23 +530,25 @@ __device__ __forceinline__ void sweep_node(const FastLds &L, uint32_t code, uint
 
 // One sweep of the window over the program, then the window boundary.
 template <int DM>
-__device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds &L, int lane, const Mu &lead_code, bool active)
+__device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds &L, const FastProgram &prog, int lane,
+                                           const Mu &lead_code, bool active)
 {
     // a lane without a complete program (rejected candidate, lane past the end of the range) must not run one:
     // its counters would leave the token ring
     if (!active) return;
     const uint32_t lane4 = (uint32_t)lane * 4u, lane8 = (uint32_t)lane * 8u;
     const int full = C.total / 6, tail = C.total - 6 * full;
-    uint32_t w = L.prog[lane];
     for (int i = 0; i < full; i++) {
-        const uint32_t wn = L.prog[(i + 1 < C.nwords ? i + 1 : i) * kWave + lane];     // next word, early
+        const uint32_t w = prog.get(i);
 #pragma unroll
         for (int j = 0; j < 6; j++) sweep_node(L, (w >> (5 * j)) & 31u, lane8, lane4);
-        w = wn;
     }
+    if (tail > 0) {
+        const uint32_t w = prog.get(full);
 #pragma unroll
-    for (int j = 0; j < 5; j++)
-        if (j < tail) sweep_node(L, (w >> (5 * j)) & 31u, lane8, lane4);
+        for (int j = 0; j < 5; j++)
+            if (j < tail) sweep_node(L, (w >> (5 * j)) & 31u, lane8, lane4);
+    }
     // window boundary: micro-batches mu >= N_R are mu - N_R of the next window; counters restart at the leads
     for (int p = 0; p < C.npaths; p++)
         for (int mu = 0; mu < C.NR; mu++) {
@@ -560,13 +574,14 @@ __device__ __forceinline__ void reset_sweep_state(const FastConst<DM> &C, const 
 // Period of the repeated window.  The sweep is a max-plus linear map F on the boundary vector x
 // (device free times, in-flight micro-batch end times).  If after some sweep every live component
 // has grown by the same delta, x is an eigenvector of F and delta is its eigenvalue = the maximum
-// cycle ratio, exactly.  Almost every candidate gets there within two or three sweeps; the rest
-// take Karp's formula over V+1 sweeps (two passes, no history).
+// cycle ratio, exactly.  Almost every candidate gets there within two or three sweeps; one that has
+// not after kTry sweeps is handed to the general kernel (Karp's formula).
 template <int DM, int VM>
-__device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds &L, int lane, const Mu &lead_code, bool want,
+__device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds &L, const FastProgram &prog, int lane,
+                                           const Mu &lead_code, bool want,
                                            uint32_t &nsweeps_used)
 {
-    const int V = C.nsweeps - 1, n = C.nsweeps;
+    const int V = C.nsweeps - 1;
     const uint32_t lane4 = (uint32_t)lane * 4u;
     uint32_t live = 0;                                    // per lane: which boundary values mean anything
     uint32_t vaddr[VM];
@@ -591,7 +606,7 @@ __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds
     constexpr int kTry = 6;
     for (int j = 0; j < kTry; j++) {
         if (__ballot(!done) == 0) break;
-        sweep_fast<DM>(C, L, lane, lead_code, !done);
+        sweep_fast<DM>(C, L, prog, lane, lead_code, !done);
         nsweeps_used += done ? 0u : 1u;
         bool same = true, have = false;
         uint32_t delta = 0;
@@ -609,35 +624,7 @@ __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds
         }
         if (!done && same && have) { T = (int)delta; done = true; }
     }
-    if (__ballot(!done) == 0) return T;
-    // rare: no eigenvector yet.  Karp over n = V+1 sweeps, twice.
-    uint32_t xn[VM], bn[VM], bd[VM];
-    reset_sweep_state<DM>(C, L, lane, lead_code);
-    for (int j = 0; j < n; j++) sweep_fast<DM>(C, L, lane, lead_code, !done);
-#pragma unroll
-    for (int v = 0; v < VM; v++) {
-        xn[v] = v < V ? *(const uint32_t *)((const char *)L.drec + vaddr[v]) : 0u;
-        bn[v] = 0xFFFFFFFFu; bd[v] = 1u;
-    }
-    reset_sweep_state<DM>(C, L, lane, lead_code);
-    for (int j = 0; j < n - 1; j++) {
-        sweep_fast<DM>(C, L, lane, lead_code, !done);
-        const uint32_t den = (uint32_t)(n - 1 - j);
-#pragma unroll
-        for (int v = 0; v < VM; v++) {
-            if (v < V) {
-                const uint32_t a = xn[v] - *(const uint32_t *)((const char *)L.drec + vaddr[v]);
-                const bool better = bn[v] == 0xFFFFFFFFu || (uint64_t)a * bd[v] < (uint64_t)bn[v] * den;
-                if (better) { bn[v] = a; bd[v] = den; }
-            }
-        }
-    }
-    nsweeps_used += done ? 0u : (uint32_t)(2 * n - 1);
-    uint32_t Tk = 0;
-#pragma unroll
-    for (int v = 0; v < VM; v++)
-        if (v < V) Tk = max(Tk, (bn[v] + bd[v] - 1u) / bd[v]);
-    return done ? T : (int)Tk;
+    return done ? T : -1;        // -1: no eigenvector within kTry sweeps (the caller defers the candidate)
 }
 
 // even bits of a 64-bit word, compacted (bit 2p -> bit p)
@@ -778,6 +765,8 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
     bool building = valid && status == kOk;
     uint32_t acc = 0;
     int sh = 0, wi = 0;
+    FastProgram prog;
+    prog.a = 0; prog.b = 0;
     for (int k = 0; k < total; k++) {
         if (__ballot(building) == 0) break;
         const uint32_t hm = R & HM;
@@ -833,7 +822,7 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
         }
         sh += 5;
         if (sh == 30 || k == total - 1) {
-            L.prog[wi * kWave + lane] = acc;
+            prog.set(wi, acc);
             acc = 0; sh = 0; wi++;
         }
     }
@@ -848,15 +837,19 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
     }
     peak_max = worst;
     if (valid && worst > C.M) status = kMem;
-    int T = period_fast<DM, VM>(C, L, lane, lead_code, valid && status == kOk, nsweeps_used);
-    if (status == kOk) period = T;
+    int T = period_fast<DM, VM>(C, L, prog, lane, lead_code, valid && status == kOk, nsweeps_used);
+    if (status == kOk) {
+        if (T < 0) return kDeferred;
+        period = T;
+    }
     return status;
 }
 
 template <int DM, int VM>
-__global__ __launch_bounds__(kWave) void eval_fast_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
+__global__ __launch_bounds__(kWave, 3) void eval_fast_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
                                                           BlockRec *__restrict__ recs, int32_t *__restrict__ code_out,
-                                                          int32_t *__restrict__ peak_out)
+                                                          int32_t *__restrict__ peak_out, uint64_t *__restrict__ defer_list,
+                                                          uint32_t *__restrict__ defer_count)
 {
     extern __shared__ uint32_t lds[];
     const KParams &P = *Pp;
@@ -877,7 +870,6 @@ __global__ __launch_bounds__(kWave) void eval_fast_kernel(const KParams *__restr
     uint32_t *sweep_base = share ? base : base + DM * kWave * 4;
     L.drec = (uint2 *)sweep_base;
     L.tok = sweep_base + P.D * kWave * 2;
-    L.prog = share ? base + DM * kWave * 4 : L.tok + ntok * kWave;
     if (lane < kMaxK) {
         const uint32_t inf = P.info_loc[lane];
         L.tt_tab[lane] = make_uint2((uint32_t)P.t_loc[lane], ((((inf >> 12) & 63u) - (uint32_t)P.D) << 8));
@@ -907,6 +899,11 @@ __global__ __launch_bounds__(kWave) void eval_fast_kernel(const KParams *__restr
         int period, pk;
         int status = evaluate_fast<DM, VM>(P, C, first + (valid ? k : 0), L, lane, period, pk, valid, nsw);
         if (!valid) continue;
+        if (status == kDeferred) {
+            const uint32_t at = atomicAdd(defer_count, 1u);
+            if (at < kWsListCap) defer_list[at] = first + k;
+            continue;
+        }
         nev++;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) cnt[s] += status == s;
@@ -939,10 +936,13 @@ __global__ __launch_bounds__(kWave) void eval_fast_kernel(const KParams *__restr
 template <int DM, int VM>
 __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
                                                      BlockRec *__restrict__ recs, int32_t *__restrict__ code_out,
-                                                     int32_t *__restrict__ peak_out, DevDetail *__restrict__ detail)
+                                                     int32_t *__restrict__ peak_out, DevDetail *__restrict__ detail,
+                                                     const uint64_t *__restrict__ list, const uint32_t *__restrict__ list_count)
 {
     const KParams &P = *Pp;
     extern __shared__ uint32_t lds[];
+    // with a list: score the listed candidates (all inside [first, first + count)) instead of the range
+    if (list) count = min(*list_count, kWsListCap);
     int32_t *t_tab = (int32_t *)lds;
     uint32_t *mask_tab = lds + kMaxK;
     uint32_t *state_all = lds + 2 * kMaxK;
@@ -961,13 +961,15 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
     uint32_t nev = 0;
 
     const uint64_t stride = (uint64_t)gridDim.x * kWave;
-    for (uint64_t k = (uint64_t)blockIdx.x * kWave + lane; k < count; k += stride) {
+    for (uint64_t kk = (uint64_t)blockIdx.x * kWave + lane; kk < count; kk += stride) {
+        const uint64_t idx = list ? list[kk] : first + kk;
+        const uint64_t k = idx - first;
         int period, peak[DM];
-        int status = evaluate<DM, VM>(P, first + k, prog, state, t_tab, mask_tab, period, peak, detail);
+        int status = evaluate<DM, VM>(P, idx, prog, state, t_tab, mask_tab, period, peak, detail);
         nev++;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) cnt[s] += status == s;
-        if (status == kOk && period < best) { best = period; best_idx = first + k; }   // ascending k: first wins
+        if (status == kOk && key_less(period, idx, best, best_idx)) { best = period; best_idx = idx; }
         int pk = 0;
         if (status == kOk || status == kMem) {
             pk = INT_MIN;
@@ -1005,7 +1007,7 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
 }
 
 // merges the block records of one launch into the running best (one wave)
-__global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int nrecs, DevResult *res)
+__global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int nrecs, DevResult *res, uint32_t *defer_count)
 {
     const int lane = threadIdx.x;
     int best = INT_MAX;
@@ -1038,6 +1040,9 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
     }
     if (lane == 0) {
         if (key_less(best, best_idx, res->period, res->index)) { res->period = best; res->index = best_idx; }
+        if (*defer_count > kWsListCap) res->overflow = 1;
+        res->n_deferred += min(*defer_count, kWsListCap);
+        *defer_count = 0;      // the deferred pass of this launch has run (stream order)
         res->n_evaluated += nev;
         res->n_sweeps += nsw;
 #pragma unroll
@@ -1045,17 +1050,22 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
     }
 }
 
+// only the counter of the deferred list (after a per-candidate scoring call)
+__global__ void clear_defer_kernel(uint32_t *defer_count) { if (threadIdx.x == 0 && blockIdx.x == 0) *defer_count = 0; }
+
 __global__ void reset_kernel(DevResult *res)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         res->period = INT_MAX; res->pad = 0; res->index = ~0ull; res->n_evaluated = 0; res->n_sweeps = 0;
+        res->n_deferred = 0; res->overflow = 0; res->defer_count = 0;
         for (int s = 0; s < kNumStatus; s++) res->n_status[s] = 0;
     }
 }
 
 // ------------------------------------------------------------------ launchers
-typedef void (*eval_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, DevDetail *);
-typedef void (*fast_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *);
+typedef void (*eval_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, DevDetail *, const uint64_t *,
+                        const uint32_t *);
+typedef void (*fast_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, uint64_t *, uint32_t *);
 
 static eval_fn pick_kernel(const KParams &kp)
 {
@@ -1086,17 +1096,23 @@ static size_t fast_lds_bytes(const KParams &kp)
 {
     const int ntok = kp.nslots - kp.D;
     const bool share = kp.D * 2 + ntok <= fast_dm(kp) * 4;
-    return (size_t)8 * kMaxK * 4 + (size_t)fast_dm(kp) * kWave * 16 + (share ? 0 : (size_t)(kp.D * 2 + ntok) * kWave * 4) +
-           (size_t)((kp.total + 5) / 6) * kWave * 4;
+    return (size_t)8 * kMaxK * 4 + (size_t)fast_dm(kp) * kWave * 16 + (share ? 0 : (size_t)(kp.D * 2 + ntok) * kWave * 4);
 }
 
 LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
 {
     LaunchShape s;
     s.threads = kWave;
-    s.lds_bytes = pick_fast(kp) ? fast_lds_bytes(kp) : general_lds_bytes(kp);
-    int per_cu = (int)((160 * 1024) / ((s.lds_bytes + 511) / 512 * 512));
-    if (per_cu > 8) per_cu = 8;
+    fast_fn ff = pick_fast(kp);
+    s.lds_bytes = ff ? fast_lds_bytes(kp) : general_lds_bytes(kp);
+    // resident workgroups per CU as the runtime computes them from LDS and registers
+    int per_cu = 0;
+    const void *fn = ff ? (const void *)ff : (const void *)pick_kernel(kp);
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kWave, s.lds_bytes) != hipSuccess || per_cu < 1) {
+        (void)hipGetLastError();
+        per_cu = (int)((160 * 1024) / ((s.lds_bytes + 511) / 512 * 512));
+    }
+    if (per_cu > 16) per_cu = 16;
     if (const char *env = getenv("TESSEL_BLOCKS_PER_CU")) {        // tuning knob: fewer resident workgroups per CU
         int want = atoi(env);
         if (want >= 1 && want < per_cu) per_cu = want;
@@ -1106,55 +1122,73 @@ LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
     return s;
 }
 
-// general == true forces the general kernel (the only one that writes the decoded candidate)
-static int launch_common(const KParams &kp, const KParams *kp_dev, uint64_t first, uint64_t count, int blocks, BlockRec *recs,
-                         int32_t *code, int32_t *peak, DevDetail *detail, bool general, hipStream_t st)
+static int launch_general(const KParams &kp, const KParams *kp_dev, uint64_t first, uint64_t count, int blocks, BlockRec *recs,
+                          int32_t *code, int32_t *peak, DevDetail *detail, const uint64_t *list, const uint32_t *list_count,
+                          hipStream_t st)
 {
-    fast_fn ff = general ? nullptr : pick_fast(kp);
-    const size_t lds = ff ? fast_lds_bytes(kp) : general_lds_bytes(kp);
-    const void *fn = ff ? (const void *)ff : (const void *)pick_kernel(kp);
+    eval_fn fn = pick_kernel(kp);
+    const size_t lds = general_lds_bytes(kp);
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return (int)e;
     }
-    if (ff) hipLaunchKernelGGL(ff, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak);
-    else hipLaunchKernelGGL(pick_kernel(kp), dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, detail);
+    hipLaunchKernelGGL(fn, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, detail, list, list_count);
     return (int)hipGetLastError();
 }
 
-static int grid_for(const KParams &kp, uint64_t count, int num_cus)
+// Scores [first, first+count): the fast kernel where the problem allows it, then the general kernel over the few
+// candidates the fast kernel deferred; else the general kernel alone.  Returns the number of block records written
+// (recs may be null: per-candidate outputs only) or a negative HIP error.
+static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, BlockRec *recs, int32_t *code,
+                       int32_t *peak, bool general, hipStream_t st)
 {
+    const KParams *kp_dev = (const KParams *)((char *)ws + kWsParamsOff);
+    uint64_t *list = (uint64_t *)((char *)ws + kWsListOff);
+    uint32_t *list_count = &((DevResult *)((char *)ws + kWsResultOff))->defer_count;
     LaunchShape s = eval_launch_shape(kp, num_cus);
     uint64_t need = (count + kWave - 1) / kWave;
-    return need < (uint64_t)s.blocks ? (int)need : s.blocks;
+    const int blocks = need < (uint64_t)s.blocks ? (int)need : s.blocks;
+    if (blocks < 1) return 0;
+    fast_fn ff = general ? nullptr : pick_fast(kp);
+    if (!ff) {
+        int rc = launch_general(kp, kp_dev, first, count, blocks, recs, code, peak, nullptr, nullptr, nullptr, st);
+        return rc ? -rc : blocks;
+    }
+    hipLaunchKernelGGL(ff, dim3(blocks), dim3(kWave), fast_lds_bytes(kp), st, kp_dev, first, count, recs, code, peak, list, list_count);
+    int rc = (int)hipGetLastError();
+    if (rc) return -rc;
+    rc = launch_general(kp, kp_dev, first, count, kDeferBlocks, recs ? recs + blocks : nullptr, code, peak, nullptr, list, list_count, st);
+    return rc ? -rc : blocks + kDeferBlocks;
 }
 
 int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    int blocks = grid_for(kp, count, num_cus);
-    if (blocks < 1) return 0;
     BlockRec *recs = (BlockRec *)((char *)ws + kWsBlockRecOff);
-    int rc = launch_common(kp, (const KParams *)((char *)ws + kWsParamsOff), first, count, blocks, recs, nullptr, nullptr,
-                           nullptr, false, st);
-    if (rc) return rc;
-    hipLaunchKernelGGL(merge_kernel, dim3(1), dim3(kWave), 0, st, recs, blocks, (DevResult *)((char *)ws + kWsResultOff));
+    DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
+    int n = launch_pass(kp, first, count, ws, num_cus, recs, nullptr, nullptr, false, st);
+    if (n < 0) return -n;
+    if (n == 0) return 0;
+    hipLaunchKernelGGL(merge_kernel, dim3(1), dim3(kWave), 0, st, recs, n, res, &res->defer_count);
     return (int)hipGetLastError();
 }
 
 int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *ws, int num_cus,
                  bool general, void *stream)
 {
-    int blocks = grid_for(kp, count, num_cus);
-    if (blocks < 1) return 0;
-    return launch_common(kp, (const KParams *)((char *)ws + kWsParamsOff), first, count, blocks, nullptr, code, peak, nullptr,
-                         general, (hipStream_t)stream);
+    hipStream_t st = (hipStream_t)stream;
+    DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
+    int n = launch_pass(kp, first, count, ws, num_cus, nullptr, code, peak, general, st);
+    if (n < 0) return -n;
+    hipLaunchKernelGGL(clear_defer_kernel, dim3(1), dim3(1), 0, st, &res->defer_count);
+    return (int)hipGetLastError();
 }
 
 int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream)
 {
-    return launch_common(kp, (const KParams *)((char *)ws + kWsParamsOff), index, 1, 1, nullptr, nullptr, nullptr,
-                         (DevDetail *)((char *)ws + kWsDetailOff), true, (hipStream_t)stream);
+    int rc = launch_general(kp, (const KParams *)((char *)ws + kWsParamsOff), index, 1, 1, nullptr, nullptr, nullptr,
+                            (DevDetail *)((char *)ws + kWsDetailOff), nullptr, nullptr, (hipStream_t)stream);
+    return rc;
 }
 
 int launch_reset(void *ws, void *stream)
