@@ -268,6 +268,11 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
             path++;
         }
         kp.fast_ok = ok;
+        kp.eigen_tries = 6;
+        if (const char *env = getenv("TESSEL_EIGEN_TRIES")) {      // test knob: force candidates onto the deferred path
+            int v = atoi(env);
+            if (v >= 0 && v <= 64) kp.eigen_tries = v;
+        }
     }
     // candidate count and the tables of the exhaustive spaces
     if (desc->space == TESSEL_SPACE_FACTORIAL) {

@@ -68,6 +68,7 @@ struct KParams {
     uint32_t dep_bit[kMaxK];     // by dependency number: its step bit, 0 if both ends sit on the same device set
     uint32_t mpack[kMaxD];       // memory deltas of the device's 4 types, 8 bits each (signed)
     uint32_t valid_codes;        // bit c set <=> code c names a block type
+    int32_t  eigen_tries;        // sweeps the fast kernel spends looking for an eigenvector before it defers
     const int8_t   *leadtab;     // CANONICAL: [nlead][K] in device memory
     const uint64_t *wtab;        // CANONICAL: arrangements by remaining counts, base NR+1 digits
 };

@@ -500,7 +500,7 @@ struct FastLds {
 // problem scalars, read once per workgroup
 template <int DM>
 struct FastConst {
-    int D, K, NR, M, total, nslots, npaths, nsweeps, space, has_fixed, nwords, ndeps;
+    int D, K, NR, M, total, nslots, npaths, nsweeps, space, has_fixed, nwords, ndeps, eigen_tries;
     uint32_t step_q16;
     uint64_t seed;
     int ntd[DM];
@@ -583,18 +583,19 @@ __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds
 {
     const int V = C.nsweeps - 1;
     const uint32_t lane4 = (uint32_t)lane * 4u;
+    // byte offset (from the device records) of boundary value v: a device's free time or a carried token
+    auto value_offset = [&](uint32_t e) -> uint32_t {
+        const uint32_t slot = e & 63u;
+        return (e >> 6 & 1u) ? slot * (kWave * 8u) + (uint32_t)lane * 8u
+                             : (uint32_t)((char *)L.tok - (char *)L.drec) + (slot - (uint32_t)C.D) * (kWave * 4u) + lane4;
+    };
     uint32_t live = 0;                                    // per lane: which boundary values mean anything
-    uint32_t vaddr[VM];
 #pragma unroll
     for (int v = 0; v < VM; v++) {
-        vaddr[v] = lane4;
         if (v < V) {
             const uint32_t e = L.vtab[v];
             const bool on = (e >> 6 & 1u) ? (e >> 17 & 1u) != 0 : lead_code.get((e >> 7) & 31u) > ((e >> 13) & 15u);
             live |= (on ? 1u : 0u) << v;
-            const uint32_t slot = e & 63u;                // device value: in its record; token value: in the token array
-            vaddr[v] = (e >> 6 & 1u) ? (uint32_t)((char *)&L.drec[slot * kWave + lane].x - (char *)L.drec)
-                                     : (uint32_t)((char *)&L.tok[(slot - (uint32_t)C.D) * kWave + lane] - (char *)L.drec);
         }
     }
     reset_sweep_state<DM>(C, L, lane, lead_code);
@@ -603,8 +604,7 @@ __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds
     for (int v = 0; v < VM; v++) prev[v] = 0;
     int T = 0;
     bool done = !want;
-    constexpr int kTry = 6;
-    for (int j = 0; j < kTry; j++) {
+    for (int j = 0; j < C.eigen_tries; j++) {
         if (__ballot(!done) == 0) break;
         sweep_fast<DM>(C, L, prog, lane, lead_code, !done);
         nsweeps_used += done ? 0u : 1u;
@@ -613,7 +613,7 @@ __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds
 #pragma unroll
         for (int v = 0; v < VM; v++) {
             if (v < V) {
-                const uint32_t x = *(const uint32_t *)((const char *)L.drec + vaddr[v]);
+                const uint32_t x = *(const uint32_t *)((const char *)L.drec + value_offset(L.vtab[v]));
                 const uint32_t dv = x - prev[v];
                 prev[v] = x;
                 if (live >> v & 1u) {
@@ -639,7 +639,7 @@ __device__ __forceinline__ uint32_t even_bits(uint64_t x)
     return (uint32_t)x;
 }
 
-template <int DM, int VM>
+template <int DM, int VM, bool SAMPLED>
 __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<DM> &C, uint64_t idx, const FastLds &L, int lane,
                                              int &period, int &peak_max, bool valid, uint32_t &nsweeps_used)
 {
@@ -648,7 +648,7 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
     period = 0; peak_max = 0;
     const uint32_t NR = (uint32_t)C.NR;
     int status = kOk;
-    const bool sampled = C.space == kSampledStrict || C.space == kSampledRepair;
+    constexpr bool sampled = SAMPLED;      // kSampledStrict / kSampledRepair; else the exhaustive spaces
     Mu leads_type;                   // by type id (exhaustive spaces, fixed leads)
     leads_type.lo = 0; leads_type.hi = 0;
     uint32_t ka = 0, kb = 0;
@@ -845,8 +845,8 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
     return status;
 }
 
-template <int DM, int VM>
-__global__ __launch_bounds__(kWave, 3) void eval_fast_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
+template <int DM, int VM, bool SAMPLED>
+__global__ __launch_bounds__(kWave, SAMPLED ? 4 : 3) void eval_fast_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
                                                           BlockRec *__restrict__ recs, int32_t *__restrict__ code_out,
                                                           int32_t *__restrict__ peak_out, uint64_t *__restrict__ defer_list,
                                                           uint32_t *__restrict__ defer_count)
@@ -880,7 +880,7 @@ __global__ __launch_bounds__(kWave, 3) void eval_fast_kernel(const KParams *__re
     __syncthreads();
     FastConst<DM> C;
     C.D = P.D; C.K = P.K; C.NR = P.NR; C.M = P.M; C.total = P.total; C.nslots = P.nslots; C.npaths = P.npaths;
-    C.nsweeps = P.nsweeps; C.space = P.space; C.has_fixed = P.has_fixed; C.nwords = (P.total + 5) / 6; C.ndeps = P.K - P.npaths;
+    C.nsweeps = P.nsweeps; C.space = P.space; C.has_fixed = P.has_fixed; C.nwords = (P.total + 5) / 6; C.ndeps = P.K - P.npaths; C.eigen_tries = P.eigen_tries;
     C.step_q16 = P.step_q16; C.seed = P.seed;
 #pragma unroll
     for (int d = 0; d < DM; d++) { C.ntd[d] = P.ntd[d]; C.mpack[d] = P.mpack[d]; }
@@ -897,7 +897,7 @@ __global__ __launch_bounds__(kWave, 3) void eval_fast_kernel(const KParams *__re
         const uint64_t k = r * stride + (uint64_t)blockIdx.x * kWave + lane;
         const bool valid = k < count;
         int period, pk;
-        int status = evaluate_fast<DM, VM>(P, C, first + (valid ? k : 0), L, lane, period, pk, valid, nsw);
+        int status = evaluate_fast<DM, VM, SAMPLED>(P, C, first + (valid ? k : 0), L, lane, period, pk, valid, nsw);
         if (!valid) continue;
         if (status == kDeferred) {
             const uint32_t at = atomicAdd(defer_count, 1u);
@@ -1082,9 +1082,15 @@ static fast_fn pick_fast(const KParams &kp)
 {
     const int V = kp.nsweeps - 1;
     if (!kp.fast_ok) return nullptr;
-    if (kp.D <= 2) return V <= 4 ? eval_fast_kernel<2, 4> : eval_fast_kernel<2, 24>;
-    if (kp.D <= 4) return V <= 8 ? eval_fast_kernel<4, 8> : eval_fast_kernel<4, 24>;
-    return V <= 16 ? eval_fast_kernel<8, 16> : eval_fast_kernel<8, 24>;
+    const bool sampled = kp.space == kSampledStrict || kp.space == kSampledRepair;
+    if (sampled) {
+        if (kp.D <= 2) return V <= 4 ? eval_fast_kernel<2, 4, true> : eval_fast_kernel<2, 24, true>;
+        if (kp.D <= 4) return V <= 8 ? eval_fast_kernel<4, 8, true> : eval_fast_kernel<4, 24, true>;
+        return V <= 16 ? eval_fast_kernel<8, 16, true> : eval_fast_kernel<8, 24, true>;
+    }
+    if (kp.D <= 2) return V <= 4 ? eval_fast_kernel<2, 4, false> : eval_fast_kernel<2, 24, false>;
+    if (kp.D <= 4) return V <= 8 ? eval_fast_kernel<4, 8, false> : eval_fast_kernel<4, 24, false>;
+    return V <= 16 ? eval_fast_kernel<8, 16, false> : eval_fast_kernel<8, 24, false>;
 }
 
 static size_t general_lds_bytes(const KParams &kp)

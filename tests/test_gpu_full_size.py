@@ -107,3 +107,43 @@ def test_fast_and_general_kernels_agree(gpu, monkeypatch):
         assert b["n_window_sweeps"] == 0 and (a["n_window_sweeps"] > 0 or a["n_feasible"] == 0)
         for key in ("period", "index", "peak", "n_feasible", "n_reject", "n_evaluated"):
             assert a[key] == b[key], (cfg, key)
+
+
+def test_deferred_candidates_take_the_general_kernel(gpu, monkeypatch):
+    """A candidate whose boundary vector is no eigenvector yet after the allowed sweeps is handed to
+    the general kernel through a list in the workspace.  With the allowance cut to 2 sweeps a few
+    percent of the feasible candidates go that way, with 1 all of them; results must not change."""
+    from oracle import Oracle
+    for tries, cfg, n in ((2, 5, 20000), (1, 3, 30000), (0, 1, 576), (2, 2, 300000)):
+        prob = W.CONFIGS[cfg]()
+        monkeypatch.setenv("TESSEL_EIGEN_TRIES", str(tries))
+        g = gpu.Problem(prob)
+        monkeypatch.delenv("TESSEL_EIGEN_TRIES")
+        first = 4321 if cfg in (3, 5) else 0
+        code, peak = g.score_candidates(first, n)
+        want_code, want_peak = Oracle(prob).score_range(first, n)
+        assert (code.cpu().numpy() == want_code).all() and (peak.cpu().numpy() == want_peak).all(), (tries, cfg)
+        for pieces in ([(first, n)], [(first, n // 2), (first + n // 2, n - n // 2)]):
+            g.reset()
+            for a, k in pieces:
+                g.eval_candidates(a, k)
+            got = g.best()
+            want = Oracle(prob).sweep(first, n)
+            assert got["n_evaluated"] == n and got["n_feasible"] == want["n_feasible"]
+            assert (got["period"], got["index"], got["peak"]) == (want["period"], want["index"], want["peak"])
+            assert got["n_reject"][1:] == want["n_reject"][1:]
+
+
+def test_deferred_list_overflow_is_reported(gpu, monkeypatch):
+    """More deferred candidates in one launch than the list holds must not be dropped silently."""
+    prob = dict(W.config3(), M=100)                   # every candidate feasible
+    monkeypatch.setenv("TESSEL_EIGEN_TRIES", "0")     # and every one deferred
+    g = gpu.Problem(prob)
+    monkeypatch.delenv("TESSEL_EIGEN_TRIES")
+    g.eval_candidates(0, 1 << 17)                     # list capacity is 2^16
+    with pytest.raises(gpu.TesselError) as e:
+        g.best()
+    assert e.value.code == -5
+    g.reset()
+    g.eval_candidates(0, 1 << 15)
+    assert g.best()["n_evaluated"] == 1 << 15
