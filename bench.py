@@ -19,8 +19,8 @@ if ROOT not in sys.path:
 
 PEAK_INT32_OPS = 256 * 64 * 2.4e9 / 1e12      # T int32 lane-ops/s: 256 CUs x 64 lanes x 2.4 GHz, full-rate VALU ops
 # HBM bytes of one launch of 2^24 candidates, from the FETCH_SIZE / WRITE_SIZE passes in
-# profiles/eval_fast_kernel_cfg5_counters.md (253.25 KiB x 2.0 + 2176 KiB x 1.0, copy-calibrated)
-TRAFFIC_BYTES_PER_2P24_LAUNCH = int((253.25 * 2.0 + 2176 * 1.0) * 1024)
+# profiles/eval_fast_kernel_cfg5_counters.md (5239.125 KiB x 2.0 + 12549.125 KiB x 1.0, copy-calibrated)
+TRAFFIC_BYTES_PER_2P24_LAUNCH = int((5239.125 * 2.0 + 12549.125 * 1.0) * 1024)
 
 
 def algorithmic_ops(prob, n_candidates, n_sweeps):
@@ -118,7 +118,7 @@ def main():
         "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_INT32_OPS, "unit": "Tint32op/s",
                      "frac": achieved / PEAK_INT32_OPS,
                      "traffic": TRAFFIC_BYTES_PER_2P24_LAUNCH if chunk == 1 << 24 else None,
-                     "kernel": "eval_fast_kernel<8, 16>", "avg_launch_ms": avg_launch_s * 1e3,
+                     "kernel": "eval_fast_kernel<8, 16, true>", "avg_launch_ms": avg_launch_s * 1e3,
                      "algorithmic_ops_per_candidate": ops_per_launch / chunk,
                      "window_sweeps_per_candidate": sweeps_per_cand},
     }
