@@ -268,7 +268,7 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
             path++;
         }
         kp.fast_ok = ok;
-        kp.eigen_tries = 6;
+        kp.eigen_tries = kFirstPassTries;
         if (const char *env = getenv("TESSEL_EIGEN_TRIES")) {      // test knob: force candidates onto the deferred path
             int v = atoi(env);
             if (v >= 0 && v <= 64) kp.eigen_tries = v;
@@ -351,7 +351,7 @@ static int ensure_device(tessel_problem *p)
 static size_t workspace_need(const tessel_problem *p, int num_cus)
 {
     LaunchShape s = eval_launch_shape(p->kp, num_cus);
-    return kWsBlockRecOff + block_rec_bytes(s.blocks + kDeferBlocks) + 256;
+    return kWsBlockRecOff + block_rec_bytes(2 * s.blocks + kDeferBlocks) + 256;
 }
 
 extern "C" int tessel_workspace_bytes(const tessel_problem *p, size_t *bytes)

@@ -68,7 +68,7 @@ struct KParams {
     uint32_t dep_bit[kMaxK];     // by dependency number: its step bit, 0 if both ends sit on the same device set
     uint32_t mpack[kMaxD];       // memory deltas of the device's 4 types, 8 bits each (signed)
     uint32_t valid_codes;        // bit c set <=> code c names a block type
-    int32_t  eigen_tries;        // sweeps the fast kernel spends looking for an eigenvector before it defers
+    int32_t  eigen_tries;        // sweeps of the first fast pass before a candidate is retried (test knob)
     const int8_t   *leadtab;     // CANONICAL: [nlead][K] in device memory
     const uint64_t *wtab;        // CANONICAL: arrangements by remaining counts, base NR+1 digits
 };
@@ -81,8 +81,10 @@ struct DevResult {
     uint64_t n_evaluated;
     uint64_t n_status[kNumStatus];   // [kOk] = feasible
     uint64_t n_sweeps;               // window sweeps spent on period computations (fast kernel)
-    uint32_t n_deferred;             // candidates the fast kernel handed to the general kernel so far
-    uint32_t overflow;               // the deferred list was too small at some point: results are incomplete
+    uint32_t n_retried;              // candidates that needed the second fast pass (more sweeps) so far
+    uint32_t n_deferred;             // candidates handed to the general kernel so far
+    uint32_t overflow;               // a list was too small at some point: results are incomplete
+    uint32_t retry_count;            // entries of the retry list of the launch in flight
     uint32_t defer_count;            // entries of the deferred list of the launch in flight
     uint32_t pad2;
 };
@@ -101,10 +103,14 @@ constexpr size_t kWsDetailOff = 256;
 constexpr size_t kWsParamsOff = 2048;          // KParams of the bound problem
 constexpr size_t kWsTablesOff = 8192;          // lead table, arrangement table
 constexpr size_t kWsTablesMax = 1 << 20;
-constexpr size_t kWsListOff = kWsTablesOff + kWsTablesMax;     // candidates deferred to the general kernel
+constexpr size_t kWsRetryOff = kWsTablesOff + kWsTablesMax;    // candidates that get a second fast pass with more sweeps
+constexpr uint32_t kWsRetryCap = 1u << 21;
+constexpr size_t kWsListOff = kWsRetryOff + (size_t)kWsRetryCap * 8;   // candidates deferred to the general kernel
 constexpr uint32_t kWsListCap = 1u << 16;
 constexpr size_t kWsBlockRecOff = kWsListOff + (size_t)kWsListCap * 8;
 constexpr int kDeferBlocks = 64;                                // grid of the deferred pass
+constexpr int kFirstPassTries = 3;                              // sweeps before a candidate goes to the retry list
+constexpr int kRetryTries = 8;                                  // ... and before the general kernel gets it
 
 static_assert(sizeof(KParams) <= kWsTablesOff - kWsParamsOff, "parameter block must fit its workspace slot");
 static_assert(sizeof(DevDetail) <= kWsParamsOff - kWsDetailOff, "detail record must fit its workspace slot");

@@ -848,9 +848,13 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
 template <int DM, int VM, bool SAMPLED>
 __global__ __launch_bounds__(kWave, SAMPLED ? 4 : 3) void eval_fast_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
                                                           BlockRec *__restrict__ recs, int32_t *__restrict__ code_out,
-                                                          int32_t *__restrict__ peak_out, uint64_t *__restrict__ defer_list,
-                                                          uint32_t *__restrict__ defer_count)
+                                                          int32_t *__restrict__ peak_out, const uint64_t *__restrict__ in_list,
+                                                          const uint32_t *__restrict__ in_count, uint32_t in_cap, int tries,
+                                                          uint64_t *__restrict__ out_list, uint32_t *__restrict__ out_count,
+                                                          uint32_t out_cap, uint32_t *__restrict__ overflow)
 {
+    // with an input list: score the listed candidates (all inside [first, first + count)) instead of the range
+    if (in_list) count = min(*in_count, in_cap);
     extern __shared__ uint32_t lds[];
     const KParams &P = *Pp;
     const int lane = threadIdx.x;
@@ -880,7 +884,7 @@ __global__ __launch_bounds__(kWave, SAMPLED ? 4 : 3) void eval_fast_kernel(const
     __syncthreads();
     FastConst<DM> C;
     C.D = P.D; C.K = P.K; C.NR = P.NR; C.M = P.M; C.total = P.total; C.nslots = P.nslots; C.npaths = P.npaths;
-    C.nsweeps = P.nsweeps; C.space = P.space; C.has_fixed = P.has_fixed; C.nwords = (P.total + 5) / 6; C.ndeps = P.K - P.npaths; C.eigen_tries = P.eigen_tries;
+    C.nsweeps = P.nsweeps; C.space = P.space; C.has_fixed = P.has_fixed; C.nwords = (P.total + 5) / 6; C.ndeps = P.K - P.npaths; C.eigen_tries = tries;
     C.step_q16 = P.step_q16; C.seed = P.seed;
 #pragma unroll
     for (int d = 0; d < DM; d++) { C.ntd[d] = P.ntd[d]; C.mpack[d] = P.mpack[d]; }
@@ -894,20 +898,23 @@ __global__ __launch_bounds__(kWave, SAMPLED ? 4 : 3) void eval_fast_kernel(const
     const uint64_t stride = (uint64_t)gridDim.x * kWave;
     const uint64_t rounds = (count + stride - 1) / stride;          // the same trip count for every lane of the grid
     for (uint64_t r = 0; r < rounds; r++) {
-        const uint64_t k = r * stride + (uint64_t)blockIdx.x * kWave + lane;
-        const bool valid = k < count;
+        const uint64_t kk = r * stride + (uint64_t)blockIdx.x * kWave + lane;
+        const bool valid = kk < count;
+        const uint64_t idx = !valid ? first : in_list ? in_list[kk] : first + kk;
+        const uint64_t k = idx - first;
         int period, pk;
-        int status = evaluate_fast<DM, VM, SAMPLED>(P, C, first + (valid ? k : 0), L, lane, period, pk, valid, nsw);
+        int status = evaluate_fast<DM, VM, SAMPLED>(P, C, idx, L, lane, period, pk, valid, nsw);
         if (!valid) continue;
         if (status == kDeferred) {
-            const uint32_t at = atomicAdd(defer_count, 1u);
-            if (at < kWsListCap) defer_list[at] = first + k;
+            // no eigenvector within the sweeps of this pass: the next pass scores it
+            const uint32_t at = atomicAdd(out_count, 1u);
+            if (at < out_cap) out_list[at] = idx; else *overflow = 1u;
             continue;
         }
         nev++;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) cnt[s] += status == s;
-        if (status == kOk && period < best) { best = period; best_idx = first + k; }
+        if (status == kOk && key_less(period, idx, best, best_idx)) { best = period; best_idx = idx; }
         if (code_out) code_out[k] = status == kOk ? period : -status;
         if (peak_out) peak_out[k] = (status == kOk || status == kMem) ? pk : 0;
     }
@@ -1007,7 +1014,7 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
 }
 
 // merges the block records of one launch into the running best (one wave)
-__global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int nrecs, DevResult *res, uint32_t *defer_count)
+__global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int nrecs, DevResult *res)
 {
     const int lane = threadIdx.x;
     int best = INT_MAX;
@@ -1040,9 +1047,10 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
     }
     if (lane == 0) {
         if (key_less(best, best_idx, res->period, res->index)) { res->period = best; res->index = best_idx; }
-        if (*defer_count > kWsListCap) res->overflow = 1;
-        res->n_deferred += min(*defer_count, kWsListCap);
-        *defer_count = 0;      // the deferred pass of this launch has run (stream order)
+        // the passes over both lists have run (stream order)
+        res->n_retried += min(res->retry_count, kWsRetryCap);
+        res->n_deferred += min(res->defer_count, kWsListCap);
+        res->retry_count = 0; res->defer_count = 0;
         res->n_evaluated += nev;
         res->n_sweeps += nsw;
 #pragma unroll
@@ -1051,13 +1059,16 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
 }
 
 // only the counter of the deferred list (after a per-candidate scoring call)
-__global__ void clear_defer_kernel(uint32_t *defer_count) { if (threadIdx.x == 0 && blockIdx.x == 0) *defer_count = 0; }
+__global__ void clear_defer_kernel(DevResult *res)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) { res->retry_count = 0; res->defer_count = 0; }
+}
 
 __global__ void reset_kernel(DevResult *res)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         res->period = INT_MAX; res->pad = 0; res->index = ~0ull; res->n_evaluated = 0; res->n_sweeps = 0;
-        res->n_deferred = 0; res->overflow = 0; res->defer_count = 0;
+        res->n_retried = 0; res->n_deferred = 0; res->overflow = 0; res->retry_count = 0; res->defer_count = 0;
         for (int s = 0; s < kNumStatus; s++) res->n_status[s] = 0;
     }
 }
@@ -1065,7 +1076,8 @@ __global__ void reset_kernel(DevResult *res)
 // ------------------------------------------------------------------ launchers
 typedef void (*eval_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, DevDetail *, const uint64_t *,
                         const uint32_t *);
-typedef void (*fast_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, uint64_t *, uint32_t *);
+typedef void (*fast_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, const uint64_t *, const uint32_t *,
+                        uint32_t, int, uint64_t *, uint32_t *, uint32_t, uint32_t *);
 
 static eval_fn pick_kernel(const KParams &kp)
 {
@@ -1142,15 +1154,16 @@ static int launch_general(const KParams &kp, const KParams *kp_dev, uint64_t fir
     return (int)hipGetLastError();
 }
 
-// Scores [first, first+count): the fast kernel where the problem allows it, then the general kernel over the few
-// candidates the fast kernel deferred; else the general kernel alone.  Returns the number of block records written
-// (recs may be null: per-candidate outputs only) or a negative HIP error.
+// Scores [first, first+count).  Where the problem allows it: the fast kernel with a short eigenvector search, the fast
+// kernel again with a longer one over the candidates that did not converge, then the general kernel over what is left
+// (next to nothing).  Otherwise the general kernel alone.  Returns the number of block records written (recs may be
+// null: per-candidate outputs only) or a negative HIP error.
 static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, BlockRec *recs, int32_t *code,
                        int32_t *peak, bool general, hipStream_t st)
 {
     const KParams *kp_dev = (const KParams *)((char *)ws + kWsParamsOff);
-    uint64_t *list = (uint64_t *)((char *)ws + kWsListOff);
-    uint32_t *list_count = &((DevResult *)((char *)ws + kWsResultOff))->defer_count;
+    DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
+    uint64_t *retry = (uint64_t *)((char *)ws + kWsRetryOff), *list = (uint64_t *)((char *)ws + kWsListOff);
     LaunchShape s = eval_launch_shape(kp, num_cus);
     uint64_t need = (count + kWave - 1) / kWave;
     const int blocks = need < (uint64_t)s.blocks ? (int)need : s.blocks;
@@ -1160,11 +1173,21 @@ static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *
         int rc = launch_general(kp, kp_dev, first, count, blocks, recs, code, peak, nullptr, nullptr, nullptr, st);
         return rc ? -rc : blocks;
     }
-    hipLaunchKernelGGL(ff, dim3(blocks), dim3(kWave), fast_lds_bytes(kp), st, kp_dev, first, count, recs, code, peak, list, list_count);
+    const size_t lds = fast_lds_bytes(kp);
+    hipLaunchKernelGGL(ff, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, (const uint64_t *)nullptr,
+                       (const uint32_t *)nullptr, 0u, kp.eigen_tries, retry, &res->retry_count, kWsRetryCap, &res->overflow);
     int rc = (int)hipGetLastError();
     if (rc) return -rc;
-    rc = launch_general(kp, kp_dev, first, count, kDeferBlocks, recs ? recs + blocks : nullptr, code, peak, nullptr, list, list_count, st);
-    return rc ? -rc : blocks + kDeferBlocks;
+    // the retry list holds a few percent of the range at most; a quarter of the grid is plenty
+    const int blocks2 = blocks >= 4 ? blocks / 4 : blocks;
+    hipLaunchKernelGGL(ff, dim3(blocks2), dim3(kWave), lds, st, kp_dev, first, count, recs ? recs + blocks : nullptr, code, peak,
+                       (const uint64_t *)retry, (const uint32_t *)&res->retry_count, kWsRetryCap, kRetryTries, list,
+                       &res->defer_count, kWsListCap, &res->overflow);
+    rc = (int)hipGetLastError();
+    if (rc) return -rc;
+    rc = launch_general(kp, kp_dev, first, count, kDeferBlocks, recs ? recs + blocks + blocks2 : nullptr, code, peak, nullptr, list,
+                        &res->defer_count, st);
+    return rc ? -rc : blocks + blocks2 + kDeferBlocks;
 }
 
 int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream)
@@ -1175,7 +1198,7 @@ int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int
     int n = launch_pass(kp, first, count, ws, num_cus, recs, nullptr, nullptr, false, st);
     if (n < 0) return -n;
     if (n == 0) return 0;
-    hipLaunchKernelGGL(merge_kernel, dim3(1), dim3(kWave), 0, st, recs, n, res, &res->defer_count);
+    hipLaunchKernelGGL(merge_kernel, dim3(1), dim3(kWave), 0, st, recs, n, res);
     return (int)hipGetLastError();
 }
 
@@ -1186,7 +1209,7 @@ int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *cod
     DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
     int n = launch_pass(kp, first, count, ws, num_cus, nullptr, code, peak, general, st);
     if (n < 0) return -n;
-    hipLaunchKernelGGL(clear_defer_kernel, dim3(1), dim3(1), 0, st, &res->defer_count);
+    hipLaunchKernelGGL(clear_defer_kernel, dim3(1), dim3(1), 0, st, res);
     return (int)hipGetLastError();
 }
 

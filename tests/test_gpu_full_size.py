@@ -110,11 +110,12 @@ def test_fast_and_general_kernels_agree(gpu, monkeypatch):
 
 
 def test_deferred_candidates_take_the_general_kernel(gpu, monkeypatch):
-    """A candidate whose boundary vector is no eigenvector yet after the allowed sweeps is handed to
-    the general kernel through a list in the workspace.  With the allowance cut to 2 sweeps a few
-    percent of the feasible candidates go that way, with 1 all of them; results must not change."""
+    """A candidate whose boundary vector is no eigenvector yet after the sweeps of the first pass goes
+    through a list in the workspace to a second pass with more sweeps (and from there, if need be, to
+    the general kernel).  With the first pass cut to 1 or 0 sweeps all feasible candidates go that
+    way; results must not change."""
     from oracle import Oracle
-    for tries, cfg, n in ((2, 5, 20000), (1, 3, 30000), (0, 1, 576), (2, 2, 300000)):
+    for tries, cfg, n in ((2, 5, 20000), (1, 3, 30000), (0, 1, 576), (1, 2, 300000), (0, 5, 5000)):
         prob = W.CONFIGS[cfg]()
         monkeypatch.setenv("TESSEL_EIGEN_TRIES", str(tries))
         g = gpu.Problem(prob)
@@ -140,7 +141,7 @@ def test_deferred_list_overflow_is_reported(gpu, monkeypatch):
     monkeypatch.setenv("TESSEL_EIGEN_TRIES", "0")     # and every one deferred
     g = gpu.Problem(prob)
     monkeypatch.delenv("TESSEL_EIGEN_TRIES")
-    g.eval_candidates(0, 1 << 17)                     # list capacity is 2^16
+    g.eval_candidates(0, 1 << 22)                     # the retry list holds 2^21
     with pytest.raises(gpu.TesselError) as e:
         g.best()
     assert e.value.code == -5
