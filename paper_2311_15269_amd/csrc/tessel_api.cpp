@@ -242,7 +242,6 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
             kp.chain_tab[k] = (uint32_t)home[i] | (su << 6) | ((uint32_t)(kp.succ[i] < 0 ? 0 : kp.edge_out[i]) << 12) |
                               ((uint32_t)(kp.succ[i] >= 0 && kp.cross_out[i]) << 19) | ((uint32_t)(kp.pred[i] < 0) << 20) |
                               ((uint32_t)i << 21);
-            kp.valid_codes |= 1u << home[i];
         }
         {
             // chain_tab lists every chain from its last block to its first, one chain after the other

@@ -67,7 +67,6 @@ struct KParams {
     uint32_t pred_bit[kMaxK];    // by code: step bit of the dependency from its producer (0 = first of its chain)
     uint32_t dep_bit[kMaxK];     // by dependency number: its step bit, 0 if both ends sit on the same device set
     uint32_t mpack[kMaxD];       // memory deltas of the device's 4 types, 8 bits each (signed)
-    uint32_t valid_codes;        // bit c set <=> code c names a block type
     int32_t  eigen_tries;        // sweeps of the first fast pass before a candidate is retried (test knob)
     const int8_t   *leadtab;     // CANONICAL: [nlead][K] in device memory
     const uint64_t *wtab;        // CANONICAL: arrangements by remaining counts, base NR+1 digits

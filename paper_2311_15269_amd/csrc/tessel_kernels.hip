@@ -4,17 +4,21 @@
 //   decode   index -> lead vector (n_i of Eq. 3) + per-device block orders
 //   build    walk the orders in an executable (topological) sequence, detect orders that
 //            can never run, repair them in the REPAIR space, track the per-device memory
-//            prefix (Eq. 1 [2]) and leave a compact "program" of the window in LDS
+//            prefix (Eq. 1 [2]) and leave a compact "program" of the window
 //   period   the repetend time t_R of Eq. 4 (with compaction of neighbouring repetends):
 //            the least period of the rigidly repeated window.  The window is a max-plus
 //            linear map on (device free times, end times of the micro-batches that are in
-//            flight at the window boundary); its growth rate is the maximum cycle ratio,
-//            obtained exactly from Karp's formula after V+1 sweeps of the window
+//            flight at the window boundary); its growth rate is the maximum cycle ratio
 //   argmin   (period, index) lexicographic, lane -> wave -> block record -> grid merge
 //
-// State that is indexed per lane at run time (device free times, micro-batch tokens, the
-// program) lives in LDS laid out [slot][lane], which is bank-conflict free for any
-// per-lane slot; everything else is in VGPRs.
+// Two kernels compute the same thing:
+//   eval_kernel       general: multi-device blocks, cyclic device scan, 16-bit program in LDS,
+//                     Karp's formula over V+1 sweeps; also decodes the best candidate
+//   eval_fast_kernel  single-device blocks: bit-mask build, program words in VGPRs, eigenvector
+//                     test after every sweep; what it cannot finish goes to the general kernel
+//
+// State that is indexed per lane at run time (device records, micro-batch tokens) lives in
+// LDS laid out [slot][lane], which is bank-conflict free for any per-lane slot.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <limits.h>
@@ -104,7 +108,7 @@ __device__ __forceinline__ uint32_t find_first(uint64_t x, uint32_t len, uint32_
     return hit ? (uint32_t)__builtin_ctzll(hit) >> 1 : 64u;
 }
 
-// ------------------------------------------------------------------ one window sweep
+// ------------------------------------------------------------------ one window sweep (general kernel)
 // Program entry: bits 0-4 home code of the block type (device*4 + symbol), bits 5-10 token
 // slot.  s = max(free time of its device(s), end of the micro-batch's previous block);
 // both become s + t.  A chain's first block reads a token slot nobody has written: 0.
@@ -153,7 +157,7 @@ __device__ __forceinline__ int reduced_slot(const KParams &P, int v)
 // that one sweep applies to the V = D + npaths*N_R boundary values (plus the constant 0 that
 // keeps start times non-negative).  Karp: with x(j) the vector after j+1 sweeps from 0 and
 // n = V+1 sweeps in total, lambda = max_v min_{j<n-1} (x_v(n-1) - x_v(j)) / (n-1-j).
-// Two passes over the same sweeps so that no history has to be stored.
+// Two passes over the same sweeps so that no history has to be stored.  (General kernel.)
 template <int VM, bool TP>
 __device__ __forceinline__ int least_period(const KParams &P, const uint16_t *prog, uint32_t *state, const int32_t *t_tab,
                             const uint32_t *mask_tab)
