@@ -101,6 +101,18 @@ def main():
     ops_per_launch = algorithmic_ops(prob, chunk, sweeps_per_cand * chunk)
     achieved = ops_per_launch / avg_launch_s / 1e12
 
+    # practical ceiling: independent full-rate integer adds/maxes on every lane of the chip
+    from paper_2311_15269_amd.binding import alu_probe
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    probe_ops, probe_out = alu_probe(n_cu * 16, 256)
+    torch.cuda.synchronize()
+    pa, pb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    pa.record()
+    probe_ops, _ = alu_probe(n_cu * 16, 20000, probe_out)
+    pb.record()
+    torch.cuda.synchronize()
+    peak_measured = probe_ops / (pa.elapsed_time(pb) / 1e3) / 1e12
+
     out = {
         "metric": "repetend candidates evaluated/sec + % peak VALU int ops, 8-dev V-shape",
         "value": n_cand * args.steps / dt,
@@ -117,6 +129,7 @@ def main():
                    "makespan_%d_microbatches" % N: sched["makespan"], "windows": sched["num_windows"]},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_INT32_OPS, "unit": "Tint32op/s",
                      "frac": achieved / PEAK_INT32_OPS,
+                     "peak_measured": peak_measured, "frac_of_measured": achieved / peak_measured,
                      "traffic": TRAFFIC_BYTES_PER_2P24_LAUNCH if chunk == 1 << 24 else None,
                      "kernel": "eval_fast_kernel<8, 16, true>", "avg_launch_ms": avg_launch_s * 1e3,
                      "algorithmic_ops_per_candidate": ops_per_launch / chunk,

@@ -181,6 +181,16 @@ int  tessel_reset(tessel_problem *p);
  * capacity too small), NO_SCHEDULE. */
 int  tessel_complete_schedule(tessel_problem *p, tessel_schedule *out);
 
+/* Measurement aid, not part of the method: launches a kernel of `blocks` x 256 threads in which
+ * every lane runs `rounds` rounds of 32 independent full-rate 32-bit integer VALU operations
+ * (add, unsigned max), asynchronously on `hip_stream`.  *lane_ops (host, may be NULL) receives the
+ * number of lane operations of the launch; divided by the launch's duration it is the integer
+ * VALU rate the chip sustains in practice, the second denominator beside the published peak.
+ * out_dev: device buffer of blocks*256 uint32 (overwritten).  Errors: INVALID_ARG, WORKSPACE
+ * (out_bytes too small), HIP. */
+int  tessel_alu_probe(int blocks, int rounds, uint32_t *out_dev, size_t out_bytes, void *hip_stream,
+                      uint64_t *lane_ops);
+
 const char *tessel_strerror(int code);
 int  tessel_last_hip_error(const tessel_problem *p);   /* hipError_t of the last failure, 0 if none */
 

@@ -22,7 +22,7 @@ E_NO_FEASIBLE = -7
 EXPORTS = (
     "tessel_problem_create", "tessel_problem_destroy", "tessel_candidate_count", "tessel_workspace_bytes",
     "tessel_eval_candidates", "tessel_score_candidates", "tessel_best", "tessel_best_candidate", "tessel_reset",
-    "tessel_complete_schedule", "tessel_strerror", "tessel_last_hip_error",
+    "tessel_complete_schedule", "tessel_alu_probe", "tessel_strerror", "tessel_last_hip_error",
 )
 
 
@@ -77,11 +77,23 @@ def load_library():
         lib.tessel_best_candidate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.tessel_reset.argtypes = [C.c_void_p]
         lib.tessel_complete_schedule.argtypes = [C.c_void_p, C.POINTER(Schedule)]
+        lib.tessel_alu_probe.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_uint64)]
         lib.tessel_strerror.argtypes = [C.c_int]
         lib.tessel_strerror.restype = C.c_char_p
         lib.tessel_last_hip_error.argtypes = [C.c_void_p]
         _lib = lib
     return _lib
+
+
+def alu_probe(blocks, rounds, out=None):
+    """tessel_alu_probe on torch's current stream; returns (lane operations of the launch, out tensor)."""
+    import torch
+    if out is None:
+        out = torch.empty(blocks * 256, dtype=torch.int32, device="cuda")
+    ops = C.c_uint64(0)
+    _check(load_library().tessel_alu_probe(blocks, rounds, out.data_ptr(), out.numel() * 4,
+                                           torch.cuda.current_stream().cuda_stream, C.byref(ops)))
+    return int(ops.value), out
 
 
 def _check(rc, allow=()):

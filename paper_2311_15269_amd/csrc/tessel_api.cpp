@@ -50,7 +50,7 @@ extern "C" const char *tessel_strerror(int code)
     case TESSEL_E_BAD_DEP: return "dependency graph of a micro-batch has a cycle";
     case TESSEL_E_UNBALANCED_MEMORY: return "memory deltas on a device do not sum to zero";
     case TESSEL_E_TOOBIG: return "count or time bound too large";
-    case TESSEL_E_WORKSPACE: return "workspace missing, misaligned or too small";
+    case TESSEL_E_WORKSPACE: return "workspace missing, misaligned or too small, or a launch overflowed its retry list (submit smaller ranges)";
     case TESSEL_E_HIP: return "HIP runtime error";
     case TESSEL_E_NO_FEASIBLE: return "no feasible candidate scored";
     case TESSEL_E_RANGE: return "range outside the candidate space or too few micro-batches";
@@ -427,6 +427,15 @@ extern "C" int tessel_score_candidates(tessel_problem *p, uint64_t first, uint64
     if (count == 0) return TESSEL_OK;
     int e = launch_score(p->kp, first, count, code_dev, peak_dev, workspace_dev, p->num_cus, p->force_general, st);
     return e ? hip_fail(p, e) : TESSEL_OK;
+}
+
+extern "C" int tessel_alu_probe(int blocks, int rounds, uint32_t *out_dev, size_t out_bytes, void *hip_stream,
+                                uint64_t *lane_ops)
+{
+    if (blocks < 1 || blocks > (1 << 20) || rounds < 1 || rounds > (1 << 24) || !out_dev) return TESSEL_E_INVALID_ARG;
+    if (out_bytes < (size_t)blocks * kProbeThreads * sizeof(uint32_t)) return TESSEL_E_WORKSPACE;
+    if (lane_ops) *lane_ops = (uint64_t)blocks * kProbeThreads * (uint64_t)rounds * kProbeLaneOpsPerRound;
+    return launch_alu_probe(out_dev, blocks, rounds, hip_stream) ? TESSEL_E_HIP : TESSEL_OK;
 }
 
 extern "C" int tessel_reset(tessel_problem *p)

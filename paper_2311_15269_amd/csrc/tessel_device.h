@@ -123,5 +123,8 @@ int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *cod
                  bool general, void *stream);
 int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream);
 int launch_reset(void *ws, void *stream);
+int launch_alu_probe(uint32_t *out, int blocks, int rounds, void *stream);
+constexpr int kProbeThreads = 256;
+constexpr int kProbeLaneOpsPerRound = 32;
 
 }  // namespace tessel

@@ -1232,4 +1232,32 @@ int launch_reset(void *ws, void *stream)
 
 size_t block_rec_bytes(int blocks) { return (size_t)blocks * sizeof(BlockRec); }
 
+// ------------------------------------------------------------------ achievable VALU rate
+// Sixteen independent accumulators per lane, one add and one unsigned max each per round: 32
+// full-rate integer VALU instructions per round with no dependency closer than 16 instructions.
+// What this kernel sustains is the practical ceiling the scoring kernels are compared with.
+constexpr int kProbeAcc = 16;
+constexpr int kProbeOpsPerRound = 2 * kProbeAcc;
+
+__global__ __launch_bounds__(256) void alu_probe_kernel(uint32_t *out, int rounds, uint32_t inc, uint32_t floor_)
+{
+    uint32_t a[kProbeAcc];
+#pragma unroll
+    for (int j = 0; j < kProbeAcc; j++) a[j] = threadIdx.x * 2654435761u + j;
+    for (int r = 0; r < rounds; r++) {
+#pragma unroll
+        for (int j = 0; j < kProbeAcc; j++) a[j] = max(a[j] + inc, floor_);
+    }
+    uint32_t x = 0;
+#pragma unroll
+    for (int j = 0; j < kProbeAcc; j++) x ^= a[j];
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = x;
+}
+
+int launch_alu_probe(uint32_t *out, int blocks, int rounds, void *stream)
+{
+    hipLaunchKernelGGL(alu_probe_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, out, rounds, 0x9E3779B9u, 12345u);
+    return (int)hipGetLastError();
+}
+
 }  // namespace tessel

@@ -50,3 +50,13 @@ def test_strerror_covers_all_codes():
     lib = binding.load_library()
     texts = {lib.tessel_strerror(c).decode() for c in range(0, -11, -1)}
     assert len(texts) == 11 and "unknown error" not in texts
+
+
+def test_alu_probe_validates_its_arguments_on_the_host():
+    lib = binding.load_library()
+    import ctypes as C
+    ops = C.c_uint64(0)
+    assert lib.tessel_alu_probe(0, 10, 1, 1 << 20, None, C.byref(ops)) == -1
+    assert lib.tessel_alu_probe(4, 0, 1, 1 << 20, None, C.byref(ops)) == -1
+    assert lib.tessel_alu_probe(4, 10, None, 1 << 20, None, C.byref(ops)) == -1
+    assert lib.tessel_alu_probe(4, 10, 256, 4 * 256 * 4 - 1, None, C.byref(ops)) == -5

@@ -259,3 +259,23 @@ def test_statuses_all_occur_somewhere(gpu):
         code = code.cpu().numpy()
         seen |= {0 if c > 0 else -int(c) for c in np.unique(code)}
     assert seen == {0, 1, 2, 3, 4, 5}
+
+
+def test_alu_probe_computes_what_it_counts():
+    """The rate probe really executes rounds x 16 x (add, unsigned max) per lane: its output is
+    the xor of 16 accumulators that numpy reproduces."""
+    import torch
+    from paper_2311_15269_amd.binding import alu_probe
+    rounds = 37
+    ops, out = alu_probe(3, rounds)
+    torch.cuda.synchronize()
+    assert ops == 3 * 256 * rounds * 32
+    tid = np.tile(np.arange(256, dtype=np.uint64), 3)
+    want = np.zeros(3 * 256, dtype=np.uint64)
+    for j in range(16):
+        a = (tid * 2654435761 + j) & 0xFFFFFFFF
+        for _ in range(rounds):
+            a = np.maximum((a + 0x9E3779B9) & 0xFFFFFFFF, 12345)
+        want ^= a
+    got = out.cpu().numpy().view(np.uint32).astype(np.uint64)
+    assert np.array_equal(got, want)
