@@ -181,6 +181,49 @@ int  tessel_reset(tessel_problem *p);
  * capacity too small), NO_SCHEDULE. */
 int  tessel_complete_schedule(tessel_problem *p, tessel_schedule *out);
 
+/* ---- the whole search of Alg. 1 (Sec. IV-D): all window sizes ---------------------------
+ * In: which window sizes and how many candidates of each; out: the incumbent and what each
+ * window size gave.  Repetend times of different window sizes compare per micro-batch:
+ * T_a/N_a < T_b/N_b  <=>  T_a*N_b < T_b*N_a. */
+typedef struct {
+    int32_t  max_nr;              /* in:  largest N_R tried, 1..TESSEL_MAX_NR                            */
+    int32_t  use_inflight_bound;  /* in:  non-zero: stop at N_R = CalMaxInflight as Alg. 1 does           */
+    uint64_t max_candidates;      /* in:  per window size, indices 0 .. min(space size, this) - 1 are scored */
+    uint64_t launch_candidates;   /* in:  candidates per kernel launch; the early exit is tested between
+                                          launches; 0 = 2^24                                              */
+    int32_t  inflights;           /* out: CalMaxInflight: min over devices of floor(M / hold_d), hold_d =
+                                          what one micro-batch alone holds on d at most (blocks in
+                                          topological order, smallest type id first); TESSEL_MAX_NR if
+                                          nothing holds memory                                            */
+    int32_t  lower_bound;         /* out: GetLowerBound: max_d sum of t on d, per micro-batch             */
+    int32_t  nr_tried;            /* out: window sizes entered                                            */
+    int32_t  best_nr;             /* out: window size of the incumbent, 0 = nothing feasible              */
+    int32_t  best_period;         /* out: its T* (per micro-batch: best_period / best_nr), -1 = none      */
+    int32_t  early_exit;          /* out: 1 = the lower bound was reached and the search stopped there    */
+    uint64_t best_index;          /* out: its candidate index in the space of window size best_nr         */
+    int32_t  period_nr[TESSEL_MAX_NR + 1];      /* out: best T* of window size n at [n], -1 = none        */
+    uint64_t index_nr[TESSEL_MAX_NR + 1];       /* out: lowest index attaining it                         */
+    uint64_t evaluated_nr[TESSEL_MAX_NR + 1];   /* out: candidates scored (whole launches)                */
+} tessel_search;
+
+/* Device workspace tessel_search_run needs for the window sizes that `in` (its max_nr and
+ * use_inflight_bound are read) selects for `desc` (desc->nr is ignored).  Errors: as
+ * tessel_problem_create. */
+int  tessel_search_workspace_bytes(const tessel_problem_desc *desc, const tessel_search *in, size_t *bytes);
+
+/* Alg. 1: for N_R = 1 .. min(max_nr, inflights) score the candidates of that window size in
+ * ascending index order, launch by launch, keep the incumbent under strict <, and stop as soon
+ * as a window reaches N_R * lower_bound.  The incumbent starts empty (the paper starts it at the
+ * serial time, which would leave a problem that cannot beat serial execution without any
+ * schedule).  desc->nr and desc->fixed_leads are ignored.  Synchronises `hip_stream` between
+ * launches.  On success *best_out (if not NULL) is a new problem handle of window size
+ * best_nr, bound to `workspace_dev`, whose running best is the incumbent: tessel_best,
+ * tessel_best_candidate and tessel_complete_schedule apply; the caller destroys it.
+ * Errors: those of tessel_problem_create for any window size, WORKSPACE, HIP, and NO_FEASIBLE
+ * (the fields of *io are still filled in; no handle is returned). */
+int  tessel_search_run(const tessel_problem_desc *desc, tessel_search *io, void *workspace_dev,
+                       size_t workspace_bytes, void *hip_stream, tessel_problem **best_out);
+
 /* Measurement aid, not part of the method: launches a kernel of `blocks` x 256 threads in which
  * every lane runs `rounds` rounds of 32 independent full-rate 32-bit integer VALU operations
  * (add, unsigned max), asynchronously on `hip_stream`.  *lane_ops (host, may be NULL) receives the

@@ -40,6 +40,16 @@ class OracleResult(C.Structure):
 _lib = None
 
 
+MAX_NR = 16
+
+
+class OracleSearch(C.Structure):
+    _fields_ = [("inflights", C.c_int), ("lower_bound", C.c_int), ("nr_tried", C.c_int), ("best_nr", C.c_int),
+                ("best_period", C.c_int), ("best_index", C.c_uint64), ("early_exit", C.c_int),
+                ("period_nr", C.c_int * (MAX_NR + 1)), ("index_nr", C.c_uint64 * (MAX_NR + 1)),
+                ("evaluated_nr", C.c_uint64 * (MAX_NR + 1))]
+
+
 def _load():
     global _lib
     if _lib is None:
@@ -67,6 +77,12 @@ def _load():
                                      C.c_void_p, C.c_void_p, C.c_void_p]
         lib.orc_draw16.restype = C.c_uint32
         lib.orc_draw16.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32]
+        lib.orc_max_inflight.argtypes = [C.c_void_p, C.c_int]
+        lib.orc_search.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
+                                   C.c_void_p, C.c_int, C.c_uint64, C.c_uint32, C.c_int, C.c_int, C.c_uint64,
+                                   C.POINTER(OracleSearch)]
+        lib.orc_sizeof_search_result.restype = C.c_uint64
+        assert lib.orc_sizeof_search_result() == C.sizeof(OracleSearch)
         assert lib.orc_sizeof_score() == C.sizeof(OracleScore)
         assert lib.orc_sizeof_result() == C.sizeof(OracleResult)
         _lib = lib
@@ -85,6 +101,26 @@ class OracleError(Exception):
 
 def _i32(a):
     return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def search(problem, max_nr, max_candidates, use_inflight_bound=True):
+    """Alg. 1 over window sizes 1..max_nr (the problem's own NR is ignored), candidate by candidate."""
+    t, m = _i32(problem["t"]), _i32(problem["m"])
+    mask = np.ascontiguousarray(np.asarray(problem["dev_mask"], dtype=np.uint32))
+    deps = problem["deps"]
+    src, dst = _i32([a for a, _ in deps]), _i32([b for _, b in deps])
+    r = OracleSearch()
+    rc = _load().orc_search(problem["D"], problem["K"], problem["M"], t.ctypes.data, m.ctypes.data, mask.ctypes.data,
+                            len(deps), src.ctypes.data, dst.ctypes.data, SPACE[problem["space"]],
+                            problem.get("seed", 0), problem.get("lead_step_q16", 0), max_nr,
+                            1 if use_inflight_bound else 0, max_candidates, C.byref(r))
+    if rc:
+        raise OracleError(rc)
+    n = r.nr_tried
+    return {"inflights": r.inflights, "lower_bound": r.lower_bound, "nr_tried": n, "best_nr": r.best_nr,
+            "best_period": r.best_period, "best_index": int(r.best_index), "early_exit": bool(r.early_exit),
+            "period_nr": list(r.period_nr[1:n + 1]), "index_nr": [int(x) for x in r.index_nr[1:n + 1]],
+            "evaluated_nr": [int(x) for x in r.evaluated_nr[1:n + 1]]}
 
 
 class Oracle:
@@ -116,6 +152,9 @@ class Oracle:
         if getattr(self, "_h", None):
             _load().orc_destroy(self._h)
             self._h = None
+
+    def max_inflight(self, unbounded=MAX_NR):
+        return int(_load().orc_max_inflight(self._h, unbounded))
 
     @property
     def count(self):

@@ -813,5 +813,83 @@ int orc_complete(const orc_problem *p, const int *leads, const int *len, const i
     return rc ? rc : makespan;
 }
 
+
+/* ------------------------------------------------------------------ Alg. 1, the whole search
+ * CalMaxInflight (Alg. 1; the paper only says "the maximum number of in-flight micro-batches
+ * that can be executed within the memory constraints"): this build's reading.  One micro-batch
+ * that runs alone, its blocks in topological order (smallest type id first), holds on device d
+ * at most hold_d = the largest prefix sum of m over its blocks on d.  n micro-batches in flight
+ * can hold n * hold_d there, so inflights = min over devices with hold_d > 0 of floor(M / hold_d);
+ * a problem that holds no memory anywhere is not bounded by memory (returns `unbounded`). */
+int orc_max_inflight(const orc_problem *p, int unbounded)
+{
+    int best = unbounded;
+    for (int d = 0; d < p->D; d++) {
+        int run = 0, hold = 0;
+        for (int k = 0; k < p->K; k++) {
+            int i = p->topo[k];
+            if (p->mask[i] >> d & 1u) { run += p->m[i]; if (run > hold) hold = run; }
+        }
+        if (hold > 0 && p->M / hold < best) best = p->M / hold;
+    }
+    return best;
+}
+
+typedef struct {
+    int inflights;                       /* CalMaxInflight                                     */
+    int lower_bound;                     /* GetLowerBound: max_d sum of t on d, per micro-batch */
+    int nr_tried;                        /* window sizes entered                               */
+    int best_nr, best_period;            /* incumbent: t_R = best_period / best_nr; 0/-1 = none */
+    uint64_t best_index;
+    int early_exit;                      /* the lower bound was reached                        */
+    int period_nr[ORC_MAX_NR + 1];       /* best T* seen at window size N_R (-1 = none), [0] unused */
+    uint64_t index_nr[ORC_MAX_NR + 1];   /* first index attaining it                            */
+    uint64_t evaluated_nr[ORC_MAX_NR + 1];
+} orc_search_result;
+
+/* Alg. 1 as printed, one candidate at a time: N_R = 1 .. inflights (and <= max_nr), every
+ * candidate index of that window size in ascending order (at most max_candidates of them),
+ * the incumbent replaced on a strictly smaller repetend time only, return as soon as the lower
+ * bound is met.  Repetend times of different window sizes are compared per micro-batch:
+ * T_a / N_a < T_b / N_b  <=>  T_a * N_b < T_b * N_a.  The incumbent starts empty instead of
+ * at the serial time (a reading: as printed, a problem where nothing beats serial execution
+ * would get no schedule at all; whenever something does, both give the same result). */
+int orc_search(int D, int K, int M, const int *t, const int *m, const uint32_t *mask,
+               int ndeps, const int *src, const int *dst, int space, uint64_t seed, uint32_t step_q16,
+               int max_nr, int use_inflight_bound, uint64_t max_candidates, orc_search_result *out)
+{
+    memset(out, 0, sizeof *out);
+    out->best_period = -1;
+    for (int n = 0; n <= ORC_MAX_NR; n++) out->period_nr[n] = -1;
+    if (max_nr < 1 || max_nr > ORC_MAX_NR) return ORC_E_INVALID;
+    int limit = max_nr;
+    for (int NR = 1; NR <= limit; NR++) {
+        int err;
+        orc_problem *p = orc_create(D, K, NR, M, t, m, mask, ndeps, src, dst, space, NULL, seed, step_q16, &err);
+        if (!p) return err;
+        if (NR == 1) {
+            out->lower_bound = p->LB;                        /* N_R = 1: LB is the per-micro-batch bound */
+            out->inflights = orc_max_inflight(p, ORC_MAX_NR);
+            if (use_inflight_bound && out->inflights < limit) limit = out->inflights;
+            if (limit < 1) { orc_destroy(p); return ORC_E_OK; }
+        }
+        out->nr_tried = NR;
+        uint64_t n = p->count < max_candidates ? p->count : max_candidates;
+        for (uint64_t idx = 0; idx < n; idx++) {
+            orc_score sc;
+            orc_eval_index(p, idx, &sc, NULL);
+            out->evaluated_nr[NR]++;
+            if (sc.status != ORC_OK) continue;
+            if (out->period_nr[NR] < 0 || sc.period < out->period_nr[NR]) { out->period_nr[NR] = sc.period; out->index_nr[NR] = idx; }
+            if (out->best_period >= 0 && (int64_t)sc.period * out->best_nr >= (int64_t)out->best_period * NR) continue;
+            out->best_period = sc.period; out->best_nr = NR; out->best_index = idx;
+            if (sc.period == NR * out->lower_bound) { out->early_exit = 1; orc_destroy(p); return ORC_E_OK; }
+        }
+        orc_destroy(p);
+    }
+    return ORC_E_OK;
+}
+
 uint64_t orc_sizeof_score(void) { return sizeof(orc_score); }
 uint64_t orc_sizeof_result(void) { return sizeof(orc_result); }
+uint64_t orc_sizeof_search_result(void) { return sizeof(orc_search_result); }

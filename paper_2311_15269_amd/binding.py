@@ -22,7 +22,7 @@ E_NO_FEASIBLE = -7
 EXPORTS = (
     "tessel_problem_create", "tessel_problem_destroy", "tessel_candidate_count", "tessel_workspace_bytes",
     "tessel_eval_candidates", "tessel_score_candidates", "tessel_best", "tessel_best_candidate", "tessel_reset",
-    "tessel_complete_schedule", "tessel_alu_probe", "tessel_strerror", "tessel_last_hip_error",
+    "tessel_complete_schedule", "tessel_search_workspace_bytes", "tessel_search_run", "tessel_alu_probe", "tessel_strerror", "tessel_last_hip_error",
 )
 
 
@@ -58,6 +58,17 @@ def library_path():
     return _build.LIB
 
 
+MAX_NR = 8
+
+
+class Search(C.Structure):
+    _fields_ = [("max_nr", C.c_int32), ("use_inflight_bound", C.c_int32), ("max_candidates", C.c_uint64),
+                ("launch_candidates", C.c_uint64), ("inflights", C.c_int32), ("lower_bound", C.c_int32),
+                ("nr_tried", C.c_int32), ("best_nr", C.c_int32), ("best_period", C.c_int32), ("early_exit", C.c_int32),
+                ("best_index", C.c_uint64), ("period_nr", C.c_int32 * (MAX_NR + 1)),
+                ("index_nr", C.c_uint64 * (MAX_NR + 1)), ("evaluated_nr", C.c_uint64 * (MAX_NR + 1))]
+
+
 def load_library():
     """Loads the in-tree HIP library; builds it first only if it has never been built."""
     global _lib
@@ -77,6 +88,9 @@ def load_library():
         lib.tessel_best_candidate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.tessel_reset.argtypes = [C.c_void_p]
         lib.tessel_complete_schedule.argtypes = [C.c_void_p, C.POINTER(Schedule)]
+        lib.tessel_search_workspace_bytes.argtypes = [C.POINTER(ProblemDesc), C.POINTER(Search), C.POINTER(C.c_size_t)]
+        lib.tessel_search_run.argtypes = [C.POINTER(ProblemDesc), C.POINTER(Search), C.c_void_p, C.c_size_t, C.c_void_p,
+                                          C.POINTER(C.c_void_p)]
         lib.tessel_alu_probe.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_uint64)]
         lib.tessel_strerror.argtypes = [C.c_int]
         lib.tessel_strerror.restype = C.c_char_p
@@ -106,6 +120,46 @@ def _i32(a):
     return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
 
 
+def _describe(problem):
+    """tessel_problem_desc of a workload dict + the arrays it points into (keep them alive)"""
+    t, m = _i32(problem["t"]), _i32(problem["m"])
+    mask = np.ascontiguousarray(np.asarray(problem["dev_mask"], dtype=np.uint32))
+    deps = problem["deps"]
+    src, dst = _i32([a for a, _ in deps]), _i32([b for _, b in deps])
+    fixed = problem.get("fixed_leads")
+    fixed = _i32(fixed) if fixed is not None else None
+    desc = ProblemDesc(problem["D"], problem["K"], problem["NR"], problem["M"], t.ctypes.data, m.ctypes.data,
+                       mask.ctypes.data, len(deps), src.ctypes.data if len(deps) else None,
+                       dst.ctypes.data if len(deps) else None, SPACE[problem["space"]],
+                       fixed.ctypes.data if fixed is not None else None,
+                       problem.get("seed", 0), problem.get("lead_step_q16", 0))
+    return desc, (t, m, mask, src, dst, fixed)
+
+
+def search(problem, max_nr, max_candidates, launch_candidates=0, use_inflight_bound=True):
+    """tessel_search_run: Alg. 1 over window sizes 1..max_nr.  Returns (dict of the out fields, Problem of
+    the incumbent's window size with the incumbent as its running best, or None if nothing is feasible)."""
+    import torch
+    lib = load_library()
+    desc, keep = _describe(problem)
+    io = Search(max_nr=max_nr, use_inflight_bound=1 if use_inflight_bound else 0, max_candidates=max_candidates,
+                launch_candidates=launch_candidates)
+    n = C.c_size_t()
+    _check(lib.tessel_search_workspace_bytes(C.byref(desc), C.byref(io), C.byref(n)))
+    ws = torch.empty(n.value + 256, dtype=torch.uint8, device="cuda")
+    ptr = (ws.data_ptr() + 255) & ~255
+    h = C.c_void_p()
+    rc = _check(lib.tessel_search_run(C.byref(desc), C.byref(io), ptr, ws.numel() - (ptr - ws.data_ptr()),
+                                      torch.cuda.current_stream().cuda_stream, C.byref(h)), allow=(E_NO_FEASIBLE,))
+    k = io.nr_tried
+    out = {"inflights": io.inflights, "lower_bound": io.lower_bound, "nr_tried": k, "best_nr": io.best_nr,
+           "best_period": io.best_period, "best_index": int(io.best_index), "early_exit": bool(io.early_exit),
+           "period_nr": list(io.period_nr[1:k + 1]), "index_nr": [int(x) for x in io.index_nr[1:k + 1]],
+           "evaluated_nr": [int(x) for x in io.evaluated_nr[1:k + 1]]}
+    best = Problem._adopt(dict(problem, NR=io.best_nr), h, ws) if rc == 0 else None
+    return out, best
+
+
 class Problem:
     """tessel_problem_create / _destroy and the calls on the handle, same names as the C ABI."""
 
@@ -113,21 +167,22 @@ class Problem:
         lib = load_library()
         self.problem = problem
         self.D, self.K, self.NR = problem["D"], problem["K"], problem["NR"]
-        self._t, self._m = _i32(problem["t"]), _i32(problem["m"])
-        self._mask = np.ascontiguousarray(np.asarray(problem["dev_mask"], dtype=np.uint32))
-        deps = problem["deps"]
-        self._src, self._dst = _i32([a for a, _ in deps]), _i32([b for _, b in deps])
-        fixed = problem.get("fixed_leads")
-        self._fixed = _i32(fixed) if fixed is not None else None
-        desc = ProblemDesc(self.D, self.K, self.NR, problem["M"], self._t.ctypes.data, self._m.ctypes.data,
-                           self._mask.ctypes.data, len(deps), self._src.ctypes.data if len(deps) else None,
-                           self._dst.ctypes.data if len(deps) else None, SPACE[problem["space"]],
-                           self._fixed.ctypes.data if self._fixed is not None else None,
-                           problem.get("seed", 0), problem.get("lead_step_q16", 0))
+        desc, self._keep = _describe(problem)
         h = C.c_void_p()
         _check(lib.tessel_problem_create(C.byref(desc), C.byref(h)))
         self._h = h
         self._ws = None
+
+    @classmethod
+    def _adopt(cls, problem, handle, ws):
+        """wraps a handle the library returned (tessel_search_run) and the workspace it is bound to"""
+        self = cls.__new__(cls)
+        self.problem = problem
+        self.D, self.K, self.NR = problem["D"], problem["K"], problem["NR"]
+        self._keep = None
+        self._h = handle
+        self._ws = ws
+        return self
 
     def close(self):
         if getattr(self, "_h", None) and _lib is not None:

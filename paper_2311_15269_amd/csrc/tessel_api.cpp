@@ -642,4 +642,114 @@ extern "C" int tessel_complete_schedule(tessel_problem *p, tessel_schedule *out)
     return TESSEL_OK;
 }
 
+// ---- Alg. 1: the loop over window sizes around the scoring kernels -------------------------
+
+// CalMaxInflight of Alg. 1 (the paper gives no formula): one micro-batch alone, blocks in topological
+// order with the smallest type id first, holds at most hold_d on device d; floor(M / hold_d) of them fit.
+static int max_inflight(const tessel_problem_desc *desc)
+{
+    const int K = desc->num_block_types;
+    std::vector<int> indeg(K, 0), done(K, 0), topo;
+    for (int e = 0; e < desc->num_deps; e++) indeg[desc->dep_dst[e]]++;
+    for (;;) {
+        int pick = -1;
+        for (int i = 0; i < K; i++) if (!done[i] && indeg[i] == 0) { pick = i; break; }
+        if (pick < 0) break;
+        done[pick] = 1; topo.push_back(pick);
+        for (int e = 0; e < desc->num_deps; e++) if (desc->dep_src[e] == pick) indeg[desc->dep_dst[e]]--;
+    }
+    int best = TESSEL_MAX_NR;
+    for (int d = 0; d < desc->num_devices; d++) {
+        int run = 0, hold = 0;
+        for (int i : topo) if (desc->dev_mask[i] >> d & 1u) { run += desc->mem[i]; hold = std::max(hold, run); }
+        if (hold > 0) best = std::min(best, desc->mem_cap / hold);
+    }
+    return best;
+}
+
+extern "C" int tessel_search_workspace_bytes(const tessel_problem_desc *desc, const tessel_search *in, size_t *bytes)
+{
+    if (!desc || !in || !bytes || in->max_nr < 1 || in->max_nr > TESSEL_MAX_NR) return TESSEL_E_INVALID_ARG;
+    size_t need = 0;
+    int limit = in->max_nr;
+    for (int nr = 1; nr <= limit; nr++) {
+        tessel_problem_desc d = *desc;
+        d.nr = nr; d.fixed_leads = nullptr;
+        tessel_problem *p = nullptr;
+        int rc = tessel_problem_create(&d, &p);
+        if (rc) return rc;
+        if (nr == 1 && in->use_inflight_bound) limit = std::max(1, std::min(limit, max_inflight(desc)));
+        size_t b = 0;
+        rc = tessel_workspace_bytes(p, &b);
+        tessel_problem_destroy(p);
+        if (rc) return rc;
+        need = std::max(need, b);
+    }
+    *bytes = need;
+    return TESSEL_OK;
+}
+
+extern "C" int tessel_search_run(const tessel_problem_desc *desc, tessel_search *io, void *workspace_dev,
+                                 size_t workspace_bytes, void *hip_stream, tessel_problem **best_out)
+{
+    if (best_out) *best_out = nullptr;
+    if (!desc || !io || io->max_nr < 1 || io->max_nr > TESSEL_MAX_NR) return TESSEL_E_INVALID_ARG;
+    const uint64_t per_launch = io->launch_candidates ? io->launch_candidates : (uint64_t)1 << 24;
+    io->inflights = 0; io->lower_bound = 0; io->nr_tried = 0; io->best_nr = 0; io->best_period = -1;
+    io->early_exit = 0; io->best_index = 0;
+    for (int n = 0; n <= TESSEL_MAX_NR; n++) { io->period_nr[n] = -1; io->index_nr[n] = 0; io->evaluated_nr[n] = 0; }
+
+    int limit = io->max_nr;
+    for (int nr = 1; nr <= limit && !io->early_exit; nr++) {
+        tessel_problem_desc d = *desc;
+        d.nr = nr; d.fixed_leads = nullptr;
+        tessel_problem *p = nullptr;
+        int rc = tessel_problem_create(&d, &p);
+        if (rc) return rc;
+        if (nr == 1) {
+            io->lower_bound = p->kp.LB;
+            io->inflights = max_inflight(desc);
+            if (io->use_inflight_bound) limit = std::min(limit, io->inflights);
+            if (limit < 1) { tessel_problem_destroy(p); break; }
+        }
+        io->nr_tried = nr;
+        const uint64_t n = std::min(p->count, io->max_candidates);
+        tessel_result r;
+        for (uint64_t first = 0; first < n && !io->early_exit; first += per_launch) {
+            const uint64_t cnt = std::min(per_launch, n - first);
+            rc = tessel_eval_candidates(p, first, cnt, workspace_dev, workspace_bytes, hip_stream);
+            if (rc) { tessel_problem_destroy(p); return rc; }
+            rc = tessel_best(p, &r);                                  // waits for the launch
+            if (rc && rc != TESSEL_E_NO_FEASIBLE) { tessel_problem_destroy(p); return rc; }
+            io->evaluated_nr[nr] = r.n_evaluated;
+            if (rc == TESSEL_OK) {
+                io->period_nr[nr] = r.period; io->index_nr[nr] = r.index;
+                // launches ascend in index, so the running best is what a candidate-by-candidate scan
+                // would hold after the first candidate that reaches the bound
+                if (r.period == nr * io->lower_bound) io->early_exit = 1;
+            }
+        }
+        if (io->period_nr[nr] >= 0 &&
+            (io->best_period < 0 || (int64_t)io->period_nr[nr] * io->best_nr < (int64_t)io->best_period * nr)) {
+            io->best_period = io->period_nr[nr]; io->best_nr = nr; io->best_index = io->index_nr[nr];
+        }
+        tessel_problem_destroy(p);
+    }
+    if (io->best_nr == 0) return TESSEL_E_NO_FEASIBLE;
+    if (best_out) {
+        tessel_problem_desc d = *desc;
+        d.nr = io->best_nr; d.fixed_leads = nullptr;
+        tessel_problem *p = nullptr;
+        int rc = tessel_problem_create(&d, &p);
+        if (rc) return rc;
+        rc = tessel_eval_candidates(p, io->best_index, 1, workspace_dev, workspace_bytes, hip_stream);
+        tessel_result r;
+        if (!rc) rc = tessel_best(p, &r);
+        if (!rc && (r.period != io->best_period || r.index != io->best_index)) rc = TESSEL_E_HIP;   // never expected
+        if (rc) { tessel_problem_destroy(p); return rc; }
+        *best_out = p;
+    }
+    return TESSEL_OK;
+}
+
 extern "C" int tessel_last_hip_error(const tessel_problem *p) { return p ? p->last_hip : 0; }

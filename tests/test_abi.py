@@ -60,3 +60,21 @@ def test_alu_probe_validates_its_arguments_on_the_host():
     assert lib.tessel_alu_probe(4, 0, 1, 1 << 20, None, C.byref(ops)) == -1
     assert lib.tessel_alu_probe(4, 10, None, 1 << 20, None, C.byref(ops)) == -1
     assert lib.tessel_alu_probe(4, 10, 256, 4 * 256 * 4 - 1, None, C.byref(ops)) == -5
+
+
+def test_search_validates_its_arguments_on_the_host():
+    import ctypes as C
+    lib = binding.load_library()
+    desc, keep = binding._describe(W.config1())
+    n = C.c_size_t()
+    io = binding.Search(max_nr=0)
+    assert lib.tessel_search_workspace_bytes(C.byref(desc), C.byref(io), C.byref(n)) == -1
+    assert lib.tessel_search_run(C.byref(desc), C.byref(io), None, 0, None, None) == -1
+    io = binding.Search(max_nr=9)
+    assert lib.tessel_search_run(C.byref(desc), C.byref(io), None, 0, None, None) == -1
+    # window sizes beyond the in-flight bound are never created: the 4-stage canonical space has no table for N_R = 8
+    desc, keep = binding._describe(W.config2())
+    io = binding.Search(max_nr=8, use_inflight_bound=1)
+    assert lib.tessel_search_workspace_bytes(C.byref(desc), C.byref(io), C.byref(n)) == 0 and n.value > 0
+    io = binding.Search(max_nr=8, use_inflight_bound=0)
+    assert lib.tessel_search_workspace_bytes(C.byref(desc), C.byref(io), C.byref(n)) == -4
