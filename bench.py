@@ -41,6 +41,9 @@ def main():
     ap.add_argument("--log2-chunk", type=int, default=24, help="candidates per kernel launch")
     ap.add_argument("--cpu-sample-log2", type=int, default=20, help="oracle baseline sample size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--search", action="store_true",
+                    help="time the whole search of Alg. 1 (window sizes 1..4, early exit) on the sequential 4-stage "
+                         "placement instead of the headline workload; prints its own JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one plain device copy of 1 GiB instead (reference for the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -65,6 +68,27 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.search:
+        from paper_2311_15269_amd.binding import search
+        prob = workloads.config2()
+        for _ in range(args.warmup):
+            search(prob, 8, 1 << 62)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            got, best = search(prob, 8, 1 << 62)
+            sched = best.complete_schedule(16)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        print(json.dumps({"metric": "wall time of the whole schedule search (Alg. 1: window sizes, early exit, completion)",
+                          "value": dt, "unit": "s", "higher_is_better": False, "n_gpus": 1, "steps": args.steps,
+                          "warmup": args.warmup, "dtype": "int32", "data": "synthetic", "vs_baseline": None,
+                          "config": {"workload": "sequential 4-stage placement, tf=1, tb=2, M=4, exhaustive canonical "
+                                                 "spaces of N_R=1..4, completion to 16 micro-batches"},
+                          "result": dict(got, makespan_16_microbatches=sched["makespan"]),
+                          "candidates_scored": sum(got["evaluated_nr"]),
+                          "candidates_per_s": sum(got["evaluated_nr"]) / dt}))
+        return
     prob = workloads.config5()
     n_cand = 1 << args.log2_candidates
     chunk = min(1 << args.log2_chunk, n_cand)
