@@ -1,0 +1,67 @@
+"""The ablations of Sec. VI-C on the sequential 4-stage placement as regression tests: bubble
+rate of the best window against the window size N_R (memory not limiting) and against the
+memory cap M (N_R = 4).  The 2.9e9-candidate spaces are out of the oracle's reach, so the
+periods are checked against what the model fixes (the in-flight argument, the lower bound,
+monotonicity) and the oracle re-scores the reported best candidates one by one."""
+from fractions import Fraction
+
+import pytest
+
+from paper_2311_15269_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+CHUNK = 1 << 24
+P, TF, TB = 4, 1, 2
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: the HIP path has no CPU fallback")
+    from paper_2311_15269_amd import binding
+    binding.load_library()
+    return binding
+
+
+def best_of_whole_space(gpu, prob):
+    g = gpu.Problem(prob)
+    total = g.candidate_count()
+    for first in range(0, total, CHUNK):
+        g.eval_candidates(first, min(CHUNK, total - first))
+    r = g.best()
+    assert r["n_evaluated"] == total
+    return r
+
+
+def test_bubble_rate_against_window_size(gpu):
+    """No bubble from N_R = 4 = number of devices on (Sec. VI-C); below that the N_R micro-batches in
+    flight share one round trip of 4 (tf + tb): bubble 1 - N_R/4."""
+    from oracle import Oracle
+    bubbles = []
+    for nr in range(1, P + 1):
+        prob = W.pipeline_problem(W.linear_placement(P), [TF] * P, [TB] * P, P, nr, 64, "canonical")
+        r = best_of_whole_space(gpu, prob)
+        assert r["period"] == max(nr, P) * (TF + TB)
+        assert r["lower_bound"] == nr * (TF + TB)
+        sc = Oracle(prob).eval_index(r["index"])
+        assert sc["status"] == 0 and sc["period"] == r["period"] and sc["peak"] == r["peak"]
+        bubbles.append(1 - Fraction(r["lower_bound"], r["period"]))
+    assert bubbles == [Fraction(3, 4), Fraction(1, 2), Fraction(1, 4), 0]
+
+
+def test_bubble_rate_against_memory_cap(gpu):
+    """N_R = 4: a lower cap never gives a smaller bubble, a cap of 4 (one activation per stage in
+    flight) reaches zero, and a cap of 1 serialises the micro-batches completely."""
+    from oracle import Oracle
+    periods = {}
+    for M in (1, 2, 3, 4, 6):
+        prob = W.pipeline_problem(W.linear_placement(P), [TF] * P, [TB] * P, P, P, M, "canonical")
+        r = best_of_whole_space(gpu, prob)
+        sc = Oracle(prob).eval_index(r["index"])
+        assert sc["status"] == 0 and sc["period"] == r["period"] and sc["peak"] == r["peak"] and sc["peak_max"] <= M
+        periods[M] = r["period"]
+    assert periods[1] == P * P * (TF + TB)                 # one micro-batch at a time: N_R round trips
+    assert periods[4] == periods[6] == P * (TF + TB)       # the lower bound
+    assert periods[1] >= periods[2] >= periods[3] >= periods[4]
+    assert periods[2] > periods[4]

@@ -110,3 +110,15 @@ def test_inflight_bound_of_the_benchmark_problems():
     assert O.Oracle(W.config5()).max_inflight() == 5
     # the tensor-parallel embedding (+2) and a stage (+1) share every device of config 4
     assert O.Oracle(W.config4()).max_inflight() == 2
+
+
+@pytest.mark.parametrize("p,tf,tb", [(2, 1, 2), (2, 1, 3), (3, 1, 2), (3, 1, 3)])
+def test_bubble_rate_against_window_size_without_memory_limit(p, tf, tb):
+    """Sec. VI-C, bubble rate and N_R for the sequential placement: a window of N_R micro-batches
+    keeps at most N_R of them in flight, one round trip takes p (tf + tb), so
+    T*(N_R) = max(N_R (tf + tb), p (tf + tb)): the bubble 1 - N_R/p vanishes first at N_R = p."""
+    prob = W.pipeline_problem(W.linear_placement(p), [tf] * p, [tb] * p, p, 1, 64, "canonical")
+    r = O.search(prob, p + 1 if p < 3 else p, 1 << 40, use_inflight_bound=False)
+    want = [max(nr, p) * (tf + tb) for nr in range(1, p + 1)]
+    assert r["period_nr"][:p] == want
+    assert r["best_nr"] == p and r["early_exit"]
