@@ -490,13 +490,13 @@ struct FastProgram {
 
 struct FastLds {
     uint2 *tt_tab;        // [32]  x: t by code, y: byte offset of the first token slot of the code's chain
-    uint32_t *info_tab;   // [32]  packed consumer/producer/memory delta by code
+    uint32_t *info_tab;   // [32]  by code: consumer code (63 none) | memory delta << 16
     uint32_t *chain_tab;  // [32]  KParams::chain_tab
     uint32_t *vtab;       // [32]  KParams::vtab
     uint32_t *cum_tab, *predbit_tab, *depbit_tab;   // [32] each: KParams::cum_code, pred_bit, dep_bit
     uint4 *rec;           // build: [DM][64] x: low plane, y: high plane, z: not-yet-placed mask,
                           //        w: micro-batches waiting at the input of the 4 types (4 bits each)
-                          //           | memory now (8 bit) << 16 | peak << 24
+                          //           | memory now (signed) << 16
     uint2 *drec;          // sweeps: [D][64] x: device free time, y: next micro-batch of the 4 types (4 bits each)
     uint32_t *tok;        // sweeps: [token slots][64] end time of the micro-batch's latest block
 };
@@ -664,25 +664,26 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
             plo[d] = phi[d] = 0; nlen[d] = 0;
             if (d >= C.D) continue;
             const uint32_t n = (uint32_t)C.ntd[d] * NR;
-            // cumulative counts of the remaining blocks by type: a digit below t1 picks symbol 0, below t2 symbol 1, ...
-            uint32_t t1 = C.ntd[d] > 0 ? NR : 0u, t2 = t1 + (C.ntd[d] > 1 ? NR : 0u), t3 = t2 + (C.ntd[d] > 2 ? NR : 0u);
+            // cumulative counts of the remaining blocks by type, t1 <= t2 <= t3 <= 32: a digit below t1 picks
+            // symbol 0, below t2 symbol 1, ...  The three are kept as bytes of one word, as 0x80 - t, so that
+            // one add of the replicated digit leaves "digit >= t" in bit 7 of every byte (no carry between
+            // bytes: 0x60 <= 0x80 - t + digit < 0xA0).
+            const uint32_t c1 = C.ntd[d] > 0 ? NR : 0u, c2 = c1 + (C.ntd[d] > 1 ? NR : 0u), c3 = c2 + (C.ntd[d] > 2 ? NR : 0u);
+            uint32_t tq = 0x808080u - (c1 | (c2 << 8) | (c3 << 16));
             uint32_t lo = 0, hi = 0;
+            auto pick = [&](uint32_t draw, uint32_t left, uint32_t pos) {
+                const uint32_t digit = __umul24(draw, left) >> 16;
+                const uint32_t ge = (__umul24(digit, 0x010101u) + tq) & 0x808080u;
+                tq += 0x010101u - (ge >> 7);                     // a threshold above the digit loses one block
+                // symbol = number of thresholds at or below the digit; they are ordered, so its low bit is the
+                // parity of the three tests and its high bit the middle one
+                lo |= ((uint32_t)__builtin_popcount(ge) & 1u) << pos;
+                hi |= ((ge >> 15) & 1u) << pos;
+            };
             for (uint32_t pos = 0; pos < n; pos += 2) {
                 const uint32_t word = stream_word(ka, kb, (kDrawOrdBase + 32u * (uint32_t)d + pos) >> 1);
-                {
-                    const uint32_t digit = __umul24(word & 0xFFFFu, n - pos) >> 16;
-                    const uint32_t g1 = digit >= t1, g2 = digit >= t2, g3 = digit >= t3;
-                    const uint32_t y = g1 + g2 + g3;
-                    t1 += g1 - 1u; t2 += g2 - 1u; t3 += g3 - 1u;
-                    lo |= (y & 1u) << pos; hi |= (y >> 1) << pos;
-                }
-                if (pos + 1 < n) {
-                    const uint32_t digit = __umul24(word >> 16, n - pos - 1u) >> 16;
-                    const uint32_t g1 = digit >= t1, g2 = digit >= t2, g3 = digit >= t3;
-                    const uint32_t y = g1 + g2 + g3;
-                    t1 += g1 - 1u; t2 += g2 - 1u; t3 += g3 - 1u;
-                    lo |= (y & 1u) << (pos + 1u); hi |= (y >> 1) << (pos + 1u);
-                }
+                pick(word & 0xFFFFu, n - pos, pos);
+                if (pos + 1 < n) pick(word >> 16, n - pos - 1u, pos + 1u);
             }
             plo[d] = lo; phi[d] = hi; nlen[d] = (int)n;
         }
@@ -759,7 +760,7 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
             mem0 += ((int)(C.mpack[d] << (24 - 8 * y)) >> 24) * (int)lead;     // blocks that ran before the window
         }
         const uint32_t alive = nlen[d] >= 32 ? 0xFFFFFFFFu : (1u << nlen[d]) - 1u;
-        L.rec[d * kWave + lane] = make_uint4(plo[d], phi[d], alive, qd | (((uint32_t)mem0 & 0xFFu) << 16) | (0x80u << 24));
+        L.rec[d * kWave + lane] = make_uint4(plo[d], phi[d], alive, qd | ((uint32_t)mem0 << 16));
         if (nlen[d] > 0) HM |= 1u << (4 * d + ((plo[d] & 1u) | ((phi[d] & 1u) << 1)));
     }
 
@@ -767,78 +768,71 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
     const bool repair = C.space == kSampledRepair;
     const int total = C.total;
     bool building = valid && status == kOk;
-    uint32_t acc = 0;
-    int sh = 0, wi = 0;
+    int worst = INT_MIN;             // largest memory prefix over all devices (Eq. 1 [2])
     FastProgram prog;
     prog.a = 0; prog.b = 0;
-    for (int k = 0; k < total; k++) {
+    for (int wi = 0; wi < C.nwords; wi++) {          // one program word = six blocks
         if (__ballot(building) == 0) break;
-        const uint32_t hm = R & HM;
-        const uint32_t sel = hm ? hm : (repair ? R : 0u);
-        if (building && sel == 0) { status = kDeadlock; building = false; }
-        const uint32_t b = (uint32_t)__builtin_ctz(sel | 0x80000000u);
-        const uint32_t d4 = building ? b & 28u : 0u;             // 4 * device
-        uint4 a = L.rec[(d4 >> 2) * kWave + lane];
-        uint4 inf4 = *(const uint4 *)(L.info_tab + d4);
-        TESSEL_PIN(a.x); TESSEL_PIN(a.y); TESSEL_PIN(a.z); TESSEL_PIN(a.w);
-        TESSEL_PIN(inf4.x); TESSEL_PIN(inf4.y); TESSEL_PIN(inf4.z); TESSEL_PIN(inf4.w);
-        // earliest remaining entry of the device whose type is allowed (all types when its head runs):
-        // a 4-way multiplexer keyed by the two planes
-        const uint32_t r4 = hm ? 15u : (R >> d4) & 15u;
-        const uint32_t r0 = 0u - (r4 & 1u), r1 = 0u - ((r4 >> 1) & 1u), r2 = 0u - ((r4 >> 2) & 1u), r3 = 0u - (r4 >> 3);
-        const uint32_t gate = bfi(a.y, bfi(a.x, r3, r2), bfi(a.x, r1, r0));
-        const uint32_t p = (uint32_t)__builtin_ctz((a.z & gate) | 0x80000000u);
-        const uint32_t y = ((a.x >> p) & 1u) | (((a.y >> p) & 1u) << 1);
-        const uint32_t c = d4 + y;
-        const uint32_t info = y & 2u ? (y & 1u ? inf4.w : inf4.z) : (y & 1u ? inf4.y : inf4.x);
-        // take the entry out; new head of the device
-        const uint32_t alive = a.z & ~(1u << p);
-        const uint32_t p2 = (uint32_t)__builtin_ctz(alive | 0x80000000u);
-        const uint32_t y2 = ((a.x >> p2) & 1u) | (((a.y >> p2) & 1u) << 1);
-        uint32_t hm_new = HM & ~(15u << d4);
-        if (alive) hm_new |= 1u << (d4 + y2);
-        // one waiting micro-batch is consumed; the type stays runnable while another one waits and
-        // entries of it remain; its consumer gets one more and becomes runnable
-        const uint32_t y4 = 4u * y;
-        const uint32_t ml = 0u - (1u - (y & 1u)), mh = 0u - (1u - (y >> 1));
-        const bool exhausted = (alive & (a.x ^ ml) & (a.y ^ mh)) == 0;
-        const uint32_t qc = (a.w >> y4) & 15u;
-        const bool ready_c = !exhausted && qc >= 2u;
-        const uint32_t su = info & 63u;
-        uint32_t r_new = (R & ~(1u << c)) | ((ready_c ? 1u : 0u) << c);
-        const uint32_t x_new = X | ((exhausted ? 1u : 0u) << c);
-        const bool has_su = su != 63u;
-        if (has_su) r_new |= (1u << (su & 31u)) & ~x_new;
-        const uint32_t su_inc = has_su ? 1u << (4u * (su & 3u)) : 0u;
-        const bool su_here = (su & 28u) == d4;
-        // memory prefix of the device (Eq. 1 [2])
-        const int m = (int)(info << 6) >> 24;
-        const int memcur = ((int)(a.w << 8) >> 24) + m;
-        const int pk = max((int)a.w >> 24, memcur);
-        const uint32_t w_new = (((a.w & 0xFFFFu) - (1u << y4) + (su_here ? su_inc : 0u)) & 0xFFFFu) |
-                               (((uint32_t)memcur & 0xFFu) << 16) | ((uint32_t)pk << 24);
-        if (building) {
-            R = r_new; X = x_new; HM = hm_new;
-            L.rec[(d4 >> 2) * kWave + lane].z = alive;
-            L.rec[(d4 >> 2) * kWave + lane].w = w_new;
-            if (has_su && !su_here) atomicAdd(&L.rec[((su & 28u) >> 2) * kWave + lane].w, su_inc);
-            acc |= c << sh;
+        uint32_t acc = 0;
+        const int nj = min(6, total - wi * 6);
+#pragma unroll 1
+        for (int j = 0; j < nj; j++) {
+            const uint32_t hm = R & HM;
+            const uint32_t sel = hm ? hm : (repair ? R : 0u);
+            if (building && sel == 0) { status = kDeadlock; building = false; }
+            const uint32_t b = (uint32_t)__builtin_ctz(sel | 0x80000000u);
+            const uint32_t d4 = building ? b & 28u : 0u;             // 4 * device
+            uint4 a = L.rec[(d4 >> 2) * kWave + lane];
+            uint4 inf4 = *(const uint4 *)(L.info_tab + d4);
+            TESSEL_PIN(a.x); TESSEL_PIN(a.y); TESSEL_PIN(a.z); TESSEL_PIN(a.w);
+            TESSEL_PIN(inf4.x); TESSEL_PIN(inf4.y); TESSEL_PIN(inf4.z); TESSEL_PIN(inf4.w);
+            // earliest remaining entry of the device whose type is allowed (all types when its head runs):
+            // a 4-way multiplexer keyed by the two planes
+            const uint32_t r4 = hm ? 15u : (R >> d4) & 15u;
+            const uint32_t r0 = 0u - (r4 & 1u), r1 = 0u - ((r4 >> 1) & 1u), r2 = 0u - ((r4 >> 2) & 1u), r3 = 0u - (r4 >> 3);
+            const uint32_t gate = bfi(a.y, bfi(a.x, r3, r2), bfi(a.x, r1, r0));
+            const uint32_t p = (uint32_t)__builtin_ctz((a.z & gate) | 0x80000000u);
+            const uint32_t y = ((a.x >> p) & 1u) | (((a.y >> p) & 1u) << 1);
+            const uint32_t c = d4 + y;
+            const uint32_t info = y & 2u ? (y & 1u ? inf4.w : inf4.z) : (y & 1u ? inf4.y : inf4.x);
+            // take the entry out; new head of the device
+            const uint32_t alive = a.z & ~(1u << p);
+            const uint32_t p2 = (uint32_t)__builtin_ctz(alive | 0x80000000u);
+            const uint32_t y2 = ((a.x >> p2) & 1u) | (((a.y >> p2) & 1u) << 1);
+            uint32_t hm_new = HM & ~(15u << d4);
+            if (alive) hm_new |= 1u << (d4 + y2);
+            // one waiting micro-batch is consumed; the type stays runnable while another one waits and
+            // entries of it remain; its consumer gets one more and becomes runnable
+            const uint32_t y4 = 4u * y;
+            const uint32_t ml = 0u - (1u - (y & 1u)), mh = 0u - (1u - (y >> 1));
+            const bool exhausted = (alive & (a.x ^ ml) & (a.y ^ mh)) == 0;
+            const uint32_t qc = (a.w >> y4) & 15u;
+            const bool ready_c = !exhausted && qc >= 2u;
+            const uint32_t su = info & 63u;
+            uint32_t r_new = (R & ~(1u << c)) | ((ready_c ? 1u : 0u) << c);
+            const uint32_t x_new = X | ((exhausted ? 1u : 0u) << c);
+            const bool has_su = su != 63u;
+            if (has_su) r_new |= (1u << (su & 31u)) & ~x_new;
+            const uint32_t su_inc = has_su ? 1u << (4u * (su & 3u)) : 0u;
+            const bool su_here = (su & 28u) == d4;
+            // the record's last word: waiting counts (16 bits) and the device's memory prefix (upper 16 bits,
+            // signed); the table entry carries the block's memory delta in its upper half, so one sum updates both
+            const uint32_t w_new = a.w + (info & 0xFFFF0000u) - (1u << y4) + (su_here ? su_inc : 0u);
+            if (building) {
+                R = r_new; X = x_new; HM = hm_new;
+                L.rec[(d4 >> 2) * kWave + lane].z = alive;
+                L.rec[(d4 >> 2) * kWave + lane].w = w_new;
+                if (has_su && !su_here) atomicAdd(&L.rec[((su & 28u) >> 2) * kWave + lane].w, su_inc);
+                worst = max(worst, (int)w_new >> 16);
+                acc |= c << (5 * j);
+            }
         }
-        sh += 5;
-        if (sh == 30 || k == total - 1) {
-            prog.set(wi, acc);
-            acc = 0; sh = 0; wi++;
-        }
+        prog.set(wi, acc);
     }
     if (status != kOk) return status;
-    int worst = INT_MIN;
 #pragma unroll
-    for (int d = 0; d < DM; d++) {
-        if (d >= C.D) continue;
-        int pk = (int)L.rec[d * kWave + lane].w >> 24;
-        if (C.ntd[d] == 0) pk = 0;
-        worst = max(worst, pk);
-    }
+    for (int d = 0; d < DM; d++)
+        if (d < C.D && C.ntd[d] == 0) worst = max(worst, 0);      // a device without blocks holds nothing
     peak_max = worst;
     if (valid && worst > C.M) status = kMem;
     int T = period_fast<DM, VM>(C, L, prog, lane, lead_code, valid && status == kOk, nsweeps_used);
@@ -881,7 +875,7 @@ __global__ __launch_bounds__(kWave, SAMPLED ? 4 : 3) void eval_fast_kernel(const
     if (lane < kMaxK) {
         const uint32_t inf = P.info_loc[lane];
         L.tt_tab[lane] = make_uint2((uint32_t)P.t_loc[lane], ((((inf >> 12) & 63u) - (uint32_t)P.D) << 8));
-        L.info_tab[lane] = inf;
+        L.info_tab[lane] = (inf & 63u) | ((uint32_t)((int32_t)(inf << 6) >> 24) << 16);     // consumer code | memory delta << 16
         L.chain_tab[lane] = P.chain_tab[lane]; L.vtab[lane] = lane < 24 ? P.vtab[lane] : 0u;
         L.cum_tab[lane] = P.cum_code[lane]; L.predbit_tab[lane] = P.pred_bit[lane]; L.depbit_tab[lane] = P.dep_bit[lane];
     }
