@@ -889,10 +889,12 @@ __global__ __launch_bounds__(kWave, SAMPLED ? 4 : 3) void eval_fast_kernel(const
 
     int best = INT_MAX;
     uint64_t best_idx = 0;
+    // counters of the whole wave (uniform values: they live in scalar registers)
     uint32_t cnt[kNumStatus];
 #pragma unroll
     for (int s = 0; s < kNumStatus; s++) cnt[s] = 0;
-    uint32_t nev = 0, nsw = 0;
+    uint32_t nev = 0;
+    uint32_t nsw = 0;                // per lane: window sweeps
     const uint64_t stride = (uint64_t)gridDim.x * kWave;
     const uint64_t rounds = (count + stride - 1) / stride;          // the same trip count for every lane of the grid
     for (uint64_t r = 0; r < rounds; r++) {
@@ -902,16 +904,16 @@ __global__ __launch_bounds__(kWave, SAMPLED ? 4 : 3) void eval_fast_kernel(const
         const uint64_t k = idx - first;
         int period, pk;
         int status = evaluate_fast<DM, VM, SAMPLED>(P, C, idx, L, lane, period, pk, valid, nsw);
-        if (!valid) continue;
-        if (status == kDeferred) {
+        if (valid && status == kDeferred) {
             // no eigenvector within the sweeps of this pass: the next pass scores it
             const uint32_t at = atomicAdd(out_count, 1u);
             if (at < out_cap) out_list[at] = idx; else *overflow = 1u;
-            continue;
         }
-        nev++;
+        const bool scored = valid && status != kDeferred;
+        nev += (uint32_t)__builtin_popcountll(__ballot(scored));
 #pragma unroll
-        for (int s = 0; s < kNumStatus; s++) cnt[s] += status == s;
+        for (int s = 0; s < kNumStatus; s++) cnt[s] += (uint32_t)__builtin_popcountll(__ballot(scored && status == s));
+        if (!scored) continue;
         if (status == kOk && key_less(period, idx, best, best_idx)) { best = period; best_idx = idx; }
         if (code_out) code_out[k] = status == kOk ? period : -status;
         if (peak_out) peak_out[k] = (status == kOk || status == kMem) ? pk : 0;
@@ -923,9 +925,6 @@ __global__ __launch_bounds__(kWave, SAMPLED ? 4 : 3) void eval_fast_kernel(const
         uint32_t ilo = __shfl_xor((uint32_t)best_idx, off), ihi = __shfl_xor((uint32_t)(best_idx >> 32), off);
         uint64_t oi = ((uint64_t)ihi << 32) | ilo;
         if (key_less(op, oi, best, best_idx)) { best = op; best_idx = oi; }
-#pragma unroll
-        for (int s = 0; s < kNumStatus; s++) cnt[s] += __shfl_xor(cnt[s], off);
-        nev += __shfl_xor(nev, off);
         nsw += __shfl_xor(nsw, off);
     }
     if (lane == 0) {
