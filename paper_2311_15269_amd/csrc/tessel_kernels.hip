@@ -643,7 +643,8 @@ __device__ __forceinline__ uint32_t even_bits(uint64_t x)
     return (uint32_t)x;
 }
 
-template <int DM, int VM, bool SAMPLED>
+// MODE: 0 exhaustive spaces, 1 sampled without repair, 2 sampled with repair
+template <int DM, int VM, int MODE>
 __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<DM> &C, uint64_t idx, const FastLds &L, int lane,
                                              int &period, int &peak_max, bool valid, uint32_t &nsweeps_used)
 {
@@ -652,7 +653,7 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
     period = 0; peak_max = 0;
     const uint32_t NR = (uint32_t)C.NR;
     int status = kOk;
-    constexpr bool sampled = SAMPLED;      // kSampledStrict / kSampledRepair; else the exhaustive spaces
+    constexpr bool sampled = MODE != 0;    // kSampledStrict / kSampledRepair; else the exhaustive spaces
     Mu leads_type;                   // by type id (exhaustive spaces, fixed leads)
     leads_type.lo = 0; leads_type.hi = 0;
     uint32_t ka = 0, kb = 0;
@@ -765,23 +766,26 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
     }
 
     const Mu lead_code = mu;
-    const bool repair = C.space == kSampledRepair;
+    // With repair every candidate has an executable order (the blocks not yet placed form a DAG, so some type
+    // is always runnable): no lane ever stops building, not even one past the end of the range (it scores a
+    // real candidate whose result is dropped), and the per-lane predicate disappears from the loop.
+    constexpr bool repair = MODE == 2;
     const int total = C.total;
-    bool building = valid && status == kOk;
+    bool building = repair || (valid && status == kOk);
     int worst = INT_MIN;             // largest memory prefix over all devices (Eq. 1 [2])
     FastProgram prog;
     prog.a = 0; prog.b = 0;
     for (int wi = 0; wi < C.nwords; wi++) {          // one program word = six blocks
-        if (__ballot(building) == 0) break;
+        if (!repair && __ballot(building) == 0) break;
         uint32_t acc = 0;
         const int nj = min(6, total - wi * 6);
 #pragma unroll 1
         for (int j = 0; j < nj; j++) {
             const uint32_t hm = R & HM;
             const uint32_t sel = hm ? hm : (repair ? R : 0u);
-            if (building && sel == 0) { status = kDeadlock; building = false; }
+            if (!repair && building && sel == 0) { status = kDeadlock; building = false; }
             const uint32_t b = (uint32_t)__builtin_ctz(sel | 0x80000000u);
-            const uint32_t d4 = building ? b & 28u : 0u;             // 4 * device
+            const uint32_t d4 = repair ? min(b & 28u, 4u * (DM - 1)) : building ? b & 28u : 0u;    // 4 * device
             uint4 a = L.rec[(d4 >> 2) * kWave + lane];
             uint4 inf4 = *(const uint4 *)(L.info_tab + d4);
             TESSEL_PIN(a.x); TESSEL_PIN(a.y); TESSEL_PIN(a.z); TESSEL_PIN(a.w);
@@ -818,7 +822,7 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
             // the record's last word: waiting counts (16 bits) and the device's memory prefix (upper 16 bits,
             // signed); the table entry carries the block's memory delta in its upper half, so one sum updates both
             const uint32_t w_new = a.w + (info & 0xFFFF0000u) - (1u << y4) + (su_here ? su_inc : 0u);
-            if (building) {
+            if (repair || building) {
                 R = r_new; X = x_new; HM = hm_new;
                 L.rec[(d4 >> 2) * kWave + lane].z = alive;
                 L.rec[(d4 >> 2) * kWave + lane].w = w_new;
@@ -843,8 +847,8 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
     return status;
 }
 
-template <int DM, int VM, bool SAMPLED>
-__global__ __launch_bounds__(kWave, SAMPLED ? 4 : 3) void eval_fast_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
+template <int DM, int VM, int MODE>
+__global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
                                                           BlockRec *__restrict__ recs, int32_t *__restrict__ code_out,
                                                           int32_t *__restrict__ peak_out, const uint64_t *__restrict__ in_list,
                                                           const uint32_t *__restrict__ in_count, uint32_t in_cap, int tries,
@@ -903,7 +907,7 @@ __global__ __launch_bounds__(kWave, SAMPLED ? 4 : 3) void eval_fast_kernel(const
         const uint64_t idx = !valid ? first : in_list ? in_list[kk] : first + kk;
         const uint64_t k = idx - first;
         int period, pk;
-        int status = evaluate_fast<DM, VM, SAMPLED>(P, C, idx, L, lane, period, pk, valid, nsw);
+        int status = evaluate_fast<DM, VM, MODE>(P, C, idx, L, lane, period, pk, valid, nsw);
         if (valid && status == kDeferred) {
             // no eigenvector within the sweeps of this pass: the next pass scores it
             const uint32_t at = atomicAdd(out_count, 1u);
@@ -1091,15 +1095,19 @@ static fast_fn pick_fast(const KParams &kp)
 {
     const int V = kp.nsweeps - 1;
     if (!kp.fast_ok) return nullptr;
-    const bool sampled = kp.space == kSampledStrict || kp.space == kSampledRepair;
-    if (sampled) {
-        if (kp.D <= 2) return V <= 4 ? eval_fast_kernel<2, 4, true> : eval_fast_kernel<2, 24, true>;
-        if (kp.D <= 4) return V <= 8 ? eval_fast_kernel<4, 8, true> : eval_fast_kernel<4, 24, true>;
-        return V <= 16 ? eval_fast_kernel<8, 16, true> : eval_fast_kernel<8, 24, true>;
+    if (kp.space == kSampledRepair) {
+        if (kp.D <= 2) return V <= 4 ? eval_fast_kernel<2, 4, 2> : eval_fast_kernel<2, 24, 2>;
+        if (kp.D <= 4) return V <= 8 ? eval_fast_kernel<4, 8, 2> : eval_fast_kernel<4, 24, 2>;
+        return V <= 16 ? eval_fast_kernel<8, 16, 2> : eval_fast_kernel<8, 24, 2>;
     }
-    if (kp.D <= 2) return V <= 4 ? eval_fast_kernel<2, 4, false> : eval_fast_kernel<2, 24, false>;
-    if (kp.D <= 4) return V <= 8 ? eval_fast_kernel<4, 8, false> : eval_fast_kernel<4, 24, false>;
-    return V <= 16 ? eval_fast_kernel<8, 16, false> : eval_fast_kernel<8, 24, false>;
+    if (kp.space == kSampledStrict) {
+        if (kp.D <= 2) return V <= 4 ? eval_fast_kernel<2, 4, 1> : eval_fast_kernel<2, 24, 1>;
+        if (kp.D <= 4) return V <= 8 ? eval_fast_kernel<4, 8, 1> : eval_fast_kernel<4, 24, 1>;
+        return V <= 16 ? eval_fast_kernel<8, 16, 1> : eval_fast_kernel<8, 24, 1>;
+    }
+    if (kp.D <= 2) return V <= 4 ? eval_fast_kernel<2, 4, 0> : eval_fast_kernel<2, 24, 0>;
+    if (kp.D <= 4) return V <= 8 ? eval_fast_kernel<4, 8, 0> : eval_fast_kernel<4, 24, 0>;
+    return V <= 16 ? eval_fast_kernel<8, 16, 0> : eval_fast_kernel<8, 24, 0>;
 }
 
 static size_t general_lds_bytes(const KParams &kp)
