@@ -490,7 +490,13 @@ struct FastProgram {
 
 struct FastLds {
     uint2 *tt_tab;        // [32]  x: t by code, y: byte offset of the first token slot of the code's chain
-    uint32_t *info_tab;   // [32]  by code: consumer code (63 none) | memory delta << 16
+    uint4 *type_tab;      // [32]  by code, what placing one block of the type does:
+                          //   x: added to the last word of its device record: memory delta << 16, one waiting
+                          //      micro-batch of the type less, one more for its consumer if that sits on the same device
+                          //   y: one-hot mask of the consumer's code (0: none)
+                          //   z: consumer on another device: byte offset of the last word of that device's records
+                          //      (lane 0) from the start of the records; 0xFFFFFFFF otherwise
+                          //   w: the increment of that word (one waiting micro-batch of the consumer)
     uint32_t *chain_tab;  // [32]  KParams::chain_tab
     uint32_t *vtab;       // [32]  KParams::vtab
     uint32_t *cum_tab, *predbit_tab, *depbit_tab;   // [32] each: KParams::cum_code, pred_bit, dep_bit
@@ -786,47 +792,42 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
             if (!repair && building && sel == 0) { status = kDeadlock; building = false; }
             const uint32_t b = (uint32_t)__builtin_ctz(sel | 0x80000000u);
             const uint32_t d4 = repair ? min(b & 28u, 4u * (DM - 1)) : building ? b & 28u : 0u;    // 4 * device
-            uint4 a = L.rec[(d4 >> 2) * kWave + lane];
-            uint4 inf4 = *(const uint4 *)(L.info_tab + d4);
+            uint4 *rp = L.rec + ((d4 >> 2) * kWave + lane);
+            uint4 a = *rp;
             TESSEL_PIN(a.x); TESSEL_PIN(a.y); TESSEL_PIN(a.z); TESSEL_PIN(a.w);
-            TESSEL_PIN(inf4.x); TESSEL_PIN(inf4.y); TESSEL_PIN(inf4.z); TESSEL_PIN(inf4.w);
             // earliest remaining entry of the device whose type is allowed (all types when its head runs):
             // a 4-way multiplexer keyed by the two planes
-            const uint32_t r4 = hm ? 15u : (R >> d4) & 15u;
-            const uint32_t r0 = 0u - (r4 & 1u), r1 = 0u - ((r4 >> 1) & 1u), r2 = 0u - ((r4 >> 2) & 1u), r3 = 0u - (r4 >> 3);
+            const int r4 = (int)((hm ? 0xFFFFFFFFu : R) >> d4);
+            const uint32_t r0 = (uint32_t)__builtin_amdgcn_sbfe(r4, 0, 1), r1 = (uint32_t)__builtin_amdgcn_sbfe(r4, 1, 1),
+                           r2 = (uint32_t)__builtin_amdgcn_sbfe(r4, 2, 1), r3 = (uint32_t)__builtin_amdgcn_sbfe(r4, 3, 1);
             const uint32_t gate = bfi(a.y, bfi(a.x, r3, r2), bfi(a.x, r1, r0));
             const uint32_t p = (uint32_t)__builtin_ctz((a.z & gate) | 0x80000000u);
-            const uint32_t y = ((a.x >> p) & 1u) | (((a.y >> p) & 1u) << 1);
+            // its symbol, as two all-or-nothing masks
+            const uint32_t ly = (uint32_t)__builtin_amdgcn_sbfe((int)a.x, p, 1), hy = (uint32_t)__builtin_amdgcn_sbfe((int)a.y, p, 1);
+            const uint32_t y = (ly & 1u) | (hy & 2u);
             const uint32_t c = d4 + y;
-            const uint32_t info = y & 2u ? (y & 1u ? inf4.w : inf4.z) : (y & 1u ? inf4.y : inf4.x);
-            // take the entry out; new head of the device
+            const uint4 e = L.type_tab[c];
+            // take the entry out; new head of the device.  (When the device is empty now the bit set below is
+            // meaningless, and harmless: all its types are exhausted, and R never holds an exhausted type.)
             const uint32_t alive = a.z & ~(1u << p);
             const uint32_t p2 = (uint32_t)__builtin_ctz(alive | 0x80000000u);
-            const uint32_t y2 = ((a.x >> p2) & 1u) | (((a.y >> p2) & 1u) << 1);
-            uint32_t hm_new = HM & ~(15u << d4);
-            if (alive) hm_new |= 1u << (d4 + y2);
+            const uint32_t y2 = __builtin_amdgcn_ubfe(a.x, p2, 1) | (__builtin_amdgcn_ubfe(a.y, p2, 1) << 1);
+            const uint32_t hm_new = (HM & ~(15u << d4)) | (1u << (d4 + y2));
             // one waiting micro-batch is consumed; the type stays runnable while another one waits and
             // entries of it remain; its consumer gets one more and becomes runnable
-            const uint32_t y4 = 4u * y;
-            const uint32_t ml = 0u - (1u - (y & 1u)), mh = 0u - (1u - (y >> 1));
-            const bool exhausted = (alive & (a.x ^ ml) & (a.y ^ mh)) == 0;
-            const uint32_t qc = (a.w >> y4) & 15u;
-            const bool ready_c = !exhausted && qc >= 2u;
-            const uint32_t su = info & 63u;
-            uint32_t r_new = (R & ~(1u << c)) | ((ready_c ? 1u : 0u) << c);
-            const uint32_t x_new = X | ((exhausted ? 1u : 0u) << c);
-            const bool has_su = su != 63u;
-            if (has_su) r_new |= (1u << (su & 31u)) & ~x_new;
-            const uint32_t su_inc = has_su ? 1u << (4u * (su & 3u)) : 0u;
-            const bool su_here = (su & 28u) == d4;
+            const uint32_t rest = alive & ~(a.x ^ ly) & ~(a.y ^ hy);        // remaining entries of the same type
+            const uint32_t more = (a.w >> (4u * y)) & 14u;                    // two or more were waiting
+            const uint32_t onec = 1u << c;
+            const uint32_t x_new = X | (rest == 0 ? onec : 0u);
+            const uint32_t r_new = (R & ~onec) | (min(rest, more) != 0 ? onec : 0u) | (e.y & ~x_new);
             // the record's last word: waiting counts (16 bits) and the device's memory prefix (upper 16 bits,
-            // signed); the table entry carries the block's memory delta in its upper half, so one sum updates both
-            const uint32_t w_new = a.w + (info & 0xFFFF0000u) - (1u << y4) + (su_here ? su_inc : 0u);
+            // signed); one sum updates both
+            const uint32_t w_new = a.w + e.x;
             if (repair || building) {
                 R = r_new; X = x_new; HM = hm_new;
-                L.rec[(d4 >> 2) * kWave + lane].z = alive;
-                L.rec[(d4 >> 2) * kWave + lane].w = w_new;
-                if (has_su && !su_here) atomicAdd(&L.rec[((su & 28u) >> 2) * kWave + lane].w, su_inc);
+                rp->z = alive;
+                rp->w = w_new;
+                if (e.z != 0xFFFFFFFFu) atomicAdd((uint32_t *)((char *)L.rec + e.z) + 4 * lane, e.w);
                 worst = max(worst, (int)w_new >> 16);
                 acc |= c << (5 * j);
             }
@@ -862,13 +863,13 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     const int lane = threadIdx.x;
     FastLds L;
     L.tt_tab = (uint2 *)lds;                                  // 64 words
-    L.info_tab = lds + 2 * kMaxK;
+    L.type_tab = (uint4 *)(lds + 8 * kMaxK);                  // 128 words
     L.chain_tab = lds + 3 * kMaxK;
     L.vtab = lds + 4 * kMaxK;
     L.cum_tab = lds + 5 * kMaxK;
     L.predbit_tab = lds + 6 * kMaxK;
     L.depbit_tab = lds + 7 * kMaxK;
-    uint32_t *base = lds + 8 * kMaxK;
+    uint32_t *base = lds + 12 * kMaxK;
     L.rec = (uint4 *)base;
     // the sweep state is only used once the build is over: it shares the records' space when it fits
     const int ntok = P.nslots - P.D;
@@ -879,7 +880,15 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     if (lane < kMaxK) {
         const uint32_t inf = P.info_loc[lane];
         L.tt_tab[lane] = make_uint2((uint32_t)P.t_loc[lane], ((((inf >> 12) & 63u) - (uint32_t)P.D) << 8));
-        L.info_tab[lane] = (inf & 63u) | ((uint32_t)((int32_t)(inf << 6) >> 24) << 16);     // consumer code | memory delta << 16
+        {
+            const uint32_t su = inf & 63u, dev = (uint32_t)lane >> 2, y = (uint32_t)lane & 3u;
+            const int32_t m = (int32_t)(inf << 6) >> 24;
+            const bool has_su = su != 63u, same = has_su && (su >> 2) == dev;
+            const uint32_t inc = has_su ? 1u << (4u * (su & 3u)) : 0u;
+            L.type_tab[lane] = make_uint4(((uint32_t)m << 16) - (1u << (4u * y)) + (same ? inc : 0u),
+                                          has_su ? 1u << (su & 31u) : 0u,
+                                          has_su && !same ? (su >> 2) * (kWave * 16u) + 12u : 0xFFFFFFFFu, inc);
+        }
         L.chain_tab[lane] = P.chain_tab[lane]; L.vtab[lane] = lane < 24 ? P.vtab[lane] : 0u;
         L.cum_tab[lane] = P.cum_code[lane]; L.predbit_tab[lane] = P.pred_bit[lane]; L.depbit_tab[lane] = P.dep_bit[lane];
     }
@@ -1119,7 +1128,7 @@ static size_t fast_lds_bytes(const KParams &kp)
 {
     const int ntok = kp.nslots - kp.D;
     const bool share = kp.D * 2 + ntok <= fast_dm(kp) * 4;
-    return (size_t)8 * kMaxK * 4 + (size_t)fast_dm(kp) * kWave * 16 + (share ? 0 : (size_t)(kp.D * 2 + ntok) * kWave * 4);
+    return (size_t)12 * kMaxK * 4 + (size_t)fast_dm(kp) * kWave * 16 + (share ? 0 : (size_t)(kp.D * 2 + ntok) * kWave * 4);
 }
 
 LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
