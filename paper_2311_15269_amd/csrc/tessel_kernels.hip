@@ -488,8 +488,11 @@ struct FastProgram {
     __device__ __forceinline__ void set(int i, uint32_t v) { if (i < 32) a[i] = v; else b[i - 32] = v; }
 };
 
+constexpr int kFastTableWords = 13 * kMaxK;      // uniform tables at the start of the fast kernel's LDS
+
 struct FastLds {
-    uint2 *tt_tab;        // [32]  x: t by code, y: byte offset of the first token slot of the code's chain
+    uint4 *tt_tab;        // [32]  by code, for the sweeps: x: t, y: byte offset of the first token slot of the code's
+                          //       chain, z: byte offset of its device's words, w: bit offset of its micro-batch counter
     uint4 *type_tab;      // [32]  by code, what placing one block of the type does:
                           //   x: added to the last word of its device record: memory delta << 16, one waiting
                           //      micro-batch of the type less, one more for its consumer if that sits on the same device
@@ -503,8 +506,10 @@ struct FastLds {
     uint4 *rec;           // build: [DM][64] x: low plane, y: high plane, z: not-yet-placed mask,
                           //        w: micro-batches waiting at the input of the 4 types (4 bits each)
                           //           | memory now (signed) << 16
-    uint2 *drec;          // sweeps: [D][64] x: device free time, y: next micro-batch of the 4 types (4 bits each)
-    uint32_t *tok;        // sweeps: [token slots][64] end time of the micro-batch's latest block
+    // sweeps: three arrays [slot][64] in a row, so that boundary value v of slot s is word s * 64 + lane
+    uint32_t *dfree;      // [D] time at which the device is free
+    uint32_t *tok;        // [token slots] end time of the micro-batch's latest block
+    uint32_t *dcnt;       // [D] next micro-batch of the device's 4 types (4 bits each)
 };
 
 // problem scalars, read once per workgroup
@@ -525,16 +530,16 @@ __device__ __forceinline__ uint32_t bfi(uint32_t sel, uint32_t a, uint32_t b) { 
 
 // one block of the window: s = max(device free, previous block of the micro-batch); both become s + t.
 // The micro-batch it handles is the device record's counter of its type.
-__device__ __forceinline__ void sweep_node(const FastLds &L, uint32_t code, uint32_t lane8, uint32_t lane4)
+// One block of the window: s = max(device free, previous block of the micro-batch); both become s + t.  The
+// micro-batch it handles is the device's counter of its type, `cnt` (read by the caller, which has already
+// written the incremented word back and may have the next node's counter read in flight).
+__device__ __forceinline__ void sweep_node(const FastLds &L, const uint4 tt, uint32_t cnt, uint32_t lane4)
 {
-    const uint32_t y4 = (code & 3u) << 2;
-    uint2 *dr = (uint2 *)((char *)L.drec + (((code & 28u) << 7) | lane8));       // (code >> 2) * 512
-    const uint2 dv = *dr;
-    const uint2 tt = L.tt_tab[code];
-    const uint32_t mu = (dv.y >> y4) & 15u;
-    uint32_t *tk = (uint32_t *)((char *)L.tok + (tt.y + (mu << 8) + lane4));
-    const uint32_t en = max(dv.x, *tk) + tt.x;
-    *dr = make_uint2(en, dv.y + (1u << y4));
+    const uint32_t mu = __builtin_amdgcn_ubfe(cnt, tt.w, 4);
+    uint32_t *fr = (uint32_t *)((char *)L.dfree + (tt.z + lane4));
+    uint32_t *tk = (uint32_t *)((char *)L.tok + (tt.y + lane4 + (mu << 8)));
+    const uint32_t en = max(*fr, *tk) + tt.x;
+    *fr = en;
     *tk = en;
 }
 
@@ -546,18 +551,40 @@ __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds
     // a lane without a complete program (rejected candidate, lane past the end of the range) must not run one:
     // its counters would leave the token ring
     if (!active) return;
-    const uint32_t lane4 = (uint32_t)lane * 4u, lane8 = (uint32_t)lane * 8u;
+    const uint32_t lane4 = (uint32_t)lane * 4u;
     const int full = C.total / 6, tail = C.total - 6 * full;
     for (int i = 0; i < full; i++) {
         const uint32_t w = prog.get(i);
+        // the six table entries first: they depend on the word only, so their reads leave the chain of the nodes
+        uint4 tt[6];
 #pragma unroll
-        for (int j = 0; j < 6; j++) sweep_node(L, (w >> (5 * j)) & 31u, lane8, lane4);
+        for (int j = 0; j < 6; j++) tt[j] = L.tt_tab[(w >> (5 * j)) & 31u];
+#pragma unroll
+        for (int j = 0; j < 6; j++) { TESSEL_PIN(tt[j].x); TESSEL_PIN(tt[j].y); TESSEL_PIN(tt[j].z); TESSEL_PIN(tt[j].w); }
+        // counters run one node ahead of the times: the counter word goes back incremented at once, the next
+        // node's read follows it (LDS keeps a wave's accesses in order), and only then this node waits for its
+        // device time and token
+        uint32_t cnt = *(uint32_t *)((char *)L.dcnt + (tt[0].z + lane4));
+#pragma unroll
+        for (int j = 0; j < 6; j++) {
+            *(uint32_t *)((char *)L.dcnt + (tt[j].z + lane4)) = cnt + (1u << tt[j].w);
+            uint32_t next = 0;
+            if (j < 5) next = *(uint32_t *)((char *)L.dcnt + (tt[j + 1].z + lane4));
+            sweep_node(L, tt[j], cnt, lane4);
+            cnt = next;
+        }
     }
     if (tail > 0) {
         const uint32_t w = prog.get(full);
 #pragma unroll
         for (int j = 0; j < 5; j++)
-            if (j < tail) sweep_node(L, (w >> (5 * j)) & 31u, lane8, lane4);
+            if (j < tail) {
+                const uint4 tt = L.tt_tab[(w >> (5 * j)) & 31u];
+                uint32_t *cp = (uint32_t *)((char *)L.dcnt + (tt.z + lane4));
+                const uint32_t cnt = *cp;
+                *cp = cnt + (1u << tt.w);
+                sweep_node(L, tt, cnt, lane4);
+            }
     }
     // window boundary: micro-batches mu >= N_R are mu - N_R of the next window; counters restart at the leads
     for (int p = 0; p < C.npaths; p++)
@@ -568,17 +595,16 @@ __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds
         }
 #pragma unroll
     for (int d = 0; d < DM; d++)
-        if (d < C.D) L.drec[d * kWave + lane].y = (uint32_t)((d < 4 ? lead_code.lo : lead_code.hi) >> (16 * (d & 3))) & 0xFFFFu;
+        if (d < C.D) L.dcnt[d * kWave + lane] = (uint32_t)((d < 4 ? lead_code.lo : lead_code.hi) >> (16 * (d & 3))) & 0xFFFFu;
 }
 
 template <int DM>
 __device__ __forceinline__ void reset_sweep_state(const FastConst<DM> &C, const FastLds &L, int lane, const Mu &lead_code)
 {
-    for (int s = 0; s < C.nslots - C.D; s++) L.tok[s * kWave + lane] = 0;
+    for (int s = 0; s < C.nslots; s++) L.dfree[s * kWave + lane] = 0;         // device times and tokens
 #pragma unroll
     for (int d = 0; d < DM; d++)
-        if (d < C.D)
-            L.drec[d * kWave + lane] = make_uint2(0u, (uint32_t)((d < 4 ? lead_code.lo : lead_code.hi) >> (16 * (d & 3))) & 0xFFFFu);
+        if (d < C.D) L.dcnt[d * kWave + lane] = (uint32_t)((d < 4 ? lead_code.lo : lead_code.hi) >> (16 * (d & 3))) & 0xFFFFu;
 }
 
 // Period of the repeated window.  The sweep is a max-plus linear map F on the boundary vector x
@@ -593,12 +619,8 @@ __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds
 {
     const int V = C.nsweeps - 1;
     const uint32_t lane4 = (uint32_t)lane * 4u;
-    // byte offset (from the device records) of boundary value v: a device's free time or a carried token
-    auto value_offset = [&](uint32_t e) -> uint32_t {
-        const uint32_t slot = e & 63u;
-        return (e >> 6 & 1u) ? slot * (kWave * 8u) + (uint32_t)lane * 8u
-                             : (uint32_t)((char *)L.tok - (char *)L.drec) + (slot - (uint32_t)C.D) * (kWave * 4u) + lane4;
-    };
+    // byte offset (from the device times) of boundary value v: a device's free time or a carried token
+    auto value_offset = [&](uint32_t e) -> uint32_t { return (e & 63u) * (kWave * 4u) + lane4; };
     uint32_t live = 0;                                    // per lane: which boundary values mean anything
 #pragma unroll
     for (int v = 0; v < VM; v++) {
@@ -623,7 +645,7 @@ __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds
 #pragma unroll
         for (int v = 0; v < VM; v++) {
             if (v < V) {
-                const uint32_t x = *(const uint32_t *)((const char *)L.drec + value_offset(L.vtab[v]));
+                const uint32_t x = *(const uint32_t *)((const char *)L.dfree + value_offset(L.vtab[v]));
                 const uint32_t dv = x - prev[v];
                 prev[v] = x;
                 if (live >> v & 1u) {
@@ -862,24 +884,26 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     const KParams &P = *Pp;
     const int lane = threadIdx.x;
     FastLds L;
-    L.tt_tab = (uint2 *)lds;                                  // 64 words
-    L.type_tab = (uint4 *)(lds + 8 * kMaxK);                  // 128 words
-    L.chain_tab = lds + 3 * kMaxK;
-    L.vtab = lds + 4 * kMaxK;
-    L.cum_tab = lds + 5 * kMaxK;
-    L.predbit_tab = lds + 6 * kMaxK;
-    L.depbit_tab = lds + 7 * kMaxK;
-    uint32_t *base = lds + 12 * kMaxK;
+    L.tt_tab = (uint4 *)lds;                                  // 128 words
+    L.type_tab = (uint4 *)(lds + 4 * kMaxK);                  // 128 words
+    L.chain_tab = lds + 8 * kMaxK;
+    L.vtab = lds + 9 * kMaxK;
+    L.cum_tab = lds + 10 * kMaxK;
+    L.predbit_tab = lds + 11 * kMaxK;
+    L.depbit_tab = lds + 12 * kMaxK;
+    uint32_t *base = lds + kFastTableWords;
     L.rec = (uint4 *)base;
     // the sweep state is only used once the build is over: it shares the records' space when it fits
     const int ntok = P.nslots - P.D;
     const bool share = P.D * 2 + ntok <= DM * 4;
     uint32_t *sweep_base = share ? base : base + DM * kWave * 4;
-    L.drec = (uint2 *)sweep_base;
-    L.tok = sweep_base + P.D * kWave * 2;
+    L.dfree = sweep_base;
+    L.tok = sweep_base + P.D * kWave;
+    L.dcnt = sweep_base + P.nslots * kWave;
     if (lane < kMaxK) {
         const uint32_t inf = P.info_loc[lane];
-        L.tt_tab[lane] = make_uint2((uint32_t)P.t_loc[lane], ((((inf >> 12) & 63u) - (uint32_t)P.D) << 8));
+        L.tt_tab[lane] = make_uint4((uint32_t)P.t_loc[lane], ((((inf >> 12) & 63u) - (uint32_t)P.D) << 8),
+                                    ((uint32_t)lane >> 2) * (kWave * 4u), 4u * ((uint32_t)lane & 3u));
         {
             const uint32_t su = inf & 63u, dev = (uint32_t)lane >> 2, y = (uint32_t)lane & 3u;
             const int32_t m = (int32_t)(inf << 6) >> 24;
@@ -1128,7 +1152,7 @@ static size_t fast_lds_bytes(const KParams &kp)
 {
     const int ntok = kp.nslots - kp.D;
     const bool share = kp.D * 2 + ntok <= fast_dm(kp) * 4;
-    return (size_t)12 * kMaxK * 4 + (size_t)fast_dm(kp) * kWave * 16 + (share ? 0 : (size_t)(kp.D * 2 + ntok) * kWave * 4);
+    return (size_t)kFastTableWords * 4 + (size_t)fast_dm(kp) * kWave * 16 + (share ? 0 : (size_t)(kp.D * 2 + ntok) * kWave * 4);
 }
 
 LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
