@@ -108,7 +108,8 @@ constexpr size_t kWsListOff = kWsRetryOff + (size_t)kWsRetryCap * 8;   // candid
 constexpr uint32_t kWsListCap = 1u << 16;
 constexpr size_t kWsBlockRecOff = kWsListOff + (size_t)kWsListCap * 8;
 constexpr int kDeferBlocks = 64;                                // grid of the deferred pass
-constexpr int kFirstPassTries = 3;                              // sweeps before a candidate goes to the retry list
+constexpr int kFirstPassTries = 2;                              // sweeps before a candidate goes to the retry list
+constexpr uint64_t kMaxPerLaunch = 1ull << 24;                  // candidates per pass of the kernels
 constexpr int kRetryTries = 8;                                  // ... and before the general kernel gets it
 
 static_assert(sizeof(KParams) <= kWsTablesOff - kWsParamsOff, "parameter block must fit its workspace slot");

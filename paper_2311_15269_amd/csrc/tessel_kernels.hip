@@ -1233,11 +1233,19 @@ int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int
     hipStream_t st = (hipStream_t)stream;
     BlockRec *recs = (BlockRec *)((char *)ws + kWsBlockRecOff);
     DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
-    int n = launch_pass(kp, first, count, ws, num_cus, recs, nullptr, nullptr, false, st);
-    if (n < 0) return -n;
-    if (n == 0) return 0;
-    hipLaunchKernelGGL(merge_kernel, dim3(1), dim3(kWave), 0, st, recs, n, res);
-    return (int)hipGetLastError();
+    // pieces of at most kMaxPerLaunch candidates, so that the lists of unfinished candidates stay small
+    for (uint64_t done = 0; done < count;) {
+        const uint64_t piece = count - done < kMaxPerLaunch ? count - done : kMaxPerLaunch;
+        int n = launch_pass(kp, first + done, piece, ws, num_cus, recs, nullptr, nullptr, false, st);
+        if (n < 0) return -n;
+        if (n > 0) {
+            hipLaunchKernelGGL(merge_kernel, dim3(1), dim3(kWave), 0, st, recs, n, res);
+            int rc = (int)hipGetLastError();
+            if (rc) return rc;
+        }
+        done += piece;
+    }
+    return 0;
 }
 
 int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *ws, int num_cus,
@@ -1245,10 +1253,16 @@ int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *cod
 {
     hipStream_t st = (hipStream_t)stream;
     DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
-    int n = launch_pass(kp, first, count, ws, num_cus, nullptr, code, peak, general, st);
-    if (n < 0) return -n;
-    hipLaunchKernelGGL(clear_defer_kernel, dim3(1), dim3(1), 0, st, res);
-    return (int)hipGetLastError();
+    for (uint64_t done = 0; done < count;) {
+        const uint64_t piece = count - done < kMaxPerLaunch ? count - done : kMaxPerLaunch;
+        int n = launch_pass(kp, first + done, piece, ws, num_cus, nullptr, code + done, peak ? peak + done : nullptr, general, st);
+        if (n < 0) return -n;
+        hipLaunchKernelGGL(clear_defer_kernel, dim3(1), dim3(1), 0, st, res);
+        int rc = (int)hipGetLastError();
+        if (rc) return rc;
+        done += piece;
+    }
+    return 0;
 }
 
 int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream)
