@@ -801,25 +801,27 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
     const int total = C.total;
     bool building = repair || (valid && status == kOk);
     int worst = INT_MIN;             // largest memory prefix over all devices (Eq. 1 [2])
+    const uint32_t lane16 = (uint32_t)lane * 16u;
     FastProgram prog;
     prog.a = 0; prog.b = 0;
     for (int wi = 0; wi < C.nwords; wi++) {          // one program word = six blocks
         if (!repair && __ballot(building) == 0) break;
         uint32_t acc = 0;
-        const int nj = min(6, total - wi * 6);
+        const int nj = __builtin_amdgcn_readfirstlane(min(6, total - wi * 6));
 #pragma unroll 1
         for (int j = 0; j < nj; j++) {
             const uint32_t hm = R & HM;
             const uint32_t sel = hm ? hm : (repair ? R : 0u);
             if (!repair && building && sel == 0) { status = kDeadlock; building = false; }
             const uint32_t b = (uint32_t)__builtin_ctz(sel | 0x80000000u);
-            const uint32_t d4 = repair ? min(b & 28u, 4u * (DM - 1)) : building ? b & 28u : 0u;    // 4 * device
-            uint4 *rp = L.rec + ((d4 >> 2) * kWave + lane);
+            uint32_t d4 = repair ? min(b & 28u, 4u * (DM - 1)) : building ? b & 28u : 0u;    // 4 * device
+            TESSEL_PIN(d4);
+            uint4 *rp = (uint4 *)((char *)L.rec + ((d4 << 8) + lane16));
             uint4 a = *rp;
             TESSEL_PIN(a.x); TESSEL_PIN(a.y); TESSEL_PIN(a.z); TESSEL_PIN(a.w);
-            // earliest remaining entry of the device whose type is allowed (all types when its head runs):
-            // a 4-way multiplexer keyed by the two planes
-            const int r4 = (int)((hm ? 0xFFFFFFFFu : R) >> d4);
+            // earliest remaining entry of the device whose type is runnable: a 4-way multiplexer keyed by the two
+            // planes.  (When the device was picked for its runnable head this is the head: nothing precedes it.)
+            const int r4 = (int)(R >> d4);
             const uint32_t r0 = (uint32_t)__builtin_amdgcn_sbfe(r4, 0, 1), r1 = (uint32_t)__builtin_amdgcn_sbfe(r4, 1, 1),
                            r2 = (uint32_t)__builtin_amdgcn_sbfe(r4, 2, 1), r3 = (uint32_t)__builtin_amdgcn_sbfe(r4, 3, 1);
             const uint32_t gate = bfi(a.y, bfi(a.x, r3, r2), bfi(a.x, r1, r0));
@@ -837,7 +839,8 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
             const uint32_t hm_new = (HM & ~(15u << d4)) | (1u << (d4 + y2));
             // one waiting micro-batch is consumed; the type stays runnable while another one waits and
             // entries of it remain; its consumer gets one more and becomes runnable
-            const uint32_t rest = alive & ~(a.x ^ ly) & ~(a.y ^ hy);        // remaining entries of the same type
+            // remaining entries of the same type: alive & ~(lo ^ ly) & ~(hi ^ hy)
+            const uint32_t rest = __builtin_amdgcn_bitop3_b32(__builtin_amdgcn_bitop3_b32(alive, a.x, ly, 0x90), a.y, hy, 0x90);
             const uint32_t more = (a.w >> (4u * y)) & 14u;                    // two or more were waiting
             const uint32_t onec = 1u << c;
             const uint32_t x_new = X | (rest == 0 ? onec : 0u);
