@@ -672,6 +672,17 @@ __device__ __forceinline__ uint32_t even_bits(uint64_t x)
 }
 
 // MODE: 0 exhaustive spaces, 1 sampled without repair, 2 sampled with repair
+// even bits of a 32-bit word, compacted (bit 2p -> bit p)
+__device__ __forceinline__ uint32_t even_bits32(uint32_t x)
+{
+    x &= 0x55555555u;
+    x = (x | (x >> 1)) & 0x33333333u;
+    x = (x | (x >> 2)) & 0x0F0F0F0Fu;
+    x = (x | (x >> 4)) & 0x00FF00FFu;
+    x = (x | (x >> 8)) & 0x0000FFFFu;
+    return x;
+}
+
 template <int DM, int VM, int MODE>
 __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<DM> &C, uint64_t idx, const FastLds &L, int lane,
                                              int &period, int &peak_max, bool valid, uint32_t &nsweeps_used)
@@ -699,21 +710,26 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
             // bytes: 0x60 <= 0x80 - t + digit < 0xA0).
             const uint32_t c1 = C.ntd[d] > 0 ? NR : 0u, c2 = c1 + (C.ntd[d] > 1 ? NR : 0u), c3 = c2 + (C.ntd[d] > 2 ? NR : 0u);
             uint32_t tq = 0x808080u - (c1 | (c2 << 8) | (c3 << 16));
-            uint32_t lo = 0, hi = 0;
-            auto pick = [&](uint32_t draw, uint32_t left, uint32_t pos) {
-                const uint32_t digit = __umul24(draw, left) >> 16;
+            // the 2-bit symbols are collected 16 to a word and split into the two planes at the end
+            uint32_t acc[2] = {0u, 0u};
+            auto pick = [&](uint32_t draw, uint32_t left, uint32_t &into, uint32_t at) {
+                const uint32_t digit = (uint32_t)(((uint64_t)draw * (uint64_t)((left << 16) & 0xFFFFFFu)) >> 32);    // (draw * left) >> 16 as a
+                                                                                                       // 24-bit high multiply (left <= 32)
                 const uint32_t ge = (__umul24(digit, 0x010101u) + tq) & 0x808080u;
-                tq += 0x010101u - (ge >> 7);                     // a threshold above the digit loses one block
-                // symbol = number of thresholds at or below the digit; they are ordered, so its low bit is the
-                // parity of the three tests and its high bit the middle one
-                lo |= ((uint32_t)__builtin_popcount(ge) & 1u) << pos;
-                hi |= ((ge >> 15) & 1u) << pos;
+                tq += (ge >> 7) ^ 0x010101u;                     // a threshold above the digit loses one block
+                into |= (uint32_t)__builtin_popcount(ge) << (2u * at);   // symbol = number of thresholds at or below the digit
             };
-            for (uint32_t pos = 0; pos < n; pos += 2) {
-                const uint32_t word = stream_word(ka, kb, (kDrawOrdBase + 32u * (uint32_t)d + pos) >> 1);
-                pick(word & 0xFFFFu, n - pos, pos);
-                if (pos + 1 < n) pick(word >> 16, n - pos - 1u, pos + 1u);
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const uint32_t from = 16u * (uint32_t)h, to = min(n, from + 16u);
+                for (uint32_t pos = from; pos < to; pos += 2) {
+                    const uint32_t word = stream_word(ka, kb, (kDrawOrdBase + 32u * (uint32_t)d + pos) >> 1);
+                    pick(word & 0xFFFFu, n - pos, acc[h], pos - from);
+                    if (pos + 1 < n) pick(word >> 16, n - pos - 1u, acc[h], pos + 1u - from);
+                }
             }
+            const uint32_t lo = even_bits32(acc[0]) | (even_bits32(acc[1]) << 16);
+            const uint32_t hi = even_bits32(acc[0] >> 1) | (even_bits32(acc[1] >> 1) << 16);
             plo[d] = lo; phi[d] = hi; nlen[d] = (int)n;
         }
         if (C.has_fixed)
