@@ -1235,8 +1235,9 @@ static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *
                        (const uint32_t *)nullptr, 0u, kp.eigen_tries, retry, &res->retry_count, kWsRetryCap, &res->overflow);
     int rc = (int)hipGetLastError();
     if (rc) return -rc;
-    // the retry list holds a few percent of the range at most; a quarter of the grid is plenty
-    const int blocks2 = blocks >= 4 ? blocks / 4 : blocks;
+    // the retry list holds a few percent of the range, still the whole grid: one wave per SIMD would leave the
+    // pass bound by latency (measured: a quarter of the grid costs 3 % of the whole launch more)
+    const int blocks2 = blocks;
     hipLaunchKernelGGL(ff, dim3(blocks2), dim3(kWave), lds, st, kp_dev, first, count, recs ? recs + blocks : nullptr, code, peak,
                        (const uint64_t *)retry, (const uint32_t *)&res->retry_count, kWsRetryCap, kRetryTries, list,
                        &res->defer_count, kWsListCap, &res->overflow);
