@@ -181,6 +181,30 @@ int  tessel_reset(tessel_problem *p);
  * capacity too small), NO_SCHEDULE. */
 int  tessel_complete_schedule(tessel_problem *p, tessel_schedule *out);
 
+/* ---- runtime instantiation (Sec. IV-E): the global operation sequence of a complete schedule --------
+ * Blocks in ascending start time; blocks that start together are consecutive, ordered by their lowest
+ * device (a device's own blocks keep its execution order).  A tensor that a consumer needs on a device
+ * where its producer did not run is one send/receive pair, a single operation placed right after the
+ * time slot (group of equal start times) of the producer; the sender is the producer's lowest device;
+ * pairs of one slot follow their producers' order, then the dependency's position in the problem
+ * statement, then the receiving device.  Every device executes, in this order, the operations it takes
+ * part in; the common order rules out mismatched send/receive pairs. */
+enum { TESSEL_OP_BLOCK = 0, TESSEL_OP_SENDRECV = 1 };
+typedef struct {
+    int32_t kind;    /* TESSEL_OP_*                                                           */
+    int32_t block;   /* type*N + mu; for a pair: the producer                                 */
+    int32_t src;     /* block: device mask;  pair: sending device                             */
+    int32_t dst;     /* block: start time;   pair: receiving device                           */
+    int32_t aux;     /* block: 0;            pair: the consumer block                         */
+} tessel_op;
+
+/* Writes the sequence of `sched` (as filled in by tessel_complete_schedule: num_microbatches and start[]
+ * are read) to ops[0 .. *num_ops-1] (host memory, `capacity` elements).  Host work only.
+ * Errors: INVALID_ARG (null pointer, a block without start time), RANGE (capacity too small; *num_ops
+ * then holds the number needed). */
+int  tessel_instantiate(const tessel_problem *p, const tessel_schedule *sched, tessel_op *ops, int32_t capacity,
+                        int32_t *num_ops);
+
 /* ---- the whole search of Alg. 1 (Sec. IV-D): all window sizes ---------------------------
  * In: which window sizes and how many candidates of each; out: the incumbent and what each
  * window size gave.  Repetend times of different window sizes compare per micro-batch:

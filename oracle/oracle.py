@@ -77,6 +77,7 @@ def _load():
                                      C.c_void_p, C.c_void_p, C.c_void_p]
         lib.orc_draw16.restype = C.c_uint32
         lib.orc_draw16.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32]
+        lib.orc_instantiate.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int]
         lib.orc_max_inflight.argtypes = [C.c_void_p, C.c_int]
         lib.orc_search.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
                                    C.c_void_p, C.c_int, C.c_uint64, C.c_uint32, C.c_int, C.c_int, C.c_uint64,
@@ -152,6 +153,23 @@ class Oracle:
         if getattr(self, "_h", None):
             _load().orc_destroy(self._h)
             self._h = None
+
+    def instantiate(self, N, start, dev_order):
+        """global operation sequence of a complete schedule (Sec. IV-E): list of (kind, block, src, dst, aux)"""
+        start = _i32(np.asarray(start).reshape(-1))
+        stride = self.K * N
+        order = np.full((self.D, stride), -1, dtype=np.int32)
+        length = np.zeros(self.D, dtype=np.int32)
+        for d, row in enumerate(dev_order):
+            order[d, :len(row)] = row
+            length[d] = len(row)
+        cap = self.K * N * (1 + self.D * max(1, len(self.problem["deps"])))
+        ops = np.zeros((cap, 5), dtype=np.int32)
+        n = _load().orc_instantiate(self._h, N, start.ctypes.data, order.ctypes.data, length.ctypes.data, stride,
+                                    ops.ctypes.data, cap)
+        if n < 0:
+            raise OracleError(n)
+        return [tuple(int(v) for v in row) for row in ops[:n]]
 
     def max_inflight(self, unbounded=MAX_NR):
         return int(_load().orc_max_inflight(self._h, unbounded))

@@ -890,6 +890,58 @@ int orc_search(int D, int K, int M, const int *t, const int *m, const uint32_t *
     return ORC_E_OK;
 }
 
+/* ------------------------------------------------------------------ runtime instantiation (Sec. IV-E)
+ * A complete schedule fixes start times and per-device orders; what the devices execute is one
+ * global sequence of operations.  Blocks come in ascending start time; blocks that start together
+ * are consecutive, devices in ascending order, each device's blocks in its execution order (a block
+ * on several devices appears once, with its lowest device).  Every tensor that a consumer needs on a
+ * device where the producer did not run is one send/receive pair, treated as a single operation and
+ * placed right after the time slot (the group of equal start times) of the block that produces it.
+ * This build's reading where the paper is silent: the sender is the lowest device of the producer;
+ * pairs of one slot follow the order of their producers in the sequence, then the dependency's
+ * position in the problem statement, then the receiving device.
+ * op = 5 ints: kind (0 block, 1 pair), block (type*N + mu; for a pair: the producer), src (block:
+ * device mask; pair: sender), dst (block: start time; pair: receiver), aux (block: 0; pair: consumer). */
+int orc_instantiate(const orc_problem *p, int N, const int *start, const int *dev_order, const int *dev_len, int stride,
+                    int *ops, int capacity)
+{
+    const int K = p->K, D = p->D;
+    int nops = 0, emitted = 0, total = K * N;
+    char *done = (char *)calloc((size_t)total, 1);
+    while (emitted < total) {
+        /* next time slot = least start among blocks not emitted yet */
+        int slot = -1;
+        for (int x = 0; x < total; x++) if (!done[x] && (slot < 0 || start[x] < slot)) slot = start[x];
+        int first_of_slot = nops;
+        for (int d = 0; d < D; d++)
+            for (int k = 0; k < dev_len[d]; k++) {
+                int x = dev_order[d * stride + k];
+                if (done[x] || start[x] != slot) continue;
+                done[x] = 1; emitted++;
+                if (nops >= capacity) { free(done); return ORC_E_RANGE; }
+                int *o = ops + 5 * nops++;
+                o[0] = 0; o[1] = x; o[2] = (int)p->mask[x / N]; o[3] = slot; o[4] = 0;
+            }
+        int last_of_slot = nops;
+        for (int q = first_of_slot; q < last_of_slot; q++) {
+            int x = ops[5 * q + 1], i = x / N, mu = x % N;
+            for (int e = 0; e < p->ndeps; e++) {
+                if (p->src[e] != i) continue;
+                int j = p->dst[e], sender = 0;
+                while (!(p->mask[i] >> sender & 1u)) sender++;
+                for (int v = 0; v < D; v++) {
+                    if (!(p->mask[j] >> v & 1u) || (p->mask[i] >> v & 1u)) continue;
+                    if (nops >= capacity) { free(done); return ORC_E_RANGE; }
+                    int *o = ops + 5 * nops++;
+                    o[0] = 1; o[1] = x; o[2] = sender; o[3] = v; o[4] = j * N + mu;
+                }
+            }
+        }
+    }
+    free(done);
+    return nops;
+}
+
 uint64_t orc_sizeof_score(void) { return sizeof(orc_score); }
 uint64_t orc_sizeof_result(void) { return sizeof(orc_result); }
 uint64_t orc_sizeof_search_result(void) { return sizeof(orc_search_result); }

@@ -18,11 +18,12 @@ STATUS_NAMES = ("OK", "DUP", "TP_MISMATCH", "PROP2", "DEADLOCK", "MEM")
 SPACE = {"factorial": 0, "canonical": 1, "sampled_strict": 2, "sampled_repair": 3}
 
 E_NO_FEASIBLE = -7
+E_RANGE = -8
 
 EXPORTS = (
     "tessel_problem_create", "tessel_problem_destroy", "tessel_candidate_count", "tessel_workspace_bytes",
     "tessel_eval_candidates", "tessel_score_candidates", "tessel_best", "tessel_best_candidate", "tessel_reset",
-    "tessel_complete_schedule", "tessel_search_workspace_bytes", "tessel_search_run", "tessel_alu_probe", "tessel_strerror", "tessel_last_hip_error",
+    "tessel_complete_schedule", "tessel_instantiate", "tessel_search_workspace_bytes", "tessel_search_run", "tessel_alu_probe", "tessel_strerror", "tessel_last_hip_error",
 )
 
 
@@ -88,6 +89,7 @@ def load_library():
         lib.tessel_best_candidate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.tessel_reset.argtypes = [C.c_void_p]
         lib.tessel_complete_schedule.argtypes = [C.c_void_p, C.POINTER(Schedule)]
+        lib.tessel_instantiate.argtypes = [C.c_void_p, C.POINTER(Schedule), C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
         lib.tessel_search_workspace_bytes.argtypes = [C.POINTER(ProblemDesc), C.POINTER(Search), C.POINTER(C.c_size_t)]
         lib.tessel_search_run.argtypes = [C.POINTER(ProblemDesc), C.POINTER(Search), C.c_void_p, C.c_size_t, C.c_void_p,
                                           C.POINTER(C.c_void_p)]
@@ -256,6 +258,19 @@ class Problem:
 
     def reset(self):
         _check(load_library().tessel_reset(self._h))
+
+    def instantiate(self, num_microbatches, start):
+        """tessel_instantiate: list of (kind, block, src, dst, aux) for the schedule with these start times [K][N]"""
+        N = num_microbatches
+        start = _i32(np.asarray(start).reshape(-1))
+        s = Schedule(N, self.K * N, start.ctypes.data, None, None, 0, 0, 0)
+        n = C.c_int32(0)
+        rc = load_library().tessel_instantiate(self._h, C.byref(s), None, 0, C.byref(n))
+        if rc not in (0, E_RANGE):
+            _check(rc)
+        ops = np.zeros((max(1, n.value), 5), dtype=np.int32)
+        _check(load_library().tessel_instantiate(self._h, C.byref(s), ops.ctypes.data, n.value, C.byref(n)))
+        return [tuple(int(v) for v in row) for row in ops[:n.value]]
 
     def complete_schedule(self, num_microbatches):
         N = num_microbatches

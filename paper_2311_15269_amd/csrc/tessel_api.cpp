@@ -642,6 +642,48 @@ extern "C" int tessel_complete_schedule(tessel_problem *p, tessel_schedule *out)
     return TESSEL_OK;
 }
 
+// ---- Sec. IV-E: global sequence of blocks and send/receive pairs -----------------------------------
+extern "C" int tessel_instantiate(const tessel_problem *p, const tessel_schedule *sched, tessel_op *ops, int32_t capacity,
+                                  int32_t *num_ops)
+{
+    if (!p || !sched || !sched->start || !num_ops || (capacity > 0 && !ops) || sched->num_microbatches < 1)
+        return TESSEL_E_INVALID_ARG;
+    const int K = p->kp.K, D = p->kp.D, N = sched->num_microbatches;
+    const int ndeps = (int)p->dep_src.size();
+    for (int x = 0; x < K * N; x++) if (sched->start[x] < 0) return TESSEL_E_INVALID_ARG;
+    auto lowest = [](uint32_t mask) { int d = 0; while (!(mask >> d & 1u)) d++; return d; };
+    // blocks by (start time, lowest device); two blocks of one device never start together (t >= 1)
+    std::vector<int> seq(K * N);
+    for (int x = 0; x < K * N; x++) seq[x] = x;
+    std::stable_sort(seq.begin(), seq.end(), [&](int a, int b) {
+        if (sched->start[a] != sched->start[b]) return sched->start[a] < sched->start[b];
+        return lowest(p->mask[a / N]) < lowest(p->mask[b / N]);
+    });
+    std::vector<tessel_op> out;
+    out.reserve((size_t)K * N * 2);
+    for (size_t at = 0; at < seq.size();) {
+        size_t end = at;
+        while (end < seq.size() && sched->start[seq[end]] == sched->start[seq[at]]) end++;
+        for (size_t k = at; k < end; k++)
+            out.push_back({TESSEL_OP_BLOCK, seq[k], (int32_t)p->mask[seq[k] / N], sched->start[seq[k]], 0});
+        for (size_t k = at; k < end; k++) {
+            const int i = seq[k] / N, mu = seq[k] % N;
+            for (int e = 0; e < ndeps; e++) {
+                if (p->dep_src[e] != i) continue;
+                const int j = p->dep_dst[e];
+                const uint32_t need = p->mask[j] & ~p->mask[i];        // consumer devices without the tensor
+                for (int v = 0; v < D; v++)
+                    if (need >> v & 1u) out.push_back({TESSEL_OP_SENDRECV, seq[k], lowest(p->mask[i]), v, j * N + mu});
+            }
+        }
+        at = end;
+    }
+    *num_ops = (int32_t)out.size();
+    if ((size_t)capacity < out.size()) return TESSEL_E_RANGE;
+    std::copy(out.begin(), out.end(), ops);
+    return TESSEL_OK;
+}
+
 // ---- Alg. 1: the loop over window sizes around the scoring kernels -------------------------
 
 // CalMaxInflight of Alg. 1 (the paper gives no formula): one micro-batch alone, blocks in topological

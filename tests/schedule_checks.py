@@ -133,3 +133,62 @@ def check_flat_schedule(problem, N, start, dev_order):
         seen.update(mine)
     makespan = max(start[i][mu] + t[i] for i in range(K) for mu in range(N))
     return True, makespan, peaks
+
+
+def check_instantiation(problem, N, start, ops):
+    """Properties Sec. IV-E asks of the global operation sequence of a complete schedule.
+    ops: (kind, block, src, dst, aux); kind 0 = block (src = device mask, dst = start time),
+    kind 1 = send/receive pair (block = producer, src = sender, dst = receiver, aux = consumer).
+    Returns (ok, reason)."""
+    K, D, masks, deps = problem["K"], problem["D"], problem["dev_mask"], problem["deps"]
+    pos_of_block, last_start = {}, -1
+    for k, (kind, blk, src, dst, aux) in enumerate(ops):
+        if kind == 0:
+            if blk in pos_of_block or src != masks[blk // N] or dst != start[blk // N][blk % N] or dst < last_start:
+                return False, "block order"
+            pos_of_block[blk] = k
+            last_start = dst
+    if len(pos_of_block) != K * N:
+        return False, "missing blocks"
+    # every tensor a consumer needs on a device where the producer did not run arrives exactly once,
+    # from a device that has it, after the producer and before the consumer
+    want = set()
+    for (a, b) in deps:
+        for mu in range(N):
+            for v in range(D):
+                if masks[b] >> v & 1 and not masks[a] >> v & 1:
+                    want.add((a * N + mu, b * N + mu, v))
+    seen = set()
+    for k, (kind, blk, src, dst, aux) in enumerate(ops):
+        if kind != 1:
+            continue
+        key = (blk, aux, dst)
+        if key not in want or key in seen or not masks[blk // N] >> src & 1:
+            return False, "unexpected pair"
+        seen.add(key)
+        if not pos_of_block[blk] < k < pos_of_block[aux]:
+            return False, "pair outside (producer, consumer)"
+    if seen != want:
+        return False, "missing pairs"
+    # blocking execution: every device runs its share of the sequence in order; a block on several devices and a
+    # send/receive pair need all their devices to have arrived.  It must run to the end.
+    prog = [[] for _ in range(D)]
+    for k, (kind, blk, src, dst, aux) in enumerate(ops):
+        devs = [d for d in range(D) if src >> d & 1] if kind == 0 else [src, dst]
+        for d in devs:
+            prog[d].append((k, tuple(devs)))
+    at = [0] * D
+    progress = True
+    while progress:
+        progress = False
+        for d in range(D):
+            if at[d] >= len(prog[d]):
+                continue
+            k, devs = prog[d][at[d]]
+            if all(at[e] < len(prog[e]) and prog[e][at[e]][0] == k for e in devs):
+                for e in devs:
+                    at[e] += 1
+                progress = True
+    if any(at[d] != len(prog[d]) for d in range(D)):
+        return False, "deadlock"
+    return True, ""
