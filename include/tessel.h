@@ -217,7 +217,7 @@ typedef struct {
                                           launches; 0 = 2^24                                              */
     int32_t  inflights;           /* out: CalMaxInflight: min over devices of floor(M / hold_d), hold_d =
                                           what one micro-batch alone holds on d at most (blocks in
-                                          topological order, smallest type id first); TESSEL_MAX_NR if
+                                          topological order, smallest type id first); max_nr if
                                           nothing holds memory                                            */
     int32_t  lower_bound;         /* out: GetLowerBound: max_d sum of t on d, per micro-batch             */
     int32_t  nr_tried;            /* out: window sizes entered                                            */

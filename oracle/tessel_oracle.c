@@ -869,7 +869,7 @@ int orc_search(int D, int K, int M, const int *t, const int *m, const uint32_t *
         if (!p) return err;
         if (NR == 1) {
             out->lower_bound = p->LB;                        /* N_R = 1: LB is the per-micro-batch bound */
-            out->inflights = orc_max_inflight(p, ORC_MAX_NR);
+            out->inflights = orc_max_inflight(p, max_nr);          /* no memory held anywhere: no bound beyond max_nr */
             if (use_inflight_bound && out->inflights < limit) limit = out->inflights;
             if (limit < 1) { orc_destroy(p); return ORC_E_OK; }
         }

@@ -688,7 +688,7 @@ extern "C" int tessel_instantiate(const tessel_problem *p, const tessel_schedule
 
 // CalMaxInflight of Alg. 1 (the paper gives no formula): one micro-batch alone, blocks in topological
 // order with the smallest type id first, holds at most hold_d on device d; floor(M / hold_d) of them fit.
-static int max_inflight(const tessel_problem_desc *desc)
+static int max_inflight(const tessel_problem_desc *desc, int unbounded)
 {
     const int K = desc->num_block_types;
     std::vector<int> indeg(K, 0), done(K, 0), topo;
@@ -700,7 +700,7 @@ static int max_inflight(const tessel_problem_desc *desc)
         done[pick] = 1; topo.push_back(pick);
         for (int e = 0; e < desc->num_deps; e++) if (desc->dep_src[e] == pick) indeg[desc->dep_dst[e]]--;
     }
-    int best = TESSEL_MAX_NR;
+    int best = unbounded;
     for (int d = 0; d < desc->num_devices; d++) {
         int run = 0, hold = 0;
         for (int i : topo) if (desc->dev_mask[i] >> d & 1u) { run += desc->mem[i]; hold = std::max(hold, run); }
@@ -720,7 +720,7 @@ extern "C" int tessel_search_workspace_bytes(const tessel_problem_desc *desc, co
         tessel_problem *p = nullptr;
         int rc = tessel_problem_create(&d, &p);
         if (rc) return rc;
-        if (nr == 1 && in->use_inflight_bound) limit = std::max(1, std::min(limit, max_inflight(desc)));
+        if (nr == 1 && in->use_inflight_bound) limit = std::max(1, std::min(limit, max_inflight(desc, in->max_nr)));
         size_t b = 0;
         rc = tessel_workspace_bytes(p, &b);
         tessel_problem_destroy(p);
@@ -750,7 +750,7 @@ extern "C" int tessel_search_run(const tessel_problem_desc *desc, tessel_search 
         if (rc) return rc;
         if (nr == 1) {
             io->lower_bound = p->kp.LB;
-            io->inflights = max_inflight(desc);
+            io->inflights = max_inflight(desc, io->max_nr);
             if (io->use_inflight_bound) limit = std::min(limit, io->inflights);
             if (limit < 1) { tessel_problem_destroy(p); break; }
         }

@@ -35,6 +35,9 @@ CASES = [
     ("3dev-tight-no-bound", linear(3, 1, 2, 2), 3, 1 << 30, 1000, False),
     ("3dev-times-2-3", linear(3, 2, 3, 3), 8, 1 << 30, 0, True),
     ("1dev", W.pipeline_problem([0], [3], [5], 1, 1, 1, "canonical"), 4, 1 << 20, 0, True),
+    ("inference-4", {"name": "inference-4", "D": 4, "K": 4, "NR": 1, "M": 1, "t": [2, 1, 3, 2], "m": [0] * 4,
+                     "dev_mask": [1, 2, 4, 8], "deps": [(0, 1), (1, 2), (2, 3)], "space": "canonical", "seed": 0,
+                     "lead_step_q16": 0}, 5, 1 << 20, 0, True),
     ("cfg3-repair", W.config3(), 4, 20000, 4096, True),
     ("cfg3-strict", dict(W.config3(), space="sampled_strict"), 3, 5000, 0, True),
     ("cfg4-tp", dict(W.config4(), M=9), 4, 6000, 2048, True),

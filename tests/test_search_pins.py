@@ -122,3 +122,19 @@ def test_bubble_rate_against_window_size_without_memory_limit(p, tf, tb):
     want = [max(nr, p) * (tf + tb) for nr in range(1, p + 1)]
     assert r["period_nr"][:p] == want
     assert r["best_nr"] == p and r["early_exit"]
+
+
+def inference_pipeline(p, tf):
+    """forward blocks only, nothing held (Sec. VI: schedules for inference drop the backward blocks)"""
+    return {"name": "inference-%d" % p, "D": p, "K": p, "NR": 1, "M": 1, "t": [tf] * p, "m": [0] * p,
+            "dev_mask": [1 << s for s in range(p)], "deps": [(s, s + 1) for s in range(p - 1)],
+            "space": "canonical", "seed": 0, "lead_step_q16": 0}
+
+
+@pytest.mark.parametrize("p", [2, 3, 4])
+def test_inference_pipeline_needs_one_micro_batch_per_window(p):
+    """Without backward blocks neighbouring windows overlap freely (negative W_R of Eq. 4): the window of one
+    micro-batch already repeats every tf, the bound; memory does not limit the window size."""
+    r = O.search(inference_pipeline(p, 2), 5, 1 << 20)
+    assert r["inflights"] == 5
+    assert (r["best_nr"], r["best_period"], r["best_index"], r["early_exit"]) == (1, 2, 0, True)
