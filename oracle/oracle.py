@@ -77,6 +77,10 @@ def _load():
                                      C.c_void_p, C.c_void_p, C.c_void_p]
         lib.orc_draw16.restype = C.c_uint32
         lib.orc_draw16.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32]
+        lib.orc_complete_jitter.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_uint64,
+                                            C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.orc_completion_scores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                              C.c_uint64, C.c_uint64, C.c_int, C.c_void_p, C.POINTER(C.c_uint64)]
         lib.orc_instantiate.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int]
         lib.orc_max_inflight.argtypes = [C.c_void_p, C.c_int]
         lib.orc_search.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
@@ -153,6 +157,32 @@ class Oracle:
         if getattr(self, "_h", None):
             _load().orc_destroy(self._h)
             self._h = None
+
+    def complete_jitter(self, leads, orders, N, ordinal, J):
+        """schedule of completion candidate `ordinal` (jitter amplitude J); ordinal 0 = the plain greedy one"""
+        length, seq = self._pack(orders)
+        leads = _i32(leads)
+        start = np.full(self.K * N, -1, dtype=np.int32)
+        dev_order = np.full((self.D, self.K * N), -1, dtype=np.int32)
+        dev_len = np.zeros(self.D, dtype=np.int32)
+        rc = _load().orc_complete_jitter(self._h, leads.ctypes.data, length.ctypes.data, seq.ctypes.data, self.stride, N,
+                                         ordinal, J, start.ctypes.data, dev_order.ctypes.data, dev_len.ctypes.data)
+        if rc < 0:
+            raise OracleError(rc)
+        return {"makespan": rc, "start": start.reshape(self.K, N),
+                "dev_order": [dev_order[d, :dev_len[d]].tolist() for d in range(self.D)]}
+
+    def completion_scores(self, leads, orders, N, first, count, J):
+        """(makespans int32[count] with INT32_MAX = no schedule, best makespan, lowest ordinal attaining it)"""
+        length, seq = self._pack(orders)
+        leads = _i32(leads)
+        out = np.zeros(count, dtype=np.int32)
+        best = C.c_uint64(0)
+        rc = _load().orc_completion_scores(self._h, leads.ctypes.data, length.ctypes.data, seq.ctypes.data, self.stride,
+                                           N, first, count, J, out.ctypes.data, C.byref(best))
+        if rc < 0 and rc != -10:
+            raise OracleError(rc)
+        return out, (rc if rc >= 0 else None), int(best.value)
 
     def instantiate(self, N, start, dev_order):
         """global operation sequence of a complete schedule (Sec. IV-E): list of (kind, block, src, dst, aux)"""

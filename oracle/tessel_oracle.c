@@ -814,6 +814,121 @@ int orc_complete(const orc_problem *p, const int *leads, const int *len, const i
 }
 
 
+/* ------------------------------------------------------------------ searched completion
+ * The paper orders warm-up and cool-down with a time-optimal solver (Sec. IV-C, Alg. 1); the greedy
+ * rule above is one guess.  This build searches a family of such guesses instead: completion
+ * candidate `ordinal` perturbs the greedy choice.  Per phase every block type offers its lowest
+ * unscheduled micro-batch only (Property 1: blocks of one type run in micro-batch order); an offered
+ * block is eligible when its producer's block of the same micro-batch is scheduled and its memory
+ * delta fits on all its devices; among the eligible the smallest (earliest start + jitter,
+ * micro-batch, type id) is appended at its earliest start.  jitter = 0 for ordinal 0 (the plain
+ * greedy schedule) or when the amplitude J is 0; otherwise (draw * (J + 1)) >> 16 with the 16-bit draw
+ * number type*N + mu of the counter-based stream keyed by (seed + ORC_COMPLETION_KEY, ordinal).
+ * The windows in between are replayed exactly as in orc_complete.  Returns the makespan or an error. */
+#define ORC_COMPLETION_KEY 0x632BE59BD9B4E019ULL
+int orc_complete_jitter(const orc_problem *p, const int *leads, const int *len, const int *seq, int stride, int N,
+                        uint64_t ordinal, int J, int *start, int *dev_order, int *dev_len)
+{
+    const int NR = p->NR, K = p->K, D = p->D;
+    int maxlead = 0;
+    for (int i = 0; i < K; i++) if (leads[i] > maxlead) maxlead = leads[i];
+    int R = (N - maxlead) / NR;
+    if (N < 1 || R < 1 || J < 0 || J > 65535) return ORC_E_RANGE;
+    int *end = (int *)malloc(sizeof(int) * (size_t)K * (size_t)N);
+    int next[ORC_MAX_K];                 /* per type: the next micro-batch to schedule */
+    int freeat[ORC_MAX_D] = {0}, cur[ORC_MAX_D] = {0};
+    for (int i = 0; i < K; i++) next[i] = 0;
+    for (int d = 0; d < D; d++) dev_len[d] = 0;
+    int rc = 0;
+    for (int phase = 0; phase < 3 && rc == 0; phase++) {
+        if (phase == 1) {                /* R windows, replayed in an executable sequence of the device orders */
+            for (int k = 0; k < R && rc == 0; k++) {
+                int pos[ORC_MAX_D] = {0}, left = K * NR;
+                while (left > 0) {
+                    int progressed = 0;
+                    for (int d = 0; d < D; d++) {
+                        if (pos[d] >= len[d]) continue;
+                        int i = seq[d * stride + pos[d]], mu = next[i], ok = 1, est = 0;
+                        for (int dd = 0; dd < D; dd++) if (p->mask[i] >> dd & 1u) {
+                            if (pos[dd] >= len[dd] || seq[dd * stride + pos[dd]] != i) ok = 0;
+                            if (freeat[dd] > est) est = freeat[dd];
+                        }
+                        for (int e = 0; e < p->ndeps && ok; e++) if (p->dst[e] == i) {
+                            if (next[p->src[e]] <= mu) ok = 0;
+                            else if (end[p->src[e] * N + mu] > est) est = end[p->src[e] * N + mu];
+                        }
+                        if (!ok) continue;
+                        start[i * N + mu] = est; end[i * N + mu] = est + p->t[i]; next[i]++;
+                        for (int dd = 0; dd < D; dd++) if (p->mask[i] >> dd & 1u) {
+                            freeat[dd] = est + p->t[i]; cur[dd] += p->m[i]; pos[dd]++;
+                            dev_order[dd * K * N + dev_len[dd]++] = i * N + mu;
+                        }
+                        left--; progressed = 1;
+                    }
+                    if (!progressed) { rc = ORC_E_NO_SCHEDULE; break; }
+                }
+            }
+            continue;
+        }
+        for (;;) {
+            int best_i = -1, best_mu = 0, best_est = 0, best_key = 0, any_left = 0;
+            for (int i = 0; i < K; i++) {
+                int hi = phase == 0 ? leads[i] : N, mu = next[i];
+                if (mu >= hi) continue;
+                any_left = 1;
+                int ok = 1, est = 0;
+                for (int e = 0; e < p->ndeps && ok; e++) if (p->dst[e] == i) {
+                    if (next[p->src[e]] <= mu) ok = 0;
+                    else if (end[p->src[e] * N + mu] > est) est = end[p->src[e] * N + mu];
+                }
+                for (int d = 0; d < D && ok; d++) if (p->mask[i] >> d & 1u) {
+                    if (p->m[i] > 0 && cur[d] + p->m[i] > p->M) ok = 0;
+                    if (freeat[d] > est) est = freeat[d];
+                }
+                if (!ok) continue;
+                int jitter = 0;
+                if (ordinal != 0 && J > 0)
+                    jitter = (int)((draw16(p->seed + ORC_COMPLETION_KEY, ordinal, (uint32_t)(i * N + mu)) * (uint32_t)(J + 1)) >> 16);
+                int key = est + jitter;
+                if (best_i < 0 || key < best_key || (key == best_key && (mu < best_mu || (mu == best_mu && i < best_i)))) {
+                    best_i = i; best_mu = mu; best_est = est; best_key = key;
+                }
+            }
+            if (!any_left) break;
+            if (best_i < 0) { rc = ORC_E_NO_SCHEDULE; break; }
+            start[best_i * N + best_mu] = best_est; end[best_i * N + best_mu] = best_est + p->t[best_i]; next[best_i]++;
+            for (int d = 0; d < D; d++) if (p->mask[best_i] >> d & 1u) {
+                freeat[d] = best_est + p->t[best_i]; cur[d] += p->m[best_i];
+                dev_order[d * K * N + dev_len[d]++] = best_i * N + best_mu;
+            }
+        }
+    }
+    int makespan = 0;
+    if (rc == 0) for (int d = 0; d < D; d++) if (freeat[d] > makespan) makespan = freeat[d];
+    free(end);
+    return rc ? rc : makespan;
+}
+
+/* makespans of completion candidates first .. first+count-1 (INT32_MAX where no schedule exists) and the
+ * lowest ordinal attaining the least one */
+int orc_completion_scores(const orc_problem *p, const int *leads, const int *len, const int *seq, int stride, int N,
+                          uint64_t first, uint64_t count, int J, int32_t *makespan, uint64_t *best_ordinal)
+{
+    int *start = (int *)malloc(sizeof(int) * (size_t)p->K * (size_t)N);
+    int *order = (int *)malloc(sizeof(int) * (size_t)p->D * (size_t)p->K * (size_t)N);
+    int dl[ORC_MAX_D], best = INT32_MAX;
+    *best_ordinal = 0;
+    for (uint64_t k = 0; k < count; k++) {
+        int mk = orc_complete_jitter(p, leads, len, seq, stride, N, first + k, J, start, order, dl);
+        if (mk == ORC_E_RANGE) { free(start); free(order); return mk; }
+        int32_t v = mk < 0 ? INT32_MAX : mk;
+        if (makespan) makespan[k] = v;
+        if (v < best) { best = v; *best_ordinal = first + k; }
+    }
+    free(start); free(order);
+    return best == INT32_MAX ? ORC_E_NO_SCHEDULE : best;
+}
+
 /* ------------------------------------------------------------------ Alg. 1, the whole search
  * CalMaxInflight (Alg. 1; the paper only says "the maximum number of in-flight micro-batches
  * that can be executed within the memory constraints"): this build's reading.  One micro-batch

@@ -611,7 +611,8 @@ __device__ __forceinline__ void reset_sweep_state(const FastConst<DM> &C, const 
 // (device free times, in-flight micro-batch end times).  If after some sweep every live component
 // has grown by the same delta, x is an eigenvector of F and delta is its eigenvalue = the maximum
 // cycle ratio, exactly.  Almost every candidate gets there within two or three sweeps; one that has
-// not after kTry sweeps is handed to the general kernel (Karp's formula).
+// not after the sweeps this pass allows (C.eigen_tries) is handed on: to a second pass of this kernel
+// with more sweeps, then to the general kernel (Karp's formula).
 template <int DM, int VM>
 __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds &L, const FastProgram &prog, int lane,
                                            const Mu &lead_code, bool want,
@@ -656,7 +657,7 @@ __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds
         }
         if (!done && same && have) { T = (int)delta; done = true; }
     }
-    return done ? T : -1;        // -1: no eigenvector within kTry sweeps (the caller defers the candidate)
+    return done ? T : -1;        // -1: no eigenvector within the sweeps allowed (the caller hands the candidate on)
 }
 
 // even bits of a 64-bit word, compacted (bit 2p -> bit p)
