@@ -44,6 +44,11 @@ def main():
     ap.add_argument("--search", action="store_true",
                     help="time the whole search of Alg. 1 (window sizes 1..4, early exit) on the sequential 4-stage "
                          "placement instead of the headline workload; prints its own JSON line")
+    ap.add_argument("--completions", action="store_true",
+                    help="time the searched completion (perturbed greedy warm-up / cool-down orders around the best window "
+                         "of the first 2^24 candidates, 64 micro-batches) instead of the headline workload")
+    ap.add_argument("--log2-completions", type=int, default=20, help="completion candidates per step = 2^this")
+    ap.add_argument("--jitter", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one plain device copy of 1 GiB instead (reference for the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -88,6 +93,35 @@ def main():
                           "result": dict(got, makespan_16_microbatches=sched["makespan"]),
                           "candidates_scored": sum(got["evaluated_nr"]),
                           "candidates_per_s": sum(got["evaluated_nr"]) / dt}))
+        return
+    if args.completions:
+        prob = workloads.config5()
+        N = prob["num_microbatches"]
+        gpu = Problem(prob)
+        gpu.eval_candidates(0, 1 << 24)
+        best = gpu.best()
+        greedy = gpu.complete_schedule(N)
+        n = 1 << args.log2_completions
+        for _ in range(args.warmup):
+            gpu.search_completions(N, args.jitter, 0, n)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            gpu.search_completions(N, args.jitter, k * n, n)
+        found = gpu.best_completion(N)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        blocks = prob["K"] * N
+        print(json.dumps({"metric": "completion candidates (whole schedules of 64 micro-batches) scored/s", "value": n * args.steps / dt,
+                          "unit": "candidates/s", "higher_is_better": True, "n_gpus": 1, "steps": args.steps,
+                          "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "dtype": "int32", "data": "synthetic",
+                          "vs_baseline": None,
+                          "config": {"workload": "cfg5 best window of the first 2^24 candidates, N=%d micro-batches (%d blocks), "
+                                                 "jitter %d, 2^%d completion candidates per step" % (N, blocks, args.jitter, args.log2_completions)},
+                          "result": {"window_period": best["period"], "windows": found["num_windows"],
+                                     "greedy_makespan": greedy["makespan"], "best_makespan": found["makespan"],
+                                     "best_ordinal": found["ordinal"]},
+                          "blocks_scheduled_per_s": n * args.steps / dt * blocks}))
         return
     prob = workloads.config5()
     n_cand = 1 << args.log2_candidates

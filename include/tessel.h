@@ -181,6 +181,31 @@ int  tessel_reset(tessel_problem *p);
  * capacity too small), NO_SCHEDULE. */
 int  tessel_complete_schedule(tessel_problem *p, tessel_schedule *out);
 
+/* ---- searched completion (Sec. IV-C; the paper orders warm-up and cool-down with a time-optimal solver) ---
+ * Completion candidate `ordinal` is a perturbed greedy list schedule of the two outer phases around the R
+ * copies of the best window: per phase every block type offers its lowest unscheduled micro-batch
+ * (Property 1); an offered block is eligible when its producer's block of the same micro-batch is scheduled
+ * and its memory delta fits on all its devices; the eligible block with the smallest (earliest start +
+ * jitter, micro-batch, type id) is appended at its earliest start.  jitter(type, mu) = (draw * (J + 1)) >> 16
+ * with the 16-bit draw number type*N + mu of the counter-based stream keyed by (seed + 0x632BE59BD9B4E019,
+ * ordinal); ordinal 0 has no jitter and is the schedule of tessel_complete_schedule.
+ *
+ * tessel_search_completions scores candidates first .. first+count-1 on the GPU (one per lane, every block of
+ * the N micro-batches simulated) and merges into the running best (makespan, lowest ordinal); asynchronous on
+ * the stream of the last tessel_eval_candidates call, in the workspace bound there.  A new best window, N or
+ * J restarts the running best.  Errors: NO_FEASIBLE, RANGE (fewer than one window fits), INVALID_ARG,
+ * TOOBIG (state of N micro-batches does not fit the LDS, or N * sum of t exceeds 16 bits), UNSUPPORTED (|m| > 127), HIP. */
+int  tessel_search_completions(tessel_problem *p, int32_t num_microbatches, int32_t jitter, uint64_t first,
+                               uint64_t count);
+/* makespan_dev[k] (device, int32) = makespan of completion candidate first+k, INT32_MAX where the greedy rule
+ * gets stuck under the memory cap.  Does not touch the running best. */
+int  tessel_score_completions(tessel_problem *p, int32_t num_microbatches, int32_t jitter, uint64_t first,
+                              uint64_t count, int32_t *makespan_dev);
+/* Waits, then writes the complete schedule of the best completion candidate scored so far (out as for
+ * tessel_complete_schedule, num_microbatches as searched) and its ordinal.  Errors: NO_FEASIBLE (nothing
+ * searched), NO_SCHEDULE (no candidate had a schedule), INVALID_ARG, RANGE, HIP. */
+int  tessel_best_completion(tessel_problem *p, tessel_schedule *out, uint64_t *ordinal);
+
 /* ---- runtime instantiation (Sec. IV-E): the global operation sequence of a complete schedule --------
  * Blocks in ascending start time; blocks that start together are consecutive, ordered by their lowest
  * device (a device's own blocks keep its execution order).  A tensor that a consumer needs on a device

@@ -23,7 +23,8 @@ E_RANGE = -8
 EXPORTS = (
     "tessel_problem_create", "tessel_problem_destroy", "tessel_candidate_count", "tessel_workspace_bytes",
     "tessel_eval_candidates", "tessel_score_candidates", "tessel_best", "tessel_best_candidate", "tessel_reset",
-    "tessel_complete_schedule", "tessel_instantiate", "tessel_search_workspace_bytes", "tessel_search_run", "tessel_alu_probe", "tessel_strerror", "tessel_last_hip_error",
+    "tessel_complete_schedule", "tessel_search_completions", "tessel_score_completions", "tessel_best_completion",
+    "tessel_instantiate", "tessel_search_workspace_bytes", "tessel_search_run", "tessel_alu_probe", "tessel_strerror", "tessel_last_hip_error",
 )
 
 
@@ -89,6 +90,9 @@ def load_library():
         lib.tessel_best_candidate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.tessel_reset.argtypes = [C.c_void_p]
         lib.tessel_complete_schedule.argtypes = [C.c_void_p, C.POINTER(Schedule)]
+        lib.tessel_search_completions.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_uint64, C.c_uint64]
+        lib.tessel_score_completions.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_uint64, C.c_uint64, C.c_void_p]
+        lib.tessel_best_completion.argtypes = [C.c_void_p, C.POINTER(Schedule), C.POINTER(C.c_uint64)]
         lib.tessel_instantiate.argtypes = [C.c_void_p, C.POINTER(Schedule), C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
         lib.tessel_search_workspace_bytes.argtypes = [C.POINTER(ProblemDesc), C.POINTER(Search), C.POINTER(C.c_size_t)]
         lib.tessel_search_run.argtypes = [C.POINTER(ProblemDesc), C.POINTER(Search), C.c_void_p, C.c_size_t, C.c_void_p,
@@ -258,6 +262,29 @@ class Problem:
 
     def reset(self):
         _check(load_library().tessel_reset(self._h))
+
+    def search_completions(self, num_microbatches, jitter, first, count):
+        _check(load_library().tessel_search_completions(self._h, num_microbatches, jitter, first, count))
+
+    def score_completions(self, num_microbatches, jitter, first, count):
+        """returns the makespans as an int32 CUDA tensor"""
+        import torch
+        out = torch.empty(max(1, count), dtype=torch.int32, device="cuda")
+        _check(load_library().tessel_score_completions(self._h, num_microbatches, jitter, first, count, out.data_ptr()))
+        torch.cuda.synchronize()
+        return out[:count]
+
+    def best_completion(self, num_microbatches):
+        N = num_microbatches
+        cap = self.K * N
+        start = np.full(cap, -1, dtype=np.int32)
+        dev_order = np.full((self.D, cap), -1, dtype=np.int32)
+        dev_len = np.zeros(self.D, dtype=np.int32)
+        s = Schedule(N, cap, start.ctypes.data, dev_order.ctypes.data, dev_len.ctypes.data, 0, 0, 0)
+        ordinal = C.c_uint64(0)
+        _check(load_library().tessel_best_completion(self._h, C.byref(s), C.byref(ordinal)))
+        return {"makespan": s.makespan, "period": s.period, "num_windows": s.num_windows, "ordinal": int(ordinal.value),
+                "start": start.reshape(self.K, N), "dev_order": [dev_order[d, :dev_len[d]].tolist() for d in range(self.D)]}
 
     def instantiate(self, num_microbatches, start):
         """tessel_instantiate: list of (kind, block, src, dst, aux) for the schedule with these start times [K][N]"""

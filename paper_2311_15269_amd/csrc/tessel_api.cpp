@@ -38,6 +38,10 @@ struct tessel_problem {
     uint64_t detail_index = 0;
     DevDetail detail;
     DevResult result;
+    // searched completion
+    bool comp_ready = false;            // CompParams of (comp_index, N, J) are in the workspace
+    uint64_t comp_index = 0;            // best candidate they were built for
+    CompParams comp;
 };
 
 static int hip_fail(tessel_problem *p, int e) { p->last_hip = e; return TESSEL_E_HIP; }
@@ -550,28 +554,29 @@ extern "C" int tessel_best_candidate(tessel_problem *p, int32_t *leads, int32_t 
 // fit the cap on each device they occupy, append the one with the smallest (earliest start,
 // micro-batch, type).  A block starts at the maximum of its devices' free times and its producers'
 // ends, which is also the earliest start for the final per-device orders.
-extern "C" int tessel_complete_schedule(tessel_problem *p, tessel_schedule *out)
+// Completion candidate `ordinal` with jitter amplitude J around R copies of the best window; ordinal 0 or
+// J = 0: the plain greedy schedule.  Per phase every type offers its lowest unscheduled micro-batch.
+static int complete_with(tessel_problem *p, tessel_schedule *out, uint64_t ordinal, int J)
 {
-    if (!p || !out || !out->start || !out->dev_order || !out->dev_len) return TESSEL_E_INVALID_ARG;
-    int rc = fetch_best(p);
-    if (rc) return rc;
-    if (p->result.period == INT_MAX) return TESSEL_E_NO_FEASIBLE;
     const DevDetail &c = p->detail;
     const int N = out->num_microbatches, K = p->kp.K, D = p->kp.D, NR = p->kp.NR, M = p->kp.M;
     int maxlead = 0;
     for (int i = 0; i < K; i++) maxlead = std::max(maxlead, c.leads[i]);
     const int R = N >= 1 ? (N - maxlead) / NR : 0;
     if (R < 1 || out->capacity < K * N) return TESSEL_E_RANGE;
-    std::vector<int> finish(K * N, -1);
+    std::vector<int> finish(K * N, -1), next(K, 0);
     std::vector<int> dev_free(D, 0), dev_mem(D, 0);
     for (int d = 0; d < D; d++) out->dev_len[d] = 0;
     std::vector<std::vector<int>> producers(K);
     for (size_t e = 0; e < p->dep_src.size(); e++) producers[p->dep_dst[e]].push_back(p->dep_src[e]);
+    uint32_t kb = 0;
+    const uint32_t ka = stream_keys(p->kp.seed + kCompletionKey, ordinal, kb);
+    const bool noisy = ordinal != 0 && J > 0;
 
     auto earliest = [&](int i, int mu, int &est) -> bool {      // false if a producer is not scheduled yet
         est = 0;
         for (int a : producers[i]) {
-            if (finish[a * N + mu] < 0) return false;
+            if (next[a] <= mu) return false;
             est = std::max(est, finish[a * N + mu]);
         }
         for (int d = 0; d < D; d++) if (p->mask[i] >> d & 1u) est = std::max(est, dev_free[d]);
@@ -580,6 +585,7 @@ extern "C" int tessel_complete_schedule(tessel_problem *p, tessel_schedule *out)
     auto commit = [&](int i, int mu, int est) {
         out->start[i * N + mu] = est;
         finish[i * N + mu] = est + p->t[i];
+        next[i] = mu + 1;
         for (int d = 0; d < D; d++) if (p->mask[i] >> d & 1u) {
             dev_free[d] = est + p->t[i];
             dev_mem[d] += p->m[i];
@@ -587,49 +593,46 @@ extern "C" int tessel_complete_schedule(tessel_problem *p, tessel_schedule *out)
         }
     };
     auto greedy_phase = [&](bool warmup) -> int {
-        std::vector<std::pair<int, int>> todo;
-        for (int i = 0; i < K; i++) {
-            int lo = warmup ? 0 : c.leads[i] + NR * R, hi = warmup ? c.leads[i] : N;
-            for (int mu = lo; mu < hi; mu++) todo.push_back({i, mu});
-        }
-        while (!todo.empty()) {
-            int pick = -1, pick_est = 0;
-            for (size_t k = 0; k < todo.size(); k++) {
-                int i = todo[k].first, mu = todo[k].second, est;
+        for (;;) {
+            int pick = -1, pick_mu = 0, pick_est = 0, pick_key = 0;
+            bool left = false;
+            for (int i = 0; i < K; i++) {
+                const int hi = warmup ? c.leads[i] : N, mu = next[i];
+                if (mu >= hi) continue;
+                left = true;
+                int est;
                 if (!earliest(i, mu, est)) continue;
                 bool fits = true;
                 if (p->m[i] > 0)
                     for (int d = 0; d < D; d++) if ((p->mask[i] >> d & 1u) && dev_mem[d] + p->m[i] > M) fits = false;
                 if (!fits) continue;
-                if (pick < 0) { pick = (int)k; pick_est = est; continue; }
-                int bi = todo[pick].first, bmu = todo[pick].second;
-                if (est < pick_est || (est == pick_est && (mu < bmu || (mu == bmu && i < bi)))) { pick = (int)k; pick_est = est; }
+                const int key = est + (noisy ? (int)((stream_draw16(ka, kb, (uint32_t)(i * N + mu)) * (uint32_t)(J + 1)) >> 16) : 0);
+                if (pick < 0 || key < pick_key || (key == pick_key && mu < pick_mu)) { pick = i; pick_mu = mu; pick_est = est; pick_key = key; }
             }
+            if (!left) return TESSEL_OK;
             if (pick < 0) return TESSEL_E_NO_SCHEDULE;
-            commit(todo[pick].first, todo[pick].second, pick_est);
-            todo.erase(todo.begin() + pick);
+            commit(pick, pick_mu, pick_est);
         }
-        return TESSEL_OK;
     };
 
-    rc = greedy_phase(true);
+    int rc = greedy_phase(true);
     if (rc) return rc;
     for (int k = 0; k < R; k++) {
         // replay the window in any executable sequence of the decoded per-device orders
-        std::vector<int> pos(D, 0), occ(K, 0);
+        std::vector<int> pos(D, 0);
         int left = K * NR;
         while (left > 0) {
             bool moved = false;
             for (int d = 0; d < D; d++) {
                 if (pos[d] >= c.order_len[d]) continue;
-                int i = c.orders[d][pos[d]], mu = c.leads[i] + occ[i] + NR * k, est;
+                int i = c.orders[d][pos[d]], mu = next[i], est;
                 bool heads = true;
                 for (int dd = 0; dd < D; dd++)
                     if ((p->mask[i] >> dd & 1u) && (pos[dd] >= c.order_len[dd] || c.orders[dd][pos[dd]] != i)) heads = false;
                 if (!heads || !earliest(i, mu, est)) continue;
                 commit(i, mu, est);
                 for (int dd = 0; dd < D; dd++) if (p->mask[i] >> dd & 1u) pos[dd]++;
-                occ[i]++; left--; moved = true;
+                left--; moved = true;
             }
             if (!moved) return TESSEL_E_NO_SCHEDULE;
         }
@@ -639,6 +642,123 @@ extern "C" int tessel_complete_schedule(tessel_problem *p, tessel_schedule *out)
     out->makespan = *std::max_element(finish.begin(), finish.end());
     out->period = c.period;
     out->num_windows = R;
+    return TESSEL_OK;
+}
+
+extern "C" int tessel_complete_schedule(tessel_problem *p, tessel_schedule *out)
+{
+    if (!p || !out || !out->start || !out->dev_order || !out->dev_len) return TESSEL_E_INVALID_ARG;
+    int rc = fetch_best(p);
+    if (rc) return rc;
+    if (p->result.period == INT_MAX) return TESSEL_E_NO_FEASIBLE;
+    return complete_with(p, out, 0, 0);
+}
+
+// ---- searched completion: many perturbed greedy completions scored on the GPU -----------------------
+// uploads what the kernel needs of the problem and of the best candidate (once per best candidate, N, J)
+static int bind_completion(tessel_problem *p, int N, int J)
+{
+    int rc = fetch_best(p);
+    if (rc) return rc;
+    if (p->result.period == INT_MAX) return TESSEL_E_NO_FEASIBLE;
+    if (p->comp_ready && p->comp_index == p->result.index && p->comp.N == N && p->comp.J == J) return TESSEL_OK;
+    const DevDetail &c = p->detail;
+    const int K = p->kp.K, D = p->kp.D, NR = p->kp.NR;
+    if (N < 1 || J < 0 || J > 65535) return TESSEL_E_INVALID_ARG;
+    int maxlead = 0;
+    for (int i = 0; i < K; i++) maxlead = std::max(maxlead, c.leads[i]);
+    const int R = (N - maxlead) / NR;
+    if (R < 1) return TESSEL_E_RANGE;
+    CompParams &cp = p->comp;
+    memset(&cp, 0, sizeof cp);
+    cp.D = D; cp.K = K; cp.NR = NR; cp.M = p->kp.M; cp.N = N; cp.J = J; cp.R = R; cp.nseq = K * NR;
+    cp.seed = p->kp.seed + kCompletionKey;
+    int npaths = 0;
+    for (int i = 0; i < K; i++) {
+        if (p->m[i] < -128 || p->m[i] > 127) return TESSEL_E_UNSUPPORTED;
+        cp.t[i] = p->t[i]; cp.m[i] = (int8_t)p->m[i]; cp.mask[i] = (uint8_t)p->mask[i]; cp.pred[i] = p->kp.pred[i];
+        cp.lead[i] = (uint8_t)c.leads[i];
+    }
+    for (int i = 0; i < K; i++) if (p->kp.pred[i] < 0) {                 // chains numbered by their first type
+        for (int g = i; g >= 0; g = p->kp.succ[g]) cp.path[g] = (uint8_t)npaths;
+        npaths++;
+    }
+    cp.npaths = npaths;
+    // one executable sequence of the window (the device orders of the best candidate)
+    {
+        std::vector<int> pos(D, 0), occ(K, 0);
+        int n = 0;
+        while (n < K * NR) {
+            bool moved = false;
+            for (int d = 0; d < D; d++) {
+                if (pos[d] >= c.order_len[d]) continue;
+                const int i = c.orders[d][pos[d]];
+                bool heads = true;
+                for (int dd = 0; dd < D; dd++)
+                    if ((p->mask[i] >> dd & 1u) && (pos[dd] >= c.order_len[dd] || c.orders[dd][pos[dd]] != i)) heads = false;
+                const int a = p->kp.pred[i];
+                // its producer's block of the same micro-batch must come first: in this window, or it ran in an earlier one
+                if (!heads || (a >= 0 && c.leads[a] + occ[a] <= c.leads[i] + occ[i])) continue;
+                cp.seq[n] = (uint8_t)i; cp.occ[n] = (uint8_t)occ[i]; n++;
+                occ[i]++;
+                for (int dd = 0; dd < D; dd++) if (p->mask[i] >> dd & 1u) pos[dd]++;
+                moved = true;
+            }
+            if (!moved) return TESSEL_E_NO_SCHEDULE;
+        }
+    }
+    {
+        // the kernel keeps times, memory and jitter in 16 bits
+        long long total = 0;
+        for (int i = 0; i < K; i++) total += (long long)p->t[i] * N;
+        if (total + J > 65535 || std::abs(p->kp.M) > 30000) return TESSEL_E_TOOBIG;
+    }
+    if (completion_lds_bytes(cp) > 64 * 1024) return TESSEL_E_TOOBIG;
+    hipError_t e = hipMemcpyAsync((char *)p->ws + kWsCompParamsOff, &cp, sizeof cp, hipMemcpyHostToDevice, p->stream);
+    if (e != hipSuccess) return hip_fail(p, (int)e);
+    int le = launch_completion_reset(p->ws, p->stream);
+    if (le) return hip_fail(p, le);
+    p->comp_ready = true; p->comp_index = p->result.index;
+    return TESSEL_OK;
+}
+
+extern "C" int tessel_search_completions(tessel_problem *p, int32_t num_microbatches, int32_t jitter, uint64_t first,
+                                         uint64_t count)
+{
+    if (!p) return TESSEL_E_INVALID_ARG;
+    if (first + count < first) return TESSEL_E_RANGE;
+    int rc = bind_completion(p, num_microbatches, jitter);
+    if (rc) return rc;
+    int e = launch_completions(p->comp, first, count, nullptr, p->ws, p->num_cus, p->stream);
+    return e < 0 ? TESSEL_E_TOOBIG : e ? hip_fail(p, e) : TESSEL_OK;
+}
+
+extern "C" int tessel_score_completions(tessel_problem *p, int32_t num_microbatches, int32_t jitter, uint64_t first,
+                                        uint64_t count, int32_t *makespan_dev)
+{
+    if (!p || !makespan_dev) return TESSEL_E_INVALID_ARG;
+    if (first + count < first) return TESSEL_E_RANGE;
+    int rc = bind_completion(p, num_microbatches, jitter);
+    if (rc) return rc;
+    int e = launch_completions(p->comp, first, count, makespan_dev, p->ws, p->num_cus, p->stream);
+    return e < 0 ? TESSEL_E_TOOBIG : e ? hip_fail(p, e) : TESSEL_OK;
+}
+
+extern "C" int tessel_best_completion(tessel_problem *p, tessel_schedule *out, uint64_t *ordinal)
+{
+    if (!p || !out || !out->start || !out->dev_order || !out->dev_len) return TESSEL_E_INVALID_ARG;
+    if (!p->comp_ready || !p->ws) return TESSEL_E_NO_FEASIBLE;
+    if (out->num_microbatches != p->comp.N) return TESSEL_E_INVALID_ARG;
+    hipError_t e = hipStreamSynchronize(p->stream);
+    if (e != hipSuccess) return hip_fail(p, (int)e);
+    DevCompletion best;
+    e = hipMemcpy(&best, (char *)p->ws + kWsCompletionOff, sizeof best, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(p, (int)e);
+    if (best.makespan == INT_MAX) return TESSEL_E_NO_SCHEDULE;
+    int rc = complete_with(p, out, best.ordinal, p->comp.J);
+    if (rc) return rc;
+    if (out->makespan != best.makespan) return TESSEL_E_HIP;        // host and kernel disagree: never expected
+    if (ordinal) *ordinal = best.ordinal;
     return TESSEL_OK;
 }
 

@@ -4,7 +4,45 @@
 #pragma once
 #include <stdint.h>
 
+#if defined(__HIPCC__)
+#define TESSEL_HD __host__ __device__ inline
+#else
+#define TESSEL_HD inline
+#endif
+
 namespace tessel {
+
+// ------------------------------------------------------------------ counter-based sampler
+// SplitMix64 finaliser keys a candidate ordinal; MurmurHash3's 32-bit finaliser, with the second
+// key folded in between its multiplications, gives the w-th word; two 16-bit draws a word.
+TESSEL_HD uint64_t mix64(uint64_t z)
+{
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27; z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31;
+    return z;
+}
+TESSEL_HD uint32_t stream_word(uint32_t a, uint32_t b, uint32_t w)
+{
+    uint32_t x = a + w * 0x9E3779B9u;
+    x ^= x >> 16; x *= 0x85EBCA6Bu;
+    x ^= b;
+    x ^= x >> 13; x *= 0xC2B2AE35u;
+    x ^= x >> 16;
+    return x;
+}
+// 16-bit draw number j of the stream keyed by (seed, ordinal)
+TESSEL_HD uint32_t stream_keys(uint64_t seed, uint64_t ordinal, uint32_t &kb)
+{
+    const uint64_t z = mix64(seed + 0x9E3779B97F4A7C15ULL * (ordinal + 1));
+    kb = (uint32_t)(z >> 32);
+    return (uint32_t)z;
+}
+TESSEL_HD uint32_t stream_draw16(uint32_t ka, uint32_t kb, uint32_t j)
+{
+    return (stream_word(ka, kb, j >> 1) >> (16u * (j & 1u))) & 0xFFFFu;
+}
+constexpr uint64_t kCompletionKey = 0x632BE59BD9B4E019ULL;      // separates the completion stream from the candidates'
 
 constexpr int kMaxD = 8;         // simulated devices
 constexpr int kMaxLT = 4;        // block types per device
@@ -97,7 +135,31 @@ struct DevDetail {
     int32_t orders[kMaxD][kMaxPos];
 };
 
+// Searched completion (warm-up / cool-down orders as perturbed greedy schedules around the best window):
+// what the kernel needs of the problem and of the best candidate, by block type, and the running best.
+constexpr int kMaxSeq = kMaxK * kMaxNR;
+struct CompParams {
+    int32_t  D, K, NR, M, N, J, R, nseq, npaths;
+    int32_t  pad;
+    uint64_t seed;                   // problem seed + kCompletionKey
+    int32_t  t[kMaxK];
+    int8_t   m[kMaxK];
+    uint8_t  mask[kMaxK];
+    int8_t   pred[kMaxK];            // producer type or -1
+    uint8_t  path[kMaxK];            // dependency chain of the type
+    uint8_t  lead[kMaxK];
+    uint8_t  seq[kMaxSeq];           // the window's blocks (types) in an executable order
+    uint8_t  occ[kMaxSeq];           // occurrence number of seq[s] among the earlier entries of its type
+};
+struct DevCompletion {
+    int32_t  makespan;               // INT32_MAX = nothing scheduled yet
+    int32_t  pad;
+    uint64_t ordinal;
+};
+struct CompRec { int32_t makespan; int32_t pad; uint64_t ordinal; };
+
 constexpr size_t kWsResultOff = 0;
+constexpr size_t kWsCompletionOff = 192;       // DevCompletion
 constexpr size_t kWsDetailOff = 256;
 constexpr size_t kWsParamsOff = 2048;          // KParams of the bound problem
 constexpr size_t kWsTablesOff = 8192;          // lead table, arrangement table
@@ -106,12 +168,15 @@ constexpr size_t kWsRetryOff = kWsTablesOff + kWsTablesMax;    // candidates tha
 constexpr uint32_t kWsRetryCap = 1u << 21;
 constexpr size_t kWsListOff = kWsRetryOff + (size_t)kWsRetryCap * 8;   // candidates deferred to the general kernel
 constexpr uint32_t kWsListCap = 1u << 16;
-constexpr size_t kWsBlockRecOff = kWsListOff + (size_t)kWsListCap * 8;
+constexpr size_t kWsCompParamsOff = kWsListOff + (size_t)kWsListCap * 8;   // CompParams
+constexpr size_t kWsBlockRecOff = kWsCompParamsOff + 1024;
 constexpr int kDeferBlocks = 64;                                // grid of the deferred pass
 constexpr int kFirstPassTries = 2;                              // sweeps before a candidate goes to the retry list
 constexpr uint64_t kMaxPerLaunch = 1ull << 24;                  // candidates per pass of the kernels
 constexpr int kRetryTries = 8;                                  // ... and before the general kernel gets it
 
+static_assert(sizeof(CompParams) <= 1024, "completion parameters must fit their workspace slot");
+static_assert(sizeof(DevResult) <= kWsCompletionOff && kWsCompletionOff + sizeof(DevCompletion) <= kWsDetailOff, "result records overlap");
 static_assert(sizeof(KParams) <= kWsTablesOff - kWsParamsOff, "parameter block must fit its workspace slot");
 static_assert(sizeof(DevDetail) <= kWsParamsOff - kWsDetailOff, "detail record must fit its workspace slot");
 
@@ -124,6 +189,11 @@ int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *cod
                  bool general, void *stream);
 int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream);
 int launch_reset(void *ws, void *stream);
+// completion search: S = state words per lane; returns 0 or a HIP error (negative: LDS need exceeds the device's)
+size_t completion_lds_bytes(const CompParams &cp);
+int launch_completions(const CompParams &cp, uint64_t first, uint64_t count, int32_t *makespan_out, void *ws, int num_cus,
+                       void *stream);
+int launch_completion_reset(void *ws, void *stream);
 int launch_alu_probe(uint32_t *out, int blocks, int rounds, void *stream);
 constexpr int kProbeThreads = 256;
 constexpr int kProbeLaneOpsPerRound = 32;

@@ -39,25 +39,6 @@ struct BlockRec {
     uint32_t n_sweeps;           // window sweeps spent on period computations
 };
 
-// ------------------------------------------------------------------ counter-based sampler
-// SplitMix64 finaliser keys the candidate; MurmurHash3's 32-bit finaliser, with the second
-// key folded in between its multiplications, gives the w-th word; two 16-bit draws a word.
-__device__ __forceinline__ uint64_t mix64(uint64_t z)
-{
-    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ULL;
-    z ^= z >> 27; z *= 0x94D049BB133111EBULL;
-    z ^= z >> 31;
-    return z;
-}
-__device__ __forceinline__ uint32_t stream_word(uint32_t a, uint32_t b, uint32_t w)
-{
-    uint32_t x = a + w * 0x9E3779B9u;
-    x ^= x >> 16; x *= 0x85EBCA6Bu;
-    x ^= b;
-    x ^= x >> 13; x *= 0xC2B2AE35u;
-    x ^= x >> 16;
-    return x;
-}
 constexpr uint32_t kDrawLeadBase = 0u;
 constexpr uint32_t kDrawOrdBase = 128u;
 
@@ -1300,6 +1281,190 @@ int launch_reset(void *ws, void *stream)
 }
 
 size_t block_rec_bytes(int blocks) { return (size_t)blocks * sizeof(BlockRec); }
+
+
+// ==================================================================== searched completion
+// Warm-up and cool-down around R copies of the best window (Sec. IV-C).  The paper orders the two outer
+// phases with a time-optimal solver; here many perturbed greedy list schedules are tried, one per lane,
+// and the shortest complete schedule wins.  Completion candidate `ordinal`: per phase every block type
+// offers its lowest unscheduled micro-batch (Property 1); an offered block is eligible when its producer's
+// block of the same micro-batch is scheduled and its memory delta fits on all its devices; the eligible
+// block with the smallest (earliest start + jitter, micro-batch, type id) is appended at its earliest
+// start.  jitter(type, mu) = (draw * (J + 1)) >> 16 with draw number type*N + mu of the stream keyed by the
+// ordinal; ordinal 0 has no jitter (the plain greedy schedule).
+// Per-lane state in LDS [slot][lane]: end time of the latest block of every (chain, micro-batch), free time
+// and memory of every device, next micro-batch and current jitter of every type.
+constexpr int kCompParamWords = 256;       // the parameter block's copy at the start of the LDS
+
+__global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__restrict__ cpg, uint64_t first, uint64_t count,
+                                                         CompRec *__restrict__ recs, int32_t *__restrict__ makespan_out)
+{
+    extern __shared__ uint32_t lds[];
+    for (int w = threadIdx.x; w < (int)(sizeof(CompParams) / 4); w += kWave) lds[w] = ((const uint32_t *)cpg)[w];
+    __syncthreads();
+    const CompParams &cp = *(const CompParams *)lds;
+    const int lane = threadIdx.x;
+    uint16_t *state = (uint16_t *)(lds + kCompParamWords) + lane;      // 16-bit words: all times stay below 65536 (checked by the host)
+    const int D = cp.D, K = cp.K, N = cp.N, NR = cp.NR, M = cp.M, J = cp.J, R = cp.R;
+    const int oTok = 0, oFree = cp.npaths * N, oMem = oFree + D, oNext = oMem + D, oJit = oNext + K, nstate = oJit + K;
+#define TESSEL_ST(slot) state[(slot) * kWave]
+    int best = INT_MAX;
+    uint64_t best_ord = 0;
+    const uint64_t stride = (uint64_t)gridDim.x * kWave;
+    const uint64_t rounds = (count + stride - 1) / stride;          // the same trip count for every lane of the grid
+    for (uint64_t r = 0; r < rounds; r++) {
+        const uint64_t kk = r * stride + (uint64_t)blockIdx.x * kWave + lane;
+        const bool live = kk < count;
+        const uint64_t c = first + (live ? kk : 0);
+        uint32_t kb;
+        const uint32_t ka = stream_keys(cp.seed, c, kb);
+        const bool noisy = c != 0 && J > 0;
+        auto jitter = [&](int i, int mu) -> uint32_t {
+            return noisy ? (stream_draw16(ka, kb, (uint32_t)(i * N + mu)) * (uint32_t)(J + 1)) >> 16 : 0u;
+        };
+        for (int s = 0; s < nstate; s++) TESSEL_ST(s) = 0;
+        bool fail = false;
+        for (int phase = 0; phase < 2; phase++) {
+            // ---- greedy phase: 0 warm-up (micro-batches below the leads), 1 cool-down (the rest up to N)
+            for (int i = 0; i < K; i++) {
+                const int mu = (int)TESSEL_ST(oNext + i), hi = phase ? N : (int)cp.lead[i];
+                TESSEL_ST(oJit + i) = (uint16_t)(mu < hi ? jitter(i, mu) : 0u);
+            }
+            for (;;) {
+                int bi = -1, bmu = 0, best_est = 0, bkey = 0;
+                bool any = false;
+                for (int i = 0; i < K; i++) {
+                    const int hi = phase ? N : (int)cp.lead[i];
+                    const int mu = (int)TESSEL_ST(oNext + i);
+                    const bool offered = mu < hi;
+                    any |= offered;
+                    const int a = cp.pred[i], mi = cp.m[i];
+                    const uint32_t mask = cp.mask[i];
+                    bool ok = offered;
+                    int est = 0;
+                    if (a >= 0) {
+                        ok = ok && (int)TESSEL_ST(oNext + a) > mu;
+                        est = (int)TESSEL_ST(oTok + (int)cp.path[i] * N + min(mu, N - 1));
+                    }
+                    for (uint32_t rest = mask; rest; rest &= rest - 1u) {          // the block's devices (uniform)
+                        const int d = __builtin_ctz(rest);
+                        if (mi > 0 && (int)(int16_t)TESSEL_ST(oMem + d) + mi > M) ok = false;
+                        est = max(est, (int)TESSEL_ST(oFree + d));
+                    }
+                    const int key = est + (int)TESSEL_ST(oJit + i);
+                    // types ascend, so on equal (key, micro-batch) the earlier type stays
+                    if (ok && (bi < 0 || key < bkey || (key == bkey && mu < bmu))) { bi = i; bmu = mu; best_est = est; bkey = key; }
+                }
+                const bool busy = live && !fail && any;
+                if (__ballot(busy) == 0) break;
+                if (busy && bi < 0) fail = true;                  // blocks left, none eligible: no schedule
+                if (busy && bi >= 0) {
+                    const int en = best_est + cp.t[bi], mi = cp.m[bi], hi = phase ? N : (int)cp.lead[bi];
+                    const uint32_t mask = cp.mask[bi];
+                    for (int d = 0; d < D; d++)
+                        if (mask >> d & 1u) { TESSEL_ST(oFree + d) = (uint16_t)en; TESSEL_ST(oMem + d) = (uint16_t)((int)(int16_t)TESSEL_ST(oMem + d) + mi); }
+                    TESSEL_ST(oTok + (int)cp.path[bi] * N + bmu) = (uint16_t)en;
+                    TESSEL_ST(oNext + bi) = (uint16_t)(bmu + 1);
+                    TESSEL_ST(oJit + bi) = (uint16_t)(bmu + 1 < hi ? jitter(bi, bmu + 1) : 0u);
+                }
+            }
+            if (phase == 1) break;
+            // ---- the R windows: the same blocks at the same micro-batches in every lane
+            for (int k = 0; k < R; k++)
+                for (int s = 0; s < cp.nseq; s++) {
+                    const int i = cp.seq[s], mu = (int)cp.lead[i] + (int)cp.occ[s] + NR * k;
+                    const uint32_t mask = cp.mask[i];
+                    const int tok = oTok + (int)cp.path[i] * N + mu;
+                    int est = cp.pred[i] >= 0 ? (int)TESSEL_ST(tok) : 0;
+                    for (uint32_t rest = mask; rest; rest &= rest - 1u) est = max(est, (int)TESSEL_ST(oFree + __builtin_ctz(rest)));
+                    const int en = est + cp.t[i];
+                    for (uint32_t rest = mask; rest; rest &= rest - 1u) {
+                        const int d = __builtin_ctz(rest);
+                        TESSEL_ST(oFree + d) = (uint16_t)en; TESSEL_ST(oMem + d) = (uint16_t)((int)(int16_t)TESSEL_ST(oMem + d) + cp.m[i]);
+                    }
+                    TESSEL_ST(tok) = (uint16_t)en;
+                }
+            for (int i = 0; i < K; i++) TESSEL_ST(oNext + i) = (uint16_t)((int)cp.lead[i] + NR * R);
+        }
+        int makespan = 0;
+        for (int d = 0; d < D; d++) makespan = max(makespan, (int)TESSEL_ST(oFree + d));
+        if (fail) makespan = INT_MAX;
+        if (!live) continue;
+        if (makespan_out) makespan_out[kk] = makespan;
+        if (makespan < best || (makespan == best && c < best_ord)) { best = makespan; best_ord = c; }
+    }
+#undef TESSEL_ST
+    if (!recs) return;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        int om = __shfl_xor(best, off);
+        uint32_t ilo = __shfl_xor((uint32_t)best_ord, off), ihi = __shfl_xor((uint32_t)(best_ord >> 32), off);
+        uint64_t oo = ((uint64_t)ihi << 32) | ilo;
+        if (key_less(om, oo, best, best_ord)) { best = om; best_ord = oo; }
+    }
+    if (lane == 0) { CompRec rr; rr.makespan = best; rr.pad = 0; rr.ordinal = best_ord; recs[blockIdx.x] = rr; }
+}
+
+__global__ void complete_merge_kernel(const CompRec *__restrict__ recs, int nrecs, DevCompletion *__restrict__ res)
+{
+    const int lane = threadIdx.x;
+    int best = INT_MAX;
+    uint64_t best_ord = ~0ull;
+    for (int k = lane; k < nrecs; k += kWave)
+        if (key_less(recs[k].makespan, recs[k].ordinal, best, best_ord)) { best = recs[k].makespan; best_ord = recs[k].ordinal; }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        int om = __shfl_xor(best, off);
+        uint32_t ilo = __shfl_xor((uint32_t)best_ord, off), ihi = __shfl_xor((uint32_t)(best_ord >> 32), off);
+        uint64_t oo = ((uint64_t)ihi << 32) | ilo;
+        if (key_less(om, oo, best, best_ord)) { best = om; best_ord = oo; }
+    }
+    if (lane == 0 && best != INT_MAX && key_less(best, best_ord, res->makespan, res->ordinal)) { res->makespan = best; res->ordinal = best_ord; }
+}
+
+__global__ void completion_reset_kernel(DevCompletion *res)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) { res->makespan = INT_MAX; res->pad = 0; res->ordinal = ~0ull; }
+}
+
+size_t completion_lds_bytes(const CompParams &cp)
+{
+    return (size_t)kCompParamWords * 4 + (size_t)(cp.npaths * cp.N + 2 * cp.D + 2 * cp.K) * kWave * 2;
+}
+
+int launch_completions(const CompParams &cp, uint64_t first, uint64_t count, int32_t *makespan_out, void *ws, int num_cus,
+                       void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const size_t lds = completion_lds_bytes(cp);
+    if (lds > 64 * 1024) return -1;
+    static bool attr_set = false;
+    if (!attr_set && lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)complete_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+        if (e != hipSuccess) return (int)e;
+        attr_set = true;
+    }
+    int per_cu = (int)((160 * 1024) / ((lds + 511) / 512 * 512));
+    if (per_cu > 8) per_cu = 8;
+    if (per_cu < 1) per_cu = 1;
+    uint64_t need = (count + kWave - 1) / kWave;
+    const int blocks = need < (uint64_t)(num_cus * per_cu) ? (int)need : num_cus * per_cu;
+    if (blocks < 1) return 0;
+    CompRec *recs = makespan_out ? nullptr : (CompRec *)((char *)ws + kWsBlockRecOff);
+    hipLaunchKernelGGL(complete_kernel, dim3(blocks), dim3(kWave), lds, st, (const CompParams *)((char *)ws + kWsCompParamsOff), first,
+                       count, recs, makespan_out);
+    int rc = (int)hipGetLastError();
+    if (rc || !recs) return rc;
+    hipLaunchKernelGGL(complete_merge_kernel, dim3(1), dim3(kWave), 0, st, (const CompRec *)recs, blocks,
+                       (DevCompletion *)((char *)ws + kWsCompletionOff));
+    return (int)hipGetLastError();
+}
+
+int launch_completion_reset(void *ws, void *stream)
+{
+    hipLaunchKernelGGL(completion_reset_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream, (DevCompletion *)((char *)ws + kWsCompletionOff));
+    return (int)hipGetLastError();
+}
 
 // ------------------------------------------------------------------ achievable VALU rate
 // Sixteen independent accumulators per lane, one add and one unsigned max each per round: 32
