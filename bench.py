@@ -189,7 +189,7 @@ def main():
                      "frac": achieved / PEAK_INT32_OPS,
                      "peak_measured": peak_measured, "frac_of_measured": achieved / peak_measured,
                      "traffic": TRAFFIC_BYTES_PER_2P24_LAUNCH if chunk == 1 << 24 else None,
-                     "kernel": "eval_fast_kernel<8, 16, 2>", "avg_launch_ms": avg_launch_s * 1e3,
+                     "kernel": "eval_fast_kernel<8, 16, 2, false>", "avg_launch_ms": avg_launch_s * 1e3,
                      "algorithmic_ops_per_candidate": ops_per_launch / chunk,
                      "window_sweeps_per_candidate": sweeps_per_cand},
     }

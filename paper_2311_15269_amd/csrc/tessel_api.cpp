@@ -225,7 +225,22 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
     }
     // tables of the fast kernel: single-device blocks, small memory deltas, few slots
     {
-        bool ok = !kp.tp && kp.nslots <= 32 && kp.nsweeps - 1 <= 24;
+        bool ok = kp.nslots <= 32 && kp.nsweeps - 1 <= 24;
+        // every (device, local symbol) is a code; a type on several devices has one code per device
+        std::vector<std::vector<int>> code_on(K, std::vector<int>(D, -1));
+        for (int d = 0; d < D; d++)
+            for (int y = 0; y < kp.ntd[d]; y++) code_on[(kp.type_of[d] >> (8 * y)) & 0xFFu][d] = d * 4 + y;
+        for (int c = 0; c < kMaxK; c++) kp.home_code[c] = 63;
+        for (int i = 0; i < K; i++) {
+            uint32_t grp = 0;
+            for (int d = 0; d < D; d++) if (code_on[i][d] >= 0) grp |= 1u << code_on[i][d];
+            for (int d = 0; d < D; d++) if (code_on[i][d] >= 0) { kp.grp_code[code_on[i][d]] = grp; kp.home_code[code_on[i][d]] = (uint8_t)home[i]; }
+            const bool multi = (desc->dev_mask[i] & (desc->dev_mask[i] - 1)) != 0;
+            const bool multi_next = kp.succ[i] >= 0 && (desc->dev_mask[kp.succ[i]] & (desc->dev_mask[kp.succ[i]] - 1)) != 0;
+            if (multi) { if (kp.ntp < kMaxD) kp.tp_group[kp.ntp++] = grp; else ok = false; }
+            if (multi || multi_next) kp.slow_mask |= grp;
+        }
+        kp.fast_tp = kp.tp;
         // the memory prefix of a device is kept in 8 bits: entry (lead <= N_R-1 each) plus N_R occurrences
         for (int d = 0; d < D; d++) {
             long span = 0;
@@ -238,7 +253,8 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
             uint32_t su = kp.succ[i] < 0 ? 63u : (uint32_t)home[kp.succ[i]];
             uint32_t pr = kp.pred[i] < 0 ? 63u : (uint32_t)home[kp.pred[i]];
             uint32_t tokbase = (uint32_t)(D + path_of[i] * 2 * NR);
-            kp.info_loc[home[i]] = su | (pr << 6) | (tokbase << 12) | (((uint32_t)desc->mem[i] & 0xFFu) << 18);
+            for (int d = 0; d < D; d++) if (code_on[i][d] >= 0)
+                kp.info_loc[code_on[i][d]] = su | (pr << 6) | (tokbase << 12) | (((uint32_t)desc->mem[i] & 0xFFu) << 18);
         }
         for (int k = 0; k < K && ok; k++) {
             int i = kp.rtopo[k];
@@ -254,8 +270,10 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
             for (int i = 0; i < K && ok; i++) {
                 uint32_t cum = 0;
                 for (int g = i; kp.succ[g] >= 0; g = kp.succ[g]) cum |= 1u << pos[g];
-                kp.cum_code[home[i]] = cum;
-                kp.pred_bit[home[i]] = kp.pred[i] < 0 ? 0u : 1u << pos[kp.pred[i]];
+                for (int d = 0; d < D; d++) if (code_on[i][d] >= 0) {
+                    kp.cum_code[code_on[i][d]] = cum;
+                    kp.pred_bit[code_on[i][d]] = kp.pred[i] < 0 ? 0u : 1u << pos[kp.pred[i]];
+                }
                 if (kp.succ[i] >= 0 && kp.edge_out[i] < kMaxK) kp.dep_bit[kp.edge_out[i]] = kp.cross_out[i] ? 1u << pos[i] : 0u;
             }
             if (desc->num_deps > kMaxK) ok = false;

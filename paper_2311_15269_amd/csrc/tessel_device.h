@@ -106,6 +106,13 @@ struct KParams {
     uint32_t dep_bit[kMaxK];     // by dependency number: its step bit, 0 if both ends sit on the same device set
     uint32_t mpack[kMaxD];       // memory deltas of the device's 4 types, 8 bits each (signed)
     int32_t  eigen_tries;        // sweeps of the first fast pass before a candidate is retried (test knob)
+    // blocks on several devices in the fast kernel: such a type has one code on every device it occupies
+    int32_t  fast_tp;            // the problem has such blocks (the fast kernel then only builds; periods by the general kernel)
+    int32_t  ntp;                // number of such types
+    uint32_t tp_group[kMaxD];    // their codes, one mask per type
+    uint32_t slow_mask;          // codes of types that sit on several devices or whose consumer does
+    uint32_t grp_code[kMaxK];    // by code: all codes of the same type
+    uint8_t  home_code[kMaxK];   // by code: the type's code on its lowest device (63: no such code)
     const int8_t   *leadtab;     // CANONICAL: [nlead][K] in device memory
     const uint64_t *wtab;        // CANONICAL: arrangements by remaining counts, base NR+1 digits
 };
@@ -167,7 +174,7 @@ constexpr size_t kWsTablesMax = 1 << 20;
 constexpr size_t kWsRetryOff = kWsTablesOff + kWsTablesMax;    // candidates that get a second fast pass with more sweeps
 constexpr uint32_t kWsRetryCap = 1u << 21;
 constexpr size_t kWsListOff = kWsRetryOff + (size_t)kWsRetryCap * 8;   // candidates deferred to the general kernel
-constexpr uint32_t kWsListCap = 1u << 16;
+constexpr uint32_t kWsListCap = 1u << 20;
 constexpr size_t kWsCompParamsOff = kWsListOff + (size_t)kWsListCap * 8;   // CompParams
 constexpr size_t kWsBlockRecOff = kWsCompParamsOff + 1024;
 constexpr int kDeferBlocks = 64;                                // grid of the deferred pass

@@ -23,6 +23,7 @@
 #include <stdint.h>
 #include <limits.h>
 #include <stdlib.h>
+#include <algorithm>
 
 #include "tessel_device.h"
 
@@ -484,6 +485,7 @@ struct FastLds {
     uint32_t *chain_tab;  // [32]  KParams::chain_tab
     uint32_t *vtab;       // [32]  KParams::vtab
     uint32_t *cum_tab, *predbit_tab, *depbit_tab;   // [32] each: KParams::cum_code, pred_bit, dep_bit
+    uint32_t *grp_tab;    // [32]  TP variants: KParams::grp_code (in the place of vtab: these variants do not sweep)
     uint4 *rec;           // build: [DM][64] x: low plane, y: high plane, z: not-yet-placed mask,
                           //        w: micro-batches waiting at the input of the 4 types (4 bits each)
                           //           | memory now (signed) << 16
@@ -501,6 +503,10 @@ struct FastConst {
     uint64_t seed;
     int ntd[DM];
     uint32_t mpack[DM];
+    // blocks on several devices (TP variants of the kernel only)
+    int ntp;
+    uint32_t slow;
+    uint32_t tpg[kMaxD];
 };
 
 __device__ __forceinline__ uint32_t bfi(uint32_t sel, uint32_t a, uint32_t b) { return (sel & a) | (~sel & b); }
@@ -653,7 +659,6 @@ __device__ __forceinline__ uint32_t even_bits(uint64_t x)
     return (uint32_t)x;
 }
 
-// MODE: 0 exhaustive spaces, 1 sampled without repair, 2 sampled with repair
 // even bits of a 32-bit word, compacted (bit 2p -> bit p)
 __device__ __forceinline__ uint32_t even_bits32(uint32_t x)
 {
@@ -665,7 +670,12 @@ __device__ __forceinline__ uint32_t even_bits32(uint32_t x)
     return x;
 }
 
-template <int DM, int VM, int MODE>
+// MODE: 0 exhaustive spaces, 1 sampled without repair, 2 sampled with repair.
+// TP: some block type occupies several devices.  Such a type has one code on every device it occupies, and R, X
+// hold all of them.  It is a runnable head only when it heads all its devices; placing it takes its earliest entry
+// out of every one of them.  These variants only build (validity, memory): the periods of the candidates
+// that survive are computed by the general kernel.
+template <int DM, int VM, int MODE, bool TP>
 __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<DM> &C, uint64_t idx, const FastLds &L, int lane,
                                              int &period, int &peak_max, bool valid, uint32_t &nsweeps_used)
 {
@@ -771,6 +781,14 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
             if (has_succ && lead > lead_succ) R |= 1u << (sc & 31u);
             if ((ct >> 20) & 1u) R |= 1u << c;
         }
+        if (TP)
+            for (int c = 0; c < 4 * C.D; c++) {           // the other codes of a type copy its lowest device's
+                const uint32_t h = P.home_code[c];
+                if (h == 63u || h == (uint32_t)c) continue;
+                mu.set((uint32_t)c, mu.get(h));
+                Q.set((uint32_t)c, Q.get(h));
+                R |= ((R >> h) & 1u) << c;
+            }
     }
 
     // per-device records
@@ -808,7 +826,9 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
         const int nj = __builtin_amdgcn_readfirstlane(min(6, total - wi * 6));
 #pragma unroll 1
         for (int j = 0; j < nj; j++) {
-            const uint32_t hm = R & HM;
+            uint32_t hm = R & HM;
+            if (TP)
+                for (int k = 0; k < C.ntp; k++) hm = (hm & C.tpg[k]) == C.tpg[k] ? hm : hm & ~C.tpg[k];
             const uint32_t sel = hm ? hm : (repair ? R : 0u);
             if (!repair && building && sel == 0) { status = kDeadlock; building = false; }
             const uint32_t b = (uint32_t)__builtin_ctz(sel | 0x80000000u);
@@ -846,14 +866,53 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
             // the record's last word: waiting counts (16 bits) and the device's memory prefix (upper 16 bits,
             // signed); one sum updates both
             const uint32_t w_new = a.w + e.x;
-            if (repair || building) {
-                R = r_new; X = x_new; HM = hm_new;
+            const bool active = repair || building;
+            uint32_t r_fin = r_new, x_fin = x_new, hm_fin = hm_new;
+            if (active) {
                 rp->z = alive;
                 rp->w = w_new;
                 if (e.z != 0xFFFFFFFFu) atomicAdd((uint32_t *)((char *)L.rec + e.z) + 4 * lane, e.w);
                 worst = max(worst, (int)w_new >> 16);
                 acc |= c << (5 * j);
             }
+            if (TP) {
+                const bool slow = active && ((C.slow >> c) & 1u);
+                if (__ballot(slow) != 0 && slow) {
+                    // the type sits on several devices, or its consumer does: all codes of the type in R and X, its
+                    // earliest entry out of every other device it occupies, one more waiting micro-batch on every
+                    // device of the consumer (the table entry of such a type leaves all that to this path)
+                    const uint32_t G = L.grp_tab[c], Gs = e.y;
+                    const int mtype = (int)e.w;
+                    x_fin = X | (rest == 0 ? G : 0u);
+                    r_fin = (R & ~G) | (min(rest, more) != 0 ? G : 0u) | (Gs & ~x_fin);
+#pragma unroll
+                    for (int dd = 0; dd < DM; dd++) {
+                        const uint32_t nib = (G >> (4 * dd)) & 15u;
+                        if (dd >= C.D || nib == 0 || 4u * dd == d4) continue;
+                        const uint32_t sym = (uint32_t)__builtin_ctz(nib);
+                        uint4 *rq = L.rec + (dd * kWave + lane);
+                        const uint4 q = *rq;
+                        const uint32_t ls = 0u - (sym & 1u), hs = 0u - (sym >> 1);
+                        const uint32_t same = q.z & ~(q.x ^ ls) & ~(q.y ^ hs);
+                        const uint32_t pos = (uint32_t)__builtin_ctz(same | 0x80000000u);
+                        const uint32_t left = q.z & ~(1u << pos);
+                        const uint32_t wq = q.w + ((uint32_t)mtype << 16) - (1u << (4u * sym));
+                        rq->z = left;
+                        rq->w = wq;
+                        worst = max(worst, (int)wq >> 16);
+                        const uint32_t ph = (uint32_t)__builtin_ctz(left | 0x80000000u);
+                        const uint32_t yh = __builtin_amdgcn_ubfe(q.x, ph, 1) | (__builtin_amdgcn_ubfe(q.y, ph, 1) << 1);
+                        hm_fin = (hm_fin & ~(15u << (4 * dd))) | (1u << (4 * dd + yh));
+                    }
+#pragma unroll
+                    for (int dd = 0; dd < DM; dd++) {
+                        const uint32_t nib = (Gs >> (4 * dd)) & 15u;
+                        if (dd >= C.D || nib == 0) continue;
+                        atomicAdd(&L.rec[dd * kWave + lane].w, 1u << (4u * (uint32_t)__builtin_ctz(nib)));
+                    }
+                }
+            }
+            if (active) { R = r_fin; X = x_fin; HM = hm_fin; }
         }
         prog.set(wi, acc);
     }
@@ -863,6 +922,7 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
         if (d < C.D && C.ntd[d] == 0) worst = max(worst, 0);      // a device without blocks holds nothing
     peak_max = worst;
     if (valid && worst > C.M) status = kMem;
+    if (TP) return status == kOk ? kDeferred : status;            // the general kernel computes the period
     int T = period_fast<DM, VM>(C, L, prog, lane, lead_code, valid && status == kOk, nsweeps_used);
     if (status == kOk) {
         if (T < 0) return kDeferred;
@@ -871,7 +931,7 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
     return status;
 }
 
-template <int DM, int VM, int MODE>
+template <int DM, int VM, int MODE, bool TP = false>
 __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
                                                           BlockRec *__restrict__ recs, int32_t *__restrict__ code_out,
                                                           int32_t *__restrict__ peak_out, const uint64_t *__restrict__ in_list,
@@ -889,6 +949,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     L.type_tab = (uint4 *)(lds + 4 * kMaxK);                  // 128 words
     L.chain_tab = lds + 8 * kMaxK;
     L.vtab = lds + 9 * kMaxK;
+    L.grp_tab = lds + 9 * kMaxK;
     L.cum_tab = lds + 10 * kMaxK;
     L.predbit_tab = lds + 11 * kMaxK;
     L.depbit_tab = lds + 12 * kMaxK;
@@ -910,11 +971,17 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
             const int32_t m = (int32_t)(inf << 6) >> 24;
             const bool has_su = su != 63u, same = has_su && (su >> 2) == dev;
             const uint32_t inc = has_su ? 1u << (4u * (su & 3u)) : 0u;
-            L.type_tab[lane] = make_uint4(((uint32_t)m << 16) - (1u << (4u * y)) + (same ? inc : 0u),
-                                          has_su ? 1u << (su & 31u) : 0u,
-                                          has_su && !same ? (su >> 2) * (kWave * 16u) + 12u : 0xFFFFFFFFu, inc);
+            if (TP && ((P.slow_mask >> lane) & 1u))
+                // a type on several devices, or with such a consumer: the step's slow path does the consumer's part
+                L.type_tab[lane] = make_uint4(((uint32_t)m << 16) - (1u << (4u * y)), has_su ? P.grp_code[su & 31u] : 0u,
+                                              0xFFFFFFFFu, (uint32_t)m);
+            else
+                L.type_tab[lane] = make_uint4(((uint32_t)m << 16) - (1u << (4u * y)) + (same ? inc : 0u),
+                                              has_su ? 1u << (su & 31u) : 0u,
+                                              has_su && !same ? (su >> 2) * (kWave * 16u) + 12u : 0xFFFFFFFFu, inc);
         }
-        L.chain_tab[lane] = P.chain_tab[lane]; L.vtab[lane] = lane < 24 ? P.vtab[lane] : 0u;
+        L.chain_tab[lane] = P.chain_tab[lane];
+        if (TP) L.grp_tab[lane] = P.grp_code[lane]; else L.vtab[lane] = lane < 24 ? P.vtab[lane] : 0u;
         L.cum_tab[lane] = P.cum_code[lane]; L.predbit_tab[lane] = P.pred_bit[lane]; L.depbit_tab[lane] = P.dep_bit[lane];
     }
     __syncthreads();
@@ -924,6 +991,9 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     C.step_q16 = P.step_q16; C.seed = P.seed;
 #pragma unroll
     for (int d = 0; d < DM; d++) { C.ntd[d] = P.ntd[d]; C.mpack[d] = P.mpack[d]; }
+    C.ntp = TP ? P.ntp : 0; C.slow = TP ? P.slow_mask : 0u;
+#pragma unroll
+    for (int k = 0; k < kMaxD; k++) C.tpg[k] = TP ? P.tp_group[k] : 0u;
 
     int best = INT_MAX;
     uint64_t best_idx = 0;
@@ -941,7 +1011,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
         const uint64_t idx = !valid ? first : in_list ? in_list[kk] : first + kk;
         const uint64_t k = idx - first;
         int period, pk;
-        int status = evaluate_fast<DM, VM, MODE>(P, C, idx, L, lane, period, pk, valid, nsw);
+        int status = evaluate_fast<DM, VM, MODE, TP>(P, C, idx, L, lane, period, pk, valid, nsw);
         if (valid && status == kDeferred) {
             // no eigenvector within the sweeps of this pass: the next pass scores it
             const uint32_t at = atomicAdd(out_count, 1u);
@@ -1129,6 +1199,14 @@ static fast_fn pick_fast(const KParams &kp)
 {
     const int V = kp.nsweeps - 1;
     if (!kp.fast_ok) return nullptr;
+    if (kp.fast_tp) {
+        // blocks on several devices: build-only variants (no sweeps, so the size of the boundary vector does not matter)
+        if (kp.space == kSampledRepair)
+            return kp.D <= 2 ? eval_fast_kernel<2, 4, 2, true> : kp.D <= 4 ? eval_fast_kernel<4, 8, 2, true> : eval_fast_kernel<8, 16, 2, true>;
+        if (kp.space == kSampledStrict)
+            return kp.D <= 2 ? eval_fast_kernel<2, 4, 1, true> : kp.D <= 4 ? eval_fast_kernel<4, 8, 1, true> : eval_fast_kernel<8, 16, 1, true>;
+        return kp.D <= 2 ? eval_fast_kernel<2, 4, 0, true> : kp.D <= 4 ? eval_fast_kernel<4, 8, 0, true> : eval_fast_kernel<8, 16, 0, true>;
+    }
     if (kp.space == kSampledRepair) {
         if (kp.D <= 2) return V <= 4 ? eval_fast_kernel<2, 4, 2> : eval_fast_kernel<2, 24, 2>;
         if (kp.D <= 4) return V <= 8 ? eval_fast_kernel<4, 8, 2> : eval_fast_kernel<4, 24, 2>;
@@ -1213,6 +1291,20 @@ static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *
         return rc ? -rc : blocks;
     }
     const size_t lds = fast_lds_bytes(kp);
+    if (kp.fast_tp) {
+        // blocks on several devices: the fast kernel builds and checks the memory; every candidate that survives goes
+        // straight to the general kernel through the deferred list (the caller keeps the range within its capacity)
+        hipLaunchKernelGGL(ff, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, (const uint64_t *)nullptr,
+                           (const uint32_t *)nullptr, 0u, 0, list, &res->defer_count, kWsListCap, &res->overflow);
+        int rc = (int)hipGetLastError();
+        if (rc) return -rc;
+        int per_cu = (int)((160 * 1024) / ((general_lds_bytes(kp) + 511) / 512 * 512));
+        per_cu = per_cu > 8 ? 8 : per_cu < 1 ? 1 : per_cu;
+        const int blocks_g = std::min(blocks, num_cus * per_cu);
+        rc = launch_general(kp, kp_dev, first, count, blocks_g, recs ? recs + blocks : nullptr, code, peak, nullptr, list,
+                            &res->defer_count, st);
+        return rc ? -rc : blocks + blocks_g;
+    }
     hipLaunchKernelGGL(ff, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, (const uint64_t *)nullptr,
                        (const uint32_t *)nullptr, 0u, kp.eigen_tries, retry, &res->retry_count, kWsRetryCap, &res->overflow);
     int rc = (int)hipGetLastError();
@@ -1236,8 +1328,9 @@ int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int
     BlockRec *recs = (BlockRec *)((char *)ws + kWsBlockRecOff);
     DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
     // pieces of at most kMaxPerLaunch candidates, so that the lists of unfinished candidates stay small
+    const uint64_t max_piece = kp.fast_tp && kp.fast_ok ? kWsListCap : kMaxPerLaunch;
     for (uint64_t done = 0; done < count;) {
-        const uint64_t piece = count - done < kMaxPerLaunch ? count - done : kMaxPerLaunch;
+        const uint64_t piece = count - done < max_piece ? count - done : max_piece;
         int n = launch_pass(kp, first + done, piece, ws, num_cus, recs, nullptr, nullptr, false, st);
         if (n < 0) return -n;
         if (n > 0) {
@@ -1255,8 +1348,9 @@ int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *cod
 {
     hipStream_t st = (hipStream_t)stream;
     DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
+    const uint64_t max_piece = kp.fast_tp && kp.fast_ok && !general ? kWsListCap : kMaxPerLaunch;
     for (uint64_t done = 0; done < count;) {
-        const uint64_t piece = count - done < kMaxPerLaunch ? count - done : kMaxPerLaunch;
+        const uint64_t piece = count - done < max_piece ? count - done : max_piece;
         int n = launch_pass(kp, first + done, piece, ws, num_cus, nullptr, code + done, peak ? peak + done : nullptr, general, st);
         if (n < 0) return -n;
         hipLaunchKernelGGL(clear_defer_kernel, dim3(1), dim3(1), 0, st, res);

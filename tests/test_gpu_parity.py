@@ -223,6 +223,35 @@ def _shape_cases():
     cases.append({"name": "tp-factorial", "D": 2, "K": 3, "NR": 2, "M": 4, "t": [1, 2, 1], "m": [1, 0, -1],
                   "dev_mask": [0b11, 0b01, 0b11], "deps": [(0, 1), (1, 2)], "space": "factorial", "seed": 0,
                   "lead_step_q16": 0, "fixed_leads": None})
+    # blocks on several devices in other arrangements: on two of four devices in the middle of the chain, two such
+    # types in a row, every type on all devices, eight devices, canonical space, a second chain beside them
+    cases.append({"name": "tp-middle", "D": 4, "K": 8, "NR": 3, "M": 5, "t": [1, 2, 1, 3, 2, 1, 2, 1],
+                  "m": [1, 1, 1, 1, -1, -1, -1, -1], "dev_mask": [1, 2, 0b1100, 8, 8, 0b1100, 2, 1],
+                  "deps": [(i, i + 1) for i in range(7)], "space": "sampled_repair", "seed": 21, "lead_step_q16": 20000,
+                  "fixed_leads": None})
+    cases.append({"name": "tp-two-in-a-row", "D": 3, "K": 6, "NR": 4, "M": 6, "t": [2, 1, 1, 2, 1, 3],
+                  "m": [1, 1, 1, -1, -1, -1], "dev_mask": [0b011, 0b110, 4, 4, 0b110, 0b011],
+                  "deps": [(i, i + 1) for i in range(5)], "space": "sampled_repair", "seed": 22, "lead_step_q16": 30000,
+                  "fixed_leads": None})
+    cases.append({"name": "tp-everything", "D": 2, "K": 4, "NR": 3, "M": 3, "t": [1, 2, 2, 1], "m": [1, 1, -1, -1],
+                  "dev_mask": [3, 3, 3, 3], "deps": [(0, 1), (1, 2), (2, 3)], "space": "sampled_repair", "seed": 23,
+                  "lead_step_q16": 40000, "fixed_leads": None})
+    cases.append({"name": "tp-8dev", "D": 8, "K": 18, "NR": 4, "M": 13,
+                  "t": [2] + [1 + (i % 3) for i in range(8)] + [2 * (1 + ((7 - i) % 3)) for i in range(8)] + [4],
+                  "m": [2] + [1] * 8 + [-1] * 8 + [-2],
+                  "dev_mask": [0xFF] + [1 << i for i in range(8)] + [1 << (7 - i) for i in range(8)] + [0xFF],
+                  "deps": [(i, i + 1) for i in range(17)], "space": "sampled_repair", "seed": 24, "lead_step_q16": 30000,
+                  "fixed_leads": None})
+    cases.append({"name": "tp-strict", "D": 2, "K": 4, "NR": 2, "M": 4, "t": [1, 2, 2, 1], "m": [1, 0, 0, -1],
+                  "dev_mask": [3, 1, 2, 3], "deps": [(0, 1), (1, 2), (2, 3)], "space": "sampled_strict", "seed": 25,
+                  "lead_step_q16": 30000, "fixed_leads": None})
+    cases.append({"name": "tp-canonical", "D": 2, "K": 4, "NR": 2, "M": 4, "t": [1, 2, 2, 1], "m": [1, 0, 0, -1],
+                  "dev_mask": [3, 1, 2, 3], "deps": [(0, 1), (1, 2), (2, 3)], "space": "canonical", "seed": 0,
+                  "lead_step_q16": 0, "fixed_leads": None})
+    cases.append({"name": "tp-and-a-second-chain", "D": 3, "K": 6, "NR": 3, "M": 4, "t": [1, 2, 1, 2, 1, 3],
+                  "m": [1, 0, -1, 1, 0, -1], "dev_mask": [0b011, 2, 0b011, 4, 0b101, 4],
+                  "deps": [(0, 1), (1, 2), (3, 4), (4, 5)], "space": "sampled_repair", "seed": 26, "lead_step_q16": 30000,
+                  "fixed_leads": None})
     # two independent chains (bidirectional pipelines sharing the devices), forward-only blocks with m = 0
     cases.append({"name": "two-chains", "D": 3, "K": 6, "NR": 3, "M": 1, "t": [1, 2, 1, 2, 1, 3], "m": [0] * 6,
                   "dev_mask": [1, 2, 4, 4, 2, 1], "deps": [(0, 1), (1, 2), (3, 4), (4, 5)], "space": "sampled_repair",
