@@ -140,12 +140,45 @@ __device__ __forceinline__ int reduced_slot(const KParams &P, int v)
 // keeps start times non-negative).  Karp: with x(j) the vector after j+1 sweeps from 0 and
 // n = V+1 sweeps in total, lambda = max_v min_{j<n-1} (x_v(n-1) - x_v(j)) / (n-1-j).
 // Two passes over the same sweeps so that no history has to be stored.  (General kernel.)
+// Before that, the shortcut the fast kernel lives on: iterate x <- F(x) from 0; as soon as every boundary value that
+// means anything (`live`: devices with blocks, micro-batches that are in flight at the boundary) has grown by the
+// same delta over one sweep, x is an eigenvector and delta the maximum cycle ratio, exactly.
+constexpr int kGeneralTries = 6;
 template <int VM, bool TP>
 __device__ __forceinline__ int least_period(const KParams &P, const uint16_t *prog, uint32_t *state, const int32_t *t_tab,
-                            const uint32_t *mask_tab)
+                            const uint32_t *mask_tab, uint32_t live)
 {
     const int V = P.nsweeps - 1, n = P.nsweeps;
     uint32_t xn[VM], bn[VM], bd[VM];
+    for (int s = 0; s < P.nslots; s++) state[s * kWave] = 0;
+    {
+        uint32_t *prev = xn;
+#pragma unroll
+        for (int v = 0; v < VM; v++) prev[v] = 0;
+        bool done = false;
+        uint32_t T = 0;
+        for (int j = 0; j < kGeneralTries; j++) {
+            if (__ballot(!done) == 0) break;
+            sweep_window<TP>(P, prog, state, t_tab, mask_tab);
+            bool same = true, have = false;
+            uint32_t delta = 0;
+#pragma unroll
+            for (int v = 0; v < VM; v++) {
+                if (v < V) {
+                    const uint32_t x = state[reduced_slot(P, v) * kWave];
+                    const uint32_t dv = x - prev[v];
+                    prev[v] = x;
+                    if (live >> v & 1u) {
+                        if (!have) { delta = dv; have = true; }
+                        else if (dv != delta) same = false;
+                    }
+                }
+            }
+            if (!done && same && have) { T = delta; done = true; }
+        }
+        // every lane of the wave is here for a candidate that needs a period (the caller's lanes diverged before)
+        if (done) return (int)T;
+    }
     for (int s = 0; s < P.nslots; s++) state[s * kWave] = 0;
     for (int j = 0; j < n; j++) sweep_window<TP>(P, prog, state, t_tab, mask_tab);
 #pragma unroll
@@ -435,8 +468,19 @@ __device__ __forceinline__ int evaluate(const KParams &P, uint64_t idx, uint16_t
     if (peak_max > P.M) return kMem;
 
     // ---------------- period
-    period = P.tp ? least_period<VM, true>(P, prog, state, t_tab, mask_tab)
-                  : least_period<VM, false>(P, prog, state, t_tab, mask_tab);
+    // boundary values that mean anything: devices with blocks; micro-batch j of a chain is in flight at the
+    // boundary when the chain's first block is j or more ahead (its counter now reads lead + N_R)
+    uint32_t live = 0;
+    for (int d = 0; d < P.D; d++) live |= (P.ntd[d] > 0 ? 1u : 0u) << d;
+    for (int g = 0, path = 0; g < P.K; g++)
+        if (P.pred[g] < 0) {
+            const int lead = (int)mu.get((uint32_t)g) - P.NR;
+            for (int j = 0; j < P.NR; j++)
+                if (lead > j && P.D + path * P.NR + j < 32) live |= 1u << (P.D + path * P.NR + j);
+            path++;
+        }
+    period = P.tp ? least_period<VM, true>(P, prog, state, t_tab, mask_tab, live)
+                  : least_period<VM, false>(P, prog, state, t_tab, mask_tab, live);
     return kOk;
 }
 
