@@ -529,7 +529,7 @@ struct FastLds {
     uint32_t *chain_tab;  // [32]  KParams::chain_tab
     uint32_t *vtab;       // [32]  KParams::vtab
     uint32_t *cum_tab, *predbit_tab, *depbit_tab;   // [32] each: KParams::cum_code, pred_bit, dep_bit
-    uint32_t *grp_tab;    // [32]  TP variants: KParams::grp_code (in the place of vtab: these variants do not sweep)
+    uint32_t *grp_tab;    // [32]  TP variants: KParams::grp_code
     uint4 *rec;           // build: [DM][64] x: low plane, y: high plane, z: not-yet-placed mask,
                           //        w: micro-batches waiting at the input of the 4 types (4 bits each)
                           //           | memory now (signed) << 16
@@ -559,8 +559,6 @@ __device__ __forceinline__ uint32_t bfi(uint32_t sel, uint32_t a, uint32_t b) { 
 // being sunk into later branches
 #define TESSEL_PIN(x) asm volatile("" : "+v"(x))
 
-// one block of the window: s = max(device free, previous block of the micro-batch); both become s + t.
-// The micro-batch it handles is the device record's counter of its type.
 // One block of the window: s = max(device free, previous block of the micro-batch); both become s + t.  The
 // micro-batch it handles is the device's counter of its type, `cnt` (read by the caller, which has already
 // written the incremented word back and may have the next node's counter read in flight).
@@ -574,8 +572,27 @@ __device__ __forceinline__ void sweep_node(const FastLds &L, const uint4 tt, uin
     *tk = en;
 }
 
-// One sweep of the window over the program, then the window boundary.
+// The same for problems with blocks on several devices: the block waits for all devices of its code group `G` (one
+// nibble per device) and frees them together.  Counter and token are those of the type's code on its lowest device,
+// which is the code the program holds.
 template <int DM>
+__device__ __forceinline__ void sweep_node_group(const FastLds &L, const uint4 tt, uint32_t cnt, uint32_t lane, uint32_t G, int D)
+{
+    const uint32_t mu = __builtin_amdgcn_ubfe(cnt, tt.w, 4);
+    uint32_t *tk = (uint32_t *)((char *)L.tok + (tt.y + lane * 4u + (mu << 8)));
+    uint32_t s = *tk;
+#pragma unroll
+    for (int dd = 0; dd < DM; dd++)
+        if (dd < D && ((G >> (4 * dd)) & 15u)) s = max(s, L.dfree[dd * kWave + lane]);
+    const uint32_t en = s + tt.x;
+#pragma unroll
+    for (int dd = 0; dd < DM; dd++)
+        if (dd < D && ((G >> (4 * dd)) & 15u)) L.dfree[dd * kWave + lane] = en;
+    *tk = en;
+}
+
+// One sweep of the window over the program, then the window boundary.
+template <int DM, bool TP>
 __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds &L, const FastProgram &prog, int lane,
                                            const Mu &lead_code, bool active)
 {
@@ -584,6 +601,16 @@ __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds
     if (!active) return;
     const uint32_t lane4 = (uint32_t)lane * 4u;
     const int full = C.total / 6, tail = C.total - 6 * full;
+    if (TP) {
+        for (int k = 0; k < C.total; k++) {
+            const uint32_t code = (prog.get(k / 6) >> (5 * (k % 6))) & 31u;
+            const uint4 tt = L.tt_tab[code];
+            uint32_t *cp = (uint32_t *)((char *)L.dcnt + (tt.z + lane4));
+            const uint32_t cnt = *cp;
+            *cp = cnt + (1u << tt.w);
+            sweep_node_group<DM>(L, tt, cnt, (uint32_t)lane, L.grp_tab[code], C.D);
+        }
+    } else {
     for (int i = 0; i < full; i++) {
         const uint32_t w = prog.get(i);
         // the six table entries first: they depend on the word only, so their reads leave the chain of the nodes
@@ -617,6 +644,7 @@ __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds
                 sweep_node(L, tt, cnt, lane4);
             }
     }
+    }
     // window boundary: micro-batches mu >= N_R are mu - N_R of the next window; counters restart at the leads
     for (int p = 0; p < C.npaths; p++)
         for (int mu = 0; mu < C.NR; mu++) {
@@ -644,7 +672,7 @@ __device__ __forceinline__ void reset_sweep_state(const FastConst<DM> &C, const 
 // cycle ratio, exactly.  Almost every candidate gets there within two or three sweeps; one that has
 // not after the sweeps this pass allows (C.eigen_tries) is handed on: to a second pass of this kernel
 // with more sweeps, then to the general kernel (Karp's formula).
-template <int DM, int VM>
+template <int DM, int VM, bool TP>
 __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds &L, const FastProgram &prog, int lane,
                                            const Mu &lead_code, bool want,
                                            uint32_t &nsweeps_used)
@@ -670,7 +698,7 @@ __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds
     bool done = !want;
     for (int j = 0; j < C.eigen_tries; j++) {
         if (__ballot(!done) == 0) break;
-        sweep_fast<DM>(C, L, prog, lane, lead_code, !done);
+        sweep_fast<DM, TP>(C, L, prog, lane, lead_code, !done);
         nsweeps_used += done ? 0u : 1u;
         bool same = true, have = false;
         uint32_t delta = 0;
@@ -917,7 +945,8 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
                 rp->w = w_new;
                 if (e.z != 0xFFFFFFFFu) atomicAdd((uint32_t *)((char *)L.rec + e.z) + 4 * lane, e.w);
                 worst = max(worst, (int)w_new >> 16);
-                acc |= c << (5 * j);
+                // the program names a type by its code on its lowest device
+                acc |= (TP ? (uint32_t)__builtin_ctz(L.grp_tab[c]) : c) << (5 * j);
             }
             if (TP) {
                 const bool slow = active && ((C.slow >> c) & 1u);
@@ -966,8 +995,7 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
         if (d < C.D && C.ntd[d] == 0) worst = max(worst, 0);      // a device without blocks holds nothing
     peak_max = worst;
     if (valid && worst > C.M) status = kMem;
-    if (TP) return status == kOk ? kDeferred : status;            // the general kernel computes the period
-    int T = period_fast<DM, VM>(C, L, prog, lane, lead_code, valid && status == kOk, nsweeps_used);
+    int T = period_fast<DM, VM, TP>(C, L, prog, lane, lead_code, valid && status == kOk, nsweeps_used);
     if (status == kOk) {
         if (T < 0) return kDeferred;
         period = T;
@@ -993,11 +1021,11 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     L.type_tab = (uint4 *)(lds + 4 * kMaxK);                  // 128 words
     L.chain_tab = lds + 8 * kMaxK;
     L.vtab = lds + 9 * kMaxK;
-    L.grp_tab = lds + 9 * kMaxK;
+    L.grp_tab = lds + kFastTableWords;                        // TP variants only
     L.cum_tab = lds + 10 * kMaxK;
     L.predbit_tab = lds + 11 * kMaxK;
     L.depbit_tab = lds + 12 * kMaxK;
-    uint32_t *base = lds + kFastTableWords;
+    uint32_t *base = lds + kFastTableWords + (TP ? kMaxK : 0);
     L.rec = (uint4 *)base;
     // the sweep state is only used once the build is over: it shares the records' space when it fits
     const int ntok = P.nslots - P.D;
@@ -1025,7 +1053,8 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
                                               has_su && !same ? (su >> 2) * (kWave * 16u) + 12u : 0xFFFFFFFFu, inc);
         }
         L.chain_tab[lane] = P.chain_tab[lane];
-        if (TP) L.grp_tab[lane] = P.grp_code[lane]; else L.vtab[lane] = lane < 24 ? P.vtab[lane] : 0u;
+        L.vtab[lane] = lane < 24 ? P.vtab[lane] : 0u;
+        if (TP) L.grp_tab[lane] = P.grp_code[lane] ? P.grp_code[lane] : 1u << lane;
         L.cum_tab[lane] = P.cum_code[lane]; L.predbit_tab[lane] = P.pred_bit[lane]; L.depbit_tab[lane] = P.dep_bit[lane];
     }
     __syncthreads();
@@ -1244,12 +1273,12 @@ static fast_fn pick_fast(const KParams &kp)
     const int V = kp.nsweeps - 1;
     if (!kp.fast_ok) return nullptr;
     if (kp.fast_tp) {
-        // blocks on several devices: build-only variants (no sweeps, so the size of the boundary vector does not matter)
+        // blocks on several devices
         if (kp.space == kSampledRepair)
-            return kp.D <= 2 ? eval_fast_kernel<2, 4, 2, true> : kp.D <= 4 ? eval_fast_kernel<4, 8, 2, true> : eval_fast_kernel<8, 16, 2, true>;
+            return kp.D <= 2 ? eval_fast_kernel<2, 24, 2, true> : kp.D <= 4 ? eval_fast_kernel<4, 24, 2, true> : eval_fast_kernel<8, 24, 2, true>;
         if (kp.space == kSampledStrict)
-            return kp.D <= 2 ? eval_fast_kernel<2, 4, 1, true> : kp.D <= 4 ? eval_fast_kernel<4, 8, 1, true> : eval_fast_kernel<8, 16, 1, true>;
-        return kp.D <= 2 ? eval_fast_kernel<2, 4, 0, true> : kp.D <= 4 ? eval_fast_kernel<4, 8, 0, true> : eval_fast_kernel<8, 16, 0, true>;
+            return kp.D <= 2 ? eval_fast_kernel<2, 24, 1, true> : kp.D <= 4 ? eval_fast_kernel<4, 24, 1, true> : eval_fast_kernel<8, 24, 1, true>;
+        return kp.D <= 2 ? eval_fast_kernel<2, 24, 0, true> : kp.D <= 4 ? eval_fast_kernel<4, 24, 0, true> : eval_fast_kernel<8, 24, 0, true>;
     }
     if (kp.space == kSampledRepair) {
         if (kp.D <= 2) return V <= 4 ? eval_fast_kernel<2, 4, 2> : eval_fast_kernel<2, 24, 2>;
@@ -1275,7 +1304,7 @@ static size_t fast_lds_bytes(const KParams &kp)
 {
     const int ntok = kp.nslots - kp.D;
     const bool share = kp.D * 2 + ntok <= fast_dm(kp) * 4;
-    return (size_t)kFastTableWords * 4 + (size_t)fast_dm(kp) * kWave * 16 + (share ? 0 : (size_t)(kp.D * 2 + ntok) * kWave * 4);
+    return (size_t)(kFastTableWords + (kp.fast_tp ? kMaxK : 0)) * 4 + (size_t)fast_dm(kp) * kWave * 16 + (share ? 0 : (size_t)(kp.D * 2 + ntok) * kWave * 4);
 }
 
 LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
@@ -1335,20 +1364,6 @@ static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *
         return rc ? -rc : blocks;
     }
     const size_t lds = fast_lds_bytes(kp);
-    if (kp.fast_tp) {
-        // blocks on several devices: the fast kernel builds and checks the memory; every candidate that survives goes
-        // straight to the general kernel through the deferred list (the caller keeps the range within its capacity)
-        hipLaunchKernelGGL(ff, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, (const uint64_t *)nullptr,
-                           (const uint32_t *)nullptr, 0u, 0, list, &res->defer_count, kWsListCap, &res->overflow);
-        int rc = (int)hipGetLastError();
-        if (rc) return -rc;
-        int per_cu = (int)((160 * 1024) / ((general_lds_bytes(kp) + 511) / 512 * 512));
-        per_cu = per_cu > 8 ? 8 : per_cu < 1 ? 1 : per_cu;
-        const int blocks_g = std::min(blocks, num_cus * per_cu);
-        rc = launch_general(kp, kp_dev, first, count, blocks_g, recs ? recs + blocks : nullptr, code, peak, nullptr, list,
-                            &res->defer_count, st);
-        return rc ? -rc : blocks + blocks_g;
-    }
     hipLaunchKernelGGL(ff, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, (const uint64_t *)nullptr,
                        (const uint32_t *)nullptr, 0u, kp.eigen_tries, retry, &res->retry_count, kWsRetryCap, &res->overflow);
     int rc = (int)hipGetLastError();
@@ -1372,7 +1387,7 @@ int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int
     BlockRec *recs = (BlockRec *)((char *)ws + kWsBlockRecOff);
     DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
     // pieces of at most kMaxPerLaunch candidates, so that the lists of unfinished candidates stay small
-    const uint64_t max_piece = kp.fast_tp && kp.fast_ok ? kWsListCap : kMaxPerLaunch;
+    const uint64_t max_piece = kMaxPerLaunch;
     for (uint64_t done = 0; done < count;) {
         const uint64_t piece = count - done < max_piece ? count - done : max_piece;
         int n = launch_pass(kp, first + done, piece, ws, num_cus, recs, nullptr, nullptr, false, st);
@@ -1392,7 +1407,7 @@ int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *cod
 {
     hipStream_t st = (hipStream_t)stream;
     DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
-    const uint64_t max_piece = kp.fast_tp && kp.fast_ok && !general ? kWsListCap : kMaxPerLaunch;
+    const uint64_t max_piece = kMaxPerLaunch;
     for (uint64_t done = 0; done < count;) {
         const uint64_t piece = count - done < max_piece ? count - done : max_piece;
         int n = launch_pass(kp, first + done, piece, ws, num_cus, nullptr, code + done, peak ? peak + done : nullptr, general, st);
