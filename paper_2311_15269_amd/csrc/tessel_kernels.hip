@@ -908,7 +908,6 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
             TESSEL_PIN(d4);
             uint4 *rp = (uint4 *)((char *)L.rec + ((d4 << 8) + lane16));
             uint4 a = *rp;
-            TESSEL_PIN(a.x); TESSEL_PIN(a.y); TESSEL_PIN(a.z); TESSEL_PIN(a.w);
             // earliest remaining entry of the device whose type is runnable: a 4-way multiplexer keyed by the two
             // planes.  (When the device was picked for its runnable head this is the head: nothing precedes it.)
             const int r4 = (int)(R >> d4);
