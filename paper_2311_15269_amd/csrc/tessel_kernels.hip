@@ -533,10 +533,10 @@ struct FastLds {
     uint4 *rec;           // build: [DM][64] x: low plane, y: high plane, z: not-yet-placed mask,
                           //        w: micro-batches waiting at the input of the 4 types (4 bits each)
                           //           | memory now (signed) << 16
-    // sweeps: three arrays [slot][64] in a row, so that boundary value v of slot s is word s * 64 + lane
-    uint32_t *dfree;      // [D] time at which the device is free
+    // sweeps: three arrays [slot][64] in a row at distances known at compile time
+    uint32_t *dfree;      // [DM] time at which the device is free
+    uint32_t *dcnt;       // [DM] next micro-batch of the device's 4 types (4 bits each)
     uint32_t *tok;        // [token slots] end time of the micro-batch's latest block
-    uint32_t *dcnt;       // [D] next micro-batch of the device's 4 types (4 bits each)
 };
 
 // problem scalars, read once per workgroup
@@ -564,9 +564,11 @@ __device__ __forceinline__ uint32_t bfi(uint32_t sel, uint32_t a, uint32_t b) { 
 // written the incremented word back and may have the next node's counter read in flight).
 __device__ __forceinline__ void sweep_node(const FastLds &L, const uint4 tt, uint32_t cnt, uint32_t lane4)
 {
+    // device times, counters and tokens lie at fixed distances in one array, so the three addresses of a block
+    // share their registers: tt.z = the device's offset, tt.y = the chain's first token slot
     const uint32_t mu = __builtin_amdgcn_ubfe(cnt, tt.w, 4);
     uint32_t *fr = (uint32_t *)((char *)L.dfree + (tt.z + lane4));
-    uint32_t *tk = (uint32_t *)((char *)L.tok + (tt.y + lane4 + (mu << 8)));
+    uint32_t *tk = (uint32_t *)((char *)L.dfree + (tt.y + lane4 + (mu << 8)));
     const uint32_t en = max(*fr, *tk) + tt.x;
     *fr = en;
     *tk = en;
@@ -579,7 +581,7 @@ template <int DM>
 __device__ __forceinline__ void sweep_node_group(const FastLds &L, const uint4 tt, uint32_t cnt, uint32_t lane, uint32_t G, int D)
 {
     const uint32_t mu = __builtin_amdgcn_ubfe(cnt, tt.w, 4);
-    uint32_t *tk = (uint32_t *)((char *)L.tok + (tt.y + lane * 4u + (mu << 8)));
+    uint32_t *tk = (uint32_t *)((char *)L.dfree + (tt.y + lane * 4u + (mu << 8)));
     uint32_t s = *tk;
 #pragma unroll
     for (int dd = 0; dd < DM; dd++)
@@ -605,7 +607,7 @@ __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds
         for (int k = 0; k < C.total; k++) {
             const uint32_t code = (prog.get(k / 6) >> (5 * (k % 6))) & 31u;
             const uint4 tt = L.tt_tab[code];
-            uint32_t *cp = (uint32_t *)((char *)L.dcnt + (tt.z + lane4));
+            uint32_t *cp = (uint32_t *)((char *)L.dfree + (tt.z + lane4)) + DM * kWave;
             const uint32_t cnt = *cp;
             *cp = cnt + (1u << tt.w);
             sweep_node_group<DM>(L, tt, cnt, (uint32_t)lane, L.grp_tab[code], C.D);
@@ -622,12 +624,12 @@ __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds
         // counters run one node ahead of the times: the counter word goes back incremented at once, the next
         // node's read follows it (LDS keeps a wave's accesses in order), and only then this node waits for its
         // device time and token
-        uint32_t cnt = *(uint32_t *)((char *)L.dcnt + (tt[0].z + lane4));
+        uint32_t cnt = *((uint32_t *)((char *)L.dfree + (tt[0].z + lane4)) + DM * kWave);
 #pragma unroll
         for (int j = 0; j < 6; j++) {
-            *(uint32_t *)((char *)L.dcnt + (tt[j].z + lane4)) = cnt + (1u << tt[j].w);
+            *((uint32_t *)((char *)L.dfree + (tt[j].z + lane4)) + DM * kWave) = cnt + (1u << tt[j].w);
             uint32_t next = 0;
-            if (j < 5) next = *(uint32_t *)((char *)L.dcnt + (tt[j + 1].z + lane4));
+            if (j < 5) next = *((uint32_t *)((char *)L.dfree + (tt[j + 1].z + lane4)) + DM * kWave);
             sweep_node(L, tt[j], cnt, lane4);
             cnt = next;
         }
@@ -638,7 +640,7 @@ __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds
         for (int j = 0; j < 5; j++)
             if (j < tail) {
                 const uint4 tt = L.tt_tab[(w >> (5 * j)) & 31u];
-                uint32_t *cp = (uint32_t *)((char *)L.dcnt + (tt.z + lane4));
+                uint32_t *cp = (uint32_t *)((char *)L.dfree + (tt.z + lane4)) + DM * kWave;
                 const uint32_t cnt = *cp;
                 *cp = cnt + (1u << tt.w);
                 sweep_node(L, tt, cnt, lane4);
@@ -660,7 +662,8 @@ __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds
 template <int DM>
 __device__ __forceinline__ void reset_sweep_state(const FastConst<DM> &C, const FastLds &L, int lane, const Mu &lead_code)
 {
-    for (int s = 0; s < C.nslots; s++) L.dfree[s * kWave + lane] = 0;         // device times and tokens
+    for (int d = 0; d < C.D; d++) L.dfree[d * kWave + lane] = 0;
+    for (int s = 0; s < C.nslots - C.D; s++) L.tok[s * kWave + lane] = 0;
 #pragma unroll
     for (int d = 0; d < DM; d++)
         if (d < C.D) L.dcnt[d * kWave + lane] = (uint32_t)((d < 4 ? lead_code.lo : lead_code.hi) >> (16 * (d & 3))) & 0xFFFFu;
@@ -680,7 +683,10 @@ __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds
     const int V = C.nsweeps - 1;
     const uint32_t lane4 = (uint32_t)lane * 4u;
     // byte offset (from the device times) of boundary value v: a device's free time or a carried token
-    auto value_offset = [&](uint32_t e) -> uint32_t { return (e & 63u) * (kWave * 4u) + lane4; };
+    auto value_offset = [&](uint32_t e) -> uint32_t {
+        const uint32_t slot = e & 63u;
+        return ((e >> 6 & 1u) ? slot : 2u * DM + slot - (uint32_t)C.D) * (kWave * 4u) + lane4;
+    };
     uint32_t live = 0;                                    // per lane: which boundary values mean anything
 #pragma unroll
     for (int v = 0; v < VM; v++) {
@@ -1028,14 +1034,14 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     L.rec = (uint4 *)base;
     // the sweep state is only used once the build is over: it shares the records' space when it fits
     const int ntok = P.nslots - P.D;
-    const bool share = P.D * 2 + ntok <= DM * 4;
+    const bool share = DM * 2 + ntok <= DM * 4;
     uint32_t *sweep_base = share ? base : base + DM * kWave * 4;
-    L.dfree = sweep_base;
-    L.tok = sweep_base + P.D * kWave;
-    L.dcnt = sweep_base + P.nslots * kWave;
+    L.dfree = sweep_base;                       // [DM] device times, [DM] counters, then the tokens
+    L.dcnt = sweep_base + DM * kWave;
+    L.tok = sweep_base + 2 * DM * kWave;
     if (lane < kMaxK) {
         const uint32_t inf = P.info_loc[lane];
-        L.tt_tab[lane] = make_uint4((uint32_t)P.t_loc[lane], ((((inf >> 12) & 63u) - (uint32_t)P.D) << 8),
+        L.tt_tab[lane] = make_uint4((uint32_t)P.t_loc[lane], ((((inf >> 12) & 63u) - (uint32_t)P.D + 2u * DM) << 8),
                                     ((uint32_t)lane >> 2) * (kWave * 4u), 4u * ((uint32_t)lane & 3u));
         {
             const uint32_t su = inf & 63u, dev = (uint32_t)lane >> 2, y = (uint32_t)lane & 3u;
@@ -1302,8 +1308,9 @@ static size_t general_lds_bytes(const KParams &kp)
 static size_t fast_lds_bytes(const KParams &kp)
 {
     const int ntok = kp.nslots - kp.D;
-    const bool share = kp.D * 2 + ntok <= fast_dm(kp) * 4;
-    return (size_t)(kFastTableWords + (kp.fast_tp ? kMaxK : 0)) * 4 + (size_t)fast_dm(kp) * kWave * 16 + (share ? 0 : (size_t)(kp.D * 2 + ntok) * kWave * 4);
+    const bool share = fast_dm(kp) * 2 + ntok <= fast_dm(kp) * 4;
+    return (size_t)(kFastTableWords + (kp.fast_tp ? kMaxK : 0)) * 4 + (size_t)fast_dm(kp) * kWave * 16 +
+           (share ? 0 : (size_t)(fast_dm(kp) * 2 + ntok) * kWave * 4);
 }
 
 LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
