@@ -162,7 +162,10 @@ int  tessel_score_candidates(tessel_problem *p, uint64_t first, uint64_t count,
                              void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
 /* Waits for the stream of the last call, then returns the running best.  NO_FEASIBLE when
- * nothing feasible has been scored (counters in *out are still valid). */
+ * nothing feasible has been scored (counters in *out are still valid).  If a launch left more
+ * candidates unfinished than its internal list holds (possible only when more than an eighth of a
+ * range of 2^24 candidates needs extra period work), every range scored since the last reset is
+ * scored again here in smaller pieces before the result is returned. */
 int  tessel_best(tessel_problem *p, tessel_result *out);
 
 /* Decoded form of the best candidate as the GPU decoded it: leads[K], order_len[D] and

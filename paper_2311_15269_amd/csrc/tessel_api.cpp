@@ -38,6 +38,10 @@ struct tessel_problem {
     uint64_t detail_index = 0;
     DevDetail detail;
     DevResult result;
+    // index ranges scored since the last reset (adjacent ones merged), and whether launches are cut into the
+    // small pieces in which no list of unfinished candidates can overflow
+    std::vector<std::pair<uint64_t, uint64_t>> ranges;
+    bool safe_pieces = false;
     // searched completion
     bool comp_ready = false;            // CompParams of (comp_index, N, J) are in the workspace
     uint64_t comp_index = 0;            // best candidate they were built for
@@ -416,6 +420,7 @@ static int bind_workspace(tessel_problem *p, void *ws, size_t bytes, hipStream_t
     int e = launch_reset(ws, st);
     if (e) return hip_fail(p, e);
     p->ws = ws; p->ws_ready = true; p->have_detail = false;
+    p->ranges.clear();
     return TESSEL_OK;
 }
 
@@ -431,7 +436,9 @@ extern "C" int tessel_eval_candidates(tessel_problem *p, uint64_t first, uint64_
     p->stream = st;
     p->have_detail = false;
     if (count == 0) return TESSEL_OK;
-    int e = launch_eval(p->kp, first, count, workspace_dev, p->num_cus, st);
+    if (!p->ranges.empty() && p->ranges.back().first + p->ranges.back().second == first) p->ranges.back().second += count;
+    else p->ranges.push_back({first, count});
+    int e = launch_eval(p->kp, first, count, workspace_dev, p->num_cus, st, p->safe_pieces ? kSafePerLaunch : kMaxPerLaunch);
     return e ? hip_fail(p, e) : TESSEL_OK;
 }
 
@@ -465,6 +472,7 @@ extern "C" int tessel_reset(tessel_problem *p)
     if (!p) return TESSEL_E_INVALID_ARG;
     p->have_detail = false;
     p->result.period = INT_MAX;
+    p->ranges.clear();
     if (!p->ws || !p->ws_ready) return TESSEL_OK;
     int e = launch_reset(p->ws, p->stream);
     return e ? hip_fail(p, e) : TESSEL_OK;
@@ -477,6 +485,21 @@ static int fetch_best(tessel_problem *p)
     if (e != hipSuccess) return hip_fail(p, (int)e);
     e = hipMemcpy(&p->result, (char *)p->ws + kWsResultOff, sizeof(DevResult), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(p, (int)e);
+    if (p->result.overflow && !p->safe_pieces) {
+        // some launch left more candidates unfinished than its list holds, so the running best is incomplete:
+        // score every range again, from now on in pieces small enough for the lists
+        p->safe_pieces = true;
+        int le = launch_reset(p->ws, p->stream);
+        if (le) return hip_fail(p, le);
+        for (const auto &r : p->ranges) {
+            le = launch_eval(p->kp, r.first, r.second, p->ws, p->num_cus, p->stream, kSafePerLaunch);
+            if (le) return hip_fail(p, le);
+        }
+        e = hipStreamSynchronize(p->stream);
+        if (e != hipSuccess) return hip_fail(p, (int)e);
+        e = hipMemcpy(&p->result, (char *)p->ws + kWsResultOff, sizeof(DevResult), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return hip_fail(p, (int)e);
+    }
     if (p->result.period == INT_MAX) { p->have_detail = false; return TESSEL_OK; }
     if (p->have_detail && p->detail_index == p->result.index) return TESSEL_OK;
     // decode and re-score the best candidate on the GPU for its peaks and orders

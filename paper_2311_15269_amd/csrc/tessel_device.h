@@ -180,6 +180,7 @@ constexpr size_t kWsBlockRecOff = kWsCompParamsOff + 1024;
 constexpr int kDeferBlocks = 64;                                // grid of the deferred pass
 constexpr int kFirstPassTries = 2;                              // sweeps before a candidate goes to the retry list
 constexpr uint64_t kMaxPerLaunch = 1ull << 24;                  // candidates per pass of the kernels
+constexpr uint64_t kSafePerLaunch = 1ull << 20;                 // ... at which no list can overflow (<= both list capacities)
 constexpr int kRetryTries = 8;                                  // ... and before the general kernel gets it
 
 static_assert(sizeof(CompParams) <= 1024, "completion parameters must fit their workspace slot");
@@ -191,7 +192,7 @@ struct LaunchShape { int blocks, threads; size_t lds_bytes; };
 
 // kernels.hip
 LaunchShape eval_launch_shape(const KParams &kp, int num_cus);
-int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream);
+int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream, uint64_t max_piece);
 int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *ws, int num_cus,
                  bool general, void *stream);
 int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream);

@@ -1387,13 +1387,12 @@ static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *
     return rc ? -rc : blocks + blocks2 + kDeferBlocks;
 }
 
-int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream)
+int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream, uint64_t max_piece)
 {
     hipStream_t st = (hipStream_t)stream;
     BlockRec *recs = (BlockRec *)((char *)ws + kWsBlockRecOff);
     DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
-    // pieces of at most kMaxPerLaunch candidates, so that the lists of unfinished candidates stay small
-    const uint64_t max_piece = kMaxPerLaunch;
+    // pieces of at most max_piece candidates, so that the lists of unfinished candidates stay small
     for (uint64_t done = 0; done < count;) {
         const uint64_t piece = count - done < max_piece ? count - done : max_piece;
         int n = launch_pass(kp, first + done, piece, ws, num_cus, recs, nullptr, nullptr, false, st);
@@ -1413,7 +1412,8 @@ int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *cod
 {
     hipStream_t st = (hipStream_t)stream;
     DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
-    const uint64_t max_piece = kMaxPerLaunch;
+    // pieces in which no list can overflow: the per-candidate outputs of a dropped candidate would stay unwritten
+    const uint64_t max_piece = kSafePerLaunch;
     for (uint64_t done = 0; done < count;) {
         const uint64_t piece = count - done < max_piece ? count - done : max_piece;
         int n = launch_pass(kp, first + done, piece, ws, num_cus, nullptr, code + done, peak ? peak + done : nullptr, general, st);

@@ -135,16 +135,23 @@ def test_deferred_candidates_take_the_general_kernel(gpu, monkeypatch):
             assert got["n_reject"][1:] == want["n_reject"][1:]
 
 
-def test_deferred_list_overflow_is_reported(gpu, monkeypatch):
-    """More deferred candidates in one launch than the list holds must not be dropped silently."""
+def test_list_overflow_is_recovered(gpu, monkeypatch):
+    """More unfinished candidates in one launch than the retry list holds must not be dropped: the ranges are
+    scored again in smaller pieces and the result equals the ordinary one."""
     prob = dict(W.config3(), M=100)                   # every candidate feasible
-    monkeypatch.setenv("TESSEL_EIGEN_TRIES", "0")     # and every one deferred
+    want_g = gpu.Problem(prob)
+    want_g.eval_candidates(0, 1 << 22)
+    want_g.eval_candidates(1 << 23, 1000)
+    want = want_g.best()
+    monkeypatch.setenv("TESSEL_EIGEN_TRIES", "0")     # and every one unfinished after the first pass
     g = gpu.Problem(prob)
     monkeypatch.delenv("TESSEL_EIGEN_TRIES")
     g.eval_candidates(0, 1 << 22)                     # the retry list holds 2^21
-    with pytest.raises(gpu.TesselError) as e:
-        g.best()
-    assert e.value.code == -5
+    g.eval_candidates(1 << 23, 1000)
+    got = g.best()
+    for key in ("period", "index", "peak", "n_evaluated", "n_feasible", "n_reject"):
+        assert got[key] == want[key], key
+    assert got["n_evaluated"] == (1 << 22) + 1000
     g.reset()
     g.eval_candidates(0, 1 << 15)
     assert g.best()["n_evaluated"] == 1 << 15
