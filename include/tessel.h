@@ -194,9 +194,10 @@ int  tessel_complete_schedule(tessel_problem *p, tessel_schedule *out);
  * ordinal); ordinal 0 has no jitter and is the schedule of tessel_complete_schedule.
  *
  * tessel_search_completions scores candidates first .. first+count-1 on the GPU (one per lane, every block of
- * the N micro-batches simulated) and merges into the running best (makespan, lowest ordinal); asynchronous on
- * the stream of the last tessel_eval_candidates call, in the workspace bound there.  A new best window, N or
- * J restarts the running best.  Errors: NO_FEASIBLE, RANGE (fewer than one window fits), INVALID_ARG,
+ * the N micro-batches simulated) and merges into the running best (makespan, lowest ordinal).  The first call
+ * for a best window waits for it (as tessel_best does); the scoring itself is asynchronous on the stream of the
+ * last tessel_eval_candidates call, in the workspace bound there.  A new best window, N or J restarts the
+ * running best.  Errors: NO_FEASIBLE, RANGE (fewer than one window fits), INVALID_ARG,
  * TOOBIG (state of N micro-batches does not fit the LDS, or N * sum of t exceeds 16 bits), UNSUPPORTED (|m| > 127), HIP. */
 int  tessel_search_completions(tessel_problem *p, int32_t num_microbatches, int32_t jitter, uint64_t first,
                                uint64_t count);
