@@ -42,6 +42,7 @@ struct tessel_problem {
     // small pieces in which no list of unfinished candidates can overflow
     std::vector<std::pair<uint64_t, uint64_t>> ranges;
     bool safe_pieces = false;
+    bool best_dirty = true;             // candidates were scored (or the search was reset) since the best was fetched
     // searched completion
     bool comp_ready = false;            // CompParams of (comp_index, N, J) are in the workspace
     uint64_t comp_index = 0;            // best candidate they were built for
@@ -421,6 +422,7 @@ static int bind_workspace(tessel_problem *p, void *ws, size_t bytes, hipStream_t
     if (e) return hip_fail(p, e);
     p->ws = ws; p->ws_ready = true; p->have_detail = false;
     p->ranges.clear();
+    p->best_dirty = true;
     return TESSEL_OK;
 }
 
@@ -436,6 +438,7 @@ extern "C" int tessel_eval_candidates(tessel_problem *p, uint64_t first, uint64_
     p->stream = st;
     p->have_detail = false;
     if (count == 0) return TESSEL_OK;
+    p->best_dirty = true;
     if (!p->ranges.empty() && p->ranges.back().first + p->ranges.back().second == first) p->ranges.back().second += count;
     else p->ranges.push_back({first, count});
     int e = launch_eval(p->kp, first, count, workspace_dev, p->num_cus, st, p->safe_pieces ? kSafePerLaunch : kMaxPerLaunch);
@@ -473,6 +476,7 @@ extern "C" int tessel_reset(tessel_problem *p)
     p->have_detail = false;
     p->result.period = INT_MAX;
     p->ranges.clear();
+    p->best_dirty = true;
     if (!p->ws || !p->ws_ready) return TESSEL_OK;
     int e = launch_reset(p->ws, p->stream);
     return e ? hip_fail(p, e) : TESSEL_OK;
@@ -501,7 +505,7 @@ static int fetch_best(tessel_problem *p)
         if (e != hipSuccess) return hip_fail(p, (int)e);
     }
     if (p->result.period == INT_MAX) { p->have_detail = false; return TESSEL_OK; }
-    if (p->have_detail && p->detail_index == p->result.index) return TESSEL_OK;
+    if (p->have_detail && p->detail_index == p->result.index) { p->best_dirty = false; return TESSEL_OK; }
     // decode and re-score the best candidate on the GPU for its peaks and orders
     int le = launch_detail(p->kp, p->result.index, p->ws, p->stream);
     if (le) return hip_fail(p, le);
@@ -510,6 +514,7 @@ static int fetch_best(tessel_problem *p)
     e = hipMemcpy(&p->detail, (char *)p->ws + kWsDetailOff, sizeof(DevDetail), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(p, (int)e);
     p->have_detail = true; p->detail_index = p->result.index;
+    p->best_dirty = false;
     return TESSEL_OK;
 }
 
@@ -699,6 +704,9 @@ extern "C" int tessel_complete_schedule(tessel_problem *p, tessel_schedule *out)
 // uploads what the kernel needs of the problem and of the best candidate (once per best candidate, N, J)
 static int bind_completion(tessel_problem *p, int N, int J)
 {
+    if (p->comp_ready && !p->best_dirty && p->comp_index == p->result.index && p->result.period != INT_MAX && p->comp.N == N &&
+        p->comp.J == J)
+        return TESSEL_OK;                                   // nothing new since the best was fetched: no wait
     int rc = fetch_best(p);
     if (rc) return rc;
     if (p->result.period == INT_MAX) return TESSEL_E_NO_FEASIBLE;
