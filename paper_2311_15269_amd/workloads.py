@@ -104,4 +104,16 @@ def config5(space="sampled_repair", seed=0x5C0FFEE5):
     return prob
 
 
+def xshape_problem(p, tf, tb, nr, cap, space="sampled_repair", seed=0x7C0FFEE7, lead_step_q16=20000):
+    """Bidirectional pipelines over p devices (the X-shape placement of Chimera, Sec. VI-A): every micro-batch makes one
+    pass down the devices and one pass up, two independent chains of 2p blocks, four block types per device."""
+    t = [tf] * p + [tb] * p + [tf] * p + [tb] * p
+    m = [1] * p + [-1] * p + [1] * p + [-1] * p
+    down, up = list(range(p)), list(reversed(range(p)))
+    masks = [1 << s for s in down + up + up + down]
+    deps = [(i, i + 1) for i in range(2 * p - 1)] + [(2 * p + i, 2 * p + i + 1) for i in range(2 * p - 1)]
+    return {"name": "xshape-%ddev" % p, "D": p, "K": 4 * p, "NR": nr, "M": cap, "t": t, "m": m, "dev_mask": masks,
+            "deps": deps, "space": space, "seed": seed, "lead_step_q16": lead_step_q16, "fixed_leads": None}
+
+
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}

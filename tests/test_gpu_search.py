@@ -43,6 +43,7 @@ CASES = [
     ("cfg4-tp", dict(W.config4(), M=9), 4, 6000, 2048, True),
     ("cfg5-repair", W.config5(), 8, 3000, 1024, True),
     ("cfg5-repair-no-bound", W.config5(), 6, 1000, 0, False),
+    ("xshape-two-chains", W.xshape_problem(4, 1, 2, 1, 4), 3, 4000, 1024, False),
 ]
 
 
@@ -97,3 +98,16 @@ def test_four_stage_pipeline_exits_at_the_stored_exhaustive_best(gpu):
     assert (got["best_nr"], got["best_period"], got["best_index"]) == (4, want4["period"], want4["index"])
     assert got["evaluated_nr"][3] == ((want4["index"] >> 24) + 1) << 24
     assert best.best()["peak"] == want4["peak"]
+
+
+def test_xshape_window_of_two_reaches_the_bubble_of_the_direct_bidirectional_schedule(gpu):
+    """Bidirectional pipelines on 4 devices, tf = 1, tb = 2 (lower bound 6 per micro-batch): the window of one
+    micro-batch repeats every 12 (bubble 1/2); with two micro-batches the sampled search finds period 15, bubble 1/5,
+    the figure Table II lists for the direct bidirectional schedule; the oracle confirms both candidates."""
+    from oracle import oracle as O
+    prob = W.xshape_problem(4, 1, 2, 1, 4, seed=77)
+    got, best = gpu.search(prob, 2, 1 << 24, use_inflight_bound=False)
+    assert got["lower_bound"] == 6 and got["period_nr"] == [12, 15] and got["best_nr"] == 2
+    for nr in (1, 2):
+        sc = O.Oracle(dict(prob, NR=nr)).eval_index(got["index_nr"][nr - 1])
+        assert sc["status"] == 0 and sc["period"] == got["period_nr"][nr - 1] and sc["peak_max"] <= 4
