@@ -624,12 +624,11 @@ __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds
         // counters run one node ahead of the times: the counter word goes back incremented at once, the next
         // node's read follows it (LDS keeps a wave's accesses in order), and only then this node waits for its
         // device time and token
-        uint32_t cnt = *((uint32_t *)((char *)L.dfree + (tt[0].z + lane4)) + DM * kWave);
+        uint32_t cnt = atomicAdd((uint32_t *)((char *)L.dfree + (tt[0].z + lane4)) + DM * kWave, 1u << tt[0].w);
 #pragma unroll
         for (int j = 0; j < 6; j++) {
-            *((uint32_t *)((char *)L.dfree + (tt[j].z + lane4)) + DM * kWave) = cnt + (1u << tt[j].w);
             uint32_t next = 0;
-            if (j < 5) next = *((uint32_t *)((char *)L.dfree + (tt[j + 1].z + lane4)) + DM * kWave);
+            if (j < 5) next = atomicAdd((uint32_t *)((char *)L.dfree + (tt[j + 1].z + lane4)) + DM * kWave, 1u << tt[j + 1].w);
             sweep_node(L, tt[j], cnt, lane4);
             cnt = next;
         }
