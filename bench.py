@@ -20,7 +20,7 @@ if ROOT not in sys.path:
 PEAK_INT32_OPS = 256 * 64 * 2.4e9 / 1e12      # T int32 lane-ops/s: 256 CUs x 64 lanes x 2.4 GHz, full-rate VALU ops
 # HBM bytes of one launch of 2^24 candidates, from the FETCH_SIZE / WRITE_SIZE passes in
 # profiles/eval_fast_kernel_cfg5_counters.md (6105 KiB x 2.0 + 29398 KiB x 1.0, copy-calibrated)
-TRAFFIC_BYTES_PER_2P24_LAUNCH = int((6105 * 2.0 + 29398 * 1.0) * 1024)
+TRAFFIC_BYTES_PER_2P24_LAUNCH = int((6051 * 2.0 + 29602 * 1.0) * 1024)
 
 
 def algorithmic_ops(prob, n_candidates, n_sweeps):
