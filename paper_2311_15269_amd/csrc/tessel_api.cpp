@@ -376,8 +376,7 @@ static int ensure_device(tessel_problem *p)
 
 static size_t workspace_need(const tessel_problem *p, int num_cus)
 {
-    LaunchShape s = eval_launch_shape(p->kp, num_cus);
-    return kWsBlockRecOff + block_rec_bytes(2 * s.blocks + kDeferBlocks) + 256;
+    return eval_workspace_bytes(p->kp, num_cus);
 }
 
 extern "C" int tessel_workspace_bytes(const tessel_problem *p, size_t *bytes)

@@ -183,6 +183,10 @@ constexpr uint64_t kMaxPerLaunch = 1ull << 24;                  // candidates pe
 constexpr uint64_t kSafePerLaunch = 1ull << 20;                 // ... at which no list can overflow (<= both list capacities)
 constexpr int kRetryTries = 8;                                  // ... and before the general kernel gets it
 
+// queue between build and sweeps of the fast kernel: one ring per wave behind the block records
+constexpr uint32_t kRingSlots = 128;                            // a power of two >= 2 * 64 - 1
+constexpr int kRingMetaWords = 8;                               // leads (4), index (2), peak (1), unused (1)
+
 static_assert(sizeof(CompParams) <= 1024, "completion parameters must fit their workspace slot");
 static_assert(sizeof(DevResult) <= kWsCompletionOff && kWsCompletionOff + sizeof(DevCompletion) <= kWsDetailOff, "result records overlap");
 static_assert(sizeof(KParams) <= kWsTablesOff - kWsParamsOff, "parameter block must fit its workspace slot");
@@ -192,6 +196,7 @@ struct LaunchShape { int blocks, threads; size_t lds_bytes; };
 
 // kernels.hip
 LaunchShape eval_launch_shape(const KParams &kp, int num_cus);
+size_t eval_workspace_bytes(const KParams &kp, int num_cus);    // everything launch_eval / launch_score touch
 int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream, uint64_t max_piece);
 int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *ws, int num_cus,
                  bool general, void *stream);

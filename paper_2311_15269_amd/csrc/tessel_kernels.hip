@@ -750,15 +750,16 @@ __device__ __forceinline__ uint32_t even_bits32(uint32_t x)
 // MODE: 0 exhaustive spaces, 1 sampled without repair, 2 sampled with repair.
 // TP: some block type occupies several devices.  Such a type has one code on every device it occupies, and R, X
 // hold all of them.  It is a runnable head only when it heads all its devices; placing it takes its earliest entry
-// out of every one of them.  These variants only build (validity, memory): the periods of the candidates
-// that survive are computed by the general kernel.
-template <int DM, int VM, int MODE, bool TP>
-__device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<DM> &C, uint64_t idx, const FastLds &L, int lane,
-                                             int &period, int &peak_max, bool valid, uint32_t &nsweeps_used)
+// out of every one of them.
+// Builds the candidate's window: validity, memory, the program of the window in executable order and the leads by
+// code.  Returns kOk or the reason of the rejection; the period is the sweeps' business (period_fast).
+template <int DM, int MODE, bool TP>
+__device__ __forceinline__ int build_fast(const KParams &P, const FastConst<DM> &C, uint64_t idx, const FastLds &L, int lane,
+                                          int &peak_max, bool valid, FastProgram &prog, Mu &lead_code)
 {
     uint32_t plo[DM], phi[DM];       // order planes per device
     int nlen[DM];
-    period = 0; peak_max = 0;
+    peak_max = 0;
     const uint32_t NR = (uint32_t)C.NR;
     int status = kOk;
     constexpr bool sampled = MODE != 0;    // kSampledStrict / kSampledRepair; else the exhaustive spaces
@@ -886,7 +887,7 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
         if (nlen[d] > 0) HM |= 1u << (4 * d + ((plo[d] & 1u) | ((phi[d] & 1u) << 1)));
     }
 
-    const Mu lead_code = mu;
+    lead_code = mu;
     // With repair every candidate has an executable order (the blocks not yet placed form a DAG, so some type
     // is always runnable): no lane ever stops building, not even one past the end of the range (it scores a
     // real candidate whose result is dropped), and the per-lane predicate disappears from the loop.
@@ -895,7 +896,6 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
     bool building = repair || (valid && status == kOk);
     int worst = INT_MIN;             // largest memory prefix over all devices (Eq. 1 [2])
     const uint32_t lane16 = (uint32_t)lane * 16u;
-    FastProgram prog;
     prog.a = 0; prog.b = 0;
     for (int wi = 0; wi < C.nwords; wi++) {          // one program word = six blocks
         if (!repair && __ballot(building) == 0) break;
@@ -999,11 +999,6 @@ __device__ __forceinline__ int evaluate_fast(const KParams &P, const FastConst<D
         if (d < C.D && C.ntd[d] == 0) worst = max(worst, 0);      // a device without blocks holds nothing
     peak_max = worst;
     if (valid && worst > C.M) status = kMem;
-    int T = period_fast<DM, VM, TP>(C, L, prog, lane, lead_code, valid && status == kOk, nsweeps_used);
-    if (status == kOk) {
-        if (T < 0) return kDeferred;
-        period = T;
-    }
     return status;
 }
 
@@ -1013,7 +1008,8 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
                                                           int32_t *__restrict__ peak_out, const uint64_t *__restrict__ in_list,
                                                           const uint32_t *__restrict__ in_count, uint32_t in_cap, int tries,
                                                           uint64_t *__restrict__ out_list, uint32_t *__restrict__ out_count,
-                                                          uint32_t out_cap, uint32_t *__restrict__ overflow)
+                                                          uint32_t out_cap, uint32_t *__restrict__ overflow, uint32_t *ring_base,
+                                                          uint32_t ring_words)
 {
     // with an input list: score the listed candidates (all inside [first, first + count)) instead of the range
     if (in_list) count = min(*in_count, in_cap);
@@ -1080,29 +1076,96 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     for (int s = 0; s < kNumStatus; s++) cnt[s] = 0;
     uint32_t nev = 0;
     uint32_t nsw = 0;                // per lane: window sweeps
+    // Building and sweeping are separate phases with a queue between them: the candidates that survive the build
+    // (valid order, memory within the cap) wait, program and leads, in a ring of this wave in global memory, and
+    // the sweeps run whenever 64 of them are there, one per lane.  So the sweeps always run on full waves although
+    // only a part of every wave's candidates gets that far.  Ring layout: [word][slot]; words 0-7 of a slot hold
+    // leads by code (4), index (2), peak memory (1), then the program.
+    uint32_t *ring = ring_base + (size_t)blockIdx.x * ring_words;
+    uint32_t rhead = 0, rcount = 0;                                  // wave-uniform
+    const int nchunks = (C.nwords + 3) / 4;
+    FastProgram prog;
+    Mu lead_code;
+
+    auto sweep_from_ring = [&](uint32_t n) {
+        // the pushes of this wave's other lanes must be visible to the loads below
+        __threadfence_block();
+        const bool have = (uint32_t)lane < n;
+        const uint32_t slot = (rhead + (uint32_t)lane) & (kRingSlots - 1u);
+        const uint32_t *src = ring + slot;
+        uint64_t idx = first;
+        int pk = 0;
+        if (have) {
+            lead_code.lo = (uint64_t)src[0 * kRingSlots] | ((uint64_t)src[1 * kRingSlots] << 32);
+            lead_code.hi = (uint64_t)src[2 * kRingSlots] | ((uint64_t)src[3 * kRingSlots] << 32);
+            idx = (uint64_t)src[4 * kRingSlots] | ((uint64_t)src[5 * kRingSlots] << 32);
+            pk = (int)src[6 * kRingSlots];
+#pragma unroll
+            for (int c4 = 0; c4 < 12; c4++)
+                if (c4 < nchunks) {
+#pragma unroll
+                    for (int w = 4 * c4; w < 4 * c4 + 4; w++) prog.set(w, src[(kRingMetaWords + w) * kRingSlots]);
+                }
+        }
+        rhead = (rhead + n) & (kRingSlots - 1u);
+        rcount -= n;
+        const int T = period_fast<DM, VM, TP>(C, L, prog, lane, lead_code, have, nsw);
+        if (have && T < 0) {
+            // no eigenvector within the sweeps of this pass: the next pass scores it
+            const uint32_t at = atomicAdd(out_count, 1u);
+            if (at < out_cap) out_list[at] = idx; else *overflow = 1u;
+        }
+        const bool scored = have && T >= 0;
+        const uint32_t ns = (uint32_t)__builtin_popcountll(__ballot(scored));
+        nev += ns;
+        cnt[kOk] += ns;
+        if (scored) {
+            if (key_less(T, idx, best, best_idx)) { best = T; best_idx = idx; }
+            if (code_out) code_out[idx - first] = T;
+            if (peak_out) peak_out[idx - first] = pk;
+        }
+    };
+
     const uint64_t stride = (uint64_t)gridDim.x * kWave;
     const uint64_t rounds = (count + stride - 1) / stride;          // the same trip count for every lane of the grid
     for (uint64_t r = 0; r < rounds; r++) {
         const uint64_t kk = r * stride + (uint64_t)blockIdx.x * kWave + lane;
         const bool valid = kk < count;
         const uint64_t idx = !valid ? first : in_list ? in_list[kk] : first + kk;
-        const uint64_t k = idx - first;
-        int period, pk;
-        int status = evaluate_fast<DM, VM, MODE, TP>(P, C, idx, L, lane, period, pk, valid, nsw);
-        if (valid && status == kDeferred) {
-            // no eigenvector within the sweeps of this pass: the next pass scores it
-            const uint32_t at = atomicAdd(out_count, 1u);
-            if (at < out_cap) out_list[at] = idx; else *overflow = 1u;
-        }
-        const bool scored = valid && status != kDeferred;
-        nev += (uint32_t)__builtin_popcountll(__ballot(scored));
+        int pk;
+        const int status = build_fast<DM, MODE, TP>(P, C, idx, L, lane, pk, valid, prog, lead_code);
+        // a rejected candidate is final
+        const bool rejected = valid && status != kOk;
+        nev += (uint32_t)__builtin_popcountll(__ballot(rejected));
 #pragma unroll
-        for (int s = 0; s < kNumStatus; s++) cnt[s] += (uint32_t)__builtin_popcountll(__ballot(scored && status == s));
-        if (!scored) continue;
-        if (status == kOk && key_less(period, idx, best, best_idx)) { best = period; best_idx = idx; }
-        if (code_out) code_out[k] = status == kOk ? period : -status;
-        if (peak_out) peak_out[k] = (status == kOk || status == kMem) ? pk : 0;
+        for (int s = 1; s < kNumStatus; s++) cnt[s] += (uint32_t)__builtin_popcountll(__ballot(rejected && status == s));
+        if (rejected) {
+            if (code_out) code_out[idx - first] = -status;
+            if (peak_out) peak_out[idx - first] = status == kMem ? pk : 0;
+        }
+        // the others queue for the sweeps
+        const bool ok = valid && status == kOk;
+        const uint64_t okm = __ballot(ok);
+        if (okm != 0) {
+            if (ok) {
+                const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
+                uint32_t *dst = ring + ((rhead + rcount + rank) & (kRingSlots - 1u));
+                dst[0 * kRingSlots] = (uint32_t)lead_code.lo; dst[1 * kRingSlots] = (uint32_t)(lead_code.lo >> 32);
+                dst[2 * kRingSlots] = (uint32_t)lead_code.hi; dst[3 * kRingSlots] = (uint32_t)(lead_code.hi >> 32);
+                dst[4 * kRingSlots] = (uint32_t)idx; dst[5 * kRingSlots] = (uint32_t)(idx >> 32);
+                dst[6 * kRingSlots] = (uint32_t)pk;
+#pragma unroll
+                for (int c4 = 0; c4 < 12; c4++)
+                    if (c4 < nchunks) {
+#pragma unroll
+                        for (int w = 4 * c4; w < 4 * c4 + 4; w++) dst[(kRingMetaWords + w) * kRingSlots] = prog.get(w);
+                    }
+            }
+            rcount += (uint32_t)__builtin_popcountll(okm);
+        }
+        if (rcount >= (uint32_t)kWave) sweep_from_ring((uint32_t)kWave);
     }
+    if (rcount > 0) sweep_from_ring(rcount);       // fewer than 64 are left
     if (!recs) return;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -1259,7 +1322,7 @@ __global__ void reset_kernel(DevResult *res)
 typedef void (*eval_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, DevDetail *, const uint64_t *,
                         const uint32_t *);
 typedef void (*fast_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, const uint64_t *, const uint32_t *,
-                        uint32_t, int, uint64_t *, uint32_t *, uint32_t, uint32_t *);
+                        uint32_t, int, uint64_t *, uint32_t *, uint32_t, uint32_t *, uint32_t *, uint32_t);
 
 static eval_fn pick_kernel(const KParams &kp)
 {
@@ -1335,6 +1398,24 @@ LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
     return s;
 }
 
+// the rings of the fast kernel's waves lie behind the block records; words of one ring
+static uint32_t ring_words(const KParams &kp)
+{
+    const int nwords = (kp.total + 5) / 6;
+    return (uint32_t)((nwords + 3) / 4 * 4 + kRingMetaWords) * kRingSlots;
+}
+
+static size_t ring_offset(int blocks)
+{
+    return (kWsBlockRecOff + (size_t)(2 * blocks + kDeferBlocks) * sizeof(BlockRec) + 256 + 255) & ~(size_t)255;
+}
+
+size_t eval_workspace_bytes(const KParams &kp, int num_cus)
+{
+    const LaunchShape s = eval_launch_shape(kp, num_cus);
+    return ring_offset(s.blocks) + (pick_fast(kp) ? (size_t)s.blocks * ring_words(kp) * 4 : 0);
+}
+
 static int launch_general(const KParams &kp, const KParams *kp_dev, uint64_t first, uint64_t count, int blocks, BlockRec *recs,
                           int32_t *code, int32_t *peak, DevDetail *detail, const uint64_t *list, const uint32_t *list_count,
                           hipStream_t st)
@@ -1369,8 +1450,10 @@ static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *
         return rc ? -rc : blocks;
     }
     const size_t lds = fast_lds_bytes(kp);
+    uint32_t *ring = (uint32_t *)((char *)ws + ring_offset(s.blocks));
+    const uint32_t rw = ring_words(kp);
     hipLaunchKernelGGL(ff, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, (const uint64_t *)nullptr,
-                       (const uint32_t *)nullptr, 0u, kp.eigen_tries, retry, &res->retry_count, kWsRetryCap, &res->overflow);
+                       (const uint32_t *)nullptr, 0u, kp.eigen_tries, retry, &res->retry_count, kWsRetryCap, &res->overflow, ring, rw);
     int rc = (int)hipGetLastError();
     if (rc) return -rc;
     // the retry list holds a few percent of the range, still the whole grid: one wave per SIMD would leave the
@@ -1378,7 +1461,7 @@ static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *
     const int blocks2 = blocks;
     hipLaunchKernelGGL(ff, dim3(blocks2), dim3(kWave), lds, st, kp_dev, first, count, recs ? recs + blocks : nullptr, code, peak,
                        (const uint64_t *)retry, (const uint32_t *)&res->retry_count, kWsRetryCap, kRetryTries, list,
-                       &res->defer_count, kWsListCap, &res->overflow);
+                       &res->defer_count, kWsListCap, &res->overflow, ring, rw);
     rc = (int)hipGetLastError();
     if (rc) return -rc;
     rc = launch_general(kp, kp_dev, first, count, kDeferBlocks, recs ? recs + blocks + blocks2 : nullptr, code, peak, nullptr, list,
