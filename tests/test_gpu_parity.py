@@ -278,6 +278,21 @@ def test_other_shapes_elementwise(gpu, prob):
         assert (code == -1).sum() > 0
 
 
+@pytest.mark.parametrize("cfg,cap,count", [(5, 10, 33001), (3, None, 90000), (3, 100, 60000), (2, None, 200000)])
+def test_queue_between_build_and_sweeps(gpu, monkeypatch, cfg, cap, count):
+    """The candidates that survive the build wait in a ring of their wave until 64 are there.  With one workgroup
+    per compute unit every wave takes several rounds of 64 candidates, so the ring fills, wraps and is drained at
+    the end; the survival rate runs from next to nothing (exhaustive space) to all."""
+    prob = W.CONFIGS[cfg]()
+    if cap is not None:
+        prob["M"] = cap
+    monkeypatch.setenv("TESSEL_BLOCKS_PER_CU", "1")
+    first = 99 if cfg != 2 else 5 * 70 ** 4
+    code = compare_scores(gpu, prob, first, count)
+    assert (code > 0).sum() > (64 if cfg != 2 else 0)
+    compare_best(gpu, prob, first, count)
+
+
 def test_statuses_all_occur_somewhere(gpu):
     """DUP, TP_MISMATCH, PROP2, DEADLOCK, MEM and OK are all exercised by the cases above."""
     seen = set()
