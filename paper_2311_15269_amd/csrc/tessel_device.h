@@ -183,9 +183,11 @@ constexpr uint64_t kMaxPerLaunch = 1ull << 24;                  // candidates pe
 constexpr uint64_t kSafePerLaunch = 1ull << 20;                 // ... at which no list can overflow (<= both list capacities)
 constexpr int kRetryTries = 8;                                  // ... and before the general kernel gets it
 
-// queue between build and sweeps of the fast kernel: one ring per wave behind the block records
+// queues between the phases of the fast kernel: two rings per wave behind the block records
 constexpr uint32_t kRingSlots = 128;                            // a power of two >= 2 * 64 - 1
-constexpr int kRingMetaWords = 8;                               // leads (4), index (2), peak (1), unused (1)
+constexpr int kRingMetaWords = 8;                               // ring 2: leads (4), index (2), peak (1), unused (1), then the program
+constexpr int kStageMetaWords = 12;                             // ring 1: R, HM, X, worst, leads (4), index (2), unused (2), then
+                                                                // the device records (4 words each) and the program so far
 
 static_assert(sizeof(CompParams) <= 1024, "completion parameters must fit their workspace slot");
 static_assert(sizeof(DevResult) <= kWsCompletionOff && kWsCompletionOff + sizeof(DevCompletion) <= kWsDetailOff, "result records overlap");

@@ -29,7 +29,6 @@
 
 namespace tessel {
 
-constexpr int kDeferred = -1;    // fast kernel only: the general kernel has to score this candidate
 
 struct BlockRec {
     int32_t  period;
@@ -753,13 +752,19 @@ __device__ __forceinline__ uint32_t even_bits32(uint32_t x)
 // out of every one of them.
 // Builds the candidate's window: validity, memory, the program of the window in executable order and the leads by
 // code.  Returns kOk or the reason of the rejection; the period is the sweeps' business (period_fast).
+// what the build carries from block to block besides the per-device records in LDS
+struct BuildState {
+    uint32_t R, HM, X;               // by code: runnable types, heads of the devices, exhausted types
+    int worst;                       // largest memory prefix over all devices so far (Eq. 1 [2])
+    int status;
+};
+
 template <int DM, int MODE, bool TP>
-__device__ __forceinline__ int build_fast(const KParams &P, const FastConst<DM> &C, uint64_t idx, const FastLds &L, int lane,
-                                          int &peak_max, bool valid, FastProgram &prog, Mu &lead_code)
+__device__ __forceinline__ void build_begin(const KParams &P, const FastConst<DM> &C, uint64_t idx, const FastLds &L, int lane,
+                                            Mu &lead_code, BuildState &S)
 {
     uint32_t plo[DM], phi[DM];       // order planes per device
     int nlen[DM];
-    peak_max = 0;
     const uint32_t NR = (uint32_t)C.NR;
     int status = kOk;
     constexpr bool sampled = MODE != 0;    // kSampledStrict / kSampledRepair; else the exhaustive spaces
@@ -888,16 +893,24 @@ __device__ __forceinline__ int build_fast(const KParams &P, const FastConst<DM> 
     }
 
     lead_code = mu;
+    S.R = R; S.HM = HM; S.X = X; S.worst = INT_MIN; S.status = status;
+}
+
+// Places the blocks of program words [w_from, w_to) (six blocks a word).  `live`: the lane holds a candidate.
+template <int DM, int MODE, bool TP>
+__device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM> &C, const FastLds &L, int lane, bool live,
+                                            int w_from, int w_to, FastProgram &prog, BuildState &S)
+{
     // With repair every candidate has an executable order (the blocks not yet placed form a DAG, so some type
-    // is always runnable): no lane ever stops building, not even one past the end of the range (it scores a
-    // real candidate whose result is dropped), and the per-lane predicate disappears from the loop.
+    // is always runnable): no lane ever stops building, not even one without a candidate of the range (it scores
+    // a real candidate whose result is dropped), and the per-lane predicate disappears from the loop.
     constexpr bool repair = MODE == 2;
     const int total = C.total;
-    bool building = repair || (valid && status == kOk);
-    int worst = INT_MIN;             // largest memory prefix over all devices (Eq. 1 [2])
+    uint32_t R = S.R, HM = S.HM, X = S.X;
+    int worst = S.worst, status = S.status;
+    bool building = repair || (live && status == kOk);
     const uint32_t lane16 = (uint32_t)lane * 16u;
-    prog.a = 0; prog.b = 0;
-    for (int wi = 0; wi < C.nwords; wi++) {          // one program word = six blocks
+    for (int wi = w_from; wi < w_to; wi++) {          // one program word = six blocks
         if (!repair && __ballot(building) == 0) break;
         uint32_t acc = 0;
         const int nj = __builtin_amdgcn_readfirstlane(min(6, total - wi * 6));
@@ -993,13 +1006,21 @@ __device__ __forceinline__ int build_fast(const KParams &P, const FastConst<DM> 
         }
         prog.set(wi, acc);
     }
-    if (status != kOk) return status;
+    S.R = R; S.HM = HM; S.X = X; S.worst = worst; S.status = status;
+}
+
+// the build's verdict once all blocks are placed
+template <int DM>
+__device__ __forceinline__ int build_end(const FastConst<DM> &C, const BuildState &S, int &peak_max)
+{
+    peak_max = 0;
+    if (S.status != kOk) return S.status;
+    int worst = S.worst;
 #pragma unroll
     for (int d = 0; d < DM; d++)
         if (d < C.D && C.ntd[d] == 0) worst = max(worst, 0);      // a device without blocks holds nothing
     peak_max = worst;
-    if (valid && worst > C.M) status = kMem;
-    return status;
+    return worst > C.M ? kMem : kOk;
 }
 
 template <int DM, int VM, int MODE, bool TP = false>
@@ -1009,7 +1030,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
                                                           const uint32_t *__restrict__ in_count, uint32_t in_cap, int tries,
                                                           uint64_t *__restrict__ out_list, uint32_t *__restrict__ out_count,
                                                           uint32_t out_cap, uint32_t *__restrict__ overflow, uint32_t *ring_base,
-                                                          uint32_t ring_words)
+                                                          uint32_t ring_words, int stage_words)
 {
     // with an input list: score the listed candidates (all inside [first, first + count)) instead of the range
     if (in_list) count = min(*in_count, in_cap);
@@ -1076,25 +1097,65 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     for (int s = 0; s < kNumStatus; s++) cnt[s] = 0;
     uint32_t nev = 0;
     uint32_t nsw = 0;                // per lane: window sweeps
-    // Building and sweeping are separate phases with a queue between them: the candidates that survive the build
-    // (valid order, memory within the cap) wait, program and leads, in a ring of this wave in global memory, and
-    // the sweeps run whenever 64 of them are there, one per lane.  So the sweeps always run on full waves although
-    // only a part of every wave's candidates gets that far.  Ring layout: [word][slot]; words 0-7 of a slot hold
-    // leads by code (4), index (2), peak memory (1), then the program.
-    uint32_t *ring = ring_base + (size_t)blockIdx.x * ring_words;
-    uint32_t rhead = 0, rcount = 0;                                  // wave-uniform
-    const int nchunks = (C.nwords + 3) / 4;
+    // The kernel works in three phases with a queue between each two, so that every phase runs on full waves
+    // although candidates drop out on the way:
+    //   A  decode + the first `stage_words` words of the build, one new candidate per lane;
+    //   B  the rest of the build for the candidates that are still alive after A (with repair, and no per-candidate
+    //      peak wanted: whose memory is within the cap so far; most candidates that exceed it do so early);
+    //   C  the window sweeps for the candidates that survive the build.
+    // A survivor of A appends its state (masks, records, program so far) to ring 1 of this wave in global memory,
+    // a survivor of B program and leads to ring 2; B and C run whenever 64 candidates wait in their ring, one per
+    // lane.  Ring layout: [word][slot]; slot = ring tail + rank of the lane among the survivors.
+    uint32_t *ring1 = ring_base + (size_t)blockIdx.x * 2u * ring_words, *ring2 = ring1 + ring_words;
+    uint32_t head1 = 0, count1 = 0, head2 = 0, count2 = 0;           // wave-uniform
+    const int nwords = C.nwords;
+    const bool split = stage_words < nwords;                         // tiny windows: A builds all of it
+    const int wordsA = split ? stage_words : nwords;
+    const int chunksA = (wordsA + 3) / 4, chunksAll = (nwords + 3) / 4;
+    const bool drop_mem = MODE == 2 && peak_out == nullptr;          // a rejected candidate's peak is that of the whole window
     FastProgram prog;
     Mu lead_code;
+    BuildState S;
 
+    auto rank_in = [&](uint64_t m) -> uint32_t {
+        return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+    };
+    // a candidate the build rejects is final
+    auto reject = [&](bool rejected, uint64_t idx, int status, int pk) {
+        nev += (uint32_t)__builtin_popcountll(__ballot(rejected));
+#pragma unroll
+        for (int s = 1; s < kNumStatus; s++) cnt[s] += (uint32_t)__builtin_popcountll(__ballot(rejected && status == s));
+        if (rejected) {
+            if (code_out) code_out[idx - first] = -status;
+            if (peak_out) peak_out[idx - first] = status == kMem ? pk : 0;
+        }
+    };
+    auto push_program = [&](bool ok, uint64_t idx, int pk) {
+        const uint64_t okm = __ballot(ok);
+        if (okm == 0) return;
+        if (ok) {
+            uint32_t *dst = ring2 + ((head2 + count2 + rank_in(okm)) & (kRingSlots - 1u));
+            dst[0 * kRingSlots] = (uint32_t)lead_code.lo; dst[1 * kRingSlots] = (uint32_t)(lead_code.lo >> 32);
+            dst[2 * kRingSlots] = (uint32_t)lead_code.hi; dst[3 * kRingSlots] = (uint32_t)(lead_code.hi >> 32);
+            dst[4 * kRingSlots] = (uint32_t)idx; dst[5 * kRingSlots] = (uint32_t)(idx >> 32);
+            dst[6 * kRingSlots] = (uint32_t)pk;
+#pragma unroll
+            for (int c4 = 0; c4 < 12; c4++)
+                if (c4 < chunksAll) {
+#pragma unroll
+                    for (int w = 4 * c4; w < 4 * c4 + 4; w++) dst[(kRingMetaWords + w) * kRingSlots] = prog.get(w);
+                }
+        }
+        count2 += (uint32_t)__builtin_popcountll(okm);
+    };
+    // phase C on the first n candidates of ring 2
     auto sweep_from_ring = [&](uint32_t n) {
-        // the pushes of this wave's other lanes must be visible to the loads below
-        __threadfence_block();
+        __threadfence_block();         // the stores of this wave's other lanes must be visible to the loads below
         const bool have = (uint32_t)lane < n;
-        const uint32_t slot = (rhead + (uint32_t)lane) & (kRingSlots - 1u);
-        const uint32_t *src = ring + slot;
+        const uint32_t *src = ring2 + ((head2 + (uint32_t)lane) & (kRingSlots - 1u));
         uint64_t idx = first;
         int pk = 0;
+        prog.a = 0; prog.b = 0;
         if (have) {
             lead_code.lo = (uint64_t)src[0 * kRingSlots] | ((uint64_t)src[1 * kRingSlots] << 32);
             lead_code.hi = (uint64_t)src[2 * kRingSlots] | ((uint64_t)src[3 * kRingSlots] << 32);
@@ -1102,13 +1163,13 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
             pk = (int)src[6 * kRingSlots];
 #pragma unroll
             for (int c4 = 0; c4 < 12; c4++)
-                if (c4 < nchunks) {
+                if (c4 < chunksAll) {
 #pragma unroll
                     for (int w = 4 * c4; w < 4 * c4 + 4; w++) prog.set(w, src[(kRingMetaWords + w) * kRingSlots]);
                 }
         }
-        rhead = (rhead + n) & (kRingSlots - 1u);
-        rcount -= n;
+        head2 = (head2 + n) & (kRingSlots - 1u);
+        count2 -= n;
         const int T = period_fast<DM, VM, TP>(C, L, prog, lane, lead_code, have, nsw);
         if (have && T < 0) {
             // no eigenvector within the sweeps of this pass: the next pass scores it
@@ -1125,47 +1186,92 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
             if (peak_out) peak_out[idx - first] = pk;
         }
     };
+    // the end of the build for the candidates the lanes hold: verdict, then ring 2 or out
+    auto finish_build = [&](bool have, uint64_t idx) {
+        int pk;
+        const int status = build_end<DM>(C, S, pk);
+        reject(have && status != kOk, idx, status, pk);
+        push_program(have && status == kOk, idx, pk);
+    };
+    // phase B on the first n candidates of ring 1
+    auto build_from_ring = [&](uint32_t n) {
+        __threadfence_block();
+        const bool have = (uint32_t)lane < n;
+        const uint32_t *src = ring1 + ((head1 + (uint32_t)lane) & (kRingSlots - 1u));
+        uint64_t idx = first;
+        S.R = S.HM = S.X = 0u; S.worst = INT_MIN; S.status = kOk;
+        prog.a = 0; prog.b = 0;
+        if (have) {
+            S.R = src[0 * kRingSlots]; S.HM = src[1 * kRingSlots]; S.X = src[2 * kRingSlots]; S.worst = (int)src[3 * kRingSlots];
+            lead_code.lo = (uint64_t)src[4 * kRingSlots] | ((uint64_t)src[5 * kRingSlots] << 32);
+            lead_code.hi = (uint64_t)src[6 * kRingSlots] | ((uint64_t)src[7 * kRingSlots] << 32);
+            idx = (uint64_t)src[8 * kRingSlots] | ((uint64_t)src[9 * kRingSlots] << 32);
+#pragma unroll
+            for (int d = 0; d < DM; d++)
+                if (d < C.D)
+                    L.rec[d * kWave + lane] = make_uint4(src[(kStageMetaWords + 4 * d) * kRingSlots], src[(kStageMetaWords + 4 * d + 1) * kRingSlots],
+                                                         src[(kStageMetaWords + 4 * d + 2) * kRingSlots], src[(kStageMetaWords + 4 * d + 3) * kRingSlots]);
+#pragma unroll
+            for (int c4 = 0; c4 < 12; c4++)
+                if (c4 < chunksA) {
+#pragma unroll
+                    for (int w = 4 * c4; w < 4 * c4 + 4; w++) prog.set(w, src[(kStageMetaWords + 4 * DM + w) * kRingSlots]);
+                }
+        }
+        head1 = (head1 + n) & (kRingSlots - 1u);
+        count1 -= n;
+        build_words<DM, MODE, TP>(P, C, L, lane, have, wordsA, nwords, prog, S);
+        finish_build(have, idx);
+    };
 
     const uint64_t stride = (uint64_t)gridDim.x * kWave;
     const uint64_t rounds = (count + stride - 1) / stride;          // the same trip count for every lane of the grid
-    for (uint64_t r = 0; r < rounds; r++) {
+    // phase A on the next 64 candidates of the wave's share
+    auto build_new = [&](uint64_t r) {
         const uint64_t kk = r * stride + (uint64_t)blockIdx.x * kWave + lane;
         const bool valid = kk < count;
         const uint64_t idx = !valid ? first : in_list ? in_list[kk] : first + kk;
-        int pk;
-        const int status = build_fast<DM, MODE, TP>(P, C, idx, L, lane, pk, valid, prog, lead_code);
-        // a rejected candidate is final
-        const bool rejected = valid && status != kOk;
-        nev += (uint32_t)__builtin_popcountll(__ballot(rejected));
-#pragma unroll
-        for (int s = 1; s < kNumStatus; s++) cnt[s] += (uint32_t)__builtin_popcountll(__ballot(rejected && status == s));
-        if (rejected) {
-            if (code_out) code_out[idx - first] = -status;
-            if (peak_out) peak_out[idx - first] = status == kMem ? pk : 0;
-        }
-        // the others queue for the sweeps
-        const bool ok = valid && status == kOk;
+        build_begin<DM, MODE, TP>(P, C, idx, L, lane, lead_code, S);
+        prog.a = 0; prog.b = 0;          // (nothing of the last program lives on: its registers are free during the decode)
+        build_words<DM, MODE, TP>(P, C, L, lane, valid, 0, wordsA, prog, S);
+        if (!split) { finish_build(valid, idx); return; }
+        const bool over = drop_mem && S.status == kOk && S.worst > C.M;
+        reject(valid && (S.status != kOk || over), idx, over ? (int)kMem : S.status, 0);
+        const bool ok = valid && S.status == kOk && !over;
         const uint64_t okm = __ballot(ok);
-        if (okm != 0) {
-            if (ok) {
-                const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(okm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)okm, 0u));
-                uint32_t *dst = ring + ((rhead + rcount + rank) & (kRingSlots - 1u));
-                dst[0 * kRingSlots] = (uint32_t)lead_code.lo; dst[1 * kRingSlots] = (uint32_t)(lead_code.lo >> 32);
-                dst[2 * kRingSlots] = (uint32_t)lead_code.hi; dst[3 * kRingSlots] = (uint32_t)(lead_code.hi >> 32);
-                dst[4 * kRingSlots] = (uint32_t)idx; dst[5 * kRingSlots] = (uint32_t)(idx >> 32);
-                dst[6 * kRingSlots] = (uint32_t)pk;
+        if (okm == 0) return;
+        if (ok) {
+            uint32_t *dst = ring1 + ((head1 + count1 + rank_in(okm)) & (kRingSlots - 1u));
+            dst[0 * kRingSlots] = S.R; dst[1 * kRingSlots] = S.HM; dst[2 * kRingSlots] = S.X; dst[3 * kRingSlots] = (uint32_t)S.worst;
+            dst[4 * kRingSlots] = (uint32_t)lead_code.lo; dst[5 * kRingSlots] = (uint32_t)(lead_code.lo >> 32);
+            dst[6 * kRingSlots] = (uint32_t)lead_code.hi; dst[7 * kRingSlots] = (uint32_t)(lead_code.hi >> 32);
+            dst[8 * kRingSlots] = (uint32_t)idx; dst[9 * kRingSlots] = (uint32_t)(idx >> 32);
 #pragma unroll
-                for (int c4 = 0; c4 < 12; c4++)
-                    if (c4 < nchunks) {
+            for (int d = 0; d < DM; d++)
+                if (d < C.D) {
+                    const uint4 q = L.rec[d * kWave + lane];
+                    dst[(kStageMetaWords + 4 * d) * kRingSlots] = q.x; dst[(kStageMetaWords + 4 * d + 1) * kRingSlots] = q.y;
+                    dst[(kStageMetaWords + 4 * d + 2) * kRingSlots] = q.z; dst[(kStageMetaWords + 4 * d + 3) * kRingSlots] = q.w;
+                }
 #pragma unroll
-                        for (int w = 4 * c4; w < 4 * c4 + 4; w++) dst[(kRingMetaWords + w) * kRingSlots] = prog.get(w);
-                    }
-            }
-            rcount += (uint32_t)__builtin_popcountll(okm);
+            for (int c4 = 0; c4 < 12; c4++)
+                if (c4 < chunksA) {
+#pragma unroll
+                    for (int w = 4 * c4; w < 4 * c4 + 4; w++) dst[(kStageMetaWords + 4 * DM + w) * kRingSlots] = prog.get(w);
+                }
         }
-        if (rcount >= (uint32_t)kWave) sweep_from_ring((uint32_t)kWave);
+        count1 += (uint32_t)__builtin_popcountll(okm);
+    };
+
+    // Later phases first: a ring is served as soon as it holds 64 candidates, so that it never holds more than 127;
+    // when the wave's share is used up the rings are drained on partial waves.  Every condition is wave-uniform.
+    for (uint64_t r = 0;;) {
+        const bool fresh = r < rounds;
+        if (count2 >= (uint32_t)kWave || (!fresh && count1 == 0 && count2 > 0)) sweep_from_ring(min(count2, (uint32_t)kWave));
+        else if (count1 >= (uint32_t)kWave || (!fresh && count1 > 0)) build_from_ring(min(count1, (uint32_t)kWave));
+        else if (fresh) build_new(r++);
+        else break;
     }
-    if (rcount > 0) sweep_from_ring(rcount);       // fewer than 64 are left
     if (!recs) return;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -1322,7 +1428,7 @@ __global__ void reset_kernel(DevResult *res)
 typedef void (*eval_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, DevDetail *, const uint64_t *,
                         const uint32_t *);
 typedef void (*fast_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, const uint64_t *, const uint32_t *,
-                        uint32_t, int, uint64_t *, uint32_t *, uint32_t, uint32_t *, uint32_t *, uint32_t);
+                        uint32_t, int, uint64_t *, uint32_t *, uint32_t, uint32_t *, uint32_t *, uint32_t, int);
 
 static eval_fn pick_kernel(const KParams &kp)
 {
@@ -1398,11 +1504,26 @@ LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
     return s;
 }
 
-// the rings of the fast kernel's waves lie behind the block records; words of one ring
+// program words the fast kernel builds before the candidates that are still alive queue for the rest (most
+// candidates that exceed the memory cap do so within the first blocks of the window); windows of fewer than
+// ten words are built in one go
+static int stage_words(const KParams &kp)
+{
+    const int nwords = (kp.total + 5) / 6;
+    if (const char *env = getenv("TESSEL_STAGE_WORDS")) {           // tuning knob
+        const int want = atoi(env);
+        if (want >= 1 && want <= nwords) return want;
+    }
+    return nwords >= 10 ? nwords / 5 : nwords;
+}
+
+// the rings of the fast kernel's waves lie behind the block records, two per wave; words of one ring
 static uint32_t ring_words(const KParams &kp)
 {
     const int nwords = (kp.total + 5) / 6;
-    return (uint32_t)((nwords + 3) / 4 * 4 + kRingMetaWords) * kRingSlots;
+    const int program = (nwords + 3) / 4 * 4 + kRingMetaWords;
+    const int stage = (nwords + 3) / 4 * 4 + kStageMetaWords + 4 * fast_dm(kp);     // any stage_words
+    return (uint32_t)(program > stage ? program : stage) * kRingSlots;
 }
 
 static size_t ring_offset(int blocks)
@@ -1413,7 +1534,7 @@ static size_t ring_offset(int blocks)
 size_t eval_workspace_bytes(const KParams &kp, int num_cus)
 {
     const LaunchShape s = eval_launch_shape(kp, num_cus);
-    return ring_offset(s.blocks) + (pick_fast(kp) ? (size_t)s.blocks * ring_words(kp) * 4 : 0);
+    return ring_offset(s.blocks) + (pick_fast(kp) ? (size_t)s.blocks * 2 * ring_words(kp) * 4 : 0);
 }
 
 static int launch_general(const KParams &kp, const KParams *kp_dev, uint64_t first, uint64_t count, int blocks, BlockRec *recs,
@@ -1452,8 +1573,9 @@ static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *
     const size_t lds = fast_lds_bytes(kp);
     uint32_t *ring = (uint32_t *)((char *)ws + ring_offset(s.blocks));
     const uint32_t rw = ring_words(kp);
+    const int sw = stage_words(kp);
     hipLaunchKernelGGL(ff, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, (const uint64_t *)nullptr,
-                       (const uint32_t *)nullptr, 0u, kp.eigen_tries, retry, &res->retry_count, kWsRetryCap, &res->overflow, ring, rw);
+                       (const uint32_t *)nullptr, 0u, kp.eigen_tries, retry, &res->retry_count, kWsRetryCap, &res->overflow, ring, rw, sw);
     int rc = (int)hipGetLastError();
     if (rc) return -rc;
     // the retry list holds a few percent of the range, still the whole grid: one wave per SIMD would leave the
@@ -1461,7 +1583,7 @@ static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *
     const int blocks2 = blocks;
     hipLaunchKernelGGL(ff, dim3(blocks2), dim3(kWave), lds, st, kp_dev, first, count, recs ? recs + blocks : nullptr, code, peak,
                        (const uint64_t *)retry, (const uint32_t *)&res->retry_count, kWsRetryCap, kRetryTries, list,
-                       &res->defer_count, kWsListCap, &res->overflow, ring, rw);
+                       &res->defer_count, kWsListCap, &res->overflow, ring, rw, sw);
     rc = (int)hipGetLastError();
     if (rc) return -rc;
     rc = launch_general(kp, kp_dev, first, count, kDeferBlocks, recs ? recs + blocks + blocks2 : nullptr, code, peak, nullptr, list,
