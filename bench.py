@@ -19,9 +19,9 @@ if ROOT not in sys.path:
 
 PEAK_INT32_OPS = 256 * 64 * 2.4e9 / 1e12      # T int32 lane-ops/s: 256 CUs x 64 lanes x 2.4 GHz, full-rate VALU ops
 # HBM bytes of one launch of 2^24 candidates, from the FETCH_SIZE / WRITE_SIZE passes in
-# profiles/eval_fast_kernel_cfg5_counters.md (919,867 KiB x 2.0 + 3,004,477 KiB x 1.0, copy-calibrated;
-# nearly all of it the queue between build and sweeps)
-TRAFFIC_BYTES_PER_2P24_LAUNCH = int((919867 * 2.0 + 3004477 * 1.0) * 1024)
+# profiles/eval_fast_kernel_cfg5_counters.md (3,425,571 KiB x 2.0 + 7,837,732 KiB x 1.0, copy-calibrated;
+# nearly all of it the queues between the kernel's phases)
+TRAFFIC_BYTES_PER_2P24_LAUNCH = int((3425571 * 2.0 + 7837732 * 1.0) * 1024)
 
 
 def algorithmic_ops(prob, n_candidates, n_sweeps):
