@@ -200,7 +200,8 @@ int  tessel_complete_schedule(tessel_problem *p, tessel_schedule *out);
  * for a best window waits for it (as tessel_best does); the scoring itself is asynchronous on the stream of the
  * last tessel_eval_candidates call, in the workspace bound there.  A new best window, N or J restarts the
  * running best.  Errors: NO_FEASIBLE, RANGE (fewer than one window fits), INVALID_ARG,
- * TOOBIG (state of N micro-batches does not fit the LDS, or N * sum of t exceeds 16 bits), UNSUPPORTED (|m| > 127), HIP. */
+ * TOOBIG (state of N micro-batches does not fit the LDS, N * sum of t exceeds 16 bits, N > 1023 or J > 63),
+ * UNSUPPORTED (|m| > 127), HIP. */
 int  tessel_search_completions(tessel_problem *p, int32_t num_microbatches, int32_t jitter, uint64_t first,
                                uint64_t count);
 /* makespan_dev[k] (device, int32) = makespan of completion candidate first+k, INT32_MAX where the greedy rule

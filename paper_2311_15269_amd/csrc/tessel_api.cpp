@@ -759,7 +759,7 @@ static int bind_completion(tessel_problem *p, int N, int J)
         // the kernel keeps times, memory and jitter in 16 bits
         long long total = 0;
         for (int i = 0; i < K; i++) total += (long long)p->t[i] * N;
-        if (total + J > 65535 || std::abs(p->kp.M) > 30000) return TESSEL_E_TOOBIG;
+        if (total + J > 65535 || std::abs(p->kp.M) > 30000 || N > 1023 || J > 63) return TESSEL_E_TOOBIG;
     }
     if (completion_lds_bytes(cp) > 64 * 1024) return TESSEL_E_TOOBIG;
     hipError_t e = hipMemcpyAsync((char *)p->ws + kWsCompParamsOff, &cp, sizeof cp, hipMemcpyHostToDevice, p->stream);

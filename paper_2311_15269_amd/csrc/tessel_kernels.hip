@@ -1669,7 +1669,11 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
     const int lane = threadIdx.x;
     uint16_t *state = (uint16_t *)(lds + kCompParamWords) + lane;      // 16-bit words: all times stay below 65536 (checked by the host)
     const int D = cp.D, K = cp.K, N = cp.N, NR = cp.NR, M = cp.M, J = cp.J, R = cp.R;
-    const int oTok = 0, oFree = cp.npaths * N, oMem = oFree + D, oNext = oMem + D, oJit = oNext + K, nstate = oJit + K;
+    // a type's next micro-batch (low 10 bits) and the jitter of that block (high 6 bits) share a word: N < 1024 and
+    // J < 64 (checked by the host)
+    const int oTok = 0, oFree = cp.npaths * N, oMem = oFree + D, oNext = oMem + D, nstate = oNext + K;
+    bool single_dev = true;
+    for (int i = 0; i < K; i++) single_dev = single_dev && (cp.mask[i] & (cp.mask[i] - 1)) == 0 && cp.mask[i] != 0;
 #define TESSEL_ST(slot) state[(slot) * kWave]
     int best = INT_MAX;
     uint64_t best_ord = 0;
@@ -1690,23 +1694,45 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
         for (int phase = 0; phase < 2; phase++) {
             // ---- greedy phase: 0 warm-up (micro-batches below the leads), 1 cool-down (the rest up to N)
             for (int i = 0; i < K; i++) {
-                const int mu = (int)TESSEL_ST(oNext + i), hi = phase ? N : (int)cp.lead[i];
-                TESSEL_ST(oJit + i) = (uint16_t)(mu < hi ? jitter(i, mu) : 0u);
+                const int mu = (int)TESSEL_ST(oNext + i) & 1023, hi = phase ? N : (int)cp.lead[i];
+                TESSEL_ST(oNext + i) = (uint16_t)((uint32_t)mu | (mu < hi ? jitter(i, mu) : 0u) << 10);
             }
             for (;;) {
                 int bi = -1, bmu = 0, best_est = 0, bkey = 0;
                 bool any = false;
+                if (single_dev) {
+                    // every type on one device: a scan without branches, so that the reads of several types are in
+                    // flight together (the kernel runs at two waves per SIMD and is bound by the latency of its LDS reads)
+#pragma unroll 8
+                    for (int i = 0; i < K; i++) {
+                        const int hi = phase ? N : (int)cp.lead[i];
+                        const int a = cp.pred[i], mi = cp.m[i], d = __builtin_ctz((uint32_t)cp.mask[i]);
+                        const int nj = (int)TESSEL_ST(oNext + i), mu = nj & 1023;
+                        const int na = (int)TESSEL_ST(oNext + (a >= 0 ? a : i)) & 1023;
+                        const int tk = (int)TESSEL_ST(oTok + (int)cp.path[i] * N + min(mu, N - 1));
+                        const int fr = (int)TESSEL_ST(oFree + d), me = (int)(int16_t)TESSEL_ST(oMem + d);
+                        const int jt = nj >> 10;
+                        const bool offered = mu < hi;
+                        any |= offered;
+                        const bool ok = offered && (a < 0 || na > mu) && !(mi > 0 && me + mi > M);
+                        const int est = max(a >= 0 ? tk : 0, fr);
+                        const int key = est + jt;
+                        if (ok && (bi < 0 || key < bkey || (key == bkey && mu < bmu))) { bi = i; bmu = mu; best_est = est; bkey = key; }
+                    }
+                } else
                 for (int i = 0; i < K; i++) {
                     const int hi = phase ? N : (int)cp.lead[i];
-                    const int mu = (int)TESSEL_ST(oNext + i);
+                    if (hi == 0) continue;                       // nothing of this type in the phase (uniform)
+                    const int nj = (int)TESSEL_ST(oNext + i), mu = nj & 1023;
                     const bool offered = mu < hi;
+                    if (__ballot(offered) == 0) continue;        // every lane is through with the type
                     any |= offered;
                     const int a = cp.pred[i], mi = cp.m[i];
                     const uint32_t mask = cp.mask[i];
                     bool ok = offered;
                     int est = 0;
                     if (a >= 0) {
-                        ok = ok && (int)TESSEL_ST(oNext + a) > mu;
+                        ok = ok && ((int)TESSEL_ST(oNext + a) & 1023) > mu;
                         est = (int)TESSEL_ST(oTok + (int)cp.path[i] * N + min(mu, N - 1));
                     }
                     for (uint32_t rest = mask; rest; rest &= rest - 1u) {          // the block's devices (uniform)
@@ -1714,7 +1740,7 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                         if (mi > 0 && (int)(int16_t)TESSEL_ST(oMem + d) + mi > M) ok = false;
                         est = max(est, (int)TESSEL_ST(oFree + d));
                     }
-                    const int key = est + (int)TESSEL_ST(oJit + i);
+                    const int key = est + (nj >> 10);
                     // types ascend, so on equal (key, micro-batch) the earlier type stays
                     if (ok && (bi < 0 || key < bkey || (key == bkey && mu < bmu))) { bi = i; bmu = mu; best_est = est; bkey = key; }
                 }
@@ -1727,8 +1753,7 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                     for (int d = 0; d < D; d++)
                         if (mask >> d & 1u) { TESSEL_ST(oFree + d) = (uint16_t)en; TESSEL_ST(oMem + d) = (uint16_t)((int)(int16_t)TESSEL_ST(oMem + d) + mi); }
                     TESSEL_ST(oTok + (int)cp.path[bi] * N + bmu) = (uint16_t)en;
-                    TESSEL_ST(oNext + bi) = (uint16_t)(bmu + 1);
-                    TESSEL_ST(oJit + bi) = (uint16_t)(bmu + 1 < hi ? jitter(bi, bmu + 1) : 0u);
+                    TESSEL_ST(oNext + bi) = (uint16_t)((uint32_t)(bmu + 1) | (bmu + 1 < hi ? jitter(bi, bmu + 1) : 0u) << 10);
                 }
             }
             if (phase == 1) break;
@@ -1792,7 +1817,7 @@ __global__ void completion_reset_kernel(DevCompletion *res)
 
 size_t completion_lds_bytes(const CompParams &cp)
 {
-    return (size_t)kCompParamWords * 4 + (size_t)(cp.npaths * cp.N + 2 * cp.D + 2 * cp.K) * kWave * 2;
+    return (size_t)kCompParamWords * 4 + (size_t)(cp.npaths * cp.N + 2 * cp.D + cp.K) * kWave * 2;
 }
 
 int launch_completions(const CompParams &cp, uint64_t first, uint64_t count, int32_t *makespan_out, void *ws, int num_cus,
@@ -1808,7 +1833,7 @@ int launch_completions(const CompParams &cp, uint64_t first, uint64_t count, int
         attr_set = true;
     }
     int per_cu = (int)((160 * 1024) / ((lds + 511) / 512 * 512));
-    if (per_cu > 8) per_cu = 8;
+    if (per_cu > 16) per_cu = 16;
     if (per_cu < 1) per_cu = 1;
     uint64_t need = (count + kWave - 1) / kWave;
     const int blocks = need < (uint64_t)(num_cus * per_cu) ? (int)need : num_cus * per_cu;
