@@ -732,6 +732,16 @@ static int bind_completion(tessel_problem *p, int N, int J)
         npaths++;
     }
     cp.npaths = npaths;
+    {
+        // Phases and windows follow one another for all types together, so two types are never further apart than
+        // (largest - smallest lead) + NR micro-batches; a ring of the next power of two above that holds every
+        // micro-batch still on its way through a chain
+        int lo = c.leads[0], hi = c.leads[0];
+        for (int i = 1; i < K; i++) { lo = std::min(lo, c.leads[i]); hi = std::max(hi, c.leads[i]); }
+        int ring = 1;
+        while (ring < hi - lo + NR + 1) ring *= 2;
+        cp.tok_ring = ring;
+    }
     // one executable sequence of the window (the device orders of the best candidate)
     {
         std::vector<int> pos(D, 0), occ(K, 0);

@@ -147,7 +147,8 @@ struct DevDetail {
 constexpr int kMaxSeq = kMaxK * kMaxNR;
 struct CompParams {
     int32_t  D, K, NR, M, N, J, R, nseq, npaths;
-    int32_t  pad;
+    int32_t  tok_ring;               // slots per chain for the end times of the micro-batches in flight: a power of two
+                                     // above (largest - smallest lead) + NR, the most two types of a chain are ever apart
     uint64_t seed;                   // problem seed + kCompletionKey
     int32_t  t[kMaxK];
     int8_t   m[kMaxK];

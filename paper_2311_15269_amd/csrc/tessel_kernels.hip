@@ -1671,7 +1671,8 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
     const int D = cp.D, K = cp.K, N = cp.N, NR = cp.NR, M = cp.M, J = cp.J, R = cp.R;
     // a type's next micro-batch (low 10 bits) and the jitter of that block (high 6 bits) share a word: N < 1024 and
     // J < 64 (checked by the host)
-    const int oTok = 0, oFree = cp.npaths * N, oMem = oFree + D, oNext = oMem + D, nstate = oNext + K;
+    const int TR = cp.tok_ring, tmask = TR - 1;          // end times of the micro-batches in flight: [chain][mu mod TR]
+    const int oTok = 0, oFree = cp.npaths * TR, oMem = oFree + D, oNext = oMem + D, nstate = oNext + K;
     bool single_dev = true;
     for (int i = 0; i < K; i++) single_dev = single_dev && (cp.mask[i] & (cp.mask[i] - 1)) == 0 && cp.mask[i] != 0;
 #define TESSEL_ST(slot) state[(slot) * kWave]
@@ -1709,7 +1710,7 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                         const int a = cp.pred[i], mi = cp.m[i], d = __builtin_ctz((uint32_t)cp.mask[i]);
                         const int nj = (int)TESSEL_ST(oNext + i), mu = nj & 1023;
                         const int na = (int)TESSEL_ST(oNext + (a >= 0 ? a : i)) & 1023;
-                        const int tk = (int)TESSEL_ST(oTok + (int)cp.path[i] * N + min(mu, N - 1));
+                        const int tk = (int)TESSEL_ST(oTok + (int)cp.path[i] * TR + (mu & tmask));
                         const int fr = (int)TESSEL_ST(oFree + d), me = (int)(int16_t)TESSEL_ST(oMem + d);
                         const int jt = nj >> 10;
                         const bool offered = mu < hi;
@@ -1733,7 +1734,7 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                     int est = 0;
                     if (a >= 0) {
                         ok = ok && ((int)TESSEL_ST(oNext + a) & 1023) > mu;
-                        est = (int)TESSEL_ST(oTok + (int)cp.path[i] * N + min(mu, N - 1));
+                        est = (int)TESSEL_ST(oTok + (int)cp.path[i] * TR + (mu & tmask));
                     }
                     for (uint32_t rest = mask; rest; rest &= rest - 1u) {          // the block's devices (uniform)
                         const int d = __builtin_ctz(rest);
@@ -1752,7 +1753,7 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                     const uint32_t mask = cp.mask[bi];
                     for (int d = 0; d < D; d++)
                         if (mask >> d & 1u) { TESSEL_ST(oFree + d) = (uint16_t)en; TESSEL_ST(oMem + d) = (uint16_t)((int)(int16_t)TESSEL_ST(oMem + d) + mi); }
-                    TESSEL_ST(oTok + (int)cp.path[bi] * N + bmu) = (uint16_t)en;
+                    TESSEL_ST(oTok + (int)cp.path[bi] * TR + (bmu & tmask)) = (uint16_t)en;
                     TESSEL_ST(oNext + bi) = (uint16_t)((uint32_t)(bmu + 1) | (bmu + 1 < hi ? jitter(bi, bmu + 1) : 0u) << 10);
                 }
             }
@@ -1762,7 +1763,7 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                 for (int s = 0; s < cp.nseq; s++) {
                     const int i = cp.seq[s], mu = (int)cp.lead[i] + (int)cp.occ[s] + NR * k;
                     const uint32_t mask = cp.mask[i];
-                    const int tok = oTok + (int)cp.path[i] * N + mu;
+                    const int tok = oTok + (int)cp.path[i] * TR + (mu & tmask);
                     int est = cp.pred[i] >= 0 ? (int)TESSEL_ST(tok) : 0;
                     for (uint32_t rest = mask; rest; rest &= rest - 1u) est = max(est, (int)TESSEL_ST(oFree + __builtin_ctz(rest)));
                     const int en = est + cp.t[i];
@@ -1817,7 +1818,7 @@ __global__ void completion_reset_kernel(DevCompletion *res)
 
 size_t completion_lds_bytes(const CompParams &cp)
 {
-    return (size_t)kCompParamWords * 4 + (size_t)(cp.npaths * cp.N + 2 * cp.D + cp.K) * kWave * 2;
+    return (size_t)kCompParamWords * 4 + (size_t)(cp.npaths * cp.tok_ring + 2 * cp.D + cp.K) * kWave * 2;
 }
 
 int launch_completions(const CompParams &cp, uint64_t first, uint64_t count, int32_t *makespan_out, void *ws, int num_cus,

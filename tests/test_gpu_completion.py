@@ -76,7 +76,10 @@ def test_completion_argument_checks(gpu):
         g.search_completions(3, 2, 0, 10)                  # fewer micro-batches than one window
     assert e.value.code == -8
     with pytest.raises(gpu.TesselError) as e:
-        g.search_completions(600, 2, 0, 10)                # state of 600 micro-batches does not fit the LDS
+        g.search_completions(1100, 2, 0, 10)               # micro-batch numbers are kept in 10 bits, times in 16
+    assert e.value.code == -4
+    with pytest.raises(gpu.TesselError) as e:
+        g.search_completions(20, 64, 0, 10)                # the jitter in 6 bits
     assert e.value.code == -4
     with pytest.raises(gpu.TesselError) as e:
         g.search_completions(20, -1, 0, 10)
