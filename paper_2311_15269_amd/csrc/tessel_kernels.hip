@@ -1657,8 +1657,8 @@ size_t block_rec_bytes(int blocks) { return (size_t)blocks * sizeof(BlockRec); }
 // ordinal; ordinal 0 has no jitter (the plain greedy schedule).
 // Per-lane state in LDS [slot][lane]: end time of the latest block of every (chain, micro-batch), free time
 // and memory of every device, next micro-batch and current jitter of every type.
-constexpr int kCompParamWords = 256;       // the parameter block's copy at the start of the LDS, a table of kMaxK words at its end
-static_assert(sizeof(CompParams) <= (kCompParamWords - kMaxK) * 4, "parameter block and per-type table share the first KB of the LDS");
+constexpr int kCompParamWords = 320;       // start of the LDS: the parameter block's copy, then two tables of kMaxK words at the end
+static_assert(sizeof(CompParams) <= (kCompParamWords - 2 * kMaxK) * 4, "parameter block and per-type tables share the start of the LDS");
 
 __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__restrict__ cpg, uint64_t first, uint64_t count,
                                                          CompRec *__restrict__ recs, int32_t *__restrict__ makespan_out)
@@ -1674,17 +1674,25 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
     // J < 64 (checked by the host)
     const int TR = cp.tok_ring, tmask = TR - 1;          // end times of the micro-batches in flight: [chain][mu mod TR]
     const int oTok = 0, oFree = cp.npaths * TR, oMem = oFree + D, oNext = oMem + D, nstate = oNext + K;
-    bool single_dev = cp.npaths <= 8;           // (the per-type table below has three bits for the chain)
+    // Problems with every type on one device (and at most 8 chains) take a path that keeps, per type, the sort key of
+    // its offered block (or "not eligible") in LDS and recomputes only the types a scheduled block can change: those
+    // on its device and its consumer.  Tables for it, per type: `ptab` lead (8 bits), memory delta (8, signed),
+    // producer + 1 (6), device (3), chain (3), 1 (a type of the problem) in one word; `aff` the types to recompute.
+    bool single_dev = cp.npaths <= 8;
     for (int i = 0; i < K; i++) single_dev = single_dev && (cp.mask[i] & (cp.mask[i] - 1)) == 0 && cp.mask[i] != 0;
-    // per type, for the scan of single-device problems: lead (8 bits), memory delta (8, signed), producer + 1 (6),
-    // device (3), chain (3), 1 (a type of the problem) in one word; 0 beyond the last type
-    uint32_t *ptab = lds + kCompParamWords - kMaxK;           // the parameter block leaves the end of its slot free
-    if (lane < kMaxK)
-        ptab[lane] = lane < K ? (uint32_t)cp.lead[lane] | ((uint32_t)(uint8_t)cp.m[lane] << 8) | ((uint32_t)(cp.pred[lane] + 1) << 16) |
-                                    ((uint32_t)__builtin_ctz((uint32_t)cp.mask[lane] | 0x100u) << 22) | ((uint32_t)cp.path[lane] << 25) |
-                                    1u << 28
-                              : 0u;
+    uint32_t *ptab = lds + kCompParamWords - 2 * kMaxK, *aff = lds + kCompParamWords - kMaxK;
+    if (lane < kMaxK) {
+        uint32_t pw = 0, af = 0;
+        if (lane < K) {
+            pw = (uint32_t)cp.lead[lane] | ((uint32_t)(uint8_t)cp.m[lane] << 8) | ((uint32_t)(cp.pred[lane] + 1) << 16) |
+                 ((uint32_t)__builtin_ctz((uint32_t)cp.mask[lane] | 0x100u) << 22) | ((uint32_t)cp.path[lane] << 25) | 1u << 28;
+            for (int j = 0; j < K; j++)
+                if ((cp.mask[j] & cp.mask[lane]) != 0 || cp.pred[j] == lane) af |= 1u << j;
+        }
+        ptab[lane] = pw; aff[lane] = af;
+    }
     __syncthreads();
+    uint32_t *ckey = lds + kCompParamWords + (nstate + 1) / 2 * kWave + lane;      // [type][lane], behind the 16-bit state
 #define TESSEL_ST(slot) state[(slot) * kWave]
     int best = INT_MAX;
     uint64_t best_ord = 0;
@@ -1710,42 +1718,30 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                 TESSEL_ST(oNext + i) = (uint16_t)((uint32_t)mu | (mu < hi ? jitter(i, mu) : 0u) << 10);
                 left += max(hi - mu, 0);
             }
+            // sort key of the block type i offers, (start + jitter, micro-batch, type) in one word, smallest first:
+            // start + jitter < 2^16 (checked by the host), micro-batch < 2^10, type < 2^5; all ones: not eligible
+            auto offer_key = [&](int i) -> uint32_t {
+                const uint32_t pw = ptab[i];
+                const bool has_a = (pw >> 16 & 63u) != 0;
+                const int hi = phase ? N : (int)(pw & 255u), a = (int)(pw >> 16 & 63u) - 1, d = (int)(pw >> 22 & 7u);
+                const int mi = (int)(int8_t)(pw >> 8);
+                const int nj = (int)TESSEL_ST(oNext + i), mu = nj & 1023;
+                const int na = (int)TESSEL_ST(oNext + (has_a ? a : i)) & 1023;
+                const int fr = (int)TESSEL_ST(oFree + d), me = (int)(int16_t)TESSEL_ST(oMem + d);
+                const int tk = (int)TESSEL_ST(oTok + (int)(pw >> 25 & 7u) * TR + (mu & tmask));
+                const bool ok = (mu < hi) & (!has_a | (na > mu)) & ((mi <= 0) | (me + mi <= M));
+                const uint32_t key = (uint32_t)(max(has_a ? tk : 0, fr) + (nj >> 10));
+                return ok ? (key << 15) | ((uint32_t)mu << 5) | (uint32_t)i : 0xFFFFFFFFu;
+            };
+            if (single_dev)
+                for (int i = 0; i < K; i++) ckey[i * kWave] = offer_key(i);
             for (;;) {
                 int bi = -1, bmu = 0, best_est = 0, bkey = 0;
                 const bool any = left > 0;
                 if (single_dev) {
-                    // every type on one device: a scan without branches, so that the reads of several types are in
-                    // flight together.  (key, micro-batch, type) in one word, smallest first: key < 2^16 (checked by
-                    // the host), micro-batch < 2^10, type < 2^5.
                     uint32_t bestp = 0xFFFFFFFFu;
-                    for (int g = 0; g < K; g += 8) {
-                        // eight types at a time, all reads of a kind issued together; a group's missing types
-                        // (table entry 0) read the last type's state and are never eligible
-                        uint32_t pw[8];
-                        int nj[8], na[8], tk[8], fr[8], me[8];
-#pragma unroll
-                        for (int u = 0; u < 8; u++) pw[u] = (uint32_t)__builtin_amdgcn_readfirstlane((int)ptab[g + u]);
-#pragma unroll
-                        for (int u = 0; u < 8; u++) nj[u] = (int)TESSEL_ST(oNext + min(g + u, K - 1));
-#pragma unroll
-                        for (int u = 0; u < 8; u++) {
-                            const int a = (int)(pw[u] >> 16 & 63u) - 1, d = (int)(pw[u] >> 22 & 7u);
-                            na[u] = (int)TESSEL_ST(oNext + (a >= 0 ? a : min(g + u, K - 1)));
-                            fr[u] = (int)TESSEL_ST(oFree + d);
-                            me[u] = (int)(int16_t)TESSEL_ST(oMem + d);
-                            tk[u] = (int)TESSEL_ST(oTok + (int)(pw[u] >> 25 & 7u) * TR + (nj[u] & tmask));
-                        }
-#pragma unroll
-                        for (int u = 0; u < 8; u++) {
-                            const bool real = (pw[u] >> 28 & 1u) != 0, has_a = (pw[u] >> 16 & 63u) != 0;
-                            const int hi = !real ? 0 : phase ? N : (int)(pw[u] & 255u);
-                            const int mi = (int)(int8_t)(pw[u] >> 8), mu = nj[u] & 1023;
-                            const bool ok = (mu < hi) & (!has_a | ((na[u] & 1023) > mu)) & ((mi <= 0) | (me[u] + mi <= M));
-                            const uint32_t key = (uint32_t)(max(has_a ? tk[u] : 0, fr[u]) + (nj[u] >> 10));
-                            const uint32_t packed = (key << 15) | ((uint32_t)mu << 5) | (uint32_t)(g + u);
-                            bestp = min(bestp, ok ? packed : 0xFFFFFFFFu);
-                        }
-                    }
+#pragma unroll 8
+                    for (int i = 0; i < K; i++) bestp = min(bestp, ckey[i * kWave]);
                     if (bestp != 0xFFFFFFFFu) {
                         bi = (int)(bestp & 31u); bmu = (int)(bestp >> 5 & 1023u); bkey = (int)(bestp >> 15);
                         best_est = bkey - ((int)TESSEL_ST(oNext + bi) >> 10);
@@ -1785,6 +1781,17 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                     TESSEL_ST(oTok + (int)cp.path[bi] * TR + (bmu & tmask)) = (uint16_t)en;
                     TESSEL_ST(oNext + bi) = (uint16_t)((uint32_t)(bmu + 1) | (bmu + 1 < hi ? jitter(bi, bmu + 1) : 0u) << 10);
                     left--;
+                }
+                if (single_dev) {
+                    // the scheduled block changes what the types on its device and its consumer offer
+                    uint32_t todo = busy && bi >= 0 ? aff[bi] : 0u;
+                    while (__ballot(todo != 0u) != 0) {
+                        if (todo != 0u) {
+                            const int i = __builtin_ctz(todo);
+                            todo &= todo - 1u;
+                            ckey[i * kWave] = offer_key(i);
+                        }
+                    }
                 }
             }
             if (phase == 1) break;
@@ -1848,7 +1855,8 @@ __global__ void completion_reset_kernel(DevCompletion *res)
 
 size_t completion_lds_bytes(const CompParams &cp)
 {
-    return (size_t)kCompParamWords * 4 + (size_t)(cp.npaths * cp.tok_ring + 2 * cp.D + cp.K) * kWave * 2;
+    // 16-bit state, then one 32-bit sort key per type
+    return (size_t)kCompParamWords * 4 + (size_t)((cp.npaths * cp.tok_ring + 2 * cp.D + cp.K + 1) / 2 * 2) * kWave * 2 + (size_t)cp.K * kWave * 4;
 }
 
 int launch_completions(const CompParams &cp, uint64_t first, uint64_t count, int32_t *makespan_out, void *ws, int num_cus,
