@@ -1655,8 +1655,9 @@ size_t block_rec_bytes(int blocks) { return (size_t)blocks * sizeof(BlockRec); }
 // block with the smallest (earliest start + jitter, micro-batch, type id) is appended at its earliest
 // start.  jitter(type, mu) = (draw * (J + 1)) >> 16 with draw number type*N + mu of the stream keyed by the
 // ordinal; ordinal 0 has no jitter (the plain greedy schedule).
-// Per-lane state in LDS [slot][lane]: end time of the latest block of every (chain, micro-batch), free time
-// and memory of every device, next micro-batch and current jitter of every type.
+// Per-lane state in LDS [slot][lane], 16-bit words: end time of the latest block of every micro-batch in flight
+// (a ring per chain), free time and memory of every device, next micro-batch and its jitter of every type; behind
+// it, for problems with every type on one device, one 32-bit sort key per type.
 constexpr int kCompParamWords = 320;       // start of the LDS: the parameter block's copy, then two tables of kMaxK words at the end
 static_assert(sizeof(CompParams) <= (kCompParamWords - 2 * kMaxK) * 4, "parameter block and per-type tables share the start of the LDS");
 
