@@ -1513,7 +1513,7 @@ static int stage_words(const KParams &kp)
     const int nwords = (kp.total + 5) / 6;
     if (const char *env = getenv("TESSEL_STAGE_WORDS")) {           // tuning knob
         const int want = atoi(env);
-        if (want >= 1 && want <= nwords) return want;
+        if (want >= 0 && want <= nwords) return want;
     }
     return nwords >= 10 ? nwords / 5 : nwords;
 }
