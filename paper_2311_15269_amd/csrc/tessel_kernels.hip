@@ -790,8 +790,7 @@ __device__ __forceinline__ void build_begin(const KParams &P, const FastConst<DM
             auto pick = [&](uint32_t draw, uint32_t left, uint32_t &into, uint32_t at) {
                 const uint32_t digit = (uint32_t)(((uint64_t)draw * (uint64_t)((left << 16) & 0xFFFFFFu)) >> 32);    // (draw * left) >> 16 as a
                                                                                                        // 24-bit high multiply (left <= 32)
-                // the digit in bytes 0-2 (a byte permute: a multiply by 0x010101 would be a quarter-rate instruction)
-                const uint32_t ge = (__builtin_amdgcn_perm(0u, digit, 0x0c000000u) + tq) & 0x808080u;
+                const uint32_t ge = (__umul24(digit, 0x010101u) + tq) & 0x808080u;
                 tq += (ge >> 7) ^ 0x010101u;                     // a threshold above the digit loses one block
                 into |= (uint32_t)__builtin_popcount(ge) << (2u * at);   // symbol = number of thresholds at or below the digit
             };
