@@ -144,7 +144,9 @@ int  tessel_candidate_count(const tessel_problem *p, uint64_t *count);
 
 /* Bytes of device workspace tessel_eval_candidates / tessel_score_candidates need: the running best, lists of
  * unfinished candidates (24 MiB) and, for problems the fast kernel takes, two queues per resident wave between the
- * phases of the kernel (2 x 27 KB per wave for 256 blocks a window; a few hundred MB in all). */
+ * phases of the kernel (2 x 27 KB per wave for 256 blocks a window; a few hundred MB in all).  Sized for the current
+ * device (for 512 compute units where there is none to ask); a workspace too small for the device a call runs on is
+ * refused there with TESSEL_E_WORKSPACE. */
 int  tessel_workspace_bytes(const tessel_problem *p, size_t *bytes);
 
 /* Scores candidates first .. first+count-1 (Alg. 1, the loop over repetends: decode,

@@ -382,10 +382,18 @@ static size_t workspace_need(const tessel_problem *p, int num_cus)
 extern "C" int tessel_workspace_bytes(const tessel_problem *p, size_t *bytes)
 {
     if (!p || !bytes) return TESSEL_E_INVALID_ARG;
-    // sized for the largest grid the launcher uses (8 blocks on each of 256 compute units at most,
-    // more if the device reports more)
-    int cus = p->num_cus ? p->num_cus : 512;
-    *bytes = workspace_need(p, std::max(cus, 512));      // 16 workgroups per CU at most
+    // sized for the grid the launcher uses on the current device (16 workgroups per compute unit at most); for 512
+    // compute units where no device can be asked
+    int cus = p->num_cus;
+    if (!cus) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+            cus = prop.multiProcessorCount;
+        else
+            (void)hipGetLastError();
+    }
+    *bytes = workspace_need(p, cus ? cus : 512);
     return TESSEL_OK;
 }
 
