@@ -293,10 +293,10 @@ def test_queue_between_build_and_sweeps(gpu, monkeypatch, cfg, cap, count):
     compare_best(gpu, prob, first, count)
 
 
-@pytest.mark.parametrize("words", [1, 5, 42])
+@pytest.mark.parametrize("words", [0, 1, 5, 42])
 def test_first_build_phase_of_any_length(gpu, monkeypatch, words):
     """The build is cut into two phases after some program words (a fifth of them by default); where the cut lies
-    must not matter.  42 of 43 words: the second phase places the last four blocks only."""
+    must not matter.  0: the first phase only decodes; 42 of 43 words: the second places the last four blocks only."""
     prob = W.config5()
     monkeypatch.setenv("TESSEL_STAGE_WORDS", str(words))
     monkeypatch.setenv("TESSEL_BLOCKS_PER_CU", "1")
