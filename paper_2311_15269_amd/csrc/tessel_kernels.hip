@@ -559,8 +559,8 @@ __device__ __forceinline__ uint32_t bfi(uint32_t sel, uint32_t a, uint32_t b) { 
 #define TESSEL_PIN(x) asm volatile("" : "+v"(x))
 
 // One block of the window: s = max(device free, previous block of the micro-batch); both become s + t.  The
-// micro-batch it handles is the device's counter of its type, `cnt` (read by the caller, which has already
-// written the incremented word back and may have the next node's counter read in flight).
+// micro-batch it handles is the device's counter of its type in `cnt`, the counter word as it was before the
+// caller's atomic incremented it (the caller may have the next node's atomic in flight already).
 __device__ __forceinline__ void sweep_node(const FastLds &L, const uint4 tt, uint32_t cnt, uint32_t lane4)
 {
     // device times, counters and tokens lie at fixed distances in one array, so the three addresses of a block
@@ -620,9 +620,9 @@ __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds
         for (int j = 0; j < 6; j++) tt[j] = L.tt_tab[(w >> (5 * j)) & 31u];
 #pragma unroll
         for (int j = 0; j < 6; j++) { TESSEL_PIN(tt[j].x); TESSEL_PIN(tt[j].y); TESSEL_PIN(tt[j].z); TESSEL_PIN(tt[j].w); }
-        // counters run one node ahead of the times: the counter word goes back incremented at once, the next
-        // node's read follows it (LDS keeps a wave's accesses in order), and only then this node waits for its
-        // device time and token
+        // counters run one node ahead of the times: one returning LDS atomic reads and increments a node's counter
+        // word, the next node's atomic is issued behind it (LDS keeps a wave's accesses in order), and only then
+        // this node waits for its device time and token
         uint32_t cnt = atomicAdd((uint32_t *)((char *)L.dfree + (tt[0].z + lane4)) + DM * kWave, 1u << tt[0].w);
 #pragma unroll
         for (int j = 0; j < 6; j++) {
