@@ -159,6 +159,15 @@ def main():
     sweeps_per_cand = best["n_window_sweeps"] / best["n_evaluated"]
     ops_per_launch = algorithmic_ops(prob, chunk, sweeps_per_cand * chunk)
     achieved = ops_per_launch / avg_launch_s / 1e12
+    # The kernel stops building a candidate that is over the memory cap at the end of its first build phase (a fifth
+    # of the window's program words).  `achieved` prices every candidate at the whole window, as the method is stated;
+    # this second figure leaves out the blocks behind that point for every candidate rejected for memory (a lower
+    # bound: some of them are only caught at the end of the window).
+    total_blocks = prob["K"] * prob["NR"]
+    nwords = (total_blocks + 5) // 6
+    first_phase_blocks = min(total_blocks, 6 * (nwords // 5 if nwords >= 10 else nwords))
+    mem_rejects = best["n_reject"][5] / best["n_evaluated"]
+    ops_placed_only = ops_per_launch - chunk * mem_rejects * 34 * (total_blocks - first_phase_blocks)
 
     # practical ceiling: independent full-rate integer adds/maxes on every lane of the chip
     from paper_2311_15269_amd.binding import alu_probe
@@ -192,6 +201,7 @@ def main():
                      "traffic": TRAFFIC_BYTES_PER_2P24_LAUNCH if chunk == 1 << 24 else None,
                      "kernel": "eval_fast_kernel<8, 16, 2, false>", "avg_launch_ms": avg_launch_s * 1e3,
                      "algorithmic_ops_per_candidate": ops_per_launch / chunk,
+                     "frac_without_blocks_behind_a_memory_reject": ops_placed_only / avg_launch_s / 1e12 / PEAK_INT32_OPS,
                      "window_sweeps_per_candidate": sweeps_per_cand},
     }
 
