@@ -18,10 +18,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_INT32_OPS = 256 * 64 * 2.4e9 / 1e12      # T int32 lane-ops/s: 256 CUs x 64 lanes x 2.4 GHz, full-rate VALU ops
-# HBM bytes of one launch of 2^24 candidates, from the FETCH_SIZE / WRITE_SIZE passes in
-# profiles/eval_fast_kernel_cfg5_counters.md (3,425,571 KiB x 2.0 + 7,837,732 KiB x 1.0, copy-calibrated;
+# HBM bytes of one launch of 2^26 candidates, from the FETCH_SIZE / WRITE_SIZE passes in
+# profiles/eval_fast_kernel_cfg5_counters.md (13,537,265 KiB x 2.0 + 31,106,650 KiB x 1.0, copy-calibrated;
 # nearly all of it the queues between the kernel's phases)
-TRAFFIC_BYTES_PER_2P24_LAUNCH = int((3425571 * 2.0 + 7837732 * 1.0) * 1024)
+TRAFFIC_BYTES_PER_2P26_LAUNCH = int((13537265 * 2.0 + 31106650 * 1.0) * 1024)
 
 
 def algorithmic_ops(prob, n_candidates, n_sweeps):
@@ -39,7 +39,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--log2-candidates", type=int, default=28, help="candidates per step = 2^this (28 = the workload)")
-    ap.add_argument("--log2-chunk", type=int, default=24, help="candidates per kernel launch")
+    ap.add_argument("--log2-chunk", type=int, default=26, help="candidates per call of the entry point (one launch)")
     ap.add_argument("--cpu-sample-log2", type=int, default=20, help="oracle baseline sample size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--search", action="store_true",
@@ -198,7 +198,7 @@ def main():
         "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_INT32_OPS, "unit": "Tint32op/s",
                      "frac": achieved / PEAK_INT32_OPS,
                      "peak_measured": peak_measured, "frac_of_measured": achieved / peak_measured,
-                     "traffic": TRAFFIC_BYTES_PER_2P24_LAUNCH if chunk == 1 << 24 else None,
+                     "traffic": TRAFFIC_BYTES_PER_2P26_LAUNCH if chunk == 1 << 26 else None,
                      "kernel": "eval_fast_kernel<8, 16, 2, false>", "avg_launch_ms": avg_launch_s * 1e3,
                      "algorithmic_ops_per_candidate": ops_per_launch / chunk,
                      "frac_without_blocks_behind_a_memory_reject": ops_placed_only / avg_launch_s / 1e12 / PEAK_INT32_OPS,

@@ -143,7 +143,7 @@ void tessel_problem_destroy(tessel_problem *p);
 int  tessel_candidate_count(const tessel_problem *p, uint64_t *count);
 
 /* Bytes of device workspace tessel_eval_candidates / tessel_score_candidates need: the running best, lists of
- * unfinished candidates (24 MiB) and, for problems the fast kernel takes, two queues per resident wave between the
+ * unfinished candidates (72 MiB) and, for problems the fast kernel takes, two queues per resident wave between the
  * phases of the kernel (2 x 27 KB per wave for 256 blocks a window; a few hundred MB in all).  Sized for the current
  * device (for 512 compute units where there is none to ask); a workspace too small for the device a call runs on is
  * refused there with TESSEL_E_WORKSPACE. */
@@ -168,7 +168,7 @@ int  tessel_score_candidates(tessel_problem *p, uint64_t first, uint64_t count,
 /* Waits for the stream of the last call, then returns the running best.  NO_FEASIBLE when
  * nothing feasible has been scored (counters in *out are still valid).  If a launch left more
  * candidates unfinished than its internal list holds (possible only when more than an eighth of a
- * range of 2^24 candidates needs extra period work), every range scored since the last reset is
+ * range of 2^26 candidates needs extra period work), every range scored since the last reset is
  * scored again here in smaller pieces before the result is returned. */
 int  tessel_best(tessel_problem *p, tessel_result *out);
 

@@ -173,14 +173,14 @@ constexpr size_t kWsParamsOff = 2048;          // KParams of the bound problem
 constexpr size_t kWsTablesOff = 8192;          // lead table, arrangement table
 constexpr size_t kWsTablesMax = 1 << 20;
 constexpr size_t kWsRetryOff = kWsTablesOff + kWsTablesMax;    // candidates that get a second fast pass with more sweeps
-constexpr uint32_t kWsRetryCap = 1u << 21;
+constexpr uint32_t kWsRetryCap = 1u << 23;
 constexpr size_t kWsListOff = kWsRetryOff + (size_t)kWsRetryCap * 8;   // candidates deferred to the general kernel
 constexpr uint32_t kWsListCap = 1u << 20;
 constexpr size_t kWsCompParamsOff = kWsListOff + (size_t)kWsListCap * 8;   // CompParams
 constexpr size_t kWsBlockRecOff = kWsCompParamsOff + 1024;
 constexpr int kDeferBlocks = 64;                                // grid of the deferred pass
 constexpr int kFirstPassTries = 2;                              // sweeps before a candidate goes to the retry list
-constexpr uint64_t kMaxPerLaunch = 1ull << 24;                  // candidates per pass of the kernels
+constexpr uint64_t kMaxPerLaunch = 1ull << 26;                  // candidates per pass of the kernels
 constexpr uint64_t kSafePerLaunch = 1ull << 20;                 // ... at which no list can overflow (<= both list capacities)
 constexpr int kRetryTries = 8;                                  // ... and before the general kernel gets it
 

@@ -1,5 +1,5 @@
 """The HIP path at the full sizes of the five benchmark configurations, in the launch shape
-bench.py uses (2^24 candidates per launch).  The oracle cannot sweep these ranges, so: the
+bench.py uses (2^26 candidates per launch).  The oracle cannot sweep these ranges, so: the
 exhaustive 4-device space is compared with a stored oracle result (written by
 tests/golden/make_exhaustive_golden.py, oracle only); for the sampled spaces the reported best
 candidate and windows of per-candidate scores spread over the range are recomputed by the
@@ -14,7 +14,7 @@ from paper_2311_15269_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
-CHUNK = 1 << 24
+CHUNK = 1 << 26
 
 
 @pytest.fixture(scope="module")
@@ -140,18 +140,18 @@ def test_list_overflow_is_recovered(gpu, monkeypatch):
     scored again in smaller pieces and the result equals the ordinary one."""
     prob = dict(W.config3(), M=100)                   # every candidate feasible
     want_g = gpu.Problem(prob)
-    want_g.eval_candidates(0, 1 << 22)
-    want_g.eval_candidates(1 << 23, 1000)
+    want_g.eval_candidates(0, 1 << 24)
+    want_g.eval_candidates(1 << 25, 1000)
     want = want_g.best()
     monkeypatch.setenv("TESSEL_EIGEN_TRIES", "0")     # and every one unfinished after the first pass
     g = gpu.Problem(prob)
     monkeypatch.delenv("TESSEL_EIGEN_TRIES")
-    g.eval_candidates(0, 1 << 22)                     # the retry list holds 2^21
-    g.eval_candidates(1 << 23, 1000)
+    g.eval_candidates(0, 1 << 24)                     # the retry list holds 2^23
+    g.eval_candidates(1 << 25, 1000)
     got = g.best()
     for key in ("period", "index", "peak", "n_evaluated", "n_feasible", "n_reject"):
         assert got[key] == want[key], key
-    assert got["n_evaluated"] == (1 << 22) + 1000
+    assert got["n_evaluated"] == (1 << 24) + 1000
     g.reset()
     g.eval_candidates(0, 1 << 15)
     assert g.best()["n_evaluated"] == 1 << 15
