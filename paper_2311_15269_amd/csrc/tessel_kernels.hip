@@ -1796,7 +1796,23 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                 }
             }
             if (phase == 1) break;
-            // ---- the R windows: the same blocks at the same micro-batches in every lane
+            // ---- the R windows: the same blocks at the same micro-batches in every lane.  (Every type on one device:
+            // from the per-type table, and without the memory, which a whole window leaves as it was: the deltas on a
+            // device sum to zero, and the window itself was scored against the cap.)
+            if (single_dev) {
+                for (int k = 0; k < R; k++)
+                    for (int s = 0; s < cp.nseq; s++) {
+                        const int i = cp.seq[s];
+                        const uint32_t pw = (uint32_t)__builtin_amdgcn_readfirstlane((int)ptab[i]);
+                        const int mu = (int)(pw & 255u) + (int)cp.occ[s] + NR * k, d = (int)(pw >> 22 & 7u);
+                        const int tok = oTok + (int)(pw >> 25 & 7u) * TR + (mu & tmask);
+                        int est = (int)TESSEL_ST(oFree + d);
+                        if ((pw >> 16 & 63u) != 0) est = max(est, (int)TESSEL_ST(tok));
+                        const int en = est + cp.t[i];
+                        TESSEL_ST(oFree + d) = (uint16_t)en;
+                        TESSEL_ST(tok) = (uint16_t)en;
+                    }
+            } else
             for (int k = 0; k < R; k++)
                 for (int s = 0; s < cp.nseq; s++) {
                     const int i = cp.seq[s], mu = (int)cp.lead[i] + (int)cp.occ[s] + NR * k;
