@@ -12,6 +12,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
     # packed FP32 instructions are kept out of every device code object of this build
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # LDS and workspace words are read and written through pointers of several types (16-bit state next to 32-bit
+    # tables, records as vectors and as words): no type-based alias analysis
+    "-fno-strict-aliasing",
     "-Wall", "-Wno-unused-function",
 ]
 
