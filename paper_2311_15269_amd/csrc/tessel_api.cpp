@@ -253,6 +253,7 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
             if (span > 120) ok = false;
         }
         for (int i = 0; i < K; i++) if (desc->mem[i] < -127 || desc->mem[i] > 127) ok = false;
+        for (int i = 0; i < K; i++) if (desc->time[i] > 65535) ok = false;      // the sweep table keeps t in 16 bits
         for (int i = 0; i < kMaxK; i++) kp.info_loc[i] = 63u | (63u << 6);
         for (int i = 0; i < K && ok; i++) {
             uint32_t su = kp.succ[i] < 0 ? 63u : (uint32_t)home[kp.succ[i]];

@@ -513,10 +513,14 @@ struct FastProgram {
     __device__ __forceinline__ void set(int i, uint32_t v) { if (i < 32) a[i] = v; else b[i - 32] = v; }
 };
 
-constexpr int kFastTableWords = 13 * kMaxK;      // uniform tables at the start of the fast kernel's LDS
+constexpr int kFastTableWords = 16 * kMaxK;      // uniform tables at the start of the fast kernel's LDS
+constexpr int kSweepTabWord = 13 * kMaxK;        // ... of which the sweeps' table by code (and the chains' behind it)
 
 struct FastLds {
-    uint4 *tt_tab;        // [32]  by code, for the sweeps: x: t, y: byte offset of the first token slot of the code's
+    uint32_t *sw_tab;     // [32]  by code, for the sweeps of problems without blocks on several devices:
+                          //       t << 16 | LDS address of the time of the code's device (lane 0)
+    uint32_t *ch_tab;     // [32]  by code, right behind sw_tab: LDS address of the first token of the code's chain (lane 0)
+    uint4 *tt_tab;        // [32]  by code, for the sweeps of the TP variants: x: t, y: byte offset of the first token slot of the code's
                           //       chain, z: byte offset of its device's words, w: bit offset of its micro-batch counter
     uint4 *type_tab;      // [32]  by code, what placing one block of the type does:
                           //   x: added to the last word of its device record: memory delta << 16, one waiting
@@ -553,6 +557,23 @@ struct FastConst {
 };
 
 __device__ __forceinline__ uint32_t bfi(uint32_t sel, uint32_t a, uint32_t b) { return (sel & a) | (~sel & b); }
+
+// position of the lowest set bit; all ones for 0, which "& 28", shift counts and bit-field offsets (all of them use the
+// low five bits) read as 31: no guard bit has to be set first
+__device__ __forceinline__ uint32_t low_bit(uint32_t x)
+{
+    uint32_t r;
+    asm("v_ffbl_b32 %0, %1" : "=v"(r) : "v"(x));
+    return r;
+}
+
+// a * b + c for a, b below 2^24, low 32 bits: the full-rate 24-bit multiply-add (b uniform)
+__device__ __forceinline__ uint32_t mad24(uint32_t a, uint32_t b, uint32_t c)
+{
+    uint32_t r;
+    asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(b), "v"(c));
+    return r;
+}
 
 // keeps a value in a VGPR at this point, so that the loads above it are issued together instead of
 // being sunk into later branches
@@ -592,6 +613,91 @@ __device__ __forceinline__ void sweep_node_group(const FastLds &L, const uint4 t
     *tk = en;
 }
 
+// LDS accesses by byte address: address arithmetic stays integer arithmetic, and a constant added to an
+// address goes into the instruction's offset field.
+typedef __attribute__((address_space(3))) uint32_t lds_word;
+__device__ __forceinline__ uint32_t lds_address(const void *p) { return (uint32_t)(uintptr_t)(const lds_word *)p; }
+__device__ __forceinline__ uint32_t lds_load(uint32_t a) { return *(const lds_word *)a; }
+__device__ __forceinline__ void lds_store(uint32_t a, uint32_t v) { *(lds_word *)a = v; }
+__device__ __forceinline__ uint32_t lds_fetch_add(uint32_t a, uint32_t v)
+{
+    return __hip_atomic_fetch_add((lds_word *)a, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// The blocks of one sweep for problems whose blocks sit on one device each, as a software pipeline four blocks deep.
+// Per block: its table word is read (T); one returning LDS atomic reads and increments the counter word of its
+// device (A), which names the micro-batch and with it the token; device time and token are read (R); s = max of the
+// two, both become s + t (W).  As a dependent chain T -> A -> R -> W the wave would wait for the LDS three times a
+// block, so block k + 3 does T, block k + 2 A and block k + 1 R before block k does W.  R(k + 1) then misses what
+// W(k) writes: when block k + 1 runs on the same device or handles the same micro-batch as block k, the value read is
+// replaced by block k's end time (two compares, two selects).  LDS keeps a wave's accesses in order, so W(k - 1) and
+// everything older is seen.
+// Table word of a code: t << 16 | LDS address of its device's time (lane 0); with several chains (MC) a second
+// table holds the LDS address of the chain's first token (lane 0).  The counter shift 4 * symbol is the low bits
+// of the table address (the table is 16-byte aligned).
+// Past the last block the stages T, A and R run on code 0 (a counter that the window boundary resets anyway, reads
+// inside the arrays); stage W does not.
+template <int DM, bool MC>
+__device__ __forceinline__ void sweep_blocks(const FastConst<DM> &C, const FastLds &L, const FastProgram &prog, uint32_t lane4)
+{
+    const int total = C.total, nfull = total / 6, tail = total - 6 * nfull;
+    constexpr uint32_t tab = kSweepTabWord * 4u;                // the kernel's LDS starts at address 0 (checked at its start)
+    const uint32_t lane_tok = lds_address(L.dfree) + 2u * DM * kWave * 4u + lane4;
+    struct Tst { uint32_t tt, sh, ch; };                        // T done
+    struct Ast { uint32_t tt, fa, sh, cnt, ch; };               // A done
+    struct Rst { uint32_t tt, fa, ta, fr, tk; };                // R done
+    auto stage_t = [&](uint32_t w, int pos) -> Tst {
+        Tst o;
+        const uint32_t c4 = (pos == 0 ? w << 2 : w >> (5 * pos - 2)) & 0x7Cu;
+        o.sh = c4 & 0xCu;
+        o.tt = lds_load(c4 + tab);
+        o.ch = MC ? lds_load(c4 + tab + kMaxK * 4u) : 0u;
+        return o;
+    };
+    auto stage_a = [&](const Tst &x) -> Ast {
+        Ast o;
+        o.tt = x.tt; o.ch = x.ch; o.sh = x.sh;
+        o.fa = (x.tt & 0xFFFFu) + lane4;
+        o.cnt = lds_fetch_add(o.fa + DM * kWave * 4u, 1u << x.sh);
+        return o;
+    };
+    auto stage_r = [&](const Ast &x) -> Rst {
+        Rst o;
+        o.tt = x.tt; o.fa = x.fa;
+        const uint32_t mu = __builtin_amdgcn_ubfe(x.cnt, x.sh, 4);
+        o.ta = MC ? (mu << 8) + lane4 + x.ch : (mu << 8) + lane_tok;
+        o.fr = lds_load(x.fa);
+        o.tk = lds_load(o.ta);
+        return o;
+    };
+    auto stage_w = [&](const Rst &x) {
+        const uint32_t en = max(x.fr, x.tk) + (x.tt >> 16);
+        lds_store(x.fa, en);
+        lds_store(x.ta, en);
+    };
+    // per program word: the six table words first (they depend on the word only), then the blocks, the counter
+    // atomic one block ahead of the times
+    auto word = [&](uint32_t w, int nblocks) {
+        Tst t[6];
+#pragma unroll
+        for (int j = 0; j < 6; j++) if (j < nblocks) t[j] = stage_t(w, j);
+        Ast a = stage_a(t[0]);
+#pragma unroll
+        for (int j = 0; j < 6; j++)
+            if (j < nblocks) {
+                Ast an = a;
+                if (j + 1 < nblocks) an = stage_a(t[j + 1]);
+                stage_w(stage_r(a));
+                a = an;
+            }
+    };
+    for (int i = 0; i < nfull; i++) word(prog.get(i), 6);
+    if (tail > 0) {
+        const uint32_t w = prog.get(nfull);
+        if (tail == 1) word(w, 1); else if (tail == 2) word(w, 2); else if (tail == 3) word(w, 3); else if (tail == 4) word(w, 4); else word(w, 5);
+    }
+}
+
 // One sweep of the window over the program, then the window boundary.
 template <int DM, bool TP>
 __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds &L, const FastProgram &prog, int lane,
@@ -601,7 +707,6 @@ __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds
     // its counters would leave the token ring
     if (!active) return;
     const uint32_t lane4 = (uint32_t)lane * 4u;
-    const int full = C.total / 6, tail = C.total - 6 * full;
     if (TP) {
         for (int k = 0; k < C.total; k++) {
             const uint32_t code = (prog.get(k / 6) >> (5 * (k % 6))) & 31u;
@@ -612,38 +717,8 @@ __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds
             sweep_node_group<DM>(L, tt, cnt, (uint32_t)lane, L.grp_tab[code], C.D);
         }
     } else {
-    for (int i = 0; i < full; i++) {
-        const uint32_t w = prog.get(i);
-        // the six table entries first: they depend on the word only, so their reads leave the chain of the nodes
-        uint4 tt[6];
-#pragma unroll
-        for (int j = 0; j < 6; j++) tt[j] = L.tt_tab[(w >> (5 * j)) & 31u];
-#pragma unroll
-        for (int j = 0; j < 6; j++) { TESSEL_PIN(tt[j].x); TESSEL_PIN(tt[j].y); TESSEL_PIN(tt[j].z); TESSEL_PIN(tt[j].w); }
-        // counters run one node ahead of the times: one returning LDS atomic reads and increments a node's counter
-        // word, the next node's atomic is issued behind it (LDS keeps a wave's accesses in order), and only then
-        // this node waits for its device time and token
-        uint32_t cnt = atomicAdd((uint32_t *)((char *)L.dfree + (tt[0].z + lane4)) + DM * kWave, 1u << tt[0].w);
-#pragma unroll
-        for (int j = 0; j < 6; j++) {
-            uint32_t next = 0;
-            if (j < 5) next = atomicAdd((uint32_t *)((char *)L.dfree + (tt[j + 1].z + lane4)) + DM * kWave, 1u << tt[j + 1].w);
-            sweep_node(L, tt[j], cnt, lane4);
-            cnt = next;
-        }
-    }
-    if (tail > 0) {
-        const uint32_t w = prog.get(full);
-#pragma unroll
-        for (int j = 0; j < 5; j++)
-            if (j < tail) {
-                const uint4 tt = L.tt_tab[(w >> (5 * j)) & 31u];
-                uint32_t *cp = (uint32_t *)((char *)L.dfree + (tt.z + lane4)) + DM * kWave;
-                const uint32_t cnt = *cp;
-                *cp = cnt + (1u << tt.w);
-                sweep_node(L, tt, cnt, lane4);
-            }
-    }
+        if (C.npaths > 1) sweep_blocks<DM, true>(C, L, prog, lane4);
+        else sweep_blocks<DM, false>(C, L, prog, lane4);
     }
     // window boundary: micro-batches mu >= N_R are mu - N_R of the next window; counters restart at the leads
     for (int p = 0; p < C.npaths; p++)
@@ -790,7 +865,7 @@ __device__ __forceinline__ void build_begin(const KParams &P, const FastConst<DM
             auto pick = [&](uint32_t draw, uint32_t left, uint32_t &into, uint32_t at) {
                 const uint32_t digit = (uint32_t)(((uint64_t)draw * (uint64_t)((left << 16) & 0xFFFFFFu)) >> 32);    // (draw * left) >> 16 as a
                                                                                                        // 24-bit high multiply (left <= 32)
-                const uint32_t ge = (__umul24(digit, 0x010101u) + tq) & 0x808080u;
+                const uint32_t ge = mad24(digit, 0x010101u, tq) & 0x808080u;
                 tq += (ge >> 7) ^ 0x010101u;                     // a threshold above the digit loses one block
                 into |= (uint32_t)__builtin_popcount(ge) << (2u * at);   // symbol = number of thresholds at or below the digit
             };
@@ -910,8 +985,8 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
     int worst = S.worst, status = S.status;
     bool building = repair || (live && status == kOk);
     const uint32_t lane16 = (uint32_t)lane * 16u;
-    for (int wi = w_from; wi < w_to; wi++) {          // one program word = six blocks
-        if (!repair && __ballot(building) == 0) break;
+    // one program word = six blocks
+    auto word = [&](int wi) -> uint32_t {
         uint32_t acc = 0;
         const int nj = __builtin_amdgcn_readfirstlane(min(6, total - wi * 6));
 #pragma unroll 1
@@ -921,7 +996,7 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
                 for (int k = 0; k < C.ntp; k++) hm = (hm & C.tpg[k]) == C.tpg[k] ? hm : hm & ~C.tpg[k];
             const uint32_t sel = hm ? hm : (repair ? R : 0u);
             if (!repair && building && sel == 0) { status = kDeadlock; building = false; }
-            const uint32_t b = (uint32_t)__builtin_ctz(sel | 0x80000000u);
+            const uint32_t b = low_bit(sel);
             uint32_t d4 = repair ? min(b & 28u, 4u * (DM - 1)) : building ? b & 28u : 0u;    // 4 * device
             TESSEL_PIN(d4);
             uint4 *rp = (uint4 *)((char *)L.rec + ((d4 << 8) + lane16));
@@ -932,7 +1007,7 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
             const uint32_t r0 = (uint32_t)__builtin_amdgcn_sbfe(r4, 0, 1), r1 = (uint32_t)__builtin_amdgcn_sbfe(r4, 1, 1),
                            r2 = (uint32_t)__builtin_amdgcn_sbfe(r4, 2, 1), r3 = (uint32_t)__builtin_amdgcn_sbfe(r4, 3, 1);
             const uint32_t gate = bfi(a.y, bfi(a.x, r3, r2), bfi(a.x, r1, r0));
-            const uint32_t p = (uint32_t)__builtin_ctz((a.z & gate) | 0x80000000u);
+            const uint32_t p = low_bit(a.z & gate);
             // its symbol, as two all-or-nothing masks
             const uint32_t ly = (uint32_t)__builtin_amdgcn_sbfe((int)a.x, p, 1), hy = (uint32_t)__builtin_amdgcn_sbfe((int)a.y, p, 1);
             const uint32_t y = (ly & 1u) | (hy & 2u);
@@ -941,7 +1016,7 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
             // take the entry out; new head of the device.  (When the device is empty now the bit set below is
             // meaningless, and harmless: all its types are exhausted, and R never holds an exhausted type.)
             const uint32_t alive = a.z & ~(1u << p);
-            const uint32_t p2 = (uint32_t)__builtin_ctz(alive | 0x80000000u);
+            const uint32_t p2 = low_bit(alive);
             const uint32_t y2 = __builtin_amdgcn_ubfe(a.x, p2, 1) | (__builtin_amdgcn_ubfe(a.y, p2, 1) << 1);
             const uint32_t hm_new = (HM & ~(15u << d4)) | (1u << (d4 + y2));
             // one waiting micro-batch is consumed; the type stays runnable while another one waits and
@@ -1004,7 +1079,16 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
             }
             if (active) { R = r_fin; X = x_fin; HM = hm_fin; }
         }
-        prog.set(wi, acc);
+        return acc;
+    };
+    // the program is two register vectors: one loop for each, so that a store never has to choose between them
+    for (int wi = w_from; wi < min(w_to, 32); wi++) {
+        if (!repair && __ballot(building) == 0) break;
+        prog.a[wi] = word(wi);
+    }
+    for (int wi = max(w_from, 32); wi < w_to; wi++) {
+        if (!repair && __ballot(building) == 0) break;
+        prog.b[wi - 32] = word(wi);
     }
     S.R = R; S.HM = HM; S.X = X; S.worst = worst; S.status = status;
 }
@@ -1035,6 +1119,8 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     // with an input list: score the listed candidates (all inside [first, first + count)) instead of the range
     if (in_list) count = min(*in_count, in_cap);
     extern __shared__ uint32_t lds[];
+    // the sweeps address their tables by LDS byte address from 0: the kernel has no other LDS in front of this array
+    if (lds_address(lds) != 0u) { if (threadIdx.x == 0) *overflow = 0x100u; return; }
     const KParams &P = *Pp;
     const int lane = threadIdx.x;
     FastLds L;
@@ -1046,6 +1132,8 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     L.cum_tab = lds + 10 * kMaxK;
     L.predbit_tab = lds + 11 * kMaxK;
     L.depbit_tab = lds + 12 * kMaxK;
+    L.sw_tab = lds + kSweepTabWord;
+    L.ch_tab = lds + kSweepTabWord + kMaxK;
     uint32_t *base = lds + kFastTableWords + (TP ? kMaxK : 0);
     L.rec = (uint4 *)base;
     // the sweep state is only used once the build is over: it shares the records' space when it fits
@@ -1072,6 +1160,13 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
                 L.type_tab[lane] = make_uint4(((uint32_t)m << 16) - (1u << (4u * y)) + (same ? inc : 0u),
                                               has_su ? 1u << (su & 31u) : 0u,
                                               has_su && !same ? (su >> 2) * (kWave * 16u) + 12u : 0xFFFFFFFFu, inc);
+        }
+        {
+            // codes no block type has: device 0, chain 0, t = 0 (the pipeline of the sweeps reads code 0 past the end)
+            const bool used = P.t_loc[lane] != 0;
+            const uint32_t dev = used ? (uint32_t)lane >> 2 : 0u, rel = used ? ((inf >> 12) & 63u) - (uint32_t)P.D : 0u;
+            L.sw_tab[lane] = ((uint32_t)P.t_loc[lane] << 16) | (lds_address(L.dfree) + dev * (kWave * 4u));
+            L.ch_tab[lane] = lds_address(L.dfree) + (2u * DM + rel) * (kWave * 4u);
         }
         L.chain_tab[lane] = P.chain_tab[lane];
         L.vtab[lane] = lane < 24 ? P.vtab[lane] : 0u;
@@ -1113,7 +1208,8 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     const int wordsA = split ? stage_words : nwords;
     const int chunksA = (wordsA + 3) / 4, chunksAll = (nwords + 3) / 4;
     const bool drop_mem = MODE == 2 && peak_out == nullptr;          // a rejected candidate's peak is that of the whole window
-    FastProgram prog;
+    // every phase has a program of its own (words it does not write stay undefined and are never read), so that no
+    // program lives on from one phase to the next
     Mu lead_code;
     BuildState S;
 
@@ -1130,7 +1226,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
             if (peak_out) peak_out[idx - first] = status == kMem ? pk : 0;
         }
     };
-    auto push_program = [&](bool ok, uint64_t idx, int pk) {
+    auto push_program = [&](bool ok, uint64_t idx, int pk, const FastProgram &prog) {
         const uint64_t okm = __ballot(ok);
         if (okm == 0) return;
         if (ok) {
@@ -1153,21 +1249,18 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
         __threadfence_block();         // the stores of this wave's other lanes must be visible to the loads below
         const bool have = (uint32_t)lane < n;
         const uint32_t *src = ring2 + ((head2 + (uint32_t)lane) & (kRingSlots - 1u));
-        uint64_t idx = first;
-        int pk = 0;
-        prog.a = 0; prog.b = 0;
-        if (have) {
-            lead_code.lo = (uint64_t)src[0 * kRingSlots] | ((uint64_t)src[1 * kRingSlots] << 32);
-            lead_code.hi = (uint64_t)src[2 * kRingSlots] | ((uint64_t)src[3 * kRingSlots] << 32);
-            idx = (uint64_t)src[4 * kRingSlots] | ((uint64_t)src[5 * kRingSlots] << 32);
-            pk = (int)src[6 * kRingSlots];
+        // every lane loads (a lane without a candidate reads a slot behind the last one: stale words, results dropped)
+        FastProgram prog;
+        lead_code.lo = (uint64_t)src[0 * kRingSlots] | ((uint64_t)src[1 * kRingSlots] << 32);
+        lead_code.hi = (uint64_t)src[2 * kRingSlots] | ((uint64_t)src[3 * kRingSlots] << 32);
+        const uint64_t idx = have ? (uint64_t)src[4 * kRingSlots] | ((uint64_t)src[5 * kRingSlots] << 32) : first;
+        const int pk = (int)src[6 * kRingSlots];
 #pragma unroll
-            for (int c4 = 0; c4 < 12; c4++)
-                if (c4 < chunksAll) {
+        for (int c4 = 0; c4 < 12; c4++)
+            if (c4 < chunksAll) {
 #pragma unroll
-                    for (int w = 4 * c4; w < 4 * c4 + 4; w++) prog.set(w, src[(kRingMetaWords + w) * kRingSlots]);
-                }
-        }
+                for (int w = 4 * c4; w < 4 * c4 + 4; w++) prog.set(w, src[(kRingMetaWords + w) * kRingSlots]);
+            }
         head2 = (head2 + n) & (kRingSlots - 1u);
         count2 -= n;
         const int T = period_fast<DM, VM, TP>(C, L, prog, lane, lead_code, have, nsw);
@@ -1187,41 +1280,38 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
         }
     };
     // the end of the build for the candidates the lanes hold: verdict, then ring 2 or out
-    auto finish_build = [&](bool have, uint64_t idx) {
+    auto finish_build = [&](bool have, uint64_t idx, const FastProgram &prog) {
         int pk;
         const int status = build_end<DM>(C, S, pk);
         reject(have && status != kOk, idx, status, pk);
-        push_program(have && status == kOk, idx, pk);
+        push_program(have && status == kOk, idx, pk, prog);
     };
     // phase B on the first n candidates of ring 1
     auto build_from_ring = [&](uint32_t n) {
         __threadfence_block();
         const bool have = (uint32_t)lane < n;
         const uint32_t *src = ring1 + ((head1 + (uint32_t)lane) & (kRingSlots - 1u));
-        uint64_t idx = first;
-        S.R = S.HM = S.X = 0u; S.worst = INT_MIN; S.status = kOk;
-        prog.a = 0; prog.b = 0;
-        if (have) {
-            S.R = src[0 * kRingSlots]; S.HM = src[1 * kRingSlots]; S.X = src[2 * kRingSlots]; S.worst = (int)src[3 * kRingSlots];
-            lead_code.lo = (uint64_t)src[4 * kRingSlots] | ((uint64_t)src[5 * kRingSlots] << 32);
-            lead_code.hi = (uint64_t)src[6 * kRingSlots] | ((uint64_t)src[7 * kRingSlots] << 32);
-            idx = (uint64_t)src[8 * kRingSlots] | ((uint64_t)src[9 * kRingSlots] << 32);
+        FastProgram prog;
+        S.status = kOk;
+        S.R = src[0 * kRingSlots]; S.HM = src[1 * kRingSlots]; S.X = src[2 * kRingSlots]; S.worst = (int)src[3 * kRingSlots];
+        lead_code.lo = (uint64_t)src[4 * kRingSlots] | ((uint64_t)src[5 * kRingSlots] << 32);
+        lead_code.hi = (uint64_t)src[6 * kRingSlots] | ((uint64_t)src[7 * kRingSlots] << 32);
+        const uint64_t idx = have ? (uint64_t)src[8 * kRingSlots] | ((uint64_t)src[9 * kRingSlots] << 32) : first;
 #pragma unroll
-            for (int d = 0; d < DM; d++)
-                if (d < C.D)
-                    L.rec[d * kWave + lane] = make_uint4(src[(kStageMetaWords + 4 * d) * kRingSlots], src[(kStageMetaWords + 4 * d + 1) * kRingSlots],
-                                                         src[(kStageMetaWords + 4 * d + 2) * kRingSlots], src[(kStageMetaWords + 4 * d + 3) * kRingSlots]);
+        for (int d = 0; d < DM; d++)
+            if (d < C.D)
+                L.rec[d * kWave + lane] = make_uint4(src[(kStageMetaWords + 4 * d) * kRingSlots], src[(kStageMetaWords + 4 * d + 1) * kRingSlots],
+                                                     src[(kStageMetaWords + 4 * d + 2) * kRingSlots], src[(kStageMetaWords + 4 * d + 3) * kRingSlots]);
 #pragma unroll
-            for (int c4 = 0; c4 < 12; c4++)
-                if (c4 < chunksA) {
+        for (int c4 = 0; c4 < 12; c4++)
+            if (c4 < chunksA) {
 #pragma unroll
-                    for (int w = 4 * c4; w < 4 * c4 + 4; w++) prog.set(w, src[(kStageMetaWords + 4 * DM + w) * kRingSlots]);
-                }
-        }
+                for (int w = 4 * c4; w < 4 * c4 + 4; w++) prog.set(w, src[(kStageMetaWords + 4 * DM + w) * kRingSlots]);
+            }
         head1 = (head1 + n) & (kRingSlots - 1u);
         count1 -= n;
         build_words<DM, MODE, TP>(P, C, L, lane, have, wordsA, nwords, prog, S);
-        finish_build(have, idx);
+        finish_build(have, idx, prog);
     };
 
     const uint64_t stride = (uint64_t)gridDim.x * kWave;
@@ -1232,9 +1322,9 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
         const bool valid = kk < count;
         const uint64_t idx = !valid ? first : in_list ? in_list[kk] : first + kk;
         build_begin<DM, MODE, TP>(P, C, idx, L, lane, lead_code, S);
-        prog.a = 0; prog.b = 0;          // (nothing of the last program lives on: its registers are free during the decode)
+        FastProgram prog;
         build_words<DM, MODE, TP>(P, C, L, lane, valid, 0, wordsA, prog, S);
-        if (!split) { finish_build(valid, idx); return; }
+        if (!split) { finish_build(valid, idx, prog); return; }
         const bool over = drop_mem && S.status == kOk && S.worst > C.M;
         reject(valid && (S.status != kOk || over), idx, over ? (int)kMem : S.status, 0);
         const bool ok = valid && S.status == kOk && !over;
