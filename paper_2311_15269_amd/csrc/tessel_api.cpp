@@ -296,9 +296,14 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         }
         kp.fast_ok = ok;
         kp.eigen_tries = kFirstPassTries;
-        if (const char *env = getenv("TESSEL_EIGEN_TRIES")) {      // test knob: force candidates onto the deferred path
+        kp.retry_tries = kRetryTries;
+        if (const char *env = getenv("TESSEL_EIGEN_TRIES")) {      // test knobs: force candidates onto the longer search
             int v = atoi(env);
             if (v >= 0 && v <= 64) kp.eigen_tries = v;
+        }
+        if (const char *env = getenv("TESSEL_RETRY_TRIES")) {      // ... and from there to the general kernel
+            int v = atoi(env);
+            if (v >= 0 && v <= 64) kp.retry_tries = v;
         }
     }
     // candidate count and the tables of the exhaustive spaces

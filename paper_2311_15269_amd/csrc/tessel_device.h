@@ -105,7 +105,8 @@ struct KParams {
     uint32_t pred_bit[kMaxK];    // by code: step bit of the dependency from its producer (0 = first of its chain)
     uint32_t dep_bit[kMaxK];     // by dependency number: its step bit, 0 if both ends sit on the same device set
     uint32_t mpack[kMaxD];       // memory deltas of the device's 4 types, 8 bits each (signed)
-    int32_t  eigen_tries;        // sweeps of the first fast pass before a candidate is retried (test knob)
+    int32_t  eigen_tries;        // window sweeps a candidate gets at first, and
+    int32_t  retry_tries;        // ... from the start again when those found no eigenvector (both: test knobs)
     // blocks on several devices in the fast kernel: such a type has one code on every device it occupies
     int32_t  fast_tp;            // the problem has such blocks (the fast kernel then only builds; periods by the general kernel)
     int32_t  ntp;                // number of such types
@@ -125,10 +126,10 @@ struct DevResult {
     uint64_t n_evaluated;
     uint64_t n_status[kNumStatus];   // [kOk] = feasible
     uint64_t n_sweeps;               // window sweeps spent on period computations (fast kernel)
-    uint32_t n_retried;              // candidates that needed the second fast pass (more sweeps) so far
+    uint32_t n_retried;              // candidates that needed the longer eigenvector search so far
     uint32_t n_deferred;             // candidates handed to the general kernel so far
     uint32_t overflow;               // a list was too small at some point: results are incomplete
-    uint32_t retry_count;            // entries of the retry list of the launch in flight
+    uint32_t pad1;
     uint32_t defer_count;            // entries of the deferred list of the launch in flight
     uint32_t pad2;
 };
@@ -172,21 +173,19 @@ constexpr size_t kWsDetailOff = 256;
 constexpr size_t kWsParamsOff = 2048;          // KParams of the bound problem
 constexpr size_t kWsTablesOff = 8192;          // lead table, arrangement table
 constexpr size_t kWsTablesMax = 1 << 20;
-constexpr size_t kWsRetryOff = kWsTablesOff + kWsTablesMax;    // candidates that get a second fast pass with more sweeps
-constexpr uint32_t kWsRetryCap = 1u << 23;
-constexpr size_t kWsListOff = kWsRetryOff + (size_t)kWsRetryCap * 8;   // candidates deferred to the general kernel
+constexpr size_t kWsListOff = kWsTablesOff + kWsTablesMax;     // candidates deferred to the general kernel
 constexpr uint32_t kWsListCap = 1u << 20;
 constexpr size_t kWsCompParamsOff = kWsListOff + (size_t)kWsListCap * 8;   // CompParams
 constexpr size_t kWsBlockRecOff = kWsCompParamsOff + 1024;
 constexpr int kDeferBlocks = 64;                                // grid of the deferred pass
-constexpr int kFirstPassTries = 2;                              // sweeps before a candidate goes to the retry list
+constexpr int kFirstPassTries = 2;                              // sweeps before a candidate queues for the longer search
 constexpr uint64_t kMaxPerLaunch = 1ull << 26;                  // candidates per pass of the kernels
 constexpr uint64_t kSafePerLaunch = 1ull << 20;                 // ... at which no list can overflow (<= both list capacities)
 constexpr int kRetryTries = 8;                                  // ... and before the general kernel gets it
 
-// queues between the phases of the fast kernel: two rings per wave behind the block records
+// queues between the phases of the fast kernel: three rings per wave behind the block records
 constexpr uint32_t kRingSlots = 128;                            // a power of two >= 2 * 64 - 1
-constexpr int kRingMetaWords = 8;                               // ring 2: leads (4), index (2), peak (1), unused (1), then the program
+constexpr int kRingMetaWords = 8;                               // rings 2 and 3: leads (4), index (2), peak (1), unused (1), then the program
 constexpr int kStageMetaWords = 12;                             // ring 1: R, HM, X, worst, leads (4), index (2), unused (2), then
                                                                 // the device records (4 words each) and the program so far
 

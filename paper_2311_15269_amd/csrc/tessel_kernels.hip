@@ -32,7 +32,7 @@ namespace tessel {
 
 struct BlockRec {
     int32_t  period;
-    int32_t  pad;
+    uint32_t n_retried;          // candidates whose first sweeps found no eigenvector (they got more in the same launch)
     uint64_t index;
     uint32_t n_status[kNumStatus];
     uint32_t n_evaluated;
@@ -545,7 +545,7 @@ struct FastLds {
 // problem scalars, read once per workgroup
 template <int DM>
 struct FastConst {
-    int D, K, NR, M, total, nslots, npaths, nsweeps, space, has_fixed, nwords, ndeps, eigen_tries;
+    int D, K, NR, M, total, nslots, npaths, nsweeps, space, has_fixed, nwords, ndeps;
     uint32_t step_q16;
     uint64_t seed;
     int ntd[DM];
@@ -746,11 +746,11 @@ __device__ __forceinline__ void reset_sweep_state(const FastConst<DM> &C, const 
 // (device free times, in-flight micro-batch end times).  If after some sweep every live component
 // has grown by the same delta, x is an eigenvector of F and delta is its eigenvalue = the maximum
 // cycle ratio, exactly.  Almost every candidate gets there within two or three sweeps; one that has
-// not after the sweeps this pass allows (C.eigen_tries) is handed on: to a second pass of this kernel
-// with more sweeps, then to the general kernel (Karp's formula).
+// not after the sweeps allowed (`tries`) is handed on by the caller: to a queue of candidates that get more
+// sweeps, from there to the general kernel (Karp's formula).
 template <int DM, int VM, bool TP>
 __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds &L, const FastProgram &prog, int lane,
-                                           const Mu &lead_code, bool want,
+                                           const Mu &lead_code, bool want, int tries,
                                            uint32_t &nsweeps_used)
 {
     const int V = C.nsweeps - 1;
@@ -775,7 +775,7 @@ __device__ __forceinline__ int period_fast(const FastConst<DM> &C, const FastLds
     for (int v = 0; v < VM; v++) prev[v] = 0;
     int T = 0;
     bool done = !want;
-    for (int j = 0; j < C.eigen_tries; j++) {
+    for (int j = 0; j < tries; j++) {
         if (__ballot(!done) == 0) break;
         sweep_fast<DM, TP>(C, L, prog, lane, lead_code, !done);
         nsweeps_used += done ? 0u : 1u;
@@ -989,7 +989,7 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
     auto word = [&](int wi) -> uint32_t {
         uint32_t acc = 0;
         const int nj = __builtin_amdgcn_readfirstlane(min(6, total - wi * 6));
-#pragma unroll 1
+#pragma unroll 2
         for (int j = 0; j < nj; j++) {
             uint32_t hm = R & HM;
             if (TP)
@@ -1025,8 +1025,11 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
             const uint32_t rest = __builtin_amdgcn_bitop3_b32(__builtin_amdgcn_bitop3_b32(alive, a.x, ly, 0x90), a.y, hy, 0x90);
             const uint32_t more = (a.w >> (4u * y)) & 14u;                    // two or more were waiting
             const uint32_t onec = 1u << c;
-            const uint32_t x_new = X | (rest == 0 ? onec : 0u);
-            const uint32_t r_new = (R & ~onec) | (min(rest, more) != 0 ? onec : 0u) | (e.y & ~x_new);
+            // exhausted: no entry of the type is left; it stays runnable only if entries are left and another
+            // micro-batch waits
+            const bool exhausted = rest == 0, stalled = exhausted | (more == 0);
+            const uint32_t x_new = X | (exhausted ? onec : 0u);
+            const uint32_t r_new = __builtin_amdgcn_bitop3_b32(R, stalled ? onec : 0u, e.y & ~x_new, 0xBA);      // (R & ~t) | z
             // the record's last word: waiting counts (16 bits) and the device's memory prefix (upper 16 bits,
             // signed); one sum updates both
             const uint32_t w_new = a.w + e.x;
@@ -1035,7 +1038,9 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
             if (active) {
                 rp->z = alive;
                 rp->w = w_new;
-                if (e.z != 0xFFFFFFFFu) atomicAdd((uint32_t *)((char *)L.rec + e.z) + 4 * lane, e.w);
+                // (without blocks on several devices every table entry names a word: a type without a consumer on
+                // another device adds 0 to its own record)
+                if (!TP || e.z != 0xFFFFFFFFu) atomicAdd((uint32_t *)((char *)L.rec + e.z) + 4 * lane, e.w);
                 worst = max(worst, (int)w_new >> 16);
                 // the program names a type by its code on its lowest device
                 acc |= (TP ? (uint32_t)__builtin_ctz(L.grp_tab[c]) : c) << (5 * j);
@@ -1110,14 +1115,11 @@ __device__ __forceinline__ int build_end(const FastConst<DM> &C, const BuildStat
 template <int DM, int VM, int MODE, bool TP = false>
 __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
                                                           BlockRec *__restrict__ recs, int32_t *__restrict__ code_out,
-                                                          int32_t *__restrict__ peak_out, const uint64_t *__restrict__ in_list,
-                                                          const uint32_t *__restrict__ in_count, uint32_t in_cap, int tries,
+                                                          int32_t *__restrict__ peak_out, int tries, int retry_tries,
                                                           uint64_t *__restrict__ out_list, uint32_t *__restrict__ out_count,
                                                           uint32_t out_cap, uint32_t *__restrict__ overflow, uint32_t *ring_base,
                                                           uint32_t ring_words, int stage_words)
 {
-    // with an input list: score the listed candidates (all inside [first, first + count)) instead of the range
-    if (in_list) count = min(*in_count, in_cap);
     extern __shared__ uint32_t lds[];
     // the sweeps address their tables by LDS byte address from 0: the kernel has no other LDS in front of this array
     if (lds_address(lds) != 0u) { if (threadIdx.x == 0) *overflow = 0x100u; return; }
@@ -1155,11 +1157,13 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
             if (TP && ((P.slow_mask >> lane) & 1u))
                 // a type on several devices, or with such a consumer: the step's slow path does the consumer's part
                 L.type_tab[lane] = make_uint4(((uint32_t)m << 16) - (1u << (4u * y)), has_su ? P.grp_code[su & 31u] : 0u,
-                                              0xFFFFFFFFu, (uint32_t)m);
+                                                              0xFFFFFFFFu, (uint32_t)m);
             else
                 L.type_tab[lane] = make_uint4(((uint32_t)m << 16) - (1u << (4u * y)) + (same ? inc : 0u),
                                               has_su ? 1u << (su & 31u) : 0u,
-                                              has_su && !same ? (su >> 2) * (kWave * 16u) + 12u : 0xFFFFFFFFu, inc);
+                                              has_su && !same ? (su >> 2) * (kWave * 16u) + 12u
+                                                              : TP ? 0xFFFFFFFFu : (dev < (uint32_t)DM ? dev : 0u) * (kWave * 16u) + 12u,
+                                              has_su && !same ? inc : 0u);
         }
         {
             // codes no block type has: device 0, chain 0, t = 0 (the pipeline of the sweeps reads code 0 past the end)
@@ -1176,7 +1180,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     __syncthreads();
     FastConst<DM> C;
     C.D = P.D; C.K = P.K; C.NR = P.NR; C.M = P.M; C.total = P.total; C.nslots = P.nslots; C.npaths = P.npaths;
-    C.nsweeps = P.nsweeps; C.space = P.space; C.has_fixed = P.has_fixed; C.nwords = (P.total + 5) / 6; C.ndeps = P.K - P.npaths; C.eigen_tries = tries;
+    C.nsweeps = P.nsweeps; C.space = P.space; C.has_fixed = P.has_fixed; C.nwords = (P.total + 5) / 6; C.ndeps = P.K - P.npaths;
     C.step_q16 = P.step_q16; C.seed = P.seed;
 #pragma unroll
     for (int d = 0; d < DM; d++) { C.ntd[d] = P.ntd[d]; C.mpack[d] = P.mpack[d]; }
@@ -1201,8 +1205,12 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     // A survivor of A appends its state (masks, records, program so far) to ring 1 of this wave in global memory,
     // a survivor of B program and leads to ring 2; B and C run whenever 64 candidates wait in their ring, one per
     // lane.  Ring layout: [word][slot]; slot = ring tail + rank of the lane among the survivors.
-    uint32_t *ring1 = ring_base + (size_t)blockIdx.x * 2u * ring_words, *ring2 = ring1 + ring_words;
-    uint32_t head1 = 0, count1 = 0, head2 = 0, count2 = 0;           // wave-uniform
+    // A candidate whose boundary vector is no eigenvector yet after the `tries` sweeps of C goes, with its program, to
+    // ring 3 and gets up to `retry_tries` sweeps from the start when 64 of them wait there (a wave sweeps until its
+    // slowest lane is done: a straggler among 63 finished lanes would cost a whole sweep of the wave).  What is still
+    // open then is appended to the list of the general kernel.
+    uint32_t *ring1 = ring_base + (size_t)blockIdx.x * 3u * ring_words, *ring2 = ring1 + ring_words, *ring3 = ring2 + ring_words;
+    uint32_t head1 = 0, count1 = 0, head2 = 0, count2 = 0, head3 = 0, count3 = 0, nretry = 0;           // wave-uniform
     const int nwords = C.nwords;
     const bool split = stage_words < nwords;                         // tiny windows: A builds all of it
     const int wordsA = split ? stage_words : nwords;
@@ -1226,11 +1234,11 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
             if (peak_out) peak_out[idx - first] = status == kMem ? pk : 0;
         }
     };
-    auto push_program = [&](bool ok, uint64_t idx, int pk, const FastProgram &prog) {
+    auto push_program = [&](bool ok, uint64_t idx, int pk, const FastProgram &prog, uint32_t *ring, uint32_t tail) -> uint32_t {
         const uint64_t okm = __ballot(ok);
-        if (okm == 0) return;
+        if (okm == 0) return 0u;
         if (ok) {
-            uint32_t *dst = ring2 + ((head2 + count2 + rank_in(okm)) & (kRingSlots - 1u));
+            uint32_t *dst = ring + ((tail + rank_in(okm)) & (kRingSlots - 1u));
             dst[0 * kRingSlots] = (uint32_t)lead_code.lo; dst[1 * kRingSlots] = (uint32_t)(lead_code.lo >> 32);
             dst[2 * kRingSlots] = (uint32_t)lead_code.hi; dst[3 * kRingSlots] = (uint32_t)(lead_code.hi >> 32);
             dst[4 * kRingSlots] = (uint32_t)idx; dst[5 * kRingSlots] = (uint32_t)(idx >> 32);
@@ -1242,13 +1250,13 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
                     for (int w = 4 * c4; w < 4 * c4 + 4; w++) dst[(kRingMetaWords + w) * kRingSlots] = prog.get(w);
                 }
         }
-        count2 += (uint32_t)__builtin_popcountll(okm);
+        return (uint32_t)__builtin_popcountll(okm);
     };
-    // phase C on the first n candidates of ring 2
-    auto sweep_from_ring = [&](uint32_t n) {
+    // phase C on the first n candidates of ring 2, or (`again`) of ring 3
+    auto sweep_from_ring = [&](uint32_t n, bool again) {
         __threadfence_block();         // the stores of this wave's other lanes must be visible to the loads below
         const bool have = (uint32_t)lane < n;
-        const uint32_t *src = ring2 + ((head2 + (uint32_t)lane) & (kRingSlots - 1u));
+        const uint32_t *src = (again ? ring3 : ring2) + (((again ? head3 : head2) + (uint32_t)lane) & (kRingSlots - 1u));
         // every lane loads (a lane without a candidate reads a slot behind the last one: stale words, results dropped)
         FastProgram prog;
         lead_code.lo = (uint64_t)src[0 * kRingSlots] | ((uint64_t)src[1 * kRingSlots] << 32);
@@ -1261,11 +1269,14 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
 #pragma unroll
                 for (int w = 4 * c4; w < 4 * c4 + 4; w++) prog.set(w, src[(kRingMetaWords + w) * kRingSlots]);
             }
-        head2 = (head2 + n) & (kRingSlots - 1u);
-        count2 -= n;
-        const int T = period_fast<DM, VM, TP>(C, L, prog, lane, lead_code, have, nsw);
-        if (have && T < 0) {
-            // no eigenvector within the sweeps of this pass: the next pass scores it
+        if (again) { head3 = (head3 + n) & (kRingSlots - 1u); count3 -= n; }
+        else { head2 = (head2 + n) & (kRingSlots - 1u); count2 -= n; }
+        const int T = period_fast<DM, VM, TP>(C, L, prog, lane, lead_code, have, again ? retry_tries : tries, nsw);
+        const bool open = have && T < 0;                  // no eigenvector within the sweeps allowed
+        if (!again) {
+            const uint32_t k = push_program(open, idx, pk, prog, ring3, head3 + count3);
+            count3 += k; nretry += k;
+        } else if (open) {
             const uint32_t at = atomicAdd(out_count, 1u);
             if (at < out_cap) out_list[at] = idx; else *overflow = 1u;
         }
@@ -1284,7 +1295,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
         int pk;
         const int status = build_end<DM>(C, S, pk);
         reject(have && status != kOk, idx, status, pk);
-        push_program(have && status == kOk, idx, pk, prog);
+        count2 += push_program(have && status == kOk, idx, pk, prog, ring2, head2 + count2);
     };
     // phase B on the first n candidates of ring 1
     auto build_from_ring = [&](uint32_t n) {
@@ -1320,7 +1331,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     auto build_new = [&](uint64_t r) {
         const uint64_t kk = r * stride + (uint64_t)blockIdx.x * kWave + lane;
         const bool valid = kk < count;
-        const uint64_t idx = !valid ? first : in_list ? in_list[kk] : first + kk;
+        const uint64_t idx = valid ? first + kk : first;
         build_begin<DM, MODE, TP>(P, C, idx, L, lane, lead_code, S);
         FastProgram prog;
         build_words<DM, MODE, TP>(P, C, L, lane, valid, 0, wordsA, prog, S);
@@ -1357,7 +1368,10 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     // when the wave's share is used up the rings are drained on partial waves.  Every condition is wave-uniform.
     for (uint64_t r = 0;;) {
         const bool fresh = r < rounds;
-        if (count2 >= (uint32_t)kWave || (!fresh && count1 == 0 && count2 > 0)) sweep_from_ring(min(count2, (uint32_t)kWave));
+        // (one call for both rings of programs, so that the sweeps exist once in the code)
+        const bool again = count3 >= (uint32_t)kWave || (!fresh && count1 == 0 && count2 == 0 && count3 > 0);
+        const bool sweep = again || count2 >= (uint32_t)kWave || (!fresh && count1 == 0 && count2 > 0);
+        if (sweep) sweep_from_ring(min(again ? count3 : count2, (uint32_t)kWave), again);
         else if (count1 >= (uint32_t)kWave || (!fresh && count1 > 0)) build_from_ring(min(count1, (uint32_t)kWave));
         else if (fresh) build_new(r++);
         else break;
@@ -1373,7 +1387,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     }
     if (lane == 0) {
         BlockRec rr;
-        rr.period = best; rr.pad = 0; rr.index = best_idx; rr.n_evaluated = nev; rr.n_sweeps = nsw;
+        rr.period = best; rr.n_retried = nretry; rr.index = best_idx; rr.n_evaluated = nev; rr.n_sweeps = nsw;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) rr.n_status[s] = cnt[s];
         recs[blockIdx.x] = rr;
@@ -1447,7 +1461,7 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
     }
     if (lane == 0) {
         BlockRec r;
-        r.period = best; r.pad = 0; r.index = best_idx; r.n_evaluated = nev; r.n_sweeps = 0;
+        r.period = best; r.n_retried = 0; r.index = best_idx; r.n_evaluated = nev; r.n_sweeps = 0;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) r.n_status[s] = cnt[s];
         recs[blockIdx.x] = r;
@@ -1460,10 +1474,12 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
     const int lane = threadIdx.x;
     int best = INT_MAX;
     uint64_t best_idx = 0, nev = 0, nsw = 0, cnt[kNumStatus];
+    uint32_t nre = 0;
 #pragma unroll
     for (int s = 0; s < kNumStatus; s++) cnt[s] = 0;
     for (int k = lane; k < nrecs; k += kWave) {
         BlockRec r = recs[k];
+        nre += r.n_retried;
         if (key_less(r.period, r.index, best, best_idx)) { best = r.period; best_idx = r.index; }
         nev += r.n_evaluated;
         nsw += r.n_sweeps;
@@ -1480,6 +1496,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
         nev += ((uint64_t)hi << 32) | lo;
         uint32_t slo = __shfl_xor((uint32_t)nsw, off), shi = __shfl_xor((uint32_t)(nsw >> 32), off);
         nsw += ((uint64_t)shi << 32) | slo;
+        nre += __shfl_xor(nre, off);
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) {
             uint32_t l2 = __shfl_xor((uint32_t)cnt[s], off), h2 = __shfl_xor((uint32_t)(cnt[s] >> 32), off);
@@ -1488,10 +1505,10 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
     }
     if (lane == 0) {
         if (key_less(best, best_idx, res->period, res->index)) { res->period = best; res->index = best_idx; }
-        // the passes over both lists have run (stream order)
-        res->n_retried += min(res->retry_count, kWsRetryCap);
+        // the pass over the list of deferred candidates has run (stream order)
+        res->n_retried += nre;
         res->n_deferred += min(res->defer_count, kWsListCap);
-        res->retry_count = 0; res->defer_count = 0;
+        res->defer_count = 0;
         res->n_evaluated += nev;
         res->n_sweeps += nsw;
 #pragma unroll
@@ -1502,14 +1519,14 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
 // only the counter of the deferred list (after a per-candidate scoring call)
 __global__ void clear_defer_kernel(DevResult *res)
 {
-    if (threadIdx.x == 0 && blockIdx.x == 0) { res->retry_count = 0; res->defer_count = 0; }
+    if (threadIdx.x == 0 && blockIdx.x == 0) res->defer_count = 0;
 }
 
 __global__ void reset_kernel(DevResult *res)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         res->period = INT_MAX; res->pad = 0; res->index = ~0ull; res->n_evaluated = 0; res->n_sweeps = 0;
-        res->n_retried = 0; res->n_deferred = 0; res->overflow = 0; res->retry_count = 0; res->defer_count = 0;
+        res->n_retried = 0; res->n_deferred = 0; res->overflow = 0; res->defer_count = 0;
         for (int s = 0; s < kNumStatus; s++) res->n_status[s] = 0;
     }
 }
@@ -1517,8 +1534,8 @@ __global__ void reset_kernel(DevResult *res)
 // ------------------------------------------------------------------ launchers
 typedef void (*eval_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, DevDetail *, const uint64_t *,
                         const uint32_t *);
-typedef void (*fast_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, const uint64_t *, const uint32_t *,
-                        uint32_t, int, uint64_t *, uint32_t *, uint32_t, uint32_t *, uint32_t *, uint32_t, int);
+typedef void (*fast_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, int, int, uint64_t *, uint32_t *,
+                        uint32_t, uint32_t *, uint32_t *, uint32_t, int);
 
 static eval_fn pick_kernel(const KParams &kp)
 {
@@ -1616,15 +1633,18 @@ static uint32_t ring_words(const KParams &kp)
     return (uint32_t)(program > stage ? program : stage) * kRingSlots;
 }
 
-static size_t ring_offset(int blocks)
+// behind the records of one launch: one per workgroup of the scoring kernels, or one (smaller) per workgroup of the
+// completion search, whose grid is 16 workgroups per compute unit at most
+static size_t ring_offset(int blocks, int num_cus)
 {
-    return (kWsBlockRecOff + (size_t)(2 * blocks + kDeferBlocks) * sizeof(BlockRec) + 256 + 255) & ~(size_t)255;
+    const size_t eval = (size_t)(blocks + kDeferBlocks) * sizeof(BlockRec), comp = (size_t)num_cus * 16 * sizeof(CompRec);
+    return (kWsBlockRecOff + (eval > comp ? eval : comp) + 256 + 255) & ~(size_t)255;
 }
 
 size_t eval_workspace_bytes(const KParams &kp, int num_cus)
 {
     const LaunchShape s = eval_launch_shape(kp, num_cus);
-    return ring_offset(s.blocks) + (pick_fast(kp) ? (size_t)s.blocks * 2 * ring_words(kp) * 4 : 0);
+    return ring_offset(s.blocks, num_cus) + (pick_fast(kp) ? (size_t)s.blocks * 3 * ring_words(kp) * 4 : 0);
 }
 
 static int launch_general(const KParams &kp, const KParams *kp_dev, uint64_t first, uint64_t count, int blocks, BlockRec *recs,
@@ -1641,16 +1661,15 @@ static int launch_general(const KParams &kp, const KParams *kp_dev, uint64_t fir
     return (int)hipGetLastError();
 }
 
-// Scores [first, first+count).  Where the problem allows it: the fast kernel with a short eigenvector search, the fast
-// kernel again with a longer one over the candidates that did not converge, then the general kernel over what is left
-// (next to nothing).  Otherwise the general kernel alone.  Returns the number of block records written (recs may be
+// Scores [first, first+count).  Where the problem allows it: the fast kernel (a short eigenvector search, a longer one
+// for the candidates that did not converge), then the general kernel over what it could not finish (next to nothing).  Otherwise the general kernel alone.  Returns the number of block records written (recs may be
 // null: per-candidate outputs only) or a negative HIP error.
 static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, BlockRec *recs, int32_t *code,
                        int32_t *peak, bool general, hipStream_t st)
 {
     const KParams *kp_dev = (const KParams *)((char *)ws + kWsParamsOff);
     DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
-    uint64_t *retry = (uint64_t *)((char *)ws + kWsRetryOff), *list = (uint64_t *)((char *)ws + kWsListOff);
+    uint64_t *list = (uint64_t *)((char *)ws + kWsListOff);
     LaunchShape s = eval_launch_shape(kp, num_cus);
     uint64_t need = (count + kWave - 1) / kWave;
     const int blocks = need < (uint64_t)s.blocks ? (int)need : s.blocks;
@@ -1661,24 +1680,14 @@ static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *
         return rc ? -rc : blocks;
     }
     const size_t lds = fast_lds_bytes(kp);
-    uint32_t *ring = (uint32_t *)((char *)ws + ring_offset(s.blocks));
-    const uint32_t rw = ring_words(kp);
-    const int sw = stage_words(kp);
-    hipLaunchKernelGGL(ff, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, (const uint64_t *)nullptr,
-                       (const uint32_t *)nullptr, 0u, kp.eigen_tries, retry, &res->retry_count, kWsRetryCap, &res->overflow, ring, rw, sw);
+    uint32_t *ring = (uint32_t *)((char *)ws + ring_offset(s.blocks, num_cus));
+    hipLaunchKernelGGL(ff, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, kp.eigen_tries, kp.retry_tries,
+                       list, &res->defer_count, kWsListCap, &res->overflow, ring, ring_words(kp), stage_words(kp));
     int rc = (int)hipGetLastError();
     if (rc) return -rc;
-    // the retry list holds a few percent of the range, still the whole grid: one wave per SIMD would leave the
-    // pass bound by latency (measured: a quarter of the grid costs 3 % of the whole launch more)
-    const int blocks2 = blocks;
-    hipLaunchKernelGGL(ff, dim3(blocks2), dim3(kWave), lds, st, kp_dev, first, count, recs ? recs + blocks : nullptr, code, peak,
-                       (const uint64_t *)retry, (const uint32_t *)&res->retry_count, kWsRetryCap, kRetryTries, list,
-                       &res->defer_count, kWsListCap, &res->overflow, ring, rw, sw);
-    rc = (int)hipGetLastError();
-    if (rc) return -rc;
-    rc = launch_general(kp, kp_dev, first, count, kDeferBlocks, recs ? recs + blocks + blocks2 : nullptr, code, peak, nullptr, list,
+    rc = launch_general(kp, kp_dev, first, count, kDeferBlocks, recs ? recs + blocks : nullptr, code, peak, nullptr, list,
                         &res->defer_count, st);
-    return rc ? -rc : blocks + blocks2 + kDeferBlocks;
+    return rc ? -rc : blocks + kDeferBlocks;
 }
 
 int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream, uint64_t max_piece)

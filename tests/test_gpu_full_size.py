@@ -110,20 +110,23 @@ def test_fast_and_general_kernels_agree(gpu, monkeypatch):
 
 
 def test_deferred_candidates_take_the_general_kernel(gpu, monkeypatch):
-    """A candidate whose boundary vector is no eigenvector yet after the sweeps of the first pass goes
-    through a list in the workspace to a second pass with more sweeps (and from there, if need be, to
-    the general kernel).  With the first pass cut to 1 or 0 sweeps all feasible candidates go that
-    way; results must not change."""
+    """A candidate whose boundary vector is no eigenvector yet after its first sweeps queues inside the kernel for
+    a longer search (from the start again), and what that leaves open goes through a list in the workspace to the
+    general kernel.  With the first search cut to 1 or 0 sweeps all feasible candidates take the queue; with the
+    longer one cut as well all of them reach the general kernel; results must not change."""
     from oracle import Oracle
-    for tries, cfg, n in ((2, 5, 20000), (1, 3, 30000), (0, 1, 576), (1, 2, 300000), (0, 5, 5000)):
+    for tries, retry, cfg, n in ((2, 8, 5, 20000), (1, 8, 3, 30000), (0, 0, 1, 576), (1, 1, 2, 300000), (0, 8, 5, 5000),
+                                 (0, 0, 5, 3000), (2, 0, 3, 30000)):
         prob = W.CONFIGS[cfg]()
         monkeypatch.setenv("TESSEL_EIGEN_TRIES", str(tries))
+        monkeypatch.setenv("TESSEL_RETRY_TRIES", str(retry))
         g = gpu.Problem(prob)
         monkeypatch.delenv("TESSEL_EIGEN_TRIES")
+        monkeypatch.delenv("TESSEL_RETRY_TRIES")
         first = 4321 if cfg in (3, 5) else 0
         code, peak = g.score_candidates(first, n)
         want_code, want_peak = Oracle(prob).score_range(first, n)
-        assert (code.cpu().numpy() == want_code).all() and (peak.cpu().numpy() == want_peak).all(), (tries, cfg)
+        assert (code.cpu().numpy() == want_code).all() and (peak.cpu().numpy() == want_peak).all(), (tries, retry, cfg)
         for pieces in ([(first, n)], [(first, n // 2), (first + n // 2, n - n // 2)]):
             g.reset()
             for a, k in pieces:
@@ -136,22 +139,24 @@ def test_deferred_candidates_take_the_general_kernel(gpu, monkeypatch):
 
 
 def test_list_overflow_is_recovered(gpu, monkeypatch):
-    """More unfinished candidates in one launch than the retry list holds must not be dropped: the ranges are
-    scored again in smaller pieces and the result equals the ordinary one."""
+    """More unfinished candidates in one launch than the list of the general kernel holds must not be dropped: the
+    ranges are scored again in smaller pieces and the result equals the ordinary one."""
     prob = dict(W.config3(), M=100)                   # every candidate feasible
     want_g = gpu.Problem(prob)
-    want_g.eval_candidates(0, 1 << 24)
+    want_g.eval_candidates(0, 1 << 22)
     want_g.eval_candidates(1 << 25, 1000)
     want = want_g.best()
-    monkeypatch.setenv("TESSEL_EIGEN_TRIES", "0")     # and every one unfinished after the first pass
+    monkeypatch.setenv("TESSEL_EIGEN_TRIES", "0")     # and every one left to the general kernel
+    monkeypatch.setenv("TESSEL_RETRY_TRIES", "0")
     g = gpu.Problem(prob)
     monkeypatch.delenv("TESSEL_EIGEN_TRIES")
-    g.eval_candidates(0, 1 << 24)                     # the retry list holds 2^23
+    monkeypatch.delenv("TESSEL_RETRY_TRIES")
+    g.eval_candidates(0, 1 << 22)                     # the list holds 2^20
     g.eval_candidates(1 << 25, 1000)
     got = g.best()
     for key in ("period", "index", "peak", "n_evaluated", "n_feasible", "n_reject"):
         assert got[key] == want[key], key
-    assert got["n_evaluated"] == (1 << 24) + 1000
+    assert got["n_evaluated"] == (1 << 22) + 1000
     g.reset()
     g.eval_candidates(0, 1 << 15)
     assert g.best()["n_evaluated"] == 1 << 15
