@@ -527,7 +527,8 @@ struct FastLds {
                           //      micro-batch of the type less, one more for its consumer if that sits on the same device
                           //   y: one-hot mask of the consumer's code (0: none)
                           //   z: consumer on another device: byte offset of the last word of that device's records
-                          //      (lane 0) from the start of the records; 0xFFFFFFFF otherwise
+                          //      (lane 0) from the start of the records; otherwise, TP variants: 0xFFFFFFFF, else the
+                          //      type's own device (w is 0 then).  Not TP: 4 * symbol of the type in bits 16-19
                           //   w: the increment of that word (one waiting micro-batch of the consumer)
     uint32_t *chain_tab;  // [32]  KParams::chain_tab
     uint32_t *vtab;       // [32]  KParams::vtab
@@ -1010,8 +1011,9 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
             const uint32_t p = low_bit(a.z & gate);
             // its symbol, as two all-or-nothing masks
             const uint32_t ly = (uint32_t)__builtin_amdgcn_sbfe((int)a.x, p, 1), hy = (uint32_t)__builtin_amdgcn_sbfe((int)a.y, p, 1);
-            const uint32_t y = (ly & 1u) | (hy & 2u);
-            const uint32_t c = d4 + y;
+            // c = d4 + y with y = (ly & 1) | (hy & 2): ly, hy are 0 or -1, so c = d4 - ly - 2 hy
+            uint32_t c;
+            asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(c) : "v"(hy), "v"(d4 - ly));
             const uint4 e = L.type_tab[c];
             // take the entry out; new head of the device.  (When the device is empty now the bit set below is
             // meaningless, and harmless: all its types are exhausted, and R never holds an exhausted type.)
@@ -1023,12 +1025,14 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
             // entries of it remain; its consumer gets one more and becomes runnable
             // remaining entries of the same type: alive & ~(lo ^ ly) & ~(hi ^ hy)
             const uint32_t rest = __builtin_amdgcn_bitop3_b32(__builtin_amdgcn_bitop3_b32(alive, a.x, ly, 0x90), a.y, hy, 0x90);
-            const uint32_t more = (a.w >> (4u * y)) & 14u;                    // two or more were waiting
+            // two or more were waiting (the shift, 4 * symbol, comes with the table entry where no type sits on several devices)
+            const uint32_t more = (a.w >> (TP ? 4u * (c & 3u) : e.z >> 16)) & 14u;
             const uint32_t onec = 1u << c;
             // exhausted: no entry of the type is left; it stays runnable only if entries are left and another
             // micro-batch waits
             const bool exhausted = rest == 0, stalled = exhausted | (more == 0);
-            const uint32_t x_new = X | (exhausted ? onec : 0u);
+            uint32_t x_new = X | (exhausted ? onec : 0u);
+            TESSEL_PIN(x_new);          // (the old X dies here: no second copy of the mask across the step)
             const uint32_t r_new = __builtin_amdgcn_bitop3_b32(R, stalled ? onec : 0u, e.y & ~x_new, 0xBA);      // (R & ~t) | z
             // the record's last word: waiting counts (16 bits) and the device's memory prefix (upper 16 bits,
             // signed); one sum updates both
@@ -1040,7 +1044,8 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
                 rp->w = w_new;
                 // (without blocks on several devices every table entry names a word: a type without a consumer on
                 // another device adds 0 to its own record)
-                if (!TP || e.z != 0xFFFFFFFFu) atomicAdd((uint32_t *)((char *)L.rec + e.z) + 4 * lane, e.w);
+                if (!TP) atomicAdd((uint32_t *)((char *)L.rec + (e.z & 0xFFFFu)) + 4 * lane, e.w);
+                else if (e.z != 0xFFFFFFFFu) atomicAdd((uint32_t *)((char *)L.rec + e.z) + 4 * lane, e.w);
                 worst = max(worst, (int)w_new >> 16);
                 // the program names a type by its code on its lowest device
                 acc |= (TP ? (uint32_t)__builtin_ctz(L.grp_tab[c]) : c) << (5 * j);
@@ -1161,8 +1166,8 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
             else
                 L.type_tab[lane] = make_uint4(((uint32_t)m << 16) - (1u << (4u * y)) + (same ? inc : 0u),
                                               has_su ? 1u << (su & 31u) : 0u,
-                                              has_su && !same ? (su >> 2) * (kWave * 16u) + 12u
-                                                              : TP ? 0xFFFFFFFFu : (dev < (uint32_t)DM ? dev : 0u) * (kWave * 16u) + 12u,
+                                              has_su && !same ? (su >> 2) * (kWave * 16u) + 12u + (TP ? 0u : y << 18)
+                                                              : TP ? 0xFFFFFFFFu : (dev < (uint32_t)DM ? dev : 0u) * (kWave * 16u) + 12u + (y << 18),
                                               has_su && !same ? inc : 0u);
         }
         {
