@@ -514,12 +514,14 @@ struct FastProgram {
 };
 
 constexpr int kFastTableWords = 16 * kMaxK;      // uniform tables at the start of the fast kernel's LDS
-constexpr int kSweepTabWord = 13 * kMaxK;        // ... of which the sweeps' table by code (and the chains' behind it)
+constexpr int kSweepTabWord = 12 * kMaxK;        // ... of which the sweeps' three tables by code; a multiple of 64 words, so
+                                                 // that one two-address LDS read fetches a code's first and third word
 
 struct FastLds {
     uint32_t *sw_tab;     // [32]  by code, for the sweeps of problems without blocks on several devices:
                           //       t << 16 | LDS address of the time of the code's device (lane 0)
     uint32_t *ch_tab;     // [32]  by code, right behind sw_tab: LDS address of the first token of the code's chain (lane 0)
+    uint32_t *in_tab;     // [32]  by code, behind ch_tab: 1 << s | s, s = 16 + 4 * symbol: counter increment and field position
     uint4 *tt_tab;        // [32]  by code, for the sweeps of the TP variants: x: t, y: byte offset of the first token slot of the code's
                           //       chain, z: byte offset of its device's words, w: bit offset of its micro-batch counter
     uint4 *type_tab;      // [32]  by code, what placing one block of the type does:
@@ -539,7 +541,7 @@ struct FastLds {
                           //           | memory now (signed) << 16
     // sweeps: three arrays [slot][64] in a row at distances known at compile time
     uint32_t *dfree;      // [DM] time at which the device is free
-    uint32_t *dcnt;       // [DM] next micro-batch of the device's 4 types (4 bits each)
+    uint32_t *dcnt;       // [DM] next micro-batch of the device's 4 types (4 bits each, in the upper half of the word)
     uint32_t *tok;        // [token slots] end time of the micro-batch's latest block
 };
 
@@ -634,8 +636,10 @@ __device__ __forceinline__ uint32_t lds_fetch_add(uint32_t a, uint32_t v)
 // replaced by block k's end time (two compares, two selects).  LDS keeps a wave's accesses in order, so W(k - 1) and
 // everything older is seen.
 // Table word of a code: t << 16 | LDS address of its device's time (lane 0); with several chains (MC) a second
-// table holds the LDS address of the chain's first token (lane 0).  The counter shift 4 * symbol is the low bits
-// of the table address (the table is 16-byte aligned).
+// table holds the LDS address of the chain's first token (lane 0).  A device's counter word holds the next micro-batch
+// of its four types in its upper half, four bits each; the third table word of a code, 1 << s | s with s = 16 +
+// 4 * symbol, is both the increment of the atomic (the low half of the counter word only collects the s, below 2^16
+// over a window) and, by its low five bits, the position of the field.
 // Past the last block the stages T, A and R run on code 0 (a counter that the window boundary resets anyway, reads
 // inside the arrays); stage W does not.
 template <int DM, bool MC>
@@ -644,28 +648,28 @@ __device__ __forceinline__ void sweep_blocks(const FastConst<DM> &C, const FastL
     const int total = C.total, nfull = total / 6, tail = total - 6 * nfull;
     constexpr uint32_t tab = kSweepTabWord * 4u;                // the kernel's LDS starts at address 0 (checked at its start)
     const uint32_t lane_tok = lds_address(L.dfree) + 2u * DM * kWave * 4u + lane4;
-    struct Tst { uint32_t tt, sh, ch; };                        // T done
-    struct Ast { uint32_t tt, fa, sh, cnt, ch; };               // A done
+    struct Tst { uint32_t tt, w2, ch; };                        // T done
+    struct Ast { uint32_t tt, fa, w2, cnt, ch; };               // A done
     struct Rst { uint32_t tt, fa, ta, fr, tk; };                // R done
     auto stage_t = [&](uint32_t w, int pos) -> Tst {
         Tst o;
         const uint32_t c4 = (pos == 0 ? w << 2 : w >> (5 * pos - 2)) & 0x7Cu;
-        o.sh = c4 & 0xCu;
         o.tt = lds_load(c4 + tab);
+        o.w2 = lds_load(c4 + tab + 2u * kMaxK * 4u);
         o.ch = MC ? lds_load(c4 + tab + kMaxK * 4u) : 0u;
         return o;
     };
     auto stage_a = [&](const Tst &x) -> Ast {
         Ast o;
-        o.tt = x.tt; o.ch = x.ch; o.sh = x.sh;
+        o.tt = x.tt; o.ch = x.ch; o.w2 = x.w2;
         o.fa = (x.tt & 0xFFFFu) + lane4;
-        o.cnt = lds_fetch_add(o.fa + DM * kWave * 4u, 1u << x.sh);
+        o.cnt = lds_fetch_add(o.fa + DM * kWave * 4u, x.w2);
         return o;
     };
     auto stage_r = [&](const Ast &x) -> Rst {
         Rst o;
         o.tt = x.tt; o.fa = x.fa;
-        const uint32_t mu = __builtin_amdgcn_ubfe(x.cnt, x.sh, 4);
+        const uint32_t mu = __builtin_amdgcn_ubfe(x.cnt, x.w2, 4);      // (the offset is the low five bits of w2)
         o.ta = MC ? (mu << 8) + lane4 + x.ch : (mu << 8) + lane_tok;
         o.fr = lds_load(x.fa);
         o.tk = lds_load(o.ta);
@@ -730,7 +734,7 @@ __device__ __forceinline__ void sweep_fast(const FastConst<DM> &C, const FastLds
         }
 #pragma unroll
     for (int d = 0; d < DM; d++)
-        if (d < C.D) L.dcnt[d * kWave + lane] = (uint32_t)((d < 4 ? lead_code.lo : lead_code.hi) >> (16 * (d & 3))) & 0xFFFFu;
+        if (d < C.D) L.dcnt[d * kWave + lane] = (uint32_t)((d < 4 ? lead_code.lo : lead_code.hi) >> (16 * (d & 3))) << 16;
 }
 
 template <int DM>
@@ -740,7 +744,7 @@ __device__ __forceinline__ void reset_sweep_state(const FastConst<DM> &C, const 
     for (int s = 0; s < C.nslots - C.D; s++) L.tok[s * kWave + lane] = 0;
 #pragma unroll
     for (int d = 0; d < DM; d++)
-        if (d < C.D) L.dcnt[d * kWave + lane] = (uint32_t)((d < 4 ? lead_code.lo : lead_code.hi) >> (16 * (d & 3))) & 0xFFFFu;
+        if (d < C.D) L.dcnt[d * kWave + lane] = (uint32_t)((d < 4 ? lead_code.lo : lead_code.hi) >> (16 * (d & 3))) << 16;
 }
 
 // Period of the repeated window.  The sweep is a max-plus linear map F on the boundary vector x
@@ -1138,9 +1142,10 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     L.grp_tab = lds + kFastTableWords;                        // TP variants only
     L.cum_tab = lds + 10 * kMaxK;
     L.predbit_tab = lds + 11 * kMaxK;
-    L.depbit_tab = lds + 12 * kMaxK;
+    L.depbit_tab = lds + 15 * kMaxK;
     L.sw_tab = lds + kSweepTabWord;
     L.ch_tab = lds + kSweepTabWord + kMaxK;
+    L.in_tab = lds + kSweepTabWord + 2 * kMaxK;
     uint32_t *base = lds + kFastTableWords + (TP ? kMaxK : 0);
     L.rec = (uint4 *)base;
     // the sweep state is only used once the build is over: it shares the records' space when it fits
@@ -1153,7 +1158,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     if (lane < kMaxK) {
         const uint32_t inf = P.info_loc[lane];
         L.tt_tab[lane] = make_uint4((uint32_t)P.t_loc[lane], ((((inf >> 12) & 63u) - (uint32_t)P.D + 2u * DM) << 8),
-                                    ((uint32_t)lane >> 2) * (kWave * 4u), 4u * ((uint32_t)lane & 3u));
+                                    ((uint32_t)lane >> 2) * (kWave * 4u), 16u + 4u * ((uint32_t)lane & 3u));
         {
             const uint32_t su = inf & 63u, dev = (uint32_t)lane >> 2, y = (uint32_t)lane & 3u;
             const int32_t m = (int32_t)(inf << 6) >> 24;
@@ -1176,6 +1181,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
             const uint32_t dev = used ? (uint32_t)lane >> 2 : 0u, rel = used ? ((inf >> 12) & 63u) - (uint32_t)P.D : 0u;
             L.sw_tab[lane] = ((uint32_t)P.t_loc[lane] << 16) | (lds_address(L.dfree) + dev * (kWave * 4u));
             L.ch_tab[lane] = lds_address(L.dfree) + (2u * DM + rel) * (kWave * 4u);
+            L.in_tab[lane] = (1u << (16u + 4u * ((uint32_t)lane & 3u))) | (16u + 4u * ((uint32_t)lane & 3u));
         }
         L.chain_tab[lane] = P.chain_tab[lane];
         L.vtab[lane] = lane < 24 ? P.vtab[lane] : 0u;
