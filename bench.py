@@ -18,19 +18,62 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_INT32_OPS = 256 * 64 * 2.4e9 / 1e12      # T int32 lane-ops/s: 256 CUs x 64 lanes x 2.4 GHz, full-rate VALU ops
-# HBM bytes of one launch of 2^26 candidates, from the FETCH_SIZE / WRITE_SIZE passes in
-# profiles/eval_fast_kernel_cfg5_counters.md (13,537,265 KiB x 2.0 + 31,106,650 KiB x 1.0, copy-calibrated;
-# nearly all of it the queues between the kernel's phases)
-TRAFFIC_BYTES_PER_2P26_LAUNCH = int((13537265 * 2.0 + 31106650 * 1.0) * 1024)
+PEAK_LDS_OPS = 256 * 32 * 2.4e9 / 1e12        # T 32-bit LDS lane accesses/s: 256 CUs x 32 banks x 2.4 GHz
+COUNTERS_MD = os.path.join(ROOT, "profiles", "eval_fast_kernel_cfg5_counters.md")
 
 
-def algorithmic_ops(prob, n_candidates, n_sweeps):
-    """Integer operations of a straight-line statement of the method (not what the kernel
-    happens to issue), per block of the window: decode 17 (half a hash word, digit, pick),
-    build 34 (select, union of runnable entries, remove, new head, counters, masks, memory
-    add + max, emit), and 2 (one max, one add) per block and executed window sweep."""
+def profiled_traffic():
+    """HBM bytes of one launch of 2^26 candidates of the headline workload: the copy-calibrated FETCH_SIZE + WRITE_SIZE
+    of the committed rocprofv3 counter summary, and the commit the kernel was at when they were taken.  The line
+    `traffic_bytes_per_2p26_launch: <bytes> (kernel at <commit>)` of that file."""
+    try:
+        for line in open(COUNTERS_MD):
+            if line.startswith("traffic_bytes_per_2p26_launch:"):
+                parts = line.split()
+                return int(parts[1]), parts[-1].rstrip(")")
+    except OSError:
+        pass
+    return None, None
+
+
+DECODE_OPS, BUILD_OPS, SWEEP_OPS = 17, 34, 2   # per block: see algorithmic_ops
+
+
+def algorithmic_ops(prob, n_candidates, n_blocks_placed, n_sweeps):
+    """Integer operations of a straight-line statement of the method (not what the kernel happens to issue):
+    decode 17 per block of the window (half a hash word, digit, pick) for every candidate, build 34 per block
+    placed (select, union of runnable entries, remove, new head, counters, masks, memory add + max, emit), and 2
+    (one max, one add) per block and executed window sweep."""
     n = prob["K"] * prob["NR"]
-    return n_candidates * n * (17 + 34) + n_sweeps * n * 2
+    return n_candidates * n * DECODE_OPS + n_blocks_placed * BUILD_OPS + n_sweeps * n * SWEEP_OPS
+
+
+def host_threads():
+    """threads the oracle gets: the cores this process may run on"""
+    try:
+        return max(1, len(os.sched_getaffinity(0)))
+    except AttributeError:
+        return os.cpu_count() or 1
+
+
+def oracle_baseline(prob, sample):
+    """The CPU oracle as it stands on the first `sample` ordinals of the workload: all host cores, then one thread on
+    a sixteenth of the sample."""
+    from oracle import Oracle
+    cores = host_threads()
+    orc = Oracle(prob)
+    t1 = time.perf_counter()
+    ref = orc.sweep(0, sample, threads=cores)
+    cdt = time.perf_counter() - t1
+    single = max(1, sample // 16)
+    t1 = time.perf_counter()
+    orc.sweep(0, single, threads=1)
+    sdt = time.perf_counter() - t1
+    return {"value": sample / cdt, "unit": "candidates/s", "cores": cores, "kind": "oracle",
+            "sample": "first 2^%d ordinals of the same workload, %d threads, %.1f s; one thread on the first %d: %.1f s"
+                      % (sample.bit_length() - 1, cores, cdt, single, sdt),
+            "single_thread_value": single / sdt,
+            "oracle_ops_per_candidate": ref["ops"] / sample}
 
 
 def main():
@@ -113,16 +156,41 @@ def main():
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         blocks = prob["K"] * N
-        print(json.dumps({"metric": "completion candidates (whole schedules of 64 micro-batches) scored/s", "value": n * args.steps / dt,
-                          "unit": "candidates/s", "higher_is_better": True, "n_gpus": 1, "steps": args.steps,
-                          "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "dtype": "int32", "data": "synthetic",
-                          "vs_baseline": None,
-                          "config": {"workload": "cfg5 best window of the first 2^24 candidates, N=%d micro-batches (%d blocks), "
-                                                 "jitter %d, 2^%d completion candidates per step" % (N, blocks, args.jitter, args.log2_completions)},
-                          "result": {"window_period": best["period"], "windows": found["num_windows"],
-                                     "greedy_makespan": greedy["makespan"], "best_makespan": found["makespan"],
-                                     "best_ordinal": found["ordinal"]},
-                          "blocks_scheduled_per_s": n * args.steps / dt * blocks}))
+        # Straight-line operations of one completion candidate: a block of a replayed window is one max and one add;
+        # a block of the two greedy phases recomputes the offers of the types it can change (those on its device and
+        # its consumer: 8 operations each: token/device maximum, jitter add, three eligibility tests, key packing),
+        # takes the minimum over the K offers, commits (6) and draws the next jitter (7).
+        cand = gpu.best_candidate()
+        affected = max(sum(1 for j in range(prob["K"]) if (prob["dev_mask"][j] & prob["dev_mask"][i]) or (j, i) in
+                           [(b, a) for a, b in prob["deps"]]) for i in range(prob["K"]))
+        greedy_blocks = blocks - found["num_windows"] * prob["K"] * prob["NR"]
+        ops = greedy_blocks * (8 * affected + (prob["K"] - 1) + 6 + 7) + (blocks - greedy_blocks) * 2
+        rate = n * args.steps / dt
+        out = {"metric": "completion candidates (whole schedules of 64 micro-batches) scored/s", "value": rate,
+               "unit": "candidates/s", "higher_is_better": True, "n_gpus": 1, "steps": args.steps,
+               "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "dtype": "int32", "data": "synthetic",
+               "vs_baseline": None,
+               "config": {"workload": "cfg5 best window of the first 2^24 candidates, N=%d micro-batches (%d blocks), "
+                                      "jitter %d, 2^%d completion candidates per step" % (N, blocks, args.jitter, args.log2_completions)},
+               "result": {"window_period": best["period"], "windows": found["num_windows"],
+                          "greedy_makespan": greedy["makespan"], "best_makespan": found["makespan"],
+                          "best_ordinal": found["ordinal"]},
+               "blocks_scheduled_per_s": rate * blocks,
+               "roofline": {"bound": "alu", "achieved": ops * rate / 1e12, "peak": PEAK_INT32_OPS, "unit": "Tint32op/s",
+                            "frac": ops * rate / 1e12 / PEAK_INT32_OPS, "traffic": None, "kernel": "complete_kernel",
+                            "algorithmic_ops_per_candidate": ops,
+                            "limited_by": "LDS latency: per-lane state of the greedy phases is read and written through "
+                                          "dependent LDS accesses (profiles/complete_kernel_cfg5_kernel_trace_counters.md)"}}
+        if not args.no_cpu_baseline:
+            from oracle import Oracle
+            orc = Oracle(prob)
+            sample = 1 << 16
+            t1 = time.perf_counter()
+            orc.completion_scores(cand["leads"], cand["orders"], N, 0, sample, args.jitter)
+            cdt = time.perf_counter() - t1
+            out["cpu_baseline"] = {"value": sample / cdt, "unit": "candidates/s", "cores": 1, "kind": "oracle",
+                                   "sample": "completion candidates 0..%d of the same window, one thread, %.1f s" % (sample - 1, cdt)}
+        print(json.dumps(out))
         return
     prob = workloads.config5()
     n_cand = 1 << args.log2_candidates
@@ -157,17 +225,14 @@ def main():
     launch_ms = [a.elapsed_time(b) for a, b in events]
     avg_launch_s = sum(launch_ms) / len(launch_ms) / 1e3
     sweeps_per_cand = best["n_window_sweeps"] / best["n_evaluated"]
-    ops_per_launch = algorithmic_ops(prob, chunk, sweeps_per_cand * chunk)
-    achieved = ops_per_launch / avg_launch_s / 1e12
-    # The kernel stops building a candidate that is over the memory cap at the end of its first build phase (a fifth
-    # of the window's program words).  `achieved` prices every candidate at the whole window, as the method is stated;
-    # this second figure leaves out the blocks behind that point for every candidate rejected for memory (a lower
-    # bound: some of them are only caught at the end of the window).
+    blocks_per_cand = best["n_blocks_placed"] / best["n_evaluated"]
     total_blocks = prob["K"] * prob["NR"]
-    nwords = (total_blocks + 5) // 6
-    first_phase_blocks = min(total_blocks, 6 * (nwords // 5 if nwords >= 10 else nwords))
-    mem_rejects = best["n_reject"][5] / best["n_evaluated"]
-    ops_placed_only = ops_per_launch - chunk * mem_rejects * 34 * (total_blocks - first_phase_blocks)
+    # Work done: the kernel stops building a candidate that is over the memory cap at the end of its first build phase,
+    # so only the blocks it placed (counted by the kernel) are priced.  The second figure prices every candidate at
+    # the whole window, as the method is stated and as the per-candidate entry point computes it.
+    ops_per_launch = algorithmic_ops(prob, chunk, blocks_per_cand * chunk, sweeps_per_cand * chunk)
+    ops_whole_window = algorithmic_ops(prob, chunk, total_blocks * chunk, sweeps_per_cand * chunk)
+    achieved = ops_per_launch / avg_launch_s / 1e12
 
     # practical ceiling: independent full-rate integer adds/maxes on every lane of the chip
     from paper_2311_15269_amd.binding import alu_probe
@@ -180,6 +245,7 @@ def main():
     pb.record()
     torch.cuda.synchronize()
     peak_measured = probe_ops / (pa.elapsed_time(pb) / 1e3) / 1e12
+    traffic, traffic_commit = profiled_traffic()
 
     out = {
         "metric": "repetend candidates evaluated/sec + % peak VALU int ops, 8-dev V-shape",
@@ -198,24 +264,16 @@ def main():
         "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_INT32_OPS, "unit": "Tint32op/s",
                      "frac": achieved / PEAK_INT32_OPS,
                      "peak_measured": peak_measured, "frac_of_measured": achieved / peak_measured,
-                     "traffic": TRAFFIC_BYTES_PER_2P26_LAUNCH if chunk == 1 << 26 else None,
+                     "traffic": traffic if chunk == 1 << 26 else None, "traffic_measured_at_commit": traffic_commit,
                      "kernel": "eval_fast_kernel<8, 16, 2, false>", "avg_launch_ms": avg_launch_s * 1e3,
                      "algorithmic_ops_per_candidate": ops_per_launch / chunk,
-                     "frac_without_blocks_behind_a_memory_reject": ops_placed_only / avg_launch_s / 1e12 / PEAK_INT32_OPS,
-                     "window_sweeps_per_candidate": sweeps_per_cand},
+                     "blocks_placed_per_candidate": blocks_per_cand,
+                     "window_sweeps_per_candidate": sweeps_per_cand,
+                     "frac_if_every_candidate_priced_at_the_whole_window": ops_whole_window / avg_launch_s / 1e12 / PEAK_INT32_OPS},
     }
 
     if not args.no_cpu_baseline:
-        from oracle import Oracle
-        cores = min(os.cpu_count() or 1, 16)
-        sample = 1 << args.cpu_sample_log2
-        orc = Oracle(prob)
-        t1 = time.perf_counter()
-        ref = orc.sweep(0, sample, threads=cores)
-        cdt = time.perf_counter() - t1
-        out["cpu_baseline"] = {"value": sample / cdt, "unit": "candidates/s", "cores": cores, "kind": "oracle",
-                               "sample": "first 2^%d ordinals of the same workload, %d threads, %.1f s" % (args.cpu_sample_log2, cores, cdt),
-                               "oracle_ops_per_candidate": ref["ops"] / sample}
+        out["cpu_baseline"] = oracle_baseline(prob, 1 << args.cpu_sample_log2)
     print(json.dumps(out))
 
 

@@ -117,6 +117,10 @@ typedef struct {
     uint64_t n_reject[TESSEL_NUM_STATUS];     /* indexed by TESSEL_STATUS_*; [0] unused        */
     uint64_t n_window_sweeps;                 /* sweeps of the window spent on period computations
                                                  (0 when the general kernel did the scoring)    */
+    uint64_t n_blocks_placed;                 /* blocks the builds placed in executable order: a candidate that
+                                                 is over the cap early is not built to the end by
+                                                 tessel_eval_candidates (exact in the REPAIR space, an upper
+                                                 bound elsewhere; 0 when the general kernel did the scoring) */
 } tessel_result;
 
 /* A complete schedule of N micro-batches: warm-up, R copies of the best window, cool-down

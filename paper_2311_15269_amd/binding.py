@@ -38,7 +38,7 @@ class ProblemDesc(C.Structure):
 class Result(C.Structure):
     _fields_ = [("period", C.c_int32), ("index", C.c_uint64), ("peak_mem", C.c_int32 * MAX_DEVICES),
                 ("peak_max", C.c_int32), ("lower_bound", C.c_int32), ("n_evaluated", C.c_uint64),
-                ("n_feasible", C.c_uint64), ("n_reject", C.c_uint64 * NUM_STATUS), ("n_window_sweeps", C.c_uint64)]
+                ("n_feasible", C.c_uint64), ("n_reject", C.c_uint64 * NUM_STATUS), ("n_window_sweeps", C.c_uint64), ("n_blocks_placed", C.c_uint64)]
 
 
 class Schedule(C.Structure):
@@ -247,7 +247,7 @@ class Problem:
         rc = _check(load_library().tessel_best(self._h, C.byref(r)), allow=(E_NO_FEASIBLE,))
         return {"period": r.period, "index": int(r.index), "peak": list(r.peak_mem[:self.D]), "peak_max": r.peak_max,
                 "lower_bound": r.lower_bound, "n_evaluated": int(r.n_evaluated), "n_feasible": int(r.n_feasible),
-                "n_reject": [int(x) for x in r.n_reject], "n_window_sweeps": int(r.n_window_sweeps),
+                "n_reject": [int(x) for x in r.n_reject], "n_window_sweeps": int(r.n_window_sweeps), "n_blocks_placed": int(r.n_blocks_placed),
                 "feasible": rc == 0}
 
     def best_candidate(self):

@@ -542,6 +542,7 @@ extern "C" int tessel_best(tessel_problem *p, tessel_result *out)
     out->n_feasible = p->result.n_status[kOk];
     for (int s = 1; s < kNumStatus; s++) out->n_reject[s] = p->result.n_status[s];
     out->n_window_sweeps = p->result.n_sweeps;
+    out->n_blocks_placed = p->result.n_blocks;
     if (p->result.overflow) return TESSEL_E_WORKSPACE;       // more candidates deferred than the list holds
     if (p->result.period == INT_MAX) { out->period = -1; return TESSEL_E_NO_FEASIBLE; }
     out->period = p->result.period;

@@ -132,6 +132,7 @@ struct DevResult {
     uint32_t pad1;
     uint32_t defer_count;            // entries of the deferred list of the launch in flight
     uint32_t pad2;
+    uint64_t n_blocks;               // blocks placed by the builds of the fast kernel
 };
 
 // Decoded best candidate, written by the detail kernel.

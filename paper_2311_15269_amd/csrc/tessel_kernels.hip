@@ -37,6 +37,8 @@ struct BlockRec {
     uint32_t n_status[kNumStatus];
     uint32_t n_evaluated;
     uint32_t n_sweeps;           // window sweeps spent on period computations
+    uint32_t n_blocks;           // blocks placed by the build (fast kernel)
+    uint32_t pad;
 };
 
 constexpr uint32_t kDrawLeadBase = 0u;
@@ -1221,7 +1223,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     // slowest lane is done: a straggler among 63 finished lanes would cost a whole sweep of the wave).  What is still
     // open then is appended to the list of the general kernel.
     uint32_t *ring1 = ring_base + (size_t)blockIdx.x * 3u * ring_words, *ring2 = ring1 + ring_words, *ring3 = ring2 + ring_words;
-    uint32_t head1 = 0, count1 = 0, head2 = 0, count2 = 0, head3 = 0, count3 = 0, nretry = 0;           // wave-uniform
+    uint32_t head1 = 0, count1 = 0, head2 = 0, count2 = 0, head3 = 0, count3 = 0, nretry = 0, nblocks = 0;           // wave-uniform
     const int nwords = C.nwords;
     const bool split = stage_words < nwords;                         // tiny windows: A builds all of it
     const int wordsA = split ? stage_words : nwords;
@@ -1333,6 +1335,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
         head1 = (head1 + n) & (kRingSlots - 1u);
         count1 -= n;
         build_words<DM, MODE, TP>(P, C, L, lane, have, wordsA, nwords, prog, S);
+        nblocks += n * (uint32_t)(C.total - min(C.total, 6 * wordsA));
         finish_build(have, idx, prog);
     };
 
@@ -1346,6 +1349,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
         build_begin<DM, MODE, TP>(P, C, idx, L, lane, lead_code, S);
         FastProgram prog;
         build_words<DM, MODE, TP>(P, C, L, lane, valid, 0, wordsA, prog, S);
+        nblocks += (uint32_t)__builtin_popcountll(__ballot(valid)) * (uint32_t)min(C.total, 6 * wordsA);
         if (!split) { finish_build(valid, idx, prog); return; }
         const bool over = drop_mem && S.status == kOk && S.worst > C.M;
         reject(valid && (S.status != kOk || over), idx, over ? (int)kMem : S.status, 0);
@@ -1398,7 +1402,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     }
     if (lane == 0) {
         BlockRec rr;
-        rr.period = best; rr.n_retried = nretry; rr.index = best_idx; rr.n_evaluated = nev; rr.n_sweeps = nsw;
+        rr.period = best; rr.n_retried = nretry; rr.index = best_idx; rr.n_evaluated = nev; rr.n_sweeps = nsw; rr.n_blocks = nblocks; rr.pad = 0;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) rr.n_status[s] = cnt[s];
         recs[blockIdx.x] = rr;
@@ -1472,7 +1476,7 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
     }
     if (lane == 0) {
         BlockRec r;
-        r.period = best; r.n_retried = 0; r.index = best_idx; r.n_evaluated = nev; r.n_sweeps = 0;
+        r.period = best; r.n_retried = 0; r.index = best_idx; r.n_evaluated = nev; r.n_sweeps = 0; r.n_blocks = 0; r.pad = 0;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) r.n_status[s] = cnt[s];
         recs[blockIdx.x] = r;
@@ -1484,7 +1488,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
 {
     const int lane = threadIdx.x;
     int best = INT_MAX;
-    uint64_t best_idx = 0, nev = 0, nsw = 0, cnt[kNumStatus];
+    uint64_t best_idx = 0, nev = 0, nsw = 0, nbl = 0, cnt[kNumStatus];
     uint32_t nre = 0;
 #pragma unroll
     for (int s = 0; s < kNumStatus; s++) cnt[s] = 0;
@@ -1494,6 +1498,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
         if (key_less(r.period, r.index, best, best_idx)) { best = r.period; best_idx = r.index; }
         nev += r.n_evaluated;
         nsw += r.n_sweeps;
+        nbl += r.n_blocks;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) cnt[s] += r.n_status[s];
     }
@@ -1507,6 +1512,8 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
         nev += ((uint64_t)hi << 32) | lo;
         uint32_t slo = __shfl_xor((uint32_t)nsw, off), shi = __shfl_xor((uint32_t)(nsw >> 32), off);
         nsw += ((uint64_t)shi << 32) | slo;
+        uint32_t blo = __shfl_xor((uint32_t)nbl, off), bhi = __shfl_xor((uint32_t)(nbl >> 32), off);
+        nbl += ((uint64_t)bhi << 32) | blo;
         nre += __shfl_xor(nre, off);
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) {
@@ -1522,6 +1529,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int 
         res->defer_count = 0;
         res->n_evaluated += nev;
         res->n_sweeps += nsw;
+        res->n_blocks += nbl;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) res->n_status[s] += cnt[s];
     }
@@ -1536,7 +1544,7 @@ __global__ void clear_defer_kernel(DevResult *res)
 __global__ void reset_kernel(DevResult *res)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
-        res->period = INT_MAX; res->pad = 0; res->index = ~0ull; res->n_evaluated = 0; res->n_sweeps = 0;
+        res->period = INT_MAX; res->pad = 0; res->index = ~0ull; res->n_evaluated = 0; res->n_sweeps = 0; res->n_blocks = 0;
         res->n_retried = 0; res->n_deferred = 0; res->overflow = 0; res->defer_count = 0;
         for (int s = 0; s < kNumStatus; s++) res->n_status[s] = 0;
     }
@@ -1623,8 +1631,8 @@ LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
 }
 
 // program words the fast kernel builds before the candidates that are still alive queue for the rest (most
-// candidates that exceed the memory cap do so within the first blocks of the window); windows of fewer than
-// ten words are built in one go
+// candidates that exceed the memory cap do so within the first blocks of the window): about two sevenths of the
+// window, a multiple of four words; windows of fewer than ten words are built in one go
 static int stage_words(const KParams &kp)
 {
     const int nwords = (kp.total + 5) / 6;
@@ -1632,7 +1640,8 @@ static int stage_words(const KParams &kp)
         const int want = atoi(env);
         if (want >= 0 && want <= nwords) return want;
     }
-    return nwords >= 10 ? nwords / 5 : nwords;
+    // (measured on windows of 256 blocks: 12 of 43 words; the queues move program words four at a time)
+    return nwords >= 10 ? (nwords * 2 / 7 + 3) / 4 * 4 : nwords;
 }
 
 // the rings of the fast kernel's waves lie behind the block records, two per wave; words of one ring
