@@ -11,9 +11,12 @@
  * Pointer conventions: `*_dev` arguments are DEVICE pointers, every other pointer is a HOST
  * pointer.  Host arrays handed to tessel_problem_create() are read during the call only.
  * The library allocates no device memory: the caller owns the workspace and the stream.
+ * A workspace serves ONE problem handle at a time (the kernels keep the problem's tables, the running
+ * best and their queues in it): handing it to another handle ends the first handle's search; that
+ * handle's result calls then return TESSEL_E_WORKSPACE and its next scoring call starts a new search.
  * Every function returns TESSEL_OK (0) or a negative TESSEL_E_* code; nothing aborts or
  * throws across this boundary.  One problem handle must not be used from two host threads
- * at once; there is no global state.
+ * at once; the only state shared between handles is the table of which handle a workspace belongs to.
  */
 #ifndef TESSEL_H
 #define TESSEL_H
@@ -146,9 +149,9 @@ void tessel_problem_destroy(tessel_problem *p);
  * ordinal is a candidate). */
 int  tessel_candidate_count(const tessel_problem *p, uint64_t *count);
 
-/* Bytes of device workspace tessel_eval_candidates / tessel_score_candidates need: the running best, lists of
- * unfinished candidates (72 MiB) and, for problems the fast kernel takes, two queues per resident wave between the
- * phases of the kernel (2 x 27 KB per wave for 256 blocks a window; a few hundred MB in all).  Sized for the current
+/* Bytes of device workspace tessel_eval_candidates / tessel_score_candidates need: the running best, the list of
+ * candidates left to the general kernel (8 MiB) and, for problems the fast kernel takes, three queues per resident
+ * wave between the phases of the kernel (3 x 27 KB per wave for 256 blocks a window; a few hundred MB in all).  Sized for the current
  * device (for 512 compute units where there is none to ask); a workspace too small for the device a call runs on is
  * refused there with TESSEL_E_WORKSPACE. */
 int  tessel_workspace_bytes(const tessel_problem *p, size_t *bytes);
@@ -171,9 +174,10 @@ int  tessel_score_candidates(tessel_problem *p, uint64_t first, uint64_t count,
 
 /* Waits for the stream of the last call, then returns the running best.  NO_FEASIBLE when
  * nothing feasible has been scored (counters in *out are still valid).  If a launch left more
- * candidates unfinished than its internal list holds (possible only when more than an eighth of a
- * range of 2^26 candidates needs extra period work), every range scored since the last reset is
- * scored again here in smaller pieces before the result is returned. */
+ * candidates to the general kernel than its list holds (2^20 of a range of up to 2^26: possible only
+ * when most periods need more than the fast kernel's ten sweeps), every range scored since the last
+ * reset is scored again here in smaller pieces before the result is returned.  WORKSPACE: the buffer
+ * was bound to another handle in the meantime. */
 int  tessel_best(tessel_problem *p, tessel_result *out);
 
 /* Decoded form of the best candidate as the GPU decoded it: leads[K], order_len[D] and
@@ -219,7 +223,7 @@ int  tessel_score_completions(tessel_problem *p, int32_t num_microbatches, int32
  * searched), NO_SCHEDULE (no candidate had a schedule), INVALID_ARG, RANGE, HIP. */
 int  tessel_best_completion(tessel_problem *p, tessel_schedule *out, uint64_t *ordinal);
 
-/* ---- runtime instantiation (Sec. IV-E): the global operation sequence of a complete schedule --------
+/* ---- runtime instantiation (Sec. IV-D): the global operation sequence of a complete schedule --------
  * Blocks in ascending start time; blocks that start together are consecutive, ordered by their lowest
  * device (a device's own blocks keep its execution order).  A tensor that a consumer needs on a device
  * where its producer did not run is one send/receive pair, a single operation placed right after the
@@ -243,7 +247,7 @@ typedef struct {
 int  tessel_instantiate(const tessel_problem *p, const tessel_schedule *sched, tessel_op *ops, int32_t capacity,
                         int32_t *num_ops);
 
-/* ---- the whole search of Alg. 1 (Sec. IV-D): all window sizes ---------------------------
+/* ---- the whole search of Alg. 1 (Sec. IV-C): all window sizes ---------------------------
  * In: which window sizes and how many candidates of each; out: the incumbent and what each
  * window size gave.  Repetend times of different window sizes compare per micro-batch:
  * T_a/N_a < T_b/N_b  <=>  T_a*N_b < T_b*N_a. */

@@ -70,6 +70,7 @@ def _load():
         lib.orc_eval_explicit.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                           C.POINTER(OracleScore), C.c_void_p]
         lib.orc_feasible_explicit.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]
+        lib.orc_repair_explicit.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
         lib.orc_sweep.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.POINTER(OracleResult)]
         lib.orc_sweep_mt.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_int, C.POINTER(OracleResult)]
         lib.orc_score_range.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p]
@@ -185,7 +186,7 @@ class Oracle:
         return out, (rc if rc >= 0 else None), int(best.value)
 
     def instantiate(self, N, start, dev_order):
-        """global operation sequence of a complete schedule (Sec. IV-E): list of (kind, block, src, dst, aux)"""
+        """global operation sequence of a complete schedule (Sec. IV-D): list of (kind, block, src, dst, aux)"""
         start = _i32(np.asarray(start).reshape(-1))
         stride = self.K * N
         order = np.full((self.D, stride), -1, dtype=np.int32)
@@ -262,6 +263,17 @@ class Oracle:
         if want_starts:
             out["starts"] = starts.reshape(self.K, self.NR)
         return out
+
+    def repair_explicit(self, leads, orders):
+        """the repair rule of the REPAIR space applied to explicit priority lists: repaired per-device orders"""
+        length, seq = self._pack(orders)
+        leads = _i32(leads)
+        out = np.zeros_like(seq)
+        rc = _load().orc_repair_explicit(self._h, leads.ctypes.data, length.ctypes.data, seq.ctypes.data, self.stride,
+                                         out.ctypes.data)
+        if rc:
+            raise OracleError(rc)
+        return [out[d, :length[d]].tolist() for d in range(self.D)]
 
     def feasible_explicit(self, leads, orders, T):
         length, seq = self._pack(orders)

@@ -112,7 +112,7 @@ static uint32_t draw16(uint64_t seed, uint64_t ordinal, uint32_t j)
     uint32_t word = stream_word(a, b, j >> 1);
     return (word >> (16 * (j & 1))) & 0xFFFFu;
 }
-/* exported so that a test can pin the sampler against values computed by hand */
+/* exported so that a test can pin the sampler against the worked example of tests/golden/sampler_hand.txt */
 uint32_t orc_draw16(uint64_t seed, uint64_t ordinal, uint32_t j) { return draw16(seed, ordinal, j); }
 
 #define DRAW_LEAD_BASE 0u     /* draw j = e            decides the lead step of dependency e   */
@@ -621,6 +621,31 @@ int orc_eval_explicit(const orc_problem *p, const int *leads, const int *len, co
     return ORC_E_OK;
 }
 
+/* the repair rule on explicitly given priority lists (pins its scan order against a worked example):
+ * seq_out[D][stride] receives the repaired per-device orders */
+int orc_repair_explicit(const orc_problem *p, const int *leads, const int *len, const int *seq, int stride, int *seq_out)
+{
+    static __thread orc_candidate c;
+    int cnt[ORC_MAX_K] = {0};
+    for (int i = 0; i < p->K; i++) { if (leads[i] < 0 || leads[i] >= p->NR) return ORC_E_INVALID; c.leads[i] = leads[i]; }
+    for (int e = 0; e < p->ndeps; e++) if (leads[p->src[e]] < leads[p->dst[e]]) return ORC_E_INVALID;
+    for (int d = 0; d < p->D; d++) {
+        if (len[d] != p->ntd[d] * p->NR) return ORC_E_INVALID;
+        c.len[d] = len[d];
+        for (int k = 0; k < len[d]; k++) {
+            int g = seq[d * stride + k];
+            if (g < 0 || g >= p->K || !(p->mask[g] >> d & 1u)) return ORC_E_INVALID;
+            c.seq[d][k] = g;
+            if (d == __builtin_ctz(p->mask[g])) cnt[g]++;
+        }
+    }
+    for (int i = 0; i < p->K; i++) if (cnt[i] != p->NR) return ORC_E_INVALID;
+    repair_orders(p, &c);
+    for (int d = 0; d < p->D; d++)
+        for (int k = 0; k < c.len[d]; k++) seq_out[d * stride + k] = c.seq[d][k];
+    return ORC_E_OK;
+}
+
 /* feasibility of one period for an explicit candidate (pins the monotone search) */
 int orc_feasible_explicit(const orc_problem *p, const int *leads, const int *len, const int *seq, int stride, int T)
 {
@@ -1005,7 +1030,7 @@ int orc_search(int D, int K, int M, const int *t, const int *m, const uint32_t *
     return ORC_E_OK;
 }
 
-/* ------------------------------------------------------------------ runtime instantiation (Sec. IV-E)
+/* ------------------------------------------------------------------ runtime instantiation (Sec. IV-D)
  * A complete schedule fixes start times and per-device orders; what the devices execute is one
  * global sequence of operations.  Blocks come in ascending start time; blocks that start together
  * are consecutive, devices in ascending order, each device's blocks in its execution order (a block

@@ -9,7 +9,10 @@
 #include <cstdlib>
 #include <cstdint>
 #include <cstring>
+#include <atomic>
+#include <mutex>
 #include <new>
+#include <unordered_map>
 #include <vector>
 
 #include "../../include/tessel.h"
@@ -20,6 +23,7 @@ using namespace tessel;
 namespace tessel { size_t block_rec_bytes(int blocks); }
 
 struct tessel_problem {
+    uint64_t id = 0;                    // never reused: names the handle as the owner of a workspace
     KParams kp;
     std::vector<int32_t> t, m;
     std::vector<uint32_t> mask;
@@ -50,6 +54,35 @@ struct tessel_problem {
 };
 
 static int hip_fail(tessel_problem *p, int e) { p->last_hip = e; return TESSEL_E_HIP; }
+
+// Which handle a device workspace belongs to.  The kernels read the problem's parameter block, the running best and
+// the queues from the workspace itself, so a buffer serves one handle at a time: binding it to another handle ends
+// the first one's search, and that handle's next scoring call binds it anew (a new search), while its calls that
+// read results are refused.  (Host memory only; the one piece of state shared between handles.)
+namespace {
+std::mutex g_owner_mutex;
+std::unordered_map<const void *, uint64_t> g_owner;
+std::atomic<uint64_t> g_next_id{1};
+
+bool owns_workspace(const tessel_problem *p)
+{
+    if (!p->ws || !p->ws_ready) return false;
+    std::lock_guard<std::mutex> lock(g_owner_mutex);
+    auto it = g_owner.find(p->ws);
+    return it != g_owner.end() && it->second == p->id;
+}
+void take_workspace(const tessel_problem *p, const void *ws)
+{
+    std::lock_guard<std::mutex> lock(g_owner_mutex);
+    g_owner[ws] = p->id;
+}
+void release_workspaces(const tessel_problem *p)
+{
+    std::lock_guard<std::mutex> lock(g_owner_mutex);
+    for (auto it = g_owner.begin(); it != g_owner.end();)
+        if (it->second == p->id) it = g_owner.erase(it); else ++it;
+}
+}  // namespace
 
 extern "C" const char *tessel_strerror(int code)
 {
@@ -161,6 +194,7 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
 
     tessel_problem *p = new (std::nothrow) tessel_problem();
     if (!p) return TESSEL_E_INVALID_ARG;
+    p->id = g_next_id.fetch_add(1);
     p->t.assign(desc->time, desc->time + K);
     p->m.assign(desc->mem, desc->mem + K);
     p->mask.assign(desc->dev_mask, desc->dev_mask + K);
@@ -358,7 +392,12 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
     return TESSEL_OK;
 }
 
-extern "C" void tessel_problem_destroy(tessel_problem *p) { delete p; }
+extern "C" void tessel_problem_destroy(tessel_problem *p)
+{
+    if (!p) return;
+    release_workspaces(p);
+    delete p;
+}
 
 extern "C" int tessel_candidate_count(const tessel_problem *p, uint64_t *count)
 {
@@ -417,7 +456,7 @@ static int bind_workspace(tessel_problem *p, void *ws, size_t bytes, hipStream_t
     int rc = ensure_device(p);
     if (rc) return rc;
     if (bytes < workspace_need(p, p->num_cus)) return TESSEL_E_WORKSPACE;
-    if (p->ws == ws && p->ws_ready) return TESSEL_OK;
+    if (p->ws == ws && owns_workspace(p)) return TESSEL_OK;
     char *base = (char *)ws + kWsTablesOff;
     size_t lead_bytes = (p->leadtab.size() + 255) & ~(size_t)255, w_bytes = p->wtab.size() * sizeof(uint64_t);
     if (lead_bytes + w_bytes > kWsTablesMax) return TESSEL_E_TOOBIG;
@@ -434,8 +473,11 @@ static int bind_workspace(tessel_problem *p, void *ws, size_t bytes, hipStream_t
     int e = launch_reset(ws, st);
     if (e) return hip_fail(p, e);
     p->ws = ws; p->ws_ready = true; p->have_detail = false;
+    p->comp_ready = false;              // the completion parameters lived in the workspace bound before
     p->ranges.clear();
     p->best_dirty = true;
+    p->result.period = INT_MAX;
+    take_workspace(p, ws);
     return TESSEL_OK;
 }
 
@@ -490,7 +532,7 @@ extern "C" int tessel_reset(tessel_problem *p)
     p->result.period = INT_MAX;
     p->ranges.clear();
     p->best_dirty = true;
-    if (!p->ws || !p->ws_ready) return TESSEL_OK;
+    if (!owns_workspace(p)) { p->ws_ready = false; return TESSEL_OK; }     // (another handle's by now: nothing of ours is left in it)
     int e = launch_reset(p->ws, p->stream);
     return e ? hip_fail(p, e) : TESSEL_OK;
 }
@@ -498,6 +540,7 @@ extern "C" int tessel_reset(tessel_problem *p)
 static int fetch_best(tessel_problem *p)
 {
     if (!p->ws || !p->ws_ready) { memset(&p->result, 0, sizeof p->result); p->result.period = INT_MAX; return TESSEL_OK; }
+    if (!owns_workspace(p)) return TESSEL_E_WORKSPACE;       // another handle has bound the buffer since: the running best is gone
     hipError_t e = hipStreamSynchronize(p->stream);
     if (e != hipSuccess) return hip_fail(p, (int)e);
     e = hipMemcpy(&p->result, (char *)p->ws + kWsResultOff, sizeof(DevResult), hipMemcpyDeviceToHost);
@@ -718,6 +761,7 @@ extern "C" int tessel_complete_schedule(tessel_problem *p, tessel_schedule *out)
 // uploads what the kernel needs of the problem and of the best candidate (once per best candidate, N, J)
 static int bind_completion(tessel_problem *p, int N, int J)
 {
+    if (p->ws && p->ws_ready && !owns_workspace(p)) return TESSEL_E_WORKSPACE;      // the buffer is another handle's by now
     if (p->comp_ready && !p->best_dirty && p->comp_index == p->result.index && p->result.period != INT_MAX && p->comp.N == N &&
         p->comp.J == J)
         return TESSEL_OK;                                   // nothing new since the best was fetched: no wait
@@ -821,6 +865,7 @@ extern "C" int tessel_best_completion(tessel_problem *p, tessel_schedule *out, u
 {
     if (!p || !out || !out->start || !out->dev_order || !out->dev_len) return TESSEL_E_INVALID_ARG;
     if (!p->comp_ready || !p->ws) return TESSEL_E_NO_FEASIBLE;
+    if (!owns_workspace(p)) return TESSEL_E_WORKSPACE;
     if (out->num_microbatches != p->comp.N) return TESSEL_E_INVALID_ARG;
     hipError_t e = hipStreamSynchronize(p->stream);
     if (e != hipSuccess) return hip_fail(p, (int)e);
@@ -835,7 +880,7 @@ extern "C" int tessel_best_completion(tessel_problem *p, tessel_schedule *out, u
     return TESSEL_OK;
 }
 
-// ---- Sec. IV-E: global sequence of blocks and send/receive pairs -----------------------------------
+// ---- Sec. IV-D: global sequence of blocks and send/receive pairs -----------------------------------
 extern "C" int tessel_instantiate(const tessel_problem *p, const tessel_schedule *sched, tessel_op *ops, int32_t capacity,
                                   int32_t *num_ops)
 {

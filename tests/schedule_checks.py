@@ -136,7 +136,7 @@ def check_flat_schedule(problem, N, start, dev_order):
 
 
 def check_instantiation(problem, N, start, ops):
-    """Properties Sec. IV-E asks of the global operation sequence of a complete schedule.
+    """Properties Sec. IV-D asks of the global operation sequence of a complete schedule.
     ops: (kind, block, src, dst, aux); kind 0 = block (src = device mask, dst = start time),
     kind 1 = send/receive pair (block = producer, src = sender, dst = receiver, aux = consumer).
     Returns (ok, reason)."""

@@ -127,6 +127,39 @@ def multiset_rank(seq, symbols, nr):
     return rank
 
 
+def test_a_workspace_serves_one_handle_at_a_time(gpu):
+    """The kernels keep the problem's tables and the running best in the workspace, so a buffer that another handle
+    has bound since is not this handle's any more: its result calls are refused, its next scoring call binds the
+    buffer anew and starts a new search (also for the completion search, whose parameters live there too)."""
+    from oracle import Oracle
+    pa, pb = W.config3(), W.config1()
+    a, b = gpu.Problem(pa), gpu.Problem(pb)
+    a.eval_candidates(0, 5000)
+    want_a = a.best()
+    a.search_completions(12, 2, 0, 256)
+    comp_a = a.best_completion(12)
+    b._ws = a._ws                                        # the same device buffer (config 3 needs the larger one)
+    b.eval_candidates(0, 576)
+    want_b = Oracle(pb).sweep(0, 576)
+    got_b = b.best()
+    assert (got_b["period"], got_b["index"], got_b["n_feasible"]) == (want_b["period"], want_b["index"], want_b["n_feasible"])
+    for call in (a.best, a.best_candidate, lambda: a.complete_schedule(12), lambda: a.best_completion(12),
+                 lambda: a.search_completions(12, 2, 0, 64)):
+        with pytest.raises(gpu.TesselError) as err:
+            call()
+        assert err.value.code == -5                      # TESSEL_E_WORKSPACE
+    a.eval_candidates(0, 5000)                           # binds again: a new search with the same outcome
+    again = a.best()
+    for key in ("period", "index", "peak", "n_evaluated", "n_feasible", "n_reject"):
+        assert again[key] == want_a[key], key
+    a.search_completions(12, 2, 0, 256)                  # the completion parameters are uploaded again
+    redo = a.best_completion(12)
+    assert (redo["makespan"], redo["ordinal"]) == (comp_a["makespan"], comp_a["ordinal"])
+    with pytest.raises(gpu.TesselError) as err:
+        b.best()
+    assert err.value.code == -5
+
+
 def test_config2_slices_and_the_1f1b_candidate(gpu):
     from oracle import Oracle
     prob = W.config2()

@@ -1,4 +1,4 @@
-"""Pins of the oracle's runtime instantiation (Sec. IV-E: one global sequence of blocks and send/receive
+"""Pins of the oracle's runtime instantiation (Sec. IV-D: one global sequence of blocks and send/receive
 pairs) against a sequence written out by hand and against the properties the section asks for, checked
 by code that shares nothing with the oracle (tests/schedule_checks.py)."""
 import os

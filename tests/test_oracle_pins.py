@@ -173,6 +173,10 @@ def test_config1_exhaustive_summary():
     assert res["n_evaluated"] == 576
     assert res["period"] == 6 == orc.lower_bound          # a zero-bubble repetend exists
     assert res["n_feasible"] == sum(v for k, v in hist.items() if k > 0)
+    # the census of the whole space: 27 of the 576 candidates are feasible, 3 at the bound, 18 at period 9, 6 at 12
+    # (worked out apart from this oracle when the problem was stated)
+    assert res["n_feasible"] == 27
+    assert {k: v for k, v in hist.items() if k > 0} == {6: 3, 9: 18, 12: 6}
     # 16 lead vectors x 36 interleavings, every label order cyclic when N_R = 2
     assert hist[-DUP] == 0 and hist[-TP_MISMATCH] == 0
     # lowest index wins among equal periods (Alg. 1 compares with strict <)
@@ -390,3 +394,47 @@ def test_error_paths():
         Oracle(dict(base, t=[0, 1, 2, 2]))
     with pytest.raises(OracleError):
         Oracle(W.pipeline_problem(W.folded_placement(8), [1] * 16, [1] * 16, 8, 8, 10, "canonical"))  # > 2^64
+
+
+def _golden_lines(name, tag):
+    path = os.path.join(os.path.dirname(__file__), "golden", name)
+    return [ln[len(tag):].strip() for ln in open(path) if ln.startswith(tag)]
+
+
+def test_sampler_matches_the_worked_example():
+    """orc_draw16 against tests/golden/sampler_hand.txt: key mixing anchored on the published first output of
+    SplitMix64 seeded with 0, every 32-bit step of the word hash written out."""
+    from oracle.oracle import draw16
+    rows = _golden_lines("sampler_hand.txt", "draw ")
+    assert len(rows) == 6
+    for row in rows:
+        seed, ordinal, j, want = (int(x) for x in row.split())
+        assert draw16(seed, ordinal, j) == want, row
+
+
+def test_repair_matches_the_worked_examples():
+    """The repair rule against tests/golden/repair_hand.txt, derived step by step there: the fallback goes to the
+    lowest device that has a runnable block and takes the earliest such entry of its list; runnable lists stay."""
+    orc = Oracle(dict(W.config1(), space="sampled_repair"))
+    rows = _golden_lines("repair_hand.txt", "case ")
+    assert len(rows) == 3
+    for row in rows:
+        leads, d0, d1, want0, want1 = ([int(x) for x in part.split()] for part in row.split("|"))
+        assert orc.repair_explicit(leads, [d0, d1]) == [want0, want1], row
+        # the repaired orders are executable and handle the same blocks
+        assert orc.eval_explicit(leads, [want0, want1])["status"] in (OK, MEM)
+        assert sorted(d0) == sorted(want0) and sorted(d1) == sorted(want1)
+
+
+def test_a_block_on_two_devices_with_two_leads_is_a_mismatch():
+    """FACTORIAL space, one block type on both of two devices, windows of two micro-batches: each device orders
+    the labelled blocks (0, 1); rank 0 = (0, 1) names lead 0, rank 1 = (1, 0) names lead 1.  Index = r_0 + 2 r_1:
+    indices 1 and 2 give the block different leads on its two devices (TP_MISMATCH); 0 and 3 are the same schedule,
+    both micro-batches one after the other: period 2 t."""
+    prob = {"name": "tp-hand", "D": 2, "K": 1, "NR": 2, "M": 0, "t": [3], "m": [0], "dev_mask": [3], "deps": [],
+            "space": "factorial", "seed": 0, "lead_step_q16": 0, "fixed_leads": None}
+    orc = Oracle(prob)
+    assert orc.count == 4
+    got = [orc.eval_index(i) for i in range(4)]
+    assert [g["status"] for g in got] == [OK, TP_MISMATCH, TP_MISMATCH, OK]
+    assert got[0]["period"] == got[3]["period"] == 6

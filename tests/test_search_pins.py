@@ -1,4 +1,4 @@
-"""Pins of the oracle's whole-search routine (Alg. 1, Sec. IV-D) against facts that do not come
+"""Pins of the oracle's whole-search routine (Alg. 1, Sec. IV-C) against facts that do not come
 from it: closed forms of the sequential pipeline (Sec. VI ablation: no bubble once the window
 holds as many micro-batches as there are stages and the memory allows them), the hand-checked
 2-device golden row, a re-derivation from the separately pinned per-window argmin with exact
