@@ -779,7 +779,7 @@ static int bind_completion(tessel_problem *p, int N, int J)
     CompParams &cp = p->comp;
     memset(&cp, 0, sizeof cp);
     cp.D = D; cp.K = K; cp.NR = NR; cp.M = p->kp.M; cp.N = N; cp.J = J; cp.R = R; cp.nseq = K * NR;
-    cp.seed = p->kp.seed + kCompletionKey;
+    { const uint64_t seed = p->kp.seed + kCompletionKey; cp.seed_lo = (uint32_t)seed; cp.seed_hi = (uint32_t)(seed >> 32); }
     int npaths = 0;
     for (int i = 0; i < K; i++) {
         if (p->m[i] < -128 || p->m[i] > 127) return TESSEL_E_UNSUPPORTED;

@@ -151,7 +151,8 @@ struct CompParams {
     int32_t  D, K, NR, M, N, J, R, nseq, npaths;
     int32_t  tok_ring;               // slots per chain for the end times of the micro-batches in flight: a power of two
                                      // above (largest - smallest lead) + NR, the most two types of a chain are ever apart
-    uint64_t seed;                   // problem seed + kCompletionKey
+    uint32_t seed_lo, seed_hi;       // problem seed + kCompletionKey (two words: the kernel's copy of this block in LDS
+                                     // is written word by word, and nothing in it is read through a wider type)
     int32_t  t[kMaxK];
     int8_t   m[kMaxK];
     uint8_t  mask[kMaxK];

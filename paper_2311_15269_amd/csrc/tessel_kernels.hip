@@ -622,11 +622,11 @@ __device__ __forceinline__ void sweep_node_group(const FastLds &L, const uint4 t
 // address goes into the instruction's offset field.
 typedef __attribute__((address_space(3))) uint32_t lds_word;
 __device__ __forceinline__ uint32_t lds_address(const void *p) { return (uint32_t)(uintptr_t)(const lds_word *)p; }
-__device__ __forceinline__ uint32_t lds_load(uint32_t a) { return *(const lds_word *)a; }
-__device__ __forceinline__ void lds_store(uint32_t a, uint32_t v) { *(lds_word *)a = v; }
+__device__ __forceinline__ uint32_t lds_load(uint32_t a) { return *(const lds_word *)(uintptr_t)a; }
+__device__ __forceinline__ void lds_store(uint32_t a, uint32_t v) { *(lds_word *)(uintptr_t)a = v; }
 __device__ __forceinline__ uint32_t lds_fetch_add(uint32_t a, uint32_t v)
 {
-    return __hip_atomic_fetch_add((lds_word *)a, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return __hip_atomic_fetch_add((lds_word *)(uintptr_t)a, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 // The blocks of one sweep for problems whose blocks sit on one device each, as a software pipeline four blocks deep.
@@ -996,7 +996,7 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
     auto word = [&](int wi) -> uint32_t {
         uint32_t acc = 0;
         const int nj = __builtin_amdgcn_readfirstlane(min(6, total - wi * 6));
-#pragma unroll 2
+#pragma unroll 1
         for (int j = 0; j < nj; j++) {
             uint32_t hm = R & HM;
             if (TP)
@@ -1823,7 +1823,7 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
         const bool live = kk < count;
         const uint64_t c = first + (live ? kk : 0);
         uint32_t kb;
-        const uint32_t ka = stream_keys(cp.seed, c, kb);
+        const uint32_t ka = stream_keys(((uint64_t)cp.seed_hi << 32) | cp.seed_lo, c, kb);
         const bool noisy = c != 0 && J > 0;
         auto jitter = [&](int i, int mu) -> uint32_t {
             return noisy ? (stream_draw16(ka, kb, (uint32_t)(i * N + mu)) * (uint32_t)(J + 1)) >> 16 : 0u;
@@ -2034,7 +2034,6 @@ int launch_completion_reset(void *ws, void *stream)
 // full-rate integer VALU instructions per round with no dependency closer than 16 instructions.
 // What this kernel sustains is the practical ceiling the scoring kernels are compared with.
 constexpr int kProbeAcc = 16;
-constexpr int kProbeOpsPerRound = 2 * kProbeAcc;
 
 __global__ __launch_bounds__(256) void alu_probe_kernel(uint32_t *out, int rounds, uint32_t inc, uint32_t floor_)
 {
