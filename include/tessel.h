@@ -165,6 +165,21 @@ int  tessel_workspace_bytes(const tessel_problem *p, size_t *bytes);
 int  tessel_eval_candidates(tessel_problem *p, uint64_t first, uint64_t count,
                             void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): tessel_eval_candidates without a workspace argument.  The running best,
+ * the problem's tables and the kernels' queues live in a buffer that is part of the library's code object
+ * (TESSEL_NOALLOC_SCRATCH_BYTES of device memory on every GPU the library runs on, held until the process
+ * ends); the grid shrinks to the workgroups whose queues fit it (about a hundred of the 4096 the chip holds
+ * for windows of 256 blocks, all of them for small windows), so this call can be much slower than the one above.  No hipMalloc, hipFree or other allocating call
+ * is made.  Every call on a GPU shares that GPU's buffer: it serves one handle at a time like any workspace
+ * (another handle's call ends this handle's search), and calls that overlap on one GPU, from different
+ * streams or threads, race.  tessel_best, tessel_reset, tessel_best_candidate, tessel_complete_schedule and
+ * the completion search apply as after tessel_eval_candidates.
+ * Errors: RANGE, TOOBIG (count above TESSEL_NOALLOC_MAX_CANDIDATES per call), HIP. */
+#define TESSEL_NOALLOC_SCRATCH_BYTES   (24u << 20)
+#define TESSEL_NOALLOC_MAX_CANDIDATES  (1ull << 26)
+int  tessel_eval_candidates_noalloc(tessel_problem *p, uint64_t first, uint64_t count, void *hip_stream);
+
 /* Per-candidate records for tests and analysis: code_dev[k] = T* of candidate first+k when
  * it is feasible, else -(TESSEL_STATUS_*); peak_dev[k] (may be NULL) = its largest
  * per-device peak when the status is OK or MEM, else 0.  Does not touch the running best. */

@@ -22,7 +22,7 @@ E_RANGE = -8
 
 EXPORTS = (
     "tessel_problem_create", "tessel_problem_destroy", "tessel_candidate_count", "tessel_workspace_bytes",
-    "tessel_eval_candidates", "tessel_score_candidates", "tessel_best", "tessel_best_candidate", "tessel_reset",
+    "tessel_eval_candidates", "tessel_eval_candidates_noalloc", "tessel_score_candidates", "tessel_best", "tessel_best_candidate", "tessel_reset",
     "tessel_complete_schedule", "tessel_search_completions", "tessel_score_completions", "tessel_best_completion",
     "tessel_instantiate", "tessel_search_workspace_bytes", "tessel_search_run", "tessel_alu_probe", "tessel_strerror", "tessel_last_hip_error",
 )
@@ -84,6 +84,7 @@ def load_library():
         lib.tessel_candidate_count.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
         lib.tessel_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
         lib.tessel_eval_candidates.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.tessel_eval_candidates_noalloc.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p]
         lib.tessel_score_candidates.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p,
                                                 C.c_void_p, C.c_size_t, C.c_void_p]
         lib.tessel_best.argtypes = [C.c_void_p, C.POINTER(Result)]
@@ -231,6 +232,11 @@ class Problem:
         ptr, size = self._workspace()
         _check(load_library().tessel_eval_candidates(self._h, first, count, ptr, size,
                                                       self._stream() if stream is None else stream))
+
+    def eval_candidates_noalloc(self, first, count, stream=None):
+        """tessel_eval_candidates_noalloc: the library's own device buffer instead of a workspace tensor"""
+        _check(load_library().tessel_eval_candidates_noalloc(self._h, first, count,
+                                                              self._stream() if stream is None else stream))
 
     def score_candidates(self, first, count):
         """returns (code, peak) int32 CUDA tensors"""

@@ -34,6 +34,7 @@ struct tessel_problem {
     uint64_t count = 0;
     int num_cus = 0;
     void *ws = nullptr;                 // workspace the running best lives in
+    int max_blocks = 0;                 // 0, or the largest grid that workspace has queues for (the library's own buffer)
     bool ws_ready = false;
     hipStream_t stream = nullptr;
     int last_hip = 0;
@@ -52,6 +53,8 @@ struct tessel_problem {
     uint64_t comp_index = 0;            // best candidate they were built for
     CompParams comp;
 };
+
+static_assert(kScratchBytes == TESSEL_NOALLOC_SCRATCH_BYTES, "header and library disagree on the size of the library's own workspace");
 
 static int hip_fail(tessel_problem *p, int e) { p->last_hip = e; return TESSEL_E_HIP; }
 
@@ -421,7 +424,7 @@ static int ensure_device(tessel_problem *p)
 
 static size_t workspace_need(const tessel_problem *p, int num_cus)
 {
-    return eval_workspace_bytes(p->kp, num_cus);
+    return eval_workspace_bytes(p->kp, num_cus, 0);
 }
 
 extern "C" int tessel_workspace_bytes(const tessel_problem *p, size_t *bytes)
@@ -450,12 +453,12 @@ static int range_ok(const tessel_problem *p, uint64_t first, uint64_t count)
 }
 
 // binds the workspace: uploads the tables of the exhaustive spaces and clears the running best
-static int bind_workspace(tessel_problem *p, void *ws, size_t bytes, hipStream_t st)
+static int bind_workspace(tessel_problem *p, void *ws, size_t bytes, hipStream_t st, int max_blocks = 0)
 {
     if (!ws || ((uintptr_t)ws & 255u)) return TESSEL_E_WORKSPACE;
     int rc = ensure_device(p);
     if (rc) return rc;
-    if (bytes < workspace_need(p, p->num_cus)) return TESSEL_E_WORKSPACE;
+    if (bytes < eval_workspace_bytes(p->kp, p->num_cus, max_blocks)) return TESSEL_E_WORKSPACE;
     if (p->ws == ws && owns_workspace(p)) return TESSEL_OK;
     char *base = (char *)ws + kWsTablesOff;
     size_t lead_bytes = (p->leadtab.size() + 255) & ~(size_t)255, w_bytes = p->wtab.size() * sizeof(uint64_t);
@@ -472,7 +475,7 @@ static int bind_workspace(tessel_problem *p, void *ws, size_t bytes, hipStream_t
     if (pe != hipSuccess) return hip_fail(p, (int)pe);
     int e = launch_reset(ws, st);
     if (e) return hip_fail(p, e);
-    p->ws = ws; p->ws_ready = true; p->have_detail = false;
+    p->ws = ws; p->ws_ready = true; p->have_detail = false; p->max_blocks = max_blocks;
     p->comp_ready = false;              // the completion parameters lived in the workspace bound before
     p->ranges.clear();
     p->best_dirty = true;
@@ -496,7 +499,36 @@ extern "C" int tessel_eval_candidates(tessel_problem *p, uint64_t first, uint64_
     p->best_dirty = true;
     if (!p->ranges.empty() && p->ranges.back().first + p->ranges.back().second == first) p->ranges.back().second += count;
     else p->ranges.push_back({first, count});
-    int e = launch_eval(p->kp, first, count, workspace_dev, p->num_cus, st, p->safe_pieces ? kSafePerLaunch : kMaxPerLaunch);
+    int e = launch_eval(p->kp, first, count, workspace_dev, p->num_cus, p->max_blocks, st, p->safe_pieces ? kSafePerLaunch : kMaxPerLaunch);
+    return e ? hip_fail(p, e) : TESSEL_OK;
+}
+
+// tessel_eval_candidates in the library's own device buffer: no allocation anywhere on the way
+extern "C" int tessel_eval_candidates_noalloc(tessel_problem *p, uint64_t first, uint64_t count, void *hip_stream)
+{
+    if (!p) return TESSEL_E_INVALID_ARG;
+    int rc = range_ok(p, first, count);
+    if (rc) return rc;
+    if (count > TESSEL_NOALLOC_MAX_CANDIDATES) return TESSEL_E_TOOBIG;
+    rc = ensure_device(p);
+    if (rc) return rc;
+    void *ws = nullptr;
+    size_t bytes = 0;
+    int e = scratch_workspace(&ws, &bytes);
+    if (e) return hip_fail(p, e);
+    const int blocks = eval_blocks_that_fit(p->kp, p->num_cus, bytes);
+    if (blocks < 1) return TESSEL_E_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // (a buffer bound with another grid limit, i.e. by the other entry point, cannot be this one: no rebinding check needed)
+    rc = bind_workspace(p, ws, bytes, st, blocks);
+    if (rc) return rc;
+    p->stream = st;
+    p->have_detail = false;
+    if (count == 0) return TESSEL_OK;
+    p->best_dirty = true;
+    if (!p->ranges.empty() && p->ranges.back().first + p->ranges.back().second == first) p->ranges.back().second += count;
+    else p->ranges.push_back({first, count});
+    e = launch_eval(p->kp, first, count, ws, p->num_cus, p->max_blocks, st, p->safe_pieces ? kSafePerLaunch : kMaxPerLaunch);
     return e ? hip_fail(p, e) : TESSEL_OK;
 }
 
@@ -512,7 +544,7 @@ extern "C" int tessel_score_candidates(tessel_problem *p, uint64_t first, uint64
     if (rc) return rc;
     p->stream = st;
     if (count == 0) return TESSEL_OK;
-    int e = launch_score(p->kp, first, count, code_dev, peak_dev, workspace_dev, p->num_cus, p->force_general, st);
+    int e = launch_score(p->kp, first, count, code_dev, peak_dev, workspace_dev, p->num_cus, p->max_blocks, p->force_general, st);
     return e ? hip_fail(p, e) : TESSEL_OK;
 }
 
@@ -552,7 +584,7 @@ static int fetch_best(tessel_problem *p)
         int le = launch_reset(p->ws, p->stream);
         if (le) return hip_fail(p, le);
         for (const auto &r : p->ranges) {
-            le = launch_eval(p->kp, r.first, r.second, p->ws, p->num_cus, p->stream, kSafePerLaunch);
+            le = launch_eval(p->kp, r.first, r.second, p->ws, p->num_cus, p->max_blocks, p->stream, kSafePerLaunch);
             if (le) return hip_fail(p, le);
         }
         e = hipStreamSynchronize(p->stream);

@@ -199,11 +199,16 @@ static_assert(sizeof(DevDetail) <= kWsParamsOff - kWsDetailOff, "detail record m
 struct LaunchShape { int blocks, threads; size_t lds_bytes; };
 
 // kernels.hip
-LaunchShape eval_launch_shape(const KParams &kp, int num_cus);
-size_t eval_workspace_bytes(const KParams &kp, int num_cus);    // everything launch_eval / launch_score touch
-int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream, uint64_t max_piece);
+// max_blocks: 0, or the most workgroups the workspace has queues for
+LaunchShape eval_launch_shape(const KParams &kp, int num_cus, int max_blocks);
+size_t eval_workspace_bytes(const KParams &kp, int num_cus, int max_blocks);    // everything launch_eval / launch_score touch
+int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, int max_blocks, void *stream, uint64_t max_piece);
 int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *ws, int num_cus,
-                 bool general, void *stream);
+                 int max_blocks, bool general, void *stream);
+// the library's own workspace on the current device (no allocation), and the grid that fits a workspace
+constexpr size_t kScratchBytes = (size_t)24 << 20;
+int scratch_workspace(void **ptr, size_t *bytes);
+int eval_blocks_that_fit(const KParams &kp, int num_cus, size_t bytes);
 int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream);
 int launch_reset(void *ws, void *stream);
 // completion search: S = state words per lane; returns 0 or a HIP error (negative: LDS need exceeds the device's)

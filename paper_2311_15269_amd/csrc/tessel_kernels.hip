@@ -1607,7 +1607,7 @@ static size_t fast_lds_bytes(const KParams &kp)
            (share ? 0 : (size_t)(fast_dm(kp) * 2 + ntok) * kWave * 4);
 }
 
-LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
+LaunchShape eval_launch_shape(const KParams &kp, int num_cus, int max_blocks)
 {
     LaunchShape s;
     s.threads = kWave;
@@ -1627,6 +1627,7 @@ LaunchShape eval_launch_shape(const KParams &kp, int num_cus)
     }
     if (per_cu < 1) per_cu = 1;
     s.blocks = num_cus * per_cu;
+    if (max_blocks > 0 && s.blocks > max_blocks) s.blocks = max_blocks;      // a workspace with room for fewer queues
     return s;
 }
 
@@ -1661,9 +1662,9 @@ static size_t ring_offset(int blocks, int num_cus)
     return (kWsBlockRecOff + (eval > comp ? eval : comp) + 256 + 255) & ~(size_t)255;
 }
 
-size_t eval_workspace_bytes(const KParams &kp, int num_cus)
+size_t eval_workspace_bytes(const KParams &kp, int num_cus, int max_blocks)
 {
-    const LaunchShape s = eval_launch_shape(kp, num_cus);
+    const LaunchShape s = eval_launch_shape(kp, num_cus, max_blocks);
     return ring_offset(s.blocks, num_cus) + (pick_fast(kp) ? (size_t)s.blocks * 3 * ring_words(kp) * 4 : 0);
 }
 
@@ -1684,13 +1685,13 @@ static int launch_general(const KParams &kp, const KParams *kp_dev, uint64_t fir
 // Scores [first, first+count).  Where the problem allows it: the fast kernel (a short eigenvector search, a longer one
 // for the candidates that did not converge), then the general kernel over what it could not finish (next to nothing).  Otherwise the general kernel alone.  Returns the number of block records written (recs may be
 // null: per-candidate outputs only) or a negative HIP error.
-static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, BlockRec *recs, int32_t *code,
-                       int32_t *peak, bool general, hipStream_t st)
+static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, int max_blocks, BlockRec *recs,
+                       int32_t *code, int32_t *peak, bool general, hipStream_t st)
 {
     const KParams *kp_dev = (const KParams *)((char *)ws + kWsParamsOff);
     DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
     uint64_t *list = (uint64_t *)((char *)ws + kWsListOff);
-    LaunchShape s = eval_launch_shape(kp, num_cus);
+    LaunchShape s = eval_launch_shape(kp, num_cus, max_blocks);
     uint64_t need = (count + kWave - 1) / kWave;
     const int blocks = need < (uint64_t)s.blocks ? (int)need : s.blocks;
     if (blocks < 1) return 0;
@@ -1710,7 +1711,7 @@ static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *
     return rc ? -rc : blocks + kDeferBlocks;
 }
 
-int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, void *stream, uint64_t max_piece)
+int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int num_cus, int max_blocks, void *stream, uint64_t max_piece)
 {
     hipStream_t st = (hipStream_t)stream;
     BlockRec *recs = (BlockRec *)((char *)ws + kWsBlockRecOff);
@@ -1718,7 +1719,7 @@ int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int
     // pieces of at most max_piece candidates, so that the lists of unfinished candidates stay small
     for (uint64_t done = 0; done < count;) {
         const uint64_t piece = count - done < max_piece ? count - done : max_piece;
-        int n = launch_pass(kp, first + done, piece, ws, num_cus, recs, nullptr, nullptr, false, st);
+        int n = launch_pass(kp, first + done, piece, ws, num_cus, max_blocks, recs, nullptr, nullptr, false, st);
         if (n < 0) return -n;
         if (n > 0) {
             hipLaunchKernelGGL(merge_kernel, dim3(1), dim3(kWave), 0, st, recs, n, res);
@@ -1731,7 +1732,7 @@ int launch_eval(const KParams &kp, uint64_t first, uint64_t count, void *ws, int
 }
 
 int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *code, int32_t *peak, void *ws, int num_cus,
-                 bool general, void *stream)
+                 int max_blocks, bool general, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
     DevResult *res = (DevResult *)((char *)ws + kWsResultOff);
@@ -1739,7 +1740,7 @@ int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *cod
     const uint64_t max_piece = kSafePerLaunch;
     for (uint64_t done = 0; done < count;) {
         const uint64_t piece = count - done < max_piece ? count - done : max_piece;
-        int n = launch_pass(kp, first + done, piece, ws, num_cus, nullptr, code + done, peak ? peak + done : nullptr, general, st);
+        int n = launch_pass(kp, first + done, piece, ws, num_cus, max_blocks, nullptr, code + done, peak ? peak + done : nullptr, general, st);
         if (n < 0) return -n;
         hipLaunchKernelGGL(clear_defer_kernel, dim3(1), dim3(1), 0, st, res);
         int rc = (int)hipGetLastError();
@@ -1763,6 +1764,44 @@ int launch_reset(void *ws, void *stream)
 }
 
 size_t block_rec_bytes(int blocks) { return (size_t)blocks * sizeof(BlockRec); }
+
+// ------------------------------------------------------------------ a workspace the library holds itself
+// For callers that cannot allocate device memory: one buffer per GPU, part of the code object, shared by every call
+// on that GPU (it keeps the last call's contents; the kernels clear what has to start at zero).  In host code the
+// array's name stands for the symbol, not for device memory: its address on the current device comes from
+// hipGetSymbolAddress, once per device.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kScratchBytes];
+
+int scratch_workspace(void **ptr, size_t *bytes)
+{
+    constexpr int kMaxGpus = 64;
+    static void *address[kMaxGpus] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= kMaxGpus) return (int)hipErrorInvalidDevice;
+    if (!address[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        address[dev] = p;
+    }
+    *ptr = address[dev];
+    *bytes = kScratchBytes;
+    return 0;
+}
+
+// the largest grid of the scoring kernels whose records and queues fit `bytes`; 0: not even one workgroup
+int eval_blocks_that_fit(const KParams &kp, int num_cus, size_t bytes)
+{
+    const size_t per_block = sizeof(BlockRec) + (pick_fast(kp) ? (size_t)3 * ring_words(kp) * 4 : 0);
+    const size_t fixed = ring_offset(0, num_cus) + 512;
+    if (bytes < fixed + per_block) return 0;
+    int blocks = (int)std::min<size_t>((bytes - fixed) / per_block, (size_t)num_cus * 16);
+    while (blocks > 0 && eval_workspace_bytes(kp, num_cus, blocks) > bytes) blocks--;
+    return blocks;
+}
 
 
 // ==================================================================== searched completion
