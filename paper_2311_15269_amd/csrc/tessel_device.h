@@ -108,7 +108,7 @@ struct KParams {
     int32_t  eigen_tries;        // window sweeps a candidate gets at first, and
     int32_t  retry_tries;        // ... from the start again when those found no eigenvector (both: test knobs)
     // blocks on several devices in the fast kernel: such a type has one code on every device it occupies
-    int32_t  fast_tp;            // the problem has such blocks (the fast kernel then only builds; periods by the general kernel)
+    int32_t  fast_tp;            // the problem has such blocks (the TP variants of the fast kernel take it)
     int32_t  ntp;                // number of such types
     uint32_t tp_group[kMaxD];    // their codes, one mask per type
     uint32_t slow_mask;          // codes of types that sit on several devices or whose consumer does
