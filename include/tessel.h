@@ -226,7 +226,7 @@ int  tessel_complete_schedule(tessel_problem *p, tessel_schedule *out);
  * last tessel_eval_candidates call, in the workspace bound there.  A new best window, N or J restarts the
  * running best.  Errors: NO_FEASIBLE, RANGE (fewer than one window fits), INVALID_ARG,
  * TOOBIG (state of N micro-batches does not fit the LDS, N * sum of t exceeds 16 bits, N > 1023 or J > 63),
- * UNSUPPORTED (|m| > 127), HIP. */
+ * UNSUPPORTED (|m| > 127; a dependency graph that is not a set of chains), HIP. */
 int  tessel_search_completions(tessel_problem *p, int32_t num_microbatches, int32_t jitter, uint64_t first,
                                uint64_t count);
 /* makespan_dev[k] (device, int32) = makespan of completion candidate first+k, INT32_MAX where the greedy rule

@@ -193,7 +193,12 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
     if (D > kMaxD || K > kMaxK || NR > kMaxNR) return TESSEL_E_UNSUPPORTED;
     std::vector<int> indeg(K, 0), outdeg(K, 0);
     for (int e = 0; e < desc->num_deps; e++) { outdeg[desc->dep_src[e]]++; indeg[desc->dep_dst[e]]++; }
-    for (int i = 0; i < K; i++) if (indeg[i] > 1 || outdeg[i] > 1) return TESSEL_E_UNSUPPORTED;   // chains only
+    // disjoint chains take the fast kernel and the chain path of the general one; any other graph (Sec. III-A allows
+    // any acyclic one) the general kernel's path for graphs, which TESSEL_FORCE_DAG=1 also forces on chains (tests)
+    bool chains = true;
+    for (int i = 0; i < K; i++) if (indeg[i] > 1 || outdeg[i] > 1) chains = false;
+    { const char *fd = getenv("TESSEL_FORCE_DAG"); if (fd && fd[0] == '1') chains = false; }
+    if (!chains && desc->num_deps > kMaxDeps) return TESSEL_E_UNSUPPORTED;
 
     tessel_problem *p = new (std::nothrow) tessel_problem();
     if (!p) return TESSEL_E_INVALID_ARG;
@@ -209,27 +214,64 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
     kp.seed = desc->seed; kp.step_q16 = desc->lead_step_q16;
     kp.has_fixed = desc->fixed_leads != nullptr;
     for (int i = 0; i < K; i++) { kp.pred[i] = -1; kp.succ[i] = -1; kp.fixed[i] = desc->fixed_leads ? (uint8_t)desc->fixed_leads[i] : 0; }
-    for (int e = 0; e < desc->num_deps; e++) {
+    for (int e = 0; e < desc->num_deps && chains; e++) {
         int a = desc->dep_src[e], b = desc->dep_dst[e];
         kp.succ[a] = (int8_t)b; kp.pred[b] = (int8_t)a;
         kp.edge_out[a] = (uint8_t)e;
         kp.cross_out[a] = desc->dev_mask[a] != desc->dev_mask[b];
     }
-    // chains and their token slots; reverse topological order = walk every chain from its end
-    std::vector<int> path_of(K, -1);
-    int npaths = 0, nrt = 0;
-    for (int i = 0; i < K; i++) if (kp.pred[i] < 0) {
-        int len = 0;
-        for (int g = i; g >= 0; g = kp.succ[g]) { path_of[g] = npaths; len++; }
-        npaths++;
-        (void)len;
+    if (!chains) {
+        kp.dag = 1; kp.ndeps = desc->num_deps;
+        kp.dag_tries = 8;
+        if (const char *env = getenv("TESSEL_DAG_TRIES")) {        // test knob: 0 leaves every period to the bisection
+            int v = atoi(env);
+            if (v >= 0 && v <= 64) kp.dag_tries = v;
+        }
+        for (int i = 0; i < K; i++) { kp.t_type[i] = desc->time[i]; kp.mask_type[i] = desc->dev_mask[i]; kp.tokbase[i] = 0xFF; }
+        for (int e = 0; e < desc->num_deps; e++) {
+            const int a = desc->dep_src[e], b = desc->dep_dst[e];
+            kp.dsrc[e] = (uint8_t)a; kp.ddst[e] = (uint8_t)b; kp.dcross[e] = desc->dev_mask[a] != desc->dev_mask[b];
+            kp.predmask[b] |= 1u << a;
+        }
+        // every type somebody consumes keeps the end times of its blocks by micro-batch: 2 N_R slots behind the devices
+        for (int i = 0; i < K; i++) if (outdeg[i] > 0) {
+            const int base = D + kp.ntok * 2 * NR;
+            if (base + 2 * NR > 255) { delete p; return TESSEL_E_UNSUPPORTED; }
+            kp.tokbase[i] = (uint8_t)base;
+            kp.ntok++;
+        }
+        // consumers before producers
+        std::vector<int> left(outdeg), done(K, 0);
+        int n = 0;
+        for (bool again = true; again;) {
+            again = false;
+            for (int i = 0; i < K; i++) if (!done[i] && left[i] == 0) {
+                done[i] = 1; kp.rtopo[n++] = (uint8_t)i; again = true;
+                for (int e = 0; e < desc->num_deps; e++) if (desc->dep_dst[e] == i) left[desc->dep_src[e]]--;
+            }
+        }
     }
-    for (int i = 0; i < K; i++) if (kp.succ[i] < 0)
-        for (int g = i; g >= 0; g = kp.pred[g]) kp.rtopo[nrt++] = (uint8_t)g;
-    kp.npaths = npaths;
-    kp.nslots = D + npaths * 2 * NR;
-    kp.nsweeps = D + npaths * NR + 1;
-    if (kp.nslots > 63 || kp.nsweeps - 1 > 24) { delete p; return TESSEL_E_UNSUPPORTED; }
+    // chains and their token slots; reverse topological order = walk every chain from its end
+    std::vector<int> path_of(K, 0);
+    int npaths = 0, nrt = 0;
+    if (chains) {
+        for (int i = 0; i < K; i++) if (kp.pred[i] < 0) {
+            for (int g = i; g >= 0; g = kp.succ[g]) path_of[g] = npaths;
+            npaths++;
+        }
+        for (int i = 0; i < K; i++) if (kp.succ[i] < 0)
+            for (int g = i; g >= 0; g = kp.pred[g]) kp.rtopo[nrt++] = (uint8_t)g;
+        kp.npaths = npaths;
+        kp.nslots = D + npaths * 2 * NR;
+        kp.nsweeps = D + npaths * NR + 1;
+        if (kp.nslots > 63 || kp.nsweeps - 1 > 24) { delete p; return TESSEL_E_UNSUPPORTED; }
+    } else {
+        kp.npaths = 0;
+        kp.nslots = D + kp.ntok * 2 * NR;
+        kp.nsweeps = D + 1;                       // (only sizes the register arrays of the chain path, unused here)
+        // state and program of a workgroup must fit the LDS a kernel may ask for
+        if ((size_t)4 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)K * NR * kWave * 2 > 64 * 1024) { delete p; return TESSEL_E_UNSUPPORTED; }
+    }
     int sumt = 0;
     for (int i = 0; i < K; i++) {
         if (desc->time[i] > (1 << 20)) { delete p; return TESSEL_E_TOOBIG; }
@@ -253,6 +295,7 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
             kp.tok_of[d] |= (uint32_t)(D + path_of[i] * 2 * NR) << (8 * n);
             kp.home_of[d] |= (uint32_t)home[i] << (8 * n);
             kp.t_of[d][n] = desc->time[i];
+            kp.predmask_of[d][n] = kp.predmask[i];
             kp.m_of[d][n] = desc->mem[i];
             busy += desc->time[i];
             n++;
@@ -267,7 +310,7 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
     }
     // tables of the fast kernel: single-device blocks, small memory deltas, few slots
     {
-        bool ok = kp.nslots <= 32 && kp.nsweeps - 1 <= 24;
+        bool ok = chains && kp.nslots <= 32 && kp.nsweeps - 1 <= 24;
         // every (device, local symbol) is a code; a type on several devices has one code per device
         std::vector<std::vector<int>> code_on(K, std::vector<int>(D, -1));
         for (int d = 0; d < D; d++)
@@ -794,6 +837,7 @@ extern "C" int tessel_complete_schedule(tessel_problem *p, tessel_schedule *out)
 static int bind_completion(tessel_problem *p, int N, int J)
 {
     if (p->ws && p->ws_ready && !owns_workspace(p)) return TESSEL_E_WORKSPACE;      // the buffer is another handle's by now
+    if (p->kp.dag) return TESSEL_E_UNSUPPORTED;          // the completion search follows chains (the greedy completion does not)
     if (p->comp_ready && !p->best_dirty && p->comp_index == p->result.index && p->result.period != INT_MAX && p->comp.N == N &&
         p->comp.J == J)
         return TESSEL_OK;                                   // nothing new since the best was fetched: no wait

@@ -2,6 +2,7 @@
 // block that carries one problem's static tables, and the records the kernels write.
 // (Not part of the public ABI; the oracle does not see this file.)
 #pragma once
+#include <stddef.h>
 #include <stdint.h>
 
 #if defined(__HIPCC__)
@@ -49,6 +50,7 @@ constexpr int kMaxLT = 4;        // block types per device
 constexpr int kMaxNR = 8;        // micro-batches per window
 constexpr int kMaxK = 32;        // block types
 constexpr int kMaxPos = kMaxLT * kMaxNR;   // blocks per device and window (32)
+constexpr int kMaxDeps = 64;      // dependencies of a micro-batch whose graph is not a set of chains
 constexpr int kNumStatus = 6;
 constexpr int kWave = 64;
 
@@ -114,6 +116,18 @@ struct KParams {
     uint32_t slow_mask;          // codes of types that sit on several devices or whose consumer does
     uint32_t grp_code[kMaxK];    // by code: all codes of the same type
     uint8_t  home_code[kMaxK];   // by code: the type's code on its lowest device (63: no such code)
+    // Dependency graphs that are not disjoint chains (a block type with several producers or consumers): scored by the
+    // general kernel's DAG path, tables by type id
+    int32_t  dag;                // the problem takes that path
+    int32_t  ndeps;
+    int32_t  dag_tries;          // sweeps of the eigenvector search before the bisection takes over (test knob)
+    int32_t  ntok;               // types somebody consumes: each has a ring of 2 N_R end times behind the D device slots
+    int32_t  t_type[kMaxK];
+    uint32_t mask_type[kMaxK];   // devices of the type
+    uint32_t predmask[kMaxK];    // its producers
+    uint8_t  tokbase[kMaxK];     // first slot of its ring, 0xFF: nobody consumes it
+    uint8_t  dsrc[kMaxDeps], ddst[kMaxDeps], dcross[kMaxDeps];   // the dependencies in the caller's order
+    uint32_t predmask_of[kMaxD][kMaxLT];   // producers of local symbol y of device d
     const int8_t   *leadtab;     // CANONICAL: [nlead][K] in device memory
     const uint64_t *wtab;        // CANONICAL: arrangements by remaining counts, base NR+1 digits
 };

@@ -67,6 +67,13 @@ struct Mu {
 
 __device__ __forceinline__ uint32_t byte_of(uint32_t packed, uint32_t y) { return (packed >> (8u * y)) & 0xFFu; }
 
+__device__ __forceinline__ uint32_t sel4u(const uint32_t (&v)[kMaxLT], uint32_t y)
+{
+    uint32_t a = y & 1u ? v[1] : v[0];
+    uint32_t b = y & 1u ? v[3] : v[2];
+    return y & 2u ? b : a;
+}
+
 __device__ __forceinline__ int sel4(const int32_t (&v)[kMaxLT], uint32_t y)
 {
     int a = y & 1u ? v[1] : v[0];
@@ -262,6 +269,10 @@ __device__ __forceinline__ int decode_candidate(const KParams &P, uint64_t idx, 
         }
         if (dup) return kDup;
         if (tpm) return kTpMismatch;
+        if (P.dag) {
+            for (int e = 0; e < P.ndeps; e++)
+                if (mu.get(P.dsrc[e]) < mu.get(P.ddst[e])) return kProp2;
+        } else
         for (int g = 0; g < P.K; g++) {
             int p = P.pred[g];
             if (p >= 0 && mu.get((uint32_t)p) < mu.get((uint32_t)g)) return kProp2;
@@ -300,6 +311,19 @@ __device__ __forceinline__ int decode_candidate(const KParams &P, uint64_t idx, 
         const uint32_t a = (uint32_t)z, b = (uint32_t)(z >> 32);
         if (P.has_fixed) {
             for (int g = 0; g < P.K; g++) mu.set((uint32_t)g, P.fixed[g]);
+        } else if (P.dag) {
+            // consumers before producers: a type's lead is the largest (consumer's lead + step) over its dependencies
+            for (int k = 0; k < P.K; k++) {
+                const uint32_t i = P.rtopo[k];
+                uint32_t lead = 0;
+                for (int e = 0; e < P.ndeps; e++) {
+                    if (P.dsrc[e] != i) continue;
+                    const uint32_t u = (stream_word(a, b, (kDrawLeadBase + (uint32_t)e) >> 1) >> (16u * ((uint32_t)e & 1u))) & 0xFFFFu;
+                    const uint32_t step = (P.dcross[e] && u < P.step_q16) ? 1u : 0u;
+                    lead = max(lead, mu.get(P.ddst[e]) + step);
+                }
+                mu.set(i, min(NR - 1u, lead));
+            }
         } else {
             for (int k = 0; k < P.K; k++) {
                 uint32_t i = P.rtopo[k];
@@ -482,6 +506,239 @@ __device__ __forceinline__ int evaluate(const KParams &P, uint64_t idx, uint16_t
         }
     period = P.tp ? least_period<VM, true>(P, prog, state, t_tab, mask_tab, live)
                   : least_period<VM, false>(P, prog, state, t_tab, mask_tab, live);
+    return kOk;
+}
+
+// ------------------------------------------------------------------ dependency graphs that are not chains
+// A block type may have several producers and several consumers (Sec. III-A, Eq. 1 [3]).  State of a sweep, in LDS
+// [slot][lane]: the D device times, then for every type somebody consumes a ring of 2 N_R end times by micro-batch
+// (micro-batches N_R and up belong to the next window and move down at the window boundary).  Program entry: type id
+// in bits 0-4, micro-batch in bits 5-8.  Tables by type id in LDS: t, device mask, producer mask, first ring slot.
+struct DagTables { const int32_t *t; const uint32_t *mask, *pred, *tok; };
+
+__device__ __forceinline__ void sweep_window_dag(const KParams &P, const DagTables &Tb, const uint16_t *prog, uint32_t *state)
+{
+    const int total = P.total;
+    for (int k = 0; k < total; k++) {
+        const uint32_t e = prog[k * kWave];
+        const uint32_t g = e & 31u, m = e >> 5;
+        uint32_t s = 0;
+        for (uint32_t rest = Tb.mask[g]; rest; rest &= rest - 1u) s = max(s, state[__builtin_ctz(rest) * kWave]);
+        for (uint32_t rest = Tb.pred[g]; rest; rest &= rest - 1u) s = max(s, state[(Tb.tok[__builtin_ctz(rest)] + m) * kWave]);
+        const uint32_t en = s + (uint32_t)Tb.t[g];
+        for (uint32_t rest = Tb.mask[g]; rest; rest &= rest - 1u) state[__builtin_ctz(rest) * kWave] = en;
+        if (Tb.tok[g] != 0xFFu) state[(Tb.tok[g] + m) * kWave] = en;
+    }
+}
+
+// The window boundary: every ring moves down by N_R micro-batches and the device times stay, all less `shift` (0, or
+// the period under test: times are then taken from the start of the next window, not below 0).  Returns whether every
+// value that crosses the boundary and means anything grew by `want` over the window (`first`: by any one amount,
+// which is handed back in `want`): ring entries below the type's lead (handled before the window by the producer),
+// compared in place with what the last boundary left there; device times against `prevfree`.
+template <int DM>
+__device__ __forceinline__ bool boundary_dag(const KParams &P, const DagTables &Tb, uint32_t *state, const Mu &lead, uint32_t (&prevfree)[DM],
+                                             uint32_t shift, bool first, uint32_t &want, uint32_t &top)
+{
+    bool same = true, have = !first;
+    top = 0;
+#pragma unroll
+    for (int d = 0; d < DM; d++) {
+        if (d >= P.D) continue;
+        const uint32_t x = state[d * kWave], y = x > shift ? x - shift : 0u;
+        if (P.ntd[d] > 0) {
+            const uint32_t dv = y - prevfree[d];
+            if (!have) { want = dv; have = true; } else if (dv != want) same = false;
+        }
+        prevfree[d] = y; state[d * kWave] = y;
+        top = max(top, y);
+    }
+    for (int g = 0; g < P.K; g++) {
+        const uint32_t base = Tb.tok[g];
+        if (base == 0xFFu) continue;
+        const uint32_t lg = lead.get((uint32_t)g);
+        for (int m = 0; m < P.NR; m++) {
+            const uint32_t old = state[(base + m) * kWave], x = state[(base + m + P.NR) * kWave];
+            const uint32_t y = x > shift ? x - shift : 0u;
+            if ((uint32_t)m < lg) {
+                const uint32_t dv = y - old;
+                if (!have) { want = dv; have = true; } else if (dv != want) same = false;
+                top = max(top, y);
+            }
+            state[(base + m) * kWave] = (uint32_t)m < lg ? y : 0u;
+            state[(base + m + P.NR) * kWave] = 0;
+        }
+    }
+    return same && have;
+}
+
+// Least period of the repeated window.  First the eigenvector search of the other kernels (sweeps from 0 until every
+// boundary value grows by the same amount, which is then the period); if that does not settle, the definition: the
+// least T in [LB, UB] for which start times exist, by bisection; start times exist for T iff the sweeps from 0, with
+// every boundary value taken T later each time, come to rest (Kleene iteration of the longest-path equations; it
+// rests after at most as many windows as values cross the boundary, or passes UB).
+template <int DM>
+__device__ __forceinline__ int least_period_dag(const KParams &P, const DagTables &Tb, const uint16_t *prog, uint32_t *state, const Mu &lead)
+{
+    uint32_t prevfree[DM];
+    auto reset = [&]() {
+        for (int s = 0; s < P.nslots; s++) state[s * kWave] = 0;
+#pragma unroll
+        for (int d = 0; d < DM; d++) prevfree[d] = 0;
+    };
+    reset();
+    bool done = false;
+    uint32_t T = 0;
+    for (int j = 0; j < P.dag_tries; j++) {
+        if (__ballot(!done) == 0) break;
+        sweep_window_dag(P, Tb, prog, state);
+        uint32_t delta = 0, top;
+        const bool eig = boundary_dag<DM>(P, Tb, state, lead, prevfree, 0u, true, delta, top);
+        if (!done && eig) { T = delta; done = true; }
+    }
+    if (__ballot(!done) == 0) return (int)T;
+    // bisection, the same number of steps in every lane; lanes that have their period keep a fixed interval
+    int crossing = P.D;
+    for (int g = 0; g < P.K; g++) if (Tb.tok[g] != 0xFFu) crossing += (int)lead.get((uint32_t)g);
+    uint32_t lo = done ? T : (uint32_t)P.LB, hi = done ? T : (uint32_t)P.UB;
+    int steps = 0;
+    for (uint32_t span = (uint32_t)(P.UB - P.LB); span; span >>= 1) steps++;
+    for (int it = 0; it < steps; it++) {
+        const uint32_t mid = lo + (hi - lo) / 2u;
+        const bool open = lo < hi;
+        reset();
+        bool decided = !open, feasible = false;
+        // (crossing + 2 windows bound the iteration; the loop runs until every lane of the wave has decided)
+        for (int w = 0; w < kMaxK * kMaxNR + kMaxD + 2; w++) {
+            if (__ballot(!decided) == 0) break;
+            sweep_window_dag(P, Tb, prog, state);
+            uint32_t zero = 0, top;
+            const bool rest = boundary_dag<DM>(P, Tb, state, lead, prevfree, mid, false, zero, top);
+            if (!decided) {
+                if (rest) { decided = true; feasible = true; }
+                else if (top > (uint32_t)P.UB || w > crossing + 1) { decided = true; feasible = false; }
+            }
+        }
+        if (open) { if (feasible) hi = mid; else lo = mid + 1u; }
+    }
+    return (int)hi;
+}
+
+// One candidate of a problem whose dependency graph is not a set of chains (general kernel only).
+template <int DM>
+__device__ __forceinline__ int evaluate_dag(const KParams &P, const DagTables &Tb, uint64_t idx, uint16_t *prog, uint32_t *state,
+                                            int &period, int (&peak)[DM], DevDetail *detail)
+{
+    uint64_t rem[DM];
+    int remlen[DM];
+    Mu mu;
+    period = 0;
+#pragma unroll
+    for (int d = 0; d < DM; d++) peak[d] = 0;
+    {
+        int st = decode_candidate<DM>(P, idx, rem, remlen, mu);
+        if (st != kOk) return st;
+    }
+    const Mu lead = mu;
+    if (detail) {
+        for (int g = 0; g < P.K; g++) detail->leads[g] = (int)mu.get((uint32_t)g);
+        for (int d = 0; d < kMaxD; d++) detail->order_len[d] = 0;
+    }
+    int memcur[DM];
+#pragma unroll
+    for (int d = 0; d < DM; d++) {
+        memcur[d] = 0;
+        if (d < P.D)
+            for (int y = 0; y < P.ntd[d]; y++)
+                memcur[d] += P.m_of[d][y] * (int)mu.get(byte_of(P.type_of[d], (uint32_t)y));
+        peak[d] = INT_MIN;
+    }
+    const bool repair = P.space == kSampledRepair;
+    int placed = 0;
+    const int total = P.total;
+    // a block may run when every producer has handled its micro-batch: in this window (counter ahead) or in the last
+    // one (micro-batch below the producer's lead, which the counter is ahead of too)
+    auto ready = [&](uint32_t g, uint32_t preds) -> bool {
+        const uint32_t mg = mu.get(g);
+        bool ok = true;
+        for (uint32_t rest = preds; rest; rest &= rest - 1u) ok = ok && mu.get((uint32_t)__builtin_ctz(rest)) > mg;
+        return ok;
+    };
+    auto place = [&](uint32_t g, uint32_t mask, int m, uint32_t pos_d, int d_static) {
+        prog[placed * kWave] = (uint16_t)(g | (mu.get(g) << 5));
+        mu.inc(g);
+        placed++;
+#pragma unroll
+        for (int dd = 0; dd < DM; dd++) {
+            if (dd >= P.D || !((mask >> dd) & 1u)) continue;
+            uint32_t pos = 0;
+            if (dd == d_static) pos = pos_d;
+            else if (pos_d != 0xFFFFFFFFu && repair) {
+                uint32_t ysym = 0;
+                for (int y = 0; y < P.ntd[dd]; y++) if (byte_of(P.type_of[dd], (uint32_t)y) == g) ysym = (uint32_t)y;
+                pos = find_first(rem[dd], (uint32_t)remlen[dd], ysym);
+            }
+            rem[dd] = remove_at(rem[dd], pos);
+            remlen[dd]--;
+            memcur[dd] += m;
+            peak[dd] = max(peak[dd], memcur[dd]);
+            if (detail) detail->orders[dd][detail->order_len[dd]++] = (int)g;
+        }
+    };
+    bool deadlock = false;
+    while (placed < total && !deadlock) {
+        bool progress = false;
+#pragma unroll
+        for (int d = 0; d < DM; d++) {
+            if (d >= P.D || remlen[d] == 0) continue;
+            const uint32_t y = (uint32_t)rem[d] & 3u;
+            const uint32_t g = byte_of(P.type_of[d], y), mask = byte_of(P.mask_of[d], y);
+            bool ok = ready(g, sel4u(P.predmask_of[d], y));
+            if (mask != (1u << d)) {
+                // a multi-device block runs when it heads the list of all its devices; it is placed from its lowest device
+                if ((mask & ((1u << d) - 1u)) != 0) ok = false;
+#pragma unroll
+                for (int dd = 0; dd < DM; dd++) {
+                    if (dd >= P.D || dd == d || !((mask >> dd) & 1u)) continue;
+                    if (!(remlen[dd] > 0 && byte_of(P.type_of[dd], (uint32_t)rem[dd] & 3u) == g)) ok = false;
+                }
+            }
+            if (ok) { place(g, mask, sel4(P.m_of[d], y), 0u, d); progress = true; }
+        }
+        if (progress) continue;
+        if (!repair) { deadlock = true; break; }
+        bool done = false;
+#pragma unroll
+        for (int d = 0; d < DM; d++) {
+            if (done || d >= P.D || remlen[d] == 0) continue;
+            uint32_t best_pos = 64u, best_y = 0;
+#pragma unroll
+            for (int y = 0; y < kMaxLT; y++) {
+                if (y >= P.ntd[d]) continue;
+                const bool ok = ready(byte_of(P.type_of[d], (uint32_t)y), P.predmask_of[d][y]);
+                const uint32_t pos = ok ? find_first(rem[d], (uint32_t)remlen[d], (uint32_t)y) : 64u;
+                if (pos < best_pos) { best_pos = pos; best_y = (uint32_t)y; }
+            }
+            if (best_pos < 64u) {
+                place(byte_of(P.type_of[d], best_y), byte_of(P.mask_of[d], best_y), sel4(P.m_of[d], best_y), best_pos, d);
+                done = true;
+            }
+        }
+        if (!done) deadlock = true;         // cannot happen: unplaced blocks form a DAG
+    }
+    if (deadlock) {
+#pragma unroll
+        for (int d = 0; d < DM; d++) peak[d] = 0;
+        return kDeadlock;
+    }
+    int peak_max = INT_MIN;
+#pragma unroll
+    for (int d = 0; d < DM; d++) {
+        if (d >= P.D || peak[d] == INT_MIN) peak[d] = 0;
+        if (d < P.D) peak_max = max(peak_max, peak[d]);
+    }
+    if (peak_max > P.M) return kMem;
+    period = least_period_dag<DM>(P, Tb, prog, state, lead);
     return kOk;
 }
 
@@ -1422,10 +1679,18 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
     if (list) count = min(*list_count, kWsListCap);
     int32_t *t_tab = (int32_t *)lds;
     uint32_t *mask_tab = lds + kMaxK;
-    uint32_t *state_all = lds + 2 * kMaxK;
+    uint32_t *state_all = lds + 4 * kMaxK;
     uint16_t *prog_all = (uint16_t *)(state_all + P.nslots * kWave);
     const int lane = threadIdx.x;
-    if (lane < kMaxK) { t_tab[lane] = P.t_loc[lane]; mask_tab[lane] = P.mask_loc[lane]; }
+    // by home code for chain problems, by type id (with the producers and the token rings) for the others
+    DagTables Tb;
+    Tb.t = t_tab; Tb.mask = mask_tab; Tb.pred = lds + 2 * kMaxK; Tb.tok = lds + 3 * kMaxK;
+    if (lane < kMaxK) {
+        t_tab[lane] = P.dag ? P.t_type[lane] : P.t_loc[lane];
+        mask_tab[lane] = P.dag ? P.mask_type[lane] : P.mask_loc[lane];
+        lds[2 * kMaxK + lane] = P.predmask[lane];
+        lds[3 * kMaxK + lane] = P.tokbase[lane];
+    }
     __syncthreads();
     uint32_t *state = state_all + lane;
     uint16_t *prog = prog_all + lane;
@@ -1442,7 +1707,8 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
         const uint64_t idx = list ? list[kk] : first + kk;
         const uint64_t k = idx - first;
         int period, peak[DM];
-        int status = evaluate<DM, VM>(P, idx, prog, state, t_tab, mask_tab, period, peak, detail);
+        int status = P.dag ? evaluate_dag<DM>(P, Tb, idx, prog, state, period, peak, detail)
+                           : evaluate<DM, VM>(P, idx, prog, state, t_tab, mask_tab, period, peak, detail);
         nev++;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) cnt[s] += status == s;
@@ -1596,7 +1862,7 @@ static fast_fn pick_fast(const KParams &kp)
 
 static size_t general_lds_bytes(const KParams &kp)
 {
-    return (size_t)2 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)kp.total * kWave * 2;
+    return (size_t)4 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)kp.total * kWave * 2;
 }
 
 static size_t fast_lds_bytes(const KParams &kp)

@@ -116,4 +116,24 @@ def xshape_problem(p, tf, tb, nr, cap, space="sampled_repair", seed=0x7C0FFEE7, 
             "deps": deps, "space": space, "seed": seed, "lead_step_q16": lead_step_q16, "fixed_leads": None}
 
 
+def kshape_problem(nr, cap, tf=(2, 1, 3), tb=(4, 2, 6), space="sampled_repair", seed=0x8C0FFEE8, lead_step_q16=20000):
+    """Two branches that join (the K-shape of Sec. VI-A: two encoders feeding a joint stage): A on device 0 and B on
+    device 1 run side by side, J on device 2 needs both; the backward pass fans out again.  Types: A_F, B_F, J_F,
+    J_B, A_B, B_B; dependencies A_F -> J_F, B_F -> J_F, J_F -> J_B, J_B -> A_B, J_B -> B_B."""
+    t = [tf[0], tf[1], tf[2], tb[2], tb[0], tb[1]]
+    return {"name": "kshape-3dev", "D": 3, "K": 6, "NR": nr, "M": cap, "t": t, "m": [1, 1, 1, -1, -1, -1],
+            "dev_mask": [1, 2, 4, 4, 1, 2], "deps": [(0, 2), (1, 2), (2, 3), (3, 4), (3, 5)],
+            "space": space, "seed": seed, "lead_step_q16": lead_step_q16, "fixed_leads": None}
+
+
+def diamond_problem(nr, cap, space="sampled_repair", seed=0x9C0FFEE9, lead_step_q16=24000):
+    """A stage that feeds two parallel stages which join again, forward and backward, on 4 devices (fan-out and
+    fan-in on both passes): S_F(0) -> L_F(1), R_F(2) -> T_F(3) -> T_B(3) -> L_B(1), R_B(2) -> S_B(0)."""
+    t = [1, 2, 3, 1, 2, 4, 5, 2]
+    return {"name": "diamond-4dev", "D": 4, "K": 8, "NR": nr, "M": cap, "t": t, "m": [1, 1, 1, 1, -1, -1, -1, -1],
+            "dev_mask": [1, 2, 4, 8, 8, 2, 4, 1],
+            "deps": [(0, 1), (0, 2), (1, 3), (2, 3), (3, 4), (4, 5), (4, 6), (5, 7), (6, 7)],
+            "space": space, "seed": seed, "lead_step_q16": lead_step_q16, "fixed_leads": None}
+
+
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
