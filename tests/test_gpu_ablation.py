@@ -65,3 +65,50 @@ def test_bubble_rate_against_memory_cap(gpu):
     assert periods[4] == periods[6] == P * (TF + TB)       # the lower bound
     assert periods[1] >= periods[2] >= periods[3] >= periods[4]
     assert periods[2] > periods[4]
+
+
+def _whole_space(gpu, prob):
+    g = gpu.Problem(prob)
+    total = g.candidate_count()
+    for first in range(0, total, 1 << 22):
+        g.eval_candidates(first, min(1 << 22, total - first))
+    return g, g.best(), total
+
+
+def test_bubble_against_window_size_with_fan_in_and_fan_out(gpu):
+    """Placements whose micro-batch graph branches (two encoders feeding a joint stage, the K-shape of Sec. VI-A; a
+    diamond): whole canonical spaces, memory not limiting.  One micro-batch per window leaves a bubble (the branches
+    wait for each other: 2/5 and 3/7), two reach the bound of the busiest device, which no larger window can beat
+    (Table II lists no bubble for the searched schedule of the K-shape placement)."""
+    from oracle import Oracle
+    for make, per_microbatch, first_period in ((W.kshape_problem, 9, 15), (W.diamond_problem, 8, 14)):
+        periods = []
+        for nr in (1, 2, 3):
+            prob = make(nr, 100, space="canonical")
+            g, got, total = _whole_space(gpu, prob)
+            orc = Oracle(prob)
+            assert got["lower_bound"] == nr * per_microbatch == orc.lower_bound
+            if total <= 300000:                            # the oracle sweeps the small spaces whole
+                want = orc.sweep(0, total, threads=4)
+                assert (got["period"], got["index"], got["n_feasible"], got["n_reject"][1:]) == \
+                       (want["period"], want["index"], want["n_feasible"], want["n_reject"][1:])
+            ref = orc.eval_index(got["index"])
+            assert ref["status"] == 0 and ref["period"] == got["period"] and ref["peak"] == got["peak"]
+            periods.append(got["period"])
+        assert periods == [first_period, 2 * per_microbatch, 3 * per_microbatch]
+        bubbles = [1 - nr * per_microbatch / t for nr, t in zip((1, 2, 3), periods)]
+        assert bubbles[0] > 0.39 and bubbles[1] == bubbles[2] == 0
+
+
+def test_kshape_bubble_against_memory(gpu):
+    """The K-shape window of two micro-batches against the cap: one unit serialises the two micro-batches (twice the
+    critical path of one), two units already reach the bound; the period never grows with the cap."""
+    from oracle import Oracle
+    periods = []
+    for cap in (1, 2, 3, 6):
+        prob = W.kshape_problem(2, cap, space="canonical")
+        g, got, total = _whole_space(gpu, prob)
+        want = Oracle(prob).sweep(0, total)
+        assert (got["period"], got["index"], got["n_feasible"]) == (want["period"], want["index"], want["n_feasible"])
+        periods.append(got["period"])
+    assert periods == [30, 18, 18, 18]
