@@ -775,6 +775,10 @@ struct FastProgram {
 constexpr int kFastTableWords = 16 * kMaxK;      // uniform tables at the start of the fast kernel's LDS
 constexpr int kSweepTabWord = 12 * kMaxK;        // ... of which the sweeps' three tables by code; a multiple of 64 words, so
                                                  // that one two-address LDS read fetches a code's first and third word
+constexpr int kTpTableWords = 5 * kMaxK;         // the TP variants' own tables behind them
+// Everything a lane reads by a run-time index lies word by word: word w of entry i at w * 64 + i words, so that
+// lanes with different entries hit different banks, a lane's words of one entry come with two-address reads
+// (stride 64 words), and an LDS atomic on one word of the records meets no bank twice.
 
 struct FastLds {
     uint32_t *sw_tab;     // [32]  by code, for the sweeps of problems without blocks on several devices:
@@ -783,21 +787,22 @@ struct FastLds {
     uint32_t *in_tab;     // [32]  by code, behind ch_tab: 1 << s | s, s = 16 + 4 * symbol: counter increment and field position
     uint4 *tt_tab;        // [32]  by code, for the sweeps of the TP variants: x: t, y: byte offset of the first token slot of the code's
                           //       chain, z: byte offset of its device's words, w: bit offset of its micro-batch counter
-    uint4 *type_tab;      // [32]  by code, what placing one block of the type does:
-                          //   x: added to the last word of its device record: memory delta << 16, one waiting
+    uint32_t *type_tab;   // [4][64], code in the low half of every 64: what placing one block of the type does:
+                          //   word 0: added to the last word of its device record: memory delta << 16, one waiting
                           //      micro-batch of the type less, one more for its consumer if that sits on the same device
-                          //   y: one-hot mask of the consumer's code (0: none)
-                          //   z: consumer on another device: byte offset of the last word of that device's records
-                          //      (lane 0) from the start of the records; otherwise, TP variants: 0xFFFFFFFF, else the
-                          //      type's own device (w is 0 then).  Not TP: 4 * symbol of the type in bits 16-19
-                          //   w: the increment of that word (one waiting micro-batch of the consumer)
+                          //   word 1: one-hot mask of the consumer's code (0: none)
+                          //   word 2: consumer on another device: LDS address of the last word of that device's record
+                          //      (lane 0); otherwise, TP variants: 0xFFFFFFFF, else that of the type's own device
+                          //      (word 3 is 0 then).  Not TP: 4 * symbol of the type in bits 16-19
+                          //   word 3: the increment of that word (one waiting micro-batch of the consumer)
+                          // the upper halves hold chain_tab, vtab, cum_tab, predbit_tab
     uint32_t *chain_tab;  // [32]  KParams::chain_tab
     uint32_t *vtab;       // [32]  KParams::vtab
     uint32_t *cum_tab, *predbit_tab, *depbit_tab;   // [32] each: KParams::cum_code, pred_bit, dep_bit
     uint32_t *grp_tab;    // [32]  TP variants: KParams::grp_code
-    uint4 *rec;           // build: [DM][64] x: low plane, y: high plane, z: not-yet-placed mask,
-                          //        w: micro-batches waiting at the input of the 4 types (4 bits each)
-                          //           | memory now (signed) << 16
+    uint32_t rec;         // build: LDS address of the records [DM][4][64]: word 0: low plane, 1: high plane,
+                          //        2: not-yet-placed mask, 3: micro-batches waiting at the input of the 4 types
+                          //        (4 bits each) | memory now (signed) << 16
     // sweeps: three arrays [slot][64] in a row at distances known at compile time
     uint32_t *dfree;      // [DM] time at which the device is free
     uint32_t *dcnt;       // [DM] next micro-batch of the device's 4 types (4 bits each, in the upper half of the word)
@@ -884,6 +889,17 @@ __device__ __forceinline__ void lds_store(uint32_t a, uint32_t v) { *(lds_word *
 __device__ __forceinline__ uint32_t lds_fetch_add(uint32_t a, uint32_t v)
 {
     return __hip_atomic_fetch_add((lds_word *)(uintptr_t)a, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// a lane's device record: four words at a stride of 64 words (two two-address accesses)
+constexpr uint32_t kRecWordStep = kWave * 4u, kRecDevStep = 4u * kRecWordStep;
+__device__ __forceinline__ uint4 rec_load(uint32_t a)
+{
+    return make_uint4(lds_load(a), lds_load(a + kRecWordStep), lds_load(a + 2u * kRecWordStep), lds_load(a + 3u * kRecWordStep));
+}
+__device__ __forceinline__ void rec_store(uint32_t a, const uint4 v)
+{
+    lds_store(a, v.x); lds_store(a + kRecWordStep, v.y); lds_store(a + 2u * kRecWordStep, v.z); lds_store(a + 3u * kRecWordStep, v.w);
 }
 
 // The blocks of one sweep for problems whose blocks sit on one device each, as a software pipeline four blocks deep.
@@ -1227,7 +1243,7 @@ __device__ __forceinline__ void build_begin(const KParams &P, const FastConst<DM
             mem0 += ((int)(C.mpack[d] << (24 - 8 * y)) >> 24) * (int)lead;     // blocks that ran before the window
         }
         const uint32_t alive = nlen[d] >= 32 ? 0xFFFFFFFFu : (1u << nlen[d]) - 1u;
-        L.rec[d * kWave + lane] = make_uint4(plo[d], phi[d], alive, qd | ((uint32_t)mem0 << 16));
+        rec_store(L.rec + (uint32_t)d * kRecDevStep + (uint32_t)lane * 4u, make_uint4(plo[d], phi[d], alive, qd | ((uint32_t)mem0 << 16)));
         if (nlen[d] > 0) HM |= 1u << (4 * d + ((plo[d] & 1u) | ((phi[d] & 1u) << 1)));
     }
 
@@ -1248,7 +1264,8 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
     uint32_t R = S.R, HM = S.HM, X = S.X;
     int worst = S.worst, status = S.status;
     bool building = repair || (live && status == kOk);
-    const uint32_t lane16 = (uint32_t)lane * 16u;
+    const uint32_t lane4 = (uint32_t)lane * 4u;
+    const uint32_t rec_lane = L.rec + lane4;
     // one program word = six blocks
     auto word = [&](int wi) -> uint32_t {
         uint32_t acc = 0;
@@ -1263,8 +1280,8 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
             const uint32_t b = low_bit(sel);
             uint32_t d4 = repair ? min(b & 28u, 4u * (DM - 1)) : building ? b & 28u : 0u;    // 4 * device
             TESSEL_PIN(d4);
-            uint4 *rp = (uint4 *)((char *)L.rec + ((d4 << 8) + lane16));
-            uint4 a = *rp;
+            const uint32_t ra = (d4 << 8) + rec_lane;          // (kRecDevStep = 4 << 8)
+            const uint4 a = rec_load(ra);
             // earliest remaining entry of the device whose type is runnable: a 4-way multiplexer keyed by the two
             // planes.  (When the device was picked for its runnable head this is the head: nothing precedes it.)
             const int r4 = (int)(R >> d4);
@@ -1277,7 +1294,8 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
             // c = d4 + y with y = (ly & 1) | (hy & 2): ly, hy are 0 or -1, so c = d4 - ly - 2 hy
             uint32_t c;
             asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(c) : "v"(hy), "v"(d4 - ly));
-            const uint4 e = L.type_tab[c];
+            const uint32_t c4 = c << 2;
+            const uint4 e = rec_load(c4);                      // (the table of the types starts the kernel's LDS, at address 0)
             // take the entry out; new head of the device.  (When the device is empty now the bit set below is
             // meaningless, and harmless: all its types are exhausted, and R never holds an exhausted type.)
             const uint32_t alive = a.z & ~(1u << p);
@@ -1303,12 +1321,12 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
             const bool active = repair || building;
             uint32_t r_fin = r_new, x_fin = x_new, hm_fin = hm_new;
             if (active) {
-                rp->z = alive;
-                rp->w = w_new;
+                lds_store(ra + 2u * kRecWordStep, alive);
+                lds_store(ra + 3u * kRecWordStep, w_new);
                 // (without blocks on several devices every table entry names a word: a type without a consumer on
                 // another device adds 0 to its own record)
-                if (!TP) atomicAdd((uint32_t *)((char *)L.rec + (e.z & 0xFFFFu)) + 4 * lane, e.w);
-                else if (e.z != 0xFFFFFFFFu) atomicAdd((uint32_t *)((char *)L.rec + e.z) + 4 * lane, e.w);
+                if (!TP) lds_fetch_add((e.z & 0xFFFFu) + lane4, e.w);
+                else if (e.z != 0xFFFFFFFFu) lds_fetch_add(e.z + lane4, e.w);
                 worst = max(worst, (int)w_new >> 16);
                 // the program names a type by its code on its lowest device
                 acc |= (TP ? (uint32_t)__builtin_ctz(L.grp_tab[c]) : c) << (5 * j);
@@ -1328,15 +1346,15 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
                         const uint32_t nib = (G >> (4 * dd)) & 15u;
                         if (dd >= C.D || nib == 0 || 4u * dd == d4) continue;
                         const uint32_t sym = (uint32_t)__builtin_ctz(nib);
-                        uint4 *rq = L.rec + (dd * kWave + lane);
-                        const uint4 q = *rq;
+                        const uint32_t rq = (uint32_t)dd * kRecDevStep + rec_lane;
+                        const uint4 q = rec_load(rq);
                         const uint32_t ls = 0u - (sym & 1u), hs = 0u - (sym >> 1);
                         const uint32_t same = q.z & ~(q.x ^ ls) & ~(q.y ^ hs);
                         const uint32_t pos = (uint32_t)__builtin_ctz(same | 0x80000000u);
                         const uint32_t left = q.z & ~(1u << pos);
                         const uint32_t wq = q.w + ((uint32_t)mtype << 16) - (1u << (4u * sym));
-                        rq->z = left;
-                        rq->w = wq;
+                        lds_store(rq + 2u * kRecWordStep, left);
+                        lds_store(rq + 3u * kRecWordStep, wq);
                         worst = max(worst, (int)wq >> 16);
                         const uint32_t ph = (uint32_t)__builtin_ctz(left | 0x80000000u);
                         const uint32_t yh = __builtin_amdgcn_ubfe(q.x, ph, 1) | (__builtin_amdgcn_ubfe(q.y, ph, 1) << 1);
@@ -1346,7 +1364,7 @@ __device__ __forceinline__ void build_words(const KParams &P, const FastConst<DM
                     for (int dd = 0; dd < DM; dd++) {
                         const uint32_t nib = (Gs >> (4 * dd)) & 15u;
                         if (dd >= C.D || nib == 0) continue;
-                        atomicAdd(&L.rec[dd * kWave + lane].w, 1u << (4u * (uint32_t)__builtin_ctz(nib)));
+                        lds_fetch_add((uint32_t)dd * kRecDevStep + 3u * kRecWordStep + rec_lane, 1u << (4u * (uint32_t)__builtin_ctz(nib)));
                     }
                 }
             }
@@ -1394,19 +1412,19 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     const KParams &P = *Pp;
     const int lane = threadIdx.x;
     FastLds L;
-    L.tt_tab = (uint4 *)lds;                                  // 128 words
-    L.type_tab = (uint4 *)(lds + 4 * kMaxK);                  // 128 words
-    L.chain_tab = lds + 8 * kMaxK;
-    L.vtab = lds + 9 * kMaxK;
-    L.grp_tab = lds + kFastTableWords;                        // TP variants only
-    L.cum_tab = lds + 10 * kMaxK;
-    L.predbit_tab = lds + 11 * kMaxK;
-    L.depbit_tab = lds + 15 * kMaxK;
+    L.type_tab = lds;                                         // 4 x 64 words, the upper half of every 64:
+    L.chain_tab = lds + kMaxK;
+    L.vtab = lds + 3 * kMaxK;
+    L.cum_tab = lds + 5 * kMaxK;
+    L.predbit_tab = lds + 7 * kMaxK;
+    L.depbit_tab = lds + 8 * kMaxK;
+    L.tt_tab = (uint4 *)(lds + kFastTableWords);              // 128 words, TP variants only
+    L.grp_tab = lds + kFastTableWords + 4 * kMaxK;            // TP variants only
     L.sw_tab = lds + kSweepTabWord;
     L.ch_tab = lds + kSweepTabWord + kMaxK;
     L.in_tab = lds + kSweepTabWord + 2 * kMaxK;
-    uint32_t *base = lds + kFastTableWords + (TP ? kMaxK : 0);
-    L.rec = (uint4 *)base;
+    uint32_t *base = lds + kFastTableWords + (TP ? kTpTableWords : 0);
+    L.rec = lds_address(base);
     // the sweep state is only used once the build is over: it shares the records' space when it fits
     const int ntok = P.nslots - P.D;
     const bool share = DM * 2 + ntok <= DM * 4;
@@ -1416,23 +1434,25 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     L.tok = sweep_base + 2 * DM * kWave;
     if (lane < kMaxK) {
         const uint32_t inf = P.info_loc[lane];
-        L.tt_tab[lane] = make_uint4((uint32_t)P.t_loc[lane], ((((inf >> 12) & 63u) - (uint32_t)P.D + 2u * DM) << 8),
+        if (TP) L.tt_tab[lane] = make_uint4((uint32_t)P.t_loc[lane], ((((inf >> 12) & 63u) - (uint32_t)P.D + 2u * DM) << 8),
                                     ((uint32_t)lane >> 2) * (kWave * 4u), 16u + 4u * ((uint32_t)lane & 3u));
         {
             const uint32_t su = inf & 63u, dev = (uint32_t)lane >> 2, y = (uint32_t)lane & 3u;
             const int32_t m = (int32_t)(inf << 6) >> 24;
             const bool has_su = su != 63u, same = has_su && (su >> 2) == dev;
             const uint32_t inc = has_su ? 1u << (4u * (su & 3u)) : 0u;
+            const uint32_t last = L.rec + 3u * kRecWordStep;          // last word of device 0's record, lane 0
+            uint4 e;
             if (TP && ((P.slow_mask >> lane) & 1u))
                 // a type on several devices, or with such a consumer: the step's slow path does the consumer's part
-                L.type_tab[lane] = make_uint4(((uint32_t)m << 16) - (1u << (4u * y)), has_su ? P.grp_code[su & 31u] : 0u,
-                                                              0xFFFFFFFFu, (uint32_t)m);
+                e = make_uint4(((uint32_t)m << 16) - (1u << (4u * y)), has_su ? P.grp_code[su & 31u] : 0u, 0xFFFFFFFFu, (uint32_t)m);
             else
-                L.type_tab[lane] = make_uint4(((uint32_t)m << 16) - (1u << (4u * y)) + (same ? inc : 0u),
-                                              has_su ? 1u << (su & 31u) : 0u,
-                                              has_su && !same ? (su >> 2) * (kWave * 16u) + 12u + (TP ? 0u : y << 18)
-                                                              : TP ? 0xFFFFFFFFu : (dev < (uint32_t)DM ? dev : 0u) * (kWave * 16u) + 12u + (y << 18),
-                                              has_su && !same ? inc : 0u);
+                e = make_uint4(((uint32_t)m << 16) - (1u << (4u * y)) + (same ? inc : 0u),
+                               has_su ? 1u << (su & 31u) : 0u,
+                               has_su && !same ? last + (su >> 2) * kRecDevStep + (TP ? 0u : y << 18)
+                                               : TP ? 0xFFFFFFFFu : last + (dev < (uint32_t)DM ? dev : 0u) * kRecDevStep + (y << 18),
+                               has_su && !same ? inc : 0u);
+            L.type_tab[lane] = e.x; L.type_tab[2 * kMaxK + lane] = e.y; L.type_tab[4 * kMaxK + lane] = e.z; L.type_tab[6 * kMaxK + lane] = e.w;
         }
         {
             // codes no block type has: device 0, chain 0, t = 0 (the pipeline of the sweeps reads code 0 past the end)
@@ -1581,8 +1601,9 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
 #pragma unroll
         for (int d = 0; d < DM; d++)
             if (d < C.D)
-                L.rec[d * kWave + lane] = make_uint4(src[(kStageMetaWords + 4 * d) * kRingSlots], src[(kStageMetaWords + 4 * d + 1) * kRingSlots],
-                                                     src[(kStageMetaWords + 4 * d + 2) * kRingSlots], src[(kStageMetaWords + 4 * d + 3) * kRingSlots]);
+                rec_store(L.rec + (uint32_t)d * kRecDevStep + (uint32_t)lane * 4u,
+                          make_uint4(src[(kStageMetaWords + 4 * d) * kRingSlots], src[(kStageMetaWords + 4 * d + 1) * kRingSlots],
+                                     src[(kStageMetaWords + 4 * d + 2) * kRingSlots], src[(kStageMetaWords + 4 * d + 3) * kRingSlots]));
 #pragma unroll
         for (int c4 = 0; c4 < 12; c4++)
             if (c4 < chunksA) {
@@ -1622,7 +1643,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
 #pragma unroll
             for (int d = 0; d < DM; d++)
                 if (d < C.D) {
-                    const uint4 q = L.rec[d * kWave + lane];
+                    const uint4 q = rec_load(L.rec + (uint32_t)d * kRecDevStep + (uint32_t)lane * 4u);
                     dst[(kStageMetaWords + 4 * d) * kRingSlots] = q.x; dst[(kStageMetaWords + 4 * d + 1) * kRingSlots] = q.y;
                     dst[(kStageMetaWords + 4 * d + 2) * kRingSlots] = q.z; dst[(kStageMetaWords + 4 * d + 3) * kRingSlots] = q.w;
                 }
@@ -1869,7 +1890,7 @@ static size_t fast_lds_bytes(const KParams &kp)
 {
     const int ntok = kp.nslots - kp.D;
     const bool share = fast_dm(kp) * 2 + ntok <= fast_dm(kp) * 4;
-    return (size_t)(kFastTableWords + (kp.fast_tp ? kMaxK : 0)) * 4 + (size_t)fast_dm(kp) * kWave * 16 +
+    return (size_t)(kFastTableWords + (kp.fast_tp ? kTpTableWords : 0)) * 4 + (size_t)fast_dm(kp) * kWave * 16 +
            (share ? 0 : (size_t)(fast_dm(kp) * 2 + ntok) * kWave * 4);
 }
 
