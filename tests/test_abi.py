@@ -32,12 +32,13 @@ def test_problem_create_validates_on_the_host():
     assert binding.Problem(W.config2()).candidate_count() == 120 * 70 ** 4
     assert binding.Problem(W.config5()).candidate_count() == 2 ** 64 - 1
     assert p.workspace_bytes() > 0
+    # a block type with two consumers: the micro-batch graph need not be a set of chains
+    assert binding.Problem(dict(W.config1(), deps=[(0, 1), (0, 2), (2, 3)])).candidate_count() > 0
     for bad, code in (
         (dict(W.config1(), m=[1, 1, -1, 0]), -3),
         (dict(W.config1(), deps=[(0, 1), (1, 0)]), -2),
         (dict(W.config1(), t=[0, 1, 2, 2]), -1),
         (dict(W.config1(), NR=9), -9),
-        (dict(W.config1(), deps=[(0, 1), (0, 2), (2, 3)]), -9),
         (dict(W.config1(), fixed_leads=[0, 0, 0, 0]), -1),
         (W.pipeline_problem(W.folded_placement(8), [1] * 16, [1] * 16, 8, 8, 10, "canonical"), -4),
     ):
