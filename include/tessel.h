@@ -29,7 +29,9 @@ extern "C" {
 #endif
 
 /* ---- limits of this implementation -------------------------------------------------- */
-#define TESSEL_MAX_DEVICES        8    /* simulated devices D                               */
+#define TESSEL_MAX_DEVICES        32   /* simulated devices D (more than 8: scored by the
+                                          general kernel alone, state in global memory; no
+                                          searched completion)                              */
 #define TESSEL_MAX_TYPES_PER_DEV  4    /* block types that occupy one device                */
 #define TESSEL_MAX_NR             8    /* micro-batches per repetend window, N_R            */
 #define TESSEL_MAX_TYPES          32   /* K                                                 */

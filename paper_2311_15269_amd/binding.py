@@ -11,7 +11,7 @@ import numpy as np
 
 from . import build as _build
 
-MAX_DEVICES = 8
+MAX_DEVICES = 32
 MAX_POS = 32
 NUM_STATUS = 6
 STATUS_NAMES = ("OK", "DUP", "TP_MISMATCH", "PROP2", "DEADLOCK", "MEM")

@@ -27,31 +27,77 @@ def is_stale():
     return any(os.path.getmtime(os.path.join(CSRC, f)) > built for f in SOURCES + HEADERS)
 
 
+def _const(tok):
+    try:
+        return int(tok, 0)
+    except ValueError:
+        return None
+
+
+def _word_aligned(reg, block, upto, depth=0, unknown=True):
+    """Is scalar register `reg` (a number) visibly a multiple of four at line `upto` of the basic block `block`?
+    Follows its latest definition inside the block: shifts left by two or more, multiples of four, sums of such;
+    a register the block does not define came in whole (`unknown`: a pointer argument or a value checked elsewhere;
+    not assumed of the factors of a product)."""
+    if depth > 8:
+        return False
+    for k in range(upto - 1, -1, -1):
+        t = block[k]
+        m = re.search(r"\bs_lshl_b64\s+s\[(\d+):(\d+)\],\s*\S+,\s*(\S+)", t)
+        if m and int(m.group(1)) <= reg <= int(m.group(2)):
+            c = _const(m.group(3))
+            return reg > int(m.group(1)) or (c is not None and c >= 2)
+        m = re.search(r"\b(s_\w+|v_readfirstlane_b32|v_readlane_b32)\s+s(\d+),\s*(.*)$", t)
+        if not m or int(m.group(2)) != reg:
+            m2 = re.search(r"\bs_(?:buffer_)?load_\w+\s+s\[(\d+):(\d+)\]", t)
+            if m2 and int(m2.group(1)) <= reg <= int(m2.group(2)):
+                return True                                      # a pointer read from memory whole
+            continue
+        op, args = m.group(1), [a.strip() for a in m.group(3).split(",")]
+
+        def ok(a, unknown=True):
+            c = _const(a)
+            if c is not None:
+                return c % 4 == 0
+            r = re.match(r"s(\d+)$", a)
+            return bool(r) and _word_aligned(int(r.group(1)), block, k, depth + 1, unknown)
+        if op == "v_readlane_b32":                               # a spilled scalar register coming back
+            return True
+        if op in ("s_lshl_b32",):
+            c = _const(args[1]) if len(args) > 1 else None
+            return c is not None and c >= 2
+        if op in ("s_mul_i32",):
+            return len(args) == 2 and (ok(args[0], False) or ok(args[1], False))
+        if op in ("s_add_u32", "s_add_i32", "s_sub_u32", "s_sub_i32"):
+            return len(args) == 2 and ok(args[0]) and ok(args[1])
+        if op in ("s_mov_b32",):
+            return len(args) == 1 and ok(args[0])
+        return False
+    return unknown
+
+
 def misaligned_scalar_loads(asm):
     """Scalar loads of the device code whose address is not visibly a multiple of four: a register offset, or a base
-    that was computed from anything but an index shifted left by two or more.  The scalar memory path drops the low
-    two bits of the base, so `base + i` with a byte index i, to which the compiler once added `3 i` as the offset of a
-    load of word i, reads the wrong word.  (Seen in a variant of the completion kernel that read its per-type
-    tables from global memory; the kernels keep such tables in LDS.)  Returns the offending lines."""
+    computed in its basic block from anything but indices shifted left by two or more or multiplied by a multiple of
+    four.  The scalar memory path drops the low two bits of the base, so `base + i` with a byte index i, to which the
+    compiler once added `3 i` as the offset of a load of word i, reads the wrong word.  (Seen in a variant of the
+    completion kernel that read its per-type tables from global memory; the kernels keep such tables in LDS.)
+    Returns the offending lines."""
     lines = asm.split("\n")
     bad = []
+    start = 0                                                    # first line of the current basic block
     for n, line in enumerate(lines):
+        if line.startswith(".L") or re.match(r"^\S+:", line):
+            start = n + 1
+            continue
         m = re.search(r"\bs_(?:buffer_)?load_\w+\s+\S+,\s+s\[(\d+):\d+\],\s*(\S+)", line)
         if not m:
             continue
         if re.match(r"s\d+", m.group(2)):                       # register offset
             bad.append("%d: %s" % (n + 1, line.strip()))
             continue
-        base = m.group(1)
-        for k in range(n - 1, max(0, n - 14), -1):
-            t = lines[k]
-            if t.startswith(".L") or re.match(r"^\S+:", t):     # start of the basic block: the base came in whole
-                break
-            if re.search(r"\b(?:s_add_u32|v_readfirstlane_b32)\s+s%s\b" % base, t):
-                before = "\n".join(lines[max(0, k - 6):k])
-                if not re.search(r"s_lshl_b64\s+s\[\d+:\d+\],\s*s\[\d+:\d+\],\s*[2-9]\b", before):
-                    bad.append("%d: %s" % (n + 1, line.strip()))
-                break
+        if not _word_aligned(int(m.group(1)), lines[start:n], n - start):
+            bad.append("%d: %s" % (n + 1, line.strip()))
     return bad
 
 

@@ -157,9 +157,9 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         (desc->num_deps > 0 && (!desc->dep_src || !desc->dep_dst)) || desc->space < 0 || desc->space > 3 ||
         desc->lead_step_q16 > 65536u)
         return TESSEL_E_INVALID_ARG;
-    if (D > 31) return TESSEL_E_UNSUPPORTED;
+    if (D > kMaxDW) return TESSEL_E_UNSUPPORTED;
     for (int i = 0; i < K; i++)
-        if (desc->time[i] < 1 || desc->dev_mask[i] == 0 || (desc->dev_mask[i] >> D)) return TESSEL_E_INVALID_ARG;
+        if (desc->time[i] < 1 || desc->dev_mask[i] == 0 || (D < 32 && (desc->dev_mask[i] >> D))) return TESSEL_E_INVALID_ARG;
     for (int e = 0; e < desc->num_deps; e++)
         if (desc->dep_src[e] < 0 || desc->dep_src[e] >= K || desc->dep_dst[e] < 0 || desc->dep_dst[e] >= K ||
             desc->dep_src[e] == desc->dep_dst[e])
@@ -190,7 +190,7 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         if (net != 0) return TESSEL_E_UNBALANCED_MEMORY;
     }
     // limits of the kernels
-    if (D > kMaxD || K > kMaxK || NR > kMaxNR) return TESSEL_E_UNSUPPORTED;
+    if (K > kMaxK || NR > kMaxNR) return TESSEL_E_UNSUPPORTED;
     std::vector<int> indeg(K, 0), outdeg(K, 0);
     for (int e = 0; e < desc->num_deps; e++) { outdeg[desc->dep_src[e]]++; indeg[desc->dep_dst[e]]++; }
     // disjoint chains take the fast kernel and the chain path of the general one; any other graph (Sec. III-A allows
@@ -198,6 +198,10 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
     bool chains = true;
     for (int i = 0; i < K; i++) if (indeg[i] > 1 || outdeg[i] > 1) chains = false;
     { const char *fd = getenv("TESSEL_FORCE_DAG"); if (fd && fd[0] == '1') chains = false; }
+    // more than kMaxD devices: the tables by (device, symbol) code of the chain path and of the fast kernel have no room
+    // for them; such a problem is scored as a graph, chains or not
+    const bool wide = D > kMaxD;
+    if (wide) chains = false;
     if (!chains && desc->num_deps > kMaxDeps) return TESSEL_E_UNSUPPORTED;
 
     tessel_problem *p = new (std::nothrow) tessel_problem();
@@ -227,7 +231,7 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
             int v = atoi(env);
             if (v >= 0 && v <= 64) kp.dag_tries = v;
         }
-        for (int i = 0; i < K; i++) { kp.t_type[i] = desc->time[i]; kp.mask_type[i] = desc->dev_mask[i]; kp.tokbase[i] = 0xFF; }
+        for (int i = 0; i < K; i++) { kp.t_type[i] = desc->time[i]; kp.mask_type[i] = desc->dev_mask[i]; kp.tokbase[i] = (uint16_t)kNoRing; }
         for (int e = 0; e < desc->num_deps; e++) {
             const int a = desc->dep_src[e], b = desc->dep_dst[e];
             kp.dsrc[e] = (uint8_t)a; kp.ddst[e] = (uint8_t)b; kp.dcross[e] = desc->dev_mask[a] != desc->dev_mask[b];
@@ -236,8 +240,7 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         // every type somebody consumes keeps the end times of its blocks by micro-batch: 2 N_R slots behind the devices
         for (int i = 0; i < K; i++) if (outdeg[i] > 0) {
             const int base = D + kp.ntok * 2 * NR;
-            if (base + 2 * NR > 255) { delete p; return TESSEL_E_UNSUPPORTED; }
-            kp.tokbase[i] = (uint8_t)base;
+            kp.tokbase[i] = (uint16_t)base;
             kp.ntok++;
         }
         // consumers before producers
@@ -270,7 +273,8 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         kp.nslots = D + kp.ntok * 2 * NR;
         kp.nsweeps = D + 1;                       // (only sizes the register arrays of the chain path, unused here)
         // state and program of a workgroup must fit the LDS a kernel may ask for
-        if ((size_t)4 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)K * NR * kWave * 2 > 64 * 1024) { delete p; return TESSEL_E_UNSUPPORTED; }
+        // (problems with more than kMaxD devices keep both in global memory)
+        if (!wide && (size_t)4 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)K * NR * kWave * 2 > 64 * 1024) { delete p; return TESSEL_E_UNSUPPORTED; }
     }
     int sumt = 0;
     for (int i = 0; i < K; i++) {
@@ -281,7 +285,8 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
     // the period kernel multiplies (sweeps * UB) by a sweep count
     if ((int64_t)kp.UB * kp.nsweeps * kp.nsweeps >= (int64_t)1 << 31) { delete p; return TESSEL_E_TOOBIG; }
     kp.LB = 0;
-    for (int d = 0; d < kMaxD; d++) { kp.type_of[d] = kp.pred_of[d] = 0xFFFFFFFFu; kp.mask_of[d] = kp.tok_of[d] = kp.home_of[d] = 0; }
+    for (int d = 0; d < kMaxDW; d++) kp.type_of[d] = 0xFFFFFFFFu;
+    for (int d = 0; d < kMaxD; d++) { kp.pred_of[d] = 0xFFFFFFFFu; kp.mask_of[d] = kp.tok_of[d] = kp.home_of[d] = 0; }
     std::vector<int> home(K, -1);
     for (int d = 0; d < D; d++) {
         int n = 0, busy = 0;
@@ -289,12 +294,14 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
             if (n >= kMaxLT) { delete p; return TESSEL_E_UNSUPPORTED; }
             if (home[i] < 0) home[i] = d * 4 + n;
             kp.type_of[d] = (kp.type_of[d] & ~(0xFFu << (8 * n))) | ((uint32_t)i << (8 * n));
-            uint32_t pr = kp.pred[i] < 0 ? 0xFFu : (uint32_t)kp.pred[i];
-            kp.pred_of[d] = (kp.pred_of[d] & ~(0xFFu << (8 * n))) | (pr << (8 * n));
-            kp.mask_of[d] |= (desc->dev_mask[i] & 0xFFu) << (8 * n);
-            kp.tok_of[d] |= (uint32_t)(D + path_of[i] * 2 * NR) << (8 * n);
-            kp.home_of[d] |= (uint32_t)home[i] << (8 * n);
-            kp.t_of[d][n] = desc->time[i];
+            if (!wide) {
+                uint32_t pr = kp.pred[i] < 0 ? 0xFFu : (uint32_t)kp.pred[i];
+                kp.pred_of[d] = (kp.pred_of[d] & ~(0xFFu << (8 * n))) | (pr << (8 * n));
+                kp.mask_of[d] |= (desc->dev_mask[i] & 0xFFu) << (8 * n);
+                kp.tok_of[d] |= (uint32_t)(D + path_of[i] * 2 * NR) << (8 * n);
+                kp.home_of[d] |= (uint32_t)home[i] << (8 * n);
+                kp.t_of[d][n] = desc->time[i];
+            }
             kp.predmask_of[d][n] = kp.predmask[i];
             kp.m_of[d][n] = desc->mem[i];
             busy += desc->time[i];
@@ -304,12 +311,11 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         kp.LB = std::max(kp.LB, NR * busy);
     }
     for (int i = 0; i < K; i++) {
-        kp.t_loc[home[i]] = desc->time[i];
-        kp.mask_loc[home[i]] = desc->dev_mask[i];
+        if (!wide) { kp.t_loc[home[i]] = desc->time[i]; kp.mask_loc[home[i]] = desc->dev_mask[i]; }
         if (desc->dev_mask[i] & (desc->dev_mask[i] - 1)) kp.tp = 1;
     }
     // tables of the fast kernel: single-device blocks, small memory deltas, few slots
-    {
+    if (!wide) {
         bool ok = chains && kp.nslots <= 32 && kp.nsweeps - 1 <= 24;
         // every (device, local symbol) is a code; a type on several devices has one code per device
         std::vector<std::vector<int>> code_on(K, std::vector<int>(D, -1));
@@ -638,7 +644,7 @@ static int fetch_best(tessel_problem *p)
     if (p->result.period == INT_MAX) { p->have_detail = false; return TESSEL_OK; }
     if (p->have_detail && p->detail_index == p->result.index) { p->best_dirty = false; return TESSEL_OK; }
     // decode and re-score the best candidate on the GPU for its peaks and orders
-    int le = launch_detail(p->kp, p->result.index, p->ws, p->stream);
+    int le = launch_detail(p->kp, p->result.index, p->ws, p->num_cus, p->max_blocks, p->stream);
     if (le) return hip_fail(p, le);
     e = hipStreamSynchronize(p->stream);
     if (e != hipSuccess) return hip_fail(p, (int)e);

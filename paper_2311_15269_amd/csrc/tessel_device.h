@@ -45,12 +45,14 @@ TESSEL_HD uint32_t stream_draw16(uint32_t ka, uint32_t kb, uint32_t j)
 }
 constexpr uint64_t kCompletionKey = 0x632BE59BD9B4E019ULL;      // separates the completion stream from the candidates'
 
-constexpr int kMaxD = 8;         // simulated devices
+constexpr int kMaxD = 8;         // simulated devices of the problems the fast kernel and the chain path of the general one take
+constexpr int kMaxDW = 32;       // ... of any problem: more than kMaxD go the general kernel's path for graphs
 constexpr int kMaxLT = 4;        // block types per device
 constexpr int kMaxNR = 8;        // micro-batches per window
 constexpr int kMaxK = 32;        // block types
 constexpr int kMaxPos = kMaxLT * kMaxNR;   // blocks per device and window (32)
 constexpr int kMaxDeps = 64;      // dependencies of a micro-batch whose graph is not a set of chains
+constexpr uint32_t kNoRing = 0xFFFFu;   // no ring of end times (KParams::tokbase)
 constexpr int kNumStatus = 6;
 constexpr int kWave = 64;
 
@@ -73,14 +75,14 @@ struct KParams {
     int32_t has_fixed;
     uint32_t step_q16;
     uint64_t seed;
-    int32_t  ntd[kMaxD];         // block types on device d
-    uint32_t type_of[kMaxD];     // 4 x 8 bit: type id of local symbol y (0xFF = none)
+    int32_t  ntd[kMaxDW];        // block types on device d
+    uint32_t type_of[kMaxDW];    // 4 x 8 bit: type id of local symbol y (0xFF = none)
     uint32_t pred_of[kMaxD];     // 4 x 8 bit: type id of its producer (0xFF = none)
     uint32_t mask_of[kMaxD];     // 4 x 8 bit: device mask of that type
     uint32_t tok_of[kMaxD];      // 4 x 8 bit: first token slot of the type's chain
     uint32_t home_of[kMaxD];     // 4 x 8 bit: (lowest device)*4 + local symbol there
     int32_t  t_of[kMaxD][kMaxLT];
-    int32_t  m_of[kMaxD][kMaxLT];
+    int32_t  m_of[kMaxDW][kMaxLT];
     int8_t   succ[kMaxK];        // consumer type of type g or -1
     uint8_t  edge_out[kMaxK];    // position of the dependency g -> succ[g] in the caller's list
     uint8_t  cross_out[kMaxK];   // that dependency joins different device sets
@@ -90,8 +92,8 @@ struct KParams {
     int32_t  t_loc[kMaxK];       // t by home code (device*4 + symbol)
     uint32_t mask_loc[kMaxK];    // device mask by home code
     uint32_t fact[13];           // FACTORIAL: n! for n <= 12
-    uint64_t init_list[kMaxD];   // FACTORIAL: labelled blocks of a device, 5 bits each (y<<3 | label)
-    uint64_t cdev[kMaxD];        // FACTORIAL: n_d!;  CANONICAL: arrangements of device d
+    uint64_t init_list[kMaxDW];  // FACTORIAL: labelled blocks of a device, 5 bits each (y<<3 | label)
+    uint64_t cdev[kMaxDW];       // FACTORIAL: n_d!;  CANONICAL: arrangements of device d
     // fast path (single-device blocks only), block types addressed by code = device*4 + symbol
     int32_t  fast_ok;            // the problem fits the fast kernel
     uint32_t info_loc[kMaxK];    // bits 0-5 consumer code (63 none), 6-11 producer code (63 none),
@@ -125,9 +127,9 @@ struct KParams {
     int32_t  t_type[kMaxK];
     uint32_t mask_type[kMaxK];   // devices of the type
     uint32_t predmask[kMaxK];    // its producers
-    uint8_t  tokbase[kMaxK];     // first slot of its ring, 0xFF: nobody consumes it
+    uint16_t tokbase[kMaxK];     // first slot of its ring, kNoRing: nobody consumes it
     uint8_t  dsrc[kMaxDeps], ddst[kMaxDeps], dcross[kMaxDeps];   // the dependencies in the caller's order
-    uint32_t predmask_of[kMaxD][kMaxLT];   // producers of local symbol y of device d
+    uint32_t predmask_of[kMaxDW][kMaxLT];  // producers of local symbol y of device d
     const int8_t   *leadtab;     // CANONICAL: [nlead][K] in device memory
     const uint64_t *wtab;        // CANONICAL: arrangements by remaining counts, base NR+1 digits
 };
@@ -152,10 +154,10 @@ struct DevResult {
 // Decoded best candidate, written by the detail kernel.
 struct DevDetail {
     int32_t status, period;
-    int32_t peak[kMaxD];
+    int32_t peak[kMaxDW];
     int32_t leads[kMaxK];
-    int32_t order_len[kMaxD];
-    int32_t orders[kMaxD][kMaxPos];
+    int32_t order_len[kMaxDW];
+    int32_t orders[kMaxDW][kMaxPos];
 };
 
 // Searched completion (warm-up / cool-down orders as perturbed greedy schedules around the best window):
@@ -186,8 +188,8 @@ struct CompRec { int32_t makespan; int32_t pad; uint64_t ordinal; };
 constexpr size_t kWsResultOff = 0;
 constexpr size_t kWsCompletionOff = 192;       // DevCompletion
 constexpr size_t kWsDetailOff = 256;
-constexpr size_t kWsParamsOff = 2048;          // KParams of the bound problem
-constexpr size_t kWsTablesOff = 8192;          // lead table, arrangement table
+constexpr size_t kWsParamsOff = 8192;          // KParams of the bound problem
+constexpr size_t kWsTablesOff = 16384;         // lead table, arrangement table
 constexpr size_t kWsTablesMax = 1 << 20;
 constexpr size_t kWsListOff = kWsTablesOff + kWsTablesMax;     // candidates deferred to the general kernel
 constexpr uint32_t kWsListCap = 1u << 20;
@@ -223,7 +225,7 @@ int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *cod
 constexpr size_t kScratchBytes = (size_t)24 << 20;
 int scratch_workspace(void **ptr, size_t *bytes);
 int eval_blocks_that_fit(const KParams &kp, int num_cus, size_t bytes);
-int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream);
+int launch_detail(const KParams &kp, uint64_t index, void *ws, int num_cus, int max_blocks, void *stream);
 int launch_reset(void *ws, void *stream);
 // completion search: S = state words per lane; returns 0 or a HIP error (negative: LDS need exceeds the device's)
 size_t completion_lds_bytes(const CompParams &cp);

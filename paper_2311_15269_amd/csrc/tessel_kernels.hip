@@ -379,7 +379,7 @@ __device__ __forceinline__ int evaluate(const KParams &P, uint64_t idx, uint16_t
 
     if (detail) {
         for (int g = 0; g < P.K; g++) detail->leads[g] = (int)mu.get((uint32_t)g);
-        for (int d = 0; d < kMaxD; d++) detail->order_len[d] = 0;
+        for (int d = 0; d < kMaxDW; d++) detail->order_len[d] = 0;
     }
 
     // ---------------- memory at the window entry: blocks that ran before it (type i has
@@ -527,7 +527,7 @@ __device__ __forceinline__ void sweep_window_dag(const KParams &P, const DagTabl
         for (uint32_t rest = Tb.pred[g]; rest; rest &= rest - 1u) s = max(s, state[(Tb.tok[__builtin_ctz(rest)] + m) * kWave]);
         const uint32_t en = s + (uint32_t)Tb.t[g];
         for (uint32_t rest = Tb.mask[g]; rest; rest &= rest - 1u) state[__builtin_ctz(rest) * kWave] = en;
-        if (Tb.tok[g] != 0xFFu) state[(Tb.tok[g] + m) * kWave] = en;
+        if (Tb.tok[g] != kNoRing) state[(Tb.tok[g] + m) * kWave] = en;
     }
 }
 
@@ -555,7 +555,7 @@ __device__ __forceinline__ bool boundary_dag(const KParams &P, const DagTables &
     }
     for (int g = 0; g < P.K; g++) {
         const uint32_t base = Tb.tok[g];
-        if (base == 0xFFu) continue;
+        if (base == kNoRing) continue;
         const uint32_t lg = lead.get((uint32_t)g);
         for (int m = 0; m < P.NR; m++) {
             const uint32_t old = state[(base + m) * kWave], x = state[(base + m + P.NR) * kWave];
@@ -599,7 +599,7 @@ __device__ __forceinline__ int least_period_dag(const KParams &P, const DagTable
     if (__ballot(!done) == 0) return (int)T;
     // bisection, the same number of steps in every lane; lanes that have their period keep a fixed interval
     int crossing = P.D;
-    for (int g = 0; g < P.K; g++) if (Tb.tok[g] != 0xFFu) crossing += (int)lead.get((uint32_t)g);
+    for (int g = 0; g < P.K; g++) if (Tb.tok[g] != kNoRing) crossing += (int)lead.get((uint32_t)g);
     uint32_t lo = done ? T : (uint32_t)P.LB, hi = done ? T : (uint32_t)P.UB;
     int steps = 0;
     for (uint32_t span = (uint32_t)(P.UB - P.LB); span; span >>= 1) steps++;
@@ -609,7 +609,7 @@ __device__ __forceinline__ int least_period_dag(const KParams &P, const DagTable
         reset();
         bool decided = !open, feasible = false;
         // (crossing + 2 windows bound the iteration; the loop runs until every lane of the wave has decided)
-        for (int w = 0; w < kMaxK * kMaxNR + kMaxD + 2; w++) {
+        for (int w = 0; w < kMaxK * kMaxNR + kMaxDW + 2; w++) {
             if (__ballot(!decided) == 0) break;
             sweep_window_dag(P, Tb, prog, state);
             uint32_t zero = 0, top;
@@ -642,7 +642,7 @@ __device__ __forceinline__ int evaluate_dag(const KParams &P, const DagTables &T
     const Mu lead = mu;
     if (detail) {
         for (int g = 0; g < P.K; g++) detail->leads[g] = (int)mu.get((uint32_t)g);
-        for (int d = 0; d < kMaxD; d++) detail->order_len[d] = 0;
+        for (int d = 0; d < kMaxDW; d++) detail->order_len[d] = 0;
     }
     int memcur[DM];
 #pragma unroll
@@ -692,7 +692,7 @@ __device__ __forceinline__ int evaluate_dag(const KParams &P, const DagTables &T
         for (int d = 0; d < DM; d++) {
             if (d >= P.D || remlen[d] == 0) continue;
             const uint32_t y = (uint32_t)rem[d] & 3u;
-            const uint32_t g = byte_of(P.type_of[d], y), mask = byte_of(P.mask_of[d], y);
+            const uint32_t g = byte_of(P.type_of[d], y), mask = Tb.mask[g];
             bool ok = ready(g, sel4u(P.predmask_of[d], y));
             if (mask != (1u << d)) {
                 // a multi-device block runs when it heads the list of all its devices; it is placed from its lowest device
@@ -720,7 +720,7 @@ __device__ __forceinline__ int evaluate_dag(const KParams &P, const DagTables &T
                 if (pos < best_pos) { best_pos = pos; best_y = (uint32_t)y; }
             }
             if (best_pos < 64u) {
-                place(byte_of(P.type_of[d], best_y), byte_of(P.mask_of[d], best_y), sel4(P.m_of[d], best_y), best_pos, d);
+                place(byte_of(P.type_of[d], best_y), Tb.mask[byte_of(P.type_of[d], best_y)], sel4(P.m_of[d], best_y), best_pos, d);
                 done = true;
             }
         }
@@ -1688,19 +1688,29 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
 }
 
 // ------------------------------------------------------------------ kernels
+// Problems with more than kMaxD devices (DM above kMaxD) are scored as dependency graphs, with the per-lane state and
+// program in global memory (`far`: one region of far_words(P) words per workgroup) instead of LDS: up to 32 devices
+// with up to 32 rings of 16 end times each do not fit there.
+__host__ __device__ inline size_t far_words(const KParams &P)
+{
+    return (((size_t)P.nslots * kWave * 4 + (size_t)P.total * kWave * 2 + 255) & ~(size_t)255) / 4;
+}
+
 template <int DM, int VM>
 __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__ Pp, uint64_t first, uint64_t count,
                                                      BlockRec *__restrict__ recs, int32_t *__restrict__ code_out,
                                                      int32_t *__restrict__ peak_out, DevDetail *__restrict__ detail,
-                                                     const uint64_t *__restrict__ list, const uint32_t *__restrict__ list_count)
+                                                     const uint64_t *__restrict__ list, const uint32_t *__restrict__ list_count,
+                                                     uint32_t *far)
 {
     const KParams &P = *Pp;
     extern __shared__ uint32_t lds[];
+    constexpr bool wide = DM > kMaxD;
     // with a list: score the listed candidates (all inside [first, first + count)) instead of the range
     if (list) count = min(*list_count, kWsListCap);
     int32_t *t_tab = (int32_t *)lds;
     uint32_t *mask_tab = lds + kMaxK;
-    uint32_t *state_all = lds + 4 * kMaxK;
+    uint32_t *state_all = wide ? far + (size_t)blockIdx.x * far_words(P) : lds + 4 * kMaxK;
     uint16_t *prog_all = (uint16_t *)(state_all + P.nslots * kWave);
     const int lane = threadIdx.x;
     // by home code for chain problems, by type id (with the producers and the token rings) for the others
@@ -1728,8 +1738,10 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
         const uint64_t idx = list ? list[kk] : first + kk;
         const uint64_t k = idx - first;
         int period, peak[DM];
-        int status = P.dag ? evaluate_dag<DM>(P, Tb, idx, prog, state, period, peak, detail)
-                           : evaluate<DM, VM>(P, idx, prog, state, t_tab, mask_tab, period, peak, detail);
+        int status;
+        if constexpr (wide) status = evaluate_dag<DM>(P, Tb, idx, prog, state, period, peak, detail);
+        else status = P.dag ? evaluate_dag<DM>(P, Tb, idx, prog, state, period, peak, detail)
+                            : evaluate<DM, VM>(P, idx, prog, state, t_tab, mask_tab, period, peak, detail);
         nev++;
 #pragma unroll
         for (int s = 0; s < kNumStatus; s++) cnt[s] += status == s;
@@ -1744,7 +1756,7 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
         if (peak_out) peak_out[k] = pk;
         if (detail) {
             detail->status = status; detail->period = period;
-            for (int d = 0; d < kMaxD; d++) detail->peak[d] = 0;
+            for (int d = 0; d < kMaxDW; d++) detail->peak[d] = 0;
 #pragma unroll
             for (int d = 0; d < DM; d++) if (d < P.D) detail->peak[d] = peak[d];
         }
@@ -1839,13 +1851,15 @@ __global__ void reset_kernel(DevResult *res)
 
 // ------------------------------------------------------------------ launchers
 typedef void (*eval_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, DevDetail *, const uint64_t *,
-                        const uint32_t *);
+                        const uint32_t *, uint32_t *);
 typedef void (*fast_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, int, int, uint64_t *, uint32_t *,
                         uint32_t, uint32_t *, uint32_t *, uint32_t, int);
 
 static eval_fn pick_kernel(const KParams &kp)
 {
     const int V = kp.nsweeps - 1;
+    if (kp.D > 16) return eval_kernel<32, 1>;
+    if (kp.D > kMaxD) return eval_kernel<16, 1>;
     if (kp.D <= 2 && V <= 4) return eval_kernel<2, 4>;
     if (kp.D <= 4 && V <= 8) return eval_kernel<4, 8>;
     if (kp.D <= 8 && V <= 16) return eval_kernel<8, 16>;
@@ -1881,9 +1895,13 @@ static fast_fn pick_fast(const KParams &kp)
     return V <= 16 ? eval_fast_kernel<8, 16, 0> : eval_fast_kernel<8, 24, 0>;
 }
 
+// state and program of the general kernel's lanes: in LDS, except for problems with more than kMaxD devices
+static bool far_state(const KParams &kp) { return kp.D > kMaxD; }
+static size_t far_bytes(const KParams &kp) { return far_state(kp) ? far_words(kp) * 4 : 0; }
+
 static size_t general_lds_bytes(const KParams &kp)
 {
-    return (size_t)4 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)kp.total * kWave * 2;
+    return (size_t)4 * kMaxK * 4 + (far_state(kp) ? 0 : (size_t)kp.nslots * kWave * 4 + (size_t)kp.total * kWave * 2);
 }
 
 static size_t fast_lds_bytes(const KParams &kp)
@@ -1908,6 +1926,7 @@ LaunchShape eval_launch_shape(const KParams &kp, int num_cus, int max_blocks)
         per_cu = (int)((160 * 1024) / ((s.lds_bytes + 511) / 512 * 512));
     }
     if (per_cu > 16) per_cu = 16;
+    if (far_state(kp) && per_cu > 4) per_cu = 4;                     // (keeps the state regions of a launch small)
     if (const char *env = getenv("TESSEL_BLOCKS_PER_CU")) {        // tuning knob: fewer resident workgroups per CU
         int want = atoi(env);
         if (want >= 1 && want < per_cu) per_cu = want;
@@ -1952,20 +1971,28 @@ static size_t ring_offset(int blocks, int num_cus)
 size_t eval_workspace_bytes(const KParams &kp, int num_cus, int max_blocks)
 {
     const LaunchShape s = eval_launch_shape(kp, num_cus, max_blocks);
-    return ring_offset(s.blocks, num_cus) + (pick_fast(kp) ? (size_t)s.blocks * 3 * ring_words(kp) * 4 : 0);
+    return ring_offset(s.blocks, num_cus) + (pick_fast(kp) ? (size_t)s.blocks * 3 * ring_words(kp) * 4 : (size_t)s.blocks * far_bytes(kp));
+}
+
+// where the state regions of the general kernel's workgroups start (problems with more than kMaxD devices)
+static uint32_t *far_base(const KParams &kp, void *ws, int num_cus, int max_blocks)
+{
+    if (!far_state(kp)) return nullptr;
+    return (uint32_t *)((char *)ws + ring_offset(eval_launch_shape(kp, num_cus, max_blocks).blocks, num_cus));
 }
 
 static int launch_general(const KParams &kp, const KParams *kp_dev, uint64_t first, uint64_t count, int blocks, BlockRec *recs,
                           int32_t *code, int32_t *peak, DevDetail *detail, const uint64_t *list, const uint32_t *list_count,
-                          hipStream_t st)
+                          uint32_t *far, hipStream_t st)
 {
+    if (far_state(kp) && !far) return (int)hipErrorInvalidValue;
     eval_fn fn = pick_kernel(kp);
     const size_t lds = general_lds_bytes(kp);
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return (int)e;
     }
-    hipLaunchKernelGGL(fn, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, detail, list, list_count);
+    hipLaunchKernelGGL(fn, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, detail, list, list_count, far);
     return (int)hipGetLastError();
 }
 
@@ -1984,7 +2011,8 @@ static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *
     if (blocks < 1) return 0;
     fast_fn ff = general ? nullptr : pick_fast(kp);
     if (!ff) {
-        int rc = launch_general(kp, kp_dev, first, count, blocks, recs, code, peak, nullptr, nullptr, nullptr, st);
+        int rc = launch_general(kp, kp_dev, first, count, blocks, recs, code, peak, nullptr, nullptr, nullptr,
+                                far_base(kp, ws, num_cus, max_blocks), st);
         return rc ? -rc : blocks;
     }
     const size_t lds = fast_lds_bytes(kp);
@@ -1994,7 +2022,7 @@ static int launch_pass(const KParams &kp, uint64_t first, uint64_t count, void *
     int rc = (int)hipGetLastError();
     if (rc) return -rc;
     rc = launch_general(kp, kp_dev, first, count, kDeferBlocks, recs ? recs + blocks : nullptr, code, peak, nullptr, list,
-                        &res->defer_count, st);
+                        &res->defer_count, nullptr, st);
     return rc ? -rc : blocks + kDeferBlocks;
 }
 
@@ -2037,10 +2065,11 @@ int launch_score(const KParams &kp, uint64_t first, uint64_t count, int32_t *cod
     return 0;
 }
 
-int launch_detail(const KParams &kp, uint64_t index, void *ws, void *stream)
+int launch_detail(const KParams &kp, uint64_t index, void *ws, int num_cus, int max_blocks, void *stream)
 {
     int rc = launch_general(kp, (const KParams *)((char *)ws + kWsParamsOff), index, 1, 1, nullptr, nullptr, nullptr,
-                            (DevDetail *)((char *)ws + kWsDetailOff), nullptr, nullptr, (hipStream_t)stream);
+                            (DevDetail *)((char *)ws + kWsDetailOff), nullptr, nullptr, far_base(kp, ws, num_cus, max_blocks),
+                            (hipStream_t)stream);
     return rc;
 }
 
@@ -2082,7 +2111,7 @@ int scratch_workspace(void **ptr, size_t *bytes)
 // the largest grid of the scoring kernels whose records and queues fit `bytes`; 0: not even one workgroup
 int eval_blocks_that_fit(const KParams &kp, int num_cus, size_t bytes)
 {
-    const size_t per_block = sizeof(BlockRec) + (pick_fast(kp) ? (size_t)3 * ring_words(kp) * 4 : 0);
+    const size_t per_block = sizeof(BlockRec) + (pick_fast(kp) ? (size_t)3 * ring_words(kp) * 4 : far_bytes(kp));
     const size_t fixed = ring_offset(0, num_cus) + 512;
     if (bytes < fixed + per_block) return 0;
     int blocks = (int)std::min<size_t>((bytes - fixed) / per_block, (size_t)num_cus * 16);

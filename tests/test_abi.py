@@ -34,7 +34,13 @@ def test_problem_create_validates_on_the_host():
     assert p.workspace_bytes() > 0
     # a block type with two consumers: the micro-batch graph need not be a set of chains
     assert binding.Problem(dict(W.config1(), deps=[(0, 1), (0, 2), (2, 3)])).candidate_count() > 0
+    # up to 32 devices
+    wide = {"name": "wide", "D": 32, "K": 32, "NR": 2, "M": 0, "t": [1] * 32, "m": [0] * 32, "dev_mask": [1 << d for d in range(32)],
+            "deps": [(i, i + 1) for i in range(31)], "space": "sampled_repair", "seed": 1, "lead_step_q16": 100, "fixed_leads": None}
+    assert binding.Problem(wide).candidate_count() == 2 ** 64 - 1
+    assert binding.Problem(wide).workspace_bytes() > 0
     for bad, code in (
+        (dict(wide, D=33), -9),
         (dict(W.config1(), m=[1, 1, -1, 0]), -3),
         (dict(W.config1(), deps=[(0, 1), (1, 0)]), -2),
         (dict(W.config1(), t=[0, 1, 2, 2]), -1),

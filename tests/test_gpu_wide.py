@@ -1,0 +1,144 @@
+"""Problems with more than 8 devices (Table I puts no bound on D; the boundary takes up to 32): scored by the general
+kernel's path for graphs with the lanes' state in global memory.  HIP path against the oracle element by element:
+V-shape pipelines on 12 and 16 devices, a forward-only pipeline on 32, a block on ten devices at once, the two
+exhaustive spaces, seeded random graphs on up to 24 devices; best candidate, its start times and its completion."""
+import numpy as np
+import pytest
+
+from paper_2311_15269_amd import workloads as W
+from tests import schedule_checks as SC
+from tests.test_gpu_dag import _compare
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: the HIP path has no CPU fallback")
+    from paper_2311_15269_amd import binding
+    binding.load_library()
+    return binding
+
+
+def vshape(D, nr, cap, space="sampled_repair", seed=0xA0FFEE0, step=20000):
+    rng = W._Stream(seed)
+    tf = [rng.randint(1, 3) for _ in range(D)]
+    tb = [2 * x for x in tf]
+    return W.pipeline_problem(W.linear_placement(D), tf, tb, D, nr, cap, space, seed=seed, lead_step_q16=step,
+                              name="vshape-%d" % D)
+
+
+def inference(D, nr, space="sampled_repair", seed=0xB0FFEE1, step=30000):
+    """forward-only pipeline, one stage per device, no memory"""
+    rng = W._Stream(seed)
+    return {"name": "inference-%d" % D, "D": D, "K": D, "NR": nr, "M": 0, "t": [rng.randint(1, 4) for _ in range(D)],
+            "m": [0] * D, "dev_mask": [1 << d for d in range(D)], "deps": [(i, i + 1) for i in range(D - 1)],
+            "space": space, "seed": seed, "lead_step_q16": step, "fixed_leads": None}
+
+
+def shared_block(D, nr, cap, space="sampled_repair", seed=0xC0FFEE2):
+    """a linear pipeline on D devices between a block that occupies all of them (forward before the first stage,
+    backward after the last): 4 block types per device"""
+    S = D
+    t = [2] + [1 + (i % 3) for i in range(S)] + [2 + 2 * ((S - 1 - i) % 3) for i in range(S)] + [4]
+    m = [2] + [1] * S + [-1] * S + [-2]
+    full = (1 << D) - 1
+    masks = [full] + [1 << d for d in range(S)] + [1 << d for d in reversed(range(S))] + [full]
+    K = 2 * S + 2
+    return {"name": "shared-%d" % D, "D": D, "K": K, "NR": nr, "M": cap, "t": t, "m": m, "dev_mask": masks,
+            "deps": [(i, i + 1) for i in range(K - 1)], "space": space, "seed": seed, "lead_step_q16": 20000,
+            "fixed_leads": None}
+
+
+SHAPES = [
+    ("vshape-12-repair", vshape(12, 2, 2), 4242, 3000),
+    ("vshape-12-strict", vshape(12, 2, 6, space="sampled_strict", step=8000), 0, 3000),
+    ("vshape-16-repair", vshape(16, 4, 5), 1 << 35, 2000),
+    ("vshape-16-nr8", vshape(16, 8, 12), 7, 600),
+    ("inference-32", inference(32, 2), 99, 3000),
+    ("inference-32-nr8", inference(32, 8), 5, 800),
+    ("shared-10-repair", shared_block(10, 2, 7), 31, 2500),
+    ("shared-10-strict", shared_block(10, 2, 8, space="sampled_strict"), 0, 2500),
+    ("inference-9-canonical", inference(9, 2, space="canonical"), 0, 1 << 20),
+    ("inference-9-factorial", inference(9, 2, space="factorial"), 0, 512),
+    ("vshape-9-strict", vshape(9, 1, 3, space="sampled_strict"), 0, 6000),
+    ("vshape-9-canonical", vshape(9, 1, 3, space="canonical"), 0, 1 << 20),
+    ("vshape-9-factorial", vshape(9, 1, 3, space="factorial"), 0, 1 << 20),
+]
+
+
+@pytest.mark.parametrize("name,prob,first,n", SHAPES, ids=[s[0] for s in SHAPES])
+def test_more_than_eight_devices(gpu, name, prob, first, n):
+    codes = _compare(gpu, prob, first, n)
+    if name in ("vshape-12-repair", "vshape-16-repair", "inference-32", "shared-10-repair"):
+        assert (codes > 0).sum() > 50                      # the comparison covers periods, not only rejects
+
+
+def random_wide_graph(rng):
+    """9-24 devices, forward types then their backward mirrors, every forward type after one or two earlier ones"""
+    while True:
+        D = int(rng.integers(9, 25))
+        S = int(rng.integers(D // 2 + 1, 17))
+        dev = [int(x) for x in rng.integers(0, D, size=S)]
+        if max(2 * dev.count(d) for d in range(D)) > 4:
+            continue
+        fwd = []
+        for i in range(1, S):
+            for a in set(int(x) for x in rng.integers(max(0, i - 3), i, size=int(rng.integers(1, 3)))):
+                fwd.append((a, i))
+        K = 2 * S
+        deps = fwd + [(K - 1 - b, K - 1 - a) for a, b in fwd]
+        sinks = [i for i in range(S) if all(a != i for a, _ in fwd)]
+        deps += [(i, K - 1 - i) for i in sinks]
+        if len(deps) > 60:
+            continue
+        per_dev = max(max(2 * dev.count(d) for d in range(D)), 1)
+        nr = int(rng.integers(1, min(4, 32 // per_dev) + 1))
+        t = [int(x) for x in rng.integers(1, 6, size=K)]
+        masks = [1 << d for d in dev] + [1 << d for d in reversed(dev)]
+        return {"name": "random-wide", "D": D, "K": K, "NR": nr, "M": int(rng.integers(1, 2 * nr + 2)), "t": t,
+                "m": [1] * S + [-1] * S, "dev_mask": masks, "deps": deps,
+                "space": ["sampled_repair", "sampled_repair", "sampled_strict"][int(rng.integers(0, 3))],
+                "seed": int(rng.integers(1, 1 << 30)), "lead_step_q16": int(rng.integers(5000, 60000)), "fixed_leads": None}
+
+
+@pytest.mark.parametrize("seed", [41, 42])
+def test_random_graphs_on_many_devices(gpu, seed):
+    rng = np.random.default_rng(seed)
+    for case in range(6):
+        prob = random_wide_graph(rng)
+        _compare(gpu, prob, int(rng.integers(0, 1 << 40)), int(rng.integers(1000, 3000)))
+
+
+def test_search_and_completion_on_sixteen_devices(gpu):
+    """a whole search on 16 devices: running best over several launches, the greedy completion of the best window"""
+    from oracle import Oracle
+    prob = vshape(16, 2, 6)
+    g, orc = gpu.Problem(prob), Oracle(prob)
+    for first in (0, 5000, 10000):
+        g.eval_candidates(first, 5000)
+    got, want = g.best(), orc.sweep(0, 15000)
+    assert got["n_evaluated"] == 15000 and got["n_feasible"] == want["n_feasible"] and got["n_reject"][1:] == want["n_reject"][1:]
+    assert (got["period"], got["index"], got["peak"]) == (want["period"], want["index"], want["peak"])
+    assert len(got["peak"]) == 16
+    sched = g.complete_schedule(8)
+    ok, makespan, peaks = SC.check_flat_schedule(g.problem, 8, sched["start"].tolist(), sched["dev_order"])
+    assert ok and makespan == sched["makespan"] and max(peaks) <= 6
+    status, leads, orders = orc.decode(got["index"])
+    cand = g.best_candidate()
+    assert cand["leads"] == leads and cand["orders"] == orders
+    ref = orc.complete(leads, orders, 8)
+    assert sched["makespan"] == ref["makespan"] and sched["start"].tolist() == ref["start"].tolist()
+    assert sched["dev_order"] == ref["dev_order"]
+    with pytest.raises(gpu.TesselError) as err:
+        g.search_completions(8, 2, 0, 64)
+    assert err.value.code == -9
+
+
+def test_the_device_limit(gpu):
+    with pytest.raises(gpu.TesselError) as err:
+        gpu.Problem(dict(inference(32, 2), D=33, K=33, t=[1] * 33, m=[0] * 33, dev_mask=[1 << (d % 32) for d in range(33)],
+                         deps=[]))
+    assert err.value.code in (-9, -1)

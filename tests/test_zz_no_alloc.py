@@ -75,6 +75,18 @@ def test_noalloc_other_problems_share_the_buffer(gpu, cfg, count):
         assert got[key] == want[key], (cfg, key)
 
 
+def test_noalloc_more_than_eight_devices(gpu):
+    """16 devices: the general kernel keeps its lanes' state in the buffer too, on as many workgroups as fit"""
+    from tests.test_gpu_wide import vshape
+    for prob, first, count in ((vshape(16, 8, 12), 7, 3000), (vshape(12, 2, 2), 0, 20000)):
+        g = gpu.Problem(prob)
+        g.eval_candidates_noalloc(first, count)
+        got = g.best()
+        want = _reference(gpu, prob, first, count)
+        for key in KEYS:
+            assert got[key] == want[key], (prob["name"], key)
+
+
 def test_noalloc_refuses_what_it_cannot_hold(gpu):
     g = gpu.Problem(W.config5())
     with pytest.raises(gpu.TesselError) as err:
