@@ -2168,6 +2168,17 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
     }
     __syncthreads();
     uint32_t *ckey = lds + kCompParamWords + (nstate + 1) / 2 * kWave + lane;      // [type][lane], behind the 16-bit state
+    // ... and behind the keys one word per block of the window for the replay: device (3 bits), chain (3), micro-batch
+    // within the first window = lead + occurrence (8), has a producer (1), t (16)
+    uint32_t *rtab = lds + kCompParamWords + (nstate + 1) / 2 * kWave + K * kWave;
+    if (single_dev) {
+        for (int s = lane; s < cp.nseq; s += kWave) {
+            const uint32_t pw = ptab[cp.seq[s]];
+            rtab[s] = (pw >> 22 & 7u) | (pw >> 25 & 7u) << 3 | ((pw & 255u) + (uint32_t)cp.occ[s]) << 6 |
+                      ((pw >> 16 & 63u) != 0 ? 1u << 14 : 0u) | (uint32_t)cp.t[cp.seq[s]] << 16;
+        }
+        __syncthreads();
+    }
 #define TESSEL_ST(slot) state[(slot) * kWave]
     int best = INT_MAX;
     uint64_t best_ord = 0;
@@ -2249,12 +2260,23 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                 if (__ballot(busy) == 0) break;
                 if (busy && bi < 0) fail = true;                  // blocks left, none eligible: no schedule
                 if (busy && bi >= 0) {
-                    const int en = best_est + cp.t[bi], mi = cp.m[bi], hi = phase ? N : (int)cp.lead[bi];
-                    const uint32_t mask = cp.mask[bi];
-                    for (int d = 0; d < D; d++)
-                        if (mask >> d & 1u) { TESSEL_ST(oFree + d) = (uint16_t)en; TESSEL_ST(oMem + d) = (uint16_t)((int)(int16_t)TESSEL_ST(oMem + d) + mi); }
-                    TESSEL_ST(oTok + (int)cp.path[bi] * TR + (bmu & tmask)) = (uint16_t)en;
-                    TESSEL_ST(oNext + bi) = (uint16_t)((uint32_t)(bmu + 1) | (bmu + 1 < hi ? jitter(bi, bmu + 1) : 0u) << 10);
+                    const int en = best_est + cp.t[bi];
+                    if (single_dev) {
+                        // its one device, its chain and its memory delta come with the type's table word
+                        const uint32_t pw = ptab[bi];
+                        const int d = (int)(pw >> 22 & 7u), mi = (int)(int8_t)(pw >> 8), hi = phase ? N : (int)(pw & 255u);
+                        TESSEL_ST(oFree + d) = (uint16_t)en;
+                        TESSEL_ST(oMem + d) = (uint16_t)((int)(int16_t)TESSEL_ST(oMem + d) + mi);
+                        TESSEL_ST(oTok + (int)(pw >> 25 & 7u) * TR + (bmu & tmask)) = (uint16_t)en;
+                        TESSEL_ST(oNext + bi) = (uint16_t)((uint32_t)(bmu + 1) | (bmu + 1 < hi ? jitter(bi, bmu + 1) : 0u) << 10);
+                    } else {
+                        const int mi = cp.m[bi], hi = phase ? N : (int)cp.lead[bi];
+                        const uint32_t mask = cp.mask[bi];
+                        for (int d = 0; d < D; d++)
+                            if (mask >> d & 1u) { TESSEL_ST(oFree + d) = (uint16_t)en; TESSEL_ST(oMem + d) = (uint16_t)((int)(int16_t)TESSEL_ST(oMem + d) + mi); }
+                        TESSEL_ST(oTok + (int)cp.path[bi] * TR + (bmu & tmask)) = (uint16_t)en;
+                        TESSEL_ST(oNext + bi) = (uint16_t)((uint32_t)(bmu + 1) | (bmu + 1 < hi ? jitter(bi, bmu + 1) : 0u) << 10);
+                    }
                     left--;
                 }
                 if (single_dev) {
@@ -2276,13 +2298,12 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
             if (single_dev) {
                 for (int k = 0; k < R; k++)
                     for (int s = 0; s < cp.nseq; s++) {
-                        const int i = cp.seq[s];
-                        const uint32_t pw = (uint32_t)__builtin_amdgcn_readfirstlane((int)ptab[i]);
-                        const int mu = (int)(pw & 255u) + (int)cp.occ[s] + NR * k, d = (int)(pw >> 22 & 7u);
-                        const int tok = oTok + (int)(pw >> 25 & 7u) * TR + (mu & tmask);
+                        const uint32_t rw = (uint32_t)__builtin_amdgcn_readfirstlane((int)rtab[s]);
+                        const int mu = (int)(rw >> 6 & 255u) + NR * k, d = (int)(rw & 7u);
+                        const int tok = oTok + (int)(rw >> 3 & 7u) * TR + (mu & tmask);
                         int est = (int)TESSEL_ST(oFree + d);
-                        if ((pw >> 16 & 63u) != 0) est = max(est, (int)TESSEL_ST(tok));
-                        const int en = est + cp.t[i];
+                        if (rw >> 14 & 1u) est = max(est, (int)TESSEL_ST(tok));
+                        const int en = est + (int)(rw >> 16);
                         TESSEL_ST(oFree + d) = (uint16_t)en;
                         TESSEL_ST(tok) = (uint16_t)en;
                     }
@@ -2346,8 +2367,9 @@ __global__ void completion_reset_kernel(DevCompletion *res)
 
 size_t completion_lds_bytes(const CompParams &cp)
 {
-    // 16-bit state, then one 32-bit sort key per type
-    return (size_t)kCompParamWords * 4 + (size_t)((cp.npaths * cp.tok_ring + 2 * cp.D + cp.K + 1) / 2 * 2) * kWave * 2 + (size_t)cp.K * kWave * 4;
+    // 16-bit state, then one 32-bit sort key per type, then one word per block of the window
+    return (size_t)kCompParamWords * 4 + (size_t)((cp.npaths * cp.tok_ring + 2 * cp.D + cp.K + 1) / 2 * 2) * kWave * 2 + (size_t)cp.K * kWave * 4 +
+           (size_t)cp.nseq * 4;
 }
 
 int launch_completions(const CompParams &cp, uint64_t first, uint64_t count, int32_t *makespan_out, void *ws, int num_cus,
