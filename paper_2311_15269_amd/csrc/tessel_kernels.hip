@@ -2132,8 +2132,8 @@ int eval_blocks_that_fit(const KParams &kp, int num_cus, size_t bytes)
 // Per-lane state in LDS [slot][lane], 16-bit words: end time of the latest block of every micro-batch in flight
 // (a ring per chain), free time and memory of every device, next micro-batch and its jitter of every type; behind
 // it, for problems with every type on one device, one 32-bit sort key per type.
-constexpr int kCompParamWords = 320;       // start of the LDS: the parameter block's copy, then two tables of kMaxK words at the end
-static_assert(sizeof(CompParams) <= (kCompParamWords - 2 * kMaxK) * 4, "parameter block and per-type tables share the start of the LDS");
+constexpr int kCompParamWords = 352;       // start of the LDS: the parameter block's copy, then three tables of kMaxK words at the end
+static_assert(sizeof(CompParams) <= (kCompParamWords - 3 * kMaxK) * 4, "parameter block and per-type tables share the start of the LDS");
 
 __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__restrict__ cpg, uint64_t first, uint64_t count,
                                                          CompRec *__restrict__ recs, int32_t *__restrict__ makespan_out)
@@ -2148,23 +2148,29 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
     // a type's next micro-batch (low 10 bits) and the jitter of that block (high 6 bits) share a word: N < 1024 and
     // J < 64 (checked by the host)
     const int TR = cp.tok_ring, tmask = TR - 1;          // end times of the micro-batches in flight: [chain][mu mod TR]
+    const int trs = __builtin_ctz((uint32_t)TR);         // (a power of two)
     const int oTok = 0, oFree = cp.npaths * TR, oMem = oFree + D, oNext = oMem + D, nstate = oNext + K;
     // Problems with every type on one device (and at most 8 chains) take a path that keeps, per type, the sort key of
-    // its offered block (or "not eligible") in LDS and recomputes only the types a scheduled block can change: those
-    // on its device and its consumer.  Tables for it, per type: `ptab` lead (8 bits), memory delta (8, signed),
-    // producer + 1 (6), device (3), chain (3), 1 (a type of the problem) in one word; `aff` the types to recompute.
+    // its offered block in LDS and touches only the types a scheduled block can change: its own type and its consumers
+    // are recomputed (`redo`); of the other types on its device (`aff`) a key that exists only moves to the device's new
+    // free time and is checked against its new memory.  Tables, per type: `ptab` lead (8 bits), memory delta (8,
+    // signed), producer + 1 (6), device (3), chain (3), 1 (a type of the problem) in one word.
     bool single_dev = cp.npaths <= 8;
     for (int i = 0; i < K; i++) single_dev = single_dev && (cp.mask[i] & (cp.mask[i] - 1)) == 0 && cp.mask[i] != 0;
-    uint32_t *ptab = lds + kCompParamWords - 2 * kMaxK, *aff = lds + kCompParamWords - kMaxK;
+    uint32_t *ptab = lds + kCompParamWords - 3 * kMaxK, *aff = lds + kCompParamWords - 2 * kMaxK, *redo = lds + kCompParamWords - kMaxK;
     if (lane < kMaxK) {
-        uint32_t pw = 0, af = 0;
+        uint32_t pw = 0, af = 0, rd = 0;
         if (lane < K) {
             pw = (uint32_t)cp.lead[lane] | ((uint32_t)(uint8_t)cp.m[lane] << 8) | ((uint32_t)(cp.pred[lane] + 1) << 16) |
                  ((uint32_t)__builtin_ctz((uint32_t)cp.mask[lane] | 0x100u) << 22) | ((uint32_t)cp.path[lane] << 25) | 1u << 28;
-            for (int j = 0; j < K; j++)
-                if ((cp.mask[j] & cp.mask[lane]) != 0 || cp.pred[j] == lane) af |= 1u << j;
+            rd = 1u << lane;
+            for (int j = 0; j < K; j++) {
+                if (cp.pred[j] == lane) rd |= 1u << j;
+                if ((cp.mask[j] & cp.mask[lane]) != 0) af |= 1u << j;
+            }
+            af &= ~rd;
         }
-        ptab[lane] = pw; aff[lane] = af;
+        ptab[lane] = pw; aff[lane] = af; redo[lane] = rd;
     }
     __syncthreads();
     uint32_t *ckey = lds + kCompParamWords + (nstate + 1) / 2 * kWave + lane;      // [type][lane], behind the 16-bit state
@@ -2205,7 +2211,9 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                 left += max(hi - mu, 0);
             }
             // sort key of the block type i offers, (start + jitter, micro-batch, type) in one word, smallest first:
-            // start + jitter < 2^16 (checked by the host), micro-batch < 2^10, type < 2^5; all ones: not eligible
+            // start + jitter < 2^16 (checked by the host) in bits 15-30, micro-batch < 2^10, type < 2^5.  All ones:
+            // nothing offered, or its producer has not handled the micro-batch yet; bit 31 on a key: offered, but its
+            // memory does not fit now (the key below stays valid)
             auto offer_key = [&](int i) -> uint32_t {
                 const uint32_t pw = ptab[i];
                 const bool has_a = (pw >> 16 & 63u) != 0;
@@ -2214,21 +2222,21 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                 const int nj = (int)TESSEL_ST(oNext + i), mu = nj & 1023;
                 const int na = (int)TESSEL_ST(oNext + (has_a ? a : i)) & 1023;
                 const int fr = (int)TESSEL_ST(oFree + d), me = (int)(int16_t)TESSEL_ST(oMem + d);
-                const int tk = (int)TESSEL_ST(oTok + (int)(pw >> 25 & 7u) * TR + (mu & tmask));
-                const bool ok = (mu < hi) & (!has_a | (na > mu)) & ((mi <= 0) | (me + mi <= M));
+                const int tk = (int)TESSEL_ST(oTok + ((int)(pw >> 25 & 7u) << trs) + (mu & tmask));
+                const bool offered = (mu < hi) & (!has_a | (na > mu)), fits = (mi <= 0) | (me + mi <= M);
                 const uint32_t key = (uint32_t)(max(has_a ? tk : 0, fr) + (nj >> 10));
-                return ok ? (key << 15) | ((uint32_t)mu << 5) | (uint32_t)i : 0xFFFFFFFFu;
+                return offered ? (key << 15) | ((uint32_t)mu << 5) | (uint32_t)i | (fits ? 0u : 0x80000000u) : 0xFFFFFFFFu;
             };
             if (single_dev)
                 for (int i = 0; i < K; i++) ckey[i * kWave] = offer_key(i);
             for (;;) {
-                int bi = -1, bmu = 0, best_est = 0, bkey = 0;
+                int bi = -1, bmu = 0, best_est = 0, bkey = 0, en = 0, me_new = 0;
                 const bool any = left > 0;
                 if (single_dev) {
                     uint32_t bestp = 0xFFFFFFFFu;
 #pragma unroll 8
                     for (int i = 0; i < K; i++) bestp = min(bestp, ckey[i * kWave]);
-                    if (bestp != 0xFFFFFFFFu) {
+                    if (bestp < 0x80000000u) {
                         bi = (int)(bestp & 31u); bmu = (int)(bestp >> 5 & 1023u); bkey = (int)(bestp >> 15);
                         best_est = bkey - ((int)TESSEL_ST(oNext + bi) >> 10);
                     }
@@ -2260,14 +2268,15 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                 if (__ballot(busy) == 0) break;
                 if (busy && bi < 0) fail = true;                  // blocks left, none eligible: no schedule
                 if (busy && bi >= 0) {
-                    const int en = best_est + cp.t[bi];
+                    en = best_est + cp.t[bi];
                     if (single_dev) {
                         // its one device, its chain and its memory delta come with the type's table word
                         const uint32_t pw = ptab[bi];
                         const int d = (int)(pw >> 22 & 7u), mi = (int)(int8_t)(pw >> 8), hi = phase ? N : (int)(pw & 255u);
+                        me_new = (int)(int16_t)TESSEL_ST(oMem + d) + mi;
                         TESSEL_ST(oFree + d) = (uint16_t)en;
-                        TESSEL_ST(oMem + d) = (uint16_t)((int)(int16_t)TESSEL_ST(oMem + d) + mi);
-                        TESSEL_ST(oTok + (int)(pw >> 25 & 7u) * TR + (bmu & tmask)) = (uint16_t)en;
+                        TESSEL_ST(oMem + d) = (uint16_t)me_new;
+                        TESSEL_ST(oTok + ((int)(pw >> 25 & 7u) << trs) + (bmu & tmask)) = (uint16_t)en;
                         TESSEL_ST(oNext + bi) = (uint16_t)((uint32_t)(bmu + 1) | (bmu + 1 < hi ? jitter(bi, bmu + 1) : 0u) << 10);
                     } else {
                         const int mi = cp.m[bi], hi = phase ? N : (int)cp.lead[bi];
@@ -2280,13 +2289,48 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                     left--;
                 }
                 if (single_dev) {
-                    // the scheduled block changes what the types on its device and its consumer offer
-                    uint32_t todo = busy && bi >= 0 ? aff[bi] : 0u;
+                    // The scheduled block changes what its own type and its consumer offer (recomputed), and for the
+                    // other types on its device (three at most) the free time and the memory: start = max(end of the
+                    // producer's block, device free), and the device was free no later than now before, so the new key
+                    // is max(old key, new free time + jitter); the same micro-batch stays offered.  Straight-line, with
+                    // the block's own type standing in for what a lane does not have, so that all the LDS reads of
+                    // the five updates are in flight together; only the writes are per lane.
+                    const bool placed = busy && bi >= 0;
+                    const int b = placed ? bi : 0;
+                    const uint32_t rd = redo[b] & ~(1u << b), af = aff[b];
+                    const uint32_t af1 = af & (af - 1u), af2 = af1 & (af1 - 1u);
+                    const bool has_c = placed && rd != 0, h0 = placed && af != 0, h1 = placed && af1 != 0, h2 = placed && af2 != 0;
+                    const int c = has_c ? __builtin_ctz(rd) : b;
+                    const int a0 = h0 ? __builtin_ctz(af) : b, a1 = h1 ? __builtin_ctz(af1) : b, a2 = h2 ? __builtin_ctz(af2) : b;
+                    auto moved = [&](int i) -> uint32_t {
+                        const uint32_t k = ckey[i * kWave];
+                        const int mi = (int)(int8_t)(ptab[i] >> 8);
+                        const uint32_t start = max(k << 1 >> 16, (uint32_t)en + ((uint32_t)TESSEL_ST(oNext + i) >> 10));
+                        const bool fits = (mi <= 0) | (me_new + mi <= M);
+                        return k == 0xFFFFFFFFu ? k : (start << 15) | (k & 0x7FFFu) | (fits ? 0u : 0x80000000u);
+                    };
+                    const uint32_t kb = offer_key(b), kc = offer_key(c), k0 = moved(a0), k1 = moved(a1), k2 = moved(a2);
+                    if (placed) ckey[b * kWave] = kb;
+                    if (has_c) ckey[c * kWave] = kc;
+                    if (h0) ckey[a0 * kWave] = k0;
+                    if (h1) ckey[a1 * kWave] = k1;
+                    if (h2) ckey[a2 * kWave] = k2;
+                    // (a type with several consumers, or more than four types on a device: the rest one by one)
+                    uint32_t todo = placed ? rd & (rd - 1u) : 0u;
                     while (__ballot(todo != 0u) != 0) {
                         if (todo != 0u) {
                             const int i = __builtin_ctz(todo);
                             todo &= todo - 1u;
                             ckey[i * kWave] = offer_key(i);
+                        }
+                    }
+                    todo = placed ? af2 & (af2 - 1u) : 0u;
+                    while (__ballot(todo != 0u) != 0) {
+                        if (todo != 0u) {
+                            const int i = __builtin_ctz(todo);
+                            todo &= todo - 1u;
+                            const uint32_t k = moved(i);
+                            ckey[i * kWave] = k;
                         }
                     }
                 }
@@ -2300,7 +2344,7 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                     for (int s = 0; s < cp.nseq; s++) {
                         const uint32_t rw = (uint32_t)__builtin_amdgcn_readfirstlane((int)rtab[s]);
                         const int mu = (int)(rw >> 6 & 255u) + NR * k, d = (int)(rw & 7u);
-                        const int tok = oTok + (int)(rw >> 3 & 7u) * TR + (mu & tmask);
+                        const int tok = oTok + ((int)(rw >> 3 & 7u) << trs) + (mu & tmask);
                         int est = (int)TESSEL_ST(oFree + d);
                         if (rw >> 14 & 1u) est = max(est, (int)TESSEL_ST(tok));
                         const int en = est + (int)(rw >> 16);
