@@ -52,6 +52,7 @@ struct tessel_problem {
     bool comp_ready = false;            // CompParams of (comp_index, N, J) are in the workspace
     uint64_t comp_index = 0;            // best candidate they were built for
     CompParams comp;
+    CompMatrix comp_matrix;
 };
 
 static_assert(kScratchBytes == TESSEL_NOALLOC_SCRATCH_BYTES, "header and library disagree on the size of the library's own workspace");
@@ -840,6 +841,58 @@ extern "C" int tessel_complete_schedule(tessel_problem *p, tessel_schedule *out)
 
 // ---- searched completion: many perturbed greedy completions scored on the GPU -----------------------
 // uploads what the kernel needs of the problem and of the best candidate (once per best candidate, N, J)
+// The R replayed windows as a (max, +) matrix (CompMatrix), for problems whose types sit on one device each and that
+// the kernel's per-type path takes.  A dry run of the replay finds the state slots read before they are written (the
+// inputs) and the slots written (the outputs); one run per input with that input at 0 and the others at "no path"
+// gives the longest paths.
+static void window_matrix(const CompParams &cp, CompMatrix &cm)
+{
+    memset(&cm, 0, sizeof cm);
+    bool single = cp.npaths <= 8;
+    for (int i = 0; i < cp.K; i++) single = single && cp.mask[i] != 0 && (cp.mask[i] & (cp.mask[i] - 1)) == 0;
+    if (!single) return;
+    const int TR = cp.tok_ring, tmask = TR - 1, oFree = cp.npaths * TR, nslot = oFree + cp.D;      // rings first, then the devices
+    struct Blk { int fr, tk, t; bool has_a; };
+    std::vector<Blk> blocks;
+    for (int k = 0; k < cp.R; k++)
+        for (int s = 0; s < cp.nseq; s++) {
+            const int i = cp.seq[s], mu = (int)cp.lead[i] + (int)cp.occ[s] + cp.NR * k;
+            blocks.push_back({oFree + __builtin_ctz((unsigned)cp.mask[i]), (int)cp.path[i] * TR + (mu & tmask), cp.t[i], cp.pred[i] >= 0});
+        }
+    std::vector<int> state(nslot, 0);                       // 0 untouched, 1 read first, 2 written first; then: written at all
+    std::vector<char> written(nslot, 0);
+    for (const Blk &b : blocks) {
+        if (!state[b.fr]) state[b.fr] = 1;
+        if (b.has_a && !state[b.tk]) state[b.tk] = 1;
+        if (!state[b.fr]) state[b.fr] = 2;
+        if (!state[b.tk]) state[b.tk] = 2;
+        written[b.fr] = written[b.tk] = 1;
+    }
+    std::vector<int> in, out;
+    for (int v = 0; v < nslot; v++) { if (state[v] == 1) in.push_back(v); if (written[v]) out.push_back(v); }
+    if (in.empty() || (int)in.size() > kMatIn || (int)out.size() > kMatOut) return;
+    const long long none = -(1ll << 60);
+    for (int o = 0; o < kMatOut; o++) for (int j = 0; j < kMatIn; j++) cm.a[o][j] = kNoPath;
+    for (size_t j = 0; j < in.size(); j++) {
+        std::vector<long long> x(nslot, none);
+        x[in[j]] = 0;
+        for (const Blk &b : blocks) {
+            long long est = x[b.fr];
+            if (b.has_a) est = std::max(est, x[b.tk]);
+            x[b.fr] = x[b.tk] = est + b.t;
+        }
+        for (size_t o = 0; o < out.size(); o++) if (x[out[o]] >= 0) cm.a[o][j] = (int32_t)x[out[o]];
+    }
+    for (size_t o = 0; o < out.size(); o++) {               // every output must depend on some input
+        bool any = false;
+        for (size_t j = 0; j < in.size(); j++) any = any || cm.a[o][j] != kNoPath;
+        if (!any) return;
+    }
+    for (size_t j = 0; j < in.size(); j++) cm.in_slot[j] = (uint16_t)in[j];
+    for (size_t o = 0; o < out.size(); o++) cm.out_slot[o] = (uint16_t)out[o];
+    cm.nin = (int32_t)in.size(); cm.nout = (int32_t)out.size();
+}
+
 static int bind_completion(tessel_problem *p, int N, int J)
 {
     if (p->ws && p->ws_ready && !owns_workspace(p)) return TESSEL_E_WORKSPACE;      // the buffer is another handle's by now
@@ -912,8 +965,15 @@ static int bind_completion(tessel_problem *p, int N, int J)
         for (int i = 0; i < K; i++) total += (long long)p->t[i] * N;
         if (total + J > 65535 || std::abs(p->kp.M) > 30000 || N > 1023 || J > 63) return TESSEL_E_TOOBIG;
     }
-    if (completion_lds_bytes(cp) > 64 * 1024) return TESSEL_E_TOOBIG;
+
+    window_matrix(cp, p->comp_matrix);
+    if (const char *env = getenv("TESSEL_REPLAY_BLOCKS")) {        // test knob: replay the windows block by block
+        if (env[0] == '1') p->comp_matrix.nin = 0;
+    }
+    if (completion_lds_bytes(cp, p->comp_matrix) > 64 * 1024) return TESSEL_E_TOOBIG;
     hipError_t e = hipMemcpyAsync((char *)p->ws + kWsCompParamsOff, &cp, sizeof cp, hipMemcpyHostToDevice, p->stream);
+    if (e != hipSuccess) return hip_fail(p, (int)e);
+    e = hipMemcpyAsync((char *)p->ws + kWsCompMatrixOff, &p->comp_matrix, sizeof(CompMatrix), hipMemcpyHostToDevice, p->stream);
     if (e != hipSuccess) return hip_fail(p, (int)e);
     int le = launch_completion_reset(p->ws, p->stream);
     if (le) return hip_fail(p, le);
@@ -928,7 +988,7 @@ extern "C" int tessel_search_completions(tessel_problem *p, int32_t num_microbat
     if (first + count < first) return TESSEL_E_RANGE;
     int rc = bind_completion(p, num_microbatches, jitter);
     if (rc) return rc;
-    int e = launch_completions(p->comp, first, count, nullptr, p->ws, p->num_cus, p->stream);
+    int e = launch_completions(p->comp, p->comp_matrix, first, count, nullptr, p->ws, p->num_cus, p->stream);
     return e < 0 ? TESSEL_E_TOOBIG : e ? hip_fail(p, e) : TESSEL_OK;
 }
 
@@ -939,7 +999,7 @@ extern "C" int tessel_score_completions(tessel_problem *p, int32_t num_microbatc
     if (first + count < first) return TESSEL_E_RANGE;
     int rc = bind_completion(p, num_microbatches, jitter);
     if (rc) return rc;
-    int e = launch_completions(p->comp, first, count, makespan_dev, p->ws, p->num_cus, p->stream);
+    int e = launch_completions(p->comp, p->comp_matrix, first, count, makespan_dev, p->ws, p->num_cus, p->stream);
     return e < 0 ? TESSEL_E_TOOBIG : e ? hip_fail(p, e) : TESSEL_OK;
 }
 

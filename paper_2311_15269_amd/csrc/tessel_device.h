@@ -178,6 +178,17 @@ struct CompParams {
     uint8_t  seq[kMaxSeq];           // the window's blocks (types) in an executable order
     uint8_t  occ[kMaxSeq];           // occurrence number of seq[s] among the earlier entries of its type
 };
+// The R replayed windows of a completion candidate as one linear map in the (max, +) algebra: every state slot the
+// windows write (device free times, end times in the rings) is the largest of (input + longest path) over the slots
+// they read before writing them.  The same for every candidate, since the window is; computed on the host.
+constexpr int kMatIn = 16, kMatOut = 32;
+constexpr int32_t kNoPath = -(1 << 24);
+struct CompMatrix {
+    int32_t  nin, nout;              // nin = 0: not available (the kernel replays the windows block by block)
+    uint16_t in_slot[kMatIn];        // state slots (numbering of the kernel), in the order of the columns
+    uint16_t out_slot[kMatOut];
+    int32_t  a[kMatOut][kMatIn];     // kNoPath: no path; columns from nin on are kNoPath
+};
 struct DevCompletion {
     int32_t  makespan;               // INT32_MAX = nothing scheduled yet
     int32_t  pad;
@@ -194,7 +205,8 @@ constexpr size_t kWsTablesMax = 1 << 20;
 constexpr size_t kWsListOff = kWsTablesOff + kWsTablesMax;     // candidates deferred to the general kernel
 constexpr uint32_t kWsListCap = 1u << 20;
 constexpr size_t kWsCompParamsOff = kWsListOff + (size_t)kWsListCap * 8;   // CompParams
-constexpr size_t kWsBlockRecOff = kWsCompParamsOff + 1024;
+constexpr size_t kWsCompMatrixOff = kWsCompParamsOff + 1024;              // CompMatrix
+constexpr size_t kWsBlockRecOff = kWsCompMatrixOff + 3072;
 constexpr int kDeferBlocks = 64;                                // grid of the deferred pass
 constexpr int kFirstPassTries = 2;                              // sweeps before a candidate queues for the longer search
 constexpr uint64_t kMaxPerLaunch = 1ull << 26;                  // candidates per pass of the kernels
@@ -209,6 +221,7 @@ constexpr int kStageMetaWords = 12;                             // ring 1: R, HM
 
 static_assert(sizeof(CompParams) <= 1024, "completion parameters must fit their workspace slot");
 static_assert(sizeof(DevResult) <= kWsCompletionOff && kWsCompletionOff + sizeof(DevCompletion) <= kWsDetailOff, "result records overlap");
+static_assert(sizeof(CompParams) <= 1024 && sizeof(CompMatrix) <= 3072, "completion parameters must fit their workspace slots");
 static_assert(sizeof(KParams) <= kWsTablesOff - kWsParamsOff, "parameter block must fit its workspace slot");
 static_assert(sizeof(DevDetail) <= kWsParamsOff - kWsDetailOff, "detail record must fit its workspace slot");
 
@@ -228,8 +241,8 @@ int eval_blocks_that_fit(const KParams &kp, int num_cus, size_t bytes);
 int launch_detail(const KParams &kp, uint64_t index, void *ws, int num_cus, int max_blocks, void *stream);
 int launch_reset(void *ws, void *stream);
 // completion search: S = state words per lane; returns 0 or a HIP error (negative: LDS need exceeds the device's)
-size_t completion_lds_bytes(const CompParams &cp);
-int launch_completions(const CompParams &cp, uint64_t first, uint64_t count, int32_t *makespan_out, void *ws, int num_cus,
+size_t completion_lds_bytes(const CompParams &cp, const CompMatrix &cm);
+int launch_completions(const CompParams &cp, const CompMatrix &cm, uint64_t first, uint64_t count, int32_t *makespan_out, void *ws, int num_cus,
                        void *stream);
 int launch_completion_reset(void *ws, void *stream);
 int launch_alu_probe(uint32_t *out, int blocks, int rounds, void *stream);

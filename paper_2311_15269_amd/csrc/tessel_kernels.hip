@@ -2135,7 +2135,8 @@ int eval_blocks_that_fit(const KParams &kp, int num_cus, size_t bytes)
 constexpr int kCompParamWords = 352;       // start of the LDS: the parameter block's copy, then three tables of kMaxK words at the end
 static_assert(sizeof(CompParams) <= (kCompParamWords - 3 * kMaxK) * 4, "parameter block and per-type tables share the start of the LDS");
 
-__global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__restrict__ cpg, uint64_t first, uint64_t count,
+__global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__restrict__ cpg, const CompMatrix *__restrict__ cmg,
+                                                         uint64_t first, uint64_t count,
                                                          CompRec *__restrict__ recs, int32_t *__restrict__ makespan_out)
 {
     extern __shared__ uint32_t lds[];
@@ -2174,10 +2175,18 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
     }
     __syncthreads();
     uint32_t *ckey = lds + kCompParamWords + (nstate + 1) / 2 * kWave + lane;      // [type][lane], behind the 16-bit state
-    // ... and behind the keys one word per block of the window for the replay: device (3 bits), chain (3), micro-batch
-    // within the first window = lead + occurrence (8), has a producer (1), t (16)
+    // ... and behind the keys what the replay of the R windows needs.  Either their (max, +) matrix: kMatIn slot
+    // numbers of the inputs, kMatOut of the outputs, then one row of kMatIn path lengths per output; or (no matrix: too
+    // many values cross the windows) one word per block of the window: device (3 bits), chain (3), micro-batch within
+    // the first window = lead + occurrence (8), has a producer (1), t (16)
     uint32_t *rtab = lds + kCompParamWords + (nstate + 1) / 2 * kWave + K * kWave;
-    if (single_dev) {
+    const int nin = single_dev ? cmg->nin : 0, nout = cmg->nout;
+    if (nin > 0) {
+        for (int s = lane; s < kMatIn; s += kWave) rtab[s] = cmg->in_slot[s];
+        for (int s = lane; s < kMatOut; s += kWave) rtab[kMatIn + s] = cmg->out_slot[s];
+        for (int s = lane; s < nout * kMatIn; s += kWave) rtab[kMatIn + kMatOut + s] = (uint32_t)cmg->a[s / kMatIn][s % kMatIn];
+        __syncthreads();
+    } else if (single_dev) {
         for (int s = lane; s < cp.nseq; s += kWave) {
             const uint32_t pw = ptab[cp.seq[s]];
             rtab[s] = (pw >> 22 & 7u) | (pw >> 25 & 7u) << 3 | ((pw & 255u) + (uint32_t)cp.occ[s]) << 6 |
@@ -2339,7 +2348,23 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
             // ---- the R windows: the same blocks at the same micro-batches in every lane.  (Every type on one device:
             // from the per-type table, and without the memory, which a whole window leaves as it was: the deltas on a
             // device sum to zero, and the window itself was scored against the cap.)
-            if (single_dev) {
+            if (nin > 0) {
+                // all R windows at once: every slot they write = max over the slots they read first of (value + longest path)
+                int x[kMatIn];
+#pragma unroll
+                for (int j = 0; j < kMatIn; j++) x[j] = j < nin ? (int)TESSEL_ST(__builtin_amdgcn_readfirstlane((int)rtab[j])) : 0;
+                for (int o = 0; o < nout; o++) {
+                    const int4 *row = (const int4 *)(rtab + kMatIn + kMatOut + o * kMatIn);
+                    int acc = 0;                         // (every output has a path from some input, and times are >= 0)
+#pragma unroll
+                    for (int q = 0; q < kMatIn / 4; q++) {
+                        const int4 a = row[q];
+                        acc = max(acc, max(x[4 * q] + a.x, x[4 * q + 1] + a.y));
+                        acc = max(acc, max(x[4 * q + 2] + a.z, x[4 * q + 3] + a.w));
+                    }
+                    TESSEL_ST(__builtin_amdgcn_readfirstlane((int)rtab[kMatIn + o])) = (uint16_t)acc;
+                }
+            } else if (single_dev) {
                 for (int k = 0; k < R; k++)
                     for (int s = 0; s < cp.nseq; s++) {
                         const uint32_t rw = (uint32_t)__builtin_amdgcn_readfirstlane((int)rtab[s]);
@@ -2409,18 +2434,19 @@ __global__ void completion_reset_kernel(DevCompletion *res)
     if (threadIdx.x == 0 && blockIdx.x == 0) { res->makespan = INT_MAX; res->pad = 0; res->ordinal = ~0ull; }
 }
 
-size_t completion_lds_bytes(const CompParams &cp)
+size_t completion_lds_bytes(const CompParams &cp, const CompMatrix &cm)
 {
-    // 16-bit state, then one 32-bit sort key per type, then one word per block of the window
+    // 16-bit state, then one 32-bit sort key per type, then the windows' matrix or one word per block of the window
+    const size_t replay = cm.nin > 0 ? (size_t)(kMatIn + kMatOut + cm.nout * kMatIn) * 4 : (size_t)cp.nseq * 4;
     return (size_t)kCompParamWords * 4 + (size_t)((cp.npaths * cp.tok_ring + 2 * cp.D + cp.K + 1) / 2 * 2) * kWave * 2 + (size_t)cp.K * kWave * 4 +
-           (size_t)cp.nseq * 4;
+           ((replay + 15) & ~(size_t)15);
 }
 
-int launch_completions(const CompParams &cp, uint64_t first, uint64_t count, int32_t *makespan_out, void *ws, int num_cus,
-                       void *stream)
+int launch_completions(const CompParams &cp, const CompMatrix &cm, uint64_t first, uint64_t count, int32_t *makespan_out, void *ws,
+                       int num_cus, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const size_t lds = completion_lds_bytes(cp);
+    const size_t lds = completion_lds_bytes(cp, cm);
     if (lds > 64 * 1024) return -1;
     static bool attr_set = false;
     if (!attr_set && lds > 48 * 1024) {
@@ -2435,7 +2461,8 @@ int launch_completions(const CompParams &cp, uint64_t first, uint64_t count, int
     const int blocks = need < (uint64_t)(num_cus * per_cu) ? (int)need : num_cus * per_cu;
     if (blocks < 1) return 0;
     CompRec *recs = makespan_out ? nullptr : (CompRec *)((char *)ws + kWsBlockRecOff);
-    hipLaunchKernelGGL(complete_kernel, dim3(blocks), dim3(kWave), lds, st, (const CompParams *)((char *)ws + kWsCompParamsOff), first,
+    hipLaunchKernelGGL(complete_kernel, dim3(blocks), dim3(kWave), lds, st, (const CompParams *)((char *)ws + kWsCompParamsOff),
+                       (const CompMatrix *)((char *)ws + kWsCompMatrixOff), first,
                        count, recs, makespan_out);
     int rc = (int)hipGetLastError();
     if (rc || !recs) return rc;

@@ -66,6 +66,25 @@ def test_completion_candidates_match_the_oracle(gpu, name, prob, budget, N, J, n
     assert greedy["makespan"] == want[0] >= sched["makespan"]
 
 
+def test_the_windows_block_by_block_equal_their_matrix(gpu, monkeypatch):
+    """The kernel applies the R replayed windows as one (max, +) matrix; TESSEL_REPLAY_BLOCKS=1 makes it run them
+    block by block instead (the path of windows with too many crossing values): both equal the oracle."""
+    from oracle import Oracle
+    for prob, budget, N, J, ncand in ((W.config5(), 2048, 40, 3, 400), (W.config3(), 4096, 33, 2, 500),
+                                      (W.xshape_problem(4, 1, 2, 2, 4), 4096, 11, 1, 300)):
+        o = Oracle(prob)
+        scores = []
+        for replay in ("0", "1"):
+            monkeypatch.setenv("TESSEL_REPLAY_BLOCKS", replay)
+            g = gpu.Problem(prob)
+            g.eval_candidates(0, budget)
+            status, leads, orders = o.decode(g.best()["index"])
+            scores.append(g.score_completions(N, J, 3, ncand).cpu().numpy())
+        monkeypatch.delenv("TESSEL_REPLAY_BLOCKS")
+        want, _, _ = o.completion_scores(leads, orders, N, 3, ncand, J)
+        assert np.array_equal(scores[0], want) and np.array_equal(scores[1], want), prob["name"]
+
+
 def test_completion_argument_checks(gpu):
     g = gpu.Problem(W.config3())
     with pytest.raises(gpu.TesselError) as e:
