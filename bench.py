@@ -180,8 +180,9 @@ def main():
                "roofline": {"bound": "alu", "achieved": ops * rate / 1e12, "peak": PEAK_INT32_OPS, "unit": "Tint32op/s",
                             "frac": ops * rate / 1e12 / PEAK_INT32_OPS, "traffic": None, "kernel": "complete_kernel",
                             "algorithmic_ops_per_candidate": ops,
-                            "limited_by": "LDS latency: per-lane state of the greedy phases is read and written through "
-                                          "dependent LDS accesses (profiles/complete_kernel_cfg5_kernel_trace_counters.md)"}}
+                            "limited_by": "latency: every scheduled block of the greedy phases is a chain of dependent per-lane "
+                                          "decisions through LDS, at two waves per SIMD "
+                                          "(profiles/complete_kernel_cfg5_kernel_trace_counters.md)"}}
         if not args.no_cpu_baseline:
             from oracle import Oracle
             orc = Oracle(prob)
