@@ -2173,6 +2173,8 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
         }
         ptab[lane] = pw; aff[lane] = af; redo[lane] = rd;
     }
+    // some type has several consumers, or more than three other types on its device (wave-uniform)
+    const bool crowded = __ballot(lane < K && (__builtin_popcount(redo[lane]) > 2 || __builtin_popcount(aff[lane]) > 3)) != 0;
     __syncthreads();
     uint32_t *ckey = lds + kCompParamWords + (nstate + 1) / 2 * kWave + lane;      // [type][lane], behind the 16-bit state
     // ... and behind the keys what the replay of the R windows needs.  Either their (max, +) matrix: kMatIn slot
@@ -2236,20 +2238,80 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                 const uint32_t key = (uint32_t)(max(has_a ? tk : 0, fr) + (nj >> 10));
                 return offered ? (key << 15) | ((uint32_t)mu << 5) | (uint32_t)i | (fits ? 0u : 0x80000000u) : 0xFFFFFFFFu;
             };
-            if (single_dev)
+            if (single_dev) {
+                // ---- every type on one device: one straight-line step per scheduled block
                 for (int i = 0; i < K; i++) ckey[i * kWave] = offer_key(i);
-            for (;;) {
-                int bi = -1, bmu = 0, best_est = 0, bkey = 0, en = 0, me_new = 0;
-                const bool any = left > 0;
-                if (single_dev) {
+                for (;;) {
+                    const bool busy = live && !fail && left > 0;
+                    if (__ballot(busy) == 0) break;
                     uint32_t bestp = 0xFFFFFFFFu;
 #pragma unroll 8
                     for (int i = 0; i < K; i++) bestp = min(bestp, ckey[i * kWave]);
-                    if (bestp < 0x80000000u) {
-                        bi = (int)(bestp & 31u); bmu = (int)(bestp >> 5 & 1023u); bkey = (int)(bestp >> 15);
-                        best_est = bkey - ((int)TESSEL_ST(oNext + bi) >> 10);
+                    const bool placed = busy && bestp < 0x80000000u;
+                    if (busy && !placed) fail = true;             // blocks left, none eligible: no schedule
+                    // A lane that places nothing goes through the step with type 0 and writes nothing.  The block's
+                    // device, chain and memory delta come with its type's table word.
+                    const int b = placed ? (int)(bestp & 31u) : 0, bmu = (int)(bestp >> 5 & 1023u);
+                    const uint32_t pw = ptab[b], rd = redo[b] & ~(1u << b), af = aff[b];
+                    const int d = (int)(pw >> 22 & 7u), mi_b = (int)(int8_t)(pw >> 8), hi_b = phase ? N : (int)(pw & 255u);
+                    const int en = (int)(bestp >> 15) - ((int)TESSEL_ST(oNext + b) >> 10) + cp.t[b];
+                    const int me_new = (int)(int16_t)TESSEL_ST(oMem + d) + mi_b;
+                    const uint32_t jn = jitter(b, bmu + 1);
+                    if (placed) {
+                        TESSEL_ST(oFree + d) = (uint16_t)en;
+                        TESSEL_ST(oMem + d) = (uint16_t)me_new;
+                        TESSEL_ST(oTok + ((int)(pw >> 25 & 7u) << trs) + (bmu & tmask)) = (uint16_t)en;
+                        TESSEL_ST(oNext + b) = (uint16_t)((uint32_t)(bmu + 1) | (bmu + 1 < hi_b ? jn : 0u) << 10);
+                        left--;
                     }
-                } else
+                    // The scheduled block changes what its own type and its consumer offer (recomputed), and for the
+                    // other types on its device (three at most) the free time and the memory: start = max(end of the
+                    // producer's block, device free), and the device was free no later than now before, so the new key
+                    // is max(old key, new free time + jitter); the same micro-batch stays offered.  The block's own
+                    // type stands in for what a lane does not have, so that all the LDS reads of the five updates
+                    // are in flight together; only the writes are per lane.
+                    const uint32_t af1 = af & (af - 1u), af2 = af1 & (af1 - 1u);
+                    const bool has_c = placed && rd != 0, h0 = placed && af != 0, h1 = placed && af1 != 0, h2 = placed && af2 != 0;
+                    const int c = has_c ? __builtin_ctz(rd) : b;
+                    const int a0 = h0 ? __builtin_ctz(af) : b, a1 = h1 ? __builtin_ctz(af1) : b, a2 = h2 ? __builtin_ctz(af2) : b;
+                    auto moved = [&](int i) -> uint32_t {
+                        const uint32_t k = ckey[i * kWave];
+                        const int mi = (int)(int8_t)(ptab[i] >> 8);
+                        const uint32_t start = max(k << 1 >> 16, (uint32_t)en + ((uint32_t)TESSEL_ST(oNext + i) >> 10));
+                        const bool fits = (mi <= 0) | (me_new + mi <= M);
+                        return k == 0xFFFFFFFFu ? k : (start << 15) | (k & 0x7FFFu) | (fits ? 0u : 0x80000000u);
+                    };
+                    const uint32_t kb = offer_key(b), kc = offer_key(c), k0 = moved(a0), k1 = moved(a1), k2 = moved(a2);
+                    if (placed) ckey[b * kWave] = kb;
+                    if (has_c) ckey[c * kWave] = kc;
+                    if (h0) ckey[a0 * kWave] = k0;
+                    if (h1) ckey[a1 * kWave] = k1;
+                    if (h2) ckey[a2 * kWave] = k2;
+                    if (crowded) {
+                        // a type with several consumers, or more than four types on a device: the rest one by one
+                        uint32_t todo = placed ? rd & (rd - 1u) : 0u;
+                        while (__ballot(todo != 0u) != 0) {
+                            if (todo != 0u) {
+                                const int i = __builtin_ctz(todo);
+                                todo &= todo - 1u;
+                                ckey[i * kWave] = offer_key(i);
+                            }
+                        }
+                        todo = placed ? af2 & (af2 - 1u) : 0u;
+                        while (__ballot(todo != 0u) != 0) {
+                            if (todo != 0u) {
+                                const int i = __builtin_ctz(todo);
+                                todo &= todo - 1u;
+                                const uint32_t k = moved(i);
+                                ckey[i * kWave] = k;
+                            }
+                        }
+                    }
+                }
+            } else
+            for (;;) {
+                int bi = -1, bmu = 0, best_est = 0, bkey = 0;
+                const bool any = left > 0;
                 for (int i = 0; i < K; i++) {
                     const int hi = phase ? N : (int)cp.lead[i];
                     if (hi == 0) continue;                       // nothing of this type in the phase (uniform)
@@ -2277,71 +2339,14 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                 if (__ballot(busy) == 0) break;
                 if (busy && bi < 0) fail = true;                  // blocks left, none eligible: no schedule
                 if (busy && bi >= 0) {
-                    en = best_est + cp.t[bi];
-                    if (single_dev) {
-                        // its one device, its chain and its memory delta come with the type's table word
-                        const uint32_t pw = ptab[bi];
-                        const int d = (int)(pw >> 22 & 7u), mi = (int)(int8_t)(pw >> 8), hi = phase ? N : (int)(pw & 255u);
-                        me_new = (int)(int16_t)TESSEL_ST(oMem + d) + mi;
-                        TESSEL_ST(oFree + d) = (uint16_t)en;
-                        TESSEL_ST(oMem + d) = (uint16_t)me_new;
-                        TESSEL_ST(oTok + ((int)(pw >> 25 & 7u) << trs) + (bmu & tmask)) = (uint16_t)en;
-                        TESSEL_ST(oNext + bi) = (uint16_t)((uint32_t)(bmu + 1) | (bmu + 1 < hi ? jitter(bi, bmu + 1) : 0u) << 10);
-                    } else {
-                        const int mi = cp.m[bi], hi = phase ? N : (int)cp.lead[bi];
-                        const uint32_t mask = cp.mask[bi];
-                        for (int d = 0; d < D; d++)
-                            if (mask >> d & 1u) { TESSEL_ST(oFree + d) = (uint16_t)en; TESSEL_ST(oMem + d) = (uint16_t)((int)(int16_t)TESSEL_ST(oMem + d) + mi); }
-                        TESSEL_ST(oTok + (int)cp.path[bi] * TR + (bmu & tmask)) = (uint16_t)en;
-                        TESSEL_ST(oNext + bi) = (uint16_t)((uint32_t)(bmu + 1) | (bmu + 1 < hi ? jitter(bi, bmu + 1) : 0u) << 10);
-                    }
+                    const int en = best_est + cp.t[bi];
+                    const int mi = cp.m[bi], hi = phase ? N : (int)cp.lead[bi];
+                    const uint32_t mask = cp.mask[bi];
+                    for (int d = 0; d < D; d++)
+                        if (mask >> d & 1u) { TESSEL_ST(oFree + d) = (uint16_t)en; TESSEL_ST(oMem + d) = (uint16_t)((int)(int16_t)TESSEL_ST(oMem + d) + mi); }
+                    TESSEL_ST(oTok + (int)cp.path[bi] * TR + (bmu & tmask)) = (uint16_t)en;
+                    TESSEL_ST(oNext + bi) = (uint16_t)((uint32_t)(bmu + 1) | (bmu + 1 < hi ? jitter(bi, bmu + 1) : 0u) << 10);
                     left--;
-                }
-                if (single_dev) {
-                    // The scheduled block changes what its own type and its consumer offer (recomputed), and for the
-                    // other types on its device (three at most) the free time and the memory: start = max(end of the
-                    // producer's block, device free), and the device was free no later than now before, so the new key
-                    // is max(old key, new free time + jitter); the same micro-batch stays offered.  Straight-line, with
-                    // the block's own type standing in for what a lane does not have, so that all the LDS reads of
-                    // the five updates are in flight together; only the writes are per lane.
-                    const bool placed = busy && bi >= 0;
-                    const int b = placed ? bi : 0;
-                    const uint32_t rd = redo[b] & ~(1u << b), af = aff[b];
-                    const uint32_t af1 = af & (af - 1u), af2 = af1 & (af1 - 1u);
-                    const bool has_c = placed && rd != 0, h0 = placed && af != 0, h1 = placed && af1 != 0, h2 = placed && af2 != 0;
-                    const int c = has_c ? __builtin_ctz(rd) : b;
-                    const int a0 = h0 ? __builtin_ctz(af) : b, a1 = h1 ? __builtin_ctz(af1) : b, a2 = h2 ? __builtin_ctz(af2) : b;
-                    auto moved = [&](int i) -> uint32_t {
-                        const uint32_t k = ckey[i * kWave];
-                        const int mi = (int)(int8_t)(ptab[i] >> 8);
-                        const uint32_t start = max(k << 1 >> 16, (uint32_t)en + ((uint32_t)TESSEL_ST(oNext + i) >> 10));
-                        const bool fits = (mi <= 0) | (me_new + mi <= M);
-                        return k == 0xFFFFFFFFu ? k : (start << 15) | (k & 0x7FFFu) | (fits ? 0u : 0x80000000u);
-                    };
-                    const uint32_t kb = offer_key(b), kc = offer_key(c), k0 = moved(a0), k1 = moved(a1), k2 = moved(a2);
-                    if (placed) ckey[b * kWave] = kb;
-                    if (has_c) ckey[c * kWave] = kc;
-                    if (h0) ckey[a0 * kWave] = k0;
-                    if (h1) ckey[a1 * kWave] = k1;
-                    if (h2) ckey[a2 * kWave] = k2;
-                    // (a type with several consumers, or more than four types on a device: the rest one by one)
-                    uint32_t todo = placed ? rd & (rd - 1u) : 0u;
-                    while (__ballot(todo != 0u) != 0) {
-                        if (todo != 0u) {
-                            const int i = __builtin_ctz(todo);
-                            todo &= todo - 1u;
-                            ckey[i * kWave] = offer_key(i);
-                        }
-                    }
-                    todo = placed ? af2 & (af2 - 1u) : 0u;
-                    while (__ballot(todo != 0u) != 0) {
-                        if (todo != 0u) {
-                            const int i = __builtin_ctz(todo);
-                            todo &= todo - 1u;
-                            const uint32_t k = moved(i);
-                            ckey[i * kWave] = k;
-                        }
-                    }
                 }
             }
             if (phase == 1) break;
