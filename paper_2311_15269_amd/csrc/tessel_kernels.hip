@@ -2249,39 +2249,73 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                     for (int i = 0; i < K; i++) bestp = min(bestp, ckey[i * kWave]);
                     const bool placed = busy && bestp < 0x80000000u;
                     if (busy && !placed) fail = true;             // blocks left, none eligible: no schedule
-                    // A lane that places nothing goes through the step with type 0 and writes nothing.  The block's
-                    // device, chain and memory delta come with its type's table word.
-                    const int b = placed ? (int)(bestp & 31u) : 0, bmu = (int)(bestp >> 5 & 1023u);
-                    const uint32_t pw = ptab[b], rd = redo[b] & ~(1u << b), af = aff[b];
+                    // A lane that places nothing goes through the step with type 0 and writes nothing.  The step is
+                    // three rounds of LDS reads, each issued as a whole before anything waits for it (the values are
+                    // pinned so that no read sinks into a branch): (1) the table words of the block's type; (2) what
+                    // they name: the memory of its device, the table word and counter of its consumer, key, table word
+                    // and counter of the other types on its device, its producer's counter and the end time its own
+                    // next micro-batch waits for; (3) after the writes of the block, the consumer's device and token.
+                    const int b = placed ? (int)(bestp & 31u) : 0, bmu = (int)(bestp >> 5 & 1023u), mu1 = bmu + 1;
+                    uint32_t pw = ptab[b], rdw = redo[b], af = aff[b], tb = (uint32_t)cp.t[b], njb = TESSEL_ST(oNext + b);
+                    TESSEL_PIN(pw); TESSEL_PIN(rdw); TESSEL_PIN(af); TESSEL_PIN(tb); TESSEL_PIN(njb);
+                    const uint32_t rd = rdw & ~(1u << b), af1 = af & (af - 1u), af2 = af1 & (af1 - 1u);
+                    const bool has_c = placed && rd != 0, h0 = placed && af != 0, h1 = placed && af1 != 0, h2 = placed && af2 != 0;
+                    const int c = has_c ? __builtin_ctz(rd) : b;
+                    const int a0 = h0 ? __builtin_ctz(af) : b, a1 = h1 ? __builtin_ctz(af1) : b, a2 = h2 ? __builtin_ctz(af2) : b;
                     const int d = (int)(pw >> 22 & 7u), mi_b = (int)(int8_t)(pw >> 8), hi_b = phase ? N : (int)(pw & 255u);
-                    const int en = (int)(bestp >> 15) - ((int)TESSEL_ST(oNext + b) >> 10) + cp.t[b];
-                    const int me_new = (int)(int16_t)TESSEL_ST(oMem + d) + mi_b;
-                    const uint32_t jn = jitter(b, bmu + 1);
+                    const bool has_ab = (pw >> 16 & 63u) != 0;
+                    uint32_t me_old = TESSEL_ST(oMem + d), pwc = ptab[c], njc = TESSEL_ST(oNext + c);
+                    uint32_t k0 = ckey[a0 * kWave], p0 = ptab[a0], n0 = TESSEL_ST(oNext + a0);
+                    uint32_t k1 = ckey[a1 * kWave], p1 = ptab[a1], n1 = TESSEL_ST(oNext + a1);
+                    uint32_t k2 = ckey[a2 * kWave], p2 = ptab[a2], n2 = TESSEL_ST(oNext + a2);
+                    uint32_t napb = TESSEL_ST(oNext + (has_ab ? (int)(pw >> 16 & 63u) - 1 : b));
+                    uint32_t tkb = TESSEL_ST(oTok + ((int)(pw >> 25 & 7u) << trs) + (mu1 & tmask));
+                    TESSEL_PIN(me_old); TESSEL_PIN(pwc); TESSEL_PIN(njc); TESSEL_PIN(k0); TESSEL_PIN(p0); TESSEL_PIN(n0);
+                    TESSEL_PIN(k1); TESSEL_PIN(p1); TESSEL_PIN(n1); TESSEL_PIN(k2); TESSEL_PIN(p2); TESSEL_PIN(n2);
+                    TESSEL_PIN(napb); TESSEL_PIN(tkb);
+                    const int en = (int)(bestp >> 15) - (int)(njb >> 10) + (int)tb;
+                    const int me_new = (int)(int16_t)me_old + mi_b;
+                    const uint32_t jn = jitter(b, mu1);
+                    const uint32_t njb_new = (uint32_t)mu1 | (mu1 < hi_b ? jn : 0u) << 10;
                     if (placed) {
                         TESSEL_ST(oFree + d) = (uint16_t)en;
                         TESSEL_ST(oMem + d) = (uint16_t)me_new;
                         TESSEL_ST(oTok + ((int)(pw >> 25 & 7u) << trs) + (bmu & tmask)) = (uint16_t)en;
-                        TESSEL_ST(oNext + b) = (uint16_t)((uint32_t)(bmu + 1) | (bmu + 1 < hi_b ? jn : 0u) << 10);
+                        TESSEL_ST(oNext + b) = (uint16_t)njb_new;
                         left--;
                     }
-                    // The scheduled block changes what its own type and its consumer offer (recomputed), and for the
-                    // other types on its device (three at most) the free time and the memory: start = max(end of the
-                    // producer's block, device free), and the device was free no later than now before, so the new key
-                    // is max(old key, new free time + jitter); the same micro-batch stays offered.  The block's own
-                    // type stands in for what a lane does not have, so that all the LDS reads of the five updates
-                    // are in flight together; only the writes are per lane.
-                    const uint32_t af1 = af & (af - 1u), af2 = af1 & (af1 - 1u);
-                    const bool has_c = placed && rd != 0, h0 = placed && af != 0, h1 = placed && af1 != 0, h2 = placed && af2 != 0;
-                    const int c = has_c ? __builtin_ctz(rd) : b;
-                    const int a0 = h0 ? __builtin_ctz(af) : b, a1 = h1 ? __builtin_ctz(af1) : b, a2 = h2 ? __builtin_ctz(af2) : b;
-                    auto moved = [&](int i) -> uint32_t {
-                        const uint32_t k = ckey[i * kWave];
-                        const int mi = (int)(int8_t)(ptab[i] >> 8);
-                        const uint32_t start = max(k << 1 >> 16, (uint32_t)en + ((uint32_t)TESSEL_ST(oNext + i) >> 10));
+                    // round 3: the consumer's device and the end time of the micro-batch it waits for, as they are now
+                    const int dc = (int)(pwc >> 22 & 7u), muc = (int)(njc & 1023u);
+                    uint32_t frc = TESSEL_ST(oFree + dc), mec = TESSEL_ST(oMem + dc);
+                    uint32_t tkc = TESSEL_ST(oTok + ((int)(pwc >> 25 & 7u) << trs) + (muc & tmask));
+                    TESSEL_PIN(frc); TESSEL_PIN(mec); TESSEL_PIN(tkc);
+                    // The scheduled block changes what its own type and its consumer offer (recomputed; the block's
+                    // own values are at hand), and for the other types on its device (three at most) the free time and
+                    // the memory: start = max(end of the producer's block, device free), and the device was free no
+                    // later than now before, so the new key is max(old key, new free time + jitter); the same
+                    // micro-batch stays offered.
+                    const uint32_t blocked = 0x80000000u;
+                    uint32_t kb, kc;
+                    {
+                        const bool offered = (mu1 < hi_b) & (!has_ab | ((int)(napb & 1023u) > mu1));
+                        const bool fits = (mi_b <= 0) | (me_new + mi_b <= M);
+                        const uint32_t key = (uint32_t)max(has_ab ? (int)tkb : 0, en) + (njb_new >> 10);
+                        kb = offered ? (key << 15) | ((uint32_t)mu1 << 5) | (uint32_t)b | (fits ? 0u : blocked) : 0xFFFFFFFFu;
+                    }
+                    {
+                        const int hic = phase ? N : (int)(pwc & 255u), mic = (int)(int8_t)(pwc >> 8);
+                        const bool offered = (muc < hic) & (mu1 > muc);            // (its producer is the block's type)
+                        const bool fits = (mic <= 0) | ((int)(int16_t)mec + mic <= M);
+                        const uint32_t key = max(tkc, frc) + (njc >> 10);
+                        kc = offered ? (key << 15) | ((uint32_t)muc << 5) | (uint32_t)c | (fits ? 0u : blocked) : 0xFFFFFFFFu;
+                    }
+                    auto moved = [&](uint32_t k, uint32_t pwi, uint32_t nji) -> uint32_t {
+                        const int mi = (int)(int8_t)(pwi >> 8);
+                        const uint32_t start = max(k << 1 >> 16, (uint32_t)en + (nji >> 10));
                         const bool fits = (mi <= 0) | (me_new + mi <= M);
-                        return k == 0xFFFFFFFFu ? k : (start << 15) | (k & 0x7FFFu) | (fits ? 0u : 0x80000000u);
+                        return k == 0xFFFFFFFFu ? k : (start << 15) | (k & 0x7FFFu) | (fits ? 0u : blocked);
                     };
-                    const uint32_t kb = offer_key(b), kc = offer_key(c), k0 = moved(a0), k1 = moved(a1), k2 = moved(a2);
+                    k0 = moved(k0, p0, n0); k1 = moved(k1, p1, n1); k2 = moved(k2, p2, n2);
                     if (placed) ckey[b * kWave] = kb;
                     if (has_c) ckey[c * kWave] = kc;
                     if (h0) ckey[a0 * kWave] = k0;
@@ -2302,8 +2336,7 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                             if (todo != 0u) {
                                 const int i = __builtin_ctz(todo);
                                 todo &= todo - 1u;
-                                const uint32_t k = moved(i);
-                                ckey[i * kWave] = k;
+                                ckey[i * kWave] = moved(ckey[i * kWave], ptab[i], TESSEL_ST(oNext + i));
                             }
                         }
                     }
