@@ -9,7 +9,7 @@ Calls only oracle/ (and the shared problem descriptions).
 Config 2 is the whole canonical space of the 4-device linear problem (2,881,200,000 candidates, minutes
 on 8 cores).  Configs 3-5 are the sampled spaces at the benchmark's sizes; their files also hold one
 record per piece of 2^26 ordinals (the launch size of the benchmark), so that every launch of the GPU
-sweep is compared on its own.  Config 5 takes about two hours on 8 cores; the file is rewritten after
+sweep is compared on its own.  Config 5 takes about five hours on 6 cores; the file is rewritten after
 every finished piece ("complete": false until the last one)."""
 import json
 import os

@@ -59,13 +59,12 @@ def _same(got, want, what):
 @pytest.mark.parametrize("cfg", [3, 4, 5])
 def test_sampled_configs_full_size(gpu, cfg):
     """Every launch of 2^26 ordinals on its own, then the running best over the pieces in one search, equal the
-    oracle's stored sweep field by field.  (The stored file of the 8-device workload holds the pieces the oracle
-    has finished: all four = the whole 2^28 range when "complete" is true.)"""
+    oracle's stored sweep field by field: 2^24, 2^26 and 2^28 ordinals."""
     from oracle import Oracle
     want = json.load(open(os.path.join(GOLDEN, "config%d_full.json" % cfg)))
     prob = W.CONFIGS[cfg]()
     assert want["seed"] == prob["seed"] and want["count"] == prob["n_candidates"] and want["workload"] == prob["name"]
-    assert want["complete"] or cfg == 5
+    assert want["complete"] and sum(piece["count"] for piece in want["pieces"]) == prob["n_candidates"]
     orc = Oracle(prob)
     g = gpu.Problem(prob)
     assert want["lower_bound"] == orc.lower_bound
@@ -81,8 +80,7 @@ def test_sampled_configs_full_size(gpu, cfg):
         g.eval_candidates(piece["first"], piece["count"])
     got = g.best()
     _same(got, want, cfg)
-    if want["complete"]:
-        assert got["n_evaluated"] == prob["n_candidates"]
+    assert got["n_evaluated"] == prob["n_candidates"]
     # windows of per-candidate scores spread over the whole range, the last one ending at the range end
     total = prob["n_candidates"]
     rng = np.random.default_rng(cfg)
