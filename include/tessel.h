@@ -224,13 +224,14 @@ int  tessel_complete_schedule(tessel_problem *p, tessel_schedule *out);
  * with the 16-bit draw number type*N + mu of the counter-based stream keyed by (seed + 0x632BE59BD9B4E019,
  * ordinal); ordinal 0 has no jitter and is the schedule of tessel_complete_schedule.
  *
- * tessel_search_completions scores candidates first .. first+count-1 on the GPU (one per lane, every block of
- * the N micro-batches simulated) and merges into the running best (makespan, lowest ordinal).  The first call
+ * tessel_search_completions scores candidates first .. first+count-1 on the GPU (one per lane: warm-up and
+ * cool-down block by block, the R windows between them as the one linear map in the (max, +) algebra that
+ * they are for every candidate) and merges into the running best (makespan, lowest ordinal).  The first call
  * for a best window waits for it (as tessel_best does); the scoring itself is asynchronous on the stream of the
  * last tessel_eval_candidates call, in the workspace bound there.  A new best window, N or J restarts the
  * running best.  Errors: NO_FEASIBLE, RANGE (fewer than one window fits), INVALID_ARG,
  * TOOBIG (state of N micro-batches does not fit the LDS, N * sum of t exceeds 16 bits, N > 1023 or J > 63),
- * UNSUPPORTED (|m| > 127; a dependency graph that is not a set of chains), HIP. */
+ * UNSUPPORTED (|m| > 127; a dependency graph that is not a set of chains; more than 8 devices), HIP. */
 int  tessel_search_completions(tessel_problem *p, int32_t num_microbatches, int32_t jitter, uint64_t first,
                                uint64_t count);
 /* makespan_dev[k] (device, int32) = makespan of completion candidate first+k, INT32_MAX where the greedy rule
