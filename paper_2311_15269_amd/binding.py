@@ -77,6 +77,9 @@ def load_library():
     if _lib is None:
         if not os.path.exists(_build.LIB):
             _build.build_library()
+        # torch (device memory and streams of this binding) brings its own HIP runtime: it has to be the one the
+        # process loads first, or torch finds no GPU afterwards
+        import torch  # noqa: F401
         lib = C.CDLL(_build.LIB)
         lib.tessel_problem_create.argtypes = [C.POINTER(ProblemDesc), C.POINTER(C.c_void_p)]
         lib.tessel_problem_destroy.argtypes = [C.c_void_p]

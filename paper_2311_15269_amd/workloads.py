@@ -116,6 +116,13 @@ def xshape_problem(p, tf, tb, nr, cap, space="sampled_repair", seed=0x7C0FFEE7, 
             "deps": deps, "space": space, "seed": seed, "lead_step_q16": lead_step_q16, "fixed_leads": None}
 
 
+def nnshape_problem(p, nr, cap, tf=1, tb=2, space="sampled_repair", seed=0x11C0FFEE, lead_step_q16=20000):
+    """Two forward passes over the p devices, then two backward passes (the NN-shape of Sec. VI-A: an encoder pipeline
+    followed by a decoder pipeline on the same devices): 2 p stages, four block types per device, one chain."""
+    return pipeline_problem(list(range(p)) + list(range(p)), [tf] * (2 * p), [tb] * (2 * p), p, nr, cap, space, seed=seed,
+                            lead_step_q16=lead_step_q16, name="nnshape-%d" % p)
+
+
 def kshape_problem(nr, cap, tf=(2, 1, 3), tb=(4, 2, 6), space="sampled_repair", seed=0x8C0FFEE8, lead_step_q16=20000):
     """Two branches that join (the K-shape of Sec. VI-A: two encoders feeding a joint stage): A on device 0 and B on
     device 1 run side by side, J on device 2 needs both; the backward pass fans out again.  Types: A_F, B_F, J_F,

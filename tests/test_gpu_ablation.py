@@ -112,3 +112,41 @@ def test_kshape_bubble_against_memory(gpu):
         assert (got["period"], got["index"], got["n_feasible"]) == (want["period"], want["index"], want["n_feasible"])
         periods.append(got["period"])
     assert periods == [30, 18, 18, 18]
+
+
+def test_bubble_against_window_size_on_the_nn_and_m_shapes(gpu):
+    """Two more placements of Sec. VI-A against the window size, memory not limiting: the NN-shape (two passes over 4
+    devices, 8 stages) and the M-shape (a block on all devices around a 4-stage pipeline, the structure of the
+    4-device benchmark configuration).  Their spaces are out of exhaustive reach from two micro-batches on, so these
+    are the best of 2^26 seeded samples (a regression record, not optima): the bubble shrinks as the window grows
+    (the paper reports that these shapes need windows of six and more micro-batches), a window of one micro-batch is
+    the critical path of one micro-batch, and the oracle confirms every reported best."""
+    from oracle import Oracle
+
+    def best_of_samples(prob):
+        g = gpu.Problem(prob)
+        for k in range(4):
+            g.eval_candidates(k << 24, 1 << 24)
+        got = g.best()
+        ref = Oracle(prob).eval_index(got["index"])
+        assert ref["status"] == 0 and ref["period"] == got["period"] and ref["peak"] == got["peak"]
+        return got
+
+    periods = []
+    for nr in (1, 2, 3, 4, 5):
+        got = best_of_samples(W.nnshape_problem(4, nr, 100))
+        assert got["lower_bound"] == 6 * nr                    # two forward and two backward stages per device
+        periods.append(got["period"])
+    assert periods == [24, 24, 25, 29, 34]                     # 24 = the 8 + 8 stages of one micro-batch in a row
+    bubbles = [1 - 6 * nr / t for nr, t in zip((1, 2, 3, 4, 5), periods)]
+    assert all(a > b for a, b in zip(bubbles, bubbles[1:])) and bubbles[-1] < 0.12
+
+    periods = []
+    for nr in (1, 2, 3, 4):
+        prob = dict(W.config4(), NR=nr, M=100)
+        got = best_of_samples(prob)
+        assert got["lower_bound"] == 15 * nr
+        periods.append(got["period"])
+    assert periods == [33, 39, 54, 71]
+    bubbles = [1 - 15 * nr / t for nr, t in zip((1, 2, 3, 4), periods)]
+    assert all(a > b for a, b in zip(bubbles, bubbles[1:])) and bubbles[-1] < 0.16
