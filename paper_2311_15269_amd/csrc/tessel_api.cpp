@@ -191,7 +191,7 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         if (net != 0) return TESSEL_E_UNBALANCED_MEMORY;
     }
     // limits of the kernels
-    if (K > kMaxK || NR > kMaxNR) return TESSEL_E_UNSUPPORTED;
+    if (K > kMaxKW || NR > kMaxNR) return TESSEL_E_UNSUPPORTED;
     std::vector<int> indeg(K, 0), outdeg(K, 0);
     for (int e = 0; e < desc->num_deps; e++) { outdeg[desc->dep_src[e]]++; indeg[desc->dep_dst[e]]++; }
     // disjoint chains take the fast kernel and the chain path of the general one; any other graph (Sec. III-A allows
@@ -199,9 +199,9 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
     bool chains = true;
     for (int i = 0; i < K; i++) if (indeg[i] > 1 || outdeg[i] > 1) chains = false;
     { const char *fd = getenv("TESSEL_FORCE_DAG"); if (fd && fd[0] == '1') chains = false; }
-    // more than kMaxD devices: the tables by (device, symbol) code of the chain path and of the fast kernel have no room
-    // for them; such a problem is scored as a graph, chains or not
-    const bool wide = D > kMaxD;
+    // more than kMaxD devices or kMaxK block types: the tables by (device, symbol) code of the chain path and of the fast
+    // kernel have no room for them; such a problem is scored as a graph, chains or not
+    const bool wide = D > kMaxD || K > kMaxK;
     if (wide) chains = false;
     if (!chains && desc->num_deps > kMaxDeps) return TESSEL_E_UNSUPPORTED;
 
@@ -218,7 +218,8 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
     kp.D = D; kp.K = K; kp.NR = NR; kp.M = desc->mem_cap; kp.total = K * NR; kp.space = desc->space;
     kp.seed = desc->seed; kp.step_q16 = desc->lead_step_q16;
     kp.has_fixed = desc->fixed_leads != nullptr;
-    for (int i = 0; i < K; i++) { kp.pred[i] = -1; kp.succ[i] = -1; kp.fixed[i] = desc->fixed_leads ? (uint8_t)desc->fixed_leads[i] : 0; }
+    for (int i = 0; i < K; i++) kp.fixed[i] = desc->fixed_leads ? (uint8_t)desc->fixed_leads[i] : 0;
+    for (int i = 0; i < K && i < kMaxK; i++) { kp.pred[i] = -1; kp.succ[i] = -1; }
     for (int e = 0; e < desc->num_deps && chains; e++) {
         int a = desc->dep_src[e], b = desc->dep_dst[e];
         kp.succ[a] = (int8_t)b; kp.pred[b] = (int8_t)a;
@@ -236,7 +237,7 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         for (int e = 0; e < desc->num_deps; e++) {
             const int a = desc->dep_src[e], b = desc->dep_dst[e];
             kp.dsrc[e] = (uint8_t)a; kp.ddst[e] = (uint8_t)b; kp.dcross[e] = desc->dev_mask[a] != desc->dev_mask[b];
-            kp.predmask[b] |= 1u << a;
+            kp.predmask[b] |= 1ull << a;
         }
         // every type somebody consumes keeps the end times of its blocks by micro-batch: 2 N_R slots behind the devices
         for (int i = 0; i < K; i++) if (outdeg[i] > 0) {

@@ -49,9 +49,10 @@ constexpr int kMaxD = 8;         // simulated devices of the problems the fast k
 constexpr int kMaxDW = 32;       // ... of any problem: more than kMaxD go the general kernel's path for graphs
 constexpr int kMaxLT = 4;        // block types per device
 constexpr int kMaxNR = 8;        // micro-batches per window
-constexpr int kMaxK = 32;        // block types
+constexpr int kMaxK = 32;        // block types of the problems the fast kernel and the chain path of the general one take
+constexpr int kMaxKW = 64;       // ... of any problem: more than kMaxK go the general kernel's path for graphs
 constexpr int kMaxPos = kMaxLT * kMaxNR;   // blocks per device and window (32)
-constexpr int kMaxDeps = 64;      // dependencies of a micro-batch whose graph is not a set of chains
+constexpr int kMaxDeps = 128;     // dependencies of a micro-batch whose graph is not a set of chains
 constexpr uint32_t kNoRing = 0xFFFFu;   // no ring of end times (KParams::tokbase)
 constexpr int kNumStatus = 6;
 constexpr int kWave = 64;
@@ -86,8 +87,8 @@ struct KParams {
     int8_t   succ[kMaxK];        // consumer type of type g or -1
     uint8_t  edge_out[kMaxK];    // position of the dependency g -> succ[g] in the caller's list
     uint8_t  cross_out[kMaxK];   // that dependency joins different device sets
-    uint8_t  rtopo[kMaxK];       // types, consumers before producers
-    uint8_t  fixed[kMaxK];       // fixed leads
+    uint8_t  rtopo[kMaxKW];      // types, consumers before producers
+    uint8_t  fixed[kMaxKW];      // fixed leads
     int8_t   pred[kMaxK];        // producer type of type g or -1
     int32_t  t_loc[kMaxK];       // t by home code (device*4 + symbol)
     uint32_t mask_loc[kMaxK];    // device mask by home code
@@ -124,12 +125,12 @@ struct KParams {
     int32_t  ndeps;
     int32_t  dag_tries;          // sweeps of the eigenvector search before the bisection takes over (test knob)
     int32_t  ntok;               // types somebody consumes: each has a ring of 2 N_R end times behind the D device slots
-    int32_t  t_type[kMaxK];
-    uint32_t mask_type[kMaxK];   // devices of the type
-    uint32_t predmask[kMaxK];    // its producers
-    uint16_t tokbase[kMaxK];     // first slot of its ring, kNoRing: nobody consumes it
+    int32_t  t_type[kMaxKW];
+    uint32_t mask_type[kMaxKW];  // devices of the type
+    uint64_t predmask[kMaxKW];   // its producers
+    uint16_t tokbase[kMaxKW];    // first slot of its ring, kNoRing: nobody consumes it
     uint8_t  dsrc[kMaxDeps], ddst[kMaxDeps], dcross[kMaxDeps];   // the dependencies in the caller's order
-    uint32_t predmask_of[kMaxDW][kMaxLT];  // producers of local symbol y of device d
+    uint64_t predmask_of[kMaxDW][kMaxLT];  // producers of local symbol y of device d
     const int8_t   *leadtab;     // CANONICAL: [nlead][K] in device memory
     const uint64_t *wtab;        // CANONICAL: arrangements by remaining counts, base NR+1 digits
 };
@@ -155,7 +156,7 @@ struct DevResult {
 struct DevDetail {
     int32_t status, period;
     int32_t peak[kMaxDW];
-    int32_t leads[kMaxK];
+    int32_t leads[kMaxKW];
     int32_t order_len[kMaxDW];
     int32_t orders[kMaxDW][kMaxPos];
 };

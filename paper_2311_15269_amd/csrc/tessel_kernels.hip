@@ -48,6 +48,8 @@ constexpr uint32_t kDrawOrdBase = 128u;
 // next micro-batch index of every block type: lead + occurrences placed, 4 bits each
 struct Mu {
     uint64_t lo, hi;
+    static constexpr int kTypeBits = 5;          // of a program entry of the path for graphs
+    __device__ __forceinline__ void clear() { lo = 0; hi = 0; }
     __device__ __forceinline__ uint32_t get(uint32_t g) const
     {
         uint64_t w = g < 16 ? lo : hi;
@@ -65,8 +67,38 @@ struct Mu {
     }
 };
 
+// the same for up to 64 block types (problems that only the general kernel's path for graphs takes)
+struct MuWide {
+    uint64_t w[4];
+    __device__ __forceinline__ void clear() { w[0] = w[1] = w[2] = w[3] = 0; }
+    __device__ __forceinline__ uint64_t word(uint32_t g) const
+    {
+        const uint64_t a = g & 16u ? w[1] : w[0], b = g & 16u ? w[3] : w[2];
+        return g & 32u ? b : a;
+    }
+    __device__ __forceinline__ uint32_t get(uint32_t g) const { return (uint32_t)(word(g) >> ((g & 15u) * 4u)) & 15u; }
+    __device__ __forceinline__ void add(uint32_t g, uint64_t x)
+    {
+#pragma unroll
+        for (int k = 0; k < 4; k++) w[k] += (g >> 4) == (uint32_t)k ? x : 0ull;
+    }
+    __device__ __forceinline__ void set(uint32_t g, uint32_t v)
+    {
+        const uint32_t sh = (g & 15u) * 4u;
+        add(g, ((uint64_t)v << sh) - (word(g) & (15ull << sh)));
+    }
+    __device__ __forceinline__ void inc(uint32_t g) { add(g, 1ull << ((g & 15u) * 4u)); }
+    static constexpr int kTypeBits = 6;          // of a program entry
+};
+
 __device__ __forceinline__ uint32_t byte_of(uint32_t packed, uint32_t y) { return (packed >> (8u * y)) & 0xFFu; }
 
+__device__ __forceinline__ uint64_t sel4u(const uint64_t (&v)[kMaxLT], uint32_t y)
+{
+    uint64_t a = y & 1u ? v[1] : v[0];
+    uint64_t b = y & 1u ? v[3] : v[2];
+    return y & 2u ? b : a;
+}
 __device__ __forceinline__ uint32_t sel4u(const uint32_t (&v)[kMaxLT], uint32_t y)
 {
     uint32_t a = y & 1u ? v[1] : v[0];
@@ -223,17 +255,17 @@ __device__ __forceinline__ int least_period(const KParams &P, const uint16_t *pr
 // index -> leads (4-bit counters by block type id) and, per device, the order of its blocks as
 // 2-bit local symbols (first block in the lowest bits).  Returns kOk or the structural reject
 // reason of the FACTORIAL space.
-template <int DM>
-__device__ __forceinline__ int decode_candidate(const KParams &P, uint64_t idx, uint64_t (&rem)[DM], int (&remlen)[DM], Mu &mu)
+template <int DM, class CNT = Mu>
+__device__ __forceinline__ int decode_candidate(const KParams &P, uint64_t idx, uint64_t (&rem)[DM], int (&remlen)[DM], CNT &mu)
 {
     const uint32_t NR = (uint32_t)P.NR;
-    mu.lo = 0; mu.hi = 0;
+    mu.clear();
 #pragma unroll
     for (int d = 0; d < DM; d++) { rem[d] = 0; remlen[d] = 0; }
     if (P.space == kFactorial) {
         uint64_t rest = idx;
         bool dup = false, tpm = false;
-        uint32_t seen_types = 0;
+        uint64_t seen_types = 0;
 #pragma unroll
         for (int d = 0; d < DM; d++) {
             if (d >= P.D) continue;
@@ -264,7 +296,7 @@ __device__ __forceinline__ int decode_candidate(const KParams &P, uint64_t idx, 
             for (int y = 0; y < P.ntd[d]; y++) {
                 uint32_t g = byte_of(P.type_of[d], (uint32_t)y), fl = byte_of(firstlab, (uint32_t)y);
                 if (seen_types >> g & 1u) { if (mu.get(g) != fl) tpm = true; }
-                else { mu.set(g, fl); seen_types |= 1u << g; }
+                else { mu.set(g, fl); seen_types |= 1ull << g; }
             }
         }
         if (dup) return kDup;
@@ -513,18 +545,23 @@ __device__ __forceinline__ int evaluate(const KParams &P, uint64_t idx, uint16_t
 // A block type may have several producers and several consumers (Sec. III-A, Eq. 1 [3]).  State of a sweep, in LDS
 // [slot][lane]: the D device times, then for every type somebody consumes a ring of 2 N_R end times by micro-batch
 // (micro-batches N_R and up belong to the next window and move down at the window boundary).  Program entry: type id
-// in bits 0-4, micro-batch in bits 5-8.  Tables by type id in LDS: t, device mask, producer mask, first ring slot.
-struct DagTables { const int32_t *t; const uint32_t *mask, *pred, *tok; };
+// in bits 0-4 (0-5 for problems with more than 32 types), micro-batch above.  Tables by type id in LDS: t, device mask,
+// producer mask (two words where there are more than 32 types), first ring slot.
+struct DagTables {
+    const int32_t *t; const uint32_t *mask, *pred, *pred_hi, *tok;
+    __device__ __forceinline__ uint64_t producers(uint32_t g) const { return pred[g] | (pred_hi ? (uint64_t)pred_hi[g] << 32 : 0ull); }
+};
 
+template <int TB>
 __device__ __forceinline__ void sweep_window_dag(const KParams &P, const DagTables &Tb, const uint16_t *prog, uint32_t *state)
 {
     const int total = P.total;
     for (int k = 0; k < total; k++) {
         const uint32_t e = prog[k * kWave];
-        const uint32_t g = e & 31u, m = e >> 5;
+        const uint32_t g = e & ((1u << TB) - 1u), m = e >> TB;
         uint32_t s = 0;
         for (uint32_t rest = Tb.mask[g]; rest; rest &= rest - 1u) s = max(s, state[__builtin_ctz(rest) * kWave]);
-        for (uint32_t rest = Tb.pred[g]; rest; rest &= rest - 1u) s = max(s, state[(Tb.tok[__builtin_ctz(rest)] + m) * kWave]);
+        for (uint64_t rest = Tb.producers(g); rest; rest &= rest - 1ull) s = max(s, state[(Tb.tok[__builtin_ctzll(rest)] + m) * kWave]);
         const uint32_t en = s + (uint32_t)Tb.t[g];
         for (uint32_t rest = Tb.mask[g]; rest; rest &= rest - 1u) state[__builtin_ctz(rest) * kWave] = en;
         if (Tb.tok[g] != kNoRing) state[(Tb.tok[g] + m) * kWave] = en;
@@ -536,8 +573,8 @@ __device__ __forceinline__ void sweep_window_dag(const KParams &P, const DagTabl
 // value that crosses the boundary and means anything grew by `want` over the window (`first`: by any one amount,
 // which is handed back in `want`): ring entries below the type's lead (handled before the window by the producer),
 // compared in place with what the last boundary left there; device times against `prevfree`.
-template <int DM>
-__device__ __forceinline__ bool boundary_dag(const KParams &P, const DagTables &Tb, uint32_t *state, const Mu &lead, uint32_t (&prevfree)[DM],
+template <int DM, class CNT>
+__device__ __forceinline__ bool boundary_dag(const KParams &P, const DagTables &Tb, uint32_t *state, const CNT &lead, uint32_t (&prevfree)[DM],
                                              uint32_t shift, bool first, uint32_t &want, uint32_t &top)
 {
     bool same = true, have = !first;
@@ -577,8 +614,8 @@ __device__ __forceinline__ bool boundary_dag(const KParams &P, const DagTables &
 // least T in [LB, UB] for which start times exist, by bisection; start times exist for T iff the sweeps from 0, with
 // every boundary value taken T later each time, come to rest (Kleene iteration of the longest-path equations; it
 // rests after at most as many windows as values cross the boundary, or passes UB).
-template <int DM>
-__device__ __forceinline__ int least_period_dag(const KParams &P, const DagTables &Tb, const uint16_t *prog, uint32_t *state, const Mu &lead)
+template <int DM, class CNT>
+__device__ __forceinline__ int least_period_dag(const KParams &P, const DagTables &Tb, const uint16_t *prog, uint32_t *state, const CNT &lead)
 {
     uint32_t prevfree[DM];
     auto reset = [&]() {
@@ -591,7 +628,7 @@ __device__ __forceinline__ int least_period_dag(const KParams &P, const DagTable
     uint32_t T = 0;
     for (int j = 0; j < P.dag_tries; j++) {
         if (__ballot(!done) == 0) break;
-        sweep_window_dag(P, Tb, prog, state);
+        sweep_window_dag<CNT::kTypeBits>(P, Tb, prog, state);
         uint32_t delta = 0, top;
         const bool eig = boundary_dag<DM>(P, Tb, state, lead, prevfree, 0u, true, delta, top);
         if (!done && eig) { T = delta; done = true; }
@@ -609,9 +646,9 @@ __device__ __forceinline__ int least_period_dag(const KParams &P, const DagTable
         reset();
         bool decided = !open, feasible = false;
         // (crossing + 2 windows bound the iteration; the loop runs until every lane of the wave has decided)
-        for (int w = 0; w < kMaxK * kMaxNR + kMaxDW + 2; w++) {
+        for (int w = 0; w < kMaxKW * kMaxNR + kMaxDW + 2; w++) {
             if (__ballot(!decided) == 0) break;
-            sweep_window_dag(P, Tb, prog, state);
+            sweep_window_dag<CNT::kTypeBits>(P, Tb, prog, state);
             uint32_t zero = 0, top;
             const bool rest = boundary_dag<DM>(P, Tb, state, lead, prevfree, mid, false, zero, top);
             if (!decided) {
@@ -625,21 +662,21 @@ __device__ __forceinline__ int least_period_dag(const KParams &P, const DagTable
 }
 
 // One candidate of a problem whose dependency graph is not a set of chains (general kernel only).
-template <int DM>
+template <int DM, class CNT>
 __device__ __forceinline__ int evaluate_dag(const KParams &P, const DagTables &Tb, uint64_t idx, uint16_t *prog, uint32_t *state,
                                             int &period, int (&peak)[DM], DevDetail *detail)
 {
     uint64_t rem[DM];
     int remlen[DM];
-    Mu mu;
+    CNT mu;
     period = 0;
 #pragma unroll
     for (int d = 0; d < DM; d++) peak[d] = 0;
     {
-        int st = decode_candidate<DM>(P, idx, rem, remlen, mu);
+        int st = decode_candidate<DM, CNT>(P, idx, rem, remlen, mu);
         if (st != kOk) return st;
     }
-    const Mu lead = mu;
+    const CNT lead = mu;
     if (detail) {
         for (int g = 0; g < P.K; g++) detail->leads[g] = (int)mu.get((uint32_t)g);
         for (int d = 0; d < kMaxDW; d++) detail->order_len[d] = 0;
@@ -658,14 +695,14 @@ __device__ __forceinline__ int evaluate_dag(const KParams &P, const DagTables &T
     const int total = P.total;
     // a block may run when every producer has handled its micro-batch: in this window (counter ahead) or in the last
     // one (micro-batch below the producer's lead, which the counter is ahead of too)
-    auto ready = [&](uint32_t g, uint32_t preds) -> bool {
+    auto ready = [&](uint32_t g, uint64_t preds) -> bool {
         const uint32_t mg = mu.get(g);
         bool ok = true;
-        for (uint32_t rest = preds; rest; rest &= rest - 1u) ok = ok && mu.get((uint32_t)__builtin_ctz(rest)) > mg;
+        for (uint64_t rest = preds; rest; rest &= rest - 1ull) ok = ok && mu.get((uint32_t)__builtin_ctzll(rest)) > mg;
         return ok;
     };
     auto place = [&](uint32_t g, uint32_t mask, int m, uint32_t pos_d, int d_static) {
-        prog[placed * kWave] = (uint16_t)(g | (mu.get(g) << 5));
+        prog[placed * kWave] = (uint16_t)(g | (mu.get(g) << CNT::kTypeBits));
         mu.inc(g);
         placed++;
 #pragma unroll
@@ -738,7 +775,7 @@ __device__ __forceinline__ int evaluate_dag(const KParams &P, const DagTables &T
         if (d < P.D) peak_max = max(peak_max, peak[d]);
     }
     if (peak_max > P.M) return kMem;
-    period = least_period_dag<DM>(P, Tb, prog, state, lead);
+    period = least_period_dag<DM, CNT>(P, Tb, prog, state, lead);
     return kOk;
 }
 
@@ -1688,9 +1725,9 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
 }
 
 // ------------------------------------------------------------------ kernels
-// Problems with more than kMaxD devices (DM above kMaxD) are scored as dependency graphs, with the per-lane state and
-// program in global memory (`far`: one region of far_words(P) words per workgroup) instead of LDS: up to 32 devices
-// with up to 32 rings of 16 end times each do not fit there.
+// Problems with more than kMaxD devices or more than kMaxK block types (DM above kMaxD) are scored as dependency graphs,
+// with the per-lane state and program in global memory (`far`: one region of far_words(P) words per workgroup)
+// instead of LDS: up to 32 devices with up to 63 rings of 16 end times each do not fit there.
 __host__ __device__ inline size_t far_words(const KParams &P)
 {
     return (((size_t)P.nslots * kWave * 4 + (size_t)P.total * kWave * 2 + 255) & ~(size_t)255) / 4;
@@ -1708,19 +1745,21 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
     constexpr bool wide = DM > kMaxD;
     // with a list: score the listed candidates (all inside [first, first + count)) instead of the range
     if (list) count = min(*list_count, kWsListCap);
+    constexpr int KT = wide ? kMaxKW : kMaxK;             // entries of a table by type
     int32_t *t_tab = (int32_t *)lds;
-    uint32_t *mask_tab = lds + kMaxK;
+    uint32_t *mask_tab = lds + KT;
     uint32_t *state_all = wide ? far + (size_t)blockIdx.x * far_words(P) : lds + 4 * kMaxK;
     uint16_t *prog_all = (uint16_t *)(state_all + P.nslots * kWave);
     const int lane = threadIdx.x;
     // by home code for chain problems, by type id (with the producers and the token rings) for the others
     DagTables Tb;
-    Tb.t = t_tab; Tb.mask = mask_tab; Tb.pred = lds + 2 * kMaxK; Tb.tok = lds + 3 * kMaxK;
-    if (lane < kMaxK) {
+    Tb.t = t_tab; Tb.mask = mask_tab; Tb.pred = lds + 2 * KT; Tb.tok = lds + 3 * KT; Tb.pred_hi = wide ? lds + 4 * KT : nullptr;
+    if (lane < KT) {
         t_tab[lane] = P.dag ? P.t_type[lane] : P.t_loc[lane];
         mask_tab[lane] = P.dag ? P.mask_type[lane] : P.mask_loc[lane];
-        lds[2 * kMaxK + lane] = P.predmask[lane];
-        lds[3 * kMaxK + lane] = P.tokbase[lane];
+        lds[2 * KT + lane] = (uint32_t)P.predmask[lane];
+        lds[3 * KT + lane] = P.tokbase[lane];
+        if (wide) lds[4 * KT + lane] = (uint32_t)(P.predmask[lane] >> 32);
     }
     __syncthreads();
     uint32_t *state = state_all + lane;
@@ -1739,8 +1778,8 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
         const uint64_t k = idx - first;
         int period, peak[DM];
         int status;
-        if constexpr (wide) status = evaluate_dag<DM>(P, Tb, idx, prog, state, period, peak, detail);
-        else status = P.dag ? evaluate_dag<DM>(P, Tb, idx, prog, state, period, peak, detail)
+        if constexpr (wide) status = evaluate_dag<DM, MuWide>(P, Tb, idx, prog, state, period, peak, detail);
+        else status = P.dag ? evaluate_dag<DM, Mu>(P, Tb, idx, prog, state, period, peak, detail)
                             : evaluate<DM, VM>(P, idx, prog, state, t_tab, mask_tab, period, peak, detail);
         nev++;
 #pragma unroll
@@ -1859,7 +1898,7 @@ static eval_fn pick_kernel(const KParams &kp)
 {
     const int V = kp.nsweeps - 1;
     if (kp.D > 16) return eval_kernel<32, 1>;
-    if (kp.D > kMaxD) return eval_kernel<16, 1>;
+    if (kp.D > kMaxD || kp.K > kMaxK) return eval_kernel<16, 1>;
     if (kp.D <= 2 && V <= 4) return eval_kernel<2, 4>;
     if (kp.D <= 4 && V <= 8) return eval_kernel<4, 8>;
     if (kp.D <= 8 && V <= 16) return eval_kernel<8, 16>;
@@ -1896,12 +1935,12 @@ static fast_fn pick_fast(const KParams &kp)
 }
 
 // state and program of the general kernel's lanes: in LDS, except for problems with more than kMaxD devices
-static bool far_state(const KParams &kp) { return kp.D > kMaxD; }
+static bool far_state(const KParams &kp) { return kp.D > kMaxD || kp.K > kMaxK; }
 static size_t far_bytes(const KParams &kp) { return far_state(kp) ? far_words(kp) * 4 : 0; }
 
 static size_t general_lds_bytes(const KParams &kp)
 {
-    return (size_t)4 * kMaxK * 4 + (far_state(kp) ? 0 : (size_t)kp.nslots * kWave * 4 + (size_t)kp.total * kWave * 2);
+    return far_state(kp) ? (size_t)5 * kMaxKW * 4 : (size_t)4 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)kp.total * kWave * 2;
 }
 
 static size_t fast_lds_bytes(const KParams &kp)

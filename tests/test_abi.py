@@ -39,8 +39,11 @@ def test_problem_create_validates_on_the_host():
             "deps": [(i, i + 1) for i in range(31)], "space": "sampled_repair", "seed": 1, "lead_step_q16": 100, "fixed_leads": None}
     assert binding.Problem(wide).candidate_count() == 2 ** 64 - 1
     assert binding.Problem(wide).workspace_bytes() > 0
+    many = dict(wide, K=64, t=[1] * 64, m=[0] * 64, dev_mask=[1 << (d % 32) for d in range(64)], deps=[(i, i + 1) for i in range(63)])
+    assert binding.Problem(many).candidate_count() == 2 ** 64 - 1
     for bad, code in (
         (dict(wide, D=33), -9),
+        (dict(many, K=65, t=[1] * 65, m=[0] * 65, dev_mask=[1 << (d % 32) for d in range(65)]), -9),
         (dict(W.config1(), m=[1, 1, -1, 0]), -3),
         (dict(W.config1(), deps=[(0, 1), (1, 0)]), -2),
         (dict(W.config1(), t=[0, 1, 2, 2]), -1),

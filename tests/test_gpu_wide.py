@@ -1,5 +1,5 @@
-"""Problems with more than 8 devices (Table I puts no bound on D; the boundary takes up to 32): scored by the general
-kernel's path for graphs with the lanes' state in global memory.  HIP path against the oracle element by element:
+"""Problems with more than 8 devices or more than 32 block types (Table I puts no bound on D and K; the boundary takes
+up to 32 and 64): scored by the general kernel's path for graphs with the lanes' state in global memory.  HIP path against the oracle element by element:
 V-shape pipelines on 12 and 16 devices, a forward-only pipeline on 32, a block on ten devices at once, the two
 exhaustive spaces, seeded random graphs on up to 24 devices; best candidate, its start times and its completion."""
 import numpy as np
@@ -57,6 +57,14 @@ SHAPES = [
     ("vshape-12-strict", vshape(12, 2, 6, space="sampled_strict", step=8000), 0, 3000),
     ("vshape-16-repair", vshape(16, 4, 5), 1 << 35, 2000),
     ("vshape-16-nr8", vshape(16, 8, 12), 7, 600),
+    ("vshape-32-repair", vshape(32, 2, 2), 17, 1500),
+    ("vshape-32-nr8", vshape(32, 8, 11), 3, 200),
+    ("folded-16-repair", W.pipeline_problem(W.folded_placement(16), [1 + (i % 3) for i in range(32)], [2 + (i % 4) for i in range(32)],
+                                            16, 2, 3, "sampled_repair", seed=77, lead_step_q16=15000, name="folded-16"), 5, 1500),
+    ("folded-9-factorial", W.pipeline_problem(W.folded_placement(9), [1] * 18, [2] * 18, 9, 1, 4, "factorial", name="folded-9f"),
+     123456789, 3000),
+    ("folded-9-canonical", W.pipeline_problem(W.folded_placement(9), [1] * 18, [2] * 18, 9, 1, 4, "canonical", name="folded-9c"),
+     987654321, 3000),
     ("inference-32", inference(32, 2), 99, 3000),
     ("inference-32-nr8", inference(32, 8), 5, 800),
     ("shared-10-repair", shared_block(10, 2, 7), 31, 2500),
@@ -80,7 +88,7 @@ def random_wide_graph(rng):
     """9-24 devices, forward types then their backward mirrors, every forward type after one or two earlier ones"""
     while True:
         D = int(rng.integers(9, 25))
-        S = int(rng.integers(D // 2 + 1, 17))
+        S = int(rng.integers(D // 2 + 1, 33))                  # up to 64 block types
         dev = [int(x) for x in rng.integers(0, D, size=S)]
         if max(2 * dev.count(d) for d in range(D)) > 4:
             continue
@@ -92,7 +100,7 @@ def random_wide_graph(rng):
         deps = fwd + [(K - 1 - b, K - 1 - a) for a, b in fwd]
         sinks = [i for i in range(S) if all(a != i for a, _ in fwd)]
         deps += [(i, K - 1 - i) for i in sinks]
-        if len(deps) > 60:
+        if len(deps) > 120:
             continue
         per_dev = max(max(2 * dev.count(d) for d in range(D)), 1)
         nr = int(rng.integers(1, min(4, 32 // per_dev) + 1))
@@ -112,20 +120,22 @@ def test_random_graphs_on_many_devices(gpu, seed):
         _compare(gpu, prob, int(rng.integers(0, 1 << 40)), int(rng.integers(1000, 3000)))
 
 
-def test_search_and_completion_on_sixteen_devices(gpu):
-    """a whole search on 16 devices: running best over several launches, the greedy completion of the best window"""
+@pytest.mark.parametrize("D,cap", [(16, 6), (32, 4)])
+def test_search_and_completion_on_many_devices(gpu, D, cap):
+    """a whole search on 16 devices and on 32 (64 block types): running best over several launches, the greedy
+    completion of the best window"""
     from oracle import Oracle
-    prob = vshape(16, 2, 6)
+    prob = vshape(D, 2, cap)
     g, orc = gpu.Problem(prob), Oracle(prob)
     for first in (0, 5000, 10000):
         g.eval_candidates(first, 5000)
     got, want = g.best(), orc.sweep(0, 15000)
     assert got["n_evaluated"] == 15000 and got["n_feasible"] == want["n_feasible"] and got["n_reject"][1:] == want["n_reject"][1:]
     assert (got["period"], got["index"], got["peak"]) == (want["period"], want["index"], want["peak"])
-    assert len(got["peak"]) == 16
+    assert len(got["peak"]) == D and got["feasible"]
     sched = g.complete_schedule(8)
     ok, makespan, peaks = SC.check_flat_schedule(g.problem, 8, sched["start"].tolist(), sched["dev_order"])
-    assert ok and makespan == sched["makespan"] and max(peaks) <= 6
+    assert ok and makespan == sched["makespan"] and max(peaks) <= cap
     status, leads, orders = orc.decode(got["index"])
     cand = g.best_candidate()
     assert cand["leads"] == leads and cand["orders"] == orders
