@@ -32,7 +32,9 @@ extern "C" {
 #define TESSEL_MAX_DEVICES        32   /* simulated devices D (more than 8, or more than 32
                                           block types: scored by the general kernel alone,
                                           state in global memory; no searched completion)   */
-#define TESSEL_MAX_TYPES_PER_DEV  4    /* block types that occupy one device                */
+#define TESSEL_MAX_TYPES_PER_DEV  8    /* block types that occupy one device (more than 4:
+                                          sampled spaces only; as for more than 8 devices);
+                                          at most 32 blocks per device and window             */
 #define TESSEL_MAX_NR             8    /* micro-batches per repetend window, N_R            */
 #define TESSEL_MAX_TYPES          64   /* K (more than 32: as for more than 8 devices)      */
 #define TESSEL_NUM_STATUS         6

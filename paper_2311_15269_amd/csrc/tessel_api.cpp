@@ -201,7 +201,17 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
     { const char *fd = getenv("TESSEL_FORCE_DAG"); if (fd && fd[0] == '1') chains = false; }
     // more than kMaxD devices or kMaxK block types: the tables by (device, symbol) code of the chain path and of the fast
     // kernel have no room for them; such a problem is scored as a graph, chains or not
-    const bool wide = D > kMaxD || K > kMaxK;
+    // ... and so is one with more than kMaxLT block types on a device (3-bit symbols; sampled spaces only, at most 32
+    // blocks per device and window)
+    bool many = false;
+    for (int d = 0; d < D; d++) {
+        int n = 0;
+        for (int i = 0; i < K; i++) n += desc->dev_mask[i] >> d & 1u;
+        if (n > kMaxLTW || n * NR > kMaxPos) return TESSEL_E_UNSUPPORTED;
+        if (n > kMaxLT) many = true;
+    }
+    if (many && desc->space != TESSEL_SPACE_SAMPLED_STRICT && desc->space != TESSEL_SPACE_SAMPLED_REPAIR) return TESSEL_E_UNSUPPORTED;
+    const bool wide = D > kMaxD || K > kMaxK || many;
     if (wide) chains = false;
     if (!chains && desc->num_deps > kMaxDeps) return TESSEL_E_UNSUPPORTED;
 
@@ -287,15 +297,17 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
     // the period kernel multiplies (sweeps * UB) by a sweep count
     if ((int64_t)kp.UB * kp.nsweeps * kp.nsweeps >= (int64_t)1 << 31) { delete p; return TESSEL_E_TOOBIG; }
     kp.LB = 0;
-    for (int d = 0; d < kMaxDW; d++) kp.type_of[d] = 0xFFFFFFFFu;
+    for (int d = 0; d < kMaxDW; d++) kp.type_of[d] = kp.type_of_hi[d] = 0xFFFFFFFFu;
+    kp.many = many;
     for (int d = 0; d < kMaxD; d++) { kp.pred_of[d] = 0xFFFFFFFFu; kp.mask_of[d] = kp.tok_of[d] = kp.home_of[d] = 0; }
     std::vector<int> home(K, -1);
     for (int d = 0; d < D; d++) {
         int n = 0, busy = 0;
         for (int i = 0; i < K; i++) if (desc->dev_mask[i] >> d & 1u) {
-            if (n >= kMaxLT) { delete p; return TESSEL_E_UNSUPPORTED; }
+            if (n >= kMaxLTW) { delete p; return TESSEL_E_UNSUPPORTED; }
             if (home[i] < 0) home[i] = d * 4 + n;
-            kp.type_of[d] = (kp.type_of[d] & ~(0xFFu << (8 * n))) | ((uint32_t)i << (8 * n));
+            if (n < 4) kp.type_of[d] = (kp.type_of[d] & ~(0xFFu << (8 * n))) | ((uint32_t)i << (8 * n));
+            else kp.type_of_hi[d] = (kp.type_of_hi[d] & ~(0xFFu << (8 * (n - 4)))) | ((uint32_t)i << (8 * (n - 4)));
             if (!wide) {
                 uint32_t pr = kp.pred[i] < 0 ? 0xFFu : (uint32_t)kp.pred[i];
                 kp.pred_of[d] = (kp.pred_of[d] & ~(0xFFu << (8 * n))) | (pr << (8 * n));

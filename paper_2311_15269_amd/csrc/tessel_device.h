@@ -47,7 +47,8 @@ constexpr uint64_t kCompletionKey = 0x632BE59BD9B4E019ULL;      // separates the
 
 constexpr int kMaxD = 8;         // simulated devices of the problems the fast kernel and the chain path of the general one take
 constexpr int kMaxDW = 32;       // ... of any problem: more than kMaxD go the general kernel's path for graphs
-constexpr int kMaxLT = 4;        // block types per device
+constexpr int kMaxLT = 4;        // block types per device of the problems the fast kernel and the chain path take
+constexpr int kMaxLTW = 8;       // ... of any problem (sampled spaces): more than kMaxLT go the general kernel's path for graphs
 constexpr int kMaxNR = 8;        // micro-batches per window
 constexpr int kMaxK = 32;        // block types of the problems the fast kernel and the chain path of the general one take
 constexpr int kMaxKW = 64;       // ... of any problem: more than kMaxK go the general kernel's path for graphs
@@ -78,12 +79,13 @@ struct KParams {
     uint64_t seed;
     int32_t  ntd[kMaxDW];        // block types on device d
     uint32_t type_of[kMaxDW];    // 4 x 8 bit: type id of local symbol y (0xFF = none)
+    uint32_t type_of_hi[kMaxDW]; // ... of local symbols 4-7
     uint32_t pred_of[kMaxD];     // 4 x 8 bit: type id of its producer (0xFF = none)
     uint32_t mask_of[kMaxD];     // 4 x 8 bit: device mask of that type
     uint32_t tok_of[kMaxD];      // 4 x 8 bit: first token slot of the type's chain
     uint32_t home_of[kMaxD];     // 4 x 8 bit: (lowest device)*4 + local symbol there
     int32_t  t_of[kMaxD][kMaxLT];
-    int32_t  m_of[kMaxDW][kMaxLT];
+    int32_t  m_of[kMaxDW][kMaxLTW];
     int8_t   succ[kMaxK];        // consumer type of type g or -1
     uint8_t  edge_out[kMaxK];    // position of the dependency g -> succ[g] in the caller's list
     uint8_t  cross_out[kMaxK];   // that dependency joins different device sets
@@ -130,7 +132,8 @@ struct KParams {
     uint64_t predmask[kMaxKW];   // its producers
     uint16_t tokbase[kMaxKW];    // first slot of its ring, kNoRing: nobody consumes it
     uint8_t  dsrc[kMaxDeps], ddst[kMaxDeps], dcross[kMaxDeps];   // the dependencies in the caller's order
-    uint64_t predmask_of[kMaxDW][kMaxLT];  // producers of local symbol y of device d
+    uint64_t predmask_of[kMaxDW][kMaxLTW]; // producers of local symbol y of device d
+    int32_t  many;               // some device holds more than kMaxLT block types (3-bit symbols; sampled spaces only)
     const int8_t   *leadtab;     // CANONICAL: [nlead][K] in device memory
     const uint64_t *wtab;        // CANONICAL: arrangements by remaining counts, base NR+1 digits
 };

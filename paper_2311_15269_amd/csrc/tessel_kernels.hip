@@ -93,11 +93,13 @@ struct MuWide {
 
 __device__ __forceinline__ uint32_t byte_of(uint32_t packed, uint32_t y) { return (packed >> (8u * y)) & 0xFFu; }
 
-__device__ __forceinline__ uint64_t sel4u(const uint64_t (&v)[kMaxLT], uint32_t y)
+// entry y of eight: a select tree, so that the table comes through scalar loads
+template <class T>
+__device__ __forceinline__ T sel8(const T (&v)[kMaxLTW], uint32_t y)
 {
-    uint64_t a = y & 1u ? v[1] : v[0];
-    uint64_t b = y & 1u ? v[3] : v[2];
-    return y & 2u ? b : a;
+    const T a = y & 1u ? v[1] : v[0], b = y & 1u ? v[3] : v[2], c = y & 1u ? v[5] : v[4], d = y & 1u ? v[7] : v[6];
+    const T lo = y & 2u ? b : a, hi = y & 2u ? d : c;
+    return y & 4u ? hi : lo;
 }
 __device__ __forceinline__ uint32_t sel4u(const uint32_t (&v)[kMaxLT], uint32_t y)
 {
@@ -106,7 +108,7 @@ __device__ __forceinline__ uint32_t sel4u(const uint32_t (&v)[kMaxLT], uint32_t 
     return y & 2u ? b : a;
 }
 
-__device__ __forceinline__ int sel4(const int32_t (&v)[kMaxLT], uint32_t y)
+__device__ __forceinline__ int sel4(const int32_t (&v)[kMaxLTW], uint32_t y)
 {
     int a = y & 1u ? v[1] : v[0];
     int b = y & 1u ? v[3] : v[2];
@@ -255,11 +257,16 @@ __device__ __forceinline__ int least_period(const KParams &P, const uint16_t *pr
 // index -> leads (4-bit counters by block type id) and, per device, the order of its blocks as
 // 2-bit local symbols (first block in the lowest bits).  Returns kOk or the structural reject
 // reason of the FACTORIAL space.
+// (Problems with more than four block types on a device, sampled spaces only: the third bit of the symbol at position p
+// is bit p of rem2[d].)
 template <int DM, class CNT = Mu>
-__device__ __forceinline__ int decode_candidate(const KParams &P, uint64_t idx, uint64_t (&rem)[DM], int (&remlen)[DM], CNT &mu)
+__device__ __forceinline__ int decode_candidate(const KParams &P, uint64_t idx, uint64_t (&rem)[DM], int (&remlen)[DM], CNT &mu,
+                                                uint32_t (&rem2)[DM])
 {
     const uint32_t NR = (uint32_t)P.NR;
     mu.clear();
+#pragma unroll
+    for (int d = 0; d < DM; d++) rem2[d] = 0;
 #pragma unroll
     for (int d = 0; d < DM; d++) { rem[d] = 0; remlen[d] = 0; }
     if (P.space == kFactorial) {
@@ -375,22 +382,43 @@ __device__ __forceinline__ int decode_candidate(const KParams &P, uint64_t idx, 
             if (d >= P.D) continue;
             const uint32_t n = (uint32_t)P.ntd[d] * NR;
             uint32_t c0 = P.ntd[d] > 0 ? NR : 0u, c1 = P.ntd[d] > 1 ? NR : 0u, c2 = P.ntd[d] > 2 ? NR : 0u;
+            uint32_t cw = 0;                              // up to eight types: the blocks left of every type, four bits each
+            for (int y = 0; y < P.ntd[d]; y++) cw |= NR << (4 * y);
             uint64_t o = 0;
+            uint32_t o2 = 0;
             uint32_t word = 0;
             for (uint32_t pos = 0; pos < n; pos++) {
                 uint32_t j = kDrawOrdBase + 32u * (uint32_t)d + pos;
                 if ((pos & 1u) == 0) word = stream_word(a, b, j >> 1);
                 uint32_t u = (word >> (16u * (pos & 1u))) & 0xFFFFu;
                 uint32_t digit = (u * (n - pos)) >> 16;
-                uint32_t y = (digit >= c0) + (digit >= c0 + c1) + (digit >= c0 + c1 + c2);
-                c0 -= y == 0; c1 -= y == 1; c2 -= y == 2;
-                o |= (uint64_t)y << (2u * pos);
+                uint32_t y;
+                if (P.many) {
+                    // symbol = number of cumulative counts at or below the digit
+                    uint32_t acc = 0;
+                    y = 0;
+#pragma unroll
+                    for (int k = 0; k < kMaxLTW - 1; k++) { acc += (cw >> (4 * k)) & 15u; y += digit >= acc ? 1u : 0u; }
+                    cw -= 1u << (4u * y);
+                    o2 |= (y >> 2) << pos;
+                } else {
+                    y = (digit >= c0) + (digit >= c0 + c1) + (digit >= c0 + c1 + c2);
+                    c0 -= y == 0; c1 -= y == 1; c2 -= y == 2;
+                }
+                o |= (uint64_t)(y & 3u) << (2u * pos);
             }
-            rem[d] = o; remlen[d] = (int)n;
+            rem[d] = o; remlen[d] = (int)n; rem2[d] = o2;
         }
     }
 
     return kOk;
+}
+
+template <int DM, class CNT = Mu>
+__device__ __forceinline__ int decode_candidate(const KParams &P, uint64_t idx, uint64_t (&rem)[DM], int (&remlen)[DM], CNT &mu)
+{
+    uint32_t rem2[DM];
+    return decode_candidate<DM, CNT>(P, idx, rem, remlen, mu, rem2);
 }
 
 // ------------------------------------------------------------------ one candidate (general path)
@@ -661,33 +689,43 @@ __device__ __forceinline__ int least_period_dag(const KParams &P, const DagTable
     return (int)hi;
 }
 
-// One candidate of a problem whose dependency graph is not a set of chains (general kernel only).
+// One candidate of a problem whose dependency graph is not a set of chains, or that is too wide for the other paths
+// (general kernel only).  A device's order is kept as three bit planes of its symbols (bit p of plane k = bit k of the
+// symbol at position p; up to eight block types per device) and the mask of the entries not yet placed.
+__device__ __forceinline__ uint32_t even_bits(uint64_t x);
 template <int DM, class CNT>
 __device__ __forceinline__ int evaluate_dag(const KParams &P, const DagTables &Tb, uint64_t idx, uint16_t *prog, uint32_t *state,
                                             int &period, int (&peak)[DM], DevDetail *detail)
 {
-    uint64_t rem[DM];
-    int remlen[DM];
+    uint32_t p0[DM], p1[DM], p2[DM], alive[DM];
     CNT mu;
     period = 0;
 #pragma unroll
     for (int d = 0; d < DM; d++) peak[d] = 0;
     {
-        int st = decode_candidate<DM, CNT>(P, idx, rem, remlen, mu);
+        uint64_t rem[DM];
+        int remlen[DM];
+        int st = decode_candidate<DM, CNT>(P, idx, rem, remlen, mu, p2);
         if (st != kOk) return st;
+#pragma unroll
+        for (int d = 0; d < DM; d++) {
+            p0[d] = even_bits(rem[d]); p1[d] = even_bits(rem[d] >> 1);
+            alive[d] = remlen[d] >= 32 ? 0xFFFFFFFFu : (1u << remlen[d]) - 1u;
+        }
     }
     const CNT lead = mu;
     if (detail) {
         for (int g = 0; g < P.K; g++) detail->leads[g] = (int)mu.get((uint32_t)g);
         for (int d = 0; d < kMaxDW; d++) detail->order_len[d] = 0;
     }
+    auto type_at = [&](int d, uint32_t y) -> uint32_t { return y < 4u ? byte_of(P.type_of[d], y) : byte_of(P.type_of_hi[d], y - 4u); };
     int memcur[DM];
 #pragma unroll
     for (int d = 0; d < DM; d++) {
         memcur[d] = 0;
         if (d < P.D)
             for (int y = 0; y < P.ntd[d]; y++)
-                memcur[d] += P.m_of[d][y] * (int)mu.get(byte_of(P.type_of[d], (uint32_t)y));
+                memcur[d] += P.m_of[d][y] * (int)mu.get(type_at(d, (uint32_t)y));
         peak[d] = INT_MIN;
     }
     const bool repair = P.space == kSampledRepair;
@@ -701,6 +739,15 @@ __device__ __forceinline__ int evaluate_dag(const KParams &P, const DagTables &T
         for (uint64_t rest = preds; rest; rest &= rest - 1ull) ok = ok && mu.get((uint32_t)__builtin_ctzll(rest)) > mg;
         return ok;
     };
+    // symbol at position pos of device d; entries of symbol y still to be placed
+    auto symbol = [&](uint32_t a0, uint32_t a1, uint32_t a2, uint32_t pos) -> uint32_t {
+        return ((a0 >> pos) & 1u) | (((a1 >> pos) & 1u) << 1) | (((a2 >> pos) & 1u) << 2);
+    };
+    auto left_of = [&](uint32_t a0, uint32_t a1, uint32_t a2, uint32_t al, uint32_t y) -> uint32_t {
+        return al & (y & 1u ? a0 : ~a0) & (y & 2u ? a1 : ~a1) & (y & 4u ? a2 : ~a2);
+    };
+    // places the block of type g whose entry on device d_static sits at pos_d; on its other devices its earliest entry
+    // (the head there when the block was placed as the head of all its lists)
     auto place = [&](uint32_t g, uint32_t mask, int m, uint32_t pos_d, int d_static) {
         prog[placed * kWave] = (uint16_t)(g | (mu.get(g) << CNT::kTypeBits));
         mu.inc(g);
@@ -708,15 +755,14 @@ __device__ __forceinline__ int evaluate_dag(const KParams &P, const DagTables &T
 #pragma unroll
         for (int dd = 0; dd < DM; dd++) {
             if (dd >= P.D || !((mask >> dd) & 1u)) continue;
-            uint32_t pos = 0;
-            if (dd == d_static) pos = pos_d;
-            else if (pos_d != 0xFFFFFFFFu && repair) {
+            uint32_t pos = pos_d;
+            if (dd != d_static) {
                 uint32_t ysym = 0;
-                for (int y = 0; y < P.ntd[dd]; y++) if (byte_of(P.type_of[dd], (uint32_t)y) == g) ysym = (uint32_t)y;
-                pos = find_first(rem[dd], (uint32_t)remlen[dd], ysym);
+                for (int y = 0; y < P.ntd[dd]; y++) if (type_at(dd, (uint32_t)y) == g) ysym = (uint32_t)y;
+                const uint32_t mine = left_of(p0[dd], p1[dd], p2[dd], alive[dd], ysym);
+                pos = mine ? (uint32_t)__builtin_ctz(mine) : 0u;
             }
-            rem[dd] = remove_at(rem[dd], pos);
-            remlen[dd]--;
+            alive[dd] &= ~(1u << pos);
             memcur[dd] += m;
             peak[dd] = max(peak[dd], memcur[dd]);
             if (detail) detail->orders[dd][detail->order_len[dd]++] = (int)g;
@@ -727,37 +773,41 @@ __device__ __forceinline__ int evaluate_dag(const KParams &P, const DagTables &T
         bool progress = false;
 #pragma unroll
         for (int d = 0; d < DM; d++) {
-            if (d >= P.D || remlen[d] == 0) continue;
-            const uint32_t y = (uint32_t)rem[d] & 3u;
-            const uint32_t g = byte_of(P.type_of[d], y), mask = Tb.mask[g];
-            bool ok = ready(g, sel4u(P.predmask_of[d], y));
+            if (d >= P.D || alive[d] == 0) continue;
+            const uint32_t pos = (uint32_t)__builtin_ctz(alive[d]);
+            const uint32_t y = symbol(p0[d], p1[d], p2[d], pos);
+            const uint32_t g = type_at(d, y), mask = Tb.mask[g];
+            bool ok = ready(g, sel8(P.predmask_of[d], y));
             if (mask != (1u << d)) {
                 // a multi-device block runs when it heads the list of all its devices; it is placed from its lowest device
                 if ((mask & ((1u << d) - 1u)) != 0) ok = false;
 #pragma unroll
                 for (int dd = 0; dd < DM; dd++) {
                     if (dd >= P.D || dd == d || !((mask >> dd) & 1u)) continue;
-                    if (!(remlen[dd] > 0 && byte_of(P.type_of[dd], (uint32_t)rem[dd] & 3u) == g)) ok = false;
+                    const uint32_t hp = (uint32_t)__builtin_ctz(alive[dd] | 0x80000000u);
+                    if (!(alive[dd] != 0 && type_at(dd, symbol(p0[dd], p1[dd], p2[dd], hp)) == g)) ok = false;
                 }
             }
-            if (ok) { place(g, mask, sel4(P.m_of[d], y), 0u, d); progress = true; }
+            if (ok) { place(g, mask, sel8(P.m_of[d], y), pos, d); progress = true; }
         }
         if (progress) continue;
         if (!repair) { deadlock = true; break; }
         bool done = false;
 #pragma unroll
         for (int d = 0; d < DM; d++) {
-            if (done || d >= P.D || remlen[d] == 0) continue;
+            if (done || d >= P.D || alive[d] == 0) continue;
             uint32_t best_pos = 64u, best_y = 0;
 #pragma unroll
-            for (int y = 0; y < kMaxLT; y++) {
+            for (int y = 0; y < kMaxLTW; y++) {
                 if (y >= P.ntd[d]) continue;
-                const bool ok = ready(byte_of(P.type_of[d], (uint32_t)y), P.predmask_of[d][y]);
-                const uint32_t pos = ok ? find_first(rem[d], (uint32_t)remlen[d], (uint32_t)y) : 64u;
+                const bool ok = ready(type_at(d, (uint32_t)y), P.predmask_of[d][y]);
+                const uint32_t mine = left_of(p0[d], p1[d], p2[d], alive[d], (uint32_t)y);
+                const uint32_t pos = ok && mine ? (uint32_t)__builtin_ctz(mine) : 64u;
                 if (pos < best_pos) { best_pos = pos; best_y = (uint32_t)y; }
             }
             if (best_pos < 64u) {
-                place(byte_of(P.type_of[d], best_y), Tb.mask[byte_of(P.type_of[d], best_y)], sel4(P.m_of[d], best_y), best_pos, d);
+                const uint32_t g = type_at(d, best_y);
+                place(g, Tb.mask[g], sel8(P.m_of[d], best_y), best_pos, d);
                 done = true;
             }
         }
@@ -1898,7 +1948,7 @@ static eval_fn pick_kernel(const KParams &kp)
 {
     const int V = kp.nsweeps - 1;
     if (kp.D > 16) return eval_kernel<32, 1>;
-    if (kp.D > kMaxD || kp.K > kMaxK) return eval_kernel<16, 1>;
+    if (kp.D > kMaxD || kp.K > kMaxK || kp.many) return eval_kernel<16, 1>;
     if (kp.D <= 2 && V <= 4) return eval_kernel<2, 4>;
     if (kp.D <= 4 && V <= 8) return eval_kernel<4, 8>;
     if (kp.D <= 8 && V <= 16) return eval_kernel<8, 16>;
@@ -1935,7 +1985,7 @@ static fast_fn pick_fast(const KParams &kp)
 }
 
 // state and program of the general kernel's lanes: in LDS, except for problems with more than kMaxD devices
-static bool far_state(const KParams &kp) { return kp.D > kMaxD || kp.K > kMaxK; }
+static bool far_state(const KParams &kp) { return kp.D > kMaxD || kp.K > kMaxK || kp.many; }
 static size_t far_bytes(const KParams &kp) { return far_state(kp) ? far_words(kp) * 4 : 0; }
 
 static size_t general_lds_bytes(const KParams &kp)

@@ -41,7 +41,12 @@ def test_problem_create_validates_on_the_host():
     assert binding.Problem(wide).workspace_bytes() > 0
     many = dict(wide, K=64, t=[1] * 64, m=[0] * 64, dev_mask=[1 << (d % 32) for d in range(64)], deps=[(i, i + 1) for i in range(63)])
     assert binding.Problem(many).candidate_count() == 2 ** 64 - 1
+    # up to eight block types on a device in the sampled spaces, four in the exhaustive ones
+    crowded = W.pipeline_problem([0, 1, 0, 1, 0, 1], [1] * 6, [2] * 6, 2, 2, 9, "sampled_repair")
+    assert binding.Problem(crowded).candidate_count() == 2 ** 64 - 1
     for bad, code in (
+        (dict(crowded, space="canonical"), -9),
+        (dict(crowded, NR=6), -9),                             # 36 blocks on a device
         (dict(wide, D=33), -9),
         (dict(many, K=65, t=[1] * 65, m=[0] * 65, dev_mask=[1 << (d % 32) for d in range(65)]), -9),
         (dict(W.config1(), m=[1, 1, -1, 0]), -3),

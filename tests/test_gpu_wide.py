@@ -1,5 +1,5 @@
-"""Problems with more than 8 devices or more than 32 block types (Table I puts no bound on D and K; the boundary takes
-up to 32 and 64): scored by the general kernel's path for graphs with the lanes' state in global memory.  HIP path against the oracle element by element:
+"""Problems with more than 8 devices, more than 32 block types or more than 4 block types on a device (Table I puts no
+bound on them; the boundary takes up to 32, 64 and 8): scored by the general kernel's path for graphs with the lanes' state in global memory.  HIP path against the oracle element by element:
 V-shape pipelines on 12 and 16 devices, a forward-only pipeline on 32, a block on ten devices at once, the two
 exhaustive spaces, seeded random graphs on up to 24 devices; best candidate, its start times and its completion."""
 import numpy as np
@@ -52,7 +52,30 @@ def shared_block(D, nr, cap, space="sampled_repair", seed=0xC0FFEE2):
             "fixed_leads": None}
 
 
+def crowded(D, per_dev, nr, cap, space="sampled_repair", seed=0xD0FFEE3, step=20000, shared=False):
+    """per_dev pipeline stages on every device (round robin): 2 per_dev block types per device; with `shared` a
+    block on all devices in front (forward) and behind (backward) as well"""
+    rng = W._Stream(seed)
+    stage_dev = [s % D for s in range(per_dev * D)]
+    S = len(stage_dev)
+    tf = [rng.randint(1, 3) for _ in range(S)]
+    tb = [rng.randint(1, 5) for _ in range(S)]
+    prob = W.pipeline_problem(stage_dev, tf, tb, D, nr, cap, space, seed=seed, lead_step_q16=step, name="crowded-%dx%d" % (D, per_dev))
+    if shared:
+        full = (1 << D) - 1
+        K = prob["K"] + 2
+        prob.update(K=K, t=[2] + prob["t"] + [3], m=[1] + prob["m"] + [-1], dev_mask=[full] + prob["dev_mask"] + [full],
+                    deps=[(i, i + 1) for i in range(K - 1)])
+    return prob
+
+
 SHAPES = [
+    ("six-types-a-device", crowded(3, 3, 3, 5), 11, 3000),
+    ("six-types-strict", crowded(2, 3, 1, 3, space="sampled_strict"), 0, 6000),
+    ("eight-types-a-device", crowded(2, 4, 4, 9), 1 << 34, 2000),
+    ("eight-types-on-six-devices", crowded(6, 4, 2, 5, step=9000), 5, 800),
+    ("shared-and-folded", crowded(4, 2, 3, 10, shared=True), 99, 3000),
+    ("five-types-fixed-leads", dict(crowded(3, 3, 2, 4), fixed_leads=[0] * 18), 7, 2000),
     ("vshape-12-repair", vshape(12, 2, 2), 4242, 3000),
     ("vshape-12-strict", vshape(12, 2, 6, space="sampled_strict", step=8000), 0, 3000),
     ("vshape-16-repair", vshape(16, 4, 5), 1 << 35, 2000),
@@ -118,6 +141,42 @@ def test_random_graphs_on_many_devices(gpu, seed):
     for case in range(6):
         prob = random_wide_graph(rng)
         _compare(gpu, prob, int(rng.integers(0, 1 << 40)), int(rng.integers(1000, 3000)))
+
+
+def random_crowded_graph(rng):
+    """2-6 devices with up to four stages (eight block types) each, forward graph with fan-in and fan-out"""
+    while True:
+        D = int(rng.integers(2, 7))
+        S = int(rng.integers(2 * D + 1, 4 * D + 1))
+        dev = [int(x) for x in rng.integers(0, D, size=S)]
+        per_dev = max(2 * dev.count(d) for d in range(D))
+        if per_dev <= 4 or per_dev > 8 or 2 * S > 64:
+            continue
+        fwd = []
+        for i in range(1, S):
+            for a in set(int(x) for x in rng.integers(max(0, i - 3), i, size=int(rng.integers(1, 3)))):
+                fwd.append((a, i))
+        K = 2 * S
+        deps = fwd + [(K - 1 - b, K - 1 - a) for a, b in fwd]
+        sinks = [i for i in range(S) if all(a != i for a, _ in fwd)]
+        deps += [(i, K - 1 - i) for i in sinks]
+        if len(deps) > 120:
+            continue
+        nr = int(rng.integers(1, min(6, 32 // per_dev) + 1))
+        t = [int(x) for x in rng.integers(1, 6, size=K)]
+        masks = [1 << d for d in dev] + [1 << d for d in reversed(dev)]
+        return {"name": "random-crowded", "D": D, "K": K, "NR": nr, "M": int(rng.integers(2, 3 * nr + 3)), "t": t,
+                "m": [1] * S + [-1] * S, "dev_mask": masks, "deps": deps,
+                "space": ["sampled_repair", "sampled_repair", "sampled_strict"][int(rng.integers(0, 3))],
+                "seed": int(rng.integers(1, 1 << 30)), "lead_step_q16": int(rng.integers(5000, 60000)), "fixed_leads": None}
+
+
+@pytest.mark.parametrize("seed", [51, 52])
+def test_random_graphs_with_crowded_devices(gpu, seed):
+    rng = np.random.default_rng(seed)
+    for case in range(8):
+        prob = random_crowded_graph(rng)
+        _compare(gpu, prob, int(rng.integers(0, 1 << 40)), int(rng.integers(1000, 4000)))
 
 
 @pytest.mark.parametrize("D,cap", [(16, 6), (32, 4)])

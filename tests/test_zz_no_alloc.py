@@ -29,11 +29,13 @@ def test_noalloc_equals_the_workspace_entry_point(gpu):
     import torch
     prob = W.config5()
     g = gpu.Problem(prob)
+    import gc
+    gc.collect()                                           # (workspaces of earlier tests go now, not during the call)
     before = torch.cuda.memory_allocated()
     # first call: a range that leaves the queues of the buffer full of stale candidates
     g.eval_candidates_noalloc(7, (1 << 20) + 3)
     got = g.best()
-    assert torch.cuda.memory_allocated() == before        # nothing came from torch's allocator either
+    assert torch.cuda.memory_allocated() <= before        # nothing came from torch's allocator either
     want = _reference(gpu, prob, 7, (1 << 20) + 3)
     for key in KEYS:
         assert got[key] == want[key], key
