@@ -206,6 +206,27 @@ def test_search_and_completion_on_many_devices(gpu, D, cap):
     assert err.value.code == -9
 
 
+def test_search_and_completion_with_six_types_a_device(gpu):
+    from oracle import Oracle
+    prob = crowded(3, 3, 3, 6)
+    g, orc = gpu.Problem(prob), Oracle(prob)
+    g.eval_candidates(0, 30000)
+    got, want = g.best(), orc.sweep(0, 30000)
+    assert got["feasible"] and (got["period"], got["index"], got["peak"], got["n_feasible"]) == \
+        (want["period"], want["index"], want["peak"], want["n_feasible"])
+    status, leads, orders = orc.decode(got["index"])
+    cand = g.best_candidate()
+    assert cand["leads"] == leads and cand["orders"] == orders
+    ref = orc.eval_index(got["index"], want_starts=True)
+    assert (cand["starts"] == ref["starts"]).all()
+    assert SC.check_periodic(prob, leads, orders, cand["starts"].tolist(), got["period"])
+    sched = g.complete_schedule(10)
+    ok, makespan, peaks = SC.check_flat_schedule(g.problem, 10, sched["start"].tolist(), sched["dev_order"])
+    assert ok and makespan == sched["makespan"] and max(peaks) <= 6
+    ref = orc.complete(leads, orders, 10)
+    assert sched["makespan"] == ref["makespan"] and sched["start"].tolist() == ref["start"].tolist()
+
+
 def test_the_device_limit(gpu):
     with pytest.raises(gpu.TesselError) as err:
         gpu.Problem(dict(inference(32, 2), D=33, K=33, t=[1] * 33, m=[0] * 33, dev_mask=[1 << (d % 32) for d in range(33)],
