@@ -1777,7 +1777,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
 // ------------------------------------------------------------------ kernels
 // Problems with more than kMaxD devices or more than kMaxK block types (DM above kMaxD) are scored as dependency graphs,
 // with the per-lane state and program in global memory (`far`: one region of far_words(P) words per workgroup)
-// instead of LDS: up to 32 devices with up to 63 rings of 16 end times each do not fit there.
+// where 64 KB of LDS do not hold them: 32 devices with up to 63 rings of 16 end times each need 330 KB.
 __host__ __device__ inline size_t far_words(const KParams &P)
 {
     return (((size_t)P.nslots * kWave * 4 + (size_t)P.total * kWave * 2 + 255) & ~(size_t)255) / 4;
@@ -1798,7 +1798,8 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
     constexpr int KT = wide ? kMaxKW : kMaxK;             // entries of a table by type
     int32_t *t_tab = (int32_t *)lds;
     uint32_t *mask_tab = lds + KT;
-    uint32_t *state_all = wide ? far + (size_t)blockIdx.x * far_words(P) : lds + 4 * kMaxK;
+    // (wide problems: in the workspace when `far` is given, else behind their five tables in LDS)
+    uint32_t *state_all = !wide ? lds + 4 * kMaxK : far ? far + (size_t)blockIdx.x * far_words(P) : lds + 5 * kMaxKW;
     uint16_t *prog_all = (uint16_t *)(state_all + P.nslots * kWave);
     const int lane = threadIdx.x;
     // by home code for chain problems, by type id (with the producers and the token rings) for the others
@@ -1944,11 +1945,14 @@ typedef void (*eval_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t
 typedef void (*fast_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, int, int, uint64_t *, uint32_t *,
                         uint32_t, uint32_t *, uint32_t *, uint32_t, int);
 
+// problems too wide for the fast kernel and the chain path (their state stays in LDS where 64 KB hold it)
+static bool wide_problem(const KParams &kp) { return kp.D > kMaxD || kp.K > kMaxK || kp.many; }
+
 static eval_fn pick_kernel(const KParams &kp)
 {
     const int V = kp.nsweeps - 1;
     if (kp.D > 16) return eval_kernel<32, 1>;
-    if (kp.D > kMaxD || kp.K > kMaxK || kp.many) return eval_kernel<16, 1>;
+    if (wide_problem(kp)) return eval_kernel<16, 1>;
     if (kp.D <= 2 && V <= 4) return eval_kernel<2, 4>;
     if (kp.D <= 4 && V <= 8) return eval_kernel<4, 8>;
     if (kp.D <= 8 && V <= 16) return eval_kernel<8, 16>;
@@ -1985,12 +1989,13 @@ static fast_fn pick_fast(const KParams &kp)
 }
 
 // state and program of the general kernel's lanes: in LDS, except for problems with more than kMaxD devices
-static bool far_state(const KParams &kp) { return kp.D > kMaxD || kp.K > kMaxK || kp.many; }
+static bool far_state(const KParams &kp) { return wide_problem(kp) && (size_t)5 * kMaxKW * 4 + far_words(kp) * 4 > 64 * 1024; }
 static size_t far_bytes(const KParams &kp) { return far_state(kp) ? far_words(kp) * 4 : 0; }
 
 static size_t general_lds_bytes(const KParams &kp)
 {
-    return far_state(kp) ? (size_t)5 * kMaxKW * 4 : (size_t)4 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)kp.total * kWave * 2;
+    if (wide_problem(kp)) return (size_t)5 * kMaxKW * 4 + (far_state(kp) ? 0 : far_words(kp) * 4);
+    return (size_t)4 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)kp.total * kWave * 2;
 }
 
 static size_t fast_lds_bytes(const KParams &kp)
