@@ -2244,7 +2244,9 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
     // J < 64 (checked by the host)
     const int TR = cp.tok_ring, tmask = TR - 1;          // end times of the micro-batches in flight: [chain][mu mod TR]
     const int trs = __builtin_ctz((uint32_t)TR);         // (a power of two)
-    const int oTok = 0, oFree = cp.npaths * TR, oMem = oFree + D, oNext = oMem + D, nstate = oNext + K;
+    // (one more slot behind the state and one more row behind the keys take the stores of lanes that have nothing to
+    // store, so that no store needs a branch)
+    const int oTok = 0, oFree = cp.npaths * TR, oMem = oFree + D, oNext = oMem + D, oTrash = oNext + K, nstate = oTrash + 1;
     // Problems with every type on one device (and at most 8 chains) take a path that keeps, per type, the sort key of
     // its offered block in LDS and touches only the types a scheduled block can change: its own type and its consumers
     // are recomputed (`redo`); of the other types on its device (`aff`) a key that exists only moves to the device's new
@@ -2275,7 +2277,7 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
     // numbers of the inputs, kMatOut of the outputs, then one row of kMatIn path lengths per output; or (no matrix: too
     // many values cross the windows) one word per block of the window: device (3 bits), chain (3), micro-batch within
     // the first window = lead + occurrence (8), has a producer (1), t (16)
-    uint32_t *rtab = lds + kCompParamWords + (nstate + 1) / 2 * kWave + K * kWave;
+    uint32_t *rtab = lds + kCompParamWords + (nstate + 1) / 2 * kWave + (K + 1) * kWave;
     const int nin = single_dev ? cmg->nin : 0, nout = cmg->nout;
     if (nin > 0) {
         for (int s = lane; s < kMatIn; s += kWave) rtab[s] = cmg->in_slot[s];
@@ -2342,7 +2344,7 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
 #pragma unroll 8
                     for (int i = 0; i < K; i++) bestp = min(bestp, ckey[i * kWave]);
                     const bool placed = busy && bestp < 0x80000000u;
-                    if (busy && !placed) fail = true;             // blocks left, none eligible: no schedule
+                    fail = fail | (busy && !placed);              // blocks left, none eligible: no schedule
                     // A lane that places nothing goes through the step with type 0 and writes nothing.  The step is
                     // three rounds of LDS reads, each issued as a whole before anything waits for it (the values are
                     // pinned so that no read sinks into a branch): (1) the table words of the block's type; (2) what
@@ -2369,15 +2371,15 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                     TESSEL_PIN(napb); TESSEL_PIN(tkb);
                     const int en = (int)(bestp >> 15) - (int)(njb >> 10) + (int)tb;
                     const int me_new = (int)(int16_t)me_old + mi_b;
-                    const uint32_t jn = jitter(b, mu1);
+                    uint32_t jn = (stream_draw16(ka, kb, (uint32_t)(b * N + mu1)) * (uint32_t)(J + 1)) >> 16;
+                    TESSEL_PIN(jn);
+                    jn = noisy ? jn : 0u;
                     const uint32_t njb_new = (uint32_t)mu1 | (mu1 < hi_b ? jn : 0u) << 10;
-                    if (placed) {
-                        TESSEL_ST(oFree + d) = (uint16_t)en;
-                        TESSEL_ST(oMem + d) = (uint16_t)me_new;
-                        TESSEL_ST(oTok + ((int)(pw >> 25 & 7u) << trs) + (bmu & tmask)) = (uint16_t)en;
-                        TESSEL_ST(oNext + b) = (uint16_t)njb_new;
-                        left--;
-                    }
+                    TESSEL_ST(placed ? oFree + d : oTrash) = (uint16_t)en;
+                    TESSEL_ST(placed ? oMem + d : oTrash) = (uint16_t)me_new;
+                    TESSEL_ST(placed ? oTok + ((int)(pw >> 25 & 7u) << trs) + (bmu & tmask) : oTrash) = (uint16_t)en;
+                    TESSEL_ST(placed ? oNext + b : oTrash) = (uint16_t)njb_new;
+                    left -= placed ? 1 : 0;
                     // round 3: the consumer's device and the end time of the micro-batch it waits for, as they are now
                     const int dc = (int)(pwc >> 22 & 7u), muc = (int)(njc & 1023u);
                     uint32_t frc = TESSEL_ST(oFree + dc), mec = TESSEL_ST(oMem + dc);
@@ -2389,32 +2391,38 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                     // later than now before, so the new key is max(old key, new free time + jitter); the same
                     // micro-batch stays offered.
                     const uint32_t blocked = 0x80000000u;
-                    uint32_t kb, kc;
+                    uint32_t key_b, key_c;
                     {
                         const bool offered = (mu1 < hi_b) & (!has_ab | ((int)(napb & 1023u) > mu1));
                         const bool fits = (mi_b <= 0) | (me_new + mi_b <= M);
                         const uint32_t key = (uint32_t)max(has_ab ? (int)tkb : 0, en) + (njb_new >> 10);
-                        kb = offered ? (key << 15) | ((uint32_t)mu1 << 5) | (uint32_t)b | (fits ? 0u : blocked) : 0xFFFFFFFFu;
+                        uint32_t word = (key << 15) | ((uint32_t)mu1 << 5) | (uint32_t)b | (fits ? 0u : blocked);
+                        TESSEL_PIN(word);                  // (computed in every lane: cheaper than a branch around it)
+                        key_b = offered ? word : 0xFFFFFFFFu;
                     }
                     {
                         const int hic = phase ? N : (int)(pwc & 255u), mic = (int)(int8_t)(pwc >> 8);
                         const bool offered = (muc < hic) & (mu1 > muc);            // (its producer is the block's type)
                         const bool fits = (mic <= 0) | ((int)(int16_t)mec + mic <= M);
                         const uint32_t key = max(tkc, frc) + (njc >> 10);
-                        kc = offered ? (key << 15) | ((uint32_t)muc << 5) | (uint32_t)c | (fits ? 0u : blocked) : 0xFFFFFFFFu;
+                        uint32_t word = (key << 15) | ((uint32_t)muc << 5) | (uint32_t)c | (fits ? 0u : blocked);
+                        TESSEL_PIN(word);
+                        key_c = offered ? word : 0xFFFFFFFFu;
                     }
                     auto moved = [&](uint32_t k, uint32_t pwi, uint32_t nji) -> uint32_t {
                         const int mi = (int)(int8_t)(pwi >> 8);
                         const uint32_t start = max(k << 1 >> 16, (uint32_t)en + (nji >> 10));
                         const bool fits = (mi <= 0) | (me_new + mi <= M);
-                        return k == 0xFFFFFFFFu ? k : (start << 15) | (k & 0x7FFFu) | (fits ? 0u : blocked);
+                        uint32_t word = (start << 15) | (k & 0x7FFFu) | (fits ? 0u : blocked);
+                        TESSEL_PIN(word);
+                        return k == 0xFFFFFFFFu ? k : word;
                     };
                     k0 = moved(k0, p0, n0); k1 = moved(k1, p1, n1); k2 = moved(k2, p2, n2);
-                    if (placed) ckey[b * kWave] = kb;
-                    if (has_c) ckey[c * kWave] = kc;
-                    if (h0) ckey[a0 * kWave] = k0;
-                    if (h1) ckey[a1 * kWave] = k1;
-                    if (h2) ckey[a2 * kWave] = k2;
+                    ckey[(placed ? b : K) * kWave] = key_b;
+                    ckey[(has_c ? c : K) * kWave] = key_c;
+                    ckey[(h0 ? a0 : K) * kWave] = k0;
+                    ckey[(h1 ? a1 : K) * kWave] = k1;
+                    ckey[(h2 ? a2 : K) * kWave] = k2;
                     if (crowded) {
                         // a type with several consumers, or more than four types on a device: the rest one by one
                         uint32_t todo = placed ? rd & (rd - 1u) : 0u;
@@ -2570,7 +2578,8 @@ size_t completion_lds_bytes(const CompParams &cp, const CompMatrix &cm)
 {
     // 16-bit state, then one 32-bit sort key per type, then the windows' matrix or one word per block of the window
     const size_t replay = cm.nin > 0 ? (size_t)(kMatIn + kMatOut + cm.nout * kMatIn) * 4 : (size_t)cp.nseq * 4;
-    return (size_t)kCompParamWords * 4 + (size_t)((cp.npaths * cp.tok_ring + 2 * cp.D + cp.K + 1) / 2 * 2) * kWave * 2 + (size_t)cp.K * kWave * 4 +
+    return (size_t)kCompParamWords * 4 + (size_t)((cp.npaths * cp.tok_ring + 2 * cp.D + cp.K + 1 + 1) / 2 * 2) * kWave * 2 +
+           (size_t)(cp.K + 1) * kWave * 4 +
            ((replay + 15) & ~(size_t)15);
 }
 
