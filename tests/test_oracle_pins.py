@@ -438,3 +438,79 @@ def test_a_block_on_two_devices_with_two_leads_is_a_mismatch():
     got = [orc.eval_index(i) for i in range(4)]
     assert [g["status"] for g in got] == [OK, TP_MISMATCH, TP_MISMATCH, OK]
     assert got[0]["period"] == got[3]["period"] == 6
+
+
+# ---------------------------------------------------------------- dependency graphs with fan-in and fan-out
+def _tiny_graph_cases():
+    """A block type with two producers (two branches that join) and with two consumers, on 2-3 devices, 4-6 blocks
+    per window, small times: orders half from plain shuffles, half from the repaired sampled space."""
+    rng = random.Random(20231116)
+    shapes = [
+        # A(0), B(1) -> J(2): fan-in only
+        dict(D=3, K=3, dev_mask=[1, 2, 4], deps=[(0, 2), (1, 2)], m=[0, 0, 0]),
+        # S(0) -> L(1), R(0): fan-out, then both into T(1): a diamond on two devices
+        dict(D=2, K=4, dev_mask=[1, 2, 1, 2], deps=[(0, 1), (0, 2), (1, 3), (2, 3)], m=[1, 1, -1, -1]),
+        # the K-shape, forward and backward: A_F(0), B_F(1) -> J_F(2) -> J_B(2) -> A_B(0), B_B(1)
+        dict(D=3, K=6, dev_mask=[1, 2, 4, 4, 1, 2], deps=[(0, 2), (1, 2), (2, 3), (3, 4), (3, 5)], m=[1, 1, 1, -1, -1, -1]),
+    ]
+    cases = []
+    for k in range(48):
+        shape = shapes[k % 3]
+        nr = 2 if shape["K"] <= 3 and k % 2 else 1
+        K, D = shape["K"], shape["D"]
+        prob = dict(shape, name="tiny-graph", NR=nr, M=99, t=[rng.randint(1, 3) for _ in range(K)], space="sampled_repair",
+                    seed=k, lead_step_q16=40000, fixed_leads=None)
+        if k % 4 == 0:
+            leads = [0] * K
+            if nr > 1:                                    # producers never behind their consumers (Property 2)
+                for i in reversed(range(K)):
+                    succ = [b for a, b in prob["deps"] if a == i]
+                    if succ:
+                        leads[i] = min(nr - 1, max(leads[b] for b in succ) + (rng.random() < 0.5))
+            orders = []
+            for d in range(D):
+                seq = [g for g in range(K) if prob["dev_mask"][g] >> d & 1 for _ in range(nr)]
+                rng.shuffle(seq)
+                orders.append(seq)
+        else:
+            _, leads, orders = Oracle(prob).decode(rng.randrange(1 << 30))
+        cases.append((prob, leads, orders))
+    return cases
+
+
+def test_period_of_graphs_with_fan_in_and_fan_out_equals_brute_force():
+    """Sec. III-A allows any acyclic dependency graph inside a micro-batch (Eq. 1 [3] for every edge).  The same brute
+    force over start vectors as above, on windows whose graph branches: a block waits for all its producers."""
+    checked = deadlocked = 0
+    for prob, leads, orders in _tiny_graph_cases():
+        orc = Oracle(prob)
+        r = orc.eval_explicit(leads, orders, want_starts=True)
+        box = orc.upper_bound
+        if r["status"] == DEADLOCK:
+            assert not SC.exists_periodic_schedule(prob, leads, orders, 2 * orc.upper_bound, box)
+            deadlocked += 1
+            continue
+        assert r["status"] == OK
+        T = r["period"]
+        assert orc.lower_bound <= T <= orc.upper_bound
+        assert SC.check_periodic(prob, leads, orders, r["starts"].tolist(), T)
+        assert SC.exists_periodic_schedule(prob, leads, orders, T, box)
+        if T > 1:
+            assert not SC.exists_periodic_schedule(prob, leads, orders, T - 1, box)
+        checked += 1
+    assert checked >= 25 and deadlocked >= 1
+
+
+def test_one_micro_batch_of_the_k_shape_takes_its_critical_path():
+    """One micro-batch per window (all leads 0): a device can only run its forward block before its backward block,
+    and the next window's forward block follows this window's backward block on the same device, so the cycles of
+    the constraint graph are, per branch device, forward + joint forward + joint backward + backward, and the joint
+    device's own two blocks: T* = t_J + t_J' + max(t_A + t_A', t_B + t_B'); every other order deadlocks."""
+    for tf, tb in (((2, 1, 3), (4, 2, 6)), ((1, 5, 2), (3, 1, 1)), ((4, 4, 1), (1, 2, 2)), ((1, 1, 7), (1, 1, 1))):
+        prob = W.kshape_problem(1, 99, tf=tf, tb=tb, space="canonical")
+        orc = Oracle(prob)
+        assert orc.count == 8                              # two orders on each of the three devices
+        best = orc.sweep(0, orc.count)
+        assert best["n_feasible"] == 1 and best["n_reject"][DEADLOCK] == 7
+        assert best["period"] == tf[2] + tb[2] + max(tf[0] + tb[0], tf[1] + tb[1])
+        assert best["peak"] == [1, 1, 1]
