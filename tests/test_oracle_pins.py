@@ -514,3 +514,58 @@ def test_one_micro_batch_of_the_k_shape_takes_its_critical_path():
         assert best["n_feasible"] == 1 and best["n_reject"][DEADLOCK] == 7
         assert best["period"] == tf[2] + tb[2] + max(tf[0] + tb[0], tf[1] + tb[1])
         assert best["peak"] == [1, 1, 1]
+
+
+def _tiny_shared_block_cases():
+    """windows with a block that occupies both devices (tensor parallelism: it takes part in both device orders
+    and needs both devices at once), 3-6 blocks per window"""
+    rng = random.Random(20231117)
+    shapes = [
+        # X on both devices feeds A(0) and B(1)
+        dict(D=2, K=3, dev_mask=[3, 1, 2], deps=[(0, 1), (0, 2)], m=[0, 0, 0]),
+        # A(0), B(1) -> X on both -> Y(0)
+        dict(D=2, K=4, dev_mask=[1, 2, 3, 1], deps=[(0, 2), (1, 2), (2, 3)], m=[0, 0, 0, 0]),
+        # a chain X(both) -> A(0) -> B(1) -> X'(both), the shape of the 4-device benchmark configuration in small
+        dict(D=2, K=4, dev_mask=[3, 1, 2, 3], deps=[(0, 1), (1, 2), (2, 3)], m=[1, 0, 0, -1]),
+    ]
+    cases = []
+    for k in range(45):
+        shape = shapes[k % 3]
+        nr = 2 if shape["K"] == 3 and k % 2 else 1
+        K, D = shape["K"], shape["D"]
+        prob = dict(shape, name="tiny-shared", NR=nr, M=99, t=[rng.randint(1, 3) for _ in range(K)], space="sampled_repair",
+                    seed=k, lead_step_q16=40000, fixed_leads=None)
+        if k % 3 == 0:
+            leads = [0] * K
+            orders = []
+            for d in range(D):
+                seq = [g for g in range(K) if prob["dev_mask"][g] >> d & 1 for _ in range(nr)]
+                rng.shuffle(seq)
+                orders.append(seq)
+        else:
+            _, leads, orders = Oracle(prob).decode(rng.randrange(1 << 30))
+        cases.append((prob, leads, orders))
+    return cases
+
+
+def test_period_with_a_block_on_two_devices_equals_brute_force():
+    """A block that occupies several devices (d_B is a set, Sec. III-A) holds all of them for its time: exclusivity
+    (Eq. 1 [1]) on every one of its devices.  Brute force over start vectors as above."""
+    checked = deadlocked = 0
+    for prob, leads, orders in _tiny_shared_block_cases():
+        orc = Oracle(prob)
+        r = orc.eval_explicit(leads, orders, want_starts=True)
+        box = orc.upper_bound
+        if r["status"] == DEADLOCK:
+            assert not SC.exists_periodic_schedule(prob, leads, orders, 2 * orc.upper_bound, box)
+            deadlocked += 1
+            continue
+        assert r["status"] == OK
+        T = r["period"]
+        assert orc.lower_bound <= T <= orc.upper_bound
+        assert SC.check_periodic(prob, leads, orders, r["starts"].tolist(), T)
+        assert SC.exists_periodic_schedule(prob, leads, orders, T, box)
+        if T > 1:
+            assert not SC.exists_periodic_schedule(prob, leads, orders, T - 1, box)
+        checked += 1
+    assert checked >= 25 and deadlocked >= 1
