@@ -569,3 +569,41 @@ def test_period_with_a_block_on_two_devices_equals_brute_force():
             assert not SC.exists_periodic_schedule(prob, leads, orders, T - 1, box)
         checked += 1
     assert checked >= 25 and deadlocked >= 1
+
+
+def test_peak_memory_is_the_running_sum_of_eq_1_on_the_expanded_schedule():
+    """Eq. 1 [2] literally: repeat the window many times at its period, take every micro-batch whose blocks all lie
+    inside the expansion, sort each device's blocks by start time and accumulate m.  Once the pipeline is full the
+    largest value over a window is the peak the oracle reports (entry memory from the leads + prefix in device order)."""
+    rng = random.Random(424242)
+    checked = 0
+    probs = [W.config1(), W.config3(), dict(W.config4(), M=99), W.kshape_problem(3, 99), W.diamond_problem(2, 99),
+             W.pipeline_problem(W.folded_placement(3), [1, 2, 1, 1, 3, 2], [2, 2, 1, 3, 1, 2], 3, 3, 99, "sampled_repair",
+                                seed=5, lead_step_q16=30000)]
+    for prob in probs:
+        prob = dict(prob, space="sampled_repair", M=99)
+        orc = Oracle(prob)
+        K, NR, D = prob["K"], prob["NR"], prob["D"]
+        for _ in range(6):
+            index = rng.randrange(1 << 40)
+            status, leads, orders = orc.decode(index)
+            r = orc.eval_explicit(leads, orders, want_starts=True)
+            assert r["status"] == OK
+            T, windows = r["period"], 8
+            blocks = SC.expand_periodic(prob, leads, orders, r["starts"].tolist(), T, windows)
+            lo, hi = max(leads), NR * windows + min(leads)             # micro-batches with every block inside
+            per_dev = [[] for _ in range(D)]
+            for (i, mu), s in blocks.items():
+                if lo <= mu < hi:
+                    for d in SC.devices_of(prob, i):
+                        per_dev[d].append((s, prob["m"][i]))
+            for d in range(D):
+                cur, peak = 0, None
+                for s, m in sorted(per_dev[d]):
+                    cur += m
+                    if 3 * T <= s < 5 * T:                               # two windows in the steady state
+                        peak = cur if peak is None else max(peak, cur)
+                want = r["peak"][d]
+                assert (peak if peak is not None else 0) == want, (prob["name"], index, d, peak, want)
+            checked += 1
+    assert checked == 36
