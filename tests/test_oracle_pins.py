@@ -426,6 +426,25 @@ def test_repair_matches_the_worked_examples():
         assert sorted(d0) == sorted(want0) and sorted(d1) == sorted(want1)
 
 
+def test_repair_on_branching_graphs_and_shared_blocks_matches_the_worked_examples():
+    """Examples 4-6 of tests/golden/repair_hand.txt: a block with two producers waits for both, the K-shape, a block
+    on both devices placed by the fallback leaves both lists."""
+    rows = _golden_lines("repair_hand.txt", "graph ")
+    assert len(rows) == 3
+    for row in rows:
+        head, masks, deps, lists, want = (part.strip() for part in row.split("|"))
+        D, K = (int(x) for x in head.split())
+        prob = {"name": "repair-hand", "D": D, "K": K, "NR": 1, "M": 99, "t": [1] * K, "m": [0] * K,
+                "dev_mask": [int(x) for x in masks.split()], "deps": [tuple(int(x) for x in e.split(">")) for e in deps.split()],
+                "space": "sampled_repair", "seed": 1, "lead_step_q16": 0, "fixed_leads": None}
+        orders = [[int(x) for x in part.split()] for part in lists.split(";")]
+        wanted = [[int(x) for x in part.split()] for part in want.split(";")]
+        orc = Oracle(prob)
+        assert orc.repair_explicit([0] * K, orders) == wanted, row
+        assert orc.eval_explicit([0] * K, wanted)["status"] == OK
+        assert orc.eval_explicit([0] * K, orders)["status"] == DEADLOCK
+
+
 def test_a_block_on_two_devices_with_two_leads_is_a_mismatch():
     """FACTORIAL space, one block type on both of two devices, windows of two micro-batches: each device orders
     the labelled blocks (0, 1); rank 0 = (0, 1) names lead 0, rank 1 = (1, 0) names lead 1.  Index = r_0 + 2 r_1:
