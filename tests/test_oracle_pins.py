@@ -362,11 +362,12 @@ def test_completion_of_1f1b_reaches_textbook_makespan(p, N):
     assert max(peaks) <= p
 
 
-def test_completion_is_valid_on_sampled_candidates():
-    prob = W.config3()
+@pytest.mark.parametrize("prob", [W.config3(), dict(W.config4(), M=12), W.kshape_problem(3, 5), W.diamond_problem(2, 4)],
+                         ids=["folded", "shared-block", "k-shape", "diamond"])
+def test_completion_is_valid_on_sampled_candidates(prob):
     orc = Oracle(prob)
     done = 0
-    for idx in range(200):
+    for idx in range(400):
         r = orc.eval_index(idx)
         if r["status"] != OK:
             continue
