@@ -285,7 +285,7 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         kp.nslots = D + kp.ntok * 2 * NR;
         kp.nsweeps = D + 1;                       // (only sizes the register arrays of the chain path, unused here)
         // state and program of a workgroup must fit the LDS a kernel may ask for
-        // (problems with more than kMaxD devices keep both in global memory)
+        // (problems too wide for the other paths keep both in global memory when they have to)
         if (!wide && (size_t)4 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)K * NR * kWave * 2 > 64 * 1024) { delete p; return TESSEL_E_UNSUPPORTED; }
     }
     int sumt = 0;

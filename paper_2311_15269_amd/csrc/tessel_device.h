@@ -64,7 +64,7 @@ enum Status { kOk = 0, kDup = 1, kTpMismatch = 2, kProp2 = 3, kDeadlock = 4, kMe
 // Everything a kernel needs to know about the problem (Table I of the paper: D, K, M,
 // t_B, m_B, d_B, dependencies) plus derived tables.  "local symbol" y = position of a block
 // type among the types of one device (ascending type id); a device order is a sequence of
-// 2-bit local symbols.
+// local symbols (2 bits each; 3 where a device holds more than four types).
 struct KParams {
     int32_t D, K, NR, M;
     int32_t total;               // K * NR blocks per window

@@ -1775,7 +1775,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
 }
 
 // ------------------------------------------------------------------ kernels
-// Problems with more than kMaxD devices or more than kMaxK block types (DM above kMaxD) are scored as dependency graphs,
+// Problems with more than kMaxD devices, kMaxK block types or kMaxLT types on a device (DM above kMaxD) are scored as dependency graphs,
 // with the per-lane state and program in global memory (`far`: one region of far_words(P) words per workgroup)
 // where 64 KB of LDS do not hold them: 32 devices with up to 63 rings of 16 end times each need 330 KB.
 __host__ __device__ inline size_t far_words(const KParams &P)
@@ -1988,7 +1988,7 @@ static fast_fn pick_fast(const KParams &kp)
     return V <= 16 ? eval_fast_kernel<8, 16, 0> : eval_fast_kernel<8, 24, 0>;
 }
 
-// state and program of the general kernel's lanes: in LDS, except for problems with more than kMaxD devices
+// state and program of the general kernel's lanes: in LDS, except for wide problems that 64 KB do not hold
 static bool far_state(const KParams &kp) { return wide_problem(kp) && (size_t)5 * kMaxKW * 4 + far_words(kp) * 4 > 64 * 1024; }
 static size_t far_bytes(const KParams &kp) { return far_state(kp) ? far_words(kp) * 4 : 0; }
 
@@ -2068,7 +2068,7 @@ size_t eval_workspace_bytes(const KParams &kp, int num_cus, int max_blocks)
     return ring_offset(s.blocks, num_cus) + (pick_fast(kp) ? (size_t)s.blocks * 3 * ring_words(kp) * 4 : (size_t)s.blocks * far_bytes(kp));
 }
 
-// where the state regions of the general kernel's workgroups start (problems with more than kMaxD devices)
+// where the state regions of the general kernel's workgroups start (wide problems whose state does not fit the LDS)
 static uint32_t *far_base(const KParams &kp, void *ws, int num_cus, int max_blocks)
 {
     if (!far_state(kp)) return nullptr;
