@@ -44,6 +44,13 @@ CASES = [
     ("cfg5-repair", W.config5(), 8, 3000, 1024, True),
     ("cfg5-repair-no-bound", W.config5(), 6, 1000, 0, False),
     ("xshape-two-chains", W.xshape_problem(4, 1, 2, 1, 4), 3, 4000, 1024, False),
+    # graphs with fan-in and fan-out, a pipeline on 12 devices, six block types per device
+    ("kshape-canonical", W.kshape_problem(1, 3, space="canonical"), 3, 1 << 30, 0, True),
+    ("diamond-repair", W.diamond_problem(1, 4), 4, 6000, 1024, True),
+    ("12-devices", W.pipeline_problem(W.linear_placement(12), [1 + (i % 2) for i in range(12)], [2] * 12, 12, 1, 3,
+                                      "sampled_repair", seed=5, lead_step_q16=20000), 3, 3000, 0, True),
+    ("six-types-a-device", W.pipeline_problem([0, 1, 0, 1, 0, 1], [1, 2, 1, 1, 2, 1], [2, 1, 2, 2, 1, 2], 2, 1, 9,
+                                              "sampled_repair", seed=6, lead_step_q16=30000), 4, 4000, 512, True),
 ]
 
 
