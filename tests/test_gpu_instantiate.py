@@ -48,3 +48,30 @@ def test_sequences_of_gpu_schedules(gpu, name, prob, budget, N, J, ncand):
         blocks = [op for op in got if op[0] == 0]
         assert sorted(op[1] for op in blocks) == list(range(prob["K"] * N))
         assert all(a[3] <= b[3] for a, b in zip(blocks, blocks[1:]))
+
+
+@pytest.mark.parametrize("name,prob,budget,N", [
+    ("k-shape", W.kshape_problem(2, 4), 1 << 14, 9),
+    ("diamond", W.diamond_problem(3, 5), 1 << 14, 10),
+    ("12-devices", W.pipeline_problem(W.linear_placement(12), [1 + (i % 3) for i in range(12)], [2 + (i % 2) for i in range(12)],
+                                      12, 2, 4, "sampled_repair", seed=9, lead_step_q16=20000), 1 << 13, 7),
+    ("six-types-a-device", W.pipeline_problem([0, 1, 2, 0, 1, 2, 0, 1, 2], [1] * 9, [2] * 9, 3, 2, 6, "sampled_repair", seed=3,
+                                              lead_step_q16=25000), 1 << 13, 8),
+])
+def test_sequences_of_greedy_schedules_on_graphs_and_wide_problems(gpu, name, prob, budget, N):
+    """the greedy completion and its operation sequence where the completion search does not go: branching graphs
+    (several send/receive pairs out of one block, several into one), more than 8 devices, six block types a device"""
+    from oracle import Oracle
+    g = gpu.Problem(prob)
+    g.eval_candidates(0, budget)
+    assert g.best()["feasible"]
+    o = Oracle(prob)
+    sched = g.complete_schedule(N)
+    ok, makespan, peaks = SC.check_flat_schedule(prob, N, sched["start"].tolist(), sched["dev_order"])
+    assert ok and makespan == sched["makespan"] and max(peaks) <= prob["M"]
+    got = g.instantiate(N, sched["start"])
+    assert got == o.instantiate(N, sched["start"], sched["dev_order"])
+    ok, why = SC.check_instantiation(prob, N, sched["start"].tolist(), got)
+    assert ok, why
+    blocks = [op for op in got if op[0] == 0]
+    assert sorted(op[1] for op in blocks) == list(range(prob["K"] * N))
