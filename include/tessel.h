@@ -35,7 +35,8 @@ extern "C" {
 #define TESSEL_MAX_TYPES_PER_DEV  8    /* block types that occupy one device (more than 4:
                                           sampled spaces only; as for more than 8 devices);
                                           at most 32 blocks per device and window             */
-#define TESSEL_MAX_NR             8    /* micro-batches per repetend window, N_R            */
+#define TESSEL_MAX_NR             16   /* micro-batches per repetend window, N_R (more than 8:
+                                          sampled spaces only; as for more than 8 devices)    */
 #define TESSEL_MAX_TYPES          64   /* K (more than 32: as for more than 8 devices)      */
 #define TESSEL_NUM_STATUS         6
 
@@ -100,7 +101,7 @@ typedef struct {
     const int32_t  *mem;        /* [K] m_B, negative = releases memory                          */
     const uint32_t *dev_mask;   /* [K] bit d set <=> the block occupies device d (d_B)          */
     int32_t  num_deps;          /* dependencies inside one micro-batch, B_src -> B_dst: any acyclic graph;
-                                   disjoint chains score fastest, other graphs (at most 64 dependencies)
+                                   disjoint chains score fastest, other graphs (at most 128 dependencies)
                                    on a slower general path                                       */
     const int32_t  *dep_src;    /* [num_deps]                                                   */
     const int32_t  *dep_dst;    /* [num_deps]                                                   */

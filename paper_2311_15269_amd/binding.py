@@ -60,7 +60,7 @@ def library_path():
     return _build.LIB
 
 
-MAX_NR = 8
+MAX_NR = 16
 
 
 class Search(C.Structure):

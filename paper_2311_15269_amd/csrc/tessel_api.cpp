@@ -191,7 +191,7 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         if (net != 0) return TESSEL_E_UNBALANCED_MEMORY;
     }
     // limits of the kernels
-    if (K > kMaxKW || NR > kMaxNR) return TESSEL_E_UNSUPPORTED;
+    if (K > kMaxKW || NR > kMaxNRW) return TESSEL_E_UNSUPPORTED;
     std::vector<int> indeg(K, 0), outdeg(K, 0);
     for (int e = 0; e < desc->num_deps; e++) { outdeg[desc->dep_src[e]]++; indeg[desc->dep_dst[e]]++; }
     // disjoint chains take the fast kernel and the chain path of the general one; any other graph (Sec. III-A allows
@@ -210,8 +210,10 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         if (n > kMaxLTW || n * NR > kMaxPos) return TESSEL_E_UNSUPPORTED;
         if (n > kMaxLT) many = true;
     }
-    if (many && desc->space != TESSEL_SPACE_SAMPLED_STRICT && desc->space != TESSEL_SPACE_SAMPLED_REPAIR) return TESSEL_E_UNSUPPORTED;
-    const bool wide = D > kMaxD || K > kMaxK || many;
+    // ... and one with a window of more than kMaxNR micro-batches (8-bit instead of 4-bit counters; sampled spaces only)
+    const bool longwin = NR > kMaxNR;
+    if ((many || longwin) && desc->space != TESSEL_SPACE_SAMPLED_STRICT && desc->space != TESSEL_SPACE_SAMPLED_REPAIR) return TESSEL_E_UNSUPPORTED;
+    const bool wide = D > kMaxD || K > kMaxK || many || longwin;
     if (wide) chains = false;
     if (!chains && desc->num_deps > kMaxDeps) return TESSEL_E_UNSUPPORTED;
 

@@ -49,7 +49,8 @@ constexpr int kMaxD = 8;         // simulated devices of the problems the fast k
 constexpr int kMaxDW = 32;       // ... of any problem: more than kMaxD go the general kernel's path for graphs
 constexpr int kMaxLT = 4;        // block types per device of the problems the fast kernel and the chain path take
 constexpr int kMaxLTW = 8;       // ... of any problem (sampled spaces): more than kMaxLT go the general kernel's path for graphs
-constexpr int kMaxNR = 8;        // micro-batches per window
+constexpr int kMaxNR = 8;        // micro-batches per window of the problems the fast kernel, the chain path and the exhaustive spaces take
+constexpr int kMaxNRW = 16;      // ... of any problem (sampled spaces): more than kMaxNR go the general kernel's path for graphs
 constexpr int kMaxK = 32;        // block types of the problems the fast kernel and the chain path of the general one take
 constexpr int kMaxKW = 64;       // ... of any problem: more than kMaxK go the general kernel's path for graphs
 constexpr int kMaxPos = kMaxLT * kMaxNR;   // blocks per device and window (32)

@@ -67,27 +67,33 @@ struct Mu {
     }
 };
 
-// the same for up to 64 block types (problems that only the general kernel's path for graphs takes)
+// the same for up to 64 block types and windows of up to 16 micro-batches, 8 bits each (problems that only the general
+// kernel's path for graphs takes)
 struct MuWide {
-    uint64_t w[4];
-    __device__ __forceinline__ void clear() { w[0] = w[1] = w[2] = w[3] = 0; }
+    uint64_t w[8];
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int k = 0; k < 8; k++) w[k] = 0;
+    }
     __device__ __forceinline__ uint64_t word(uint32_t g) const
     {
-        const uint64_t a = g & 16u ? w[1] : w[0], b = g & 16u ? w[3] : w[2];
-        return g & 32u ? b : a;
+        const uint64_t a = g & 8u ? w[1] : w[0], b = g & 8u ? w[3] : w[2], c = g & 8u ? w[5] : w[4], d = g & 8u ? w[7] : w[6];
+        const uint64_t lo = g & 16u ? b : a, hi = g & 16u ? d : c;
+        return g & 32u ? hi : lo;
     }
-    __device__ __forceinline__ uint32_t get(uint32_t g) const { return (uint32_t)(word(g) >> ((g & 15u) * 4u)) & 15u; }
+    __device__ __forceinline__ uint32_t get(uint32_t g) const { return (uint32_t)(word(g) >> ((g & 7u) * 8u)) & 255u; }
     __device__ __forceinline__ void add(uint32_t g, uint64_t x)
     {
 #pragma unroll
-        for (int k = 0; k < 4; k++) w[k] += (g >> 4) == (uint32_t)k ? x : 0ull;
+        for (int k = 0; k < 8; k++) w[k] += (g >> 3) == (uint32_t)k ? x : 0ull;
     }
     __device__ __forceinline__ void set(uint32_t g, uint32_t v)
     {
-        const uint32_t sh = (g & 15u) * 4u;
-        add(g, ((uint64_t)v << sh) - (word(g) & (15ull << sh)));
+        const uint32_t sh = (g & 7u) * 8u;
+        add(g, ((uint64_t)v << sh) - (word(g) & (255ull << sh)));
     }
-    __device__ __forceinline__ void inc(uint32_t g) { add(g, 1ull << ((g & 15u) * 4u)); }
+    __device__ __forceinline__ void inc(uint32_t g) { add(g, 1ull << ((g & 7u) * 8u)); }
     static constexpr int kTypeBits = 6;          // of a program entry
 };
 
@@ -674,7 +680,7 @@ __device__ __forceinline__ int least_period_dag(const KParams &P, const DagTable
         reset();
         bool decided = !open, feasible = false;
         // (crossing + 2 windows bound the iteration; the loop runs until every lane of the wave has decided)
-        for (int w = 0; w < kMaxKW * kMaxNR + kMaxDW + 2; w++) {
+        for (int w = 0; w < kMaxKW * kMaxNRW + kMaxDW + 2; w++) {
             if (__ballot(!decided) == 0) break;
             sweep_window_dag<CNT::kTypeBits>(P, Tb, prog, state);
             uint32_t zero = 0, top;
@@ -1946,7 +1952,7 @@ typedef void (*fast_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t
                         uint32_t, uint32_t *, uint32_t *, uint32_t, int);
 
 // problems too wide for the fast kernel and the chain path (their state stays in LDS where 64 KB hold it)
-static bool wide_problem(const KParams &kp) { return kp.D > kMaxD || kp.K > kMaxK || kp.many; }
+static bool wide_problem(const KParams &kp) { return kp.D > kMaxD || kp.K > kMaxK || kp.many || kp.NR > kMaxNR; }
 
 static eval_fn pick_kernel(const KParams &kp)
 {

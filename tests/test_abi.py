@@ -44,6 +44,9 @@ def test_problem_create_validates_on_the_host():
     # up to eight block types on a device in the sampled spaces, four in the exhaustive ones
     crowded = W.pipeline_problem([0, 1, 0, 1, 0, 1], [1] * 6, [2] * 6, 2, 2, 9, "sampled_repair")
     assert binding.Problem(crowded).candidate_count() == 2 ** 64 - 1
+    # windows of up to 16 micro-batches in the sampled spaces, 8 in the exhaustive ones
+    assert binding.Problem(dict(W.config1(), NR=16, M=16, space="sampled_repair")).workspace_bytes() > 0
+    assert binding.Problem(dict(wide, NR=16)).workspace_bytes() > 0
     for bad, code in (
         (dict(crowded, space="canonical"), -9),
         (dict(crowded, NR=6), -9),                             # 36 blocks on a device
@@ -52,7 +55,9 @@ def test_problem_create_validates_on_the_host():
         (dict(W.config1(), m=[1, 1, -1, 0]), -3),
         (dict(W.config1(), deps=[(0, 1), (1, 0)]), -2),
         (dict(W.config1(), t=[0, 1, 2, 2]), -1),
-        (dict(W.config1(), NR=9), -9),
+        (dict(W.config1(), NR=9), -9),                                  # windows of more than 8 micro-batches: sampled spaces only
+        (dict(W.config1(), NR=17, space="sampled_repair"), -9),
+        (dict(W.config3(), NR=9), -9),                                  # 4 types a device: at most 32 blocks per device and window
         (dict(W.config1(), fixed_leads=[0, 0, 0, 0]), -1),
         (W.pipeline_problem(W.folded_placement(8), [1] * 16, [1] * 16, 8, 8, 10, "canonical"), -4),
     ):
@@ -85,7 +90,7 @@ def test_search_validates_its_arguments_on_the_host():
     io = binding.Search(max_nr=0)
     assert lib.tessel_search_workspace_bytes(C.byref(desc), C.byref(io), C.byref(n)) == -1
     assert lib.tessel_search_run(C.byref(desc), C.byref(io), None, 0, None, None) == -1
-    io = binding.Search(max_nr=9)
+    io = binding.Search(max_nr=17)
     assert lib.tessel_search_run(C.byref(desc), C.byref(io), None, 0, None, None) == -1
     # window sizes beyond the in-flight bound are never created: the 4-stage canonical space has no table for N_R = 8
     desc, keep = binding._describe(W.config2())

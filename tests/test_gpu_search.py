@@ -51,6 +51,11 @@ CASES = [
                                       "sampled_repair", seed=5, lead_step_q16=20000), 3, 3000, 0, True),
     ("six-types-a-device", W.pipeline_problem([0, 1, 0, 1, 0, 1], [1, 2, 1, 1, 2, 1], [2, 1, 2, 2, 1, 2], 2, 1, 9,
                                               "sampled_repair", seed=6, lead_step_q16=30000), 4, 4000, 512, True),
+    # window sizes beyond 8 (sampled spaces)
+    ("10-devices-to-nr-11", W.pipeline_problem(list(range(10)), [1] * 10, [2] * 10, 10, 1, 14, "sampled_repair", seed=9,
+                                               lead_step_q16=20000), 11, 150, 0, False),
+    ("4-devices-cap-1-to-nr-12", W.pipeline_problem(list(range(4)), [1] * 4, [2] * 4, 4, 1, 1, "sampled_repair", seed=9,
+                                                    lead_step_q16=20000), 12, 150, 64, False),
 ]
 
 

@@ -1,7 +1,8 @@
 """Problems with more than 8 devices, more than 32 block types or more than 4 block types on a device (Table I puts no
 bound on them; the boundary takes up to 32, 64 and 8): scored by the general kernel's path for graphs with the lanes' state in global memory.  HIP path against the oracle element by element:
 V-shape pipelines on 12 and 16 devices, a forward-only pipeline on 32, a block on ten devices at once, the two
-exhaustive spaces, seeded random graphs on up to 24 devices; best candidate, its start times and its completion."""
+exhaustive spaces, seeded random graphs on up to 24 devices, windows of 9 to 16 micro-batches; best candidate, its start
+times and its completion."""
 import numpy as np
 import pytest
 
@@ -97,6 +98,16 @@ SHAPES = [
     ("vshape-9-strict", vshape(9, 1, 3, space="sampled_strict"), 0, 6000),
     ("vshape-9-canonical", vshape(9, 1, 3, space="canonical"), 0, 1 << 20),
     ("vshape-9-factorial", vshape(9, 1, 3, space="factorial"), 0, 1 << 20),
+    # windows of 9 to 16 micro-batches
+    ("nr12-on-4-devices", vshape(4, 12, 13, seed=0xE0FFEE4), 21, 2500),
+    ("nr9-on-2-devices-strict", vshape(2, 9, 12, space="sampled_strict", seed=0xE0FFEE5, step=6000), 0, 6000),
+    ("nr16-on-2-devices", vshape(2, 16, 12, seed=0xE0FFEE5, step=6000), 0, 4000),
+    ("nr10-three-types-a-device", {"name": "nr10-three-types", "D": 2, "K": 6, "NR": 10, "M": 0, "t": [2, 3, 1, 4, 2, 1], "m": [0] * 6,
+                                   "dev_mask": [1, 2, 1, 2, 1, 2], "deps": [(i, i + 1) for i in range(5)], "space": "sampled_repair",
+                                   "seed": 0xE0FFEE6, "lead_step_q16": 25000, "fixed_leads": None}, 3, 2500),
+    ("kshape-nr10", W.kshape_problem(10, 12), 1 << 33, 2500),
+    ("vshape-16-nr16", vshape(16, 16, 24, seed=0xE0FFEE7), 9, 300),
+    ("inference-32-nr16", inference(32, 16), 2, 300),
 ]
 
 
