@@ -221,7 +221,7 @@ int  tessel_complete_schedule(tessel_problem *p, tessel_schedule *out);
 /* ---- searched completion (Sec. IV-C; the paper orders warm-up and cool-down with a time-optimal solver) ---
  * Completion candidate `ordinal` is a perturbed greedy list schedule of the two outer phases around the R
  * copies of the best window: per phase every block type offers its lowest unscheduled micro-batch
- * (Property 1); an offered block is eligible when its producer's block of the same micro-batch is scheduled
+ * (Property 1); an offered block is eligible when its producers' blocks of the same micro-batch are scheduled
  * and its memory delta fits on all its devices; the eligible block with the smallest (earliest start +
  * jitter, micro-batch, type id) is appended at its earliest start.  jitter(type, mu) = (draw * (J + 1)) >> 16
  * with the 16-bit draw number type*N + mu of the counter-based stream keyed by (seed + 0x632BE59BD9B4E019,
@@ -234,7 +234,8 @@ int  tessel_complete_schedule(tessel_problem *p, tessel_schedule *out);
  * last tessel_eval_candidates call, in the workspace bound there.  A new best window, N or J restarts the
  * running best.  Errors: NO_FEASIBLE, RANGE (fewer than one window fits), INVALID_ARG,
  * TOOBIG (state of N micro-batches does not fit the LDS, N * sum of t exceeds 16 bits, N > 1023 or J > 63),
- * UNSUPPORTED (|m| > 127; a dependency graph that is not a set of chains; more than 8 devices), HIP. */
+ * UNSUPPORTED (|m| > 127; more than 8 devices, 32 block types, 4 types on a device or 8 micro-batches per
+ * window), HIP. */
 int  tessel_search_completions(tessel_problem *p, int32_t num_microbatches, int32_t jitter, uint64_t first,
                                uint64_t count);
 /* makespan_dev[k] (device, int32) = makespan of completion candidate first+k, INT32_MAX where the greedy rule

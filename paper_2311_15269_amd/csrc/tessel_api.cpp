@@ -863,7 +863,7 @@ extern "C" int tessel_complete_schedule(tessel_problem *p, tessel_schedule *out)
 static void window_matrix(const CompParams &cp, CompMatrix &cm)
 {
     memset(&cm, 0, sizeof cm);
-    bool single = cp.npaths <= 8;
+    bool single = cp.npaths <= 8 && !cp.dag;
     for (int i = 0; i < cp.K; i++) single = single && cp.mask[i] != 0 && (cp.mask[i] & (cp.mask[i] - 1)) == 0;
     if (!single) return;
     const int TR = cp.tok_ring, tmask = TR - 1, oFree = cp.npaths * TR, nslot = oFree + cp.D;      // rings first, then the devices
@@ -911,7 +911,9 @@ static void window_matrix(const CompParams &cp, CompMatrix &cm)
 static int bind_completion(tessel_problem *p, int N, int J)
 {
     if (p->ws && p->ws_ready && !owns_workspace(p)) return TESSEL_E_WORKSPACE;      // the buffer is another handle's by now
-    if (p->kp.dag) return TESSEL_E_UNSUPPORTED;          // the completion search follows chains (the greedy completion does not)
+    // (problems beyond the limits of the fast kernel keep their types, devices and micro-batches in more bits than the
+    // completion kernel's tables hold; their greedy completion needs no kernel)
+    if (p->kp.D > kMaxD || p->kp.K > kMaxK || p->kp.many || p->kp.NR > kMaxNR) return TESSEL_E_UNSUPPORTED;
     if (p->comp_ready && !p->best_dirty && p->comp_index == p->result.index && p->result.period != INT_MAX && p->comp.N == N &&
         p->comp.J == J)
         return TESSEL_OK;                                   // nothing new since the best was fetched: no wait
@@ -931,11 +933,21 @@ static int bind_completion(tessel_problem *p, int N, int J)
     cp.D = D; cp.K = K; cp.NR = NR; cp.M = p->kp.M; cp.N = N; cp.J = J; cp.R = R; cp.nseq = K * NR;
     { const uint64_t seed = p->kp.seed + kCompletionKey; cp.seed_lo = (uint32_t)seed; cp.seed_hi = (uint32_t)(seed >> 32); }
     int npaths = 0;
+    std::vector<std::vector<int>> producers(K);
+    for (size_t e = 0; e < p->dep_src.size(); e++) producers[p->dep_dst[e]].push_back(p->dep_src[e]);
     for (int i = 0; i < K; i++) {
         if (p->m[i] < -128 || p->m[i] > 127) return TESSEL_E_UNSUPPORTED;
-        cp.t[i] = p->t[i]; cp.m[i] = (int8_t)p->m[i]; cp.mask[i] = (uint8_t)p->mask[i]; cp.pred[i] = p->kp.pred[i];
+        cp.t[i] = p->t[i]; cp.m[i] = (int8_t)p->m[i]; cp.mask[i] = (uint8_t)p->mask[i];
+        cp.pred[i] = p->kp.dag ? (int8_t)-1 : p->kp.pred[i];
         cp.lead[i] = (uint8_t)c.leads[i];
     }
+    if (p->kp.dag) {
+        // any acyclic graph: every type somebody consumes keeps the end times of its own blocks
+        cp.dag = 1;
+        std::vector<char> consumed(K, 0);
+        for (size_t e = 0; e < p->dep_src.size(); e++) { consumed[p->dep_src[e]] = 1; cp.predmask[p->dep_dst[e]] |= 1u << p->dep_src[e]; }
+        for (int i = 0; i < K; i++) cp.path[i] = consumed[i] ? (uint8_t)npaths++ : (uint8_t)0xFF;
+    } else
     for (int i = 0; i < K; i++) if (p->kp.pred[i] < 0) {                 // chains numbered by their first type
         for (int g = i; g >= 0; g = p->kp.succ[g]) cp.path[g] = (uint8_t)npaths;
         npaths++;
@@ -963,9 +975,10 @@ static int bind_completion(tessel_problem *p, int N, int J)
                 bool heads = true;
                 for (int dd = 0; dd < D; dd++)
                     if ((p->mask[i] >> dd & 1u) && (pos[dd] >= c.order_len[dd] || c.orders[dd][pos[dd]] != i)) heads = false;
-                const int a = p->kp.pred[i];
-                // its producer's block of the same micro-batch must come first: in this window, or it ran in an earlier one
-                if (!heads || (a >= 0 && c.leads[a] + occ[a] <= c.leads[i] + occ[i])) continue;
+                // its producers' blocks of the same micro-batch must come first: in this window, or they ran in an earlier one
+                bool fed = true;
+                for (int a : producers[i]) if (c.leads[a] + occ[a] <= c.leads[i] + occ[i]) fed = false;
+                if (!heads || !fed) continue;
                 cp.seq[n] = (uint8_t)i; cp.occ[n] = (uint8_t)occ[i]; n++;
                 occ[i]++;
                 for (int dd = 0; dd < D; dd++) if (p->mask[i] >> dd & 1u) pos[dd]++;

@@ -170,15 +170,18 @@ struct DevDetail {
 constexpr int kMaxSeq = kMaxK * kMaxNR;
 struct CompParams {
     int32_t  D, K, NR, M, N, J, R, nseq, npaths;
-    int32_t  tok_ring;               // slots per chain for the end times of the micro-batches in flight: a power of two
-                                     // above (largest - smallest lead) + NR, the most two types of a chain are ever apart
+    int32_t  tok_ring;               // slots per chain (graphs: per consumed type; npaths counts them) for the end times of the
+                                     // micro-batches in flight: a power of two above (largest - smallest lead) + NR, the most
+                                     // two types are ever apart
     uint32_t seed_lo, seed_hi;       // problem seed + kCompletionKey (two words: the kernel's copy of this block in LDS
                                      // is written word by word, and nothing in it is read through a wider type)
     int32_t  t[kMaxK];
     int8_t   m[kMaxK];
     uint8_t  mask[kMaxK];
-    int8_t   pred[kMaxK];            // producer type or -1
-    uint8_t  path[kMaxK];            // dependency chain of the type
+    int8_t   pred[kMaxK];            // producer type or -1 (chains)
+    uint8_t  path[kMaxK];            // dependency chain of the type; graphs: the type's own ring, 0xFF = nobody consumes it
+    int32_t  dag;                    // the micro-batch graph is not a set of chains: producers by mask, one ring per consumed type
+    uint32_t predmask[kMaxK];        // graphs: bit a = type a is a producer
     uint8_t  lead[kMaxK];
     uint8_t  seq[kMaxSeq];           // the window's blocks (types) in an executable order
     uint8_t  occ[kMaxSeq];           // occurrence number of seq[s] among the earlier entries of its type

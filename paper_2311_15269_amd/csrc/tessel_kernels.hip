@@ -2258,7 +2258,7 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
     // are recomputed (`redo`); of the other types on its device (`aff`) a key that exists only moves to the device's new
     // free time and is checked against its new memory.  Tables, per type: `ptab` lead (8 bits), memory delta (8,
     // signed), producer + 1 (6), device (3), chain (3), 1 (a type of the problem) in one word.
-    bool single_dev = cp.npaths <= 8;
+    bool single_dev = cp.npaths <= 8 && !cp.dag;
     for (int i = 0; i < K; i++) single_dev = single_dev && (cp.mask[i] & (cp.mask[i] - 1)) == 0 && cp.mask[i] != 0;
     uint32_t *ptab = lds + kCompParamWords - 3 * kMaxK, *aff = lds + kCompParamWords - 2 * kMaxK, *redo = lds + kCompParamWords - kMaxK;
     if (lane < kMaxK) {
@@ -2463,7 +2463,14 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                     const uint32_t mask = cp.mask[i];
                     bool ok = offered;
                     int est = 0;
-                    if (a >= 0) {
+                    if (cp.dag) {
+                        // every producer has handled the micro-batch; the latest of their end times
+                        for (uint32_t rest = cp.predmask[i]; rest; rest &= rest - 1u) {
+                            const int pa = __builtin_ctz(rest);
+                            ok = ok && ((int)TESSEL_ST(oNext + pa) & 1023) > mu;
+                            est = max(est, (int)TESSEL_ST(oTok + (int)cp.path[pa] * TR + (mu & tmask)));
+                        }
+                    } else if (a >= 0) {
                         ok = ok && ((int)TESSEL_ST(oNext + a) & 1023) > mu;
                         est = (int)TESSEL_ST(oTok + (int)cp.path[i] * TR + (mu & tmask));
                     }
@@ -2485,7 +2492,7 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                     const uint32_t mask = cp.mask[bi];
                     for (int d = 0; d < D; d++)
                         if (mask >> d & 1u) { TESSEL_ST(oFree + d) = (uint16_t)en; TESSEL_ST(oMem + d) = (uint16_t)((int)(int16_t)TESSEL_ST(oMem + d) + mi); }
-                    TESSEL_ST(oTok + (int)cp.path[bi] * TR + (bmu & tmask)) = (uint16_t)en;
+                    TESSEL_ST(cp.path[bi] != 0xFF ? oTok + (int)cp.path[bi] * TR + (bmu & tmask) : oTrash) = (uint16_t)en;
                     TESSEL_ST(oNext + bi) = (uint16_t)((uint32_t)(bmu + 1) | (bmu + 1 < hi ? jitter(bi, bmu + 1) : 0u) << 10);
                     left--;
                 }
@@ -2527,8 +2534,12 @@ __global__ __launch_bounds__(kWave) void complete_kernel(const CompParams *__res
                 for (int s = 0; s < cp.nseq; s++) {
                     const int i = cp.seq[s], mu = (int)cp.lead[i] + (int)cp.occ[s] + NR * k;
                     const uint32_t mask = cp.mask[i];
-                    const int tok = oTok + (int)cp.path[i] * TR + (mu & tmask);
-                    int est = cp.pred[i] >= 0 ? (int)TESSEL_ST(tok) : 0;
+                    const int tok = cp.path[i] != 0xFF ? oTok + (int)cp.path[i] * TR + (mu & tmask) : oTrash;
+                    int est = 0;
+                    if (cp.dag)
+                        for (uint32_t rest = cp.predmask[i]; rest; rest &= rest - 1u)
+                            est = max(est, (int)TESSEL_ST(oTok + (int)cp.path[__builtin_ctz(rest)] * TR + (mu & tmask)));
+                    else if (cp.pred[i] >= 0) est = (int)TESSEL_ST(tok);
                     for (uint32_t rest = mask; rest; rest &= rest - 1u) est = max(est, (int)TESSEL_ST(oFree + __builtin_ctz(rest)));
                     const int en = est + cp.t[i];
                     for (uint32_t rest = mask; rest; rest &= rest - 1u) {

@@ -30,6 +30,11 @@ CASES = [
     ("cfg5", W.config5(), 2048, 24, 4, 600),
     ("cfg5-64", W.config5(), 2048, 64, 2, 200),
     ("lin3", W.pipeline_problem(W.linear_placement(3), [1, 2, 1], [2, 3, 1], 3, 3, 3, "canonical"), 1 << 30, 10, 5, 333),
+    # micro-batch graphs with fan-in and fan-out (Sec. III-A, Eq. 1 [3]): two encoders into a joint stage, a diamond
+    ("kshape", W.kshape_problem(2, 4), 4000, 12, 3, 700),
+    ("kshape-nr4", W.kshape_problem(4, 5), 4000, 21, 6, 500),
+    ("diamond", W.diamond_problem(3, 5), 4000, 12, 3, 700),
+    ("diamond-tight", W.diamond_problem(2, 3), 4000, 17, 8, 500),
 ]
 
 
@@ -83,6 +88,41 @@ def test_the_windows_block_by_block_equal_their_matrix(gpu, monkeypatch):
         monkeypatch.delenv("TESSEL_REPLAY_BLOCKS")
         want, _, _ = o.completion_scores(leads, orders, N, 3, ncand, J)
         assert np.array_equal(scores[0], want) and np.array_equal(scores[1], want), prob["name"]
+
+
+@pytest.mark.parametrize("seed", [51, 52, 53])
+def test_completion_candidates_on_random_graphs(gpu, seed):
+    """seeded random micro-batch graphs on 2-5 devices: every completion candidate's makespan, the best and its schedule"""
+    from oracle import Oracle
+    from tests.test_gpu_dag import random_graph_problem
+    rng = np.random.default_rng(seed)
+    ran = 0
+    for case in range(10):
+        prob = dict(random_graph_problem(rng), space="sampled_repair")
+        prob["M"] = max(prob["M"], prob["NR"])
+        g, o = gpu.Problem(prob), Oracle(prob)
+        g.eval_candidates(int(rng.integers(0, 1 << 30)), 4096)
+        best = g.best()
+        if not best["feasible"]:
+            continue
+        status, leads, orders = o.decode(best["index"])
+        N = int(rng.integers(prob["NR"] + max(leads), 50))
+        J, first, ncand = int(rng.integers(1, 9)), int(rng.integers(0, 40)), int(rng.integers(100, 400))
+        want, want_best, want_ord = o.completion_scores(leads, orders, N, first, ncand, J)
+        got = g.score_completions(N, J, first, ncand).cpu().numpy()
+        assert np.array_equal(got, want), (seed, case, prob)
+        g.search_completions(N, J, first, ncand)
+        if want_best is None:
+            with pytest.raises(gpu.TesselError) as e:
+                g.best_completion(N)
+            assert e.value.code == -10
+            continue
+        sched = g.best_completion(N)
+        assert (sched["makespan"], sched["ordinal"]) == (want_best, want_ord), (seed, case)
+        ok, makespan, peaks = SC.check_flat_schedule(prob, N, sched["start"].tolist(), sched["dev_order"])
+        assert ok and makespan == sched["makespan"] and max(peaks) <= prob["M"]
+        ran += 1
+    assert ran >= 5
 
 
 def test_completion_argument_checks(gpu):
