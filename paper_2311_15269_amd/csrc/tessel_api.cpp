@@ -251,11 +251,38 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
             kp.dsrc[e] = (uint8_t)a; kp.ddst[e] = (uint8_t)b; kp.dcross[e] = desc->dev_mask[a] != desc->dev_mask[b];
             kp.predmask[b] |= 1ull << a;
         }
-        // every type somebody consumes keeps the end times of its blocks by micro-batch: 2 N_R slots behind the devices
-        for (int i = 0; i < K; i++) if (outdeg[i] > 0) {
-            const int base = D + kp.ntok * 2 * NR;
-            kp.tokbase[i] = (uint16_t)base;
-            kp.ntok++;
+        // End times by micro-batch, 2 N_R slots per ring behind the devices (and N_R more: what the last window boundary
+        // left in the ring's lower half, for the comparison at the next one).  A stretch of the graph without branches
+        // (a -> b with a's only consumer b and b's only producer a) shares one ring: b reads a's end time of a
+        // micro-batch and puts its own in its place, which only b's consumers read.  A chain is one ring.
+        {
+            std::vector<int> head(K), next_in(K, -1);
+            for (int i = 0; i < K; i++) head[i] = i;
+            for (int e = 0; e < desc->num_deps; e++) {
+                const int a = desc->dep_src[e], b = desc->dep_dst[e];
+                bool twice = false;                          // (a dependency listed twice counts once)
+                for (int f = 0; f < e; f++) if (desc->dep_src[f] == a && desc->dep_dst[f] == b) twice = true;
+                int outs = 0, ins = 0;
+                for (int f = 0; f < desc->num_deps; f++) {
+                    bool seen = false;
+                    for (int h = 0; h < f; h++) if (desc->dep_src[h] == desc->dep_src[f] && desc->dep_dst[h] == desc->dep_dst[f]) seen = true;
+                    if (seen) continue;
+                    outs += desc->dep_src[f] == a; ins += desc->dep_dst[f] == b;
+                }
+                if (!twice && outs == 1 && ins == 1) next_in[a] = b;
+            }
+            std::vector<char> inner(K, 0);
+            for (int i = 0; i < K; i++) if (next_in[i] >= 0) inner[next_in[i]] = 1;
+            for (int i = 0; i < K; i++) {
+                if (inner[i]) continue;                       // i starts a stretch
+                bool consumed = false;
+                for (int g = i; g >= 0; g = next_in[g]) consumed = consumed || outdeg[g] > 0;
+                if (!consumed) continue;
+                const int base = D + kp.ntok * 3 * NR;
+                kp.ring_head[kp.ntok] = (uint8_t)i;
+                for (int g = i; g >= 0; g = next_in[g]) if (outdeg[g] > 0) kp.tokbase[g] = (uint16_t)base;
+                kp.ntok++;
+            }
         }
         // consumers before producers
         std::vector<int> left(outdeg), done(K, 0);
@@ -284,7 +311,7 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         if (kp.nslots > 63 || kp.nsweeps - 1 > 24) { delete p; return TESSEL_E_UNSUPPORTED; }
     } else {
         kp.npaths = 0;
-        kp.nslots = D + kp.ntok * 2 * NR;
+        kp.nslots = D + kp.ntok * 3 * NR;
         kp.nsweeps = D + 1;                       // (only sizes the register arrays of the chain path, unused here)
         // state and program of a workgroup must fit the LDS a kernel may ask for
         // (problems too wide for the other paths keep both in global memory when they have to)

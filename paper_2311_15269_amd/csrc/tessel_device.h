@@ -127,11 +127,13 @@ struct KParams {
     int32_t  dag;                // the problem takes that path
     int32_t  ndeps;
     int32_t  dag_tries;          // sweeps of the eigenvector search before the bisection takes over (test knob)
-    int32_t  ntok;               // types somebody consumes: each has a ring of 2 N_R end times behind the D device slots
+    int32_t  ntok;               // rings of 2 N_R end times by micro-batch behind the D device slots: one per unbranched stretch
+                                 // of the graph (types joined by dependencies a -> b with a's only consumer b and b's only producer a)
     int32_t  t_type[kMaxKW];
     uint32_t mask_type[kMaxKW];  // devices of the type
     uint64_t predmask[kMaxKW];   // its producers
-    uint16_t tokbase[kMaxKW];    // first slot of its ring, kNoRing: nobody consumes it
+    uint16_t tokbase[kMaxKW];    // first slot of the ring the type writes its end times to, kNoRing: nobody consumes it
+    uint8_t  ring_head[kMaxKW];  // by ring: the first type of its stretch (the largest lead: Property 2)
     uint8_t  dsrc[kMaxDeps], ddst[kMaxDeps], dcross[kMaxDeps];   // the dependencies in the caller's order
     uint64_t predmask_of[kMaxDW][kMaxLTW]; // producers of local symbol y of device d
     int32_t  many;               // some device holds more than kMaxLT block types (3-bit symbols; sampled spaces only)

@@ -577,8 +577,9 @@ __device__ __forceinline__ int evaluate(const KParams &P, uint64_t idx, uint16_t
 
 // ------------------------------------------------------------------ dependency graphs that are not chains
 // A block type may have several producers and several consumers (Sec. III-A, Eq. 1 [3]).  State of a sweep, in LDS
-// [slot][lane]: the D device times, then for every type somebody consumes a ring of 2 N_R end times by micro-batch
-// (micro-batches N_R and up belong to the next window and move down at the window boundary).  Program entry: type id
+// [slot][lane]: the D device times, then for every unbranched stretch of the graph with a type somebody consumes a
+// ring of 2 N_R end times by micro-batch (micro-batches N_R and up belong to the next window and move down at the
+// window boundary) and N_R more slots for the boundary's comparison.  Program entry: type id
 // in bits 0-4 (0-5 for problems with more than 32 types), micro-batch above.  Tables by type id in LDS: t, device mask,
 // producer mask (two words where there are more than 32 types), first ring slot.
 struct DagTables {
@@ -605,8 +606,9 @@ __device__ __forceinline__ void sweep_window_dag(const KParams &P, const DagTabl
 // The window boundary: every ring moves down by N_R micro-batches and the device times stay, all less `shift` (0, or
 // the period under test: times are then taken from the start of the next window, not below 0).  Returns whether every
 // value that crosses the boundary and means anything grew by `want` over the window (`first`: by any one amount,
-// which is handed back in `want`): ring entries below the type's lead (handled before the window by the producer),
-// compared in place with what the last boundary left there; device times against `prevfree`.
+// which is handed back in `want`): ring entries below the lead of the ring's first type (micro-batches it handled
+// before the window), compared with the copy the last boundary kept of them behind the ring (later types of the
+// ring's stretch overwrite the entries themselves); device times against `prevfree`.
 template <int DM, class CNT>
 __device__ __forceinline__ bool boundary_dag(const KParams &P, const DagTables &Tb, uint32_t *state, const CNT &lead, uint32_t (&prevfree)[DM],
                                              uint32_t shift, bool first, uint32_t &want, uint32_t &top)
@@ -624,19 +626,20 @@ __device__ __forceinline__ bool boundary_dag(const KParams &P, const DagTables &
         prevfree[d] = y; state[d * kWave] = y;
         top = max(top, y);
     }
-    for (int g = 0; g < P.K; g++) {
-        const uint32_t base = Tb.tok[g];
-        if (base == kNoRing) continue;
-        const uint32_t lg = lead.get((uint32_t)g);
+    for (int r = 0; r < P.ntok; r++) {
+        const uint32_t base = (uint32_t)(P.D + r * 3 * P.NR), kept = base + 2u * (uint32_t)P.NR;
+        const uint32_t lg = lead.get((uint32_t)P.ring_head[r]);
         for (int m = 0; m < P.NR; m++) {
-            const uint32_t old = state[(base + m) * kWave], x = state[(base + m + P.NR) * kWave];
+            const uint32_t old = state[(kept + m) * kWave], x = state[(base + m + P.NR) * kWave];
             const uint32_t y = x > shift ? x - shift : 0u;
             if ((uint32_t)m < lg) {
                 const uint32_t dv = y - old;
                 if (!have) { want = dv; have = true; } else if (dv != want) same = false;
                 top = max(top, y);
             }
-            state[(base + m) * kWave] = (uint32_t)m < lg ? y : 0u;
+            const uint32_t keep = (uint32_t)m < lg ? y : 0u;
+            state[(base + m) * kWave] = keep;
+            state[(kept + m) * kWave] = keep;
             state[(base + m + P.NR) * kWave] = 0;
         }
     }
@@ -670,7 +673,7 @@ __device__ __forceinline__ int least_period_dag(const KParams &P, const DagTable
     if (__ballot(!done) == 0) return (int)T;
     // bisection, the same number of steps in every lane; lanes that have their period keep a fixed interval
     int crossing = P.D;
-    for (int g = 0; g < P.K; g++) if (Tb.tok[g] != kNoRing) crossing += (int)lead.get((uint32_t)g);
+    for (int r = 0; r < P.ntok; r++) crossing += (int)lead.get((uint32_t)P.ring_head[r]);
     uint32_t lo = done ? T : (uint32_t)P.LB, hi = done ? T : (uint32_t)P.UB;
     int steps = 0;
     for (uint32_t span = (uint32_t)(P.UB - P.LB); span; span >>= 1) steps++;
@@ -1781,9 +1784,10 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
 }
 
 // ------------------------------------------------------------------ kernels
-// Problems with more than kMaxD devices, kMaxK block types or kMaxLT types on a device (DM above kMaxD) are scored as dependency graphs,
-// with the per-lane state and program in global memory (`far`: one region of far_words(P) words per workgroup)
-// where 64 KB of LDS do not hold them: 32 devices with up to 63 rings of 16 end times each need 330 KB.
+// Problems with more than kMaxD devices, kMaxK block types, kMaxLT types on a device or kMaxNR micro-batches per window (DM above kMaxD)
+// are scored as dependency graphs, with the per-lane state and program in global memory (`far`: one region of
+// far_words(P) words per workgroup) where the LDS of a workgroup does not hold them: 24 devices with 40 rings of 24
+// slots and 384 program entries need 300 KB.
 __host__ __device__ inline size_t far_words(const KParams &P)
 {
     return (((size_t)P.nslots * kWave * 4 + (size_t)P.total * kWave * 2 + 255) & ~(size_t)255) / 4;
@@ -1995,7 +1999,23 @@ static fast_fn pick_fast(const KParams &kp)
 }
 
 // state and program of the general kernel's lanes: in LDS, except for wide problems that 64 KB do not hold
-static bool far_state(const KParams &kp) { return wide_problem(kp) && (size_t)5 * kMaxKW * 4 + far_words(kp) * 4 > 64 * 1024; }
+// (the LDS one workgroup may ask for: what the device reports, 64 KB where there is none to ask)
+static size_t lds_per_workgroup()
+{
+    static size_t cap = 0;
+    if (!cap) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess &&
+            v >= 64 * 1024)
+            cap = (size_t)v < (size_t)160 * 1024 ? (size_t)v : (size_t)160 * 1024;
+        else {
+            (void)hipGetLastError();
+            cap = 64 * 1024;
+        }
+    }
+    return cap;
+}
+static bool far_state(const KParams &kp) { return wide_problem(kp) && (size_t)5 * kMaxKW * 4 + far_words(kp) * 4 > lds_per_workgroup(); }
 static size_t far_bytes(const KParams &kp) { return far_state(kp) ? far_words(kp) * 4 : 0; }
 
 static size_t general_lds_bytes(const KParams &kp)

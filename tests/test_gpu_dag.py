@@ -131,13 +131,21 @@ def test_periods_by_bisection_alone(gpu, monkeypatch):
         monkeypatch.delenv("TESSEL_FORCE_DAG", raising=False)
 
 
-def test_graphs_are_refused_where_only_chains_work(gpu):
+def test_completions_of_graphs_and_where_the_search_ends(gpu):
     g = gpu.Problem(W.kshape_problem(4, 6))
     g.eval_candidates(0, 4096)
     assert g.best()["feasible"]
     sched = g.complete_schedule(12)                        # the greedy completion follows any graph
     ok, makespan, peaks = SC.check_flat_schedule(g.problem, 12, sched["start"].tolist(), sched["dev_order"])
     assert ok and makespan == sched["makespan"] and max(peaks) <= 6
+    # ... and so does the completion search, whose candidate 0 is the greedy schedule
+    assert int(g.score_completions(12, 2, 0, 64).cpu().numpy()[0]) == makespan
+    # problems beyond the fast kernel's limits (here: 12 devices) have the greedy completion only
+    wide = gpu.Problem(W.pipeline_problem(W.linear_placement(12), [1] * 12, [2] * 12, 12, 2, 4, "sampled_repair", seed=3,
+                                          lead_step_q16=20000))
+    wide.eval_candidates(0, 4096)
+    assert wide.best()["feasible"]
+    assert wide.complete_schedule(16)["makespan"] > 0
     with pytest.raises(gpu.TesselError) as err:
-        g.search_completions(12, 2, 0, 64)                 # the completion search does not
+        wide.search_completions(16, 2, 0, 64)
     assert err.value.code == -9
