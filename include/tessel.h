@@ -30,8 +30,8 @@ extern "C" {
 
 /* ---- limits of this implementation -------------------------------------------------- */
 #define TESSEL_MAX_DEVICES        32   /* simulated devices D (more than 8, or more than 32
-                                          block types: scored by the general kernel alone,
-                                          state in global memory; no searched completion)   */
+                                          block types: scored by the general kernel alone;
+                                          no searched completion)                            */
 #define TESSEL_MAX_TYPES_PER_DEV  8    /* block types that occupy one device (more than 4:
                                           sampled spaces only; as for more than 8 devices);
                                           at most 32 blocks per device and window             */

@@ -251,8 +251,8 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
             kp.dsrc[e] = (uint8_t)a; kp.ddst[e] = (uint8_t)b; kp.dcross[e] = desc->dev_mask[a] != desc->dev_mask[b];
             kp.predmask[b] |= 1ull << a;
         }
-        // End times by micro-batch, 2 N_R slots per ring behind the devices (and N_R more: what the last window boundary
-        // left in the ring's lower half, for the comparison at the next one).  A stretch of the graph without branches
+        // End times by micro-batch, 2 N_R slots per ring behind the devices (and for a shared ring N_R more: what the last
+        // window boundary left in the ring's lower half, for the comparison at the next one).  A stretch of the graph without branches
         // (a -> b with a's only consumer b and b's only producer a) shares one ring: b reads a's end time of a
         // micro-batch and puts its own in its place, which only b's consumers read.  A chain is one ring.
         {
@@ -272,17 +272,23 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
                 if (!twice && outs == 1 && ins == 1) next_in[a] = b;
             }
             std::vector<char> inner(K, 0);
+            int slots = 0;
             for (int i = 0; i < K; i++) if (next_in[i] >= 0) inner[next_in[i]] = 1;
             for (int i = 0; i < K; i++) {
                 if (inner[i]) continue;                       // i starts a stretch
                 bool consumed = false;
                 for (int g = i; g >= 0; g = next_in[g]) consumed = consumed || outdeg[g] > 0;
                 if (!consumed) continue;
-                const int base = D + kp.ntok * 3 * NR;
+                const int base = D + slots;
+                const bool shared = next_in[i] >= 0;
                 kp.ring_head[kp.ntok] = (uint8_t)i;
+                kp.ring_base[kp.ntok] = (uint16_t)base;
+                kp.ring_kept[kp.ntok] = (uint16_t)(shared ? base + 2 * NR : base);
                 for (int g = i; g >= 0; g = next_in[g]) if (outdeg[g] > 0) kp.tokbase[g] = (uint16_t)base;
                 kp.ntok++;
+                slots += (shared ? 3 : 2) * NR;
             }
+            kp.nslots = D + slots;
         }
         // consumers before producers
         std::vector<int> left(outdeg), done(K, 0);
@@ -311,7 +317,6 @@ extern "C" int tessel_problem_create(const tessel_problem_desc *desc, tessel_pro
         if (kp.nslots > 63 || kp.nsweeps - 1 > 24) { delete p; return TESSEL_E_UNSUPPORTED; }
     } else {
         kp.npaths = 0;
-        kp.nslots = D + kp.ntok * 3 * NR;
         kp.nsweeps = D + 1;                       // (only sizes the register arrays of the chain path, unused here)
         // state and program of a workgroup must fit the LDS a kernel may ask for
         // (problems too wide for the other paths keep both in global memory when they have to)

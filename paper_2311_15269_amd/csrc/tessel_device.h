@@ -134,6 +134,10 @@ struct KParams {
     uint64_t predmask[kMaxKW];   // its producers
     uint16_t tokbase[kMaxKW];    // first slot of the ring the type writes its end times to, kNoRing: nobody consumes it
     uint8_t  ring_head[kMaxKW];  // by ring: the first type of its stretch (the largest lead: Property 2)
+    uint16_t ring_base[kMaxKW];  // ... its first slot
+    uint16_t ring_kept[kMaxKW];  // ... first of the N_R slots that keep what the last window boundary left in its lower half: behind
+                                 // the ring for a stretch of several types (the later ones overwrite the entries), the ring's own
+                                 // lower half for a single type (which never writes below its lead)
     uint8_t  dsrc[kMaxDeps], ddst[kMaxDeps], dcross[kMaxDeps];   // the dependencies in the caller's order
     uint64_t predmask_of[kMaxDW][kMaxLTW]; // producers of local symbol y of device d
     int32_t  many;               // some device holds more than kMaxLT block types (3-bit symbols; sampled spaces only)

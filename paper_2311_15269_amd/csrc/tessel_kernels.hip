@@ -627,7 +627,7 @@ __device__ __forceinline__ bool boundary_dag(const KParams &P, const DagTables &
         top = max(top, y);
     }
     for (int r = 0; r < P.ntok; r++) {
-        const uint32_t base = (uint32_t)(P.D + r * 3 * P.NR), kept = base + 2u * (uint32_t)P.NR;
+        const uint32_t base = P.ring_base[r], kept = P.ring_kept[r];
         const uint32_t lg = lead.get((uint32_t)P.ring_head[r]);
         for (int m = 0; m < P.NR; m++) {
             const uint32_t old = state[(kept + m) * kWave], x = state[(base + m + P.NR) * kWave];
@@ -1788,9 +1788,11 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
 // are scored as dependency graphs, with the per-lane state and program in global memory (`far`: one region of
 // far_words(P) words per workgroup) where the LDS of a workgroup does not hold them: 24 devices with 40 rings of 24
 // slots and 384 program entries need 300 KB.
-__host__ __device__ inline size_t far_words(const KParams &P)
+// (`where`: 1 = only the program lives there, the state stays in LDS; 2 = both)
+__host__ __device__ inline size_t far_words(const KParams &P, int where)
 {
-    return (((size_t)P.nslots * kWave * 4 + (size_t)P.total * kWave * 2 + 255) & ~(size_t)255) / 4;
+    const size_t state = where == 2 ? (size_t)P.nslots * kWave * 4 : 0, prog = where ? (size_t)P.total * kWave * 2 : 0;
+    return ((state + prog + 255) & ~(size_t)255) / 4;
 }
 
 template <int DM, int VM>
@@ -1798,7 +1800,7 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
                                                      BlockRec *__restrict__ recs, int32_t *__restrict__ code_out,
                                                      int32_t *__restrict__ peak_out, DevDetail *__restrict__ detail,
                                                      const uint64_t *__restrict__ list, const uint32_t *__restrict__ list_count,
-                                                     uint32_t *far)
+                                                     uint32_t *far, int where)
 {
     const KParams &P = *Pp;
     extern __shared__ uint32_t lds[];
@@ -1808,9 +1810,11 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
     constexpr int KT = wide ? kMaxKW : kMaxK;             // entries of a table by type
     int32_t *t_tab = (int32_t *)lds;
     uint32_t *mask_tab = lds + KT;
-    // (wide problems: in the workspace when `far` is given, else behind their five tables in LDS)
-    uint32_t *state_all = !wide ? lds + 4 * kMaxK : far ? far + (size_t)blockIdx.x * far_words(P) : lds + 5 * kMaxKW;
-    uint16_t *prog_all = (uint16_t *)(state_all + P.nslots * kWave);
+    // (wide problems: behind their five tables in LDS, or in this workgroup's region of the workspace: `where` = 1 the
+    // program, 2 state and program)
+    uint32_t *region = wide && where ? far + (size_t)blockIdx.x * far_words(P, where) : nullptr;
+    uint32_t *state_all = !wide ? lds + 4 * kMaxK : where == 2 ? region : lds + 5 * kMaxKW;
+    uint16_t *prog_all = where == 1 ? (uint16_t *)region : (uint16_t *)(state_all + P.nslots * kWave);
     const int lane = threadIdx.x;
     // by home code for chain problems, by type id (with the producers and the token rings) for the others
     DagTables Tb;
@@ -1951,7 +1955,7 @@ __global__ void reset_kernel(DevResult *res)
 
 // ------------------------------------------------------------------ launchers
 typedef void (*eval_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, DevDetail *, const uint64_t *,
-                        const uint32_t *, uint32_t *);
+                        const uint32_t *, uint32_t *, int);
 typedef void (*fast_fn)(const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, int, int, uint64_t *, uint32_t *,
                         uint32_t, uint32_t *, uint32_t *, uint32_t, int);
 
@@ -2015,12 +2019,32 @@ static size_t lds_per_workgroup()
     }
     return cap;
 }
-static bool far_state(const KParams &kp) { return wide_problem(kp) && (size_t)5 * kMaxKW * 4 + far_words(kp) * 4 > lds_per_workgroup(); }
-static size_t far_bytes(const KParams &kp) { return far_state(kp) ? far_words(kp) * 4 : 0; }
+constexpr size_t kLdsAllBytes = 20 * 1024;       // state and program in LDS up to this much per workgroup (8 workgroups per CU)
+constexpr size_t kLdsStateBytes = 40 * 1024;     // the state alone up to this much (4 per CU)
+// Where the lanes' state and program of a wide problem live: 0 = in LDS, 1 = the program in the workspace, 2 = both.
+// (TESSEL_FAR_MODE: tuning knob, honoured where the LDS allows it.)
+static int far_mode(const KParams &kp)
+{
+    if (!wide_problem(kp)) return 0;
+    const size_t tables = (size_t)5 * kMaxKW * 4, state = (size_t)kp.nslots * kWave * 4, prog = (size_t)kp.total * kWave * 2;
+    int mode = tables + state + prog <= kLdsAllBytes ? 0 : tables + state <= kLdsStateBytes ? 1 : 2;
+    if (const char *env = getenv("TESSEL_FAR_MODE")) {
+        const int want = atoi(env);
+        if (want == 2 || (want == 1 && tables + state <= lds_per_workgroup()) || (want == 0 && tables + state + prog <= lds_per_workgroup()))
+            mode = want;
+    }
+    if (mode == 0 && tables + state + prog > lds_per_workgroup()) mode = 1;
+    if (mode == 1 && tables + state > lds_per_workgroup()) mode = 2;
+    return mode;
+}
+static size_t far_bytes(const KParams &kp) { return far_words(kp, far_mode(kp)) * 4; }
 
 static size_t general_lds_bytes(const KParams &kp)
 {
-    if (wide_problem(kp)) return (size_t)5 * kMaxKW * 4 + (far_state(kp) ? 0 : far_words(kp) * 4);
+    if (wide_problem(kp)) {
+        const int where = far_mode(kp);
+        return (size_t)5 * kMaxKW * 4 + (where == 2 ? 0 : (size_t)kp.nslots * kWave * 4) + (where ? 0 : (((size_t)kp.total * kWave * 2 + 255) & ~(size_t)255));
+    }
     return (size_t)4 * kMaxK * 4 + (size_t)kp.nslots * kWave * 4 + (size_t)kp.total * kWave * 2;
 }
 
@@ -2046,7 +2070,7 @@ LaunchShape eval_launch_shape(const KParams &kp, int num_cus, int max_blocks)
         per_cu = (int)((160 * 1024) / ((s.lds_bytes + 511) / 512 * 512));
     }
     if (per_cu > 16) per_cu = 16;
-    if (far_state(kp) && per_cu > 4) per_cu = 4;                     // (keeps the state regions of a launch small)
+    if (far_mode(kp) == 2 && per_cu > 4) per_cu = 4;                 // (keeps the state regions of a launch small)
     if (const char *env = getenv("TESSEL_BLOCKS_PER_CU")) {        // tuning knob: fewer resident workgroups per CU
         int want = atoi(env);
         if (want >= 1 && want < per_cu) per_cu = want;
@@ -2097,7 +2121,7 @@ size_t eval_workspace_bytes(const KParams &kp, int num_cus, int max_blocks)
 // where the state regions of the general kernel's workgroups start (wide problems whose state does not fit the LDS)
 static uint32_t *far_base(const KParams &kp, void *ws, int num_cus, int max_blocks)
 {
-    if (!far_state(kp)) return nullptr;
+    if (!far_mode(kp)) return nullptr;
     return (uint32_t *)((char *)ws + ring_offset(eval_launch_shape(kp, num_cus, max_blocks).blocks, num_cus));
 }
 
@@ -2105,14 +2129,15 @@ static int launch_general(const KParams &kp, const KParams *kp_dev, uint64_t fir
                           int32_t *code, int32_t *peak, DevDetail *detail, const uint64_t *list, const uint32_t *list_count,
                           uint32_t *far, hipStream_t st)
 {
-    if (far_state(kp) && !far) return (int)hipErrorInvalidValue;
+    const int where = far_mode(kp);
+    if (where && !far) return (int)hipErrorInvalidValue;
     eval_fn fn = pick_kernel(kp);
     const size_t lds = general_lds_bytes(kp);
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return (int)e;
     }
-    hipLaunchKernelGGL(fn, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, detail, list, list_count, far);
+    hipLaunchKernelGGL(fn, dim3(blocks), dim3(kWave), lds, st, kp_dev, first, count, recs, code, peak, detail, list, list_count, far, where);
     return (int)hipGetLastError();
 }
 
