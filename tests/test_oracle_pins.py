@@ -37,7 +37,7 @@ def gpipe(p, nr):
 
 
 # ---------------------------------------------------------------- closed forms
-@pytest.mark.parametrize("p", [2, 3, 4, 6])
+@pytest.mark.parametrize("p", [2, 3, 4, 6, 9, 12, 16])             # windows of up to 16 micro-batches
 @pytest.mark.parametrize("tf,tb", [(1, 2), (2, 3), (3, 3)])
 def test_1f1b_period_is_device_busy_time(p, tf, tb):
     """Zero-bubble 1F1B (Table II; Sec. III-C): the steady-state period of N_R = p
@@ -53,7 +53,7 @@ def test_1f1b_period_is_device_busy_time(p, tf, tb):
 
 
 @pytest.mark.parametrize("p", [2, 3, 4])
-@pytest.mark.parametrize("nr", [1, 2, 4, 5])
+@pytest.mark.parametrize("nr", [1, 2, 4, 5, 9, 13, 16])
 @pytest.mark.parametrize("tf,tb", [(1, 2), (2, 3)])
 def test_gpipe_window_period_is_gpipe_makespan(p, nr, tf, tb):
     """All forwards then all backwards on every device cannot overlap with the next window,
