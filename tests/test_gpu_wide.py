@@ -108,6 +108,7 @@ SHAPES = [
     ("kshape-nr10", W.kshape_problem(10, 12), 1 << 33, 2500),
     ("vshape-16-nr16", vshape(16, 16, 24, seed=0xE0FFEE7), 9, 300),
     ("inference-32-nr16", inference(32, 16), 2, 300),
+    ("vshape-32-nr16", vshape(32, 16, 40, seed=0xE0FFEE8), 1, 130),           # the largest window: 64 types, 1,024 blocks
 ]
 
 
@@ -116,6 +117,19 @@ def test_more_than_eight_devices(gpu, name, prob, first, n):
     codes = _compare(gpu, prob, first, n)
     if name in ("vshape-12-repair", "vshape-16-repair", "inference-32", "shared-10-repair"):
         assert (codes > 0).sum() > 50                      # the comparison covers periods, not only rejects
+
+
+def test_state_in_lds_or_in_the_workspace(gpu, monkeypatch):
+    """The lanes' sweep state and program live in LDS, or the program, or both, in the workspace, by size;
+    TESSEL_FAR_MODE forces each of the three: same scores as the oracle."""
+    for mode in ("0", "1", "2"):
+        monkeypatch.setenv("TESSEL_FAR_MODE", mode)
+        try:
+            _compare(gpu, vshape(12, 2, 2), 4242, 2000)
+            _compare(gpu, vshape(16, 4, 5), 99, 1500)
+            _compare(gpu, crowded(3, 3, 3, 5), 11, 2000)
+        finally:
+            monkeypatch.delenv("TESSEL_FAR_MODE")
 
 
 def random_wide_graph(rng):

@@ -78,9 +78,10 @@ def test_noalloc_other_problems_share_the_buffer(gpu, cfg, count):
 
 
 def test_noalloc_more_than_eight_devices(gpu):
-    """16 devices: the general kernel keeps its lanes' state in the buffer too, on as many workgroups as fit"""
+    """16 and 32 devices: the general kernel keeps its lanes' program (and a state too large for the LDS) in the buffer too,
+    on as many workgroups as fit"""
     from tests.test_gpu_wide import vshape
-    for prob, first, count in ((vshape(16, 8, 12), 7, 3000), (vshape(12, 2, 2), 0, 20000)):
+    for prob, first, count in ((vshape(16, 8, 12), 7, 3000), (vshape(12, 2, 2), 0, 20000), (vshape(32, 16, 40), 3, 700)):
         g = gpu.Problem(prob)
         g.eval_candidates_noalloc(first, count)
         got = g.best()
