@@ -125,6 +125,23 @@ def test_completion_candidates_on_random_graphs(gpu, seed):
     assert ran >= 5
 
 
+def test_greedy_completion_matches_the_worked_example(gpu):
+    """The hand-worked tie-order example of the oracle's pins (one device, types of 1, 2, 3 time units, leads 2, 1, 0,
+    five micro-batches): whatever order the best window has, the device never idles, so warm-up and cool-down start
+    where the derivation puts them."""
+    prob = {"name": "one-device", "D": 1, "K": 3, "NR": 3, "M": 0, "t": [1, 2, 3], "m": [0, 0, 0], "dev_mask": [1, 1, 1],
+            "deps": [], "space": "sampled_repair", "seed": 1, "lead_step_q16": 0, "fixed_leads": [2, 1, 0]}
+    g = gpu.Problem(prob)
+    g.eval_candidates(0, 64)
+    assert g.best()["period"] == 18
+    sched = g.complete_schedule(5)
+    start = sched["start"].tolist()
+    assert sched["makespan"] == 30
+    assert (start[0][0], start[1][0], start[0][1]) == (0, 1, 3)            # warm-up: A0, B0, A1
+    assert (start[2][3], start[1][4], start[2][4]) == (22, 25, 27)         # cool-down: C3, B4, C4
+    assert int(g.score_completions(5, 0, 0, 4).cpu().numpy()[0]) == 30
+
+
 def test_completion_argument_checks(gpu):
     g = gpu.Problem(W.config3())
     with pytest.raises(gpu.TesselError) as e:

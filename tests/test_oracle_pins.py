@@ -385,6 +385,28 @@ def test_completion_is_valid_on_sampled_candidates(prob):
     assert done >= 5
 
 
+def test_greedy_completion_matches_the_worked_example():
+    """The tie order of the greedy rule (earliest start, then micro-batch, then type id), worked out by hand on one
+    device, where every offered block can start when the device is free and only the tie order decides:
+    types A, B, C (t = 1, 2, 3; no memory, no dependencies), N_R = 3, leads 2, 1, 0, window order AAA BBB CCC,
+    N = 5 micro-batches, so one window between warm-up and cool-down.
+    Warm-up (micro-batches below the leads: A0, A1, B0), all free to start at 0: A0 (micro-batch 0, type 0) before
+    B0 (micro-batch 0, type 1); then B0 before A1 (micro-batch before type): A0 at 0, B0 at 1, A1 at 3.
+    Window, back to back from 4: A2 A3 A4 at 4, 5, 6; B1 B2 B3 at 7, 9, 11; C0 C1 C2 at 13, 16, 19 (ends 22).
+    Cool-down (B4, C3, C4): C3 (micro-batch 3) before B4 (micro-batch 4) at 22; then B4 before C4 (type) at 25;
+    C4 at 27; the device never idles: makespan 30 = 5 (1 + 2 + 3)."""
+    prob = {"name": "one-device", "D": 1, "K": 3, "NR": 3, "M": 0, "t": [1, 2, 3], "m": [0, 0, 0], "dev_mask": [1, 1, 1],
+            "deps": [], "space": "sampled_repair", "seed": 1, "lead_step_q16": 0, "fixed_leads": None}
+    leads, orders = [2, 1, 0], [[0, 0, 0, 1, 1, 1, 2, 2, 2]]
+    orc = Oracle(prob)
+    assert orc.eval_explicit(leads, orders)["status"] == OK
+    c = orc.complete(leads, orders, 5)
+    assert c["makespan"] == 30
+    assert c["start"].tolist() == [[0, 3, 4, 5, 6], [1, 7, 9, 11, 25], [13, 16, 19, 22, 27]]
+    ok, makespan, peaks = SC.check_flat_schedule(prob, 5, c["start"].tolist(), c["dev_order"])
+    assert ok and makespan == 30
+
+
 def test_error_paths():
     base = W.config1()
     with pytest.raises(OracleError):
