@@ -385,6 +385,28 @@ def test_completion_is_valid_on_sampled_candidates(prob):
     assert done >= 5
 
 
+def test_lead_law_at_its_deterministic_ends():
+    """The leads of a sampled candidate: consumers before producers, a type's lead is the largest (consumer's lead +
+    step) over its dependencies, capped at N_R - 1; the step is drawn only where the two blocks sit on different
+    device sets.  With the probability of a step at 1 or at 0 no draw matters and the vector can be written down."""
+    lin = W.pipeline_problem(W.linear_placement(3), [1] * 3, [2] * 3, 3, 4, 4, "sampled_repair", seed=5, lead_step_q16=65536)
+    cases = [
+        (lin, [3, 3, 2, 2, 1, 0]),                          # F0 F1 F2 B2 B1 B0: no step between F2 and B2 (same device), cap 3
+        (dict(lin, NR=2), [1, 1, 1, 1, 1, 0]),
+        (dict(lin, lead_step_q16=0), [0] * 6),
+        (W.kshape_problem(4, 8, lead_step_q16=65536), [2, 2, 1, 1, 0, 0]),           # A_F B_F J_F J_B A_B B_B
+        (W.diamond_problem(8, 16, lead_step_q16=65536), [4, 3, 3, 2, 2, 1, 1, 0]),   # S_F L_F R_F T_F T_B L_B R_B S_B
+        (W.diamond_problem(3, 6, lead_step_q16=65536), [2, 2, 2, 2, 2, 1, 1, 0]),
+        # a block on all devices at both ends of the chain: a step wherever the device sets differ
+        (dict(W.config4(), lead_step_q16=65536), [3, 3, 3, 3, 3, 3, 3, 2, 1, 0]),
+    ]
+    for prob, want in cases:
+        orc = Oracle(prob)
+        for index in (0, 1, 12345, 1 << 40):
+            status, leads, orders = orc.decode(index)
+            assert leads == want, (prob["name"], index, leads)
+
+
 def test_greedy_completion_matches_the_worked_example():
     """The tie order of the greedy rule (earliest start, then micro-batch, then type id), worked out by hand on one
     device, where every offered block can start when the device is free and only the tie order decides:
