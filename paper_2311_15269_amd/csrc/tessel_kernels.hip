@@ -1639,10 +1639,11 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
         return (uint32_t)__builtin_popcountll(okm);
     };
     // phase C on the first n candidates of ring 2, or (`again`) of ring 3
-    // (Wave priority by phase: the sweeps wait for the LDS after every few instructions and issue first (3), the rest
-    // of the build next (1), decode and first build phase, which always have an instruction ready, fill what is left
-    // (0).  Measured on windows of 256 blocks: 33.6 ms per 2^26 candidates against 37.3 with all waves equal;
-    // 3/2/0 the same, 3/3/0 34.3, the sweeps alone at 3 35.9.)
+    // (Wave priority by phase, set where a phase starts: the sweeps wait for the LDS after every few instructions and
+    // issue first (3), then the second build phase (2), then the first (1: a build step waits for two rounds of LDS
+    // reads); the decode, which always has an instruction ready, fills what is left (0).  Measured on windows of 256
+    // blocks: 32.5 ms per 2^26 candidates against 37.3 with all waves equal; decode and first build phase both at 0
+    // with the second at 1 or 2: 33.6 to 33.8; both build phases at 3: 34.3; the sweeps alone at 3: 35.9.)
     auto sweep_from_ring = [&](uint32_t n, bool again) {
         __builtin_amdgcn_s_setprio(3);
         __threadfence_block();         // the stores of this wave's other lanes must be visible to the loads below
@@ -1680,7 +1681,6 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
             if (code_out) code_out[idx - first] = T;
             if (peak_out) peak_out[idx - first] = pk;
         }
-        __builtin_amdgcn_s_setprio(0);
     };
     // the end of the build for the candidates the lanes hold: verdict, then ring 2 or out
     auto finish_build = [&](bool have, uint64_t idx, const FastProgram &prog) {
@@ -1691,7 +1691,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     };
     // phase B on the first n candidates of ring 1
     auto build_from_ring = [&](uint32_t n) {
-        __builtin_amdgcn_s_setprio(1);
+        __builtin_amdgcn_s_setprio(2);
         __threadfence_block();
         const bool have = (uint32_t)lane < n;
         const uint32_t *src = ring1 + ((head1 + (uint32_t)lane) & (kRingSlots - 1u));
@@ -1718,7 +1718,6 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
         build_words<DM, MODE, TP>(P, C, L, lane, have, wordsA, nwords, prog, S);
         nblocks += n * (uint32_t)(C.total - min(C.total, 6 * wordsA));
         finish_build(have, idx, prog);
-        __builtin_amdgcn_s_setprio(0);
     };
 
     const uint64_t stride = (uint64_t)gridDim.x * kWave;
@@ -1728,8 +1727,10 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
         const uint64_t kk = r * stride + (uint64_t)blockIdx.x * kWave + lane;
         const bool valid = kk < count;
         const uint64_t idx = valid ? first + kk : first;
+        __builtin_amdgcn_s_setprio(0);
         build_begin<DM, MODE, TP>(P, C, idx, L, lane, lead_code, S);
         FastProgram prog;
+        __builtin_amdgcn_s_setprio(1);
         build_words<DM, MODE, TP>(P, C, L, lane, valid, 0, wordsA, prog, S);
         nblocks += (uint32_t)__builtin_popcountll(__ballot(valid)) * (uint32_t)min(C.total, 6 * wordsA);
         if (!split) { finish_build(valid, idx, prog); return; }
