@@ -1,4 +1,5 @@
 """Builds the HIP library (gfx950) in-tree with hipcc."""
+import concurrent.futures
 import glob
 import os
 import re
@@ -9,11 +10,11 @@ import tempfile
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libtessel_hip.so")
-SOURCES = ["tessel_kernels.hip", "tessel_api.cpp"]
+SOURCES = ["tessel_kernels.hip", "tessel_wide.hip", "tessel_api.cpp"]
 HEADERS = ["tessel_device.h", os.path.join("..", "..", "include", "tessel.h")]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
     # packed FP32 instructions are kept out of every device code object of this build
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
@@ -110,12 +111,25 @@ def build_library(force=True, verbose=False, check=True):
     tmp = tempfile.mkdtemp(prefix="tessel_build_")
     try:
         out = os.path.join(tmp, "libtessel_hip.so")
-        cmd = [hipcc] + HIPCC_FLAGS + (["-save-temps=obj"] if check else []) + [os.path.join(CSRC, f) for f in SOURCES] + ["-o", out]
+        # one object per source, compiled side by side (each in a folder of its own, which also takes what
+        # -save-temps leaves behind), then one link
+        def compile_one(src):
+            work = os.path.join(tmp, os.path.splitext(src)[0])
+            os.makedirs(work)
+            obj = os.path.join(work, os.path.splitext(src)[0] + ".o")
+            cmd = [hipcc] + HIPCC_FLAGS + (["-save-temps=obj"] if check else []) + ["-c", os.path.join(CSRC, src), "-o", obj]
+            if verbose:
+                print(" ".join(cmd))
+            subprocess.check_call(cmd, cwd=work)
+            return obj
+        with concurrent.futures.ThreadPoolExecutor(max_workers=len(SOURCES)) as pool:
+            objs = list(pool.map(compile_one, SOURCES))
+        link = [hipcc, "--offload-arch=gfx950", "--hip-link", "-shared", "-fPIC"] + objs + ["-o", out]
         if verbose:
-            print(" ".join(cmd))
-        subprocess.check_call(cmd, cwd=tmp)
+            print(" ".join(link))
+        subprocess.check_call(link, cwd=tmp)
         if check:
-            listings = glob.glob(os.path.join(tmp, "*gfx950*.s"))
+            listings = glob.glob(os.path.join(tmp, "*", "*gfx950*.s"))
             if not listings:
                 raise RuntimeError("no device assembly found to check")
             for path in listings:

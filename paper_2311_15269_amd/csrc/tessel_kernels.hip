@@ -1895,6 +1895,17 @@ __global__ __launch_bounds__(kWave) void eval_kernel(const KParams *__restrict__
     }
 }
 
+// The two instantiations for problems beyond the fast kernel's limits (16 and 32 devices) take as long to compile as
+// everything else in this file: tessel_wide.hip includes this file up to here and holds them, so that the two halves
+// build side by side.
+#define TESSEL_EVAL_KERNEL_ARGS const KParams *, uint64_t, uint64_t, BlockRec *, int32_t *, int32_t *, DevDetail *, const uint64_t *, const uint32_t *, uint32_t *, int
+#ifdef TESSEL_WIDE_INSTANTIATIONS
+template __global__ void eval_kernel<16, 1>(TESSEL_EVAL_KERNEL_ARGS);
+template __global__ void eval_kernel<32, 1>(TESSEL_EVAL_KERNEL_ARGS);
+#else
+extern template __global__ void eval_kernel<16, 1>(TESSEL_EVAL_KERNEL_ARGS);
+extern template __global__ void eval_kernel<32, 1>(TESSEL_EVAL_KERNEL_ARGS);
+
 // merges the block records of one launch into the running best (one wave)
 __global__ __launch_bounds__(kWave) void merge_kernel(const BlockRec *recs, int nrecs, DevResult *res)
 {
@@ -2715,5 +2726,7 @@ int launch_alu_probe(uint32_t *out, int blocks, int rounds, void *stream)
     hipLaunchKernelGGL(alu_probe_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, out, rounds, 0x9E3779B9u, 12345u);
     return (int)hipGetLastError();
 }
+
+#endif  // TESSEL_WIDE_INSTANTIATIONS
 
 }  // namespace tessel
