@@ -1280,8 +1280,10 @@ __device__ __forceinline__ void build_begin(const KParams &P, const FastConst<DM
         uint32_t S = 0;
         for (int e = 0; e < C.ndeps; e += 2) {
             const uint32_t wv = stream_word(ka, kb, (kDrawLeadBase + (uint32_t)e) >> 1);
-            S |= (wv & 0xFFFFu) < C.step_q16 ? L.depbit_tab[e] : 0u;
-            S |= (wv >> 16) < C.step_q16 && e + 1 < C.ndeps ? L.depbit_tab[e + 1] : 0u;
+            // (the dependency's bit through scalar loads: the index is the same in every lane)
+            const uint32_t b0 = P.dep_bit[e], b1 = e + 1 < C.ndeps ? P.dep_bit[e + 1] : 0u;
+            S |= (wv & 0xFFFFu) < C.step_q16 ? b0 : 0u;
+            S |= (wv >> 16) < C.step_q16 ? b1 : 0u;
         }
 #pragma unroll
         for (int d = 0; d < DM; d++) {
