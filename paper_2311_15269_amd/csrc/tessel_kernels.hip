@@ -894,7 +894,7 @@ struct FastLds {
                           // the upper halves hold chain_tab, vtab, cum_tab, predbit_tab
     uint32_t *chain_tab;  // [32]  KParams::chain_tab
     uint32_t *vtab;       // [32]  KParams::vtab
-    uint32_t *cum_tab, *predbit_tab, *depbit_tab;   // [32] each: KParams::cum_code, pred_bit, dep_bit
+    uint32_t *cum_tab, *predbit_tab;   // [32] each: KParams::cum_code, pred_bit
     uint32_t *grp_tab;    // [32]  TP variants: KParams::grp_code
     uint32_t rec;         // build: LDS address of the records [DM][4][64]: word 0: low plane, 1: high plane,
                           //        2: not-yet-placed mask, 3: micro-batches waiting at the input of the 4 types
@@ -1515,7 +1515,6 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
     L.vtab = lds + 3 * kMaxK;
     L.cum_tab = lds + 5 * kMaxK;
     L.predbit_tab = lds + 7 * kMaxK;
-    L.depbit_tab = lds + 8 * kMaxK;
     L.tt_tab = (uint4 *)(lds + kFastTableWords);              // 128 words, TP variants only
     L.grp_tab = lds + kFastTableWords + 4 * kMaxK;            // TP variants only
     L.sw_tab = lds + kSweepTabWord;
@@ -1563,7 +1562,7 @@ __global__ __launch_bounds__(kWave, MODE ? 4 : 3) void eval_fast_kernel(const KP
         L.chain_tab[lane] = P.chain_tab[lane];
         L.vtab[lane] = lane < 24 ? P.vtab[lane] : 0u;
         if (TP) L.grp_tab[lane] = P.grp_code[lane] ? P.grp_code[lane] : 1u << lane;
-        L.cum_tab[lane] = P.cum_code[lane]; L.predbit_tab[lane] = P.pred_bit[lane]; L.depbit_tab[lane] = P.dep_bit[lane];
+        L.cum_tab[lane] = P.cum_code[lane]; L.predbit_tab[lane] = P.pred_bit[lane];
     }
     __syncthreads();
     FastConst<DM> C;
